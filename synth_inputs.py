@@ -1,0 +1,255 @@
+"""Seeded synthetic input tensors for the Convolution op family.
+
+This module is *data only*: it holds no convolution, layout or epilogue
+arithmetic.  It is the single place both the CPU oracle's tests and the HIP
+path's tests / benchmark take their inputs from, so that the two sides see the
+same bits.
+
+Generator: counter based.  Element ``i`` of tensor ``tensor_id`` under ``seed``
+is a pure function of ``(seed, tensor_id, i)`` (a splitmix64-style finaliser of
+a 64-bit counter), so results do not depend on numpy's or torch's RNG streams,
+on chunking, or on the order tensors are generated in.
+
+* uniform tensors: 53-bit uniform in [0,1) mapped affinely to [lo, hi)
+* normal tensors : Box-Muller on two such uniforms (counters 2i and 2i+1)
+* values are produced in fp64, cast to fp32, and, for bf16 configurations,
+  rounded once to bf16 (round-to-nearest-even) here on the host; the bf16
+  bit patterns are what both sides consume.
+
+Workload recipes (shapes / distributions of the five benchmark configurations,
+ResNet-shaped layers) live in :func:`config_layers`.
+"""
+from __future__ import annotations
+
+import math
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+TENSOR_X, TENSOR_W, TENSOR_BIAS, TENSOR_DY = 0, 1, 2, 3
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_CHUNK = 1 << 20
+_THREADS = max(1, min(16, os.cpu_count() or 1))
+
+
+def _fill_chunks(n: int, fill) -> None:
+    """Run fill(start, count) over [0, n) in chunks; chunks are independent
+    (counter-based generator), so they may run on several host threads."""
+    starts = range(0, n, _CHUNK)
+    if n <= _CHUNK or _THREADS == 1:
+        for s in starts:
+            fill(s, min(_CHUNK, n - s))
+        return
+    with ThreadPoolExecutor(_THREADS) as ex:
+        list(ex.map(lambda s: fill(s, min(_CHUNK, n - s)), starts))
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    """splitmix64 output function on an array of uint64 (wrapping arithmetic)."""
+    z = z.copy()
+    z ^= z >> np.uint64(30)
+    z *= _M1
+    z ^= z >> np.uint64(27)
+    z *= _M2
+    z ^= z >> np.uint64(31)
+    return z
+
+
+def _stream_key(seed: int, tensor_id: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = _mix64(np.array([np.uint64(seed & 0xFFFFFFFFFFFFFFFF)]))[0]
+        k = _mix64(np.array([k ^ (np.uint64(tensor_id + 1) * _GOLDEN)]))[0]
+    return k
+
+
+def _uniform01(key: np.uint64, start: int, count: int) -> np.ndarray:
+    """`count` uniforms in [0,1) for counters start .. start+count-1."""
+    with np.errstate(over="ignore"):
+        ctr = np.arange(start, start + count, dtype=np.uint64)
+        bits = _mix64(key + (ctr + np.uint64(1)) * _GOLDEN)
+    return (bits >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+def uniform(seed: int, tensor_id: int, shape, lo: float, hi: float) -> np.ndarray:
+    """fp32 tensor, elements U[lo, hi)."""
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.float32)
+    key = _stream_key(seed, tensor_id)
+
+    def fill(s, c):
+        out[s:s + c] = (lo + (hi - lo) * _uniform01(key, s, c)).astype(np.float32)
+
+    _fill_chunks(n, fill)
+    return out.reshape(shape)
+
+
+def normal(seed: int, tensor_id: int, shape, mean: float, std: float) -> np.ndarray:
+    """fp32 tensor, elements N(mean, std^2) by Box-Muller (cosine branch)."""
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.float32)
+    key = _stream_key(seed, tensor_id)
+
+    def fill(s, c):
+        u = _uniform01(key, 2 * s, 2 * c)
+        u1 = 1.0 - u[0::2]            # (0,1]  -> log is finite
+        u2 = u[1::2]
+        z = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
+        out[s:s + c] = (mean + std * z).astype(np.float32)
+
+    _fill_chunks(n, fill)
+    return out.reshape(shape)
+
+
+# --------------------------------------------------------------------------
+# bf16 containers (bit patterns in uint16).  Data preparation only.
+# --------------------------------------------------------------------------
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 -> bf16, round-to-nearest-even; returns uint16 bit patterns.
+    Inputs are finite by construction (no NaN handling needed)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u.astype(np.uint64) + np.uint64(0x7FFF) + lsb.astype(np.uint64)) >> np.uint64(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns to fp32 exactly."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Workload recipes
+# --------------------------------------------------------------------------
+
+@dataclass
+class ConvLayer:
+    """One convolution layer of a benchmark configuration (logical NCHW axes)."""
+    name: str
+    n: int
+    c: int
+    h: int
+    w: int
+    k: int
+    r: int
+    s: int
+    stride: int = 1
+    pad: int = 0
+    dil: int = 1
+    dtype: str = "bf16"             # "f32" | "bf16"
+    bias_relu: bool = True          # forward epilogue
+    ops: Tuple[str, ...] = ("fwd", "bwd_data", "bwd_filters")
+    x_dist: Tuple = ("normal", 0.0, 1.0)
+    dy_dist: Tuple = ("normal", 0.0, 0.1)
+    w_dist: Tuple = ("he",)
+    seed: int = 0
+    count: int = 1                  # multiplicity inside the configuration
+
+    @property
+    def p(self) -> int:
+        return (self.h + 2 * self.pad - self.dil * (self.r - 1) - 1) // self.stride + 1
+
+    @property
+    def q(self) -> int:
+        return (self.w + 2 * self.pad - self.dil * (self.s - 1) - 1) // self.stride + 1
+
+    @property
+    def flop_per_op(self) -> float:
+        return 2.0 * self.n * self.k * self.p * self.q * self.c * self.r * self.s
+
+
+BASE_SEED = 180108058 * 10
+
+
+def _resnet50_layers(n: int) -> List[ConvLayer]:
+    """The 53 convolutions of ResNet-50 (stride 2 on the first 3x3 of stages 2-4,
+    projection 1x1 with the stage stride), as unique shapes with multiplicities."""
+    layers: List[Tuple[Tuple, int]] = []
+
+    def add(c, k, hw, r, stride, pad):
+        key = (c, k, hw, r, stride, pad)
+        for i, (kk, cnt) in enumerate(layers):
+            if kk == key:
+                layers[i] = (kk, cnt + 1)
+                return
+        layers.append((key, 1))
+
+    add(3, 64, 224, 7, 2, 3)
+    hw, cin = 56, 64
+    for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3))):
+        for b in range(blocks):
+            stride = 2 if (stage > 0 and b == 0) else 1
+            add(cin, width, hw, 1, 1, 0)                    # 1x1 a (input resolution)
+            add(width, width, hw, 3, stride, 1)             # 3x3
+            hw_out = hw // stride
+            add(width, 4 * width, hw_out, 1, 1, 0)          # 1x1 c
+            if b == 0:
+                add(cin, 4 * width, hw, 1, stride, 0)       # projection
+            cin, hw = 4 * width, hw_out
+    out = []
+    for idx, ((c, k, hw_, r, stride, pad), cnt) in enumerate(layers):
+        out.append(ConvLayer(
+            name=f"c{c}k{k}hw{hw_}r{r}s{stride}", n=n, c=c, h=hw_, w=hw_, k=k, r=r, s=r,
+            stride=stride, pad=pad, dtype="bf16", bias_relu=True,
+            x_dist=("uniform", 0.0, 1.0) if c == 3 else ("normal", 0.0, 1.0),
+            seed=BASE_SEED + 5 + 1000 * idx, count=cnt))
+    return out
+
+
+def config_layers(cfg: int, batch: int | None = None) -> List[ConvLayer]:
+    """Layer list of benchmark configuration `cfg` (1..5).  `batch` overrides N
+    (used by tests that want the same recipe at a size the oracle finishes)."""
+    if cfg == 1:
+        return [ConvLayer("cfg1_f32_3x3", batch or 2, 16, 16, 16, 32, 3, 3, 1, 1, dtype="f32",
+                          x_dist=("uniform", -1.0, 1.0), dy_dist=("uniform", -1.0, 1.0),
+                          w_dist=("uniform", -1.0, 1.0), seed=BASE_SEED + 1)]
+    if cfg == 2:
+        return [ConvLayer("cfg2_3x3_c64", batch or 64, 64, 56, 56, 64, 3, 3, 1, 1, seed=BASE_SEED + 2)]
+    if cfg == 3:
+        return [ConvLayer("cfg3_1x1_c256k64", batch or 64, 256, 56, 56, 64, 1, 1, 1, 0,
+                          bias_relu=False, seed=BASE_SEED + 3)]
+    if cfg == 4:
+        return [ConvLayer("cfg4_stem7x7", batch or 64, 3, 224, 224, 64, 7, 7, 2, 3,
+                          ops=("fwd", "bwd_filters"), x_dist=("uniform", 0.0, 1.0),
+                          seed=BASE_SEED + 4)]
+    if cfg == 5:
+        return _resnet50_layers(batch or 128)
+    raise ValueError(f"unknown configuration {cfg}")
+
+
+def _draw(dist: Tuple, seed: int, tid: int, shape, fan_in: int) -> np.ndarray:
+    if dist[0] == "uniform":
+        return uniform(seed, tid, shape, dist[1], dist[2])
+    if dist[0] == "normal":
+        return normal(seed, tid, shape, dist[1], dist[2])
+    if dist[0] == "he":
+        return normal(seed, tid, shape, 0.0, math.sqrt(2.0 / fan_in))
+    raise ValueError(dist)
+
+
+def layer_tensors(L: ConvLayer, which=("x", "w", "bias", "dy")) -> Dict[str, np.ndarray]:
+    """Synthetic tensors of a layer, logical NCHW / KCRS axis order.
+
+    Returns fp32 arrays.  For bf16 layers x, w and dy hold values that are
+    exactly representable in bf16 (rounded once here); bias stays fp32."""
+    out: Dict[str, np.ndarray] = {}
+    fan_in = L.c * L.r * L.s
+    if "x" in which:
+        out["x"] = _draw(L.x_dist, L.seed, TENSOR_X, (L.n, L.c, L.h, L.w), fan_in)
+    if "w" in which:
+        out["w"] = _draw(L.w_dist, L.seed, TENSOR_W, (L.k, L.c, L.r, L.s), fan_in)
+    if "bias" in which:
+        out["bias"] = uniform(L.seed, TENSOR_BIAS, (L.k,), -0.1, 0.1)
+    if "dy" in which:
+        out["dy"] = _draw(L.dy_dist, L.seed, TENSOR_DY, (L.n, L.k, L.p, L.q), fan_in)
+    if L.dtype == "bf16":
+        for name in ("x", "w", "dy"):
+            if name in out:
+                out[name] = bf16_bits_to_f32(f32_to_bf16_bits(out[name]))
+    return out

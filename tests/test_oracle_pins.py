@@ -1,0 +1,300 @@
+"""Pins for the CPU oracle (no GPU).  Each test fixes the oracle against something
+other than itself: hand-worked values, an independent brute force written in a
+different code shape, a library matmul, adjoint / finite-difference identities,
+closed forms and construction identities.  A dropped term, wrong sign, wrong
+index or transposed operand in oracle/conv_ref.c fails at least one of them."""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Attrs
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "hand_examples.json")
+rng = np.random.default_rng(20180125)
+
+
+def _attrs_from(d):
+    return Attrs(d["n"], d["c"], d["h"], d["w"], d["k"], d["r"], d["s"],
+                 d["stride"], d["stride"], d["dilation"], d["dilation"],
+                 d["pad_below"], d["pad_below"], d["pad_above"], d["pad_above"])
+
+
+# ---------------------------------------------------------------- P1 hand examples
+def test_hand_example_1():
+    g = json.load(open(GOLD))["example_1"]
+    a = _attrs_from(g["attrs"])
+    x = np.array(g["x"], float).reshape(1, 1, 3, 3)
+    w = np.array(g["w"], float).reshape(1, 1, 2, 2)
+    dy = np.array(g["dy"], float).reshape(1, 1, 2, 2)
+    y = oracle.conv_fwd(a, x, w)
+    assert np.array_equal(y[0, 0], np.array(g["y"], float))
+    assert np.array_equal(oracle.conv_fwd(a, x, w, bias=[5.0], relu=True)[0, 0], np.array(g["y_bias5_relu"], float))
+    assert np.array_equal(oracle.conv_fwd(a, x, w, bias=[0.0], relu=True)[0, 0], np.array(g["y_bias0_relu"], float))
+    dx = oracle.conv_bwd_data(a, dy, w)
+    assert np.array_equal(dx[0, 0], np.array(g["dx"], float))
+    assert np.array_equal(oracle.conv_bwd_data_gather(a, dy, w), dx)
+    dw = oracle.conv_bwd_filters(a, x, dy)
+    assert np.array_equal(dw[0, 0], np.array(g["dw"], float))
+    ip = g["inner_product"]
+    assert (y * dy).sum() == ip and (x * dx).sum() == ip and (w * dw).sum() == ip
+
+
+def test_hand_example_2_stride_pad():
+    g = json.load(open(GOLD))["example_2"]
+    a = _attrs_from(g["attrs"])
+    assert oracle.out_shape(a) == (2, 2)
+    x = np.array(g["x"], float).reshape(1, 1, 3, 3)
+    w = np.array(g["w"], float).reshape(1, 1, 3, 3)
+    assert np.array_equal(oracle.conv_fwd(a, x, w)[0, 0], np.array(g["y"], float))
+
+
+# ---------------------------------------------------------------- P2 brute force
+def _brute(a: Attrs, x, w, dy):
+    """Independent 7-loop scalar routine on an explicitly zero-padded copy of x
+    (no bounds tests); returns y, dx, dw.  Written from the definition, different
+    code shape from the oracle (padding buffer, flat python loops, dict of terms)."""
+    Hp = a.h + a.pbh + a.pah
+    Wp = a.w + a.pbw + a.paw
+    xp = np.zeros((a.n, a.c, Hp, Wp))
+    xp[:, :, a.pbh:a.pbh + a.h, a.pbw:a.pbw + a.w] = x
+    P = (Hp - (a.dh * (a.r - 1) + 1)) // a.sh + 1 if Hp >= a.dh * (a.r - 1) + 1 else 0
+    Q = (Wp - (a.dw * (a.s - 1) + 1)) // a.sw + 1 if Wp >= a.dw * (a.s - 1) + 1 else 0
+    y = np.zeros((a.n, a.k, P, Q))
+    dxp = np.zeros_like(xp)
+    dw = np.zeros((a.k, a.c, a.r, a.s))
+    for n, k, p, q, c, r, s in itertools.product(range(a.n), range(a.k), range(P), range(Q),
+                                                 range(a.c), range(a.r), range(a.s)):
+        ii = p * a.sh + r * a.dh
+        jj = q * a.sw + s * a.dw
+        y[n, k, p, q] += xp[n, c, ii, jj] * w[k, c, r, s]
+        if dy is not None:
+            dxp[n, c, ii, jj] += dy[n, k, p, q] * w[k, c, r, s]
+            dw[k, c, r, s] += dy[n, k, p, q] * xp[n, c, ii, jj]
+    dx = dxp[:, :, a.pbh:a.pbh + a.h, a.pbw:a.pbw + a.w]
+    return y, dx, dw, (P, Q)
+
+
+def _random_attrs(max_hw=7):
+    while True:
+        a = Attrs(n=int(rng.integers(1, 4)), c=int(rng.integers(1, 4)), h=int(rng.integers(1, max_hw + 1)),
+                  w=int(rng.integers(1, max_hw + 1)), k=int(rng.integers(1, 4)), r=int(rng.integers(1, 4)),
+                  s=int(rng.integers(1, 4)), sh=int(rng.integers(1, 4)), sw=int(rng.integers(1, 4)),
+                  dh=int(rng.integers(1, 3)), dw=int(rng.integers(1, 3)),
+                  pbh=int(rng.integers(0, 3)), pbw=int(rng.integers(0, 3)),
+                  pah=int(rng.integers(0, 3)), paw=int(rng.integers(0, 3)))
+        P, Q = oracle.out_shape(a)
+        if P > 0 and Q > 0:
+            return a
+
+
+def _random_tensors(a):
+    P, Q = oracle.out_shape(a)
+    return (rng.uniform(-1, 1, (a.n, a.c, a.h, a.w)), rng.uniform(-1, 1, (a.k, a.c, a.r, a.s)),
+            rng.uniform(-1, 1, (a.n, a.k, P, Q)))
+
+
+@pytest.mark.parametrize("trial", range(40))
+def test_brute_force_tiny(trial):
+    a = _random_attrs()
+    x, w, dy = _random_tensors(a)
+    y_b, dx_b, dw_b, pq = _brute(a, x, w, dy)
+    assert pq == oracle.out_shape(a)
+    np.testing.assert_allclose(oracle.conv_fwd(a, x, w), y_b, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.conv_bwd_data(a, dy, w), dx_b, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.conv_bwd_data_gather(a, dy, w), dx_b, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.conv_bwd_filters(a, x, dy), dw_b, rtol=0, atol=1e-13)
+
+
+def test_sampled_entry_points_match_full():
+    for _ in range(5):
+        a = _random_attrs(9)
+        x, w, dy = _random_tensors(a)
+        b = rng.uniform(-1, 1, a.k)
+        y = oracle.conv_fwd(a, x, w, bias=b, relu=True)
+        dx = oracle.conv_bwd_data(a, dy, w)
+        dw = oracle.conv_bwd_filters(a, x, dy)
+        for full, fn in ((y, lambda i: oracle.conv_fwd_at(a, x, w, i, bias=b, relu=True)),
+                         (dx, lambda i: oracle.conv_bwd_data_at(a, dy, w, i)),
+                         (dw, lambda i: oracle.conv_bwd_filters_at(a, x, dy, i))):
+            idx = rng.integers(0, full.size, size=min(64, full.size))
+            np.testing.assert_allclose(fn(idx), full.reshape(-1)[idx], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P3 1x1 conv == matmul
+def test_1x1_is_matmul():
+    a = Attrs(n=3, c=7, h=5, w=6, k=4, r=1, s=1)
+    x, w, dy = _random_tensors(a)
+    y = oracle.conv_fwd(a, x, w)
+    W2 = w.reshape(a.k, a.c)
+    for n in range(a.n):
+        np.testing.assert_allclose(y[n].reshape(a.k, -1), W2 @ x[n].reshape(a.c, -1), rtol=0, atol=1e-13)
+    dx = oracle.conv_bwd_data(a, dy, w)
+    for n in range(a.n):
+        np.testing.assert_allclose(dx[n].reshape(a.c, -1), W2.T @ dy[n].reshape(a.k, -1), rtol=0, atol=1e-13)
+    dw = oracle.conv_bwd_filters(a, x, dy)
+    ref = sum(dy[n].reshape(a.k, -1) @ x[n].reshape(a.c, -1).T for n in range(a.n))
+    np.testing.assert_allclose(dw.reshape(a.k, a.c), ref, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P4 adjoint identities
+@pytest.mark.parametrize("trial", range(12))
+def test_adjoint_identities(trial):
+    a = _random_attrs(11)
+    if trial == 0:   # stride 2 with a leftover row / column no window reaches
+        a = Attrs(n=2, c=3, h=8, w=10, k=4, r=3, s=3, sh=2, sw=2, pbh=0, pbw=1, pah=0, paw=0)
+    x, w, dy = _random_tensors(a)
+    lhs = float((oracle.conv_fwd(a, x, w) * dy).sum())
+    mid = float((x * oracle.conv_bwd_data(a, dy, w)).sum())
+    rhs = float((w * oracle.conv_bwd_filters(a, x, dy)).sum())
+    scale = max(abs(lhs), 1e-30)
+    assert abs(lhs - mid) / scale < 1e-12 and abs(lhs - rhs) / scale < 1e-12
+
+
+def test_unreached_pixels_get_zero_gradient():
+    # 1x1 stride 2: odd rows / columns of dx are never touched
+    a = Attrs(n=1, c=2, h=6, w=6, k=3, r=1, s=1, sh=2, sw=2)
+    x, w, dy = _random_tensors(a)
+    dx = oracle.conv_bwd_data(a, dy, w)
+    assert np.all(dx[:, :, 1::2, :] == 0) and np.all(dx[:, :, :, 1::2] == 0)
+    assert np.any(dx[:, :, 0::2, 0::2] != 0)
+
+
+# ---------------------------------------------------------------- P5 finite differences
+def test_finite_differences_exact_by_linearity():
+    a = Attrs(n=2, c=3, h=7, w=6, k=4, r=3, s=2, sh=2, sw=1, dh=1, dw=2, pbh=1, pbw=0, pah=2, paw=1)
+    x, w, dy = _random_tensors(a)
+    v = rng.uniform(-1, 1, w.shape)
+    u = rng.uniform(-1, 1, x.shape)
+    base = (oracle.conv_fwd(a, x, w) * dy).sum()
+    dw = oracle.conv_bwd_filters(a, x, dy)
+    dx = oracle.conv_bwd_data(a, dy, w)
+    for eps in (1.0, 1e-3):
+        fd_w = ((oracle.conv_fwd(a, x, w + eps * v) * dy).sum() - base) / eps
+        fd_x = ((oracle.conv_fwd(a, x + eps * u, w) * dy).sum() - base) / eps
+        assert abs(fd_w - (v * dw).sum()) < 1e-9 / eps * 1e-3 + 1e-10
+        assert abs(fd_x - (u * dx).sum()) < 1e-9 / eps * 1e-3 + 1e-10
+
+
+# ---------------------------------------------------------------- P6 closed forms
+def test_all_ones_counts_window_overlap():
+    a = Attrs(n=1, c=3, h=6, w=5, k=2, r=3, s=3, sh=2, sw=1, dh=2, dw=1, pbh=2, pbw=1, pah=1, paw=2)
+    P, Q = oracle.out_shape(a)
+    y = oracle.conv_fwd(a, np.ones((1, 3, 6, 5)), np.ones((2, 3, 3, 3)))
+    for p in range(P):
+        for q in range(Q):
+            ch = sum(1 for r in range(a.r) if 0 <= p * a.sh - a.pbh + r * a.dh < a.h)
+            cw = sum(1 for s in range(a.s) if 0 <= q * a.sw - a.pbw + s * a.dw < a.w)
+            assert np.all(y[:, :, p, q] == a.c * ch * cw)
+
+
+def test_delta_filter_is_identity():
+    a = Attrs(n=2, c=3, h=5, w=4, k=3, r=3, s=3, pbh=1, pbw=1, pah=1, paw=1)
+    x = rng.uniform(-1, 1, (2, 3, 5, 4))
+    w = np.zeros((3, 3, 3, 3))
+    for k in range(3):
+        w[k, k, 1, 1] = 1.0
+    assert np.array_equal(oracle.conv_fwd(a, x, w), x)
+
+
+def test_no_flip_off_centre_delta():
+    # tap (r,s)=(0,2) of a 3x3 filter picks x[p-1, q+1] under pad 1: cross-correlation, not flipped
+    a = Attrs(n=1, c=1, h=4, w=4, k=1, r=3, s=3, pbh=1, pbw=1, pah=1, paw=1)
+    x = rng.uniform(-1, 1, (1, 1, 4, 4))
+    w = np.zeros((1, 1, 3, 3)); w[0, 0, 0, 2] = 1.0
+    y = oracle.conv_fwd(a, x, w)
+    exp = np.zeros_like(x)
+    exp[0, 0, 1:, :3] = x[0, 0, :3, 1:]
+    assert np.array_equal(y, exp)
+
+
+# ---------------------------------------------------------------- P7 construction identities
+def test_padding_equals_explicit_zero_pad():
+    a = Attrs(n=2, c=2, h=5, w=6, k=3, r=3, s=2, sh=1, sw=2, pbh=2, pbw=1, pah=0, paw=3)
+    x, w, _ = _random_tensors(a)
+    xp = np.zeros((2, 2, 5 + 2, 6 + 4)); xp[:, :, 2:7, 1:7] = x
+    b = Attrs(n=2, c=2, h=7, w=10, k=3, r=3, s=2, sh=1, sw=2)
+    assert np.array_equal(oracle.conv_fwd(a, x, w), oracle.conv_fwd(b, xp, w))
+
+
+def test_stride_is_subsample_of_stride1():
+    a1 = Attrs(n=1, c=2, h=9, w=8, k=2, r=3, s=3, pbh=1, pbw=1, pah=1, paw=1)
+    a2 = Attrs(n=1, c=2, h=9, w=8, k=2, r=3, s=3, sh=2, sw=3, pbh=1, pbw=1, pah=1, paw=1)
+    x, w, _ = _random_tensors(a1)
+    y1 = oracle.conv_fwd(a1, x, w)
+    y2 = oracle.conv_fwd(a2, x, w)
+    assert np.array_equal(y2, y1[:, :, ::2, ::3][:, :, :y2.shape[2], :y2.shape[3]])
+
+
+def test_dilation_equals_zero_stuffed_filter():
+    a = Attrs(n=1, c=2, h=9, w=9, k=2, r=3, s=2, dh=2, dw=3, pbh=1, pbw=2, pah=2, paw=1)
+    x, w, _ = _random_tensors(a)
+    wz = np.zeros((2, 2, 5, 4)); wz[:, :, ::2, ::3] = w
+    b = Attrs(n=1, c=2, h=9, w=9, k=2, r=5, s=4, pbh=1, pbw=2, pah=2, paw=1)
+    assert oracle.out_shape(a) == oracle.out_shape(b)
+    assert np.array_equal(oracle.conv_fwd(a, x, w), oracle.conv_fwd(b, x, wz))
+
+
+# ---------------------------------------------------------------- P8 linearity
+def test_linearity():
+    a = Attrs(n=2, c=3, h=6, w=6, k=2, r=3, s=3, pbh=1, pbw=1, pah=1, paw=1)
+    x1, w, _ = _random_tensors(a)
+    x2 = rng.uniform(-1, 1, x1.shape)
+    lhs = oracle.conv_fwd(a, 2.5 * x1 + x2, w)
+    rhs = 2.5 * oracle.conv_fwd(a, x1, w) + oracle.conv_fwd(a, x2, w)
+    np.testing.assert_allclose(lhs, rhs, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P9 epilogue
+def test_epilogue_bias_then_relu():
+    a = Attrs(n=2, c=3, h=6, w=6, k=4, r=3, s=3, pbh=1, pbw=1, pah=1, paw=1)
+    x, w, _ = _random_tensors(a)
+    b = rng.uniform(-0.5, 0.5, a.k)
+    y = oracle.conv_fwd(a, x, w)
+    yb = oracle.conv_fwd(a, x, w, bias=b)
+    z = oracle.conv_fwd(a, x, w, bias=b, relu=True)
+    np.testing.assert_array_equal(yb, y + b[None, :, None, None])
+    assert np.all(z >= 0)
+    assert np.array_equal(z, np.where(yb > 0, yb, 0.0))
+    assert np.array_equal(oracle.conv_fwd(a, x, w, relu=True), np.where(y > 0, y, 0.0))
+    assert (yb < 0).any() and (yb > 0).any()
+
+
+# ---------------------------------------------------------------- P10 layout
+@pytest.mark.parametrize("dtype", [np.uint16, np.uint32])
+@pytest.mark.parametrize("c", [1, 3, 16, 17, 40])
+def test_layout_roundtrip_and_formula(dtype, c):
+    n, h, w = 2, 3, 5
+    x = rng.integers(1, np.iinfo(dtype).max, size=(n, c, h, w), dtype=dtype)   # never 0
+    xb = oracle.nchw_to_blocked16(x)
+    cb = (c + 15) // 16
+    assert xb.shape == (n, cb, h, w, 16) and xb.dtype == dtype
+    # independent statement of the permutation with numpy axis moves
+    pad = np.zeros((n, cb * 16, h, w), dtype=dtype); pad[:, :c] = x
+    exp = pad.reshape(n, cb, 16, h, w).transpose(0, 1, 3, 4, 2)
+    assert np.array_equal(xb, exp)
+    assert np.count_nonzero(xb) == x.size                  # tail lanes are zero bits
+    assert np.array_equal(oracle.blocked16_to_nchw(xb, c), x)
+    assert np.array_equal(np.sort(xb[xb != 0].ravel()), np.sort(x.ravel()))
+
+
+# ---------------------------------------------------------------- P11 bf16 rounding
+def test_bf16_rne_fixed_cases():
+    lib = oracle.conv_oracle._load()
+    for src, want in json.load(open(GOLD))["bf16_rne"]["cases"]:
+        assert lib.ref_f32_bits_to_bf16_rne(int(src, 16)) == int(want, 16), src
+
+
+def test_bf16_rne_matches_torch_and_generator():
+    import torch
+    import synth_inputs
+    v = rng.standard_normal(1_000_000).astype(np.float32) * np.float32(10.0) ** rng.integers(-20, 20, 1_000_000).astype(np.float32)
+    v[:1000] = np.ldexp(1.0 + (2 * rng.integers(0, 128, 1000) + 1) / 256.0, rng.integers(-10, 10, 1000)).astype(np.float32)  # exact ties
+    ours = oracle.f32_to_bf16_bits_rne(v)
+    t = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, t)
+    assert np.array_equal(ours, synth_inputs.f32_to_bf16_bits(v))
+    assert np.array_equal(oracle.bf16_bits_to_f64(ours), torch.from_numpy(t.view(np.int16)).view(torch.bfloat16).double().numpy())
