@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the Convolution hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input for the workload
+the headline metric is quoted on (BASELINE configs[1]): ResNet-style 3x3 conv layer, bf16
+data with fp32 accumulate, N=64, C=K=64, 56x56, stride 1, pad 1 -- forward with the fused
+bias+ReLU epilogue, ConvolutionBackpropData and ConvolutionBackpropFilters, all on
+16-channel-blocked tensors, inputs resident in HBM, filters already in their blocked
+layouts (the re-layout happens once per weight update and is timed separately).
+
+Prints ONE JSON line (see README for the fields).  `--workload` selects another
+configuration for experiments; the default line is the contract.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
+    return ap.parse_args()
+
+
+class LayerBench:
+    """Device buffers and launch closures of one layer (all ops through the C ABI)."""
+
+    def __init__(self, L, ng, torch, gpu_util, nchw_input=False, sets=1):
+        import numpy as np
+        import oracle  # host-side input preparation only (layout of the uploaded tensors)
+        self.L, self.ng, self.torch = L, ng, torch
+        a = gpu_util.attrs_of(L)
+        self.a = a
+        t = __import__("synth_inputs").layer_tensors(L)
+        blocked_in = L.c % 16 == 0
+        self.xl = ng.NGC_NCHW16C if blocked_in else ng.NGC_NCHW
+        self.yl = ng.NGC_NCHW16C
+        epi = (ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU) if L.bias_relu else ng.NGC_EPI_NONE
+        mk = gpu_util.desc_of
+        self.d_fwd = mk(a, "bf16", self.xl, self.yl, ng.NGC_BLOCKED_FWD if blocked_in else ng.NGC_KCRS, epi)
+        self.d_bwd = mk(a, "bf16", self.xl, self.yl, ng.NGC_BLOCKED_BWD if blocked_in else ng.NGC_KCRS)
+        self.d_wg = mk(a, "bf16", self.xl, self.yl)
+        wbits = gpu_util.encode(t["w"], "bf16")
+        self.w_kcrs = gpu_util.dev(wbits)
+        if blocked_in:
+            self.w_fwd = torch.empty(ng.ngc_filter_elems(self.d_fwd, ng.NGC_BLOCKED_FWD), dtype=torch.int16, device="cuda")
+            self.w_bwd = torch.empty(ng.ngc_filter_elems(self.d_fwd, ng.NGC_BLOCKED_BWD), dtype=torch.int16, device="cuda")
+            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_fwd, ng.NGC_BLOCKED_FWD, gpu_util.stream())
+            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_bwd, ng.NGC_BLOCKED_BWD, gpu_util.stream())
+        else:
+            self.w_fwd = self.w_bwd = self.w_kcrs
+        self.bias = gpu_util.dev(np.asarray(t["bias"], dtype=np.float32))
+        self.nchw_input = nchw_input
+        self.sets = []
+        x0 = gpu_util.data_to_device(t["x"], "bf16", self.xl)
+        dy0 = gpu_util.data_to_device(t["dy"], "bf16", self.yl)
+        x_nchw0 = gpu_util.dev(gpu_util.encode(t["x"], "bf16")) if nchw_input else None
+        for i in range(sets):
+            s = {"x": x0 if i == 0 else x0.clone(), "dy": dy0 if i == 0 else dy0.clone(),
+                 "y": torch.empty(ng.ngc_data_elems(self.d_fwd, 1), dtype=torch.int16, device="cuda"),
+                 "dx": torch.empty(ng.ngc_data_elems(self.d_fwd, 0), dtype=torch.int16, device="cuda"),
+                 "dw": torch.empty(L.k * L.c * L.r * L.s, dtype=torch.float32, device="cuda")}
+            if nchw_input:
+                s["x_nchw"] = x_nchw0 if i == 0 else x_nchw0.clone()
+            self.sets.append(s)
+        self.ws = {op: gpu_util.workspace(d, op) for op, d in
+                   ((ng.NGC_OP_FWD, self.d_fwd), (ng.NGC_OP_BWD_DATA, self.d_bwd), (ng.NGC_OP_BWD_FILTERS, self.d_wg))}
+        self.stream = gpu_util.stream()
+        self.ops = list(L.ops)
+        if nchw_input:
+            self.ops = ["convert"] + self.ops
+
+    def launch(self, op, i=0):
+        ng, s = self.ng, self.sets[i % len(self.sets)]
+        L = self.L
+        if op == "convert":
+            ng.ngc_layout_convert(ng.NGC_BF16, L.n, L.c, L.h, L.w, s["x_nchw"], ng.NGC_NCHW, s["x"], ng.NGC_NCHW16C, self.stream)
+        elif op == "fwd":
+            ng.ngc_conv_fwd(self.d_fwd, s["x"], self.w_fwd, self.bias if L.bias_relu else None, s["y"],
+                            self.ws[ng.NGC_OP_FWD], self.stream)
+        elif op == "bwd_data":
+            ng.ngc_conv_bwd_data(self.d_bwd, s["dy"], self.w_bwd, s["dx"], self.ws[ng.NGC_OP_BWD_DATA], self.stream)
+        elif op == "bwd_filters":
+            ng.ngc_conv_bwd_filters(self.d_wg, s["x"], s["dy"], s["dw"], self.ws[ng.NGC_OP_BWD_FILTERS], self.stream)
+        else:
+            raise ValueError(op)
+
+    def step(self, i=0):
+        for op in self.ops:
+            self.launch(op, i)
+
+    def algorithmic_bytes(self, op):
+        """Each tensor once (bf16 data, fp32 dw / bias)."""
+        L = self.L
+        xb = 2 * L.n * L.c * L.h * L.w
+        yb = 2 * L.n * L.k * L.p * L.q
+        wb = 2 * L.k * L.c * L.r * L.s
+        if op == "convert":
+            return 2 * xb
+        if op == "fwd":
+            return xb + yb + wb + 4 * L.k
+        if op == "bwd_data":
+            return xb + yb + wb
+        return xb + yb + 2 * wb          # bwd_filters: dw fp32
+
+
+def event_time_ms(torch, fn, reps):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(L):
+    """The oracle as it stands, one pass over the full cfg2 tensors, timed on the host cores."""
+    import numpy as np
+    import oracle
+    import synth_inputs
+    from gpu_util import attrs_of
+    a = attrs_of(L)
+    t = synth_inputs.layer_tensors(L)
+    x, w, dy = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
+    t0 = time.perf_counter()
+    oracle.conv_fwd(a, x, w, bias=t["bias"], relu=True)
+    oracle.conv_bwd_data_gather(a, dy, w)
+    oracle.conv_bwd_filters(a, x, dy)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+    return {"value": 3 * L.flop_per_op / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"one full pass (fwd+bias+ReLU, backprop-data gather form, backprop-filters) over the "
+                      f"N={L.n} {L.name} tensors in fp64"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives are part of it); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    import paper_1801_08058_amd as ng
+    import gpu_util
+    import synth_inputs
+
+    cfg = int(args.workload[3:])
+    layers = synth_inputs.config_layers(cfg)
+    sets = 1
+    if args.cold:
+        per_set = sum(2 * 2 * (L.n * L.c * L.h * L.w + L.n * L.k * L.p * L.q) for L in layers[:1])
+        sets = max(2, int(600e6 // per_set) + 1)
+    benches = [LayerBench(L, ng, torch, gpu_util, nchw_input=(cfg == 3), sets=sets) for L in layers]
+    torch.cuda.synchronize()
+
+    def step(i):
+        for b in benches:
+            for _ in range(b.L.count):
+                b.step(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    flop_step = sum(L.flop_per_op * len(L.ops) * L.count for L in layers)
+    value = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel durations (HIP events on the launch stream around back-to-back launches)
+    kern = {}
+    reps = max(20, min(args.steps, 200))
+    for b in benches:
+        for op in b.ops:
+            ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps)
+            flop = 0.0 if op == "convert" else b.L.flop_per_op
+            kern[f"{b.L.name}:{op}"] = {
+                "us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+                "gbs": round(b.algorithmic_bytes(op) / (ms * 1e-3) / 1e9, 1),
+                "variant": {"convert": "layout", "fwd": ng.ngc_conv_variant(b.d_fwd, 0),
+                            "bwd_data": ng.ngc_conv_variant(b.d_bwd, 1),
+                            "bwd_filters": ng.ngc_conv_variant(b.d_wg, 2)}[op],
+                "count": b.L.count}
+    dom_name = max(kern, key=lambda k: kern[k]["us"] * kern[k]["count"])
+    dom = kern[dom_name]
+    if cfg in (2,):
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": dom_name}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom_name}
+
+    out = {
+        "metric": "conv TFLOP/s fwd+bwd (ResNet 3x3 bf16 layer) and % of MFMA peak, 1 GPU",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": {2: "configs[1]: 3x3 conv N=64 C=K=64 56x56 s1 p1 bf16, fwd(+bias+ReLU) + bwd_data + bwd_filters",
+                                3: "configs[2]: 1x1 conv N=64 C=256 K=64 56x56 bf16, NCHW->nChw16c convert + fwd + bwd_data + bwd_filters",
+                                4: "configs[3]: stem 7x7/2 N=64 C=3 K=64 224x224 bf16, fwd(+bias+ReLU) + bwd_filters",
+                                5: "configs[4]: ResNet-50 conv stack N=128 bf16, 53 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
+                   "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm"},
+        "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "gflop_per_step": round(flop_step / 1e9, 2),
+        "roofline": roof,
+        "kernels": kern,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth_inputs.config_layers(2)[0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

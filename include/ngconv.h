@@ -1,0 +1,149 @@
+/*
+ * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family.
+ *
+ * The library plays the part of the kernels a backend "transformer" selects
+ * for an IR graph (paper Sec. 4, "Transformers": tensor-element layout and
+ * shape management combined with backend kernel selection; convolution named
+ * as a common backend kernel) behind the "allocation and execution API" the
+ * paper's Sec. 1 describes: the caller allocates, the library executes.
+ * An op is a stateless node; its inputs and constant attributes determine the
+ * output shape and element type (Sec. 2, "Intermediate Representation").  The
+ * attributes here are the Convolution op's: window movement strides, padding
+ * below / above, window dilation, plus the element type and the element
+ * layout of each tensor (Sec. 2: no fixed relation between axis order and
+ * element layout for tensors the user does not see).
+ *
+ * Definitions (cross-correlation, no filter flip; floor output size):
+ *   P = floor((H + pad_below_h + pad_above_h - dil_h*(R-1) - 1) / stride_h) + 1, Q likewise
+ *   forward         y[n,k,p,q]  = sum_{c,r,s} X(n,c, p*stride_h - pad_below_h + r*dil_h,
+ *                                                   q*stride_w - pad_below_w + s*dil_w) * w[k,c,r,s]
+ *                   X = x inside the image, 0 outside
+ *   epilogue        z = y (+ bias[k]) ; z = max(z,0)     (the compounded op, Abstract:
+ *                   "HW-specific compounding of operations"), applied on the fp32
+ *                   accumulator before the single rounding to the output type
+ *   backprop-data   dx = adjoint of forward w.r.t. x applied to dy  (Sec. 3: derivative
+ *                   ops come from autodiff of the forward op); elements of dx that no
+ *                   window touches are written as 0
+ *   backprop-filt.  dw = adjoint of forward w.r.t. w applied to dy; always fp32, [K,C,R,S]
+ *
+ * Conventions common to every call
+ *   - All data / filter / bias / workspace pointers are DEVICE pointers on the current
+ *     HIP device.  `hip_stream` is a hipStream_t (NULL = the default stream).
+ *   - The caller owns every buffer.  The library never allocates or frees device
+ *     memory, never synchronises, never changes the current device.  All work is
+ *     enqueued on `hip_stream`; calls return once enqueued.
+ *   - Outputs are fully overwritten (never accumulated into).  Inputs and outputs must
+ *     not overlap.
+ *   - Every call validates its arguments on the host first and returns a negative
+ *     ngc_status without launching anything if they are invalid.  A descriptor for
+ *     which no kernel exists returns NGC_UNSUPPORTED; there is no CPU fallback.
+ *   - Accumulation is always fp32.  bf16 results are rounded once, to nearest even.
+ *   - Results are run-to-run identical (no floating-point atomics).
+ *   - Each tensor must hold fewer than 2^31 elements.
+ *
+ * Element layouts
+ *   NGC_NCHW      x[n][c][h][w]
+ *   NGC_NCHW16C   x[n][cb][h][w][ci], c = 16*cb + ci, cb < ceil(C/16); lanes with
+ *                 c >= C hold +0 (writers store +0 there, readers may rely on it)
+ *   NGC_KCRS          w[k][c][r][s]
+ *   NGC_BLOCKED_FWD   w[r][s][cb][k][ci]   (c = 16*cb+ci; C padded to 16 with +0)
+ *   NGC_BLOCKED_BWD   w[r][s][kb][c][ki]   (k = 16*kb+ki; K padded to 16 with +0)
+ *                 The two blocked filter layouts put the reduction axis of forward /
+ *                 backprop-data innermost; they are produced by ngc_filter_convert.
+ */
+#ifndef NGCONV_H
+#define NGCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NGC_OK = 0,
+    NGC_BAD_ARG = -1,             /* null pointer, bad enum value, bias missing with NGC_EPI_BIAS */
+    NGC_BAD_SHAPE = -2,           /* non-positive dim, stride/dilation < 1, negative pad, P or Q <= 0,
+                                     tensor with >= 2^31 elements */
+    NGC_UNSUPPORTED = -3,         /* valid descriptor, but no kernel for this dtype/layout combination */
+    NGC_WORKSPACE_TOO_SMALL = -4, /* ws_bytes < ngc_conv_workspace_bytes(...) or ws null when needed */
+    NGC_LAUNCH_FAILED = -5        /* the HIP runtime refused a launch (hipGetLastError != success) */
+} ngc_status;
+
+typedef enum { NGC_F32 = 0, NGC_BF16 = 1 } ngc_dtype;
+typedef enum { NGC_NCHW = 0, NGC_NCHW16C = 1 } ngc_data_layout;
+typedef enum { NGC_KCRS = 0, NGC_BLOCKED_FWD = 1, NGC_BLOCKED_BWD = 2 } ngc_filter_layout;
+enum { NGC_EPI_NONE = 0, NGC_EPI_BIAS = 1, NGC_EPI_RELU = 2 };   /* bit flags, forward only */
+enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2 };
+
+/* Constant attributes of one Convolution node and of its two derivative nodes. */
+typedef struct {
+    int32_t n, c, h, w;            /* data batch shape, logical axes N,C,H,W whatever the layout    */
+    int32_t k, r, s;               /* filters: K x C x R x S                                        */
+    int32_t stride_h, stride_w;    /* window movement strides, >= 1                                 */
+    int32_t dil_h, dil_w;          /* window dilation, >= 1                                         */
+    int32_t pad_below_h, pad_below_w;   /* zero padding on the low-index side (top, left), >= 0     */
+    int32_t pad_above_h, pad_above_w;   /* zero padding on the high-index side (bottom, right), >= 0*/
+    int32_t dtype;                 /* ngc_dtype of x, w, y, dy, dx (bias and dw are always fp32)    */
+    int32_t x_layout;              /* ngc_data_layout of x and dx                                   */
+    int32_t y_layout;              /* ngc_data_layout of y and dy                                   */
+    int32_t w_layout;              /* ngc_filter_layout of the filter argument of fwd / bwd_data    */
+    int32_t epilogue;              /* NGC_EPI_* flags, used by ngc_conv_fwd only                    */
+} ngc_conv_desc;
+
+/* Output extents P, Q of the node (Sec. 2: attributes determine the output shape).
+ * Host only.  Returns NGC_OK, NGC_BAD_ARG (null) or NGC_BAD_SHAPE. */
+int ngc_conv_out_shape(const ngc_conv_desc *desc, int32_t *p, int32_t *q);
+
+/* Bytes of device workspace `op` (NGC_OP_*) needs for this descriptor; 0 if none or if the
+ * descriptor is invalid / unsupported (the op call itself reports the error).  Host only. */
+size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op);
+
+/* Convolution forward with the compounded bias / ReLU epilogue (Sec. 4 kernel; Abstract,
+ * compounding).  x: [N,C,H,W] in x_layout; w: [K,C,R,S] in w_layout (KCRS or BLOCKED_FWD);
+ * bias: fp32 [K], may be NULL unless NGC_EPI_BIAS is set; y: [N,K,P,Q] in y_layout, overwritten. */
+int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const float *bias,
+                 void *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ConvolutionBackpropData (Sec. 3, derivative of the forward node w.r.t. its data input).
+ * dy: [N,K,P,Q] in y_layout; w: in w_layout (KCRS or BLOCKED_BWD); dx: [N,C,H,W] in x_layout,
+ * every element overwritten (0 where no window reaches).  No epilogue. */
+int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w,
+                      void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ConvolutionBackpropFilters (Sec. 3, derivative w.r.t. the filters input).
+ * x in x_layout, dy in y_layout; dw: fp32 [K][C][R][S], overwritten.  The cross-workgroup
+ * reduction goes through `ws` (partials) and a fixed-order second stage. */
+int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy,
+                         float *dw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Data layout conversion (Abstract / Sec. 2: data layout abstraction): copies bit patterns
+ * between NGC_NCHW and NGC_NCHW16C for an [n,c,h,w] tensor of `dtype`; tail lanes of a blocked
+ * destination are written as +0.  src_layout == dst_layout is a plain copy.  Bit exact. */
+int ngc_layout_convert(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w,
+                       const void *src, int32_t src_layout, void *dst, int32_t dst_layout,
+                       void *hip_stream);
+
+/* Filter re-layout (done once per weight update): w_kcrs [K][C][R][S] of desc->dtype ->
+ * dst_layout (NGC_BLOCKED_FWD or NGC_BLOCKED_BWD), padded lanes +0.  Bit exact.
+ * Destination sizes: ngc_filter_elems(desc, dst_layout) elements. */
+int ngc_filter_convert(const ngc_conv_desc *desc, const void *w_kcrs, void *w_blocked,
+                       int32_t dst_layout, void *hip_stream);
+
+/* Element counts of the tensors of a node in their layouts (blocked layouts pad the blocked
+ * axis to a multiple of 16).  which: 0 = x/dx, 1 = y/dy.  Host only; 0 on invalid input. */
+size_t ngc_data_elems(const ngc_conv_desc *desc, int which);
+size_t ngc_filter_elems(const ngc_conv_desc *desc, int32_t layout);
+
+/* Name of the kernel variant the dispatcher picks for (desc, op): a static string such as
+ * "igemm_bf16_128x128" or "direct"; "unsupported" / "invalid" otherwise.  Host only. */
+const char *ngc_conv_variant(const ngc_conv_desc *desc, int op);
+
+/* Static description of a status code. */
+const char *ngc_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGCONV_H */

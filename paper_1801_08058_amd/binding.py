@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libngconv.so (the C ABI declared in include/ngconv.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  Tensors are
+passed as anything with a ``data_ptr()`` (torch tensors) or as raw integer device
+addresses; the stream is a raw ``hipStream_t`` value (``torch.cuda.current_stream().cuda_stream``)
+or None for the default stream.  There is no CPU fallback: if the library is missing
+the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libngconv.so")
+
+# enums of include/ngconv.h
+NGC_OK, NGC_BAD_ARG, NGC_BAD_SHAPE, NGC_UNSUPPORTED, NGC_WORKSPACE_TOO_SMALL, NGC_LAUNCH_FAILED = 0, -1, -2, -3, -4, -5
+NGC_F32, NGC_BF16 = 0, 1
+NGC_NCHW, NGC_NCHW16C = 0, 1
+NGC_KCRS, NGC_BLOCKED_FWD, NGC_BLOCKED_BWD = 0, 1, 2
+NGC_EPI_NONE, NGC_EPI_BIAS, NGC_EPI_RELU = 0, 1, 2
+NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS = 0, 1, 2
+
+EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
+           "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
+           "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string")
+
+
+class ngc_conv_desc(ctypes.Structure):
+    """Mirror of the C struct: constant attributes of a Convolution node."""
+    _fields_ = [(name, ctypes.c_int32) for name in (
+        "n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "dil_h", "dil_w",
+        "pad_below_h", "pad_below_w", "pad_above_h", "pad_above_w",
+        "dtype", "x_layout", "y_layout", "w_layout", "epilogue")]
+
+    def __repr__(self):
+        return "ngc_conv_desc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"
+
+
+class NgcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {ngc_status_string(status)} ({status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1801_08058_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    D = ctypes.POINTER(ngc_conv_desc)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    lib.ngc_conv_out_shape.argtypes = [D, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.ngc_conv_out_shape.restype = ctypes.c_int
+    lib.ngc_conv_workspace_bytes.argtypes = [D, ctypes.c_int]
+    lib.ngc_conv_workspace_bytes.restype = sz
+    lib.ngc_conv_fwd.argtypes = [D, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv_fwd.restype = ctypes.c_int
+    lib.ngc_conv_bwd_data.argtypes = [D, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv_bwd_data.restype = ctypes.c_int
+    lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv_bwd_filters.restype = ctypes.c_int
+    lib.ngc_layout_convert.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp]
+    lib.ngc_layout_convert.restype = ctypes.c_int
+    lib.ngc_filter_convert.argtypes = [D, vp, vp, i32, vp]
+    lib.ngc_filter_convert.restype = ctypes.c_int
+    lib.ngc_data_elems.argtypes = [D, ctypes.c_int]
+    lib.ngc_data_elems.restype = sz
+    lib.ngc_filter_elems.argtypes = [D, i32]
+    lib.ngc_filter_elems.restype = sz
+    lib.ngc_conv_variant.argtypes = [D, ctypes.c_int]
+    lib.ngc_conv_variant.restype = ctypes.c_char_p
+    lib.ngc_status_string.argtypes = [ctypes.c_int]
+    lib.ngc_status_string.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    if t is None or isinstance(t, int):
+        return 0
+    return t.numel() * t.element_size()
+
+
+def _stream(s):
+    return ctypes.c_void_p(s) if s else None
+
+
+def _check(status: int, where: str, check: bool) -> int:
+    if check and status != NGC_OK:
+        raise NgcError(status, where)
+    return status
+
+
+def make_desc(n, c, h, w, k, r, s, stride=(1, 1), dilation=(1, 1), pad_below=(0, 0), pad_above=(0, 0),
+              dtype=NGC_BF16, x_layout=NGC_NCHW16C, y_layout=NGC_NCHW16C, w_layout=NGC_KCRS,
+              epilogue=NGC_EPI_NONE) -> ngc_conv_desc:
+    return ngc_conv_desc(n, c, h, w, k, r, s, stride[0], stride[1], dilation[0], dilation[1],
+                         pad_below[0], pad_below[1], pad_above[0], pad_above[1],
+                         dtype, x_layout, y_layout, w_layout, epilogue)
+
+
+def ngc_status_string(status: int) -> str:
+    return _lib.ngc_status_string(int(status)).decode()
+
+
+def ngc_conv_out_shape(desc: ngc_conv_desc, check: bool = True):
+    p, q = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = _lib.ngc_conv_out_shape(ctypes.byref(desc), ctypes.byref(p), ctypes.byref(q))
+    if st != NGC_OK:
+        if check:
+            raise NgcError(st, "ngc_conv_out_shape")
+        return st
+    return p.value, q.value
+
+
+def ngc_conv_workspace_bytes(desc: ngc_conv_desc, op: int) -> int:
+    return int(_lib.ngc_conv_workspace_bytes(ctypes.byref(desc), op))
+
+
+def ngc_data_elems(desc: ngc_conv_desc, which: int) -> int:
+    return int(_lib.ngc_data_elems(ctypes.byref(desc), which))
+
+
+def ngc_filter_elems(desc: ngc_conv_desc, layout: int) -> int:
+    return int(_lib.ngc_filter_elems(ctypes.byref(desc), layout))
+
+
+def ngc_conv_variant(desc: ngc_conv_desc, op: int) -> str:
+    return _lib.ngc_conv_variant(ctypes.byref(desc), op).decode()
+
+
+def ngc_conv_fwd(desc, x, w, bias, y, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_fwd(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(ws), _nbytes(ws),
+                                    _stream(stream)), "ngc_conv_fwd", check)
+
+
+def ngc_conv_bwd_data(desc, dy, w, dx, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_data(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), _nbytes(ws),
+                                         _stream(stream)), "ngc_conv_bwd_data", check)
+
+
+def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_filters(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), _nbytes(ws),
+                                            _stream(stream)), "ngc_conv_bwd_filters", check)
+
+
+def ngc_layout_convert(dtype, n, c, h, w, src, src_layout, dst, dst_layout, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_layout_convert(dtype, n, c, h, w, _ptr(src), src_layout, _ptr(dst), dst_layout,
+                                          _stream(stream)), "ngc_layout_convert", check)
+
+
+def ngc_filter_convert(desc, w_kcrs, w_blocked, dst_layout, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_filter_convert(ctypes.byref(desc), _ptr(w_kcrs), _ptr(w_blocked), dst_layout,
+                                          _stream(stream)), "ngc_filter_convert", check)

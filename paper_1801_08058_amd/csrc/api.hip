@@ -1,0 +1,373 @@
+// C ABI of libngconv: argument validation, shape inference, kernel selection, launches.
+// Host code only.  Kernel selection is the small analogue of the paper's Sec. 4 "combining of
+// tensor-element layout and shape management with backend kernel selection": the descriptor
+// (shape, attributes, element type, layouts) picks a hand-written kernel variant; a descriptor
+// without a kernel is reported as NGC_UNSUPPORTED, never routed to a CPU path.
+#include "common.h"
+
+#include <limits.h>
+#include <string.h>
+
+using namespace ngc;
+
+namespace {
+
+constexpr size_t MAX_ELEMS = (size_t)1 << 31;
+
+int out_dim(int in, int pb, int pa, int dil, int win, int stride)
+{
+    const long span = (long)in + pb + pa - (long)dil * (win - 1) - 1;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+bool layout_ok(int l) { return l == NGC_NCHW || l == NGC_NCHW16C; }
+
+size_t phys(int layout, size_t n, size_t c, size_t h, size_t w)
+{
+    return layout == NGC_NCHW ? n * c * h * w : n * ((c + 15) / 16) * h * w * 16;
+}
+
+// Validates everything that does not depend on the op.  Fills P, Q.
+int validate(const ngc_conv_desc *d, int *P, int *Q)
+{
+    if (!d) return NGC_BAD_ARG;
+    if (d->dtype != NGC_F32 && d->dtype != NGC_BF16) return NGC_BAD_ARG;
+    if (!layout_ok(d->x_layout) || !layout_ok(d->y_layout)) return NGC_BAD_ARG;
+    if (d->w_layout != NGC_KCRS && d->w_layout != NGC_BLOCKED_FWD && d->w_layout != NGC_BLOCKED_BWD) return NGC_BAD_ARG;
+    if (d->epilogue & ~(NGC_EPI_BIAS | NGC_EPI_RELU)) return NGC_BAD_ARG;
+    if (d->n < 1 || d->c < 1 || d->h < 1 || d->w < 1 || d->k < 1 || d->r < 1 || d->s < 1) return NGC_BAD_SHAPE;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1) return NGC_BAD_SHAPE;
+    if (d->pad_below_h < 0 || d->pad_below_w < 0 || d->pad_above_h < 0 || d->pad_above_w < 0) return NGC_BAD_SHAPE;
+    // keep every intermediate index comfortably inside int32
+    if (d->h > (1 << 20) || d->w > (1 << 20) || d->r > 1024 || d->s > 1024 || d->dil_h > 1024 || d->dil_w > 1024 ||
+        d->stride_h > 1024 || d->stride_w > 1024 || d->pad_below_h > (1 << 20) || d->pad_below_w > (1 << 20) ||
+        d->pad_above_h > (1 << 20) || d->pad_above_w > (1 << 20))
+        return NGC_BAD_SHAPE;
+    const int p = out_dim(d->h, d->pad_below_h, d->pad_above_h, d->dil_h, d->r, d->stride_h);
+    const int q = out_dim(d->w, d->pad_below_w, d->pad_above_w, d->dil_w, d->s, d->stride_w);
+    if (p < 1 || q < 1) return NGC_BAD_SHAPE;
+    if (phys(d->x_layout, d->n, d->c, d->h, d->w) >= MAX_ELEMS) return NGC_BAD_SHAPE;
+    if (phys(d->y_layout, d->n, d->k, p, q) >= MAX_ELEMS) return NGC_BAD_SHAPE;
+    if ((size_t)((d->k + 15) / 16) * 16 * ((d->c + 15) / 16) * 16 * d->r * d->s >= MAX_ELEMS) return NGC_BAD_SHAPE;
+    *P = p;
+    *Q = q;
+    return NGC_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64 };
+
+bool blocked_bf16(const ngc_conv_desc *d)
+{
+    return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
+}
+
+Variant pick(const ngc_conv_desc *d, int op)
+{
+    int P, Q;
+    if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
+    if (op == NGC_OP_FWD) {
+        const bool mf = blocked_bf16(d) && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
+                        (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
+        if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
+        return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
+    }
+    if (op == NGC_OP_BWD_DATA) {
+        const bool mf = blocked_bf16(d) && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
+                        d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES &&
+                        (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
+        if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
+        return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
+    }
+    if (op == NGC_OP_BWD_FILTERS) {
+        if (blocked_bf16(d) && d->c % 64 == 0 && d->k % 64 == 0 && d->r * d->s <= 65535) return V_WGRAD_64;
+        return V_DIRECT;
+    }
+    return V_INVALID;
+}
+
+size_t filter_elems(const ngc_conv_desc *d, int layout)
+{
+    if (layout == NGC_KCRS) return (size_t)d->k * d->c * d->r * d->s;
+    if (layout == NGC_BLOCKED_FWD) return (size_t)d->r * d->s * ((d->c + 15) / 16) * d->k * 16;
+    if (layout == NGC_BLOCKED_BWD) return (size_t)d->r * d->s * ((d->k + 15) / 16) * d->c * 16;
+    return 0;
+}
+
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// split of the N*P*Q reduction of backprop-filters over workgroups
+void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *splits)
+{
+    const uint32_t M = (uint32_t)d->n * P * Q;
+    const uint32_t base = (uint32_t)(d->k / 64) * (d->c / 64) * d->r * d->s;
+    uint32_t want = (1024 + base - 1) / base;
+    const uint32_t max_splits = (M + 63) / 64;
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    uint32_t ch = (M + want - 1) / want;
+    ch = (ch + 63) / 64 * 64;
+    *chunk = ch;
+    *splits = (int)((M + ch - 1) / ch);
+}
+
+size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
+{
+    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64))
+        return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
+    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64))
+        return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
+    if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_64) {
+        uint32_t chunk;
+        int splits;
+        wgrad_split(d, P, Q, &chunk, &splits);
+        return round256((size_t)splits * d->r * d->s * d->k * d->c * sizeof(float));
+    }
+    return 0;
+}
+
+int launch_status(hipError_t e) { return e == hipSuccess ? NGC_OK : NGC_LAUNCH_FAILED; }
+
+void fill_class(IgemmClass &c, int oa_h, int oa_w, int OP, int OQ, int tap_begin, int tap_count, int N)
+{
+    c.oa_h = oa_h;
+    c.oa_w = oa_w;
+    c.OP = OP;
+    c.OQ = OQ;
+    c.tap_begin = tap_begin;
+    c.tap_count = tap_count;
+    c.M = (uint32_t)N * OP * OQ;
+    c.div_pq = make_fastdiv((uint32_t)(OP * OQ > 0 ? OP * OQ : 1));
+    c.div_q = make_fastdiv((uint32_t)(OQ > 0 ? OQ : 1));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ngc_conv_out_shape(const ngc_conv_desc *desc, int32_t *p, int32_t *q)
+{
+    if (!desc || !p || !q) return NGC_BAD_ARG;
+    int P, Q;
+    const int st = validate(desc, &P, &Q);
+    if (st != NGC_OK) return st;
+    *p = P;
+    *q = Q;
+    return NGC_OK;
+}
+
+size_t ngc_data_elems(const ngc_conv_desc *desc, int which)
+{
+    int P, Q;
+    if (validate(desc, &P, &Q) != NGC_OK) return 0;
+    if (which == 0) return phys(desc->x_layout, desc->n, desc->c, desc->h, desc->w);
+    if (which == 1) return phys(desc->y_layout, desc->n, desc->k, P, Q);
+    return 0;
+}
+
+size_t ngc_filter_elems(const ngc_conv_desc *desc, int32_t layout)
+{
+    int P, Q;
+    if (validate(desc, &P, &Q) != NGC_OK) return 0;
+    return filter_elems(desc, layout);
+}
+
+size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
+{
+    int P, Q;
+    if (validate(desc, &P, &Q) != NGC_OK) return 0;
+    return workspace_bytes(desc, op, pick(desc, op), P, Q);
+}
+
+const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
+{
+    switch (pick(desc, op)) {
+    case V_UNSUPPORTED: return "unsupported";
+    case V_DIRECT: return "direct";
+    case V_IGEMM_128: return "igemm_bf16_128x128";
+    case V_IGEMM_64: return "igemm_bf16_256x64";
+    case V_WGRAD_64: return "wgrad_bf16_64x64";
+    default: return "invalid";
+    }
+}
+
+const char *ngc_status_string(int status)
+{
+    switch (status) {
+    case NGC_OK: return "ok";
+    case NGC_BAD_ARG: return "bad argument (null pointer, misaligned pointer, bad enum or flag)";
+    case NGC_BAD_SHAPE: return "bad shape or attribute (non-positive dim, stride/dilation < 1, negative pad, empty output, tensor too large)";
+    case NGC_UNSUPPORTED: return "no kernel for this element type / layout combination";
+    case NGC_WORKSPACE_TOO_SMALL: return "workspace too small or missing";
+    case NGC_LAUNCH_FAILED: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const float *bias, void *y, void *ws,
+                 size_t ws_bytes, void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!x || !w || !y) return NGC_BAD_ARG;
+    if ((desc->epilogue & NGC_EPI_BIAS) && !bias) return NGC_BAD_ARG;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws)) return NGC_BAD_ARG;
+    const Variant v = pick(desc, NGC_OP_FWD);
+    if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V_DIRECT)
+        return launch_status(launch_direct_fwd(*desc, P, Q, x, w, (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr, y, st));
+
+    const size_t need = workspace_bytes(desc, NGC_OP_FWD, v, P, Q);
+    if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
+    const void *wt = w;
+    if (desc->w_layout == NGC_KCRS) {
+        const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_FWD, st);
+        if (e != hipSuccess) return NGC_LAUNCH_FAILED;
+        wt = ws;
+    }
+    IgemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.in = static_cast<const uint16_t *>(x);
+    p.wt = static_cast<const uint16_t *>(wt);
+    p.out = static_cast<uint16_t *>(y);
+    p.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+    p.N = desc->n; p.Cin = desc->c; p.Hin = desc->h; p.Win = desc->w;
+    p.Cout = desc->k; p.Hout = P; p.Wout = Q;
+    p.os_h = p.os_w = 1;
+    p.is_h = desc->stride_h; p.is_w = desc->stride_w;
+    p.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+    p.ncls = 1;
+    int t = 0;
+    for (int r = 0; r < desc->r; ++r)
+        for (int s = 0; s < desc->s; ++s) {
+            p.taps[t].dh = r * desc->dil_h - desc->pad_below_h;
+            p.taps[t].dw = s * desc->dil_w - desc->pad_below_w;
+            p.taps[t].slab = r * desc->s + s;
+            ++t;
+        }
+    fill_class(p.cls[0], 0, 0, P, Q, 0, t, desc->n);
+    return launch_status(launch_igemm(p, v == V_IGEMM_128 ? 128 : 64, p.cls[0].M, st));
+}
+
+int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
+                      void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!dy || !w || !dx) return NGC_BAD_ARG;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws)) return NGC_BAD_ARG;
+    const Variant v = pick(desc, NGC_OP_BWD_DATA);
+    if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, dx, st));
+
+    const size_t need = workspace_bytes(desc, NGC_OP_BWD_DATA, v, P, Q);
+    if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
+    const void *wt = w;
+    if (desc->w_layout == NGC_KCRS) {
+        const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_BWD, st);
+        if (e != hipSuccess) return NGC_LAUNCH_FAILED;
+        wt = ws;
+    }
+    IgemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.in = static_cast<const uint16_t *>(dy);
+    p.wt = static_cast<const uint16_t *>(wt);
+    p.out = static_cast<uint16_t *>(dx);
+    p.bias = nullptr;
+    p.N = desc->n; p.Cin = desc->k; p.Hin = P; p.Win = Q;
+    p.Cout = desc->c; p.Hout = desc->h; p.Wout = desc->w;
+    p.os_h = desc->stride_h; p.os_w = desc->stride_w;
+    p.is_h = p.is_w = 1;
+    p.relu = 0;
+    const int sh = desc->stride_h, sw = desc->stride_w;
+    p.ncls = sh * sw;
+    int t = 0;
+    uint32_t max_m = 0;
+    for (int a = 0; a < sh; ++a)
+        for (int b = 0; b < sw; ++b) {
+            const int begin = t;
+            for (int r = 0; r < desc->r; ++r) {
+                const int vh = a + desc->pad_below_h - r * desc->dil_h;
+                if (((vh % sh) + sh) % sh != 0) continue;
+                for (int s = 0; s < desc->s; ++s) {
+                    const int vw = b + desc->pad_below_w - s * desc->dil_w;
+                    if (((vw % sw) + sw) % sw != 0) continue;
+                    p.taps[t].dh = vh / sh;              // exact
+                    p.taps[t].dw = vw / sw;
+                    p.taps[t].slab = r * desc->s + s;
+                    ++t;
+                }
+            }
+            const int OPc = a < desc->h ? (desc->h - a + sh - 1) / sh : 0;
+            const int OQc = b < desc->w ? (desc->w - b + sw - 1) / sw : 0;
+            IgemmClass &c = p.cls[a * sw + b];
+            fill_class(c, a, b, OPc, OQc, begin, t - begin, desc->n);
+            if (OPc == 0 || OQc == 0) c.M = 0;
+            if (c.M > max_m) max_m = c.M;
+        }
+    return launch_status(launch_igemm(p, v == V_IGEMM_128 ? 128 : 64, max_m, st));
+}
+
+int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw, void *ws,
+                         size_t ws_bytes, void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!x || !dy || !dw) return NGC_BAD_ARG;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(ws)) return NGC_BAD_ARG;
+    const Variant v = pick(desc, NGC_OP_BWD_FILTERS);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V_DIRECT) return launch_status(launch_direct_bwd_filters(*desc, P, Q, x, dy, dw, st));
+
+    const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);
+    if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    WgradParams p;
+    memset(&p, 0, sizeof(p));
+    p.x = static_cast<const uint16_t *>(x);
+    p.dy = static_cast<const uint16_t *>(dy);
+    p.partial = static_cast<float *>(ws);
+    p.N = desc->n; p.C = desc->c; p.H = desc->h; p.W = desc->w;
+    p.K = desc->k; p.P = P; p.Q = Q; p.R = desc->r; p.S = desc->s;
+    p.sh = desc->stride_h; p.sw = desc->stride_w; p.dh = desc->dil_h; p.dw = desc->dil_w;
+    p.pbh = desc->pad_below_h; p.pbw = desc->pad_below_w;
+    p.M = (uint32_t)desc->n * P * Q;
+    wgrad_split(desc, P, Q, &p.chunk, &p.splits);
+    p.div_pq = make_fastdiv((uint32_t)(P * Q));
+    p.div_q = make_fastdiv((uint32_t)Q);
+    hipError_t e = launch_wgrad(p, st);
+    if (e != hipSuccess) return NGC_LAUNCH_FAILED;
+    return launch_status(launch_wgrad_reduce(p.partial, dw, p.splits, desc->k, desc->c, desc->r, desc->s, st));
+}
+
+int ngc_layout_convert(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, const void *src, int32_t src_layout,
+                       void *dst, int32_t dst_layout, void *hip_stream)
+{
+    if (dtype != NGC_F32 && dtype != NGC_BF16) return NGC_BAD_ARG;
+    if (!layout_ok(src_layout) || !layout_ok(dst_layout)) return NGC_BAD_ARG;
+    if (!src || !dst) return NGC_BAD_ARG;
+    if (n < 1 || c < 1 || h < 1 || w < 1) return NGC_BAD_SHAPE;
+    if ((size_t)n * (((size_t)c + 15) / 16) * 16 * h * w >= MAX_ELEMS) return NGC_BAD_SHAPE;
+    return launch_status(launch_layout_convert(dtype == NGC_F32 ? 4 : 2, n, c, h, w, src, src_layout, dst, dst_layout,
+                                               static_cast<hipStream_t>(hip_stream)));
+}
+
+int ngc_filter_convert(const ngc_conv_desc *desc, const void *w_kcrs, void *w_blocked, int32_t dst_layout,
+                       void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!w_kcrs || !w_blocked) return NGC_BAD_ARG;
+    if (dst_layout != NGC_BLOCKED_FWD && dst_layout != NGC_BLOCKED_BWD) return NGC_BAD_ARG;
+    return launch_status(launch_filter_convert(desc->dtype == NGC_F32 ? 4 : 2, desc->k, desc->c, desc->r, desc->s, w_kcrs,
+                                               w_blocked, dst_layout, static_cast<hipStream_t>(hip_stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Internal declarations shared by the translation units of libngconv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/ngconv.h"
+
+namespace ngc {
+
+// ---- exact unsigned division by a runtime constant (round-up multiplier method) ----
+// q = n / d for every 32-bit n: t = mulhi(mul, n); q = (t + ((n - t) >> sh1)) >> sh2.
+struct FastDiv {
+    uint32_t mul, sh1, sh2, d;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;                       // l = ceil(log2 d)
+    f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l - f.sh1;
+    f.d = d;
+    return f;
+}
+
+__host__ __device__ inline uint32_t fd_mulhi(uint32_t a, uint32_t b)
+{
+    return (uint32_t)(((uint64_t)a * b) >> 32);      // v_mul_hi_u32 on the device
+}
+
+__host__ __device__ inline uint32_t fd_div(uint32_t n, const FastDiv &f)
+{
+    uint32_t t = fd_mulhi(f.mul, n);
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+// ---- bf16 bit helpers ----
+__host__ __device__ inline float bf16_bits_to_float(uint16_t b)
+{
+    union { uint32_t u; float f; } v;
+    v.u = (uint32_t)b << 16;
+    return v.f;
+}
+
+// round-to-nearest-even on the 16 dropped bits (finite inputs; canonical NaN stays NaN)
+__host__ __device__ inline uint32_t float_to_bf16_bits(float x)
+{
+    union { uint32_t u; float f; } v;
+    v.f = x;
+    uint32_t u = v.u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__host__ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
+{
+    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+}
+
+// ---- element index functions for the public layouts ----
+__host__ __device__ inline size_t data_index(int layout, int C, int H, int W, int n, int c, int h, int w)
+{
+    if (layout == NGC_NCHW) return (((size_t)n * C + c) * H + h) * W + w;
+    const int CB = (C + 15) >> 4;
+    return ((((size_t)n * CB + (c >> 4)) * H + h) * W + w) * 16 + (c & 15);
+}
+
+__host__ __device__ inline size_t filter_index(int layout, int K, int C, int R, int S, int k, int c, int r, int s)
+{
+    if (layout == NGC_KCRS) return (((size_t)k * C + c) * R + r) * S + s;
+    if (layout == NGC_BLOCKED_FWD) {                    // [r][s][cb][k][ci]
+        const int CB = (C + 15) >> 4;
+        return ((((size_t)(r * S + s)) * CB + (c >> 4)) * K + k) * 16 + (c & 15);
+    }
+    const int KB = (K + 15) >> 4;                       // [r][s][kb][c][ki]
+    return ((((size_t)(r * S + s)) * KB + (k >> 4)) * C + c) * 16 + (k & 15);
+}
+
+// ---- implicit-GEMM (MFMA) forward / backprop-data: generalised gather convolution ----
+// out[n, co, i*os_h+oa_h, j*os_w+oa_w] = sum_{tap t in class} sum_ci
+//        in[n, ci, i*is_h + t.dh, j*is_w + t.dw] * wt[t.slab][ci/16][co][ci%16]
+constexpr int IGEMM_MAX_TAPS = 49;
+constexpr int IGEMM_MAX_CLASSES = 16;
+
+struct IgemmTap {
+    int32_t dh, dw, slab;
+};
+
+struct IgemmClass {
+    int32_t oa_h, oa_w;        // output offset of the class inside the output-stride lattice
+    int32_t OP, OQ;            // lattice extents of the class
+    int32_t tap_begin, tap_count;
+    uint32_t M;                // N*OP*OQ
+    FastDiv div_pq, div_q;     // divide by OP*OQ and by OQ
+};
+
+struct IgemmParams {
+    const uint16_t *in;
+    const uint16_t *wt;
+    uint16_t *out;
+    const float *bias;         // may be null
+    int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
+    int32_t os_h, os_w, is_h, is_w;
+    int32_t relu;
+    int32_t ncls;
+    IgemmClass cls[IGEMM_MAX_CLASSES];
+    IgemmTap taps[IGEMM_MAX_TAPS];
+};
+
+// ---- MFMA backprop-filters ----
+struct WgradParams {
+    const uint16_t *x;         // blocked [N][C/16][H][W][16]
+    const uint16_t *dy;        // blocked [N][K/16][P][Q][16]
+    float *partial;            // [split][tap][K][C]
+    int32_t N, C, H, W, K, P, Q, R, S;
+    int32_t sh, sw, dh, dw, pbh, pbw;
+    uint32_t M;                // N*P*Q
+    uint32_t chunk;            // positions per split (multiple of 64)
+    int32_t splits;
+    FastDiv div_pq, div_q;
+};
+
+// launchers (each returns hipGetLastError() after the launch)
+hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
+hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
+hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,
+                               hipStream_t st);
+hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x, const void *w,
+                             const float *bias, void *y, hipStream_t st);
+hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w,
+                                  void *dx, hipStream_t st);
+hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const void *x, const void *dy,
+                                     float *dw, hipStream_t st);
+hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,
+                                 void *dst, int dst_layout, hipStream_t st);
+hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, const void *w_kcrs, void *dst,
+                                 int dst_layout, hipStream_t st);
+
+}  // namespace ngc

@@ -1,0 +1,160 @@
+"""Helpers for the GPU parity tests: move seeded host tensors to the device in the layouts
+the C ABI takes, run the HIP path, bring results back as fp64 in logical axis order.
+The host-side layout permutations used to *prepare inputs and read outputs* are the
+oracle's (pinned in test_oracle_pins.py); the device conversion kernels are tested
+separately against them."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_1801_08058_amd as ng
+import synth_inputs
+from synth_inputs import ConvLayer
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def attrs_of(L: ConvLayer) -> oracle.Attrs:
+    return oracle.Attrs(L.n, L.c, L.h, L.w, L.k, L.r, L.s, L.stride, L.stride, L.dil, L.dil,
+                        L.pad, L.pad, L.pad, L.pad)
+
+
+def desc_of(a: oracle.Attrs, dtype: str, x_layout, y_layout, w_layout=ng.NGC_KCRS, epilogue=ng.NGC_EPI_NONE):
+    return ng.make_desc(a.n, a.c, a.h, a.w, a.k, a.r, a.s, (a.sh, a.sw), (a.dh, a.dw), (a.pbh, a.pbw),
+                        (a.pah, a.paw), ng.NGC_F32 if dtype == "f32" else ng.NGC_BF16, x_layout, y_layout,
+                        w_layout, epilogue)
+
+
+def dev(arr: np.ndarray) -> torch.Tensor:
+    a = np.ascontiguousarray(arr)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def host(t: torch.Tensor, as_dtype) -> np.ndarray:
+    a = t.cpu().numpy()
+    return a.view(as_dtype)
+
+
+def encode(values_f32: np.ndarray, dtype: str) -> np.ndarray:
+    """fp32 host values -> element container (fp32 itself, or bf16 bits; values of bf16
+    configurations are already exactly representable)."""
+    if dtype == "f32":
+        return np.ascontiguousarray(values_f32, dtype=np.float32)
+    return synth_inputs.f32_to_bf16_bits(values_f32)
+
+
+def data_to_device(values_f32: np.ndarray, dtype: str, layout: int) -> torch.Tensor:
+    e = encode(values_f32, dtype)
+    if layout == ng.NGC_NCHW16C:
+        e = oracle.nchw_to_blocked16(e)
+    return dev(e)
+
+
+def data_from_device(t: torch.Tensor, dtype: str, layout: int, shape) -> np.ndarray:
+    """device tensor -> fp64 array in logical [N,C,H,W] order."""
+    n, c, h, w = shape
+    raw = host(t, np.float32 if dtype == "f32" else np.uint16)
+    if layout == ng.NGC_NCHW16C:
+        raw = raw.reshape(n, (c + 15) // 16, h, w, 16)
+        raw = oracle.blocked16_to_nchw(raw, c)
+    else:
+        raw = raw.reshape(n, c, h, w)
+    if dtype == "f32":
+        return raw.astype(np.float64)
+    return oracle.bf16_bits_to_f64(raw)
+
+
+def filter_blocked_host(w_bits: np.ndarray, layout: int) -> np.ndarray:
+    """Definition of the two blocked filter layouts, stated with numpy axis moves
+    (header of include/ngconv.h): FWD [r][s][cb][k][ci], BWD [r][s][kb][c][ki]."""
+    K, C, R, S = w_bits.shape
+    if layout == ng.NGC_BLOCKED_FWD:
+        CB = (C + 15) // 16
+        pad = np.zeros((K, CB * 16, R, S), dtype=w_bits.dtype); pad[:, :C] = w_bits
+        return np.ascontiguousarray(pad.reshape(K, CB, 16, R, S).transpose(3, 4, 1, 0, 2))
+    KB = (K + 15) // 16
+    pad = np.zeros((KB * 16, C, R, S), dtype=w_bits.dtype); pad[:K] = w_bits
+    return np.ascontiguousarray(pad.reshape(KB, 16, C, R, S).transpose(3, 4, 0, 2, 1))
+
+
+def workspace(desc, op) -> torch.Tensor | None:
+    nbytes = ng.ngc_conv_workspace_bytes(desc, op)
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+
+def stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def out_tensor(desc, which: int, dtype: str, fill: float | None = None) -> torch.Tensor:
+    n = ng.ngc_data_elems(desc, which)
+    t = torch.empty(n, dtype=torch.float32 if dtype == "f32" else torch.int16, device="cuda")
+    # poison so that unwritten elements are caught
+    if dtype == "f32":
+        t.fill_(float("nan"))
+    else:
+        t.fill_(0x7FC0)
+    return t
+
+
+class Run:
+    """Runs the three ops of one layer through the C ABI and returns fp64 results."""
+
+    def __init__(self, a: oracle.Attrs, dtype: str, x_layout: int, y_layout: int, pre_block_filters: bool):
+        self.a, self.dtype, self.xl, self.yl, self.pre = a, dtype, x_layout, y_layout, pre_block_filters
+        self.P, self.Q = oracle.out_shape(a)
+
+    def _filter(self, w_f32, layout):
+        """Filters pre-converted to the op's blocked layout when asked for and when a kernel
+        takes them (the direct kernels take KCRS only), else KCRS."""
+        wb = encode(w_f32, self.dtype)
+        op = ng.NGC_OP_FWD if layout == ng.NGC_BLOCKED_FWD else ng.NGC_OP_BWD_DATA
+        if self.pre and ng.ngc_conv_variant(desc_of(self.a, self.dtype, self.xl, self.yl, layout), op) != "unsupported":
+            return dev(filter_blocked_host(wb, layout)), layout
+        return dev(wb), ng.NGC_KCRS
+
+    def fwd(self, x, w, bias=None, relu=False):
+        a = self.a
+        epi = (ng.NGC_EPI_BIAS if bias is not None else 0) | (ng.NGC_EPI_RELU if relu else 0)
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_FWD)
+        d = desc_of(a, self.dtype, self.xl, self.yl, wl, epi)
+        xd = data_to_device(x, self.dtype, self.xl)
+        bd = dev(np.asarray(bias, dtype=np.float32)) if bias is not None else None
+        y = out_tensor(d, 1, self.dtype)
+        ws = workspace(d, ng.NGC_OP_FWD)
+        ng.ngc_conv_fwd(d, xd, wd, bd, y, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, y
+        return data_from_device(y, self.dtype, self.yl, (a.n, a.k, self.P, self.Q))
+
+    def bwd_data(self, dy, w):
+        a = self.a
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_BWD)
+        d = desc_of(a, self.dtype, self.xl, self.yl, wl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        dx = out_tensor(d, 0, self.dtype)
+        ws = workspace(d, ng.NGC_OP_BWD_DATA)
+        ng.ngc_conv_bwd_data(d, dyd, wd, dx, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, dx
+        return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
+
+    def bwd_filters(self, x, dy):
+        a = self.a
+        d = desc_of(a, self.dtype, self.xl, self.yl)
+        xd = data_to_device(x, self.dtype, self.xl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        dw = torch.full((a.k * a.c * a.r * a.s,), float("nan"), dtype=torch.float32, device="cuda")
+        ws = workspace(d, ng.NGC_OP_BWD_FILTERS)
+        ng.ngc_conv_bwd_filters(d, xd, dyd, dw, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, dw
+        return dw.cpu().numpy().astype(np.float64).reshape(a.k, a.c, a.r, a.s)

@@ -1,0 +1,261 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the fp64 CPU oracle, element
+by element, on seeded inputs.  Tolerances (max normalised error, L-inf / L-inf):
+1e-5 for fp32, 2e-2 for bf16 data; layout transforms bit exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1801_08058_amd as ng
+import synth_inputs
+from oracle import Attrs
+from gpu_util import (TOL, Run, attrs_of, data_to_device, desc_of, dev, encode, filter_blocked_host, host,
+                      out_tensor, stream, workspace)
+
+pytestmark = pytest.mark.gpu
+
+NCHW, BLK = ng.NGC_NCHW, ng.NGC_NCHW16C
+
+
+def _tensors(a: Attrs, dtype: str, seed: int):
+    P, Q = oracle.out_shape(a)
+    x = synth_inputs.normal(seed, 0, (a.n, a.c, a.h, a.w), 0.0, 1.0)
+    w = synth_inputs.normal(seed, 1, (a.k, a.c, a.r, a.s), 0.0, (2.0 / (a.c * a.r * a.s)) ** 0.5)
+    b = synth_inputs.uniform(seed, 2, (a.k,), -0.1, 0.1)
+    dy = synth_inputs.normal(seed, 3, (a.n, a.k, P, Q), 0.0, 0.1)
+    if dtype == "bf16":
+        rt = lambda t: synth_inputs.bf16_bits_to_f32(synth_inputs.f32_to_bf16_bits(t))
+        x, w, dy = rt(x), rt(w), rt(dy)
+    return x, w, b, dy
+
+
+def _check_all(a: Attrs, dtype: str, xl: int, yl: int, pre: bool, seed: int, expect_variant=None):
+    print(f"case attrs={a} dtype={dtype} xl={xl} yl={yl} pre={pre} seed={seed}", flush=True)
+    x, w, b, dy = _tensors(a, dtype, seed)
+    run = Run(a, dtype, xl, yl, pre)
+    tol = TOL[dtype]
+    y = run.fwd(x, w, bias=b, relu=True)
+    if expect_variant:
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD).startswith(expect_variant[0])
+    e = oracle.max_normalised_error(y, oracle.conv_fwd(a, x, w, bias=b, relu=True))
+    assert e <= tol, f"fwd+bias+relu err {e}"
+    y0 = run.fwd(x, w)
+    e = oracle.max_normalised_error(y0, oracle.conv_fwd(a, x, w))
+    assert e <= tol, f"fwd err {e}"
+    dx = run.bwd_data(dy, w)
+    if expect_variant:
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect_variant[1])
+    e = oracle.max_normalised_error(dx, oracle.conv_bwd_data(a, dy, w))
+    assert e <= tol, f"bwd_data err {e}"
+    dw = run.bwd_filters(x, dy)
+    if expect_variant:
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS).startswith(expect_variant[2])
+    e = oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy))
+    assert e <= (1e-5 if dtype == "f32" else tol), f"bwd_filters err {e}"
+
+
+# ------------------------------------------------------------------ layout conversion (bit exact)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 40, 7, 7), (2, 3, 14, 14), (1, 17, 5, 3), (2, 64, 56, 56),
+                                   (1, 33, 30, 31), (2, 256, 9, 30)])
+def test_layout_convert_bit_exact(dtype, shape):
+    n, c, h, w = shape
+    rng = np.random.default_rng(1234 + c * h)
+    if dtype == "bf16":
+        bits = rng.integers(1, 0xFFFF, size=shape, dtype=np.uint16)
+    else:
+        bits = rng.integers(1, 0xFFFFFFFF, size=shape, dtype=np.uint32)
+    code = ng.NGC_BF16 if dtype == "bf16" else ng.NGC_F32
+    src = dev(bits)
+    cb = (c + 15) // 16
+    dst = torch.full((n * cb * h * w * 16,), -1, dtype=src.dtype, device="cuda")
+    ng.ngc_layout_convert(code, n, c, h, w, src, NCHW, dst, BLK, stream())
+    torch.cuda.synchronize()
+    got = host(dst, bits.dtype).reshape(n, cb, h, w, 16)
+    assert np.array_equal(got, oracle.nchw_to_blocked16(bits))           # includes +0 tail lanes
+    back = torch.full((n * c * h * w,), -1, dtype=src.dtype, device="cuda")
+    ng.ngc_layout_convert(code, n, c, h, w, dst, BLK, back, NCHW, stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(host(back, bits.dtype).reshape(shape), bits)
+    # same-layout call is a copy
+    cp = torch.full((n * c * h * w,), -1, dtype=src.dtype, device="cuda")
+    ng.ngc_layout_convert(code, n, c, h, w, src, NCHW, cp, NCHW, stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(host(cp, bits.dtype).reshape(shape), bits)
+
+
+@pytest.mark.parametrize("kcrs", [(64, 32, 3, 3), (20, 17, 1, 2), (128, 64, 1, 1)])
+def test_filter_convert_bit_exact(kcrs):
+    K, C, R, S = kcrs
+    rng = np.random.default_rng(99)
+    bits = rng.integers(1, 0xFFFF, size=kcrs, dtype=np.uint16)
+    d = ng.make_desc(1, C, 8, 8, K, R, S, pad_below=(R // 2, S // 2), pad_above=(R // 2, S // 2))
+    for layout in (ng.NGC_BLOCKED_FWD, ng.NGC_BLOCKED_BWD):
+        exp = filter_blocked_host(bits, layout)
+        assert ng.ngc_filter_elems(d, layout) == exp.size
+        dst = torch.full((exp.size,), -1, dtype=torch.int16, device="cuda")
+        ng.ngc_filter_convert(d, dev(bits), dst, layout, stream())
+        torch.cuda.synchronize()
+        assert np.array_equal(host(dst, np.uint16).reshape(exp.shape), exp)
+
+
+# ------------------------------------------------------------------ configuration 1 (fp32, exact shape)
+def test_cfg1_fp32():
+    L = synth_inputs.config_layers(1)[0]
+    a = attrs_of(L)
+    t = synth_inputs.layer_tensors(L)
+    run = Run(a, "f32", NCHW, NCHW, False)
+    y = run.fwd(t["x"], t["w"], bias=t["bias"], relu=True)
+    assert oracle.max_normalised_error(y, oracle.conv_fwd(a, t["x"], t["w"], bias=t["bias"], relu=True)) <= 1e-5
+    dx = run.bwd_data(t["dy"], t["w"])
+    assert oracle.max_normalised_error(dx, oracle.conv_bwd_data(a, t["dy"], t["w"])) <= 1e-5
+    dw = run.bwd_filters(t["x"], t["dy"])
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, t["x"], t["dy"])) <= 1e-5
+
+
+# ------------------------------------------------------------------ direct kernels: every attribute
+DIRECT_CASES = [
+    Attrs(2, 5, 9, 8, 7, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),
+    Attrs(1, 3, 11, 13, 4, 3, 2, 2, 3, 1, 2, 2, 0, 1, 3),        # stride, dilation, asymmetric pads
+    Attrs(2, 17, 6, 6, 19, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),        # 1x1 stride 2, channel tails
+    Attrs(1, 4, 10, 10, 6, 5, 5, 1, 1, 2, 2, 4, 4, 4, 4),        # dilation 2
+    Attrs(3, 2, 7, 5, 3, 7, 3, 3, 1, 1, 1, 3, 1, 3, 1),
+]
+
+
+@pytest.mark.parametrize("case", range(len(DIRECT_CASES)))
+@pytest.mark.parametrize("dtype,xl,yl", [("f32", NCHW, NCHW), ("bf16", NCHW, NCHW), ("bf16", BLK, BLK),
+                                         ("f32", BLK, NCHW), ("bf16", NCHW, BLK)])
+def test_direct_kernels(case, dtype, xl, yl):
+    _check_all(DIRECT_CASES[case], dtype, xl, yl, False, 1000 + case, ("direct", "direct", "direct"))
+
+
+def test_blocked_output_tail_lanes_are_zero():
+    a = Attrs(1, 5, 6, 6, 20, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1)
+    x, w, b, dy = _tensors(a, "bf16", 7)
+    run = Run(a, "bf16", BLK, BLK, False)
+    run.fwd(x, w, bias=b, relu=False)
+    raw = host(run.last_raw, np.uint16).reshape(1, 2, 6, 6, 16)
+    assert np.all(raw[:, 1, :, :, 4:] == 0)
+    run.bwd_data(dy, w)
+    raw = host(run.last_raw, np.uint16).reshape(1, 1, 6, 6, 16)
+    assert np.all(raw[..., 5:] == 0)
+
+
+# ------------------------------------------------------------------ MFMA kernels, small multi-tile shapes
+MFMA_CASES = [
+    # n  c   h   w   k   r  s  sh sw dh dw pbh pbw pah paw
+    Attrs(3, 64, 13, 13, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # 507 positions: 2 tiles of 256 + ragged tail
+    Attrs(2, 32, 12, 10, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),     # 128x128 tile variant fwd; bwd -> direct (c%64)
+    Attrs(2, 128, 9, 11, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 1x1
+    Attrs(2, 64, 14, 14, 128, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),     # 3x3 stride 2 (bwd-data parity classes)
+    Attrs(2, 128, 14, 14, 256, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),    # 1x1 stride 2 projection (empty classes)
+    Attrs(1, 64, 15, 9, 64, 3, 3, 2, 1, 2, 1, 2, 0, 1, 1),       # mixed stride / dilation / asymmetric pads
+    Attrs(5, 64, 7, 7, 192, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # 7x7 images, several per tile; K=192 -> 256x64 tile
+    Attrs(1, 64, 16, 16, 64, 5, 5, 1, 1, 1, 1, 2, 2, 2, 2),      # 5x5
+    Attrs(2, 64, 9, 9, 64, 3, 3, 3, 3, 1, 1, 1, 1, 1, 1),        # stride 3 (9 classes)
+]
+
+
+@pytest.mark.parametrize("case", range(len(MFMA_CASES)))
+@pytest.mark.parametrize("pre", [True, False])
+def test_mfma_kernels_small(case, pre):
+    a = MFMA_CASES[case]
+    fwd_v = "igemm"
+    bwd_v = "igemm" if (a.c % 64 == 0 and a.k % 32 == 0) else "direct"
+    wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
+    _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
+
+
+def test_run_to_run_identical():
+    a = MFMA_CASES[0]
+    x, w, b, dy = _tensors(a, "bf16", 5)
+    run = Run(a, "bf16", BLK, BLK, True)
+    outs = []
+    for _ in range(2):
+        run.fwd(x, w, bias=b, relu=True); r1 = run.last_raw.clone()
+        run.bwd_data(dy, w); r2 = run.last_raw.clone()
+        run.bwd_filters(x, dy); r3 = run.last_raw.clone()
+        outs.append((r1, r2, r3))
+    for t0, t1 in zip(*outs):
+        assert torch.equal(t0.view(torch.int32) if t0.dtype == torch.float32 else t0,
+                           t1.view(torch.int32) if t1.dtype == torch.float32 else t1)
+
+
+# ------------------------------------------------------------------ benchmark configurations
+def _sampled_layer_check(L, n_y=100_000, n_dw=2048, convert_x_on_device=False):
+    """Full-size launch configuration; oracle evaluated at sampled output elements."""
+    print(f"layer {L.name} n={L.n}", flush=True)
+    a = attrs_of(L)
+    t = synth_inputs.layer_tensors(L)
+    P, Q = oracle.out_shape(a)
+    rng = np.random.default_rng(L.seed % (2 ** 32))
+    blocked_ok = L.c % 16 == 0
+    xl = BLK if blocked_ok else NCHW
+    run = Run(a, "bf16", xl, BLK, True if blocked_ok else False)
+    x64, w64, dy64 = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
+    bias = t["bias"] if L.bias_relu else None
+    if "fwd" in L.ops:
+        y = run.fwd(t["x"], t["w"], bias=bias, relu=L.bias_relu)
+        idx = rng.integers(0, y.size, n_y)
+        ref = oracle.conv_fwd_at(a, x64, w64, idx, bias=bias, relu=L.bias_relu)
+        assert oracle.max_normalised_error(y.reshape(-1)[idx], ref) <= 2e-2, "fwd"
+        assert np.isfinite(y).all()
+    if "bwd_data" in L.ops:
+        dx = run.bwd_data(t["dy"], t["w"])
+        idx = rng.integers(0, dx.size, n_y)
+        ref = oracle.conv_bwd_data_at(a, dy64, w64, idx)
+        assert oracle.max_normalised_error(dx.reshape(-1)[idx], ref) <= 2e-2, "bwd_data"
+        assert np.isfinite(dx).all()
+    if "bwd_filters" in L.ops:
+        dw = run.bwd_filters(t["x"], t["dy"])
+        idx = rng.integers(0, dw.size, min(n_dw, dw.size))
+        ref = oracle.conv_bwd_filters_at(a, x64, dy64, idx)
+        assert oracle.max_normalised_error(dw.reshape(-1)[idx], ref) <= 2e-2, "bwd_filters"
+        assert np.isfinite(dw).all()
+
+
+def test_cfg2_full_size_sampled():
+    _sampled_layer_check(synth_inputs.config_layers(2)[0])
+
+
+def test_cfg2_reduced_batch_full_tensors():
+    L = synth_inputs.config_layers(2, batch=2)[0]
+    a = attrs_of(L)
+    t = synth_inputs.layer_tensors(L)
+    run = Run(a, "bf16", BLK, BLK, True)
+    y = run.fwd(t["x"], t["w"], bias=t["bias"], relu=True)
+    assert oracle.max_normalised_error(y, oracle.conv_fwd(a, t["x"], t["w"], bias=t["bias"], relu=True)) <= 2e-2
+    dx = run.bwd_data(t["dy"], t["w"])
+    assert oracle.max_normalised_error(dx, oracle.conv_bwd_data_gather(a, t["dy"], t["w"])) <= 2e-2
+    dw = run.bwd_filters(t["x"], t["dy"])
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, t["x"], t["dy"])) <= 2e-2
+
+
+def test_cfg3_full_size_with_device_layout_conversion():
+    """1x1 bottleneck: x arrives in NCHW, is converted on the device (bit exact), then the
+    three ops run on the blocked tensor."""
+    L = synth_inputs.config_layers(3)[0]
+    a = attrs_of(L)
+    t = synth_inputs.layer_tensors(L)
+    xbits = encode(t["x"], "bf16")
+    x_nchw = dev(xbits)
+    xb = torch.empty(L.n * (L.c // 16) * L.h * L.w * 16, dtype=torch.int16, device="cuda")
+    ng.ngc_layout_convert(ng.NGC_BF16, L.n, L.c, L.h, L.w, x_nchw, NCHW, xb, BLK, stream())
+    torch.cuda.synchronize()
+    got = host(xb, np.uint16).reshape(L.n, L.c // 16, L.h, L.w, 16)
+    exp = xbits.reshape(L.n, L.c // 16, 16, L.h, L.w).transpose(0, 1, 3, 4, 2)
+    assert np.array_equal(got, exp)
+    del got, exp
+    _sampled_layer_check(L)
+
+
+def test_cfg4_stem_reduced_batch():
+    L = synth_inputs.config_layers(4, batch=4)[0]
+    _sampled_layer_check(L, n_y=50_000, n_dw=512)
+
+
+@pytest.mark.parametrize("idx", range(23))
+def test_cfg5_shapes_reduced_batch(idx):
+    L = synth_inputs.config_layers(5, batch=4)[idx]
+    _sampled_layer_check(L, n_y=20_000, n_dw=256)
