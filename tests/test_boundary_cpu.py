@@ -1,0 +1,148 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, infers shapes like the oracle, and rejects invalid descriptors on the
+host before anything is launched."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1801_08058_amd as ng
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ngconv.h")
+
+
+def _good(**kw):
+    base = dict(n=2, c=64, h=14, w=14, k=64, r=3, s=3, pad_below=(1, 1), pad_above=(1, 1))
+    base.update(kw)
+    return ng.make_desc(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ngc_[a-z_]+)\s*\(", text))
+    assert declared == set(ng.EXPORTS), declared ^ set(ng.EXPORTS)
+    lib = ctypes.CDLL(ng.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_size_matches_header():
+    fields = re.findall(r"int32_t\s+([a-z_, ]+);", re.search(r"typedef struct \{(.*?)\} ngc_conv_desc;", open(HEADER).read(), re.S).group(1))
+    names = [n.strip() for f in fields for n in f.split(",")]
+    assert names == [n for n, _ in ng.ngc_conv_desc._fields_]
+    assert ctypes.sizeof(ng.ngc_conv_desc) == 4 * len(names)
+
+
+def test_out_shape_matches_oracle():
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        h, w, r, s = (int(v) for v in rng.integers(1, 40, 4))
+        sh, sw, dh, dw = (int(v) for v in rng.integers(1, 4, 4))
+        pb = [int(v) for v in rng.integers(0, 4, 4)]
+        a = oracle.Attrs(1, 3, h, w, 4, r, s, sh, sw, dh, dw, *pb)
+        P, Q = oracle.out_shape(a)
+        d = ng.make_desc(1, 3, h, w, 4, r, s, (sh, sw), (dh, dw), (pb[0], pb[1]), (pb[2], pb[3]))
+        got = ng.ngc_conv_out_shape(d, check=False)
+        if P < 1 or Q < 1:
+            assert got == ng.NGC_BAD_SHAPE
+        else:
+            assert got == (P, Q)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n=0), ng.NGC_BAD_SHAPE), (dict(c=-1), ng.NGC_BAD_SHAPE), (dict(stride=(0, 1)), ng.NGC_BAD_SHAPE),
+    (dict(dilation=(1, 0)), ng.NGC_BAD_SHAPE), (dict(pad_below=(-1, 0)), ng.NGC_BAD_SHAPE),
+    (dict(h=1, w=1, pad_below=(0, 0), pad_above=(0, 0)), ng.NGC_BAD_SHAPE),       # 3x3 window does not fit
+    (dict(dtype=7), ng.NGC_BAD_ARG), (dict(x_layout=5), ng.NGC_BAD_ARG), (dict(w_layout=9), ng.NGC_BAD_ARG),
+    (dict(epilogue=8), ng.NGC_BAD_ARG), (dict(n=1 << 20, h=1 << 10, w=1 << 10), ng.NGC_BAD_SHAPE),
+])
+def test_invalid_descriptors_are_rejected_before_launch(kw, status):
+    d = _good(**kw)
+    fake = 0x1000                       # never dereferenced: validation fails first
+    assert ng.ngc_conv_out_shape(d, check=False) == status
+    assert ng.ngc_conv_fwd(d, fake, fake, fake, fake, None, None, check=False) == status
+    assert ng.ngc_conv_bwd_data(d, fake, fake, fake, None, None, check=False) == status
+    assert ng.ngc_conv_bwd_filters(d, fake, fake, fake, None, None, check=False) == status
+    assert ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_FILTERS) == 0
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD) == "invalid"
+
+
+def test_null_pointers_missing_bias_and_workspace():
+    d = _good(epilogue=ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU)
+    fake = 0x1000
+    assert ng.ngc_conv_fwd(d, None, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_conv_fwd(d, fake, fake, None, fake, None, None, check=False) == ng.NGC_BAD_ARG     # bias flag, no bias
+    assert ng.ngc_conv_fwd(d, fake + 2, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_ARG  # misaligned
+    # KCRS filters on the MFMA path need workspace for the re-layout
+    assert ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_FWD) >= 64 * 64 * 9 * 2
+    assert ng.ngc_conv_fwd(d, fake, fake, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv_bwd_filters(d, fake, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    with pytest.raises(ng.NgcError):
+        ng.ngc_conv_fwd(d, fake, fake, fake, fake, None, None)
+    assert ng.ngc_layout_convert(ng.NGC_BF16, 1, 0, 4, 4, fake, 0, fake, 1, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_layout_convert(3, 1, 4, 4, 4, fake, 0, fake, 1, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_filter_convert(d, fake, fake, ng.NGC_KCRS, None, check=False) == ng.NGC_BAD_ARG
+
+
+def test_unsupported_is_reported_not_routed_elsewhere():
+    # blocked filters with a shape only the direct kernels cover
+    d = _good(c=5, k=7, w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD) == "unsupported"
+    assert ng.ngc_conv_fwd(d, 0x1000, 0x1000, None, 0x1000, None, None, check=False) == ng.NGC_UNSUPPORTED
+
+
+def test_kernel_selection_and_sizes():
+    d = _good(n=64, h=56, w=56, w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD).startswith("igemm")
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_BWD_FILTERS).startswith("wgrad")
+    assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56
+    assert ng.ngc_filter_elems(d, ng.NGC_BLOCKED_FWD) == 9 * 4 * 64 * 16
+    f32 = _good(dtype=ng.NGC_F32, x_layout=ng.NGC_NCHW, y_layout=ng.NGC_NCHW)
+    assert [ng.ngc_conv_variant(f32, o) for o in range(3)] == ["direct"] * 3
+    stem = ng.make_desc(64, 3, 224, 224, 64, 7, 7, (2, 2), (1, 1), (3, 3), (3, 3), x_layout=ng.NGC_NCHW)
+    assert ng.ngc_conv_out_shape(stem) == (112, 112)
+    assert ng.ngc_data_elems(stem, 0) == 64 * 3 * 224 * 224
+    for s in range(-6, 1):
+        assert ng.ngc_status_string(s)
+
+
+def test_fastdiv_exact_on_host():
+    """The runtime-constant division the kernels use for index decoding, checked on the host
+    against integer division (compiled from the product header, host code only)."""
+    src = r'''
+#include "common.h"
+#include <stdio.h>
+#include <stdlib.h>
+int main() {
+    unsigned long long bad = 0; unsigned s = 12345;
+    for (unsigned d = 1; d <= 20000; ++d) {
+        ngc::FastDiv f = ngc::make_fastdiv(d);
+        for (int t = 0; t < 200; ++t) {
+            s = s * 1664525u + 1013904223u;
+            unsigned n = (t < 4) ? (unsigned[]){0u, d - 1, d, 0xFFFFFFFFu}[t] : (t & 1 ? s : s >> 8);
+            if (ngc::fd_div(n, f) != n / d) ++bad;
+        }
+    }
+    for (unsigned d : {1u << 31, 0xFFFFFFFFu, 12544u * 128u, 3u, 7u, 49u}) {
+        ngc::FastDiv f = ngc::make_fastdiv(d);
+        for (unsigned n : {0u, 1u, d - 1, d, d + 1, 0x7FFFFFFFu, 0xFFFFFFFFu}) if (ngc::fd_div(n, f) != n / d) ++bad;
+    }
+    printf("%llu\n", bad);
+    return bad != 0;
+}
+'''
+    with tempfile.TemporaryDirectory() as td:
+        cpp = os.path.join(td, "fd.cpp")
+        open(cpp, "w").write(src)
+        exe = os.path.join(td, "fd")
+        subprocess.check_call(["/opt/rocm/bin/hipcc", "-O1", "-std=c++17", "-Wno-unused-value", "-I",
+                               os.path.join(ROOT, "paper_1801_08058_amd", "csrc"), "-o", exe, cpp],
+                              stderr=subprocess.DEVNULL)
+        assert subprocess.run([exe], capture_output=True, text=True).stdout.strip() == "0"
