@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
+                         "cfg2 activation tensor: 25.7 MB read + 25.7 MB written) so that HBM counters can be scaled")
     return ap.parse_args()
 
 
@@ -206,6 +209,13 @@ def main():
                             "bwd_data": ng.ngc_conv_variant(b.d_bwd, 1),
                             "bwd_filters": ng.ngc_conv_variant(b.d_wg, 2)}[op],
                 "count": b.L.count}
+    if args.calibrate_copy:
+        b0 = benches[0]
+        src, dst = b0.sets[0]["x"], torch.empty_like(b0.sets[0]["x"])
+        L0 = b0.L
+        for _ in range(10):
+            ng.ngc_layout_convert(ng.NGC_BF16, L0.n, L0.c, L0.h, L0.w, src, b0.xl, dst, b0.xl, b0.stream)
+        torch.cuda.synchronize()
     dom_name = max(kern, key=lambda k: kern[k]["us"] * kern[k]["count"])
     dom = kern[dom_name]
     if cfg in (2,):
