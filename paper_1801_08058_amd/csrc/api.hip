@@ -6,6 +6,7 @@
 #include "common.h"
 
 #include <limits.h>
+#include <stdlib.h>
 #include <string.h>
 
 using namespace ngc;
@@ -57,7 +58,93 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64 };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP };
+
+constexpr int NUM_CUS = 256;                      // MI355X
+constexpr size_t LDS_LIMIT = 160 * 1024;
+
+// Geometry of the output-stationary strip kernel for forward (op 0) or backprop-data (op 1).
+// Returns false if the shape does not fit it.
+bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, int *nf_out, size_t *lds_out)
+{
+    if (d->stride_h != 1 || d->stride_w != 1) return false;
+    // NGC_STRIP_NF (tests / benchmarks only): 0 disables this kernel, 7 / 4 / 2 forces a strip size
+    const char *force = getenv("NGC_STRIP_NF");
+    const int forced_nf = force ? atoi(force) : -1;
+    if (forced_nf == 0) return false;
+    const int ntaps = d->r * d->s;
+    if (ntaps < 2 || ntaps > STRIP_MAX_TAPS) return false;
+    const int Cin = op == NGC_OP_FWD ? d->c : d->k, Cout = op == NGC_OP_FWD ? d->k : d->c;
+    if (Cin % 16 != 0 || Cout % 64 != 0) return false;
+    const int Hin = op == NGC_OP_FWD ? d->h : P, Win = op == NGC_OP_FWD ? d->w : Q;
+    const int Hout = op == NGC_OP_FWD ? P : d->h, Wout = op == NGC_OP_FWD ? Q : d->w;
+    const size_t in_bytes = (size_t)d->n * Cin * Hin * Win * 2;
+    const size_t wt_bytes = (size_t)ntaps * Cin * Cout * 2;
+    if (in_bytes >= ((size_t)1 << 31) || wt_bytes >= ((size_t)1 << 31)) return false;
+    const int span_h = d->dil_h * (d->r - 1), span_w = d->dil_w * (d->s - 1);
+    const int min_dh = op == NGC_OP_FWD ? -d->pad_below_h : d->pad_below_h - span_h;
+    const int min_dw = op == NGC_OP_FWD ? -d->pad_below_w : d->pad_below_w - span_w;
+
+    StripParams best;
+    int best_nf = 0;
+    size_t best_lds = 0;
+    const int nfs[3] = {7, 4, 2};
+    for (int nf : nfs) {
+        if (forced_nf > 0 && nf != forced_nf) continue;
+        const int maxpix = 4 * nf * 32;
+        if (Wout > maxpix) continue;
+        StripParams q;
+        memset(&q, 0, sizeof(q));
+        const int rows_fit = maxpix / Wout;
+        if (rows_fit >= Hout) {
+            q.TP = Hout;
+            q.TN = maxpix / (Hout * Wout);
+            if (q.TN > d->n) q.TN = d->n;
+            q.strips = 1;
+        } else {
+            q.TN = 1;
+            q.strips = (Hout + rows_fit - 1) / rows_fit;
+            q.TP = (Hout + q.strips - 1) / q.strips;
+            q.strips = (Hout + q.TP - 1) / q.TP;
+        }
+        q.groups = (d->n + q.TN - 1) / q.TN;
+        q.PR = q.TP + span_h;
+        q.PC = Wout + span_w;
+        q.npix = q.TN * q.TP * Wout;
+        q.npatch = q.TN * q.PR * q.PC;
+        const int nblocks = (q.npatch + 63) / 64;
+        if (nblocks > 4 * 6) continue;                              // STRIP_MAXXB blocks per wave
+        q.xpitch = nblocks * 1024 + 128;
+        const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)2 * ntaps * (64 * 16 + 128));
+        if (lds > LDS_LIMIT) continue;
+        q.N = d->n; q.Cin = Cin; q.Hin = Hin; q.Win = Win; q.Cout = Cout; q.Hout = Hout; q.Wout = Wout;
+        q.min_dh = min_dh; q.min_dw = min_dw;
+        q.ntaps = ntaps;
+        int t = 0;
+        for (int r = 0; r < d->r; ++r)
+            for (int s2 = 0; s2 < d->s; ++s2) {
+                const int dh = op == NGC_OP_FWD ? r * d->dil_h - d->pad_below_h : d->pad_below_h - r * d->dil_h;
+                const int dw = op == NGC_OP_FWD ? s2 * d->dil_w - d->pad_below_w : d->pad_below_w - s2 * d->dil_w;
+                q.tap_off[t] = (dh - min_dh) * q.PC + (dw - min_dw);
+                q.tap_slab[t] = r * d->s + s2;
+                ++t;
+            }
+        q.in_bytes = (uint32_t)in_bytes;
+        q.wt_bytes = (uint32_t)wt_bytes;
+        q.div_tpq = make_fastdiv((uint32_t)(q.TP * Wout));
+        q.div_q = make_fastdiv((uint32_t)Wout);
+        q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
+        q.div_pc = make_fastdiv((uint32_t)q.PC);
+        const long wgs = (long)q.groups * q.strips * (Cout / 64);
+        best = q; best_nf = nf; best_lds = lds;
+        if (wgs >= NUM_CUS) break;                                   // largest strip that still fills the chip
+    }
+    if (!best_nf) return false;
+    if (sp) *sp = best;
+    if (nf_out) *nf_out = best_nf;
+    if (lds_out) *lds_out = best_lds;
+    return true;
+}
 
 bool blocked_bf16(const ngc_conv_desc *d)
 {
@@ -69,15 +156,17 @@ Variant pick(const ngc_conv_desc *d, int op)
     int P, Q;
     if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
     if (op == NGC_OP_FWD) {
-        const bool mf = blocked_bf16(d) && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
-                        (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
+        const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
+        const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
+        if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
         if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_DATA) {
-        const bool mf = blocked_bf16(d) && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
-                        d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES &&
-                        (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
+        const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
+        const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
+                        d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
+        if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
         if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
@@ -115,9 +204,9 @@ void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *spl
 
 size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
-    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64))
+    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
-    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64))
+    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_64) {
         uint32_t chunk;
@@ -189,6 +278,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_IGEMM_128: return "igemm_bf16_128x128";
     case V_IGEMM_64: return "igemm_bf16_256x64";
     case V_WGRAD_64: return "wgrad_bf16_64x64";
+    case V_STRIP: return "strip_bf16";
     default: return "invalid";
     }
 }
@@ -228,6 +318,18 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_FWD, st);
         if (e != hipSuccess) return NGC_LAUNCH_FAILED;
         wt = ws;
+    }
+    if (v == V_STRIP) {
+        StripParams sp;
+        int nf;
+        size_t lds;
+        if (!strip_plan(desc, NGC_OP_FWD, P, Q, &sp, &nf, &lds)) return NGC_UNSUPPORTED;
+        sp.in = static_cast<const uint16_t *>(x);
+        sp.wt = static_cast<const uint16_t *>(wt);
+        sp.out = static_cast<uint16_t *>(y);
+        sp.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+        sp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+        return launch_status(launch_strip(sp, nf, lds, st));
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));
@@ -273,6 +375,18 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_BWD, st);
         if (e != hipSuccess) return NGC_LAUNCH_FAILED;
         wt = ws;
+    }
+    if (v == V_STRIP) {
+        StripParams sp;
+        int nf;
+        size_t lds;
+        if (!strip_plan(desc, NGC_OP_BWD_DATA, P, Q, &sp, &nf, &lds)) return NGC_UNSUPPORTED;
+        sp.in = static_cast<const uint16_t *>(dy);
+        sp.wt = static_cast<const uint16_t *>(wt);
+        sp.out = static_cast<uint16_t *>(dx);
+        sp.bias = nullptr;
+        sp.relu = 0;
+        return launch_status(launch_strip(sp, nf, lds, st));
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));

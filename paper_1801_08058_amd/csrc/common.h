@@ -108,6 +108,29 @@ struct IgemmParams {
     IgemmTap taps[IGEMM_MAX_TAPS];
 };
 
+// ---- output-stationary strip kernel (stride-1 forward / backprop-data) ----
+constexpr int STRIP_MAX_TAPS = 25;
+
+struct StripParams {
+    const uint16_t *in;
+    const uint16_t *wt;
+    uint16_t *out;
+    const float *bias;         // may be null
+    int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
+    int32_t TN, TP;            // images and output rows per workgroup
+    int32_t groups, strips;    // ceil(N/TN), ceil(Hout/TP)
+    int32_t PR, PC;            // patch rows / columns per image
+    int32_t min_dh, min_dw;    // input row/col of patch (0,0) relative to output (p0, 0)
+    int32_t npix, npatch;      // TN*TP*Wout, TN*PR*PC
+    int32_t xpitch;            // bytes per X plane in LDS
+    int32_t relu;
+    int32_t ntaps;
+    int32_t tap_off[STRIP_MAX_TAPS];    // patch-pixel offset of the tap
+    int32_t tap_slab[STRIP_MAX_TAPS];
+    uint32_t in_bytes, wt_bytes;
+    FastDiv div_tpq, div_q, div_prpc, div_pc;
+};
+
 // ---- MFMA backprop-filters ----
 struct WgradParams {
     const uint16_t *x;         // blocked [N][C/16][H][W][16]
@@ -123,6 +146,7 @@ struct WgradParams {
 
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
+hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,
                                hipStream_t st);

@@ -1,0 +1,232 @@
+// Stride-1 convolution (forward and backprop-data) as an output-stationary "strip" kernel on
+// bf16 MFMA (gfx950), fp32 accumulate.
+//
+// A workgroup (256 threads, 4 waves, one per SIMD) owns a strip of up to 4*NF*32 output
+// positions (TN images x TP output rows x full width) for 64 output channels and keeps ALL
+// of its accumulators in registers: wave w owns position fragments w, w+4, ... (NF of them,
+// 32 positions each) x 2 channel fragments = 2*NF MFMA 32x32 tiles.  The reduction runs over
+// 16-input-channel chunks.  For each chunk the workgroup brings into LDS, with direct
+// global->LDS loads (buffer_load_dwordx4 ... lds, 16 bytes per lane, out-of-range lanes
+// return zeros = the padding halo):
+//     X patch : the input footprint of the strip (TN x PR x PC pixels) x 16 channels, once,
+//               and uses it for every filter tap (an input pixel is read from L2/HBM once per
+//               strip instead of once per tap),
+//     W slab  : all taps x 16 channels x 64 output channels,
+// as 16-byte-unit planes (g = which 8 of the 16 channels) so that every MFMA operand fetch is
+// one conflict-free ds_read_b128.  Two LDS stages: the loads of chunk c+1 are issued right
+// after the barrier that opens chunk c and are in flight during its MFMAs (one chunk = taps *
+// 2 * NF MFMAs per wave, about 4000 cycles for 3x3), so one barrier per chunk suffices.
+//
+// MFMA roles as in the gather kernel: A = filters (rows = output channels), B = activations
+// (columns = positions), v_mfma_f32_32x32x16_bf16; epilogue (bias, ReLU, one RNE rounding,
+// lane-pair exchange, 16-byte stores) identical.
+#include "common.h"
+
+namespace ngc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr int STRIP_WPITCH = 64 * 16 + 128;     // bytes per (tap, g) filter plane
+constexpr int STRIP_MAXXB = 6;                  // 64-pixel patch blocks per wave (per plane)
+constexpr unsigned STRIP_OOB = 0x80000000u;     // byte offset beyond any buffer -> load returns 0
+
+__device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned char *lds_dst_uniform, unsigned voff,
+                                           unsigned soff)
+{
+    // each lane: 16 bytes from (base + voff + soff) -> lds_dst_uniform + lane*16
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)lds_dst_uniform, 16, (int)voff, (int)soff, 0, 0);
+}
+
+template <int NF>
+__global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31;
+    const int lg = lane >> 5;
+
+    const int grp = blockIdx.x / p.strips;
+    const int strip = blockIdx.x - grp * p.strips;
+    const int n0 = grp * p.TN;
+    const int p0 = strip * p.TP;
+    const int k0 = blockIdx.y * 64;
+
+    const int CB = p.Cin >> 4;
+    const int HWin = p.Hin * p.Win;
+    const int xplane = p.xpitch;
+    const int stage_bytes = 2 * xplane + 2 * p.ntaps * STRIP_WPITCH;
+
+    __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
+
+    // ---- loader bookkeeping: wave w loads patch blocks b = w, w+4, ... of both planes
+    const int nblocks = (p.npatch + 63) >> 6;
+    unsigned xoff[STRIP_MAXXB];
+#pragma unroll
+    for (int i = 0; i < STRIP_MAXXB; ++i) {
+        const int b = wave + 4 * i;
+        const uint32_t pi = (uint32_t)(b * 64 + lane);
+        unsigned off = STRIP_OOB;
+        if (b < nblocks && pi < (uint32_t)p.npatch) {
+            const uint32_t ti = fd_div(pi, p.div_prpc);
+            const uint32_t rem = pi - ti * p.div_prpc.d;
+            const uint32_t pr = fd_div(rem, p.div_pc);
+            const uint32_t pc = rem - pr * p.div_pc.d;
+            const int n = n0 + (int)ti;
+            const int h = p0 + p.min_dh + (int)pr;
+            const int w = p.min_dw + (int)pc;
+            if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)w < (unsigned)p.Win)
+                off = (unsigned)((n * CB * HWin + h * p.Win + w) * 32);
+        }
+        xoff[i] = off;
+    }
+    const unsigned woff_lane = (unsigned)((k0 + lane) * 32);           // row of the filter slab
+
+    auto issue_loads = [&](int chunk, int stage) {
+        unsigned char *xs = smem + stage * stage_bytes;
+        unsigned char *ws = xs + 2 * xplane;
+        const unsigned soff_x = (unsigned)(chunk * HWin * 32);
+#pragma unroll
+        for (int i = 0; i < STRIP_MAXXB; ++i) {
+            const int b = wave + 4 * i;
+            if (b < nblocks) {                                           // wave-uniform
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const unsigned v = (xoff[i] == STRIP_OOB) ? STRIP_OOB : xoff[i] + 16 * g;
+                    load_lds16(rs_in, xs + g * xplane + b * 1024, v, soff_x);
+                }
+            }
+        }
+        for (int j = wave; j < 2 * p.ntaps; j += 4) {                    // plane j = tap*2 + g
+            const int t = j >> 1, g = j & 1;
+            const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32 + 16 * g);
+            load_lds16(rs_wt, ws + j * STRIP_WPITCH, woff_lane, soff_w);
+        }
+    };
+
+    // ---- positions owned by this lane: fragment f = wave + 4 i, position m = 32 f + l32
+    int pbase[NF];          // patch pixel index of the position at tap offset 0 (clamped to 0 if invalid)
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+        const uint32_t m = (uint32_t)((wave + 4 * i) * 32 + l32);
+        int pb = 0;
+        if (m < (uint32_t)p.npix) {
+            const uint32_t ti = fd_div(m, p.div_tpq);
+            const uint32_t rem = m - ti * p.div_tpq.d;
+            const uint32_t tp = fd_div(rem, p.div_q);
+            const uint32_t q = rem - tp * p.div_q.d;
+            pb = (int)((ti * p.PR + tp) * p.PC + q);
+        }
+        pbase[i] = pb * 16;
+    }
+
+    f32x16 acc[NF][2];
+#pragma unroll
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][a][v] = 0.f;
+
+    const int nchunks = CB;
+    issue_loads(0, 0);
+    for (int c = 0; c < nchunks; ++c) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's loads of chunk c have landed
+        __syncthreads();                                    // ... and everybody else's; stage (c+1)&1 is free
+        if (c + 1 < nchunks) issue_loads(c + 1, (c + 1) & 1);
+        const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
+        const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * STRIP_WPITCH + l32 * 16;
+        for (int t = 0; t < p.ntaps; ++t) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + (2 * t) * STRIP_WPITCH);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ws + (2 * t) * STRIP_WPITCH + 32 * 16);
+            const int toff = p.tap_off[t] * 16;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) {
+                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue
+    const int CBout = p.Cout >> 4;
+    const int HWout = p.Hout * p.Wout;
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+        const uint32_t m = (uint32_t)((wave + 4 * i) * 32 + l32);
+        bool ok = m < (uint32_t)p.npix;
+        const uint32_t mm = ok ? m : 0;
+        const uint32_t ti = fd_div(mm, p.div_tpq);
+        const uint32_t rem = mm - ti * p.div_tpq.d;
+        const uint32_t tp = fd_div(rem, p.div_q);
+        const uint32_t q = rem - tp * p.div_q.d;
+        const int n = n0 + (int)ti;
+        const int oh = p0 + (int)tp;
+        ok = ok && n < p.N && oh < p.Hout;
+        const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + q;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const int co_base = k0 + a * 32;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = acc[i][a][8 * h + e];
+                if (p.bias) {
+                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 4 * lg);
+                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 8 + 4 * lg);
+                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+                }
+                if (p.relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                const uint32_t q0 = pack_bf16x2(v[0], v[1]), q1 = pack_bf16x2(v[2], v[3]);
+                const uint32_t q2 = pack_bf16x2(v[4], v[5]), q3 = pack_bf16x2(v[6], v[7]);
+                const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
+                const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
+                const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
+                const uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
+                if (ok) {
+                    const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                }
+            }
+        }
+    }
+}
+
+
+template <int NF>
+static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
+{
+    static bool attr_set = false;                   // raise the dynamic LDS limit once per process
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid(p.groups * p.strips, p.Cout / 64);
+    hipLaunchKernelGGL(conv_strip_bf16<NF>, grid, dim3(256), lds_bytes, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st)
+{
+    switch (nf) {
+    case 7: return launch_strip_nf<7>(p, lds_bytes, st);
+    case 4: return launch_strip_nf<4>(p, lds_bytes, st);
+    case 2: return launch_strip_nf<2>(p, lds_bytes, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ngc

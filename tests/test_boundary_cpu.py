@@ -100,7 +100,9 @@ def test_unsupported_is_reported_not_routed_elsewhere():
 
 def test_kernel_selection_and_sizes():
     d = _good(n=64, h=56, w=56, w_layout=ng.NGC_BLOCKED_FWD)
-    assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD).startswith("igemm")
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD) == "strip_bf16"
+    s2 = _good(n=64, h=56, w=56, stride=(2, 2), w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv_variant(s2, ng.NGC_OP_FWD).startswith("igemm")
     assert ng.ngc_conv_variant(d, ng.NGC_OP_BWD_FILTERS).startswith("wgrad")
     assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56
     assert ng.ngc_filter_elems(d, ng.NGC_BLOCKED_FWD) == 9 * 4 * 64 * 16

@@ -154,15 +154,36 @@ MFMA_CASES = [
     Attrs(5, 64, 7, 7, 192, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # 7x7 images, several per tile; K=192 -> 256x64 tile
     Attrs(1, 64, 16, 16, 64, 5, 5, 1, 1, 1, 1, 2, 2, 2, 2),      # 5x5
     Attrs(2, 64, 9, 9, 64, 3, 3, 3, 3, 1, 1, 1, 1, 1, 1),        # stride 3 (9 classes)
+    Attrs(2, 48, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # 14-row strips of a 56x56 image, C = 3 chunks
+    Attrs(9, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),     # several whole images per strip, ragged last group
+    Attrs(1, 32, 30, 20, 64, 3, 2, 1, 1, 2, 1, 3, 0, 1, 1),      # dilation / asymmetric pads, ragged last strip
 ]
+
+
+@pytest.fixture
+def strip_nf(monkeypatch):
+    """NGC_STRIP_NF: 0 = gather kernel only, 7/4/2 = force a strip size, unset = dispatcher's choice."""
+    def set_(v):
+        if v is None:
+            monkeypatch.delenv("NGC_STRIP_NF", raising=False)
+        else:
+            monkeypatch.setenv("NGC_STRIP_NF", str(v))
+    return set_
 
 
 @pytest.mark.parametrize("case", range(len(MFMA_CASES)))
 @pytest.mark.parametrize("pre", [True, False])
-def test_mfma_kernels_small(case, pre):
+@pytest.mark.parametrize("nf", [None, 0, 7, 4])
+def test_mfma_kernels_small(case, pre, nf, strip_nf):
     a = MFMA_CASES[case]
-    fwd_v = "igemm"
-    bwd_v = "igemm" if (a.c % 64 == 0 and a.k % 32 == 0) else "direct"
+    if nf in (7, 4) and ((a.sh, a.sw) != (1, 1) or a.r * a.s == 1 or not pre):
+        pytest.skip("strip kernel covers stride-1 multi-tap shapes; one filter-layout mode is enough for forced sizes")
+    strip_nf(nf)
+    strip_ok = (a.sh, a.sw) == (1, 1) and a.r * a.s > 1 and nf != 0
+    fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 64 == 0) else \
+        "igemm" if (a.c % 32 == 0 and a.k % 64 == 0) else "direct"
+    bwd_v = "strip" if (strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else \
+        "igemm" if (a.k % 32 == 0 and a.c % 64 == 0) else "direct"
     wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
     _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
 
