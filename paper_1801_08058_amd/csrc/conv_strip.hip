@@ -22,6 +22,8 @@
 // lane-pair exchange, 16-byte stores) identical.
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace ngc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -29,7 +31,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr int STRIP_WPITCH = 64 * 16 + 128;     // bytes per (tap, g) filter plane
-constexpr int STRIP_MAXXB = 6;                  // 64-pixel patch blocks per wave (per plane)
+constexpr int STRIP_MAXBLOCKS = 24;             // 64-pixel patch blocks per plane (whole workgroup)
 constexpr unsigned STRIP_OOB = 0x80000000u;     // byte offset beyond any buffer -> load returns 0
 
 __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned char *lds_dst_uniform, unsigned voff,
@@ -39,9 +41,10 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)lds_dst_uniform, 16, (int)voff, (int)soff, 0, 0);
 }
 
-template <int NF>
-__global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
+template <int NF, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
+    constexpr int MAXXB = STRIP_MAXBLOCKS / NW;         // patch blocks per wave
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -66,10 +69,10 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
 
     // ---- loader bookkeeping: wave w loads patch blocks b = w, w+4, ... of both planes
     const int nblocks = (p.npatch + 63) >> 6;
-    unsigned xoff[STRIP_MAXXB];
+    unsigned xoff[MAXXB];
 #pragma unroll
-    for (int i = 0; i < STRIP_MAXXB; ++i) {
-        const int b = wave + 4 * i;
+    for (int i = 0; i < MAXXB; ++i) {
+        const int b = wave + NW * i;
         const uint32_t pi = (uint32_t)(b * 64 + lane);
         unsigned off = STRIP_OOB;
         if (b < nblocks && pi < (uint32_t)p.npatch) {
@@ -86,14 +89,18 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
         xoff[i] = off;
     }
     const unsigned woff_lane = (unsigned)((k0 + lane) * 32);           // row of the filter slab
+    // fragments of this wave that hold at least one position of the strip (wave-uniform)
+    int nfrag = 0;
+#pragma unroll
+    for (int i = 0; i < NF; ++i) nfrag += ((wave + NW * i) * 32 < p.npix) ? 1 : 0;
 
     auto issue_loads = [&](int chunk, int stage) {
         unsigned char *xs = smem + stage * stage_bytes;
         unsigned char *ws = xs + 2 * xplane;
         const unsigned soff_x = (unsigned)(chunk * HWin * 32);
 #pragma unroll
-        for (int i = 0; i < STRIP_MAXXB; ++i) {
-            const int b = wave + 4 * i;
+        for (int i = 0; i < MAXXB; ++i) {
+            const int b = wave + NW * i;
             if (b < nblocks) {                                           // wave-uniform
 #pragma unroll
                 for (int g = 0; g < 2; ++g) {
@@ -102,7 +109,7 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
                 }
             }
         }
-        for (int j = wave; j < 2 * p.ntaps; j += 4) {                    // plane j = tap*2 + g
+        for (int j = wave; j < 2 * p.ntaps; j += NW) {                    // plane j = tap*2 + g
             const int t = j >> 1, g = j & 1;
             const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32 + 16 * g);
             load_lds16(rs_wt, ws + j * STRIP_WPITCH, woff_lane, soff_w);
@@ -113,7 +120,7 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
     int pbase[NF];          // patch pixel index of the position at tap offset 0 (clamped to 0 if invalid)
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        const uint32_t m = (uint32_t)((wave + 4 * i) * 32 + l32);
+        const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
         int pb = 0;
         if (m < (uint32_t)p.npix) {
             const uint32_t ti = fd_div(m, p.div_tpq);
@@ -147,9 +154,11 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
             const int toff = p.tap_off[t] * 16;
 #pragma unroll
             for (int i = 0; i < NF; ++i) {
-                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+                if (i < nfrag) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
+                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+                }
             }
         }
     }
@@ -157,9 +166,21 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
     // ---- epilogue
     const int CBout = p.Cout >> 4;
     const int HWout = p.Hout * p.Wout;
+    float4 bv[2][2][2];                                   // [a][h][which quad]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.bias) {
+                bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
+                bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
+            }
+        }
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        const uint32_t m = (uint32_t)((wave + 4 * i) * 32 + l32);
+        if (i >= nfrag) break;
+        const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
         bool ok = m < (uint32_t)p.npix;
         const uint32_t mm = ok ? m : 0;
         const uint32_t ti = fd_div(mm, p.div_tpq);
@@ -178,9 +199,8 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
                 float v[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = acc[i][a][8 * h + e];
-                if (p.bias) {
-                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 4 * lg);
-                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 8 + 4 * lg);
+                {
+                    const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                     v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
                 }
@@ -204,27 +224,30 @@ __global__ __launch_bounds__(256) void conv_strip_bf16(const StripParams p)
 }
 
 
-template <int NF>
+template <int NF, int NW>
 static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static bool attr_set = false;                   // raise the dynamic LDS limit once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.groups * p.strips, p.Cout / 64);
-    hipLaunchKernelGGL(conv_strip_bf16<NF>, grid, dim3(256), lds_bytes, st, p);
+    hipLaunchKernelGGL((conv_strip_bf16<NF, NW>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
 
+// nf = 32-position fragments per SIMD (7, 4 or 2); the fragments of a SIMD are spread over
+// `waves_per_simd` waves so that one wave's LDS latency hides behind the other's MFMAs
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st)
 {
+    static const int two_waves = getenv("NGC_STRIP_1WAVE") ? 0 : 1;
     switch (nf) {
-    case 7: return launch_strip_nf<7>(p, lds_bytes, st);
-    case 4: return launch_strip_nf<4>(p, lds_bytes, st);
-    case 2: return launch_strip_nf<2>(p, lds_bytes, st);
+    case 7: return two_waves ? launch_strip_nf<4, 8>(p, lds_bytes, st) : launch_strip_nf<7, 4>(p, lds_bytes, st);
+    case 4: return two_waves ? launch_strip_nf<2, 8>(p, lds_bytes, st) : launch_strip_nf<4, 4>(p, lds_bytes, st);
+    case 2: return two_waves ? launch_strip_nf<1, 8>(p, lds_bytes, st) : launch_strip_nf<2, 4>(p, lds_bytes, st);
     default: return hipErrorInvalidValue;
     }
 }
