@@ -58,7 +58,7 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -146,6 +146,64 @@ bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, i
     return true;
 }
 
+// Geometry of the all-taps backprop-filters kernel (stride 1, exactly 9 taps, C and K multiples of 64).
+bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp, size_t *lds_out)
+{
+    const char *force = getenv("NGC_WGRAD_STRIP");
+    if (force && atoi(force) == 0) return false;
+    if (d->stride_h != 1 || d->stride_w != 1 || d->r * d->s != 9) return false;
+    if (d->c % 64 != 0 || d->k % 64 != 0) return false;
+    const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * P * Q * 2;
+    if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
+    if (Q > 224) return false;
+    WgradStripParams q;
+    memset(&q, 0, sizeof(q));
+    const int span_h = d->dil_h * (d->r - 1), span_w = d->dil_w * (d->s - 1);
+    q.SR = 224 / Q;
+    if (q.SR > P) q.SR = P;
+    q.PRS = q.SR + span_h;
+    q.PC = Q + span_w;
+    const int nblk_x = (q.PRS * q.PC + 31) / 32;
+    const int nblk_dy = (q.SR * Q + 31) / 32;                           // 32-position steps per stage
+    q.dyplane = nblk_dy * 1024 + 128;
+    q.xplane = nblk_x * 1024 + 128;
+    size_t lds = (size_t)2 * 4 * (q.dyplane + q.xplane);
+    const size_t red = (size_t)4 * 144 * 64 * sizeof(float);           // final cross-wave sum
+    if (lds < red) lds = red;
+    if (lds > LDS_LIMIT) return false;
+    const int tiles = (d->k / 64) * (d->c / 64);
+    // enough workgroups to fill the chip, as few partial copies of dw as possible
+    int parts_wanted = (2 * NUM_CUS + tiles - 1) / tiles;
+    if (tiles >= NUM_CUS) parts_wanted = 1;
+    const int max_strips = (P + q.SR - 1) / q.SR;
+    if (parts_wanted <= d->n) {
+        q.strips = 1;
+        q.NI = d->n / parts_wanted;                                      // >= 1
+    } else {
+        q.NI = 1;
+        q.strips = (parts_wanted + d->n - 1) / d->n;
+        if (q.strips > max_strips) q.strips = max_strips;
+    }
+    q.TP = (P + q.strips - 1) / q.strips;
+    q.strips = (P + q.TP - 1) / q.TP;
+    q.nstages = (q.TP + q.SR - 1) / q.SR;
+    q.nparts = ((d->n + q.NI - 1) / q.NI) * q.strips;
+    q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q;
+    q.min_dh = -d->pad_below_h;
+    q.min_dw = -d->pad_below_w;
+    int t = 0;
+    for (int r = 0; r < d->r; ++r)
+        for (int s2 = 0; s2 < d->s; ++s2) q.tap_off[t++] = r * d->dil_h * q.PC + s2 * d->dil_w;
+    q.ctiles = d->c / 64;
+    q.x_bytes = (uint32_t)x_bytes;
+    q.dy_bytes = (uint32_t)dy_bytes;
+    q.div_q = make_fastdiv((uint32_t)Q);
+    q.div_pc = make_fastdiv((uint32_t)q.PC);
+    if (wp) *wp = q;
+    if (lds_out) *lds_out = lds;
+    return true;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -171,6 +229,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_FILTERS) {
+        if (blocked_bf16(d) && wgrad_strip_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STRIP;
         if (blocked_bf16(d) && d->c % 64 == 0 && d->k % 64 == 0 && d->r * d->s <= 65535) return V_WGRAD_64;
         return V_DIRECT;
     }
@@ -208,6 +267,11 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
+    if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STRIP) {
+        WgradStripParams wp;
+        wgrad_strip_plan(d, P, Q, &wp, nullptr);
+        return round256((size_t)wp.nparts * 9 * d->k * d->c * sizeof(float));
+    }
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_64) {
         uint32_t chunk;
         int splits;
@@ -279,6 +343,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_IGEMM_64: return "igemm_bf16_256x64";
     case V_WGRAD_64: return "wgrad_bf16_64x64";
     case V_STRIP: return "strip_bf16";
+    case V_WGRAD_STRIP: return "wgrad_strip_bf16";
     default: return "invalid";
     }
 }
@@ -442,6 +507,16 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);
     if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    if (v == V_WGRAD_STRIP) {
+        WgradStripParams wp;
+        size_t lds;
+        if (!wgrad_strip_plan(desc, P, Q, &wp, &lds)) return NGC_UNSUPPORTED;
+        wp.x = static_cast<const uint16_t *>(x);
+        wp.dy = static_cast<const uint16_t *>(dy);
+        wp.partial = static_cast<float *>(ws);
+        wp.dw = dw;
+        return launch_status(launch_wgrad_strip(wp, lds, st));
+    }
     WgradParams p;
     memset(&p, 0, sizeof(p));
     p.x = static_cast<const uint16_t *>(x);

@@ -58,6 +58,14 @@ __host__ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
 }
 
+// two fp32 -> packed bf16x2 with the hardware conversion (v_cvt_pk_bf16_f32, round-to-nearest-even)
+__device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t r = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, r);
+}
+
 // ---- element index functions for the public layouts ----
 __host__ __device__ inline size_t data_index(int layout, int C, int H, int W, int n, int c, int h, int w)
 {
@@ -144,10 +152,31 @@ struct WgradParams {
     FastDiv div_pq, div_q;
 };
 
+// ---- backprop-filters, all taps per pass (stride-1, 9 taps) ----
+struct WgradStripParams {
+    const uint16_t *x;         // blocked [N][C/16][H][W][16]
+    const uint16_t *dy;        // blocked [N][K/16][P][Q][16]
+    float *partial;            // [nparts][tap][K][C]
+    float *dw;                 // [K][C][R][S]
+    int32_t N, C, H, W, K, P, Q;
+    int32_t NI;                // images per workgroup
+    int32_t TP, strips;        // dy rows per workgroup, row strips per image
+    int32_t SR, nstages;       // rows per LDS stage, stages per (image, strip)
+    int32_t nparts;            // ceil(N/NI) * strips
+    int32_t PRS, PC;           // x patch rows per stage, patch columns
+    int32_t min_dh, min_dw;
+    int32_t tap_off[9];        // patch-pixel offset of the tap
+    int32_t dyplane, xplane;   // bytes per 16-channel plane of a stage
+    int32_t ctiles;
+    uint32_t x_bytes, dy_bytes;
+    FastDiv div_q, div_pc;
+};
+
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
+hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,
                                hipStream_t st);
 hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x, const void *w,

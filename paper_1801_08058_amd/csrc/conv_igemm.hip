@@ -221,8 +221,8 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
                 }
-                const uint32_t p0 = pack_bf16x2(v[0], v[1]), p1 = pack_bf16x2(v[2], v[3]);
-                const uint32_t p2 = pack_bf16x2(v[4], v[5]), p3 = pack_bf16x2(v[6], v[7]);
+                const uint32_t p0 = pack_bf16x2_hw(v[0], v[1]), p1 = pack_bf16x2_hw(v[2], v[3]);
+                const uint32_t p2 = pack_bf16x2_hw(v[4], v[5]), p3 = pack_bf16x2_hw(v[6], v[7]);
                 // lg=0 owns channels {0-3, 8-11}, lg=1 owns {4-7, 12-15}; swap so that
                 // lg=0 ends with 0-7 and lg=1 with 8-15
                 const uint32_t s0 = lg ? p0 : p2, s1 = lg ? p1 : p3;

@@ -208,8 +208,8 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
                 }
-                const uint32_t q0 = pack_bf16x2(v[0], v[1]), q1 = pack_bf16x2(v[2], v[3]);
-                const uint32_t q2 = pack_bf16x2(v[4], v[5]), q3 = pack_bf16x2(v[6], v[7]);
+                const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
+                const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
                 const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);

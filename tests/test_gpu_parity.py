@@ -157,6 +157,9 @@ MFMA_CASES = [
     Attrs(2, 48, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # 14-row strips of a 56x56 image, C = 3 chunks
     Attrs(9, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),     # several whole images per strip, ragged last group
     Attrs(1, 32, 30, 20, 64, 3, 2, 1, 1, 2, 1, 3, 0, 1, 1),      # dilation / asymmetric pads, ragged last strip
+    Attrs(3, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # all-taps wgrad: row strips + 4-row stages
+    Attrs(5, 128, 20, 9, 64, 3, 3, 1, 1, 2, 2, 2, 2, 2, 2),      # all-taps wgrad: dilation 2, two c tiles, odd width
+    Attrs(70, 64, 7, 7, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # many small images
 ]
 
 
@@ -186,6 +189,20 @@ def test_mfma_kernels_small(case, pre, nf, strip_nf):
         "igemm" if (a.k % 32 == 0 and a.c % 64 == 0) else "direct"
     wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
     _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
+
+
+@pytest.mark.parametrize("case", [0, 9, 10, 11])
+def test_wgrad_per_tap_kernel_still_matches(case, monkeypatch):
+    """3x3 stride-1 shapes through the per-tap split kernel (the all-taps kernel switched off)."""
+    monkeypatch.setenv("NGC_WGRAD_STRIP", "0")
+    a = MFMA_CASES[case]
+    if a.c % 64 or a.k % 64:
+        pytest.skip("per-tap MFMA kernel needs C, K multiples of 64")
+    x, w, b, dy = _tensors(a, "bf16", 3000 + case)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_bf16_64x64"
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
 
 
 def test_run_to_run_identical():
