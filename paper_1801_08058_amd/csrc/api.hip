@@ -167,13 +167,18 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     const int nblk_dy = (q.SR * Q + 31) / 32;                           // 32-position steps per stage
     q.dyplane = nblk_dy * 1024 + 128;
     q.xplane = nblk_x * 1024 + 128;
-    size_t lds = (size_t)2 * 4 * (q.dyplane + q.xplane);
+    // channel groups per workgroup: few (k,c) tiles -> narrower c per workgroup, longer position chunks
+    const int tiles64 = (d->k / 64) * (d->c / 64);
+    q.ncq = tiles64 <= 4 ? 2 : 4;
+    const char *fq = getenv("NGC_WGRAD_NCQ");
+    if (fq && (atoi(fq) == 1 || atoi(fq) == 2 || atoi(fq) == 4)) q.ncq = atoi(fq);
+    size_t lds = (size_t)2 * (4 * q.dyplane + q.ncq * q.xplane);
     const size_t red = (size_t)4 * 144 * 64 * sizeof(float);           // final cross-wave sum
     if (lds < red) lds = red;
     if (lds > LDS_LIMIT) return false;
-    const int tiles = (d->k / 64) * (d->c / 64);
+    const int tiles = (d->k / 64) * (d->c / (16 * q.ncq));
     // enough workgroups to fill the chip, as few partial copies of dw as possible
-    int parts_wanted = (2 * NUM_CUS + tiles - 1) / tiles;
+    int parts_wanted = (NUM_CUS + tiles - 1) / tiles;
     if (tiles >= NUM_CUS) parts_wanted = 1;
     const int max_strips = (P + q.SR - 1) / q.SR;
     if (parts_wanted <= d->n) {
@@ -194,7 +199,7 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     int t = 0;
     for (int r = 0; r < d->r; ++r)
         for (int s2 = 0; s2 < d->s; ++s2) q.tap_off[t++] = r * d->dil_h * q.PC + s2 * d->dil_w;
-    q.ctiles = d->c / 64;
+    q.ctiles = d->c / (16 * q.ncq);
     q.x_bytes = (uint32_t)x_bytes;
     q.dy_bytes = (uint32_t)dy_bytes;
     q.div_q = make_fastdiv((uint32_t)Q);

@@ -167,7 +167,8 @@ struct WgradStripParams {
     int32_t min_dh, min_dw;
     int32_t tap_off[9];        // patch-pixel offset of the tap
     int32_t dyplane, xplane;   // bytes per 16-channel plane of a stage
-    int32_t ctiles;
+    int32_t ncq;               // 16-channel groups of c per workgroup (4, 2 or 1)
+    int32_t ctiles;            // C / (16 * ncq)
     uint32_t x_bytes, dy_bytes;
     FastDiv div_q, div_pc;
 };

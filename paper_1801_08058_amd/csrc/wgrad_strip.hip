@@ -27,7 +27,7 @@
 // Per 32-position step a wave issues 8 (dy) + 18 (x, 9 taps) transpose loads for 36 MFMAs; x
 // fragments run three taps ahead of the MFMAs in a rolling 3-slot buffer (across step
 // boundaries), the dy fragments of the wave's next step are fetched during the current one.
-// The per-workgroup partial [tap][k][c] goes to the workspace; wgrad_strip_reduce adds the
+// The per-workgroup partial (in register order) goes to the workspace; wgrad_strip_reduce adds the
 // workgroups in index order (deterministic) and writes dw as [K][C][R][S].
 #include "common.h"
 
@@ -52,17 +52,21 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigne
     return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void wgrad_strip_bf16(const WgradStripParams p)
+// NCQ = 16-channel groups of c per workgroup (4, 2 or 1); the 8 waves are NCQ channel groups x
+// NH = 8/NCQ interleaved step streams.  Fewer channels per workgroup means fewer, longer position
+// chunks for the same number of workgroups, i.e. fewer partial copies of dw to write and re-read.
+template <int NCQ>
+__global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p)
 {
-    constexpr int NH = NW / 4;               // waves per channel quarter = step interleave
+    constexpr int NW = 8;
+    constexpr int NH = NW / NCQ;             // waves per channel group = step interleave
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int cq = wave & 3;                 // 16-channel quarter of the 64 c
-    const int wh = wave >> 2;                // step parity (NW = 8)
+    const int cq = wave % NCQ;               // 16-channel group inside the workgroup's c tile
+    const int wh = wave / NCQ;               // which of the NH step streams
     const int L = lane & 15;                 // lane inside its 16-lane transpose group
     const int grp = lane >> 4;               // reduction group: positions +8*grp
 
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(NW * 64) void wgrad_strip_bf16(const WgradStripPara
     const int PQ = p.P * p.Q;
     const int HW = p.H * p.W;
     const int KB = p.K >> 4, CB = p.C >> 4;
-    const int stage_bytes = 4 * p.dyplane + 4 * p.xplane;
+    const int stage_bytes = 4 * p.dyplane + NCQ * p.xplane;
 
     __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
@@ -88,33 +92,41 @@ __global__ __launch_bounds__(NW * 64) void wgrad_strip_bf16(const WgradStripPara
     const int steps_full = (p.SR * p.Q + 31) >> 5;           // 32-position steps of a full stage
     const int nblk_dy = steps_full;
 
-    // waves (cq, h) share plane cq (16 k of dy, 16 c of x) of every stage: blocks h, h+NH, ...
+    // load items of a stage: (plane, 32-position block) pairs, 4 dy planes then NCQ x planes,
+    // dealt round-robin to the 8 waves
+    const int items_dy = 4 * nblk_dy;
+    const int items = items_dy + NCQ * nblk_x;
     auto issue_loads = [&](int stage_lin, int buf) {
         const int img = n0 + stage_lin / p.nstages;                      // stages run image by image
         const int stage_i = stage_lin - (stage_lin / p.nstages) * p.nstages;
-        unsigned char *dys = smem + buf * stage_bytes + cq * p.dyplane;
-        unsigned char *xs = smem + buf * stage_bytes + 4 * p.dyplane + cq * p.xplane;
+        unsigned char *base = smem + buf * stage_bytes;
         const int r0 = stage_i * p.SR;                                   // first strip row of the stage
         int rows = rows_strip - r0;
         if (rows > p.SR) rows = p.SR;
         const int nvalid = rows * p.Q;                                   // positions of the stage that exist
-        const unsigned dy_base = (unsigned)((((img * KB + kt * 4 + cq) * PQ) + (p0 + r0) * p.Q) * 32);
-        for (int blk = wh; blk < nblk_dy; blk += NH) {
-            const int pos = blk * 32 + (lane >> 1);
-            const unsigned off = (pos < nvalid) ? dy_base + (unsigned)(pos * 32 + (lane & 1) * 16) : WS_OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_t *)(dys + blk * 1024), 16, (int)off, 0, 0, 0);
-        }
-        const unsigned x_base = (unsigned)(((img * CB + ct * 4 + cq) * HW) * 32);
         const int h0 = p0 + r0 + p.min_dh;
-        for (int blk = wh; blk < nblk_x; blk += NH) {
-            const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
-            const uint32_t pr = fd_div(px, p.div_pc);
-            const uint32_t pc = px - pr * p.div_pc.d;
-            const int h = h0 + (int)pr;
-            const int w = p.min_dw + (int)pc;
-            const bool ok = px < (uint32_t)npatch && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
-            const unsigned off = ok ? x_base + (unsigned)((h * p.W + w) * 32 + (lane & 1) * 16) : WS_OOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(xs + blk * 1024), 16, (int)off, 0, 0, 0);
+        for (int it = wave; it < items; it += NW) {
+            if (it < items_dy) {
+                const int pln = it / nblk_dy, blk = it - pln * nblk_dy;
+                const unsigned dy_base = (unsigned)((((img * KB + kt * 4 + pln) * PQ) + (p0 + r0) * p.Q) * 32);
+                const int pos = blk * 32 + (lane >> 1);
+                const unsigned off = (pos < nvalid) ? dy_base + (unsigned)(pos * 32 + (lane & 1) * 16) : WS_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_t *)(base + pln * p.dyplane + blk * 1024), 16,
+                                                         (int)off, 0, 0, 0);
+            } else {
+                const int itx = it - items_dy;
+                const int pln = itx / nblk_x, blk = itx - pln * nblk_x;
+                const unsigned x_base = (unsigned)(((img * CB + ct * NCQ + pln) * HW) * 32);
+                const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
+                const uint32_t pr = fd_div(px, p.div_pc);
+                const uint32_t pc = px - pr * p.div_pc.d;
+                const int h = h0 + (int)pr;
+                const int w = p.min_dw + (int)pc;
+                const bool ok = px < (uint32_t)npatch && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
+                const unsigned off = ok ? x_base + (unsigned)((h * p.W + w) * 32 + (lane & 1) * 16) : WS_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(base + 4 * p.dyplane + pln * p.xplane + blk * 1024),
+                                                         16, (int)off, 0, 0, 0);
+            }
         }
     };
 
@@ -162,7 +174,8 @@ __global__ __launch_bounds__(NW * 64) void wgrad_strip_bf16(const WgradStripPara
             return tr_frag(xs + xoff[0] + p.tap_off[t] * 32, xs + xoff[1] + p.tap_off[t] * 32);
         };
 
-        int j = wh;
+        // step streams continue across stages so that the remainders even out
+        int j = (wh - (s * steps_full) % NH + NH) % NH;
         if (j < nsteps) {
             int dyo[2], xo[2], dyn[2], xn[2];
             bf16x8 acur[4], anext[4], b[3];
@@ -198,84 +211,99 @@ __global__ __launch_bounds__(NW * 64) void wgrad_strip_bf16(const WgradStripPara
 
     // ---- sum the step-parity copies (waves h=1 publish, h=0 add) and write the partial tile.
     // Accumulator register v of tile (kb, t): k = 16 kb + 4*(lane/16) + v, c = 16 cq + lane%16.
-    float *red = reinterpret_cast<float *>(smem) + cq * (4 * WS_NT * 4 * 64);     // 144 floats per lane
-    if (NH == 2 && wh == 1) {
+    // The partial is stored in register order, [tile][cq][kb][tap][lane][v] (16 bytes per lane,
+    // 1 KB per store instruction); wgrad_strip_reduce maps it back to [K][C][R][S].
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
+    for (int stride = NH / 2; stride >= 1; stride >>= 1) {
+        if (wh >= stride && wh < 2 * stride) {
+            f32x4 *dst = red + ((wh - stride) * NCQ + cq) * (4 * WS_NT * 64);
 #pragma unroll
-            for (int t = 0; t < WS_NT; ++t)
+            for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[((kb * WS_NT + t) * 4 + v) * 64 + lane] = acc[kb][t][v];
-    }
-    __syncthreads();
-    if (wh == 0) {
-        float *out = p.partial + (size_t)blockIdx.x * WS_NT * p.K * p.C;
-        const int c = ct * 64 + cq * 16 + L;
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-            for (int t = 0; t < WS_NT; ++t)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int k = kt * 64 + kb * 16 + 4 * grp + v;
-                    float r = acc[kb][t][v];
-                    if (NH == 2) r += red[((kb * WS_NT + t) * 4 + v) * 64 + lane];
-                    out[((size_t)t * p.K + k) * p.C + c] = r;
-                }
-    }
-}
-
-// dw[k][c][tap] = sum over workgroup partials (index order) of partial[i][tap][k][c].
-// 256 threads = 64 outputs x 4 interleaved partial streams, joined in a fixed order.
-__global__ __launch_bounds__(256) void wgrad_strip_reduce(const float *__restrict__ partial, float *__restrict__ dw,
-                                                         int nparts, int K, int C, int RS)
-{
-    __shared__ float sm[4][64];
-    const size_t per = (size_t)RS * K * C;
-    const int o = threadIdx.x & 63;
-    const int sl = threadIdx.x >> 6;
-    const size_t i = (size_t)blockIdx.x * 64 + o;
-    float acc = 0.f;
-    if (i < per) {
-        float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
-        int sp = sl;
-        for (; sp + 12 < nparts; sp += 16) {
-            t0 += partial[(size_t)sp * per + i];
-            t1 += partial[(size_t)(sp + 4) * per + i];
-            t2 += partial[(size_t)(sp + 8) * per + i];
-            t3 += partial[(size_t)(sp + 12) * per + i];
+                for (int t = 0; t < WS_NT; ++t) dst[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
         }
-        for (; sp < nparts; sp += 4) t0 += partial[(size_t)sp * per + i];
-        acc = (t0 + t1) + (t2 + t3);
+        __syncthreads();
+        if (wh < stride) {
+            const f32x4 *src = red + (wh * NCQ + cq) * (4 * WS_NT * 64);
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int t = 0; t < WS_NT; ++t) acc[kb][t] += src[(kb * WS_NT + t) * 64 + lane];
+        }
+        __syncthreads();
     }
-    sm[sl][o] = acc;
-    __syncthreads();
-    if (sl == 0 && i < per) {
-        const float r = (sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o]);
-        const int c = (int)(i % C);
-        const size_t t = i / C;
-        const int k = (int)(t % K);
-        const int tap = (int)(t / K);
-        dw[((size_t)k * C + c) * RS + tap] = r;
+    if (wh == 0) {
+        f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
+                     (((size_t)blockIdx.x * gridDim.y + blockIdx.y) * NCQ + cq) * (4 * WS_NT * 64);
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) out[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
     }
 }
 
-hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
+// dw[k][c][tap] = sum over workgroup partials (index order) of partial[part][tile][cq][kb][tap][lane][v].
+// 256 threads = 32 float4 outputs x 8 interleaved partial streams, joined in a fixed order.
+__global__ __launch_bounds__(256) void wgrad_strip_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
+                                                         int nparts, int K, int C, int ctiles, int ncq)
+{
+    __shared__ f32x4 sm[8][32];
+    const size_t per4 = (size_t)WS_NT * K * C / 4;          // float4 elements of one partial
+    const int o = threadIdx.x & 31;
+    const int sl = threadIdx.x >> 5;
+    const size_t i = (size_t)blockIdx.x * 32 + o;           // per4 is a multiple of 32
+    f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
+    int sp = sl;
+    for (; sp + 8 < nparts; sp += 16) {
+        t0 += partial[(size_t)sp * per4 + i];
+        t1 += partial[(size_t)(sp + 8) * per4 + i];
+    }
+    if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
+    sm[sl][o] = t0 + t1;
+    __syncthreads();
+    if (sl == 0) {
+        const f32x4 r = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+        // decode register order: i = (((tile*ncq + cq)*4 + kb)*9 + t)*64 + lane
+        const int lane = (int)(i & 63);
+        size_t u = i >> 6;
+        const int t = (int)(u % WS_NT); u /= WS_NT;
+        const int kb = (int)(u & 3); u >>= 2;
+        const int cq = (int)(u % ncq); u /= ncq;
+        const int tile = (int)u;
+        const int kt = tile / ctiles, ct = tile - kt * ctiles;
+        const int c = (ct * ncq + cq) * 16 + (lane & 15);
+        const int k = kt * 64 + kb * 16 + 4 * (lane >> 4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dw[((size_t)(k + v) * C + c) * WS_NT + t] = r[v];
+    }
+}
+
+template <int NCQ>
+static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_strip_bf16<8>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
-    hipLaunchKernelGGL(wgrad_strip_bf16<8>, grid, dim3(512), lds_bytes, st, p);
-    hipError_t e = hipGetLastError();
+    hipLaunchKernelGGL(wgrad_strip_bf16<NCQ>, grid, dim3(512), lds_bytes, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
+{
+    hipError_t e = p.ncq == 4   ? launch_wgrad_strip_ncq<4>(p, lds_bytes, st)
+                   : p.ncq == 2 ? launch_wgrad_strip_ncq<2>(p, lds_bytes, st)
+                   : p.ncq == 1 ? launch_wgrad_strip_ncq<1>(p, lds_bytes, st)
+                                : hipErrorInvalidValue;
     if (e != hipSuccess) return e;
-    const size_t per = (size_t)WS_NT * p.K * p.C;
-    hipLaunchKernelGGL(wgrad_strip_reduce, dim3((unsigned)((per + 63) / 64)), dim3(256), 0, st, p.partial, p.dw,
-                       p.nparts, p.K, p.C, WS_NT);
+    const size_t per4 = (size_t)WS_NT * p.K * p.C / 4;
+    hipLaunchKernelGGL(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+                       reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
     return hipGetLastError();
 }
 

@@ -205,6 +205,18 @@ def test_wgrad_per_tap_kernel_still_matches(case, monkeypatch):
     assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
 
 
+@pytest.mark.parametrize("case", [12, 13, 14])
+@pytest.mark.parametrize("ncq", [1, 2, 4])
+def test_wgrad_all_taps_channel_group_variants(case, ncq, monkeypatch):
+    monkeypatch.setenv("NGC_WGRAD_NCQ", str(ncq))
+    a = MFMA_CASES[case]
+    x, w, b, dy = _tensors(a, "bf16", 4000 + case)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_strip_bf16"
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
+
+
 def test_run_to_run_identical():
     a = MFMA_CASES[0]
     x, w, b, dy = _tensors(a, "bf16", 5)
