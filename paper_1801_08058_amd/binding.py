@@ -49,6 +49,13 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_1801_08058_amd.build` "
             "(there is no fallback path)")
+    # PyTorch supplies device memory and streams and ships its own HIP runtime under the same
+    # soname as the system one; the process must end up with ONE runtime, and it has to be the
+    # one torch initialises, so torch is loaded first when it is installed.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     D = ctypes.POINTER(ngc_conv_desc)
     vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32

@@ -6,6 +6,7 @@
 #include "common.h"
 
 #include <limits.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -286,7 +287,12 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
     return 0;
 }
 
-int launch_status(hipError_t e) { return e == hipSuccess ? NGC_OK : NGC_LAUNCH_FAILED; }
+int launch_status(hipError_t e)
+{
+    if (e == hipSuccess) return NGC_OK;
+    fprintf(stderr, "ngconv: HIP launch failed: %s\n", hipGetErrorString(e));   // error path only
+    return NGC_LAUNCH_FAILED;
+}
 
 void fill_class(IgemmClass &c, int oa_h, int oa_w, int OP, int OQ, int tap_begin, int tap_count, int N)
 {

@@ -4,6 +4,15 @@
 #include <stdint.h>
 #include "../../include/ngconv.h"
 
+// Launch wrapper: the HIP "last error" is per-thread state shared with every other user of the
+// runtime in the process (a pending hipEventQuery of the caller's allocator leaves
+// hipErrorNotReady there), so it is cleared before the launch and read right after it.
+#define NGC_LAUNCH(...)            \
+    do {                           \
+        (void)hipGetLastError();   \
+        hipLaunchKernelGGL(__VA_ARGS__); \
+    } while (0)
+
 namespace ngc {
 
 // ---- exact unsigned division by a runtime constant (round-up multiplier method) ----

@@ -133,10 +133,10 @@ hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x
     const size_t total = phys_elems(d.y_layout, d.n, d.k, P, Q);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (d.dtype == NGC_F32)
-        hipLaunchKernelGGL(direct_fwd<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q, static_cast<const float *>(x),
+        NGC_LAUNCH(direct_fwd<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q, static_cast<const float *>(x),
                            static_cast<const float *>(w), bias, static_cast<float *>(y), total);
     else
-        hipLaunchKernelGGL(direct_fwd<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
+        NGC_LAUNCH(direct_fwd<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), bias,
                            static_cast<uint16_t *>(y), total);
     return hipGetLastError();
@@ -148,11 +148,11 @@ hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const vo
     const size_t total = phys_elems(d.x_layout, d.n, d.c, d.h, d.w);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (d.dtype == NGC_F32)
-        hipLaunchKernelGGL(direct_bwd_data<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
+        NGC_LAUNCH(direct_bwd_data<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const float *>(dy), static_cast<const float *>(w), static_cast<float *>(dx),
                            total);
     else
-        hipLaunchKernelGGL(direct_bwd_data<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
+        NGC_LAUNCH(direct_bwd_data<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(dy), static_cast<const uint16_t *>(w),
                            static_cast<uint16_t *>(dx), total);
     return hipGetLastError();
@@ -163,10 +163,10 @@ hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const
 {
     const unsigned blocks = (unsigned)((size_t)d.k * d.c * d.r * d.s);
     if (d.dtype == NGC_F32)
-        hipLaunchKernelGGL(direct_bwd_filters<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
+        NGC_LAUNCH(direct_bwd_filters<float>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const float *>(x), static_cast<const float *>(dy), dw);
     else
-        hipLaunchKernelGGL(direct_bwd_filters<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
+        NGC_LAUNCH(direct_bwd_filters<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(dy), dw);
     return hipGetLastError();
 }

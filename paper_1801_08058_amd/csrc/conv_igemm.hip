@@ -242,10 +242,10 @@ hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_
 {
     if (bn == 128) {
         dim3 grid((max_m + 127) / 128, p.Cout / 128, p.ncls);
-        hipLaunchKernelGGL((igemm_bf16<128, 128>), grid, dim3(256), 0, st, p);
+        NGC_LAUNCH((igemm_bf16<128, 128>), grid, dim3(256), 0, st, p);
     } else {
         dim3 grid((max_m + 255) / 256, p.Cout / 64, p.ncls);
-        hipLaunchKernelGGL((igemm_bf16<256, 64>), grid, dim3(256), 0, st, p);
+        NGC_LAUNCH((igemm_bf16<256, 64>), grid, dim3(256), 0, st, p);
     }
     return hipGetLastError();
 }

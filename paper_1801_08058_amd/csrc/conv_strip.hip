@@ -235,7 +235,7 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
         attr_set = true;
     }
     dim3 grid(p.groups * p.strips, p.Cout / 64);
-    hipLaunchKernelGGL((conv_strip_bf16<NF, NW>), grid, dim3(NW * 64), lds_bytes, st, p);
+    NGC_LAUNCH((conv_strip_bf16<NF, NW>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
 

@@ -199,25 +199,25 @@ hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, con
         uint16_t *d = static_cast<uint16_t *>(dst);
         const int v = (HW % 8 == 0) ? 8 : (HW % 4 == 0) ? 4 : (HW % 2 == 0) ? 2 : 1;
         if (src_layout == NGC_NCHW) {
-            if (v == 8) hipLaunchKernelGGL(nchw_to_blocked16_b16<8>, grid, block, 0, st, s, d, c, HW);
-            else if (v == 4) hipLaunchKernelGGL(nchw_to_blocked16_b16<4>, grid, block, 0, st, s, d, c, HW);
-            else if (v == 2) hipLaunchKernelGGL(nchw_to_blocked16_b16<2>, grid, block, 0, st, s, d, c, HW);
-            else hipLaunchKernelGGL(nchw_to_blocked16_b16<1>, grid, block, 0, st, s, d, c, HW);
+            if (v == 8) NGC_LAUNCH(nchw_to_blocked16_b16<8>, grid, block, 0, st, s, d, c, HW);
+            else if (v == 4) NGC_LAUNCH(nchw_to_blocked16_b16<4>, grid, block, 0, st, s, d, c, HW);
+            else if (v == 2) NGC_LAUNCH(nchw_to_blocked16_b16<2>, grid, block, 0, st, s, d, c, HW);
+            else NGC_LAUNCH(nchw_to_blocked16_b16<1>, grid, block, 0, st, s, d, c, HW);
         } else {
-            if (v == 8) hipLaunchKernelGGL(blocked16_to_nchw_b16<8>, grid, block, 0, st, s, d, c, HW);
-            else if (v == 4) hipLaunchKernelGGL(blocked16_to_nchw_b16<4>, grid, block, 0, st, s, d, c, HW);
-            else if (v == 2) hipLaunchKernelGGL(blocked16_to_nchw_b16<2>, grid, block, 0, st, s, d, c, HW);
-            else hipLaunchKernelGGL(blocked16_to_nchw_b16<1>, grid, block, 0, st, s, d, c, HW);
+            if (v == 8) NGC_LAUNCH(blocked16_to_nchw_b16<8>, grid, block, 0, st, s, d, c, HW);
+            else if (v == 4) NGC_LAUNCH(blocked16_to_nchw_b16<4>, grid, block, 0, st, s, d, c, HW);
+            else if (v == 2) NGC_LAUNCH(blocked16_to_nchw_b16<2>, grid, block, 0, st, s, d, c, HW);
+            else NGC_LAUNCH(blocked16_to_nchw_b16<1>, grid, block, 0, st, s, d, c, HW);
         }
         return hipGetLastError();
     }
     const size_t total = (dst_layout == NGC_NCHW) ? (size_t)n * c * HW : (size_t)n * CB * HW * 16;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (elem_bytes == 2)
-        hipLaunchKernelGGL(layout_generic<uint16_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint16_t *>(src),
+        NGC_LAUNCH(layout_generic<uint16_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint16_t *>(src),
                            static_cast<uint16_t *>(dst), n, c, h, w, src_layout, dst_layout, total);
     else
-        hipLaunchKernelGGL(layout_generic<uint32_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint32_t *>(src),
+        NGC_LAUNCH(layout_generic<uint32_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint32_t *>(src),
                            static_cast<uint32_t *>(dst), n, c, h, w, src_layout, dst_layout, total);
     return hipGetLastError();
 }
@@ -229,11 +229,11 @@ hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, con
                                                          : (size_t)R * S * ((K + 15) / 16) * C * 16;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (elem_bytes == 2)
-        hipLaunchKernelGGL(filter_to_blocked<uint16_t>, dim3(blocks), dim3(256), 0, st,
+        NGC_LAUNCH(filter_to_blocked<uint16_t>, dim3(blocks), dim3(256), 0, st,
                            static_cast<const uint16_t *>(w_kcrs), static_cast<uint16_t *>(dst), K, C, R, S, dst_layout,
                            total);
     else
-        hipLaunchKernelGGL(filter_to_blocked<uint32_t>, dim3(blocks), dim3(256), 0, st,
+        NGC_LAUNCH(filter_to_blocked<uint32_t>, dim3(blocks), dim3(256), 0, st,
                            static_cast<const uint32_t *>(w_kcrs), static_cast<uint32_t *>(dst), K, C, R, S, dst_layout,
                            total);
     return hipGetLastError();

@@ -215,14 +215,14 @@ __global__ __launch_bounds__(256) void wgrad_reduce(const float *__restrict__ pa
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st)
 {
     dim3 grid(p.splits, (p.K / 64) * (p.C / 64), p.R * p.S);
-    hipLaunchKernelGGL(wgrad_bf16, grid, dim3(256), 0, st, p);
+    NGC_LAUNCH(wgrad_bf16, grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S, hipStream_t st)
 {
     const size_t per = (size_t)R * S * K * C;
-    hipLaunchKernelGGL(wgrad_reduce, dim3((unsigned)((per + 255) / 256)), dim3(256), 0, st, partial, dw, splits, K, C,
+    NGC_LAUNCH(wgrad_reduce, dim3((unsigned)((per + 255) / 256)), dim3(256), 0, st, partial, dw, splits, K, C,
                        R * S);
     return hipGetLastError();
 }

@@ -290,7 +290,7 @@ static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_b
         attr_set = true;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
-    hipLaunchKernelGGL(wgrad_strip_bf16<NCQ>, grid, dim3(512), lds_bytes, st, p);
+    NGC_LAUNCH(wgrad_strip_bf16<NCQ>, grid, dim3(512), lds_bytes, st, p);
     return hipGetLastError();
 }
 
@@ -302,7 +302,7 @@ hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipSt
                                 : hipErrorInvalidValue;
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)WS_NT * p.K * p.C / 4;
-    hipLaunchKernelGGL(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+    NGC_LAUNCH(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
                        reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
     return hipGetLastError();
 }
