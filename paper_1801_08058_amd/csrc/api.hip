@@ -59,7 +59,7 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -210,6 +210,30 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     return true;
 }
 
+// low-channel stem forward: C <= 3, 7x7, stride 2, pad_below_w 3, NCHW input, blocked output
+bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size_t *lds_out)
+{
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_KCRS)
+        return false;
+    if (d->c > 3 || d->r != 7 || d->s != 7 || d->stride_h != 2 || d->stride_w != 2 || d->dil_h != 1 || d->dil_w != 1)
+        return false;
+    if (d->pad_below_w != 3 || d->w % 8 != 0 || d->k % 64 != 0 || 2 * Q > d->w + 2) return false;
+    StemFwdParams q;
+    memset(&q, 0, sizeof(q));
+    q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q;
+    q.pbh = d->pad_below_h;
+    q.TP = P < 8 ? P : 8;
+    q.tiles_per_img = (P + q.TP - 1) / q.TP;
+    q.div_q = make_fastdiv((uint32_t)Q);
+    const size_t patch = (size_t)d->c * (2 * q.TP + 5) * (2 * d->w + 16);
+    const size_t lds = ((patch + 15) & ~(size_t)15) + (size_t)64 * d->c * 49 * 2;
+    if (lds > 64 * 1024) return false;
+    if ((size_t)d->n * q.tiles_per_img > 0x7FFFFFFF) return false;
+    if (sp) *sp = q;
+    if (lds_out) *lds_out = lds;
+    return true;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -220,6 +244,7 @@ Variant pick(const ngc_conv_desc *d, int op)
     int P, Q;
     if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
     if (op == NGC_OP_FWD) {
+        if (stem_fwd_plan(d, P, Q, nullptr, nullptr)) return V_STEM_FWD;
         const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
         const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
         if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
@@ -355,6 +380,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_WGRAD_64: return "wgrad_bf16_64x64";
     case V_STRIP: return "strip_bf16";
     case V_WGRAD_STRIP: return "wgrad_strip_bf16";
+    case V_STEM_FWD: return "stem_fwd_bf16";
     default: return "invalid";
     }
 }
@@ -386,6 +412,17 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (v == V_DIRECT)
         return launch_status(launch_direct_fwd(*desc, P, Q, x, w, (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr, y, st));
+    if (v == V_STEM_FWD) {
+        StemFwdParams sp;
+        size_t lds;
+        if (!stem_fwd_plan(desc, P, Q, &sp, &lds)) return NGC_UNSUPPORTED;
+        sp.x = static_cast<const uint16_t *>(x);
+        sp.w = static_cast<const uint16_t *>(w);
+        sp.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+        sp.y = static_cast<uint16_t *>(y);
+        sp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+        return launch_status(launch_stem_fwd(sp, lds, st));
+    }
 
     const size_t need = workspace_bytes(desc, NGC_OP_FWD, v, P, Q);
     if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;

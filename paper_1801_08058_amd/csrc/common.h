@@ -182,9 +182,23 @@ struct WgradStripParams {
     FastDiv div_q, div_pc;
 };
 
+// ---- low-channel stem forward (C <= 3, 7x7 stride 2, NCHW in, blocked out) ----
+struct StemFwdParams {
+    const uint16_t *x;         // NCHW
+    const uint16_t *w;         // KCRS
+    const float *bias;         // may be null
+    uint16_t *y;               // blocked
+    int32_t N, C, H, W, K, P, Q;
+    int32_t pbh;
+    int32_t relu;
+    int32_t TP, tiles_per_img;
+    FastDiv div_q;
+};
+
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
+hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,

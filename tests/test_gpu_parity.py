@@ -300,6 +300,19 @@ def test_cfg3_full_size_with_device_layout_conversion():
     _sampled_layer_check(L)
 
 
+STEM_CASES = [
+    Attrs(2, 3, 38, 40, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3),       # ragged last tile (P = 19), Q = 20
+    Attrs(1, 2, 23, 16, 128, 7, 7, 2, 2, 1, 1, 2, 3, 4, 2),      # C = 2, asymmetric pads, two k tiles
+    Attrs(3, 1, 64, 64, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3),       # C = 1
+]
+
+
+@pytest.mark.parametrize("case", range(len(STEM_CASES)))
+def test_stem_kernels_small(case):
+    a = STEM_CASES[case]
+    _check_all(a, "bf16", NCHW, BLK, False, 5000 + case, ("stem_fwd", "", ""))
+
+
 def test_cfg4_stem_reduced_batch():
     L = synth_inputs.config_layers(4, batch=4)[0]
     _sampled_layer_check(L, n_y=50_000, n_dw=512)
