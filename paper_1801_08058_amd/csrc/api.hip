@@ -59,7 +59,7 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -234,6 +234,46 @@ bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size
     return true;
 }
 
+// low-channel stem backprop-filters: same shapes as stem forward, plus Q % 8 == 0
+bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, size_t *lds_out)
+{
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C) return false;
+    if (d->c > 3 || d->r != 7 || d->s != 7 || d->stride_h != 2 || d->stride_w != 2 || d->dil_h != 1 || d->dil_w != 1)
+        return false;
+    if (d->pad_below_w != 3 || d->w % 8 != 0 || d->k % 64 != 0 || 2 * Q > d->w || Q % 8 != 0) return false;
+    const size_t dy_bytes = (size_t)d->n * d->k * P * Q * 2;
+    if (dy_bytes >= ((size_t)1 << 31)) return false;
+    WgradStemParams q;
+    memset(&q, 0, sizeof(q));
+    int sr = 1;
+    while ((sr * Q) % 32 != 0) ++sr;                                    // <= 4 since Q % 8 == 0
+    while (2 * sr * Q <= 256 && 2 * sr <= P) sr *= 2;                   // about 224 positions per stage
+    q.SR = sr;
+    const int rows_in = 2 * sr + 5;
+    if (d->c * rows_in * (d->w / 8) > 1024) return false;               // 2 x-chunks per thread
+    q.dyplane = (sr * Q / 32) * 1024 + 128;
+    const size_t xbytes = (size_t)d->c * rows_in * 2 * (d->w + 16);
+    size_t lds = 2 * ((size_t)4 * q.dyplane + ((xbytes + 15) & ~(size_t)15));
+    if (lds < 98304) lds = 98304;                                       // final cross-wave tree
+    if (lds > LDS_LIMIT) return false;
+    const int ktiles = d->k / 64;
+    int strips = (NUM_CUS + d->n * ktiles - 1) / (d->n * ktiles);
+    const int max_strips = (P + sr - 1) / sr;
+    if (strips > max_strips) strips = max_strips;
+    if (strips < 1) strips = 1;
+    int tp = (P + strips - 1) / strips;
+    tp = (tp + sr - 1) / sr * sr;
+    q.TP = tp;
+    q.strips = (P + tp - 1) / tp;
+    q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q;
+    q.pbh = d->pad_below_h;
+    q.dy_bytes = (uint32_t)dy_bytes;
+    q.div_q = make_fastdiv((uint32_t)Q);
+    if (wp) *wp = q;
+    if (lds_out) *lds_out = lds;
+    return true;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -260,6 +300,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_FILTERS) {
+        if (wgrad_stem_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STEM;
         if (blocked_bf16(d) && wgrad_strip_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STRIP;
         if (blocked_bf16(d) && d->c % 64 == 0 && d->k % 64 == 0 && d->r * d->s <= 65535) return V_WGRAD_64;
         return V_DIRECT;
@@ -298,6 +339,11 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
+    if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STEM) {
+        WgradStemParams wp;
+        wgrad_stem_plan(d, P, Q, &wp, nullptr);
+        return round256((size_t)d->n * wp.strips * (d->k / 64) * 2 * 4 * 6 * 64 * 16);
+    }
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STRIP) {
         WgradStripParams wp;
         wgrad_strip_plan(d, P, Q, &wp, nullptr);
@@ -381,6 +427,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_STRIP: return "strip_bf16";
     case V_WGRAD_STRIP: return "wgrad_strip_bf16";
     case V_STEM_FWD: return "stem_fwd_bf16";
+    case V_WGRAD_STEM: return "wgrad_stem_bf16";
     default: return "invalid";
     }
 }
@@ -555,6 +602,16 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);
     if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    if (v == V_WGRAD_STEM) {
+        WgradStemParams wp;
+        size_t lds;
+        if (!wgrad_stem_plan(desc, P, Q, &wp, &lds)) return NGC_UNSUPPORTED;
+        wp.x = static_cast<const uint16_t *>(x);
+        wp.dy = static_cast<const uint16_t *>(dy);
+        wp.partial = static_cast<float *>(ws);
+        wp.dw = dw;
+        return launch_status(launch_wgrad_stem(wp, lds, st));
+    }
     if (v == V_WGRAD_STRIP) {
         WgradStripParams wp;
         size_t lds;

@@ -195,10 +195,26 @@ struct StemFwdParams {
     FastDiv div_q;
 };
 
+// ---- low-channel stem backprop-filters ----
+struct WgradStemParams {
+    const uint16_t *x;         // NCHW
+    const uint16_t *dy;        // blocked
+    float *partial;
+    float *dw;                 // [K][C][7][7]
+    int32_t N, C, H, W, K, P, Q;
+    int32_t pbh;
+    int32_t TP, strips;        // dy rows per workgroup (multiple of SR), strips per image
+    int32_t SR;                // dy rows per LDS stage (SR*Q multiple of 32)
+    int32_t dyplane;           // bytes per 16-channel dy plane of a stage
+    uint32_t dy_bytes;
+    FastDiv div_q;
+};
+
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);
+hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,

@@ -304,6 +304,8 @@ STEM_CASES = [
     Attrs(2, 3, 38, 40, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3),       # ragged last tile (P = 19), Q = 20
     Attrs(1, 2, 23, 16, 128, 7, 7, 2, 2, 1, 1, 2, 3, 4, 2),      # C = 2, asymmetric pads, two k tiles
     Attrs(3, 1, 64, 64, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3),       # C = 1
+    Attrs(2, 3, 50, 48, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3),       # Q = 24: 4-row stages, ragged last stage (P = 25)
+    Attrs(5, 3, 30, 80, 128, 7, 7, 2, 2, 1, 1, 1, 3, 2, 3),      # Q = 40, two k tiles, asymmetric pad_h
 ]
 
 
