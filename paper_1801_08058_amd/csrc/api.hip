@@ -59,20 +59,71 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
 
-// Geometry of the output-stationary strip kernel for forward (op 0) or backprop-data (op 1).
-// Returns false if the shape does not fit it.
-bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, int *nf_out, size_t *lds_out)
+// Tiling of the output-stationary strip kernel: picks the strip size (nf = 32-position fragments
+// per SIMD) and fills the geometry fields of `q` for an output of N x Hout x Wout positions whose
+// taps span span_h x span_w input pixels.  Returns false if nothing fits.
+bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int span_w, int ntaps, int Cout,
+                    int *nf_out, size_t *lds_out)
 {
-    if (d->stride_h != 1 || d->stride_w != 1) return false;
     // NGC_STRIP_NF (tests / benchmarks only): 0 disables this kernel, 7 / 4 / 2 forces a strip size
     const char *force = getenv("NGC_STRIP_NF");
     const int forced_nf = force ? atoi(force) : -1;
     if (forced_nf == 0) return false;
+    StripParams best;
+    int best_nf = 0;
+    size_t best_lds = 0;
+    const int nfs[3] = {7, 4, 2};
+    for (int nf : nfs) {
+        if (forced_nf > 0 && nf != forced_nf) continue;
+        const int maxpix = 4 * nf * 32;
+        if (Wout > maxpix) continue;
+        StripParams q = out;
+        const int rows_fit = maxpix / Wout;
+        if (rows_fit >= Hout) {
+            q.TP = Hout;
+            q.TN = maxpix / (Hout * Wout);
+            if (q.TN > N) q.TN = N;
+            q.strips = 1;
+        } else {
+            q.TN = 1;
+            q.strips = (Hout + rows_fit - 1) / rows_fit;
+            q.TP = (Hout + q.strips - 1) / q.strips;
+            q.strips = (Hout + q.TP - 1) / q.TP;
+        }
+        q.groups = (N + q.TN - 1) / q.TN;
+        q.PR = q.TP + span_h;
+        q.PC = Wout + span_w;
+        q.npix = q.TN * q.TP * Wout;
+        q.npatch = q.TN * q.PR * q.PC;
+        const int nblocks = (q.npatch + 63) / 64;
+        if (nblocks > 24) continue;                                  // 64-pixel patch blocks per plane
+        q.xpitch = nblocks * 1024 + 128;
+        const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)2 * ntaps * (64 * 16 + 128));
+        if (lds > LDS_LIMIT) continue;
+        q.div_tpq = make_fastdiv((uint32_t)(q.TP * Wout));
+        q.div_q = make_fastdiv((uint32_t)Wout);
+        q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
+        q.div_pc = make_fastdiv((uint32_t)q.PC);
+        const long wgs = (long)q.groups * q.strips * (Cout / 64);
+        best = q; best_nf = nf; best_lds = lds;
+        if (wgs >= NUM_CUS) break;                                   // largest strip that still fills the chip
+    }
+    if (!best_nf) return false;
+    out = best;
+    if (nf_out) *nf_out = best_nf;
+    if (lds_out) *lds_out = best_lds;
+    return true;
+}
+
+// Strip kernel for forward (op 0) or backprop-data (op 1) of a stride-1 multi-tap convolution.
+bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, int *nf_out, size_t *lds_out)
+{
+    if (d->stride_h != 1 || d->stride_w != 1) return false;
     const int ntaps = d->r * d->s;
     if (ntaps < 2 || ntaps > STRIP_MAX_TAPS) return false;
     const int Cin = op == NGC_OP_FWD ? d->c : d->k, Cout = op == NGC_OP_FWD ? d->k : d->c;
@@ -86,64 +137,92 @@ bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, i
     const int min_dh = op == NGC_OP_FWD ? -d->pad_below_h : d->pad_below_h - span_h;
     const int min_dw = op == NGC_OP_FWD ? -d->pad_below_w : d->pad_below_w - span_w;
 
-    StripParams best;
-    int best_nf = 0;
-    size_t best_lds = 0;
-    const int nfs[3] = {7, 4, 2};
-    for (int nf : nfs) {
-        if (forced_nf > 0 && nf != forced_nf) continue;
-        const int maxpix = 4 * nf * 32;
-        if (Wout > maxpix) continue;
-        StripParams q;
-        memset(&q, 0, sizeof(q));
-        const int rows_fit = maxpix / Wout;
-        if (rows_fit >= Hout) {
-            q.TP = Hout;
-            q.TN = maxpix / (Hout * Wout);
-            if (q.TN > d->n) q.TN = d->n;
-            q.strips = 1;
-        } else {
-            q.TN = 1;
-            q.strips = (Hout + rows_fit - 1) / rows_fit;
-            q.TP = (Hout + q.strips - 1) / q.strips;
-            q.strips = (Hout + q.TP - 1) / q.TP;
+    StripParams q;
+    memset(&q, 0, sizeof(q));
+    q.N = d->n; q.Cin = Cin; q.Hin = Hin; q.Win = Win; q.Cout = Cout; q.Hout = Hout; q.Wout = Wout;
+    q.min_dh = min_dh; q.min_dw = min_dw;
+    q.ntaps = ntaps;
+    q.in_bytes = (uint32_t)in_bytes;
+    q.wt_bytes = (uint32_t)wt_bytes;
+    if (!strip_geometry(q, d->n, Hout, Wout, span_h, span_w, ntaps, Cout, nf_out, lds_out)) return false;
+    int t = 0;
+    for (int r = 0; r < d->r; ++r)
+        for (int s2 = 0; s2 < d->s; ++s2) {
+            const int dh = op == NGC_OP_FWD ? r * d->dil_h - d->pad_below_h : d->pad_below_h - r * d->dil_h;
+            const int dw = op == NGC_OP_FWD ? s2 * d->dil_w - d->pad_below_w : d->pad_below_w - s2 * d->dil_w;
+            q.tap_off[t] = (dh - min_dh) * q.PC + (dw - min_dw);
+            q.tap_slab[t] = r * d->s + s2;
+            ++t;
         }
-        q.groups = (d->n + q.TN - 1) / q.TN;
-        q.PR = q.TP + span_h;
-        q.PC = Wout + span_w;
-        q.npix = q.TN * q.TP * Wout;
-        q.npatch = q.TN * q.PR * q.PC;
-        const int nblocks = (q.npatch + 63) / 64;
-        if (nblocks > 4 * 6) continue;                              // STRIP_MAXXB blocks per wave
-        q.xpitch = nblocks * 1024 + 128;
-        const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)2 * ntaps * (64 * 16 + 128));
-        if (lds > LDS_LIMIT) continue;
-        q.N = d->n; q.Cin = Cin; q.Hin = Hin; q.Win = Win; q.Cout = Cout; q.Hout = Hout; q.Wout = Wout;
-        q.min_dh = min_dh; q.min_dw = min_dw;
-        q.ntaps = ntaps;
-        int t = 0;
-        for (int r = 0; r < d->r; ++r)
-            for (int s2 = 0; s2 < d->s; ++s2) {
-                const int dh = op == NGC_OP_FWD ? r * d->dil_h - d->pad_below_h : d->pad_below_h - r * d->dil_h;
-                const int dw = op == NGC_OP_FWD ? s2 * d->dil_w - d->pad_below_w : d->pad_below_w - s2 * d->dil_w;
-                q.tap_off[t] = (dh - min_dh) * q.PC + (dw - min_dw);
-                q.tap_slab[t] = r * d->s + s2;
-                ++t;
-            }
-        q.in_bytes = (uint32_t)in_bytes;
-        q.wt_bytes = (uint32_t)wt_bytes;
-        q.div_tpq = make_fastdiv((uint32_t)(q.TP * Wout));
-        q.div_q = make_fastdiv((uint32_t)Wout);
-        q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
-        q.div_pc = make_fastdiv((uint32_t)q.PC);
-        const long wgs = (long)q.groups * q.strips * (Cout / 64);
-        best = q; best_nf = nf; best_lds = lds;
-        if (wgs >= NUM_CUS) break;                                   // largest strip that still fills the chip
+    if (sp) *sp = q;
+    return true;
+}
+
+// Backprop-data of a low-channel stride-2 convolution (the stem) through the strip kernel.
+// Output pixels are grouped into 2x2 blocks (i,j) -> (2i+a, 2j+b); block (i,j), "channel"
+// col = (2a+b)*C + c is a stride-1 convolution of dy over the union of the four residue classes'
+// tap offsets, with a combined filter (zeros where a class has no tap) built by
+// launch_subpixel_filter.  Columns are padded to 64; the strip kernel stores them as NCHW pixels.
+struct StemBwdPlan {
+    StripParams sp;
+    int nf;
+    size_t lds;
+    int dr_min, ndr, ds_min, nds;
+    size_t wu_bytes;
+};
+
+bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
+{
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_KCRS)
+        return false;
+    if (d->stride_h != 2 || d->stride_w != 2 || d->dil_h != 1 || d->dil_w != 1) return false;
+    if (4 * d->c > 64 || d->k % 16 != 0) return false;
+    int dr_min = INT_MAX, dr_max = INT_MIN, ds_min = INT_MAX, ds_max = INT_MIN;
+    for (int a = 0; a < 2; ++a) {
+        for (int r = 0; r < d->r; ++r) {
+            const int v = a + d->pad_below_h - r;
+            if (v & 1) continue;
+            const int dr = v / 2;                              // exact
+            if (dr < dr_min) dr_min = dr;
+            if (dr > dr_max) dr_max = dr;
+        }
+        for (int s2 = 0; s2 < d->s; ++s2) {
+            const int v = a + d->pad_below_w - s2;
+            if (v & 1) continue;
+            const int ds = v / 2;
+            if (ds < ds_min) ds_min = ds;
+            if (ds > ds_max) ds_max = ds;
+        }
     }
-    if (!best_nf) return false;
-    if (sp) *sp = best;
-    if (nf_out) *nf_out = best_nf;
-    if (lds_out) *lds_out = best_lds;
+    if (dr_min > dr_max || ds_min > ds_max) return false;
+    StemBwdPlan pl;
+    pl.dr_min = dr_min; pl.ndr = dr_max - dr_min + 1;
+    pl.ds_min = ds_min; pl.nds = ds_max - ds_min + 1;
+    const int ntaps = pl.ndr * pl.nds;
+    if (ntaps < 2 || ntaps > STRIP_MAX_TAPS) return false;
+    const size_t in_bytes = (size_t)d->n * d->k * P * Q * 2;
+    pl.wu_bytes = (size_t)ntaps * d->k * 64 * 2;
+    if (in_bytes >= ((size_t)1 << 31)) return false;
+    StripParams q;
+    memset(&q, 0, sizeof(q));
+    const int Hout = (d->h + 1) / 2, Wout = (d->w + 1) / 2;
+    q.N = d->n; q.Cin = d->k; q.Hin = P; q.Win = Q; q.Cout = 64; q.Hout = Hout; q.Wout = Wout;
+    q.min_dh = dr_min; q.min_dw = ds_min;
+    q.ntaps = ntaps;
+    q.in_bytes = (uint32_t)in_bytes;
+    q.wt_bytes = (uint32_t)pl.wu_bytes;
+    q.out_mode = 1;
+    q.sub_C = d->c; q.sub_H = d->h; q.sub_W = d->w;
+    if (!strip_geometry(q, d->n, Hout, Wout, pl.ndr - 1, pl.nds - 1, ntaps, 64, &pl.nf, &pl.lds)) return false;
+    int t = 0;
+    for (int i = 0; i < pl.ndr; ++i)
+        for (int j = 0; j < pl.nds; ++j) {
+            q.tap_off[t] = i * q.PC + j;
+            q.tap_slab[t] = t;
+            ++t;
+        }
+    pl.sp = q;
+    if (out) *out = pl;
     return true;
 }
 
@@ -292,6 +371,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_DATA) {
+        if (stem_bwd_plan(d, P, Q, nullptr)) return V_STEM_BWD;
         const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
         const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
                         d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
@@ -339,6 +419,11 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
+    if (op == NGC_OP_BWD_DATA && v == V_STEM_BWD) {
+        StemBwdPlan pl;
+        stem_bwd_plan(d, P, Q, &pl);
+        return round256(pl.wu_bytes);
+    }
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STEM) {
         WgradStemParams wp;
         wgrad_stem_plan(d, P, Q, &wp, nullptr);
@@ -428,6 +513,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_WGRAD_STRIP: return "wgrad_strip_bf16";
     case V_STEM_FWD: return "stem_fwd_bf16";
     case V_WGRAD_STEM: return "wgrad_stem_bf16";
+    case V_STEM_BWD: return "stem_bwd_strip_bf16";
     default: return "invalid";
     }
 }
@@ -527,6 +613,21 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, dx, st));
+    if (v == V_STEM_BWD) {
+        StemBwdPlan pl;
+        if (!stem_bwd_plan(desc, P, Q, &pl)) return NGC_UNSUPPORTED;
+        if (!ws || ws_bytes < round256(pl.wu_bytes)) return NGC_WORKSPACE_TOO_SMALL;
+        hipError_t e = launch_subpixel_filter(desc->k, desc->c, desc->r, desc->s, desc->pad_below_h, desc->pad_below_w,
+                                              pl.dr_min, pl.ndr, pl.ds_min, pl.nds, static_cast<const uint16_t *>(w),
+                                              static_cast<uint16_t *>(ws), st);
+        if (e != hipSuccess) return launch_status(e);
+        pl.sp.in = static_cast<const uint16_t *>(dy);
+        pl.sp.wt = static_cast<const uint16_t *>(ws);
+        pl.sp.out = static_cast<uint16_t *>(dx);
+        pl.sp.bias = nullptr;
+        pl.sp.relu = 0;
+        return launch_status(launch_strip(pl.sp, pl.nf, pl.lds, st));
+    }
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_DATA, v, P, Q);
     if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;

@@ -145,6 +145,10 @@ struct StripParams {
     int32_t tap_off[STRIP_MAX_TAPS];    // patch-pixel offset of the tap
     int32_t tap_slab[STRIP_MAX_TAPS];
     uint32_t in_bytes, wt_bytes;
+    // out_mode 0: 16-channel-blocked [N][Cout/16][Hout][Wout][16].
+    // out_mode 1: "sub-pixel" NCHW: output channel col = (2a+b)*sub_C + c of position (i,j) is
+    //             pixel (2i+a, 2j+b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.
+    int32_t out_mode, sub_C, sub_H, sub_W;
     FastDiv div_tpq, div_q, div_prpc, div_pc;
 };
 
@@ -227,6 +231,8 @@ hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const
                                      float *dw, hipStream_t st);
 hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,
                                  void *dst, int dst_layout, hipStream_t st);
+hipError_t launch_subpixel_filter(int K, int C, int R, int S, int pbh, int pbw, int dr_min, int ndr, int ds_min, int nds,
+                                  const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st);
 hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, const void *w_kcrs, void *dst,
                                  int dst_layout, hipStream_t st);
 

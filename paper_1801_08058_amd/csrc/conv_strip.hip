@@ -191,6 +191,24 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         const int oh = p0 + (int)tp;
         ok = ok && n < p.N && oh < p.Hout;
         const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + q;
+        if (p.out_mode == 1) {
+            // sub-pixel NCHW store: column col = (2a+b)*C + c -> pixel (2 oh + a, 2 q + b) of channel c
+            const int ncol = 4 * p.sub_C;
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int col = k0 + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                    if (ok && col < ncol) {
+                        const int ab = col / p.sub_C, c = col - ab * p.sub_C;
+                        const int hh = 2 * oh + (ab >> 1), ww = 2 * (int)q + (ab & 1);
+                        if (hh < p.sub_H && ww < p.sub_W)
+                            p.out[(((size_t)n * p.sub_C + c) * p.sub_H + hh) * p.sub_W + ww] =
+                                (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
+                    }
+                }
+            continue;
+        }
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             const int co_base = k0 + a * 32;

@@ -184,6 +184,42 @@ __global__ __launch_bounds__(256) void filter_to_blocked(const E *__restrict__ s
     dst[i] = v;
 }
 
+// Combined filter of a stride-2 backprop-data written as a stride-1 convolution over 2x2 output
+// blocks: wu[ut][k/16][col][k%16], col = (2a+b)*C + c (64 columns, the rest zero), union tap
+// ut = (dr - dr_min)*nds + (ds - ds_min); entry = w[k][c][r][s] with r = a + pad_h - 2 dr,
+// s = b + pad_w - 2 ds when that tap exists, else 0.
+__global__ __launch_bounds__(256) void subpixel_filter(const uint16_t *__restrict__ w, uint16_t *__restrict__ wu, int K,
+                                                       int C, int R, int S, int pbh, int pbw, int dr_min, int ds_min,
+                                                       int nds, size_t total)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    size_t t = i;
+    const int ki = t % 16; t /= 16;
+    const int col = t % 64; t /= 64;
+    const int KB = K >> 4;
+    const int kb = t % KB; t /= KB;
+    const int ut = (int)t;
+    const int dr = dr_min + ut / nds, ds = ds_min + ut % nds;
+    uint16_t v = 0;
+    if (col < 4 * C) {
+        const int ab = col / C, c = col - ab * C;
+        const int a = ab >> 1, b = ab & 1;
+        const int r = a + pbh - 2 * dr, s = b + pbw - 2 * ds;
+        if (r >= 0 && r < R && s >= 0 && s < S) v = w[(((size_t)(kb * 16 + ki) * C + c) * R + r) * S + s];
+    }
+    wu[i] = v;
+}
+
+hipError_t launch_subpixel_filter(int K, int C, int R, int S, int pbh, int pbw, int dr_min, int ndr, int ds_min, int nds,
+                                  const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st)
+{
+    const size_t total = (size_t)ndr * nds * K * 64;
+    NGC_LAUNCH(subpixel_filter, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w_kcrs, wu, K, C, R, S, pbh, pbw,
+               dr_min, ds_min, nds, total);
+    return hipGetLastError();
+}
+
 static bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,
