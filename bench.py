@@ -25,6 +25,14 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch (fetch + write) of the cfg2 kernels from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
+# (profiles/cfg2_strip_wgrad_strip.txt), each scaled by what the same counter reads for a plain 102.8 MB copy
+# launched in the same run (FETCH_SIZE reads 0.5004 of the bytes copied, WRITE_SIZE 1.000).
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_3x3_c64:fwd": int((14287.6 / 0.5004 + 25088.0) * 1024),
+    "cfg2_3x3_c64:bwd_data": int((14287.6 / 0.5004 + 25088.0) * 1024),
+    "cfg2_3x3_c64:bwd_filters": int(((25605.1 + 9230.5) / 0.5004 + 18432.0 + 576.0) * 1024),
+}
 
 
 def parse():
@@ -37,7 +45,7 @@ def parse():
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
-                         "cfg2 activation tensor: 25.7 MB read + 25.7 MB written) so that HBM counters can be scaled")
+                         "[64,256,56,56] bf16 tensor: 102.8 MB read + 102.8 MB written) so that HBM counters can be scaled")
     return ap.parse_args()
 
 
@@ -210,17 +218,21 @@ def main():
                             "bwd_filters": ng.ngc_conv_variant(b.d_wg, 2)}[op],
                 "count": b.L.count}
     if args.calibrate_copy:
-        b0 = benches[0]
-        src, dst = b0.sets[0]["x"], torch.empty_like(b0.sets[0]["x"])
-        L0 = b0.L
+        # 64 x 256 x 56 x 56 bf16 = 102.8 MB read + 102.8 MB written per launch: larger than the
+        # 8 x 4 MB of L2, so FETCH_SIZE sees (almost) every byte of the source
+        cn, cc, chh, cww = 64, 256, 56, 56
+        src = torch.zeros(cn * cc * chh * cww, dtype=torch.int16, device="cuda")
+        dst = torch.empty_like(src)
         for _ in range(10):
-            ng.ngc_layout_convert(ng.NGC_BF16, L0.n, L0.c, L0.h, L0.w, src, b0.xl, dst, b0.xl, b0.stream)
+            ng.ngc_layout_convert(ng.NGC_BF16, cn, cc, chh, cww, src, ng.NGC_NCHW, dst, ng.NGC_NCHW, benches[0].stream)
         torch.cuda.synchronize()
     dom_name = max(kern, key=lambda k: kern[k]["us"] * kern[k]["count"])
     dom = kern[dom_name]
     if cfg in (2,):
         roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": dom_name}
+                "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom_name), "traffic_unit": "bytes per launch (HBM fetch + write)",
+                "algorithmic_bytes": benches[0].algorithmic_bytes(dom_name.split(":")[1]), "kernel": dom_name}
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom_name}
