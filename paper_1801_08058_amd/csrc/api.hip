@@ -59,7 +59,7 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -353,6 +353,40 @@ bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, 
     return true;
 }
 
+// backprop-filters as a per-tap GEMM over positions (1x1 layers, strided multi-tap layers)
+bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
+{
+    const char *force = getenv("NGC_WGRAD_GEMM");
+    if (force && atoi(force) == 0) return false;
+    if (d->c % 64 != 0 || d->k % 64 != 0 || d->r * d->s > 64) return false;
+    const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * P * Q * 2;
+    if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
+    WgradGemmParams q;
+    memset(&q, 0, sizeof(q));
+    q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q; q.R = d->r; q.S = d->s;
+    q.sh = d->stride_h; q.sw = d->stride_w; q.dil_h = d->dil_h; q.dil_w = d->dil_w;
+    q.pbh = d->pad_below_h; q.pbw = d->pad_below_w;
+    q.wk = d->k % 128 == 0 ? 2 : 1;
+    q.wc = d->c % 128 == 0 ? 2 : 1;
+    q.ctiles = d->c / (64 * q.wc);
+    q.M = (uint32_t)d->n * P * Q;
+    const uint32_t tiles = (uint32_t)(d->k / (64 * q.wk)) * q.ctiles * d->r * d->s;
+    uint32_t parts = (NUM_CUS + tiles - 1) / tiles;
+    const uint32_t max_parts = (q.M + 127) / 128;
+    if (parts > max_parts) parts = max_parts;
+    if (parts < 1) parts = 1;
+    uint32_t chunk = (q.M + parts - 1) / parts;
+    chunk = (chunk + 127) / 128 * 128;
+    q.chunk = chunk;
+    q.nparts = (int)((q.M + chunk - 1) / chunk);
+    q.x_bytes = (uint32_t)x_bytes;
+    q.dy_bytes = (uint32_t)dy_bytes;
+    q.div_pq = make_fastdiv((uint32_t)(P * Q));
+    q.div_q = make_fastdiv((uint32_t)Q);
+    if (wp) *wp = q;
+    return true;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -382,6 +416,7 @@ Variant pick(const ngc_conv_desc *d, int op)
     if (op == NGC_OP_BWD_FILTERS) {
         if (wgrad_stem_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STEM;
         if (blocked_bf16(d) && wgrad_strip_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STRIP;
+        if (blocked_bf16(d) && wgrad_gemm_plan(d, P, Q, nullptr)) return V_WGRAD_GEMM;
         if (blocked_bf16(d) && d->c % 64 == 0 && d->k % 64 == 0 && d->r * d->s <= 65535) return V_WGRAD_64;
         return V_DIRECT;
     }
@@ -428,6 +463,11 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
         WgradStemParams wp;
         wgrad_stem_plan(d, P, Q, &wp, nullptr);
         return round256((size_t)d->n * wp.strips * (d->k / 64) * 2 * 4 * 6 * 64 * 16);
+    }
+    if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_GEMM) {
+        WgradGemmParams wp;
+        wgrad_gemm_plan(d, P, Q, &wp);
+        return round256((size_t)wp.nparts * d->r * d->s * d->k * d->c * sizeof(float));
     }
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STRIP) {
         WgradStripParams wp;
@@ -514,6 +554,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_STEM_FWD: return "stem_fwd_bf16";
     case V_WGRAD_STEM: return "wgrad_stem_bf16";
     case V_STEM_BWD: return "stem_bwd_strip_bf16";
+    case V_WGRAD_GEMM: return "wgrad_gemm_bf16";
     default: return "invalid";
     }
 }
@@ -703,6 +744,15 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);
     if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    if (v == V_WGRAD_GEMM) {
+        WgradGemmParams wp;
+        if (!wgrad_gemm_plan(desc, P, Q, &wp)) return NGC_UNSUPPORTED;
+        wp.x = static_cast<const uint16_t *>(x);
+        wp.dy = static_cast<const uint16_t *>(dy);
+        wp.partial = static_cast<float *>(ws);
+        wp.dw = dw;
+        return launch_status(launch_wgrad_gemm(wp, st));
+    }
     if (v == V_WGRAD_STEM) {
         WgradStemParams wp;
         size_t lds;

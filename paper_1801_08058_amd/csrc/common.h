@@ -214,11 +214,28 @@ struct WgradStemParams {
     FastDiv div_q;
 };
 
+// ---- backprop-filters as a GEMM over positions, one tap per workgroup ----
+struct WgradGemmParams {
+    const uint16_t *x;
+    const uint16_t *dy;
+    float *partial;            // [part][tap][tile][sub][kb][cq][lane][4]
+    float *dw;                 // [K][C][R][S]
+    int32_t N, C, H, W, K, P, Q, R, S;
+    int32_t sh, sw, dil_h, dil_w, pbh, pbw;
+    int32_t wk, wc;            // 64-wide sub-tiles of k and c per workgroup
+    int32_t ctiles;            // C / (64 wc)
+    int32_t nparts;
+    uint32_t M, chunk;         // N*P*Q, positions per part (multiple of 128)
+    uint32_t x_bytes, dy_bytes;
+    FastDiv div_pq, div_q;
+};
+
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st);
+hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, hipStream_t st);
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S,

@@ -1,0 +1,269 @@
+// ConvolutionBackpropFilters as a GEMM over positions, one filter tap per workgroup
+// (1x1 layers; strided 3x3 layers run it once per tap) on bf16 MFMA (gfx950).
+//
+//   dw[k,c,tap] = sum_{m=(n,p,q)} dy[m][k] * X[m @ tap][c]
+//
+// Workgroup = 8 waves, tile 64*WK (k) x 64*WC (c) of dw for one tap over a chunk of positions.
+// Wave (wk, wc, h) owns a 64 x 64 sub-tile as 4x4 MFMA 16x16 tiles (64 accumulator registers)
+// and every NH-th 32-position step (NH = 8 / (WK*WC) interleaved step streams = a wave-level
+// split of the reduction, summed through LDS in a fixed tree at the end).
+// A stage = 128 positions: dy [128][64 WK] and x [128][64 WC] go to LDS in their natural
+// channel-contiguous form with direct global->LDS loads (out-of-range lanes deliver zeros =
+// padding and the tail of the chunk); MFMA operands (8 consecutive positions per lane) are
+// fetched with the LDS transpose load ds_read_b64_tr_b16.  Two stages, one barrier per stage.
+// Partials go to the workspace in register order; wgrad_gemm_reduce adds the parts in index
+// order (deterministic) and writes dw as [K][C][R][S].
+#include "common.h"
+
+namespace ngc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void lds_void_g;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4_g;
+
+constexpr unsigned WGG_OOB = 0x80000000u;
+constexpr int WGG_SP = 128;                       // positions per stage
+constexpr int WGG_PLANE = WGG_SP * 32 + 128;      // bytes per 16-channel plane of a stage
+
+__device__ __forceinline__ bf16x8 tr_frag_g(const unsigned char *lo)
+{
+    // two 4x16 transposed blocks (positions +0..3 and +4..7) -> this lane's 8 reduction elements
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)lo);
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)(lo + 128));
+    const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int WK, int WC>
+__global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
+{
+    constexpr int NW = 8;
+    constexpr int NH = NW / (WK * WC);
+    constexpr int NPL = 4 * (WK + WC);            // 16-channel planes per stage: dy first, then x
+    constexpr int STAGE = NPL * WGG_PLANE;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wk = wave % WK;
+    const int wc = (wave / WK) % WC;
+    const int wh = wave / (WK * WC);
+    const int L = lane & 15;
+    const int grp = lane >> 4;
+
+    const int part = blockIdx.x;
+    const int kt = blockIdx.y / p.ctiles;
+    const int ct = blockIdx.y - kt * p.ctiles;
+    const int tap = blockIdx.z;
+    const int tr = tap / p.S, ts = tap - tr * p.S;
+    const int dh_off = tr * p.dil_h - p.pbh;
+    const int dw_off = ts * p.dil_w - p.pbw;
+
+    const uint32_t m_begin = (uint32_t)part * p.chunk;
+    const uint32_t m_end = (m_begin + p.chunk < p.M) ? m_begin + p.chunk : p.M;
+    const int nstages = (m_begin < m_end) ? (int)((m_end - m_begin + WGG_SP - 1) / WGG_SP) : 0;
+
+    const int PQ = p.P * p.Q;
+    const int HW = p.H * p.W;
+    const int KB = p.K >> 4, CB = p.C >> 4;
+    const int kb0 = kt * 4 * WK, cb0 = ct * 4 * WC;
+
+    __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
+
+    // load items of a stage: item = plane * 4 + block (32 positions); wave w takes items w, w+8, ...
+    // -> always block w % 4, so one position decode per stage and lane
+    const int my_blk = wave & 3;
+    auto issue_loads = [&](int s, int buf) {
+        unsigned char *base = smem + buf * STAGE;
+        const uint32_t m = m_begin + (uint32_t)(s * WGG_SP + my_blk * 32 + (lane >> 1));
+        const bool in = m < m_end;
+        const uint32_t mm = in ? m : 0;
+        const uint32_t n = fd_div(mm, p.div_pq);
+        const uint32_t rem = mm - n * p.div_pq.d;
+        const uint32_t pp = fd_div(rem, p.div_q);
+        const uint32_t qq = rem - pp * p.div_q.d;
+        const int h = (int)pp * p.sh + dh_off;
+        const int w = (int)qq * p.sw + dw_off;
+        const bool xin = in && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
+        const unsigned half = (lane & 1) * 16;
+        const unsigned dy_off = (unsigned)(((n * KB + kb0) * PQ + rem) * 32) + half;
+        const unsigned x_off = (unsigned)(((n * CB + cb0) * HW + h * p.W + w) * 32) + half;
+#pragma unroll
+        for (int j = 0; j < NPL / 2; ++j) {
+            const int pl = (wave >> 2) + 2 * j;                          // plane index of item wave + 8 j
+            unsigned char *dst = base + pl * WGG_PLANE + my_blk * 1024;
+            if (pl < 4 * WK) {
+                const unsigned off = in ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
+            } else {
+                const unsigned off = xin ? x_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
+            }
+        }
+    };
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+
+    // this lane's byte offset inside a plane for step j: positions 32 j + 8 grp + L/4 (+4), column group L%4
+    const int lane_off = (grp * 8 + (L >> 2)) * 32 + (L & 3) * 8;
+
+    if (nstages > 0) issue_loads(0, 0);
+    for (int s = 0; s < nstages; ++s) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's loads of stage s have landed
+        __syncthreads();
+        if (s + 1 < nstages) issue_loads(s + 1, (s + 1) & 1);
+        const unsigned char *dys = smem + (s & 1) * STAGE + (4 * wk) * WGG_PLANE + lane_off;
+        const unsigned char *xs = smem + (s & 1) * STAGE + (4 * WK + 4 * wc) * WGG_PLANE + lane_off;
+        auto fetch = [&](int j, bf16x8 (&a)[4], bf16x8 (&b)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = tr_frag_g(dys + i * WGG_PLANE + j * 1024);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b[i] = tr_frag_g(xs + i * WGG_PLANE + j * 1024);
+        };
+        auto multiply = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    acc[i][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[k], acc[i][k], 0, 0, 0);
+        };
+        // step streams continue across stages (4 steps per stage)
+        int j = (wh - (s * 4) % NH + NH) % NH;
+        if (NH <= 2) {
+            // two steps of this stage belong to the wave: fetch the second while multiplying the first
+            bf16x8 a0[4], b0[4], a1[4], b1[4];
+            fetch(j, a0, b0);
+            fetch(j + NH, a1, b1);
+            multiply(a0, b0);
+            if (NH == 1) {
+                fetch(j + 2, a0, b0);
+                multiply(a1, b1);
+                fetch(j + 3, a1, b1);
+                multiply(a0, b0);
+                multiply(a1, b1);
+            } else {
+                multiply(a1, b1);
+            }
+        } else if (j < 4) {
+            bf16x8 a0[4], b0[4];
+            fetch(j, a0, b0);
+            multiply(a0, b0);
+        }
+    }
+    __syncthreads();
+
+    // ---- fixed-order tree over the NH step streams, then the partial in register order
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+    const int sub = wk * WC + wc;
+#pragma unroll
+    for (int stride = NH / 2; stride >= 1; stride >>= 1) {
+        if (wh >= stride && wh < 2 * stride) {
+            f32x4 *dst = red + ((wh - stride) * (WK * WC) + sub) * (16 * 64);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) dst[(a * 4 + b) * 64 + lane] = acc[a][b];
+        }
+        __syncthreads();
+        if (wh < stride) {
+            const f32x4 *src = red + (wh * (WK * WC) + sub) * (16 * 64);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] += src[(a * 4 + b) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wh == 0) {
+        // partial[part][tap][tile][sub][kb][cq][lane] (float4 per lane)
+        const size_t tile = (size_t)blockIdx.y;
+        f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
+                     ((((size_t)part * gridDim.z + tap) * gridDim.y + tile) * (WK * WC) + sub) * (16 * 64);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) out[(a * 4 + b) * 64 + lane] = acc[a][b];
+    }
+}
+
+// dw[k][c][tap] = sum over parts (index order).  Element i (float4) of a part:
+// i = ((((tap * tiles + tile) * WK*WC + sub) * 4 + kb) * 4 + cq) * 64 + lane.
+__global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
+                                                        int nparts, int K, int C, int RS, int ctiles, int WK, int WC)
+{
+    __shared__ f32x4 sm[8][32];
+    const size_t per4 = (size_t)RS * K * C / 4;
+    const int o = threadIdx.x & 31;
+    const int sl = threadIdx.x >> 5;
+    const size_t i = (size_t)blockIdx.x * 32 + o;
+    f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
+    int sp = sl;
+    for (; sp + 8 < nparts; sp += 16) {
+        t0 += partial[(size_t)sp * per4 + i];
+        t1 += partial[(size_t)(sp + 8) * per4 + i];
+    }
+    if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
+    sm[sl][o] = t0 + t1;
+    __syncthreads();
+    if (sl == 0) {
+        const f32x4 r = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+        const int lane = (int)(i & 63);
+        size_t u = i >> 6;
+        const int cq = (int)(u & 3); u >>= 2;
+        const int kb = (int)(u & 3); u >>= 2;
+        const int sub = (int)(u % (WK * WC)); u /= (WK * WC);
+        const int tiles = (K / (64 * WK)) * ctiles;
+        const int tile = (int)(u % tiles);
+        const int tap = (int)(u / tiles);
+        const int kt = tile / ctiles, ct = tile - kt * ctiles;
+        const int wk = sub / WC, wc = sub - wk * WC;
+        const int k = (kt * WK + wk) * 64 + kb * 16 + 4 * (lane >> 4);
+        const int c = (ct * WC + wc) * 64 + cq * 16 + (lane & 15);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dw[((size_t)(k + v) * C + c) * RS + tap] = r[v];
+    }
+}
+
+template <int WK, int WC>
+static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    size_t lds = (size_t)2 * 4 * (WK + WC) * WGG_PLANE;
+    if (lds < 65536) lds = 65536;                                       // final cross-wave tree
+    dim3 grid(p.nparts, (p.K / (64 * WK)) * p.ctiles, p.R * p.S);
+    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC>), grid, dim3(512), lds, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
+{
+    hipError_t e = hipErrorInvalidValue;
+    if (p.wk == 2 && p.wc == 2) e = launch_wgrad_gemm_t<2, 2>(p, st);
+    else if (p.wk == 2 && p.wc == 1) e = launch_wgrad_gemm_t<2, 1>(p, st);
+    else if (p.wk == 1 && p.wc == 2) e = launch_wgrad_gemm_t<1, 2>(p, st);
+    else if (p.wk == 1 && p.wc == 1) e = launch_wgrad_gemm_t<1, 1>(p, st);
+    if (e != hipSuccess) return e;
+    const size_t per4 = (size_t)p.R * p.S * p.K * p.C / 4;
+    NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.R * p.S, p.ctiles, p.wk, p.wc);
+    return hipGetLastError();
+}
+
+}  // namespace ngc

@@ -195,6 +195,7 @@ def test_mfma_kernels_small(case, pre, nf, strip_nf):
 def test_wgrad_per_tap_kernel_still_matches(case, monkeypatch):
     """3x3 stride-1 shapes through the per-tap split kernel (the all-taps kernel switched off)."""
     monkeypatch.setenv("NGC_WGRAD_STRIP", "0")
+    monkeypatch.setenv("NGC_WGRAD_GEMM", "0")
     a = MFMA_CASES[case]
     if a.c % 64 or a.k % 64:
         pytest.skip("per-tap MFMA kernel needs C, K multiples of 64")
@@ -214,6 +215,18 @@ def test_wgrad_all_taps_channel_group_variants(case, ncq, monkeypatch):
     run = Run(a, "bf16", BLK, BLK, True)
     dw = run.bwd_filters(x, dy)
     assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_strip_bf16"
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
+
+
+@pytest.mark.parametrize("case", [0, 2, 3, 4, 5, 6, 8, 13])
+def test_wgrad_gemm_kernel(case, monkeypatch):
+    """Per-tap GEMM backprop-filters (the all-taps kernel switched off so that 3x3 shapes reach it too)."""
+    monkeypatch.setenv("NGC_WGRAD_STRIP", "0")
+    a = MFMA_CASES[case]
+    x, w, b, dy = _tensors(a, "bf16", 6000 + case)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
     assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
 
 
