@@ -59,7 +59,7 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1 };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -387,6 +387,52 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     return true;
 }
 
+// One-tap GEMM kernel for forward (op 0) or backprop-data (op 1) of a 1x1 convolution, any stride.
+// Backprop-data with stride > 1 computes the one residue class of pixels the tap reaches; `zero`
+// reports that the rest of dx has to be cleared first.
+bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *gp, bool *zero)
+{
+    const char *sw = getenv("NGC_GEMM1X1");              // tests / benchmarks only: 0 disables this kernel
+    if (sw && atoi(sw) == 0) return false;
+    if (d->r != 1 || d->s != 1) return false;
+    const bool fwd = op == NGC_OP_FWD;
+    const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
+    if (Cin % 64 != 0 || Cout % 64 != 0) return false;
+    Gemm1x1Params q;
+    memset(&q, 0, sizeof(q));
+    q.Cin = Cin; q.Cout = Cout;
+    int OP, OQ;
+    bool z = false;
+    if (fwd) {
+        q.Hin = d->h; q.Win = d->w; q.Hout = P; q.Wout = Q;
+        q.is_h = d->stride_h; q.is_w = d->stride_w;
+        q.dh = -d->pad_below_h; q.dw = -d->pad_below_w;
+        q.os_h = q.os_w = 1; q.oa_h = q.oa_w = 0;
+        OP = P; OQ = Q;
+    } else {
+        const int sh = d->stride_h, sw_ = d->stride_w;
+        const int a = (sh - d->pad_below_h % sh) % sh, b = (sw_ - d->pad_below_w % sw_) % sw_;
+        q.Hin = P; q.Win = Q; q.Hout = d->h; q.Wout = d->w;
+        q.is_h = q.is_w = 1;
+        q.dh = (a + d->pad_below_h) / sh; q.dw = (b + d->pad_below_w) / sw_;      // exact
+        q.os_h = sh; q.os_w = sw_; q.oa_h = a; q.oa_w = b;
+        OP = a < d->h ? (d->h - a + sh - 1) / sh : 0;
+        OQ = b < d->w ? (d->w - b + sw_ - 1) / sw_ : 0;
+        z = sh > 1 || sw_ > 1;
+    }
+    const size_t in_bytes = (size_t)d->n * Cin * q.Hin * q.Win * 2, wt_bytes = (size_t)Cin * Cout * 2;
+    const size_t m = (size_t)d->n * OP * OQ;
+    if (in_bytes >= 0x80000000ull || wt_bytes >= 0x80000000ull || m >= 0x7fff0000ull) return false;
+    q.M = (uint32_t)m;
+    q.in_bytes = (uint32_t)in_bytes;
+    q.wt_bytes = (uint32_t)wt_bytes;
+    q.div_pq = make_fastdiv((uint32_t)(OP * OQ > 0 ? OP * OQ : 1));
+    q.div_q = make_fastdiv((uint32_t)(OQ > 0 ? OQ : 1));
+    if (gp) *gp = q;
+    if (zero) *zero = z;
+    return true;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -401,6 +447,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
         const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
         if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
+        if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
@@ -410,6 +457,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
                         d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
         if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
+        if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
@@ -450,9 +498,9 @@ void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *spl
 
 size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
-    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
+    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
-    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP))
+    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && v == V_STEM_BWD) {
         StemBwdPlan pl;
@@ -555,6 +603,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_WGRAD_STEM: return "wgrad_stem_bf16";
     case V_STEM_BWD: return "stem_bwd_strip_bf16";
     case V_WGRAD_GEMM: return "wgrad_gemm_bf16";
+    case V_GEMM1X1: return "gemm1x1_bf16";
     default: return "invalid";
     }
 }
@@ -617,6 +666,16 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
         sp.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
         sp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
         return launch_status(launch_strip(sp, nf, lds, st));
+    }
+    if (v == V_GEMM1X1) {
+        Gemm1x1Params gp;
+        if (!gemm1x1_plan(desc, NGC_OP_FWD, P, Q, &gp, nullptr)) return NGC_UNSUPPORTED;
+        gp.in = static_cast<const uint16_t *>(x);
+        gp.wt = static_cast<const uint16_t *>(wt);
+        gp.out = static_cast<uint16_t *>(y);
+        gp.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+        gp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+        return launch_status(launch_gemm1x1(gp, st));
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));
@@ -689,6 +748,20 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         sp.bias = nullptr;
         sp.relu = 0;
         return launch_status(launch_strip(sp, nf, lds, st));
+    }
+    if (v == V_GEMM1X1) {
+        Gemm1x1Params gp;
+        bool zero;
+        if (!gemm1x1_plan(desc, NGC_OP_BWD_DATA, P, Q, &gp, &zero)) return NGC_UNSUPPORTED;
+        if (zero) {
+            const hipError_t e = launch_zero_fill(dx, (size_t)desc->n * desc->c * desc->h * desc->w * 2, st);
+            if (e != hipSuccess) return launch_status(e);
+        }
+        if (gp.M == 0) return NGC_OK;
+        gp.in = static_cast<const uint16_t *>(dy);
+        gp.wt = static_cast<const uint16_t *>(wt);
+        gp.out = static_cast<uint16_t *>(dx);
+        return launch_status(launch_gemm1x1(gp, st));
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));

@@ -230,7 +230,24 @@ struct WgradGemmParams {
     FastDiv div_pq, div_q;
 };
 
+// ---- one-tap (1x1) forward / backprop-data as a pipelined GEMM ----
+struct Gemm1x1Params {
+    const uint16_t *in;
+    const uint16_t *wt;        // [Cin/16][Cout][16]
+    uint16_t *out;
+    const float *bias;         // may be null
+    int32_t Cin, Hin, Win, Cout, Hout, Wout;
+    int32_t is_h, is_w, dh, dw;        // input pixel of lattice position (i,j): (i*is_h + dh, j*is_w + dw)
+    int32_t os_h, os_w, oa_h, oa_w;    // output pixel: (i*os_h + oa_h, j*os_w + oa_w)
+    int32_t relu;
+    uint32_t M;                // N * OP * OQ lattice positions
+    uint32_t in_bytes, wt_bytes;
+    FastDiv div_pq, div_q;
+};
+
 // launchers (each returns hipGetLastError() after the launch)
+hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st);
+hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);

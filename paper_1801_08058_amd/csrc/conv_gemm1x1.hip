@@ -1,0 +1,227 @@
+// 1x1 convolution (forward and backprop-data) as a pipelined GEMM on bf16 MFMA (gfx950).
+//
+//   out[pos][co] = sum_ci in[pos'][ci] * wt[ci/16][co][ci%16]        (one tap, any stride)
+//
+// Workgroup = 8 waves, tile BM = 64*WM positions x BN = 64*WN output channels (WM*WN = 8), wave
+// tile 64 x 64 = 2x2 v_mfma_f32_32x32x16_bf16 (A = filters, B = activations, as in the other
+// forward kernels).  The reduction runs over 64-input-channel stages through an NS-deep LDS ring
+// filled by direct global->LDS loads (buffer_load_dwordx4 ... lds); every wave issues the same
+// number of loads per stage, so "stage s has landed" is a counted s_waitcnt vmcnt(N) and the
+// loads of the next NS-1 stages stay in flight during the MFMAs of stage s.  One barrier per stage.
+// LDS planes of 16-byte units (8 channels of one row) as in the strip kernel: conflict-free
+// ds_read_b128 operand fetches.
+//
+// Workgroups that share an activation tile (different output-channel tiles) are given ids that
+// land on the same XCD (id % 8), so the tile is fetched into one L2 only.
+#include "common.h"
+
+namespace ngc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void_q;
+
+constexpr unsigned G1_OOB = 0x80000000u;
+
+template <int WM, int WN, int NS>
+__global__ __launch_bounds__(512) void conv_gemm1x1_bf16(const Gemm1x1Params p)
+{
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int XPLANE = BM * 16 + 128, WPLANE = BN * 16 + 128;
+    constexpr int STAGE = 8 * XPLANE + 8 * WPLANE;
+    constexpr int LPW = WM + WN;                      // loads per wave per stage: (8 WM + 8 WN) items / 8 waves
+    static_assert(WM * WN == 8, "8 waves");
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM;
+    const int wn = wave / WM;
+    const int l32 = lane & 31;
+    const int lg = lane >> 5;
+
+    // XCD-aware tile order: id = xcd + 8 * (mgroup * NT + ntile), m-tile = mgroup * 8 + xcd
+    const int NT = p.Cout / BN;
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int ntile = slot % NT;
+    const int mtile = (slot / NT) * 8 + xcd;
+    const uint32_t m0 = (uint32_t)mtile * BM;
+    if (m0 >= p.M) return;                             // uniform per workgroup
+    const int n0 = ntile * BN;
+
+    const int CBin = p.Cin >> 4;
+    const int HWin = p.Hin * p.Win;
+
+    __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
+
+    // ---- loader roles.  X items: plane * WM + block (64 rows); W items: plane * WN + block.
+    // Wave w takes X items w + 8 j (j < WM): block = w % WM, plane = w / WM + (8 / WM) * j
+    //             W items w + 8 j (j < WN): block = w % WN, plane = w / WN + (8 / WN) * j
+    unsigned xvoff;
+    {
+        const uint32_t m = m0 + (uint32_t)((wave % WM) * 64 + lane);
+        xvoff = G1_OOB;
+        if (m < p.M) {
+            const uint32_t n = fd_div(m, p.div_pq);
+            const uint32_t rem = m - n * p.div_pq.d;
+            const uint32_t i = fd_div(rem, p.div_q);
+            const uint32_t j = rem - i * p.div_q.d;
+            const int ih = (int)i * p.is_h + p.dh;
+            const int iw = (int)j * p.is_w + p.dw;
+            if ((unsigned)ih < (unsigned)p.Hin && (unsigned)iw < (unsigned)p.Win)
+                xvoff = (unsigned)(((int)n * CBin * HWin + ih * p.Win + iw) * 32);
+        }
+    }
+    const unsigned wvoff = (unsigned)((n0 + (wave % WN) * 64 + lane) * 32);
+
+    auto issue_loads = [&](int s, int buf) {
+        unsigned char *xs = smem + buf * STAGE;
+        unsigned char *ws = xs + 8 * XPLANE;
+#pragma unroll
+        for (int j = 0; j < WM; ++j) {
+            const int pl = wave / WM + (8 / WM) * j;                     // plane = cbi * 2 + g
+            const unsigned soff = (unsigned)((s * 4 + (pl >> 1)) * HWin * 32);
+            const unsigned v = (xvoff == G1_OOB) ? G1_OOB : xvoff + (pl & 1) * 16;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + pl * XPLANE + (wave % WM) * 1024), 16, (int)v,
+                                                     (int)soff, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int pl = wave / WN + (8 / WN) * j;
+            const unsigned soff = (unsigned)((s * 4 + (pl >> 1)) * p.Cout * 32 + (pl & 1) * 16);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void_q *)(ws + pl * WPLANE + (wave % WN) * 1024), 16,
+                                                     (int)wvoff, (int)soff, 0, 0);
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int nsteps = p.Cin >> 6;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nsteps) issue_loads(s, s);
+
+    for (int s = 0; s < nsteps; ++s) {
+        // stage s has landed when at most the loads of the NS-2 later stages are outstanding
+        static_assert(NS == 2 || NS == 3, "ring depth");
+        if (NS == 3 && s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F70 | LPW);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (s + NS - 1 < nsteps) issue_loads(s + NS - 1, (s + NS - 1) % NS);
+
+        const unsigned char *xs = smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;
+        const unsigned char *ws = smem + (s % NS) * STAGE + 8 * XPLANE + lg * WPLANE + (wn * 64 + l32) * 16;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(ws + (2 * ks) * WPLANE + a * 512);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(xs + (2 * ks) * XPLANE + b * 512);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: bias, ReLU, one RNE rounding, lane-pair exchange, 16-byte stores
+    const int CBout = p.Cout >> 4;
+    const int HWout = p.Hout * p.Wout;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const uint32_t m = m0 + (uint32_t)(wm * 64 + b * 32 + l32);
+        const bool ok = m < p.M;
+        const uint32_t mm = ok ? m : 0;
+        const uint32_t n = fd_div(mm, p.div_pq);
+        const uint32_t rem = mm - n * p.div_pq.d;
+        const uint32_t i = fd_div(rem, p.div_q);
+        const uint32_t j = rem - i * p.div_q.d;
+        const int oh = (int)i * p.os_h + p.oa_h;
+        const int ow = (int)j * p.os_w + p.oa_w;
+        const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + ow;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const int co_base = n0 + wn * 64 + a * 32;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = acc[a][b][8 * h + e];
+                if (p.bias) {
+                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 4 * lg);
+                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 8 + 4 * lg);
+                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+                }
+                if (p.relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
+                const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
+                const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
+                const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
+                const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
+                const uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
+                if (ok) {
+                    const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                }
+            }
+        }
+    }
+}
+
+// 16-byte zero fill (pixels of a strided backprop-data that no tap reaches)
+__global__ __launch_bounds__(256) void zero_fill16(uint4 *__restrict__ dst, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;                     // blocked tensors are multiples of 32 bytes
+    unsigned blocks = (unsigned)((n16 + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    NGC_LAUNCH(zero_fill16, dim3(blocks), dim3(256), 0, st, static_cast<uint4 *>(dst), n16);
+    return hipGetLastError();
+}
+
+template <int WM, int WN, int NS>
+static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr size_t lds = (size_t)NS * (8 * (BM * 16 + 128) + 8 * (BN * 16 + 128));
+    const unsigned mtiles = (p.M + BM - 1) / BM;
+    const unsigned grid = ((mtiles + 7) / 8) * 8 * (p.Cout / BN);
+    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS>), dim3(grid), dim3(512), lds, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
+{
+    if (p.Cout % 128 == 0) return launch_gemm1x1_t<4, 2, 3>(p, st);
+    return launch_gemm1x1_t<8, 1, 2>(p, st);
+}
+
+}  // namespace ngc

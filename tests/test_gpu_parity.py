@@ -183,9 +183,10 @@ def test_mfma_kernels_small(case, pre, nf, strip_nf):
         pytest.skip("strip kernel covers stride-1 multi-tap shapes; one filter-layout mode is enough for forced sizes")
     strip_nf(nf)
     strip_ok = (a.sh, a.sw) == (1, 1) and a.r * a.s > 1 and nf != 0
-    fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 64 == 0) else \
+    one_tap = a.r * a.s == 1 and a.c % 64 == 0 and a.k % 64 == 0
+    fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 64 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.c % 32 == 0 and a.k % 64 == 0) else "direct"
-    bwd_v = "strip" if (strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else \
+    bwd_v = "strip" if (strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.k % 32 == 0 and a.c % 64 == 0) else "direct"
     wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
     _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
@@ -228,6 +229,34 @@ def test_wgrad_gemm_kernel(case, monkeypatch):
     dw = run.bwd_filters(x, dy)
     assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
     assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
+
+
+GEMM1X1_CASES = [
+    # n  c    h   w   k    r  s  sh sw dh dw pbh pbw pah paw
+    Attrs(3, 64, 13, 13, 128, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),     # one 64-channel stage, ragged position tail
+    Attrs(2, 192, 17, 9, 256, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),     # 3 stages = ring depth
+    Attrs(2, 320, 12, 12, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),     # 5 stages; 64 outputs fwd (512x64 tile), 320 bwd
+    Attrs(5, 128, 15, 14, 256, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),    # stride-2 projection, odd height
+    Attrs(2, 64, 11, 12, 128, 1, 1, 2, 3, 1, 1, 1, 2, 1, 0),     # mixed strides with padding (tap class offset != 0)
+    Attrs(1, 64, 9, 9, 64, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1),        # padded 1x1: border outputs see no input
+    Attrs(40, 128, 14, 14, 128, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),   # 7840 positions: all 8 XCD slots, several m groups
+    Attrs(2, 64, 3, 3, 64, 1, 1, 4, 4, 1, 1, 0, 0, 0, 0),        # stride larger than the image: single output pixel
+]
+
+
+@pytest.mark.parametrize("case", range(len(GEMM1X1_CASES)))
+@pytest.mark.parametrize("pre", [True, False])
+def test_gemm1x1_kernel(case, pre):
+    a = GEMM1X1_CASES[case]
+    _check_all(a, "bf16", BLK, BLK, pre, 7000 + case, ("gemm1x1", "gemm1x1", "wgrad"))
+
+
+@pytest.mark.parametrize("case", [0, 3, 4, 5])
+def test_one_tap_gather_kernel_still_matches(case, monkeypatch):
+    """1x1 shapes through the gather implicit-GEMM kernel (the pipelined GEMM switched off)."""
+    monkeypatch.setenv("NGC_GEMM1X1", "0")
+    a = GEMM1X1_CASES[case]
+    _check_all(a, "bf16", BLK, BLK, True, 7100 + case, ("igemm", "igemm", "wgrad"))
 
 
 def test_run_to_run_identical():
