@@ -252,7 +252,11 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     q.ncq = tiles64 <= 4 ? 2 : 4;
     const char *fq = getenv("NGC_WGRAD_NCQ");
     if (fq && (atoi(fq) == 1 || atoi(fq) == 2 || atoi(fq) == 4)) q.ncq = atoi(fq);
-    size_t lds = (size_t)2 * (4 * q.dyplane + q.ncq * q.xplane);
+    const size_t stage = (size_t)4 * q.dyplane + (size_t)q.ncq * q.xplane;
+    q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
+    const char *fr = getenv("NGC_WGRAD_RING");                          // tests / benchmarks only
+    if (fr && atoi(fr) == 2) q.nring = 2;
+    size_t lds = q.nring * stage;
     const size_t red = (size_t)4 * 144 * 64 * sizeof(float);           // final cross-wave sum
     if (lds < red) lds = red;
     if (lds > LDS_LIMIT) return false;

@@ -181,6 +181,7 @@ struct WgradStripParams {
     int32_t tap_off[9];        // patch-pixel offset of the tap
     int32_t dyplane, xplane;   // bytes per 16-channel plane of a stage
     int32_t ncq;               // 16-channel groups of c per workgroup (4, 2 or 1)
+    int32_t nring;             // LDS stage buffers (2 or 3)
     int32_t ctiles;            // C / (16 * ncq)
     uint32_t x_bytes, dy_bytes;
     FastDiv div_q, div_pc;
@@ -244,6 +245,19 @@ struct Gemm1x1Params {
     uint32_t in_bytes, wt_bytes;
     FastDiv div_pq, div_q;
 };
+
+// Workgroup barrier without the memory fence of __syncthreads().  The fence waits for every
+// outstanding global->LDS load of the wave (s_waitcnt vmcnt(0)), which would serialise a
+// multi-stage prefetch ring.  Callers order their LDS traffic themselves: s_waitcnt vmcnt(n) for
+// the stage they are about to read before the barrier (and lgkmcnt(0) if they have LDS writes
+// pending); LDS reads of a buffer have returned to registers before the wave reaches the barrier
+// after which that buffer is refilled.
+__device__ __forceinline__ void wg_barrier_nofence()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
 
 // launchers (each returns hipGetLastError() after the launch)
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st);

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(512) void conv_gemm1x1_bf16(const Gemm1x1Params p)
         static_assert(NS == 2 || NS == 3, "ring depth");
         if (NS == 3 && s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F70 | LPW);
         else __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+        wg_barrier_nofence();
         if (s + NS - 1 < nsteps) issue_loads(s + NS - 1, (s + NS - 1) % NS);
 
         const unsigned char *xs = smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;

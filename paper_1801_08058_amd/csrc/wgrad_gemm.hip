@@ -30,9 +30,9 @@ constexpr int WGG_PLANE = WGG_SP * 32 + 128;      // bytes per 16-channel plane 
 
 __device__ __forceinline__ bf16x8 tr_frag_g(const unsigned char *lo)
 {
-    // two 4x16 transposed blocks (positions +0..3 and +4..7) -> this lane's 8 reduction elements
+    // two 4x16 transposed blocks (positions +0..3 and +16..19) -> this lane's 8 reduction elements
     const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)lo);
-    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)(lo + 128));
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)(lo + 512));
     const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
 }
@@ -115,8 +115,9 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
-    // this lane's byte offset inside a plane for step j: positions 32 j + 8 grp + L/4 (+4), column group L%4
-    const int lane_off = (grp * 8 + (L >> 2)) * 32 + (L & 3) * 8;
+    // this lane's byte offset inside a plane for step j: positions 32 j + 4 grp + L/4 (+16), column group
+    // L%4; the 64 lanes of one load cover 512 contiguous bytes (no bank conflicts)
+    const int lane_off = (grp * 4 + (L >> 2)) * 32 + (L & 3) * 8;
 
     if (nstages > 0) issue_loads(0, 0);
     for (int s = 0; s < nstages; ++s) {

@@ -11,7 +11,8 @@
 // latency hides behind the other's MFMAs.  dy and x are read from HBM/L2 once per workgroup
 // instead of once per tap.
 //
-// The strip is processed in stages of SR rows.  A stage brings into LDS, with direct
+// The strip is processed in stages of SR rows through a ring of 2 or 3 LDS buffers (3 when they
+// fit: one stage of MFMAs is shorter than the latency of a load).  A stage brings into LDS, with direct
 // global->LDS loads (16 bytes per lane; out-of-range lanes deliver zeros, which is the padding
 // halo and the tail of the strip):
 //     dy tile : [positions][64 k]   as 4 planes of [position][16 k]  (32-byte rows)
@@ -19,8 +20,10 @@
 // i.e. both in their natural channel-contiguous form.  The MFMA needs the reduction axis
 // (positions) contiguous per lane; the LDS transpose load ds_read_b64_tr_b16 does exactly that:
 // 16 lanes read a 4(position) x 16(channel) block and each lane receives one channel's 4
-// positions.  Two such loads give a lane its 8 reduction elements of v_mfma_f32_16x16x32_bf16
-// (lane group l/16 = positions +8*(l/16)).  Because rows of the transposed block are whole
+// positions.  Two such loads give a lane its 8 reduction elements of v_mfma_f32_16x16x32_bf16.
+// Which 8 of the step's 32 positions a lane group holds is free as long as both operands agree:
+// group g takes positions 4g..4g+3 and 16+4g..16+4g+3, so that the 64 lanes of one load cover
+// 512 contiguous bytes (lane groups 256 bytes apart would hit the same banks).  Because rows of the transposed block are whole
 // 32-byte pixels, a filter tap is just a pixel offset in the address (no alignment problem, no
 // shifted copies).
 //
@@ -30,6 +33,8 @@
 // The per-workgroup partial (in register order) goes to the workspace; wgrad_strip_reduce adds the
 // workgroups in index order (deterministic) and writes dw as [K][C][R][S].
 #include "common.h"
+
+#include <type_traits>
 
 namespace ngc {
 
@@ -52,6 +57,30 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigne
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n; waiting for fewer outstanding loads than
+// necessary is always correct, so counts beyond the table fall back to vmcnt(0).
+__device__ __forceinline__ void wait_vmcnt(int n)
+{
+    switch (n) {
+    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
+    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
+    case 15: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    }
+}
+
 // NCQ = 16-channel groups of c per workgroup (4, 2 or 1); the 8 waves are NCQ channel groups x
 // NH = 8/NCQ interleaved step streams.  Fewer channels per workgroup means fewer, longer position
 // chunks for the same number of workgroups, i.e. fewer partial copies of dw to write and re-read.
@@ -68,7 +97,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     const int cq = wave % NCQ;               // 16-channel group inside the workgroup's c tile
     const int wh = wave / NCQ;               // which of the NH step streams
     const int L = lane & 15;                 // lane inside its 16-lane transpose group
-    const int grp = lane >> 4;               // reduction group: positions +8*grp
+    const int grp = lane >> 4;               // reduction group: positions 4*grp.. and 16+4*grp..
 
     const int igrp = blockIdx.x / p.strips;            // group of NI images
     const int strip = blockIdx.x - igrp * p.strips;
@@ -146,7 +175,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     auto step_offsets = [&](int step, int (&dyoff)[2], int (&xoff)[2]) {
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            int pos = step * 32 + grp * 8 + e * 4 + (L >> 2);
+            int pos = step * 32 + e * 16 + grp * 4 + (L >> 2);
             dyoff[e] = pos * 32 + lane_col;
             if (pos > last_pos) pos = last_pos;                          // dy is zero there; keep x in range
             const uint32_t row = fd_div((uint32_t)pos, p.div_q);
@@ -155,17 +184,24 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         }
     };
 
+    // Ring of p.nring (2 or 3) stage buffers.  Every stage costs this wave the same number of
+    // loads (lpw), so "stage s has landed" is vmcnt <= lpw * (stages issued after s).
     const int total_stages = nimg * p.nstages;
-    issue_loads(0, 0);
+    const int lpw = (items - wave + NW - 1) / NW;
+    const int ahead = p.nring - 1;
+    for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s, s);
+    int buf = 0;                                            // s % nring
     for (int s = 0; s < total_stages; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's loads of stage s have landed
-        __syncthreads();
-        if (s + 1 < total_stages) issue_loads(s + 1, (s + 1) & 1);
+        const int later = (total_stages - 1 - s < ahead - 1) ? total_stages - 1 - s : ahead - 1;
+        wait_vmcnt(later * lpw);
+        wg_barrier_nofence();                                 // stage s complete for everybody; buffer of s-1 is free
+        if (s + ahead < total_stages) issue_loads(s + ahead, (buf + ahead) % p.nring);
         int rows = rows_strip - (s % p.nstages) * p.SR;
         if (rows > p.SR) rows = p.SR;
         const int nsteps = (rows * p.Q + 31) >> 5;          // steps that contain at least one position
-        const unsigned char *dys = smem + (s & 1) * stage_bytes;
-        const unsigned char *xs = smem + (s & 1) * stage_bytes + 4 * p.dyplane + cq * p.xplane;
+        const unsigned char *dys = smem + buf * stage_bytes;
+        const unsigned char *xs = smem + buf * stage_bytes + 4 * p.dyplane + cq * p.xplane;
+        buf = (buf + 1 == p.nring) ? 0 : buf + 1;
         auto load_a = [&](const int (&dyoff)[2], bf16x8 (&a)[4]) {
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) a[kb] = tr_frag(dys + kb * p.dyplane + dyoff[0], dys + kb * p.dyplane + dyoff[1]);
@@ -177,17 +213,19 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         // step streams continue across stages so that the remainders even out
         int j = (wh - (s * steps_full) % NH + NH) % NH;
         if (j < nsteps) {
-            int dyo[2], xo[2], dyn[2], xn[2];
-            bf16x8 acur[4], anext[4], b[3];
+            int dyo[2], xo[2];
+            bf16x8 acur[4], b[3];
             step_offsets(j, dyo, xo);
             load_a(dyo, acur);
 #pragma unroll
             for (int t = 0; t < 3; ++t) b[t] = load_b(xo, t);
-            while (true) {
-                const bool has_next = j + NH < nsteps;
-                step_offsets(has_next ? j + NH : j, dyn, xn);
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb) anext[kb] = acur[kb];
+            // One step = 9 taps x 4 MFMAs.  The body exists in two straight-line versions (with and
+            // without the fetches of the wave's next step) so that every LDS wait is an exact count.
+            auto step_body = [&](auto has_next_tag) {
+                constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+                int dyn[2], xn[2];
+                bf16x8 anext[4];
+                if (HAS_NEXT) step_offsets(j + NH, dyn, xn);
 #pragma unroll
                 for (int t = 0; t < WS_NT; ++t) {
 #pragma unroll
@@ -195,16 +233,21 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
                         acc[kb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[kb], b[t % 3], acc[kb][t], 0, 0, 0);
                     // refill the slot just consumed: tap t+3 of this step, or tap t+3-9 of the next
                     if (t + 3 < WS_NT) b[t % 3] = load_b(xo, t + 3);
-                    else if (has_next) b[t % 3] = load_b(xn, t + 3 - WS_NT);
-                    if (t == 2 && has_next) load_a(dyn, anext);
+                    else if (HAS_NEXT) b[t % 3] = load_b(xn, t + 3 - WS_NT);
+                    if (t == 2 && HAS_NEXT) load_a(dyn, anext);
                 }
-                if (!has_next) break;
+                if (HAS_NEXT) {
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb) acur[kb] = anext[kb];
+                    for (int kb = 0; kb < 4; ++kb) acur[kb] = anext[kb];
 #pragma unroll
-                for (int e = 0; e < 2; ++e) { dyo[e] = dyn[e]; xo[e] = xn[e]; }
+                    for (int e = 0; e < 2; ++e) { dyo[e] = dyn[e]; xo[e] = xn[e]; }
+                }
+            };
+            while (j + NH < nsteps) {
+                step_body(std::true_type{});
                 j += NH;
             }
+            step_body(std::false_type{});
         }
     }
     __syncthreads();                                        // all stage buffers are free

@@ -208,9 +208,11 @@ def test_wgrad_per_tap_kernel_still_matches(case, monkeypatch):
 
 
 @pytest.mark.parametrize("case", [12, 13, 14])
-@pytest.mark.parametrize("ncq", [1, 2, 4])
-def test_wgrad_all_taps_channel_group_variants(case, ncq, monkeypatch):
+@pytest.mark.parametrize("ncq,ring", [(1, 3), (2, 3), (4, 3), (2, 2)])
+def test_wgrad_all_taps_channel_group_variants(case, ncq, ring, monkeypatch):
+    """Channel-group splits and LDS ring depths (3 buffers are used when they fit, 2 otherwise / when forced)."""
     monkeypatch.setenv("NGC_WGRAD_NCQ", str(ncq))
+    monkeypatch.setenv("NGC_WGRAD_RING", str(ring))
     a = MFMA_CASES[case]
     x, w, b, dy = _tensors(a, "bf16", 4000 + case)
     run = Run(a, "bf16", BLK, BLK, True)
