@@ -252,6 +252,7 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     q.ncq = tiles64 <= 4 ? 2 : 4;
     const char *fq = getenv("NGC_WGRAD_NCQ");
     if (fq && (atoi(fq) == 1 || atoi(fq) == 2 || atoi(fq) == 4)) q.ncq = atoi(fq);
+    if (4 * nblk_dy + q.ncq * nblk_x > 80) return false;                // load items per stage (10 per wave)
     const size_t stage = (size_t)4 * q.dyplane + (size_t)q.ncq * q.xplane;
     q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
     const char *fr = getenv("NGC_WGRAD_RING");                          // tests / benchmarks only

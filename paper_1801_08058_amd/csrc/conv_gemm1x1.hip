@@ -2,18 +2,21 @@
 //
 //   out[pos][co] = sum_ci in[pos'][ci] * wt[ci/16][co][ci%16]        (one tap, any stride)
 //
-// Workgroup = 8 waves, tile BM = 64*WM positions x BN = 64*WN output channels (WM*WN = 8), wave
-// tile 64 x 64 = 2x2 v_mfma_f32_32x32x16_bf16 (A = filters, B = activations, as in the other
-// forward kernels).  The reduction runs over 64-input-channel stages through an NS-deep LDS ring
-// filled by direct global->LDS loads (buffer_load_dwordx4 ... lds); every wave issues the same
-// number of loads per stage, so "stage s has landed" is a counted s_waitcnt vmcnt(N) and the
-// loads of the next NS-1 stages stay in flight during the MFMAs of stage s.  One barrier per stage.
+// Workgroup = 8 MFMA waves + 2 loader waves, tile BM = 64*WM positions x BN = 64*WN output
+// channels (WM*WN = 8), MFMA wave tile 64 x 64 = 2x2 v_mfma_f32_32x32x16_bf16 (A = filters, B =
+// activations, as in the other forward kernels).  The reduction runs over 16*KB-input-channel stages
+// through an NS-deep LDS ring filled by direct global->LDS loads (buffer_load_dwordx4 ... lds)
+// that only the loader waves issue: a loader issues the same number of loads per stage, so
+// "stage s has landed" is a counted s_waitcnt vmcnt(N) and the loads of the next NS-1 stages stay
+// in flight during the MFMAs of stage s.  One barrier per stage, shared by all 10 waves.
 // LDS planes of 16-byte units (8 channels of one row) as in the strip kernel: conflict-free
 // ds_read_b128 operand fetches.
 //
 // Workgroups that share an activation tile (different output-channel tiles) are given ids that
 // land on the same XCD (id % 8), so the tile is fetched into one L2 only.
 #include "common.h"
+
+#include <stdlib.h>
 
 namespace ngc {
 
@@ -23,23 +26,26 @@ typedef __attribute__((address_space(3))) void lds_void_q;
 
 constexpr unsigned G1_OOB = 0x80000000u;
 
-template <int WM, int WN, int NS>
-__global__ __launch_bounds__(512) void conv_gemm1x1_bf16(const Gemm1x1Params p)
+// NS = ring depth; KB = 16-channel blocks per stage (4 or 2): a stage holds 2 KB planes (8-channel halves) per operand.
+// NL = loader waves (1 or 2); WM x WN MFMA waves.
+template <int WM, int WN, int NS, int KB, int NL>
+__global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int XPLANE = BM * 16 + 128, WPLANE = BN * 16 + 128;
-    constexpr int STAGE = 8 * XPLANE + 8 * WPLANE;
-    constexpr int LPW = WM + WN;                      // loads per wave per stage: (8 WM + 8 WN) items / 8 waves
-    static_assert(WM * WN == 8, "8 waves");
+    constexpr int NPL = 2 * KB;                       // planes per operand and stage
+    constexpr int STAGE = NPL * XPLANE + NPL * WPLANE;
+    constexpr int NCW = WM * WN;                      // MFMA waves
+    constexpr int PPL = NPL / NL;                     // planes per loader wave
+    constexpr int LPL = PPL * (WM + WN);              // loads per loader wave per stage
+    static_assert((NCW == 8 || NCW == 4) && (NL == 1 || NL == 2), "wave roles");
+    static_assert(NS >= 2 && NS <= 4 && (KB == 2 || KB == 4), "ring depth / stage size");
+    static_assert(LPL * (NS - 2) < 64, "vmcnt range");
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WM;
-    const int wn = wave / WM;
-    const int l32 = lane & 31;
-    const int lg = lane >> 5;
 
     // XCD-aware tile order: id = xcd + 8 * (mgroup * NT + ntile), m-tile = mgroup * 8 + xcd
     const int NT = p.Cout / BN;
@@ -50,52 +56,77 @@ __global__ __launch_bounds__(512) void conv_gemm1x1_bf16(const Gemm1x1Params p)
     const uint32_t m0 = (uint32_t)mtile * BM;
     if (m0 >= p.M) return;                             // uniform per workgroup
     const int n0 = ntile * BN;
+    const int nsteps = p.Cin / (16 * KB);
 
-    const int CBin = p.Cin >> 4;
-    const int HWin = p.Hin * p.Win;
-
-    __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
-    __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
-
-    // ---- loader roles.  X items: plane * WM + block (64 rows); W items: plane * WN + block.
-    // Wave w takes X items w + 8 j (j < WM): block = w % WM, plane = w / WM + (8 / WM) * j
-    //             W items w + 8 j (j < WN): block = w % WN, plane = w / WN + (8 / WN) * j
-    unsigned xvoff;
-    {
-        const uint32_t m = m0 + (uint32_t)((wave % WM) * 64 + lane);
-        xvoff = G1_OOB;
-        if (m < p.M) {
-            const uint32_t n = fd_div(m, p.div_pq);
-            const uint32_t rem = m - n * p.div_pq.d;
-            const uint32_t i = fd_div(rem, p.div_q);
-            const uint32_t j = rem - i * p.div_q.d;
-            const int ih = (int)i * p.is_h + p.dh;
-            const int iw = (int)j * p.is_w + p.dw;
-            if ((unsigned)ih < (unsigned)p.Hin && (unsigned)iw < (unsigned)p.Win)
-                xvoff = (unsigned)(((int)n * CBin * HWin + ih * p.Win + iw) * 32);
+    if (wave >= NCW) {
+        // ---- loader waves (the last NL): all global->LDS traffic of the workgroup.  A wave whose loads are
+        // held back by the memory system stalls at issue; keeping the loads out of the MFMA waves
+        // lets the matrix pipes run meanwhile.  Loader l fills planes PPL*l .. PPL*l+PPL-1 (plane = 16-channel
+        // block * 2 + 8-channel half) of both operands, KB planes each: LPL loads per stage.
+        const int lw = wave - NCW;
+        const int CBin = p.Cin >> 4;
+        const int HWin = p.Hin * p.Win;
+        __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
+        __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
+        unsigned xvoff[WM];
+#pragma unroll
+        for (int b = 0; b < WM; ++b) {
+            const uint32_t m = m0 + (uint32_t)(b * 64 + lane);
+            xvoff[b] = G1_OOB;
+            if (m < p.M) {
+                const uint32_t n = fd_div(m, p.div_pq);
+                const uint32_t rem = m - n * p.div_pq.d;
+                const uint32_t i = fd_div(rem, p.div_q);
+                const uint32_t j = rem - i * p.div_q.d;
+                const int ih = (int)i * p.is_h + p.dh;
+                const int iw = (int)j * p.is_w + p.dw;
+                if ((unsigned)ih < (unsigned)p.Hin && (unsigned)iw < (unsigned)p.Win)
+                    xvoff[b] = (unsigned)(((int)n * CBin * HWin + ih * p.Win + iw) * 32);
+            }
         }
+        const unsigned wvoff = (unsigned)((n0 + lane) * 32);
+
+        auto issue_loads = [&](int s, int buf) {
+            unsigned char *xs = smem + buf * STAGE;
+            unsigned char *ws = xs + NPL * XPLANE;
+#pragma unroll
+            for (int q = 0; q < PPL; ++q) {
+                const int pl = lw * PPL + q;
+                const int cb = s * KB + (pl >> 1);
+                const unsigned soff_x = (unsigned)(cb * HWin * 32);
+                const unsigned soff_w = (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16);
+#pragma unroll
+                for (int b = 0; b < WM; ++b) {
+                    const unsigned v = (xvoff[b] == G1_OOB) ? G1_OOB : xvoff[b] + (pl & 1) * 16;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + pl * XPLANE + b * 1024), 16, (int)v,
+                                                             (int)soff_x, 0, 0);
+                }
+#pragma unroll
+                for (int b = 0; b < WN; ++b)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void_q *)(ws + pl * WPLANE + b * 1024), 16,
+                                                             (int)(wvoff + b * 64 * 32), (int)soff_w, 0, 0);
+            }
+        };
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s)
+            if (s < nsteps) issue_loads(s, s);
+        for (int s = 0; s < nsteps; ++s) {
+            // stage s has landed when at most the loads of the NS-2 later stages are outstanding
+            constexpr int W2 = LPL * 2, W1 = LPL;
+            if (NS == 4 && s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F70 | (W2 & 15) | ((W2 >> 4) << 14));
+            else if (NS >= 3 && s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F70 | (W1 & 15) | ((W1 >> 4) << 14));
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+            wg_barrier_nofence();                      // stage s visible to all; buffer of stage s-1 is free
+            if (s + NS - 1 < nsteps) issue_loads(s + NS - 1, (s + NS - 1) % NS);
+        }
+        return;
     }
-    const unsigned wvoff = (unsigned)((n0 + (wave % WN) * 64 + lane) * 32);
 
-    auto issue_loads = [&](int s, int buf) {
-        unsigned char *xs = smem + buf * STAGE;
-        unsigned char *ws = xs + 8 * XPLANE;
-#pragma unroll
-        for (int j = 0; j < WM; ++j) {
-            const int pl = wave / WM + (8 / WM) * j;                     // plane = cbi * 2 + g
-            const unsigned soff = (unsigned)((s * 4 + (pl >> 1)) * HWin * 32);
-            const unsigned v = (xvoff == G1_OOB) ? G1_OOB : xvoff + (pl & 1) * 16;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + pl * XPLANE + (wave % WM) * 1024), 16, (int)v,
-                                                     (int)soff, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int pl = wave / WN + (8 / WN) * j;
-            const unsigned soff = (unsigned)((s * 4 + (pl >> 1)) * p.Cout * 32 + (pl & 1) * 16);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void_q *)(ws + pl * WPLANE + (wave % WN) * 1024), 16,
-                                                     (int)wvoff, (int)soff, 0, 0);
-        }
-    };
+    // ---- MFMA waves 0 .. NCW-1
+    const int wm = wave % WM;
+    const int wn = wave / WM;
+    const int l32 = lane & 31;
+    const int lg = lane >> 5;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -105,23 +136,12 @@ __global__ __launch_bounds__(512) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    const int nsteps = p.Cin >> 6;
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < nsteps) issue_loads(s, s);
-
     for (int s = 0; s < nsteps; ++s) {
-        // stage s has landed when at most the loads of the NS-2 later stages are outstanding
-        static_assert(NS == 2 || NS == 3, "ring depth");
-        if (NS == 3 && s + 1 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F70 | LPW);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
         wg_barrier_nofence();
-        if (s + NS - 1 < nsteps) issue_loads(s + NS - 1, (s + NS - 1) % NS);
-
         const unsigned char *xs = smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;
-        const unsigned char *ws = smem + (s % NS) * STAGE + 8 * XPLANE + lg * WPLANE + (wn * 64 + l32) * 16;
+        const unsigned char *ws = smem + (s % NS) * STAGE + NPL * XPLANE + lg * WPLANE + (wn * 64 + l32) * 16;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < KB; ++ks) {
             bf16x8 fa[2], fb[2];
 #pragma unroll
             for (int a = 0; a < 2; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(ws + (2 * ks) * WPLANE + a * 512);
@@ -200,28 +220,45 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int WM, int WN, int NS>
+template <int WM, int WN, int NS, int KB, int NL>
 static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr size_t lds = (size_t)NS * (8 * (BM * 16 + 128) + 8 * (BN * 16 + 128));
+    constexpr size_t stage = (size_t)2 * KB * ((BM * 16 + 128) + (BN * 16 + 128));
+    // short reductions use fewer ring buffers than NS: less LDS, more workgroups per compute unit
+    const int nsteps = p.Cin / (16 * KB);
+    const size_t lds = (size_t)(nsteps < NS ? nsteps : NS) * stage;
     const unsigned mtiles = (p.M + BM - 1) / BM;
     const unsigned grid = ((mtiles + 7) / 8) * 8 * (p.Cout / BN);
-    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS>), dim3(grid), dim3(512), lds, st, p);
+    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
     return hipGetLastError();
 }
 
+// 32-channel stages in a ring of 3 (75 KB of LDS): two workgroups per compute unit, so one's
+// epilogue and ring start-up overlap the other's MFMAs.  NGC_G1_VARIANT (experiments only) selects
+// 64-channel stages with one workgroup per compute unit (1) or a ring of 4 (2).
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
-    if (p.Cout % 128 == 0) return launch_gemm1x1_t<4, 2, 3>(p, st);
-    return launch_gemm1x1_t<8, 1, 2>(p, st);
+    const char *ev = getenv("NGC_G1_VARIANT");
+    const int variant = ev ? atoi(ev) : 0;
+    if (p.Cout % 128 == 0) {
+        if (variant == 1) return launch_gemm1x1_t<4, 2, 3, 4, 2>(p, st);
+        if (variant == 2) return launch_gemm1x1_t<4, 2, 4, 2, 2>(p, st);
+        if (variant == 3) return launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st);
+        if (variant == 4) return launch_gemm1x1_t<2, 2, 4, 2, 1>(p, st);
+        return launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
+    }
+    if (variant == 1) return launch_gemm1x1_t<8, 1, 2, 4, 2>(p, st);
+    if (variant == 2) return launch_gemm1x1_t<8, 1, 3, 2, 2>(p, st);
+    if (variant == 3 || variant == 4) return launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st);
+    return launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
 }
 
 }  // namespace ngc

@@ -47,6 +47,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr unsigned WS_OOB = 0x80000000u;
 constexpr int WS_NT = 9;
+constexpr int WS_MAXI = 10;                        // load items per wave and stage (host guarantees items <= 80)
 
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigned char *hi)
 {
@@ -122,9 +123,35 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     const int nblk_dy = steps_full;
 
     // load items of a stage: (plane, 32-position block) pairs, 4 dy planes then NCQ x planes,
-    // dealt round-robin to the 8 waves
+    // dealt round-robin to the 8 waves.  What does not change from stage to stage is computed once
+    // per lane and item (the address arithmetic would otherwise cost more issue cycles than the MFMAs
+    // of a stage): item_off = byte offset relative to the stage origin (WS_OOB if the lane never
+    // loads), item_row = position (dy) or patch row (x) that decides validity in a given stage.
     const int items_dy = 4 * nblk_dy;
     const int items = items_dy + NCQ * nblk_x;
+    unsigned item_off[WS_MAXI];
+    int item_row[WS_MAXI];
+#pragma unroll
+    for (int i = 0; i < WS_MAXI; ++i) {
+        const int it = wave + NW * i;
+        item_off[i] = WS_OOB;
+        item_row[i] = 0;
+        if (it < items_dy) {
+            const int blk = it % nblk_dy;
+            const int pos = blk * 32 + (lane >> 1);
+            item_off[i] = (unsigned)(pos * 32 + (lane & 1) * 16);
+            item_row[i] = pos;
+        } else if (it < items) {
+            const int blk = (it - items_dy) % nblk_x;
+            const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
+            const uint32_t pr = fd_div(px, p.div_pc);
+            const uint32_t pc = px - pr * p.div_pc.d;
+            const int w = p.min_dw + (int)pc;
+            if (px < (uint32_t)npatch && (unsigned)w < (unsigned)p.W)
+                item_off[i] = (unsigned)(((int)pr * p.W + (int)pc) * 32 + (lane & 1) * 16);
+            item_row[i] = (int)pr;
+        }
+    }
     auto issue_loads = [&](int stage_lin, int buf) {
         const int img = n0 + stage_lin / p.nstages;                      // stages run image by image
         const int stage_i = stage_lin - (stage_lin / p.nstages) * p.nstages;
@@ -134,25 +161,22 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         if (rows > p.SR) rows = p.SR;
         const int nvalid = rows * p.Q;                                   // positions of the stage that exist
         const int h0 = p0 + r0 + p.min_dh;
-        for (int it = wave; it < items; it += NW) {
-            if (it < items_dy) {
+        // stage origins (x: pixel (h0, min_dw), possibly outside the image; valid lanes end up in range)
+        const unsigned dy_org = (unsigned)((((img * KB + kt * 4) * PQ) + (p0 + r0) * p.Q) * 32);
+        const unsigned x_org = (unsigned)(((img * CB + ct * NCQ) * HW + h0 * p.W + p.min_dw) * 32);
+#pragma unroll
+        for (int i = 0; i < WS_MAXI; ++i) {
+            const int it = wave + NW * i;
+            if (it < items_dy) {                                         // wave-uniform
                 const int pln = it / nblk_dy, blk = it - pln * nblk_dy;
-                const unsigned dy_base = (unsigned)((((img * KB + kt * 4 + pln) * PQ) + (p0 + r0) * p.Q) * 32);
-                const int pos = blk * 32 + (lane >> 1);
-                const unsigned off = (pos < nvalid) ? dy_base + (unsigned)(pos * 32 + (lane & 1) * 16) : WS_OOB;
+                const unsigned off = (item_row[i] < nvalid) ? dy_org + (unsigned)(pln * PQ * 32) + item_off[i] : WS_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_t *)(base + pln * p.dyplane + blk * 1024), 16,
                                                          (int)off, 0, 0, 0);
-            } else {
+            } else if (it < items) {
                 const int itx = it - items_dy;
                 const int pln = itx / nblk_x, blk = itx - pln * nblk_x;
-                const unsigned x_base = (unsigned)(((img * CB + ct * NCQ + pln) * HW) * 32);
-                const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
-                const uint32_t pr = fd_div(px, p.div_pc);
-                const uint32_t pc = px - pr * p.div_pc.d;
-                const int h = h0 + (int)pr;
-                const int w = p.min_dw + (int)pc;
-                const bool ok = px < (uint32_t)npatch && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
-                const unsigned off = ok ? x_base + (unsigned)((h * p.W + w) * 32 + (lane & 1) * 16) : WS_OOB;
+                const bool ok = item_off[i] != WS_OOB && (unsigned)(h0 + item_row[i]) < (unsigned)p.H;
+                const unsigned off = ok ? x_org + (unsigned)(pln * HW * 32) + item_off[i] : WS_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(base + 4 * p.dyplane + pln * p.xplane + blk * 1024),
                                                          16, (int)off, 0, 0, 0);
             }
