@@ -65,8 +65,9 @@ constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
 
 // Tiling of the output-stationary strip kernel: picks the strip size (nf = 32-position fragments
-// per SIMD) and fills the geometry fields of `q` for an output of N x Hout x Wout positions whose
-// taps span span_h x span_w input pixels.  Returns false if nothing fits.
+// per SIMD) and fills the geometry fields of `out` for a lattice of N x Hout x Wout positions whose
+// taps span span_h x span_w input pixels beyond the position's own pixel (position stride out.sh,
+// out.sw in input pixels).  Returns false if nothing fits.
 bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int span_w, int ntaps, int Cout,
                     int *nf_out, size_t *lds_out)
 {
@@ -74,6 +75,8 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
     const char *force = getenv("NGC_STRIP_NF");
     const int forced_nf = force ? atoi(force) : -1;
     if (forced_nf == 0) return false;
+    constexpr int MAXPATCH = 24 * 64;                                    // patch pixels per plane (24 blocks of 64)
+    const int sh = out.sh, sw = out.sw;
     StripParams best;
     int best_nf = 0;
     size_t best_lds = 0;
@@ -83,25 +86,32 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
         const int maxpix = 4 * nf * 32;
         if (Wout > maxpix) continue;
         StripParams q = out;
-        const int rows_fit = maxpix / Wout;
-        if (rows_fit >= Hout) {
+        q.PC = (Wout - 1) * sw + span_w + 1;
+        const int pr_full = (Hout - 1) * sh + span_h + 1;
+        int tn = maxpix / (Hout * Wout);
+        if (tn > MAXPATCH / (pr_full * q.PC)) tn = MAXPATCH / (pr_full * q.PC);
+        if (tn >= 1) {
             q.TP = Hout;
-            q.TN = maxpix / (Hout * Wout);
-            if (q.TN > N) q.TN = N;
+            q.TN = tn > N ? N : tn;
             q.strips = 1;
         } else {
+            int rows_fit = maxpix / Wout;
+            const int prows = MAXPATCH / q.PC;                           // patch rows that fit
+            if (prows < span_h + 1) continue;
+            const int rows_patch = (prows - span_h - 1) / sh + 1;
+            if (rows_fit > rows_patch) rows_fit = rows_patch;
+            if (rows_fit < 1) continue;
             q.TN = 1;
             q.strips = (Hout + rows_fit - 1) / rows_fit;
             q.TP = (Hout + q.strips - 1) / q.strips;
             q.strips = (Hout + q.TP - 1) / q.TP;
         }
         q.groups = (N + q.TN - 1) / q.TN;
-        q.PR = q.TP + span_h;
-        q.PC = Wout + span_w;
+        q.PR = (q.TP - 1) * sh + span_h + 1;
         q.npix = q.TN * q.TP * Wout;
         q.npatch = q.TN * q.PR * q.PC;
         const int nblocks = (q.npatch + 63) / 64;
-        if (nblocks > 24) continue;                                  // 64-pixel patch blocks per plane
+        if (nblocks > 24) continue;
         q.xpitch = nblocks * 1024 + 128;
         const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)2 * ntaps * (64 * 16 + 128));
         if (lds > LDS_LIMIT) continue;
@@ -110,7 +120,13 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
         q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
         q.div_pc = make_fastdiv((uint32_t)q.PC);
         const long wgs = (long)q.groups * q.strips * (Cout / 64);
-        best = q; best_nf = nf; best_lds = lds;
+        // the patch limit may leave the strip smaller than the candidate: smallest variant that holds it
+        int nf_eff = nf;
+        if (forced_nf <= 0) {
+            if (q.npix <= 4 * 2 * 32) nf_eff = 2;
+            else if (q.npix <= 4 * 4 * 32) nf_eff = 4;
+        }
+        best = q; best_nf = nf_eff; best_lds = lds;
         if (wgs >= NUM_CUS) break;                                   // largest strip that still fills the chip
     }
     if (!best_nf) return false;
@@ -120,41 +136,91 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
     return true;
 }
 
-// Strip kernel for forward (op 0) or backprop-data (op 1) of a stride-1 multi-tap convolution.
-bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q, StripParams *sp, int *nf_out, size_t *lds_out)
+// Strip kernel for forward (op 0; any stride) or for residue class (ca, cb) of the output pixels of
+// backprop-data (op 1; stride-1 layers have the single class (0,0)) of a multi-tap convolution.
+// *empty is set when the class has no output pixel (nothing to launch).
+bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
+                      size_t *lds_out, bool *empty)
 {
-    if (d->stride_h != 1 || d->stride_w != 1) return false;
-    const int ntaps = d->r * d->s;
-    if (ntaps < 2 || ntaps > STRIP_MAX_TAPS) return false;
-    const int Cin = op == NGC_OP_FWD ? d->c : d->k, Cout = op == NGC_OP_FWD ? d->k : d->c;
+    if (empty) *empty = false;
+    const int all_taps = d->r * d->s;
+    if (all_taps < 2 || all_taps > STRIP_MAX_TAPS) return false;
+    const bool fwd = op == NGC_OP_FWD;
+    const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
     if (Cin % 16 != 0 || Cout % 64 != 0) return false;
-    const int Hin = op == NGC_OP_FWD ? d->h : P, Win = op == NGC_OP_FWD ? d->w : Q;
-    const int Hout = op == NGC_OP_FWD ? P : d->h, Wout = op == NGC_OP_FWD ? Q : d->w;
+    const int Hin = fwd ? d->h : P, Win = fwd ? d->w : Q;
+    const int Hfull = fwd ? P : d->h, Wfull = fwd ? Q : d->w;
     const size_t in_bytes = (size_t)d->n * Cin * Hin * Win * 2;
-    const size_t wt_bytes = (size_t)ntaps * Cin * Cout * 2;
+    const size_t wt_bytes = (size_t)all_taps * Cin * Cout * 2;
     if (in_bytes >= ((size_t)1 << 31) || wt_bytes >= ((size_t)1 << 31)) return false;
-    const int span_h = d->dil_h * (d->r - 1), span_w = d->dil_w * (d->s - 1);
-    const int min_dh = op == NGC_OP_FWD ? -d->pad_below_h : d->pad_below_h - span_h;
-    const int min_dw = op == NGC_OP_FWD ? -d->pad_below_w : d->pad_below_w - span_w;
+
+    // taps of this launch: offset (dh, dw) of the input pixel relative to the position's own pixel
+    int tdh[STRIP_MAX_TAPS], tdw[STRIP_MAX_TAPS], tslab[STRIP_MAX_TAPS];
+    int ntaps = 0;
+    const int sh = d->stride_h, sw = d->stride_w;
+    for (int r = 0; r < d->r; ++r)
+        for (int s2 = 0; s2 < d->s; ++s2) {
+            int dh, dw;
+            if (fwd) {
+                dh = r * d->dil_h - d->pad_below_h;
+                dw = s2 * d->dil_w - d->pad_below_w;
+            } else {
+                const int vh = ca + d->pad_below_h - r * d->dil_h, vw = cb + d->pad_below_w - s2 * d->dil_w;
+                if (((vh % sh) + sh) % sh != 0 || ((vw % sw) + sw) % sw != 0) continue;
+                dh = vh / sh;                                            // exact
+                dw = vw / sw;
+            }
+            tdh[ntaps] = dh; tdw[ntaps] = dw; tslab[ntaps] = r * d->s + s2;
+            ++ntaps;
+        }
+    if (ntaps == 0) return false;                                        // class without taps: zero pixels, not handled here
+    int min_dh = tdh[0], max_dh = tdh[0], min_dw = tdw[0], max_dw = tdw[0];
+    for (int t = 1; t < ntaps; ++t) {
+        if (tdh[t] < min_dh) min_dh = tdh[t];
+        if (tdh[t] > max_dh) max_dh = tdh[t];
+        if (tdw[t] < min_dw) min_dw = tdw[t];
+        if (tdw[t] > max_dw) max_dw = tdw[t];
+    }
+    // position lattice
+    const int Hout = fwd ? P : (ca < d->h ? (d->h - ca + sh - 1) / sh : 0);
+    const int Wout = fwd ? Q : (cb < d->w ? (d->w - cb + sw - 1) / sw : 0);
+    if (Hout == 0 || Wout == 0) {
+        if (empty) *empty = true;
+        return true;
+    }
 
     StripParams q;
     memset(&q, 0, sizeof(q));
     q.N = d->n; q.Cin = Cin; q.Hin = Hin; q.Win = Win; q.Cout = Cout; q.Hout = Hout; q.Wout = Wout;
+    q.Hfull = Hfull; q.Wfull = Wfull;
+    q.sh = fwd ? sh : 1; q.sw = fwd ? sw : 1;
+    q.os_h = fwd ? 1 : sh; q.os_w = fwd ? 1 : sw;
+    q.oa_h = fwd ? 0 : ca; q.oa_w = fwd ? 0 : cb;
     q.min_dh = min_dh; q.min_dw = min_dw;
     q.ntaps = ntaps;
     q.in_bytes = (uint32_t)in_bytes;
     q.wt_bytes = (uint32_t)wt_bytes;
-    if (!strip_geometry(q, d->n, Hout, Wout, span_h, span_w, ntaps, Cout, nf_out, lds_out)) return false;
-    int t = 0;
-    for (int r = 0; r < d->r; ++r)
-        for (int s2 = 0; s2 < d->s; ++s2) {
-            const int dh = op == NGC_OP_FWD ? r * d->dil_h - d->pad_below_h : d->pad_below_h - r * d->dil_h;
-            const int dw = op == NGC_OP_FWD ? s2 * d->dil_w - d->pad_below_w : d->pad_below_w - s2 * d->dil_w;
-            q.tap_off[t] = (dh - min_dh) * q.PC + (dw - min_dw);
-            q.tap_slab[t] = r * d->s + s2;
-            ++t;
-        }
+    if (!strip_geometry(q, d->n, Hout, Wout, max_dh - min_dh, max_dw - min_dw, ntaps, Cout, nf_out, lds_out)) return false;
+    for (int t = 0; t < ntaps; ++t) {
+        q.tap_off[t] = (tdh[t] - min_dh) * q.PC + (tdw[t] - min_dw);
+        q.tap_slab[t] = tslab[t];
+    }
     if (sp) *sp = q;
+    return true;
+}
+
+// number of residue classes of backprop-data launches (1 for forward)
+int strip_classes(const ngc_conv_desc *d, int op) { return op == NGC_OP_FWD ? 1 : d->stride_h * d->stride_w; }
+
+// true if every launch of the op can go through the strip kernel
+bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q)
+{
+    const char *sw = getenv("NGC_STRIP_STRIDED");                        // tests / benchmarks only: 0 = stride-1 layers only
+    if (sw && atoi(sw) == 0 && (d->stride_h != 1 || d->stride_w != 1)) return false;
+    const int ncls = strip_classes(d, op);
+    if (ncls > 16) return false;
+    for (int c = 0; c < ncls; ++c)
+        if (!strip_plan_class(d, op, c / d->stride_w, c % d->stride_w, P, Q, nullptr, nullptr, nullptr, nullptr)) return false;
     return true;
 }
 
@@ -213,6 +279,7 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
     q.wt_bytes = (uint32_t)pl.wu_bytes;
     q.out_mode = 1;
     q.sub_C = d->c; q.sub_H = d->h; q.sub_W = d->w;
+    q.sh = q.sw = q.os_h = q.os_w = 1; q.Hfull = Hout; q.Wfull = Wout;
     if (!strip_geometry(q, d->n, Hout, Wout, pl.ndr - 1, pl.nds - 1, ntaps, 64, &pl.nf, &pl.lds)) return false;
     int t = 0;
     for (int i = 0; i < pl.ndr; ++i)
@@ -451,7 +518,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         if (stem_fwd_plan(d, P, Q, nullptr, nullptr)) return V_STEM_FWD;
         const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
         const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
-        if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
+        if (base && strip_plan(d, op, P, Q)) return V_STRIP;
         if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
@@ -461,7 +528,7 @@ Variant pick(const ngc_conv_desc *d, int op)
         const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
         const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
                         d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
-        if (base && strip_plan(d, op, P, Q, nullptr, nullptr, nullptr)) return V_STRIP;
+        if (base && strip_plan(d, op, P, Q)) return V_STRIP;
         if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
@@ -664,7 +731,7 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
         StripParams sp;
         int nf;
         size_t lds;
-        if (!strip_plan(desc, NGC_OP_FWD, P, Q, &sp, &nf, &lds)) return NGC_UNSUPPORTED;
+        if (!strip_plan_class(desc, NGC_OP_FWD, 0, 0, P, Q, &sp, &nf, &lds, nullptr)) return NGC_UNSUPPORTED;
         sp.in = static_cast<const uint16_t *>(x);
         sp.wt = static_cast<const uint16_t *>(wt);
         sp.out = static_cast<uint16_t *>(y);
@@ -743,16 +810,24 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         wt = ws;
     }
     if (v == V_STRIP) {
-        StripParams sp;
-        int nf;
-        size_t lds;
-        if (!strip_plan(desc, NGC_OP_BWD_DATA, P, Q, &sp, &nf, &lds)) return NGC_UNSUPPORTED;
-        sp.in = static_cast<const uint16_t *>(dy);
-        sp.wt = static_cast<const uint16_t *>(wt);
-        sp.out = static_cast<uint16_t *>(dx);
-        sp.bias = nullptr;
-        sp.relu = 0;
-        return launch_status(launch_strip(sp, nf, lds, st));
+        const int ncls = strip_classes(desc, NGC_OP_BWD_DATA);
+        for (int c = 0; c < ncls; ++c) {                                 // one launch per residue class of the stride
+            StripParams sp;
+            int nf;
+            size_t lds;
+            bool empty;
+            if (!strip_plan_class(desc, NGC_OP_BWD_DATA, c / desc->stride_w, c % desc->stride_w, P, Q, &sp, &nf, &lds, &empty))
+                return NGC_UNSUPPORTED;
+            if (empty) continue;
+            sp.in = static_cast<const uint16_t *>(dy);
+            sp.wt = static_cast<const uint16_t *>(wt);
+            sp.out = static_cast<uint16_t *>(dx);
+            sp.bias = nullptr;
+            sp.relu = 0;
+            const int rc = launch_status(launch_strip(sp, nf, lds, st));
+            if (rc != NGC_OK) return rc;
+        }
+        return NGC_OK;
     }
     if (v == V_GEMM1X1) {
         Gemm1x1Params gp;

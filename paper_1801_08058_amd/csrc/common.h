@@ -149,6 +149,11 @@ struct StripParams {
     // out_mode 1: "sub-pixel" NCHW: output channel col = (2a+b)*sub_C + c of position (i,j) is
     //             pixel (2i+a, 2j+b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.
     int32_t out_mode, sub_C, sub_H, sub_W;
+    // Positions form a lattice of Hout x Wout per image.  Position (i, j) reads the patch at input
+    // pixel (i*sh, j*sw) + tap and is stored at pixel (i*os_h + oa_h, j*os_w + oa_w) of an output
+    // tensor of Hfull x Wfull pixels (forward: sh/sw = stride, os = 1; backprop-data: sh = sw = 1,
+    // one launch per residue class (oa_h, oa_w) of the stride os).
+    int32_t sh, sw, os_h, os_w, oa_h, oa_w, Hfull, Wfull;
     FastDiv div_tpq, div_q, div_prpc, div_pc;
 };
 

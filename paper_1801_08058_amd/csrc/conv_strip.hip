@@ -1,5 +1,5 @@
-// Stride-1 convolution (forward and backprop-data) as an output-stationary "strip" kernel on
-// bf16 MFMA (gfx950), fp32 accumulate.
+// Multi-tap convolution (forward with any stride, backprop-data per residue class of the stride)
+// as an output-stationary "strip" kernel on bf16 MFMA (gfx950), fp32 accumulate.
 //
 // A workgroup (256 threads, 4 waves, one per SIMD) owns a strip of up to 4*NF*32 output
 // positions (TN images x TP output rows x full width) for 64 output channels and keeps ALL
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
             const uint32_t pr = fd_div(rem, p.div_pc);
             const uint32_t pc = rem - pr * p.div_pc.d;
             const int n = n0 + (int)ti;
-            const int h = p0 + p.min_dh + (int)pr;
+            const int h = p0 * p.sh + p.min_dh + (int)pr;
             const int w = p.min_dw + (int)pc;
             if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)w < (unsigned)p.Win)
                 off = (unsigned)((n * CB * HWin + h * p.Win + w) * 32);
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
             const uint32_t rem = m - ti * p.div_tpq.d;
             const uint32_t tp = fd_div(rem, p.div_q);
             const uint32_t q = rem - tp * p.div_q.d;
-            pb = (int)((ti * p.PR + tp) * p.PC + q);
+            pb = (int)((ti * p.PR + tp * p.sh) * p.PC + q * p.sw);
         }
         pbase[i] = pb * 16;
     }
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 
     // ---- epilogue
     const int CBout = p.Cout >> 4;
-    const int HWout = p.Hout * p.Wout;
+    const int HWout = p.Hfull * p.Wfull;
     float4 bv[2][2][2];                                   // [a][h][which quad]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         const int n = n0 + (int)ti;
         const int oh = p0 + (int)tp;
         ok = ok && n < p.N && oh < p.Hout;
-        const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + q;
+        const size_t pix = (size_t)n * CBout * HWout + (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
         if (p.out_mode == 1) {
             // sub-pixel NCHW store: column col = (2a+b)*C + c -> pixel (2 oh + a, 2 q + b) of channel c
             const int ncol = 4 * p.sub_C;

@@ -36,7 +36,8 @@ def _check_all(a: Attrs, dtype: str, xl: int, yl: int, pre: bool, seed: int, exp
     tol = TOL[dtype]
     y = run.fwd(x, w, bias=b, relu=True)
     if expect_variant:
-        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD).startswith(expect_variant[0])
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD).startswith(expect_variant[0]), \
+            ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD)
     e = oracle.max_normalised_error(y, oracle.conv_fwd(a, x, w, bias=b, relu=True))
     assert e <= tol, f"fwd+bias+relu err {e}"
     y0 = run.fwd(x, w)
@@ -44,7 +45,8 @@ def _check_all(a: Attrs, dtype: str, xl: int, yl: int, pre: bool, seed: int, exp
     assert e <= tol, f"fwd err {e}"
     dx = run.bwd_data(dy, w)
     if expect_variant:
-        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect_variant[1])
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect_variant[1]), \
+            ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA)
     e = oracle.max_normalised_error(dx, oracle.conv_bwd_data(a, dy, w))
     assert e <= tol, f"bwd_data err {e}"
     dw = run.bwd_filters(x, dy)
@@ -179,14 +181,17 @@ def strip_nf(monkeypatch):
 @pytest.mark.parametrize("nf", [None, 0, 7, 4])
 def test_mfma_kernels_small(case, pre, nf, strip_nf):
     a = MFMA_CASES[case]
-    if nf in (7, 4) and ((a.sh, a.sw) != (1, 1) or a.r * a.s == 1 or not pre):
+    if nf in (7, 4) and ((a.sh, a.sw) != (1, 1) or a.r * a.s == 1 or not pre):  # forced sizes: stride-1 shapes only
         pytest.skip("strip kernel covers stride-1 multi-tap shapes; one filter-layout mode is enough for forced sizes")
     strip_nf(nf)
-    strip_ok = (a.sh, a.sw) == (1, 1) and a.r * a.s > 1 and nf != 0
+    # multi-tap layers go through the strip kernel: forward with any stride, backprop-data one launch per
+    # residue class of the stride unless a class has no tap at all (case 5: odd rows of dx stay zero)
+    strip_ok = a.r * a.s > 1 and nf != 0
+    bwd_strip_ok = strip_ok and case != 5
     one_tap = a.r * a.s == 1 and a.c % 64 == 0 and a.k % 64 == 0
     fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 64 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.c % 32 == 0 and a.k % 64 == 0) else "direct"
-    bwd_v = "strip" if (strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else "gemm1x1" if one_tap else \
+    bwd_v = "strip" if (bwd_strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.k % 32 == 0 and a.c % 64 == 0) else "direct"
     wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
     _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
@@ -261,6 +266,32 @@ def test_one_tap_gather_kernel_still_matches(case, monkeypatch):
     monkeypatch.setenv("NGC_GEMM1X1", "0")
     a = GEMM1X1_CASES[case]
     _check_all(a, "bf16", BLK, BLK, True, 7100 + case, ("igemm", "igemm", "wgrad"))
+
+
+STRIDED_STRIP_CASES = [
+    # n  c    h   w   k    r  s  sh sw dh dw pbh pbw pah paw
+    Attrs(3, 128, 56, 56, 128, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),    # ResNet stage transition: row strips of a 57-wide patch
+    Attrs(5, 64, 28, 28, 64, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),      # whole 14x14 outputs, one image per strip
+    Attrs(9, 64, 14, 14, 128, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),     # several 7x7 outputs per strip, ragged last group
+    Attrs(2, 64, 17, 23, 64, 5, 3, 2, 3, 1, 1, 2, 1, 2, 1),      # 5x3 taps, strides (2,3), odd sizes
+    Attrs(2, 64, 20, 20, 64, 3, 3, 2, 2, 1, 1, 0, 0, 0, 0),      # no padding: the last input row / column is never read
+    Attrs(1, 64, 9, 9, 64, 2, 2, 2, 2, 1, 1, 0, 0, 1, 1),        # 2x2 taps, stride 2: every class has exactly one tap
+]
+
+
+@pytest.mark.parametrize("case", range(len(STRIDED_STRIP_CASES)))
+@pytest.mark.parametrize("pre", [True, False])
+def test_strided_strip_kernel(case, pre):
+    a = STRIDED_STRIP_CASES[case]
+    _check_all(a, "bf16", BLK, BLK, pre, 8000 + case, ("strip", "strip", "wgrad"))
+
+
+@pytest.mark.parametrize("case", [0, 3])
+def test_strided_gather_kernel_still_matches(case, monkeypatch):
+    """Strided multi-tap shapes through the gather implicit-GEMM kernel (strided strips switched off)."""
+    monkeypatch.setenv("NGC_STRIP_STRIDED", "0")
+    a = STRIDED_STRIP_CASES[case]
+    _check_all(a, "bf16", BLK, BLK, True, 8100 + case, ("igemm", "igemm", "wgrad"))
 
 
 def test_run_to_run_identical():
