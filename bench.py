@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
+                    help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
+                         "of equal (default) priority, so that independent ops overlap their launch gaps and tails; "
+                         "1: everything on one stream")
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
@@ -97,24 +101,26 @@ class LayerBench:
         if nchw_input:
             self.ops = ["convert"] + self.ops
 
-    def launch(self, op, i=0):
+    def launch(self, op, i=0, streams=None):
+        """streams: optional {op: raw HIP stream}; default is the stream the bench was built on."""
         ng, s = self.ng, self.sets[i % len(self.sets)]
         L = self.L
+        st = self.stream if streams is None else streams[op]
         if op == "convert":
-            ng.ngc_layout_convert(ng.NGC_BF16, L.n, L.c, L.h, L.w, s["x_nchw"], ng.NGC_NCHW, s["x"], ng.NGC_NCHW16C, self.stream)
+            ng.ngc_layout_convert(ng.NGC_BF16, L.n, L.c, L.h, L.w, s["x_nchw"], ng.NGC_NCHW, s["x"], ng.NGC_NCHW16C, st)
         elif op == "fwd":
             ng.ngc_conv_fwd(self.d_fwd, s["x"], self.w_fwd, self.bias if L.bias_relu else None, s["y"],
-                            self.ws[ng.NGC_OP_FWD], self.stream)
+                            self.ws[ng.NGC_OP_FWD], st)
         elif op == "bwd_data":
-            ng.ngc_conv_bwd_data(self.d_bwd, s["dy"], self.w_bwd, s["dx"], self.ws[ng.NGC_OP_BWD_DATA], self.stream)
+            ng.ngc_conv_bwd_data(self.d_bwd, s["dy"], self.w_bwd, s["dx"], self.ws[ng.NGC_OP_BWD_DATA], st)
         elif op == "bwd_filters":
-            ng.ngc_conv_bwd_filters(self.d_wg, s["x"], s["dy"], s["dw"], self.ws[ng.NGC_OP_BWD_FILTERS], self.stream)
+            ng.ngc_conv_bwd_filters(self.d_wg, s["x"], s["dy"], s["dw"], self.ws[ng.NGC_OP_BWD_FILTERS], st)
         else:
             raise ValueError(op)
 
-    def step(self, i=0):
+    def step(self, i=0, streams=None):
         for op in self.ops:
-            self.launch(op, i)
+            self.launch(op, i, streams)
 
     def algorithmic_bytes(self, op):
         """Each tensor once (bf16 data, fp32 dw / bias)."""
@@ -186,10 +192,18 @@ def main():
     benches = [LayerBench(L, ng, torch, gpu_util, nchw_input=(cfg == 3), sets=sets) for L in layers]
     torch.cuda.synchronize()
 
+    # The ops of a layer read and write disjoint buffers (each has its own inputs, outputs and
+    # workspace), so with --streams 3 they are issued to one stream per op kind; cfg3's layout
+    # conversion feeds the forward op and stays single-stream.
+    streams = None
+    if args.streams == 3 and cfg != 3:
+        extra = [torch.cuda.Stream() for _ in range(2)]                 # default priority
+        streams = {"fwd": benches[0].stream, "bwd_data": extra[0].cuda_stream, "bwd_filters": extra[1].cuda_stream}
+
     def step(i):
         for b in benches:
             for _ in range(b.L.count):
-                b.step(i)
+                b.step(i, streams)
 
     for i in range(args.warmup):
         step(i)
@@ -246,7 +260,8 @@ def main():
                                 3: "configs[2]: 1x1 conv N=64 C=256 K=64 56x56 bf16, NCHW->nChw16c convert + fwd + bwd_data + bwd_filters",
                                 4: "configs[3]: stem 7x7/2 N=64 C=3 K=64 224x224 bf16, fwd(+bias+ReLU) + bwd_filters",
                                 5: "configs[4]: ResNet-50 conv stack N=128 bf16, 53 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
-                   "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm"},
+                   "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
+                   "streams": 3 if streams else 1},
         "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "gflop_per_step": round(flop_step / 1e9, 2),
         "roofline": roof,
