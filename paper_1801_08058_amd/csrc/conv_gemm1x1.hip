@@ -242,13 +242,20 @@ static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
 }
 
 // 32-channel stages in a ring of 3 (75 KB of LDS): two workgroups per compute unit, so one's
-// epilogue and ring start-up overlap the other's MFMAs.  NGC_G1_VARIANT (experiments only) selects
-// 64-channel stages with one workgroup per compute unit (1) or a ring of 4 (2).
+// epilogue and ring start-up overlap the other's MFMAs.  Few-tile launches (fewer 256x128 tiles
+// than the 512 workgroup slots of the chip) and strided forward gathers take 128x128 tiles (4 MFMA
+// waves + 1 loader, three workgroups per compute unit).  NGC_G1_VARIANT (experiments only) forces
+// 64-channel stages (1), a ring of 4 (2), the 128x128 tile with a ring of 3 (3) / 4 (4), or the
+// 256x128 tile whatever the size (5).
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
-    const int variant = ev ? atoi(ev) : 0;
+    int variant = ev ? atoi(ev) : 0;
     if (p.Cout % 128 == 0) {
+        if (variant == 0) {
+            const unsigned tiles = ((p.M + 255) / 256) * (unsigned)(p.Cout / 128);
+            if (tiles < 2 * 256 || p.is_h > 1 || p.is_w > 1) variant = 3;
+        }
         if (variant == 1) return launch_gemm1x1_t<4, 2, 3, 4, 2>(p, st);
         if (variant == 2) return launch_gemm1x1_t<4, 2, 4, 2, 2>(p, st);
         if (variant == 3) return launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st);
