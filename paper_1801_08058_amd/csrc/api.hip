@@ -443,7 +443,15 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     q.ctiles = d->c / (64 * q.wc);
     q.M = (uint32_t)d->n * P * Q;
     const uint32_t tiles = (uint32_t)(d->k / (64 * q.wk)) * q.ctiles * d->r * d->s;
-    uint32_t parts = (NUM_CUS + tiles - 1) / tiles;
+    // Stage size: 64-position stages take half the LDS, so two workgroups fit a compute unit and
+    // twice as many position chunks are cut.  That pays when there are many (tile, tap) pairs, i.e.
+    // few chunks and little extra partial traffic, and for multi-tap layers; the large-image 1x1
+    // layers are HBM-bound and keep 128-position stages.  NGC_WGG_SP (experiments only) forces 64 / 128.
+    const char *fsp = getenv("NGC_WGG_SP");
+    q.sp = (d->r * d->s > 1 || tiles >= 32) ? 64 : 128;
+    if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
+    const uint32_t slots = q.sp == 64 ? 2 * NUM_CUS : NUM_CUS;
+    uint32_t parts = (slots + tiles - 1) / tiles;
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;

@@ -229,6 +229,7 @@ struct WgradGemmParams {
     int32_t N, C, H, W, K, P, Q, R, S;
     int32_t sh, sw, dil_h, dil_w, pbh, pbw;
     int32_t wk, wc;            // 64-wide sub-tiles of k and c per workgroup
+    int32_t sp;                // positions per LDS stage (128 or 64)
     int32_t ctiles;            // C / (64 wc)
     int32_t nparts;
     uint32_t M, chunk;         // N*P*Q, positions per part (multiple of 128)

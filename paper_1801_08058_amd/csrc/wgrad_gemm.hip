@@ -7,7 +7,7 @@
 // Wave (wk, wc, h) owns a 64 x 64 sub-tile as 4x4 MFMA 16x16 tiles (64 accumulator registers)
 // and every NH-th 32-position step (NH = 8 / (WK*WC) interleaved step streams = a wave-level
 // split of the reduction, summed through LDS in a fixed tree at the end).
-// A stage = 128 positions: dy [128][64 WK] and x [128][64 WC] go to LDS in their natural
+// A stage = SP (128 or 64) positions: dy [SP][64 WK] and x [SP][64 WC] go to LDS in their natural
 // channel-contiguous form with direct global->LDS loads (out-of-range lanes deliver zeros =
 // padding and the tail of the chunk); MFMA operands (8 consecutive positions per lane) are
 // fetched with the LDS transpose load ds_read_b64_tr_b16.  Two stages, one barrier per stage.
@@ -25,8 +25,6 @@ typedef __attribute__((address_space(3))) void lds_void_g;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_g;
 
 constexpr unsigned WGG_OOB = 0x80000000u;
-constexpr int WGG_SP = 128;                       // positions per stage
-constexpr int WGG_PLANE = WGG_SP * 32 + 128;      // bytes per 16-channel plane of a stage
 
 __device__ __forceinline__ bf16x8 tr_frag_g(const unsigned char *lo)
 {
@@ -37,12 +35,19 @@ __device__ __forceinline__ bf16x8 tr_frag_g(const unsigned char *lo)
     return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int WK, int WC>
+// SP = positions per stage (128, or 64: half the LDS, two workgroups per compute unit)
+template <int WK, int WC, int SP>
 __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 {
     constexpr int NW = 8;
     constexpr int NH = NW / (WK * WC);
     constexpr int NPL = 4 * (WK + WC);            // 16-channel planes per stage: dy first, then x
+    constexpr int WGG_SP = SP;
+    constexpr int WGG_PLANE = SP * 32 + 128;      // bytes per 16-channel plane of a stage
+    constexpr int BLK = SP / 32;                  // 32-position blocks per plane = steps per stage
+    constexpr int NITEM = NPL * BLK / NW;         // load items (plane, block) per wave and stage
+    constexpr int MS = (BLK + NH - 1) / NH;       // steps of a stage per wave, at most
+    static_assert((SP == 128 || SP == 64) && NH >= 2 && MS <= 2, "stage shape");
     constexpr int STAGE = NPL * WGG_PLANE;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -75,9 +80,9 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
 
-    // load items of a stage: item = plane * 4 + block (32 positions); wave w takes items w, w+8, ...
-    // -> always block w % 4, so one position decode per stage and lane
-    const int my_blk = wave & 3;
+    // load items of a stage: item = plane * BLK + block (32 positions); wave w takes items w, w+8, ...
+    // -> always block w % BLK, so one position decode per stage and lane
+    const int my_blk = wave % BLK;
     auto issue_loads = [&](int s, int buf) {
         unsigned char *base = smem + buf * STAGE;
         const uint32_t m = m_begin + (uint32_t)(s * WGG_SP + my_blk * 32 + (lane >> 1));
@@ -94,8 +99,8 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
         const unsigned dy_off = (unsigned)(((n * KB + kb0) * PQ + rem) * 32) + half;
         const unsigned x_off = (unsigned)(((n * CB + cb0) * HW + h * p.W + w) * 32) + half;
 #pragma unroll
-        for (int j = 0; j < NPL / 2; ++j) {
-            const int pl = (wave >> 2) + 2 * j;                          // plane index of item wave + 8 j
+        for (int j = 0; j < NITEM; ++j) {
+            const int pl = wave / BLK + (NW / BLK) * j;                  // plane index of item wave + 8 j
             unsigned char *dst = base + pl * WGG_PLANE + my_blk * 1024;
             if (pl < 4 * WK) {
                 const unsigned off = in ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
@@ -139,24 +144,16 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
                 for (int k = 0; k < 4; ++k)
                     acc[i][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[k], acc[i][k], 0, 0, 0);
         };
-        // step streams continue across stages (4 steps per stage)
-        int j = (wh - (s * 4) % NH + NH) % NH;
-        if (NH <= 2) {
+        // step streams continue across stages (BLK steps per stage)
+        const int j = (wh - (s * BLK) % NH + NH) % NH;
+        if (MS == 2) {
             // two steps of this stage belong to the wave: fetch the second while multiplying the first
             bf16x8 a0[4], b0[4], a1[4], b1[4];
             fetch(j, a0, b0);
             fetch(j + NH, a1, b1);
             multiply(a0, b0);
-            if (NH == 1) {
-                fetch(j + 2, a0, b0);
-                multiply(a1, b1);
-                fetch(j + 3, a1, b1);
-                multiply(a0, b0);
-                multiply(a1, b1);
-            } else {
-                multiply(a1, b1);
-            }
-        } else if (j < 4) {
+            multiply(a1, b1);
+        } else if (j < BLK) {
             bf16x8 a0[4], b0[4];
             fetch(j, a0, b0);
             multiply(a0, b0);
@@ -236,30 +233,36 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
     }
 }
 
-template <int WK, int WC>
+template <int WK, int WC, int SP>
 static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    size_t lds = (size_t)2 * 4 * (WK + WC) * WGG_PLANE;
+    size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
     dim3 grid(p.nparts, (p.K / (64 * WK)) * p.ctiles, p.R * p.S);
-    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC>), grid, dim3(512), lds, st, p);
+    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
+}
+
+template <int SP>
+static hipError_t launch_wgrad_gemm_sp(const WgradGemmParams &p, hipStream_t st)
+{
+    if (p.wk == 2 && p.wc == 2) return launch_wgrad_gemm_t<2, 2, SP>(p, st);
+    if (p.wk == 2 && p.wc == 1) return launch_wgrad_gemm_t<2, 1, SP>(p, st);
+    if (p.wk == 1 && p.wc == 2) return launch_wgrad_gemm_t<1, 2, SP>(p, st);
+    if (p.wk == 1 && p.wc == 1) return launch_wgrad_gemm_t<1, 1, SP>(p, st);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
 {
-    hipError_t e = hipErrorInvalidValue;
-    if (p.wk == 2 && p.wc == 2) e = launch_wgrad_gemm_t<2, 2>(p, st);
-    else if (p.wk == 2 && p.wc == 1) e = launch_wgrad_gemm_t<2, 1>(p, st);
-    else if (p.wk == 1 && p.wc == 2) e = launch_wgrad_gemm_t<1, 2>(p, st);
-    else if (p.wk == 1 && p.wc == 1) e = launch_wgrad_gemm_t<1, 1>(p, st);
+    const hipError_t e = p.sp == 64 ? launch_wgrad_gemm_sp<64>(p, st) : launch_wgrad_gemm_sp<128>(p, st);
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)p.R * p.S * p.K * p.C / 4;
     NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,

@@ -227,9 +227,13 @@ def test_wgrad_all_taps_channel_group_variants(case, ncq, ring, monkeypatch):
 
 
 @pytest.mark.parametrize("case", [0, 2, 3, 4, 5, 6, 8, 13])
-def test_wgrad_gemm_kernel(case, monkeypatch):
-    """Per-tap GEMM backprop-filters (the all-taps kernel switched off so that 3x3 shapes reach it too)."""
+@pytest.mark.parametrize("sp", [0, 64, 128])
+def test_wgrad_gemm_kernel(case, sp, monkeypatch):
+    """Per-tap GEMM backprop-filters (the all-taps kernel switched off so that 3x3 shapes reach it too);
+    sp = positions per LDS stage (0: the dispatcher's choice)."""
     monkeypatch.setenv("NGC_WGRAD_STRIP", "0")
+    if sp:
+        monkeypatch.setenv("NGC_WGG_SP", str(sp))
     a = MFMA_CASES[case]
     x, w, b, dy = _tensors(a, "bf16", 6000 + case)
     run = Run(a, "bf16", BLK, BLK, True)
