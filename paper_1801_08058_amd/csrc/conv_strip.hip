@@ -140,6 +140,8 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][a][v] = 0.f;
 
+    // the sub-pixel store mode may use no more than 32 of the 64 output columns: skip the upper MFMA
+    const bool upper = !(p.out_mode == 1 && 4 * p.sub_C <= 32);
     const int nchunks = CB;
     issue_loads(0, 0);
     for (int c = 0; c < nchunks; ++c) {
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 if (i < nfrag) {
                     const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
                     acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
-                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+                    if (upper) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
                 }
             }
         }
