@@ -27,17 +27,19 @@ typedef __attribute__((address_space(3))) void lds_void_q;
 constexpr unsigned G1_OOB = 0x80000000u;
 
 // NS = ring depth; KB = 16-channel blocks per stage (4 or 2): a stage holds 2 KB planes (8-channel halves) per operand.
-// NL = loader waves (1 or 2); WM x WN MFMA waves.
-template <int WM, int WN, int NS, int KB, int NL>
+// NL = loader waves (1 or 2); WM x WN MFMA waves; FA = 32-channel output fragments per MFMA wave
+// (2: 64 x 64 wave tiles; 4: 64 positions x 128 channels, 6 instead of 8 LDS operand fetches per 8 MFMAs).
+template <int WM, int WN, int NS, int KB, int NL, int FA>
 __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 {
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int BM = 64 * WM, BN = 32 * FA * WN;
+    constexpr int WB = BN / 64;                       // 64-row blocks of a filter plane
     constexpr int XPLANE = BM * 16 + 128, WPLANE = BN * 16 + 128;
     constexpr int NPL = 2 * KB;                       // planes per operand and stage
     constexpr int STAGE = NPL * XPLANE + NPL * WPLANE;
     constexpr int NCW = WM * WN;                      // MFMA waves
     constexpr int PPL = NPL / NL;                     // planes per loader wave
-    constexpr int LPL = PPL * (WM + WN);              // loads per loader wave per stage
+    constexpr int LPL = PPL * (WM + WB);              // loads per loader wave per stage
     static_assert((NCW == 8 || NCW == 4) && (NL == 1 || NL == 2), "wave roles");
     static_assert(NS >= 2 && NS <= 4 && (KB == 2 || KB == 4), "ring depth / stage size");
     static_assert(LPL * (NS - 2) < 64, "vmcnt range");
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                                                              (int)soff_x, 0, 0);
                 }
 #pragma unroll
-                for (int b = 0; b < WN; ++b)
+                for (int b = 0; b < WB; ++b)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void_q *)(ws + pl * WPLANE + b * 1024), 16,
                                                              (int)(wvoff + b * 64 * 32), (int)soff_w, 0, 0);
             }
@@ -128,9 +130,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     const int l32 = lane & 31;
     const int lg = lane >> 5;
 
-    f32x16 acc[2][2];
+    f32x16 acc[FA][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < FA; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -139,16 +141,16 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     for (int s = 0; s < nsteps; ++s) {
         wg_barrier_nofence();
         const unsigned char *xs = smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;
-        const unsigned char *ws = smem + (s % NS) * STAGE + NPL * XPLANE + lg * WPLANE + (wn * 64 + l32) * 16;
+        const unsigned char *ws = smem + (s % NS) * STAGE + NPL * XPLANE + lg * WPLANE + (wn * 32 * FA + l32) * 16;
 #pragma unroll
         for (int ks = 0; ks < KB; ++ks) {
-            bf16x8 fa[2], fb[2];
+            bf16x8 fa[FA], fb[2];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(ws + (2 * ks) * WPLANE + a * 512);
+            for (int a = 0; a < FA; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(ws + (2 * ks) * WPLANE + a * 512);
 #pragma unroll
             for (int b = 0; b < 2; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(xs + (2 * ks) * XPLANE + b * 512);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < FA; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
@@ -171,8 +173,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         const int ow = (int)j * p.os_w + p.oa_w;
         const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + ow;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            const int co_base = n0 + wn * 64 + a * 32;
+        for (int a = 0; a < FA; ++a) {
+            const int co_base = n0 + wn * 32 * FA + a * 32;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 float v[8];
@@ -220,24 +222,24 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int WM, int WN, int NS, int KB, int NL>
+template <int WM, int WN, int NS, int KB, int NL, int FA = 2>
 static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int BM = 64 * WM, BN = 32 * FA * WN;
     constexpr size_t stage = (size_t)2 * KB * ((BM * 16 + 128) + (BN * 16 + 128));
     // short reductions use fewer ring buffers than NS: less LDS, more workgroups per compute unit
     const int nsteps = p.Cin / (16 * KB);
     const size_t lds = (size_t)(nsteps < NS ? nsteps : NS) * stage;
     const unsigned mtiles = (p.M + BM - 1) / BM;
     const unsigned grid = ((mtiles + 7) / 8) * 8 * (p.Cout / BN);
-    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
+    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
     return hipGetLastError();
 }
 
@@ -246,7 +248,7 @@ static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
 // than the 512 workgroup slots of the chip) and strided forward gathers take 128x128 tiles (4 MFMA
 // waves + 1 loader, three workgroups per compute unit).  NGC_G1_VARIANT (experiments only) forces
 // 64-channel stages (1), a ring of 4 (2), the 128x128 tile with a ring of 3 (3) / 4 (4), or the
-// 256x128 tile whatever the size (5).
+// 256x128 tile whatever the size (5), or the 256x256 tile with 64x128 wave tiles (6; needs Cout % 256 == 0).
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
@@ -254,12 +256,16 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
     if (p.Cout % 128 == 0) {
         if (variant == 0) {
             const unsigned tiles = ((p.M + 255) / 256) * (unsigned)(p.Cout / 128);
-            if (tiles < 2 * 256 || p.is_h > 1 || p.is_w > 1) variant = 3;
+            // long reductions over enough 256 x 256 tiles: 64 x 128 wave tiles (fewer LDS operand fetches
+            // per MFMA; one workgroup per compute unit, which short reductions do not amortise)
+            if (p.Cout % 256 == 0 && p.Cin >= 512 && tiles / 2 >= 192) variant = 6;
+            else if (tiles < 2 * 256 || p.is_h > 1 || p.is_w > 1) variant = 3;
         }
         if (variant == 1) return launch_gemm1x1_t<4, 2, 3, 4, 2>(p, st);
         if (variant == 2) return launch_gemm1x1_t<4, 2, 4, 2, 2>(p, st);
         if (variant == 3) return launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st);
         if (variant == 4) return launch_gemm1x1_t<2, 2, 4, 2, 1>(p, st);
+        if (variant == 6 && p.Cout % 256 == 0) return launch_gemm1x1_t<4, 2, 3, 2, 2, 4>(p, st);
         return launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
     }
     if (variant == 1) return launch_gemm1x1_t<8, 1, 2, 4, 2>(p, st);

@@ -256,7 +256,7 @@ GEMM1X1_CASES = [
 
 
 @pytest.mark.parametrize("case", range(len(GEMM1X1_CASES)))
-@pytest.mark.parametrize("pre,variant", [(True, 0), (False, 0), (True, 1), (True, 2), (True, 3), (True, 4), (True, 5)])
+@pytest.mark.parametrize("pre,variant", [(True, 0), (False, 0), (True, 1), (True, 2), (True, 3), (True, 4), (True, 5), (True, 6)])
 def test_gemm1x1_kernel(case, pre, variant, monkeypatch):
     """variant 0 = the dispatcher's tile, stage size and ring depth; 1..5 = forced tile / stage / ring choices (5 = the large-layer default)."""
     monkeypatch.setenv("NGC_G1_VARIANT", str(variant))
