@@ -113,7 +113,7 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
         const int nblocks = (q.npatch + 63) / 64;
         if (nblocks > 24) continue;
         q.xpitch = nblocks * 1024 + 128;
-        const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)2 * ntaps * (64 * 16 + 128));
+        const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)(out.half_cols ? 1 : 2) * ntaps * (64 * 16 + 128));
         if (lds > LDS_LIMIT) continue;
         q.div_tpq = make_fastdiv((uint32_t)(q.TP * Wout));
         q.div_q = make_fastdiv((uint32_t)Wout);
@@ -225,15 +225,17 @@ bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q)
 }
 
 // Backprop-data of a low-channel stride-2 convolution (the stem) through the strip kernel.
-// Output pixels are grouped into 2x2 blocks (i,j) -> (2i+a, 2j+b); block (i,j), "channel"
-// col = (2a+b)*C + c is a stride-1 convolution of dy over the union of the four residue classes'
-// tap offsets, with a combined filter (zeros where a class has no tap) built by
+// Output pixels are grouped into BH x BW blocks (i,j) -> (BH i + a, BW j + b); block (i,j), "channel"
+// col = (a BW + b)*C + c is a convolution of dy, read at pixel (BH/2 i, BW/2 j), over the union of the
+// classes' tap offsets, with a combined filter (zeros where a class has no tap) built by
 // launch_subpixel_filter.  Columns are padded to 64; the strip kernel stores them as NCHW pixels.
+// Blocks of 4 x 2 pixels: 24 columns for C = 3 (the kernel then skips the upper 32), 20 union taps
+// for 7x7 - fewer MFMAs and LDS operand fetches per output pixel than 2 x 2 blocks with 16 taps.
 struct StemBwdPlan {
     StripParams sp;
     int nf;
     size_t lds;
-    int dr_min, ndr, ds_min, nds;
+    int dr_min, ndr, ds_min, nds, BH, BW;
     size_t wu_bytes;
 };
 
@@ -242,26 +244,31 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
     if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_KCRS)
         return false;
     if (d->stride_h != 2 || d->stride_w != 2 || d->dil_h != 1 || d->dil_w != 1) return false;
-    if (4 * d->c > 64 || d->k % 16 != 0) return false;
+    if (d->k % 16 != 0) return false;
+    StemBwdPlan pl;
+    pl.BW = 2;
+    pl.BH = (4 * 2 * d->c <= 32) ? 4 : 2;
+    const char *fb = getenv("NGC_STEM_BH");                               // tests / experiments only
+    if (fb && atoi(fb) == 2) pl.BH = 2;
+    if (pl.BH * pl.BW * d->c > 64) return false;
     int dr_min = INT_MAX, dr_max = INT_MIN, ds_min = INT_MAX, ds_max = INT_MIN;
-    for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < pl.BH; ++a)
         for (int r = 0; r < d->r; ++r) {
             const int v = a + d->pad_below_h - r;
             if (v & 1) continue;
-            const int dr = v / 2;                              // exact
+            const int dr = v / 2;                                  // exact (v may be negative and even)
             if (dr < dr_min) dr_min = dr;
             if (dr > dr_max) dr_max = dr;
         }
+    for (int b = 0; b < pl.BW; ++b)
         for (int s2 = 0; s2 < d->s; ++s2) {
-            const int v = a + d->pad_below_w - s2;
+            const int v = b + d->pad_below_w - s2;
             if (v & 1) continue;
             const int ds = v / 2;
             if (ds < ds_min) ds_min = ds;
             if (ds > ds_max) ds_max = ds;
         }
-    }
     if (dr_min > dr_max || ds_min > ds_max) return false;
-    StemBwdPlan pl;
     pl.dr_min = dr_min; pl.ndr = dr_max - dr_min + 1;
     pl.ds_min = ds_min; pl.nds = ds_max - ds_min + 1;
     const int ntaps = pl.ndr * pl.nds;
@@ -271,16 +278,21 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
     if (in_bytes >= ((size_t)1 << 31)) return false;
     StripParams q;
     memset(&q, 0, sizeof(q));
-    const int Hout = (d->h + 1) / 2, Wout = (d->w + 1) / 2;
+    const int Hout = (d->h + pl.BH - 1) / pl.BH, Wout = (d->w + pl.BW - 1) / pl.BW;
     q.N = d->n; q.Cin = d->k; q.Hin = P; q.Win = Q; q.Cout = 64; q.Hout = Hout; q.Wout = Wout;
     q.min_dh = dr_min; q.min_dw = ds_min;
     q.ntaps = ntaps;
     q.in_bytes = (uint32_t)in_bytes;
     q.wt_bytes = (uint32_t)pl.wu_bytes;
     q.out_mode = 1;
-    q.sub_C = d->c; q.sub_H = d->h; q.sub_W = d->w;
-    q.sh = q.sw = q.os_h = q.os_w = 1; q.Hfull = Hout; q.Wfull = Wout;
+    q.sub_C = d->c; q.sub_H = d->h; q.sub_W = d->w; q.sub_BH = pl.BH; q.sub_BW = pl.BW;
+    q.sh = pl.BH / 2; q.sw = pl.BW / 2;                                  // dy pixels per block step
+    q.half_cols = pl.BH * pl.BW * d->c <= 32 ? 1 : 0;
+    q.os_h = q.os_w = 1; q.Hfull = Hout; q.Wfull = Wout;
     if (!strip_geometry(q, d->n, Hout, Wout, pl.ndr - 1, pl.nds - 1, ntaps, 64, &pl.nf, &pl.lds)) return false;
+    // rows of the strip can go through LDS if they fit the stage buffers and are made of 16-byte pieces
+    q.sub_stage = (d->w % 8 == 0 && pl.BW * Wout == d->w &&
+                   (size_t)q.TN * d->c * pl.BH * q.TP * d->w * 2 <= pl.lds) ? 1 : 0;
     int t = 0;
     for (int i = 0; i < pl.ndr; ++i)
         for (int j = 0; j < pl.nds; ++j) {
@@ -798,7 +810,8 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         if (!stem_bwd_plan(desc, P, Q, &pl)) return NGC_UNSUPPORTED;
         if (!ws || ws_bytes < round256(pl.wu_bytes)) return NGC_WORKSPACE_TOO_SMALL;
         hipError_t e = launch_subpixel_filter(desc->k, desc->c, desc->r, desc->s, desc->pad_below_h, desc->pad_below_w,
-                                              pl.dr_min, pl.ndr, pl.ds_min, pl.nds, static_cast<const uint16_t *>(w),
+                                              pl.dr_min, pl.ndr, pl.ds_min, pl.nds, pl.BH, pl.BW, 2, 2,
+                                              static_cast<const uint16_t *>(w),
                                               static_cast<uint16_t *>(ws), st);
         if (e != hipSuccess) return launch_status(e);
         pl.sp.in = static_cast<const uint16_t *>(dy);

@@ -146,9 +146,11 @@ struct StripParams {
     int32_t tap_slab[STRIP_MAX_TAPS];
     uint32_t in_bytes, wt_bytes;
     // out_mode 0: 16-channel-blocked [N][Cout/16][Hout][Wout][16].
-    // out_mode 1: "sub-pixel" NCHW: output channel col = (2a+b)*sub_C + c of position (i,j) is
-    //             pixel (2i+a, 2j+b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.
-    int32_t out_mode, sub_C, sub_H, sub_W;
+    // out_mode 1: "sub-pixel" NCHW: output channel col = (a*sub_BW + b)*sub_C + c of position (i,j) is
+    //             pixel (sub_BH*i + a, sub_BW*j + b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.
+    int32_t out_mode, sub_C, sub_H, sub_W, sub_BH, sub_BW;
+    int32_t sub_stage;         // out_mode 1: assemble the strip's pixels in LDS and store whole rows
+    int32_t half_cols;         // only output columns 0..31 of the tile are in use (out_mode 1 with few columns)
     // Positions form a lattice of Hout x Wout per image.  Position (i, j) reads the patch at input
     // pixel (i*sh, j*sw) + tap and is stored at pixel (i*os_h + oa_h, j*os_w + oa_w) of an output
     // tensor of Hfull x Wfull pixels (forward: sh/sw = stride, os = 1; backprop-data: sh = sw = 1,
@@ -286,7 +288,7 @@ hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const
 hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,
                                  void *dst, int dst_layout, hipStream_t st);
 hipError_t launch_subpixel_filter(int K, int C, int R, int S, int pbh, int pbw, int dr_min, int ndr, int ds_min, int nds,
-                                  const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st);
+                                  int BH, int BW, int sh, int sw, const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st);
 hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, const void *w_kcrs, void *dst,
                                  int dst_layout, hipStream_t st);
 

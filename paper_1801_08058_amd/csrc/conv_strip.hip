@@ -41,9 +41,14 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)lds_dst_uniform, 16, (int)voff, (int)soff, 0, 0);
 }
 
-template <int NF, int NW>
+// SUB = 0: blocked output (p.out_mode 0).  SUB = 1 / 2: sub-pixel NCHW output (p.out_mode 1); with
+// SUB = 1 only the lower 32 of the tile's 64 output columns are in use: one filter plane per tap (32
+// rows of g = 0, then 32 rows of g = 1) and no upper MFMA.  The store modes are separate
+// instantiations so that the blocked-output kernel carries none of the sub-pixel code.
+template <int NF, int NW, int SUB = 0>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
+    constexpr bool HALF = SUB == 1;
     constexpr int MAXXB = STRIP_MAXBLOCKS / NW;         // patch blocks per wave
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -62,7 +67,10 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
     const int CB = p.Cin >> 4;
     const int HWin = p.Hin * p.Win;
     const int xplane = p.xpitch;
-    const int stage_bytes = 2 * xplane + 2 * p.ntaps * STRIP_WPITCH;
+    // filter planes of a stage: (tap, g) planes of 64 output channels, or one plane per tap (HALF)
+    constexpr int wstride_t = HALF ? STRIP_WPITCH : 2 * STRIP_WPITCH;
+    constexpr int wstride_g = HALF ? 512 : STRIP_WPITCH;
+    const int stage_bytes = 2 * xplane + p.ntaps * wstride_t;
 
     __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
@@ -109,10 +117,17 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 }
             }
         }
-        for (int j = wave; j < 2 * p.ntaps; j += NW) {                    // plane j = tap*2 + g
-            const int t = j >> 1, g = j & 1;
-            const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32 + 16 * g);
-            load_lds16(rs_wt, ws + j * STRIP_WPITCH, woff_lane, soff_w);
+        if (HALF) {
+            for (int t = wave; t < p.ntaps; t += NW) {                   // lanes 0-31: g = 0, lanes 32-63: g = 1
+                const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32);
+                load_lds16(rs_wt, ws + t * STRIP_WPITCH, (unsigned)((k0 + l32) * 32 + lg * 16), soff_w);
+            }
+        } else {
+            for (int j = wave; j < 2 * p.ntaps; j += NW) {                // plane j = tap*2 + g
+                const int t = j >> 1, g = j & 1;
+                const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32 + 16 * g);
+                load_lds16(rs_wt, ws + j * STRIP_WPITCH, woff_lane, soff_w);
+            }
         }
     };
 
@@ -141,7 +156,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
             for (int v = 0; v < 16; ++v) acc[i][a][v] = 0.f;
 
     // the sub-pixel store mode may use no more than 32 of the 64 output columns: skip the upper MFMA
-    const bool upper = !(p.out_mode == 1 && 4 * p.sub_C <= 32);
+    constexpr bool upper = !HALF;
     const int nchunks = CB;
     issue_loads(0, 0);
     for (int c = 0; c < nchunks; ++c) {
@@ -149,10 +164,11 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         __syncthreads();                                    // ... and everybody else's; stage (c+1)&1 is free
         if (c + 1 < nchunks) issue_loads(c + 1, (c + 1) & 1);
         const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
-        const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * STRIP_WPITCH + l32 * 16;
+        const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
         for (int t = 0; t < p.ntaps; ++t) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + (2 * t) * STRIP_WPITCH);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ws + (2 * t) * STRIP_WPITCH + 32 * 16);
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t);
+            bf16x8 a1 = a0;
+            if (upper) a1 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t + 32 * 16);
             const int toff = p.tap_off[t] * 16;
 #pragma unroll
             for (int i = 0; i < NF; ++i) {
@@ -179,6 +195,56 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
             }
         }
+    if (SUB != 0 && p.sub_stage) {
+        // Sub-pixel NCHW store through LDS: column col = (a*BW+b)*C + c of position (tp, q) of image ti is
+        // pixel (BH tp + a, BW q + b) of channel c; the strip's pixels are assembled as [ti][c][row][WP]
+        // in LDS (the stage buffers are free now) and written out as whole rows with 16-byte stores
+        // (scattered 2-byte stores cost a wave hundreds of cycles each).
+        __syncthreads();
+        uint16_t *ob = reinterpret_cast<uint16_t *>(smem);
+        const int ncol = p.sub_BH * p.sub_BW * p.sub_C;
+        const int ROWS = p.sub_BH * p.TP, WP = p.sub_BW * p.Wout;
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+            if (i >= nfrag) break;
+            const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
+            const bool ok = m < (uint32_t)p.npix;
+            const uint32_t mm = ok ? m : 0;
+            const uint32_t ti = fd_div(mm, p.div_tpq);
+            const uint32_t rem = mm - ti * p.div_tpq.d;
+            const uint32_t tp = fd_div(rem, p.div_q);
+            const uint32_t q = rem - tp * p.div_q.d;
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int col = k0 + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                    if (ok && col < ncol) {
+                        const int ab = col / p.sub_C, c = col - ab * p.sub_C;
+                        const int a2 = ab / p.sub_BW;
+                        const int lrow = p.sub_BH * (int)tp + a2, lcol = p.sub_BW * (int)q + (ab - a2 * p.sub_BW);
+                        ob[(((int)ti * p.sub_C + c) * ROWS + lrow) * WP + lcol] =
+                            (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
+                    }
+                }
+        }
+        __syncthreads();
+        // rows of the strip: (ti, c, lrow) -> global row ((n0+ti)*C + c, BH*p0 + lrow); sub_W % 8 == 0
+        const int chunks = p.sub_W >> 3;                                 // 16-byte pieces per row
+        const int nrows = p.TN * p.sub_C * ROWS;
+        for (int e = tid; e < nrows * chunks; e += NW * 64) {
+            const int row = e / chunks, ch = e - row * chunks;
+            const int lrow = row % ROWS;
+            const int tc = row / ROWS;
+            const int ti = tc / p.sub_C, c = tc - ti * p.sub_C;
+            const int n = n0 + ti, y = p.sub_BH * p0 + lrow;
+            if (n < p.N && y < p.sub_H && lrow < p.sub_BH * (p.Hout - p0 < p.TP ? p.Hout - p0 : p.TP)) {
+                const uint4 val = *reinterpret_cast<const uint4 *>(ob + (size_t)row * WP + ch * 8);
+                *reinterpret_cast<uint4 *>(p.out + (((size_t)n * p.sub_C + c) * p.sub_H + y) * p.sub_W + ch * 8) = val;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         if (i >= nfrag) break;
@@ -193,9 +259,9 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         const int oh = p0 + (int)tp;
         ok = ok && n < p.N && oh < p.Hout;
         const size_t pix = (size_t)n * CBout * HWout + (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
-        if (p.out_mode == 1) {
-            // sub-pixel NCHW store: column col = (2a+b)*C + c -> pixel (2 oh + a, 2 q + b) of channel c
-            const int ncol = 4 * p.sub_C;
+        if (SUB != 0) {
+            // sub-pixel NCHW store: column col = (a*BW+b)*C + c -> pixel (BH oh + a, BW q + b) of channel c
+            const int ncol = p.sub_BH * p.sub_BW * p.sub_C;
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -203,7 +269,8 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                     const int col = k0 + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
                     if (ok && col < ncol) {
                         const int ab = col / p.sub_C, c = col - ab * p.sub_C;
-                        const int hh = 2 * oh + (ab >> 1), ww = 2 * (int)q + (ab & 1);
+                        const int a2 = ab / p.sub_BW;
+                        const int hh = p.sub_BH * oh + a2, ww = p.sub_BW * (int)q + (ab - a2 * p.sub_BW);
                         if (hh < p.sub_H && ww < p.sub_W)
                             p.out[(((size_t)n * p.sub_C + c) * p.sub_H + hh) * p.sub_W + ww] =
                                 (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
@@ -244,18 +311,18 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 }
 
 
-template <int NF, int NW>
+template <int NF, int NW, int SUB = 0>
 static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static bool attr_set = false;                   // raise the dynamic LDS limit once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.groups * p.strips, p.Cout / 64);
-    NGC_LAUNCH((conv_strip_bf16<NF, NW>), grid, dim3(NW * 64), lds_bytes, st, p);
+    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
 
@@ -264,6 +331,22 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st)
 {
     static const int two_waves = getenv("NGC_STRIP_1WAVE") ? 0 : 1;
+    if (p.out_mode == 1 && p.half_cols) {
+        switch (nf) {
+        case 7: return launch_strip_nf<4, 8, 1>(p, lds_bytes, st);
+        case 4: return launch_strip_nf<2, 8, 1>(p, lds_bytes, st);
+        case 2: return launch_strip_nf<1, 8, 1>(p, lds_bytes, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    if (p.out_mode == 1) {
+        switch (nf) {
+        case 7: return launch_strip_nf<4, 8, 2>(p, lds_bytes, st);
+        case 4: return launch_strip_nf<2, 8, 2>(p, lds_bytes, st);
+        case 2: return launch_strip_nf<1, 8, 2>(p, lds_bytes, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (nf) {
     case 7: return two_waves ? launch_strip_nf<4, 8>(p, lds_bytes, st) : launch_strip_nf<7, 4>(p, lds_bytes, st);
     case 4: return two_waves ? launch_strip_nf<2, 8>(p, lds_bytes, st) : launch_strip_nf<4, 4>(p, lds_bytes, st);

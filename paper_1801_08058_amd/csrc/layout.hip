@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void filter_to_blocked(const E *__restrict__ s
 // s = b + pad_w - 2 ds when that tap exists, else 0.
 __global__ __launch_bounds__(256) void subpixel_filter(const uint16_t *__restrict__ w, uint16_t *__restrict__ wu, int K,
                                                        int C, int R, int S, int pbh, int pbw, int dr_min, int ds_min,
-                                                       int nds, size_t total)
+                                                       int nds, int BH, int BW, int sh, int sw, size_t total)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
@@ -202,21 +202,21 @@ __global__ __launch_bounds__(256) void subpixel_filter(const uint16_t *__restric
     const int ut = (int)t;
     const int dr = dr_min + ut / nds, ds = ds_min + ut % nds;
     uint16_t v = 0;
-    if (col < 4 * C) {
+    if (col < BH * BW * C) {
         const int ab = col / C, c = col - ab * C;
-        const int a = ab >> 1, b = ab & 1;
-        const int r = a + pbh - 2 * dr, s = b + pbw - 2 * ds;
+        const int a = ab / BW, b = ab - a * BW;
+        const int r = a + pbh - sh * dr, s = b + pbw - sw * ds;
         if (r >= 0 && r < R && s >= 0 && s < S) v = w[(((size_t)(kb * 16 + ki) * C + c) * R + r) * S + s];
     }
     wu[i] = v;
 }
 
 hipError_t launch_subpixel_filter(int K, int C, int R, int S, int pbh, int pbw, int dr_min, int ndr, int ds_min, int nds,
-                                  const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st)
+                                  int BH, int BW, int sh, int sw, const uint16_t *w_kcrs, uint16_t *wu, hipStream_t st)
 {
     const size_t total = (size_t)ndr * nds * K * 64;
     NGC_LAUNCH(subpixel_filter, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w_kcrs, wu, K, C, R, S, pbh, pbw,
-               dr_min, ds_min, nds, total);
+               dr_min, ds_min, nds, BH, BW, sh, sw, total);
     return hipGetLastError();
 }
 

@@ -391,9 +391,19 @@ STEM_CASES = [
 
 
 @pytest.mark.parametrize("case", range(len(STEM_CASES)))
-def test_stem_kernels_small(case):
+@pytest.mark.parametrize("bh", [0, 2])
+def test_stem_kernels_small(case, bh, monkeypatch):
+    """bh: rows per sub-pixel block of the backprop-data formulation (0: the dispatcher's 4 x 2 blocks, 2: 2 x 2)."""
+    if bh:
+        monkeypatch.setenv("NGC_STEM_BH", str(bh))
     a = STEM_CASES[case]
     _check_all(a, "bf16", NCHW, BLK, False, 5000 + case, ("stem_fwd", "", ""))
+
+
+def test_stem_backprop_data_unstaged_store():
+    """Width not a multiple of 8: the sub-pixel store cannot go through whole 16-byte row pieces."""
+    a = Attrs(2, 3, 30, 44, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3)
+    _check_all(a, "bf16", NCHW, BLK, False, 5100, ("", "stem_bwd", ""))
 
 
 def test_cfg4_stem_reduced_batch():
