@@ -293,6 +293,20 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
     // rows of the strip can go through LDS if they fit the stage buffers and are made of 16-byte pieces
     q.sub_stage = (d->w % 8 == 0 && pl.BW * Wout == d->w &&
                    (size_t)q.TN * d->c * pl.BH * q.TP * d->w * 2 <= pl.lds) ? 1 : 0;
+    {
+        const int ROWS = pl.BH * q.TP, WP = pl.BW * Wout;
+        for (int col = 0; col < 64; ++col) {
+            q.sub_off[col] = -1;
+            if (col < pl.BH * pl.BW * d->c) {
+                const int ab = col / d->c, c = col - ab * d->c;
+                const int a = ab / pl.BW, b = ab - a * pl.BW;
+                q.sub_off[col] = (c * ROWS + a) * WP + b;
+            }
+        }
+        q.div_chunks = make_fastdiv((uint32_t)(d->w / 8 > 0 ? d->w / 8 : 1));
+        q.div_rows = make_fastdiv((uint32_t)ROWS);
+        q.div_subc = make_fastdiv((uint32_t)d->c);
+    }
     int t = 0;
     for (int i = 0; i < pl.ndr; ++i)
         for (int j = 0; j < pl.nds; ++j) {

@@ -150,6 +150,9 @@ struct StripParams {
     //             pixel (sub_BH*i + a, sub_BW*j + b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.
     int32_t out_mode, sub_C, sub_H, sub_W, sub_BH, sub_BW;
     int32_t sub_stage;         // out_mode 1: assemble the strip's pixels in LDS and store whole rows
+    int32_t sub_off[64];       // sub_stage: element offset of column col inside the staged [c][row][WP] block of
+                               // a position, (c*ROWS + a)*WP + b, or -1 for padding columns
+    FastDiv div_chunks, div_rows, div_subc;   // sub_stage row copy: 16-byte pieces per row, rows per channel, channels
     int32_t half_cols;         // only output columns 0..31 of the tile are in use (out_mode 1 with few columns)
     // Positions form a lattice of Hout x Wout per image.  Position (i, j) reads the patch at input
     // pixel (i*sh, j*sw) + tap and is stored at pixel (i*os_h + oa_h, j*os_w + oa_w) of an output

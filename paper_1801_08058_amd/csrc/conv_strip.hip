@@ -202,8 +202,18 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         // (scattered 2-byte stores cost a wave hundreds of cycles each).
         __syncthreads();
         uint16_t *ob = reinterpret_cast<uint16_t *>(smem);
-        const int ncol = p.sub_BH * p.sub_BW * p.sub_C;
         const int ROWS = p.sub_BH * p.TP, WP = p.sub_BW * p.Wout;
+        // element offsets of this lane's 16 (32) columns inside a position's block: the column of
+        // accumulator register v is a*32 + 8*(v/4) + 4*lg + v%4 (table from the host, -1 = padding)
+        constexpr int NA = HALF ? 1 : 2;
+        int coff[NA][16];
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c0 = a * 32 + 8 * (v >> 2) + (v & 3);
+                coff[a][v] = lg ? p.sub_off[c0 + 4] : p.sub_off[c0];
+            }
 #pragma unroll
         for (int i = 0; i < NF; ++i) {
             if (i >= nfrag) break;
@@ -214,31 +224,25 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
             const uint32_t rem = mm - ti * p.div_tpq.d;
             const uint32_t tp = fd_div(rem, p.div_q);
             const uint32_t q = rem - tp * p.div_q.d;
+            const int base = ((int)ti * p.sub_C * ROWS + p.sub_BH * (int)tp) * WP + p.sub_BW * (int)q;
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < NA; ++a)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int col = k0 + a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    if (ok && col < ncol) {
-                        const int ab = col / p.sub_C, c = col - ab * p.sub_C;
-                        const int a2 = ab / p.sub_BW;
-                        const int lrow = p.sub_BH * (int)tp + a2, lcol = p.sub_BW * (int)q + (ab - a2 * p.sub_BW);
-                        ob[(((int)ti * p.sub_C + c) * ROWS + lrow) * WP + lcol] =
-                            (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
-                    }
-                }
+                for (int v = 0; v < 16; ++v)
+                    if (ok && coff[a][v] >= 0)
+                        ob[base + coff[a][v]] = (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
         }
         __syncthreads();
         // rows of the strip: (ti, c, lrow) -> global row ((n0+ti)*C + c, BH*p0 + lrow); sub_W % 8 == 0
         const int chunks = p.sub_W >> 3;                                 // 16-byte pieces per row
         const int nrows = p.TN * p.sub_C * ROWS;
+        const int vrows = p.sub_BH * (p.Hout - p0 < p.TP ? p.Hout - p0 : p.TP);
         for (int e = tid; e < nrows * chunks; e += NW * 64) {
-            const int row = e / chunks, ch = e - row * chunks;
-            const int lrow = row % ROWS;
-            const int tc = row / ROWS;
-            const int ti = tc / p.sub_C, c = tc - ti * p.sub_C;
+            const int row = (int)fd_div((uint32_t)e, p.div_chunks), ch = e - row * chunks;
+            const int tc = (int)fd_div((uint32_t)row, p.div_rows), lrow = row - tc * ROWS;
+            const int ti = (int)fd_div((uint32_t)tc, p.div_subc), c = tc - ti * p.sub_C;
             const int n = n0 + ti, y = p.sub_BH * p0 + lrow;
-            if (n < p.N && y < p.sub_H && lrow < p.sub_BH * (p.Hout - p0 < p.TP ? p.Hout - p0 : p.TP)) {
+            if (n < p.N && y < p.sub_H && lrow < vrows) {
                 const uint4 val = *reinterpret_cast<const uint4 *>(ob + (size_t)row * WP + ch * 8);
                 *reinterpret_cast<uint4 *>(p.out + (((size_t)n * p.sub_C + c) * p.sub_H + y) * p.sub_W + ch * 8) = val;
             }
