@@ -336,15 +336,27 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     if (q.SR > P) q.SR = P;
     q.PRS = q.SR + span_h;
     q.PC = Q + span_w;
-    const int nblk_x = (q.PRS * q.PC + 31) / 32;
-    const int nblk_dy = (q.SR * Q + 31) / 32;                           // 32-position steps per stage
-    q.dyplane = nblk_dy * 1024 + 128;
-    q.xplane = nblk_x * 1024 + 128;
     // channel groups per workgroup: few (k,c) tiles -> narrower c per workgroup, longer position chunks
     const int tiles64 = (d->k / 64) * (d->c / 64);
     q.ncq = tiles64 <= 4 ? 2 : 4;
     const char *fq = getenv("NGC_WGRAD_NCQ");
     if (fq && (atoi(fq) == 1 || atoi(fq) == 2 || atoi(fq) == 4)) q.ncq = atoi(fq);
+    // small images: several whole images per stage (a stage of one 7x7 image would be 1.5 steps),
+    // as many as a workgroup's share of the batch allows
+    q.G = 1;
+    {
+        const int tiles_g = (d->k / 64) * (d->c / (16 * q.ncq));
+        const int parts_g = tiles_g >= NUM_CUS ? 1 : (NUM_CUS + tiles_g - 1) / tiles_g;
+        const char *fg = getenv("NGC_WGRAD_G1");                        // tests / experiments only: one image per stage
+        if (q.SR == P && 2 * P * Q <= 224 && parts_g <= d->n && !(fg && atoi(fg) == 1)) {
+            q.G = 224 / (P * Q);
+            if (q.G > d->n / parts_g) q.G = d->n / parts_g;
+        }
+    }
+    const int nblk_x = (q.G * q.PRS * q.PC + 31) / 32;
+    const int nblk_dy = (q.G > 1 ? q.G * P * Q + 31 : q.SR * Q + 31) / 32;   // 32-position steps per stage
+    q.dyplane = nblk_dy * 1024 + 128;
+    q.xplane = nblk_x * 1024 + 128;
     if (4 * nblk_dy + q.ncq * nblk_x > 80) return false;                // load items per stage (10 per wave)
     const size_t stage = (size_t)4 * q.dyplane + (size_t)q.ncq * q.xplane;
     q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
@@ -382,6 +394,8 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     q.dy_bytes = (uint32_t)dy_bytes;
     q.div_q = make_fastdiv((uint32_t)Q);
     q.div_pc = make_fastdiv((uint32_t)q.PC);
+    q.div_pq = make_fastdiv((uint32_t)(P * Q));
+    q.div_patch = make_fastdiv((uint32_t)(q.PRS * q.PC));
     if (wp) *wp = q;
     if (lds_out) *lds_out = lds;
     return true;

@@ -192,9 +192,10 @@ struct WgradStripParams {
     int32_t dyplane, xplane;   // bytes per 16-channel plane of a stage
     int32_t ncq;               // 16-channel groups of c per workgroup (4, 2 or 1)
     int32_t nring;             // LDS stage buffers (2 or 3)
+    int32_t G;                 // whole images per stage (small images; 1 = row blocks of one image)
     int32_t ctiles;            // C / (16 * ncq)
     uint32_t x_bytes, dy_bytes;
-    FastDiv div_q, div_pc;
+    FastDiv div_q, div_pc, div_pq, div_patch;
 };
 
 // ---- low-channel stem forward (C <= 3, 7x7 stride 2, NCHW in, blocked out) ----

@@ -85,7 +85,9 @@ __device__ __forceinline__ void wait_vmcnt(int n)
 // NCQ = 16-channel groups of c per workgroup (4, 2 or 1); the 8 waves are NCQ channel groups x
 // NH = 8/NCQ interleaved step streams.  Fewer channels per workgroup means fewer, longer position
 // chunks for the same number of workgroups, i.e. fewer partial copies of dw to write and re-read.
-template <int NCQ>
+// MULTI: stages of several whole images (p.G of them); a separate instantiation so that the
+// one-image path carries none of the extra index arithmetic.
+template <int NCQ, bool MULTI>
 __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p)
 {
     constexpr int NW = 8;
@@ -117,16 +119,22 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
 
-    const int npatch = p.PRS * p.PC;
+    // G > 1: a stage holds G whole (small) images: positions and patch pixels are numbered image after
+    // image (G = 1: one image, SR of its rows)
+    const int G = MULTI ? p.G : 1;
+    const int npatch1 = p.PRS * p.PC;                       // patch pixels of one image
+    const int npatch = G * npatch1;
     const int nblk_x = (npatch + 31) >> 5;
-    const int steps_full = (p.SR * p.Q + 31) >> 5;           // 32-position steps of a full stage
+    const int stage_pos = MULTI ? G * PQ : p.SR * p.Q;      // positions of a full stage
+    const int steps_full = (stage_pos + 31) >> 5;           // 32-position steps of a full stage
     const int nblk_dy = steps_full;
 
     // load items of a stage: (plane, 32-position block) pairs, 4 dy planes then NCQ x planes,
     // dealt round-robin to the 8 waves.  What does not change from stage to stage is computed once
     // per lane and item (the address arithmetic would otherwise cost more issue cycles than the MFMAs
     // of a stage): item_off = byte offset relative to the stage origin (WS_OOB if the lane never
-    // loads), item_row = position (dy) or patch row (x) that decides validity in a given stage.
+    // loads), item_row = what decides validity in a given stage: the position (dy), the patch row
+    // (x, G = 1) or the image inside the stage (x, G > 1; rows are then always the whole image).
     const int items_dy = 4 * nblk_dy;
     const int items = items_dy + NCQ * nblk_x;
     unsigned item_off[WS_MAXI];
@@ -139,27 +147,34 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         if (it < items_dy) {
             const int blk = it % nblk_dy;
             const int pos = blk * 32 + (lane >> 1);
-            item_off[i] = (unsigned)(pos * 32 + (lane & 1) * 16);
+            const uint32_t g = MULTI ? fd_div((uint32_t)pos, p.div_pq) : 0;     // image inside the stage
+            item_off[i] = (unsigned)(((int)g * (KB - 1) * PQ + pos) * 32 + (lane & 1) * 16);
             item_row[i] = pos;
         } else if (it < items) {
             const int blk = (it - items_dy) % nblk_x;
             const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
-            const uint32_t pr = fd_div(px, p.div_pc);
-            const uint32_t pc = px - pr * p.div_pc.d;
+            const uint32_t g = MULTI ? fd_div(px, p.div_patch) : 0;
+            const uint32_t px1 = px - g * (uint32_t)npatch1;
+            const uint32_t pr = fd_div(px1, p.div_pc);
+            const uint32_t pc = px1 - pr * p.div_pc.d;
             const int w = p.min_dw + (int)pc;
-            if (px < (uint32_t)npatch && (unsigned)w < (unsigned)p.W)
-                item_off[i] = (unsigned)(((int)pr * p.W + (int)pc) * 32 + (lane & 1) * 16);
-            item_row[i] = (int)pr;
+            bool ok = px < (uint32_t)npatch && (unsigned)w < (unsigned)p.W;
+            if (MULTI) ok = ok && (unsigned)(p.min_dh + (int)pr) < (unsigned)p.H;   // stage = whole images: rows fixed
+            if (ok) item_off[i] = (unsigned)((((int)g * CB * p.H + (int)pr) * p.W + (int)pc) * 32 + (lane & 1) * 16);
+            item_row[i] = MULTI ? (int)g : (int)pr;
         }
     }
     auto issue_loads = [&](int stage_lin, int buf) {
-        const int img = n0 + stage_lin / p.nstages;                      // stages run image by image
-        const int stage_i = stage_lin - (stage_lin / p.nstages) * p.nstages;
+        // stages run image by image (G = 1: nstages row blocks per image; G > 1: G images per stage)
+        const int img = n0 + (MULTI ? stage_lin * G : stage_lin / p.nstages);
+        const int stage_i = MULTI ? 0 : stage_lin - (stage_lin / p.nstages) * p.nstages;
         unsigned char *base = smem + buf * stage_bytes;
         const int r0 = stage_i * p.SR;                                   // first strip row of the stage
         int rows = rows_strip - r0;
         if (rows > p.SR) rows = p.SR;
-        const int nvalid = rows * p.Q;                                   // positions of the stage that exist
+        int gvalid = nimg - stage_lin * G;                               // images of the stage that exist (G > 1)
+        if (gvalid > G) gvalid = G;
+        const int nvalid = MULTI ? gvalid * PQ : rows * p.Q;             // positions of the stage that exist
         const int h0 = p0 + r0 + p.min_dh;
         // stage origins (x: pixel (h0, min_dw), possibly outside the image; valid lanes end up in range)
         const unsigned dy_org = (unsigned)((((img * KB + kt * 4) * PQ) + (p0 + r0) * p.Q) * 32);
@@ -175,7 +190,8 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             } else if (it < items) {
                 const int itx = it - items_dy;
                 const int pln = itx / nblk_x, blk = itx - pln * nblk_x;
-                const bool ok = item_off[i] != WS_OOB && (unsigned)(h0 + item_row[i]) < (unsigned)p.H;
+                const bool ok = item_off[i] != WS_OOB &&
+                                (MULTI ? item_row[i] < gvalid : (unsigned)(h0 + item_row[i]) < (unsigned)p.H);
                 const unsigned off = ok ? x_org + (unsigned)(pln * HW * 32) + item_off[i] : WS_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(base + 4 * p.dyplane + pln * p.xplane + blk * 1024),
                                                          16, (int)off, 0, 0, 0);
@@ -191,7 +207,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[a][t][v] = 0.f;
 
-    const int last_pos = p.SR * p.Q - 1;
+    const int last_pos = stage_pos - 1;
     // byte offset of this lane inside a transposed 4x16 block: row L/4 (32 B each), 8-byte column group L%4
     const int lane_col = (L & 3) * 8;
 
@@ -202,15 +218,17 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             int pos = step * 32 + e * 16 + grp * 4 + (L >> 2);
             dyoff[e] = pos * 32 + lane_col;
             if (pos > last_pos) pos = last_pos;                          // dy is zero there; keep x in range
-            const uint32_t row = fd_div((uint32_t)pos, p.div_q);
-            const uint32_t col = (uint32_t)pos - row * p.div_q.d;
-            xoff[e] = (int)(row * p.PC + col) * 32 + lane_col;
+            const uint32_t g = MULTI ? fd_div((uint32_t)pos, p.div_pq) : 0;
+            const uint32_t pos1 = (uint32_t)pos - g * (uint32_t)PQ;
+            const uint32_t row = fd_div(pos1, p.div_q);
+            const uint32_t col = pos1 - row * p.div_q.d;
+            xoff[e] = (int)((g * p.PRS + row) * p.PC + col) * 32 + lane_col;
         }
     };
 
     // Ring of p.nring (2 or 3) stage buffers.  Every stage costs this wave the same number of
     // loads (lpw), so "stage s has landed" is vmcnt <= lpw * (stages issued after s).
-    const int total_stages = nimg * p.nstages;
+    const int total_stages = MULTI ? (nimg + G - 1) / G : nimg * p.nstages;
     const int lpw = (items - wave + NW - 1) / NW;
     const int ahead = p.nring - 1;
     for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s, s);
@@ -222,7 +240,9 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         if (s + ahead < total_stages) issue_loads(s + ahead, (buf + ahead) % p.nring);
         int rows = rows_strip - (s % p.nstages) * p.SR;
         if (rows > p.SR) rows = p.SR;
-        const int nsteps = (rows * p.Q + 31) >> 5;          // steps that contain at least one position
+        int gv = nimg - s * G;
+        if (gv > G) gv = G;
+        const int nsteps = ((MULTI ? gv * PQ : rows * p.Q) + 31) >> 5;      // steps that contain at least one position
         const unsigned char *dys = smem + buf * stage_bytes;
         const unsigned char *xs = smem + buf * stage_bytes + 4 * p.dyplane + cq * p.xplane;
         buf = (buf + 1 == p.nring) ? 0 : buf + 1;
@@ -346,27 +366,35 @@ __global__ __launch_bounds__(256) void wgrad_strip_reduce(const f32x4 *__restric
     }
 }
 
-template <int NCQ>
+template <int NCQ, bool MULTI>
 static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ, MULTI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
-    NGC_LAUNCH(wgrad_strip_bf16<NCQ>, grid, dim3(512), lds_bytes, st, p);
+    NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI>), grid, dim3(512), lds_bytes, st, p);
     return hipGetLastError();
 }
 
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
-    hipError_t e = p.ncq == 4   ? launch_wgrad_strip_ncq<4>(p, lds_bytes, st)
-                   : p.ncq == 2 ? launch_wgrad_strip_ncq<2>(p, lds_bytes, st)
-                   : p.ncq == 1 ? launch_wgrad_strip_ncq<1>(p, lds_bytes, st)
-                                : hipErrorInvalidValue;
+    hipError_t e = hipErrorInvalidValue;
+    if (p.G > 1) {
+        e = p.ncq == 4 ? launch_wgrad_strip_ncq<4, true>(p, lds_bytes, st)
+            : p.ncq == 2 ? launch_wgrad_strip_ncq<2, true>(p, lds_bytes, st)
+            : p.ncq == 1 ? launch_wgrad_strip_ncq<1, true>(p, lds_bytes, st)
+                         : hipErrorInvalidValue;
+    } else {
+        e = p.ncq == 4 ? launch_wgrad_strip_ncq<4, false>(p, lds_bytes, st)
+            : p.ncq == 2 ? launch_wgrad_strip_ncq<2, false>(p, lds_bytes, st)
+            : p.ncq == 1 ? launch_wgrad_strip_ncq<1, false>(p, lds_bytes, st)
+                         : hipErrorInvalidValue;
+    }
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)WS_NT * p.K * p.C / 4;
     NGC_LAUNCH(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,

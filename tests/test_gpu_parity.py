@@ -226,6 +226,30 @@ def test_wgrad_all_taps_channel_group_variants(case, ncq, ring, monkeypatch):
     assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
 
 
+SMALL_IMAGE_WGRAD_CASES = [
+    # n   c    h  w  k    r  s  sh sw dh dw pbh pbw pah paw
+    Attrs(70, 64, 7, 7, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # 4 images per stage, ragged last stage
+    Attrs(33, 128, 7, 7, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # two c tiles
+    Attrs(21, 64, 9, 5, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # 9x5 images (45 positions), two k tiles
+    Attrs(13, 64, 6, 10, 64, 3, 3, 1, 1, 2, 1, 2, 1, 2, 1),      # dilation 2 in h: 3 images of 60 positions
+    Attrs(9, 64, 3, 3, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),        # 3x3 images: 24 per stage, fewer than that exist
+]
+
+
+@pytest.mark.parametrize("case", range(len(SMALL_IMAGE_WGRAD_CASES)))
+@pytest.mark.parametrize("g1", [False, True])
+def test_wgrad_all_taps_small_images(case, g1, monkeypatch):
+    """Stages of several whole images (g1: forced back to one image per stage)."""
+    if g1:
+        monkeypatch.setenv("NGC_WGRAD_G1", "1")
+    a = SMALL_IMAGE_WGRAD_CASES[case]
+    x, w, b, dy = _tensors(a, "bf16", 9000 + case)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_strip_bf16"
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
+
+
 @pytest.mark.parametrize("case", [0, 2, 3, 4, 5, 6, 8, 13])
 @pytest.mark.parametrize("sp", [0, 64, 128])
 def test_wgrad_gemm_kernel(case, sp, monkeypatch):
