@@ -430,9 +430,21 @@ def test_stem_backprop_data_unstaged_store():
     _check_all(a, "bf16", NCHW, BLK, False, 5100, ("", "stem_bwd", ""))
 
 
+def test_cfg4_stem_full_size_sampled():
+    _sampled_layer_check(synth_inputs.config_layers(4)[0], n_y=50_000, n_dw=512)
+
+
 def test_cfg4_stem_reduced_batch():
     L = synth_inputs.config_layers(4, batch=4)[0]
     _sampled_layer_check(L, n_y=50_000, n_dw=512)
+
+
+@pytest.mark.parametrize("idx", range(23))
+def test_cfg5_shapes_full_batch(idx):
+    """Batch 128, i.e. the launch configurations the benchmark times: tile shapes, stage sizes, position
+    chunks and images per stage depend on the batch."""
+    L = synth_inputs.config_layers(5)[idx]
+    _sampled_layer_check(L, n_y=20_000, n_dw=256)
 
 
 @pytest.mark.parametrize("idx", range(23))
