@@ -102,7 +102,15 @@ def test_kernel_selection_and_sizes():
     d = _good(n=64, h=56, w=56, w_layout=ng.NGC_BLOCKED_FWD)
     assert ng.ngc_conv_variant(d, ng.NGC_OP_FWD) == "strip_bf16"
     s2 = _good(n=64, h=56, w=56, stride=(2, 2), w_layout=ng.NGC_BLOCKED_FWD)
-    assert ng.ngc_conv_variant(s2, ng.NGC_OP_FWD).startswith("igemm")
+    assert ng.ngc_conv_variant(s2, ng.NGC_OP_FWD) == "strip_bf16"            # strided strips
+    s2b = _good(n=64, h=56, w=56, stride=(2, 2), w_layout=ng.NGC_BLOCKED_BWD)
+    assert ng.ngc_conv_variant(s2b, ng.NGC_OP_BWD_DATA) == "strip_bf16"      # one launch per residue class
+    # stride 2 with dilation 2: the odd rows of dx have no tap -> the gather kernel (it writes their zeros)
+    s2d = _good(n=2, h=15, w=9, stride=(2, 1), dilation=(2, 1), pad_below=(2, 0), w_layout=ng.NGC_BLOCKED_BWD)
+    assert ng.ngc_conv_variant(s2d, ng.NGC_OP_BWD_DATA).startswith("igemm")
+    one = _good(n=64, h=56, w=56, r=1, s=1, pad_below=(0, 0), pad_above=(0, 0), w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv_variant(one, ng.NGC_OP_FWD) == "gemm1x1_bf16"
+    assert ng.ngc_conv_variant(one, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
     assert ng.ngc_conv_variant(d, ng.NGC_OP_BWD_FILTERS).startswith("wgrad")
     assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56
     assert ng.ngc_filter_elems(d, ng.NGC_BLOCKED_FWD) == 9 * 4 * 64 * 16
