@@ -7,4 +7,5 @@ from .conv_oracle import (  # noqa: F401
     Attrs, build, out_shape, conv_fwd, conv_fwd_at, conv_bwd_data, conv_bwd_data_gather,
     conv_bwd_data_at, conv_bwd_filters, conv_bwd_filters_at, nchw_to_blocked16,
     blocked16_to_nchw, f32_to_bf16_bits_rne, bf16_bits_to_f64, max_normalised_error,
+    relu_bwd_mask, bias_grad, conv_bwd_data_relu,
 )

@@ -82,9 +82,12 @@ def _load():
     lib.ref_f32_bits_to_bf16_rne.restype = ctypes.c_uint16
     lib.ref_f32_bits_to_bf16_rne.argtypes = [ctypes.c_uint32]
     lib.ref_f32_to_bf16_rne_array.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    lib.ref_relu_bwd_mask.argtypes = [ctypes.c_int64, _D, _D, _D]
+    lib.ref_bias_grad.argtypes = [ctypes.c_int32] * 4 + [_D, _D]
     for f in ("ref_conv_fwd", "ref_conv_fwd_at", "ref_conv_bwd_data", "ref_conv_bwd_data_gather",
               "ref_conv_bwd_data_at", "ref_conv_bwd_filters", "ref_conv_bwd_filters_at",
-              "ref_nchw_to_blocked16", "ref_blocked16_to_nchw", "ref_f32_to_bf16_rne_array"):
+              "ref_nchw_to_blocked16", "ref_blocked16_to_nchw", "ref_f32_to_bf16_rne_array",
+              "ref_relu_bwd_mask", "ref_bias_grad"):
         getattr(lib, f).restype = None
     _lib = lib
     return lib
@@ -171,6 +174,31 @@ def conv_bwd_filters_at(a: Attrs, x, dy, flat_idx) -> np.ndarray:
     out = np.empty(idx.shape[0], dtype=np.float64)
     _load().ref_conv_bwd_filters_at(ctypes.byref(a._c()), x, dy, idx.shape[0], idx, out)
     return out
+
+
+def relu_bwd_mask(g, z) -> np.ndarray:
+    """ReLU backprop: g where z > 0, else 0 (z: the ReLU's output, or equally its input)."""
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    assert g.shape == z.shape
+    out = np.empty_like(g)
+    _load().ref_relu_bwd_mask(g.size, g.reshape(-1), z.reshape(-1), out.reshape(-1))
+    return out
+
+
+def bias_grad(dy) -> np.ndarray:
+    """db[k] = sum over n, p, q of dy[n,k,p,q]."""
+    dy = np.ascontiguousarray(dy, dtype=np.float64)
+    n, k, p, q = dy.shape
+    db = np.empty(k, dtype=np.float64)
+    _load().ref_bias_grad(n, k, p, q, dy.reshape(-1), db)
+    return db
+
+
+def conv_bwd_data_relu(a: Attrs, dy, w, x_in) -> np.ndarray:
+    """ConvolutionBackpropData followed by the backprop of the ReLU that produced the convolution's
+    input: dx[i] if x_in[i] > 0 else 0 (the two ops in the order the derivative graph has them)."""
+    return relu_bwd_mask(conv_bwd_data(a, dy, w), x_in)
 
 
 def _elem_bytes(arr: np.ndarray) -> int:

@@ -286,3 +286,27 @@ void ref_f32_to_bf16_rne_array(int64_t count, const uint32_t *f32_bits, uint16_t
 {
     for (int64_t i = 0; i < count; ++i) bf16_bits[i] = ref_f32_bits_to_bf16_rne(f32_bits[i]);
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Backward-direction compounding (the derivative of the compounded bias + ReLU forward op;
+ * the paper's Sec. 3 obtains derivative graphs by autodiff of the forward ops, Sec. 1 / 4 name
+ * the compounding of ops as a backend optimisation; it prints no formula).
+ *
+ *   ReLU backprop:   g'[i] = g[i] if z[i] > 0 else 0       (z = the ReLU's output or input: same sign test)
+ *   bias gradient:   db[k] = sum_{n,p,q} dy[n,k,p,q]       (adjoint of broadcasting b over n, p, q)
+ * ------------------------------------------------------------------------------------------ */
+void ref_relu_bwd_mask(int64_t count, const double *g, const double *z, double *out)
+{
+    for (int64_t i = 0; i < count; ++i) out[i] = (z[i] > 0.0) ? g[i] : 0.0;
+}
+
+void ref_bias_grad(int32_t n, int32_t k, int32_t p, int32_t q, const double *dy, double *db)
+{
+    for (int32_t kk = 0; kk < k; ++kk) {
+        double acc = 0.0;
+        for (int32_t nn = 0; nn < n; ++nn)
+            for (int32_t i = 0; i < p * q; ++i) acc += dy[((size_t)nn * k + kk) * p * q + i];
+        db[kk] = acc;
+    }
+}
+

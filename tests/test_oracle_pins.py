@@ -298,3 +298,51 @@ def test_bf16_rne_matches_torch_and_generator():
     assert np.array_equal(ours, t)
     assert np.array_equal(ours, synth_inputs.f32_to_bf16_bits(v))
     assert np.array_equal(oracle.bf16_bits_to_f64(ours), torch.from_numpy(t.view(np.int16)).view(torch.bfloat16).double().numpy())
+
+
+# ---------------------------------------------------------------- P12 backward compounding: ReLU mask, bias gradient
+def test_relu_bwd_mask_cases():
+    g = np.array([1.5, -2.0, 3.0, 4.0, -5.0, 6.0, 7.0])
+    z = np.array([2.0, 1e-30, 0.0, -0.0, -1.0, np.inf, np.nan])
+    out = oracle.relu_bwd_mask(g, z)
+    # strictly positive z passes the gradient; +0, -0, negative and NaN block it
+    np.testing.assert_array_equal(out, np.array([1.5, -2.0, 0.0, 0.0, 0.0, 6.0, 0.0]))
+    big = rng.normal(size=(3, 4, 5, 6))
+    np.testing.assert_array_equal(oracle.relu_bwd_mask(big, np.abs(big) + 1.0), big)      # identity
+    np.testing.assert_array_equal(oracle.relu_bwd_mask(big, -np.abs(big)), np.zeros_like(big))
+
+
+def test_bias_grad_closed_form_and_brute_force():
+    n, k, p, q = 3, 5, 4, 7
+    np.testing.assert_allclose(oracle.bias_grad(np.full((n, k, p, q), 0.25)), np.full(k, 0.25 * n * p * q), rtol=1e-15)
+    dy = rng.normal(size=(n, k, p, q))
+    brute = [sum(dy[nn, kk, i, j] for nn in range(n) for i in range(p) for j in range(q)) for kk in range(k)]
+    np.testing.assert_allclose(oracle.bias_grad(dy), brute, rtol=1e-13)
+    # only channel kk of dy reaches db[kk]
+    e = np.zeros((n, k, p, q)); e[1, 2, 3, 4] = 2.0
+    np.testing.assert_array_equal(oracle.bias_grad(e), np.array([0, 0, 2.0, 0, 0]))
+
+
+def test_bias_grad_is_adjoint_of_bias_broadcast():
+    a = Attrs(n=2, c=3, h=7, w=6, k=4, r=3, s=2, sh=2, sw=1, pbh=1, pbw=0, pah=1, paw=1)
+    x, w, dy = _random_tensors(a)
+    b = rng.uniform(-1, 1, a.k)
+    lhs = ((oracle.conv_fwd(a, x, w, bias=b) - oracle.conv_fwd(a, x, w)) * dy).sum()
+    assert abs(lhs - (b * oracle.bias_grad(dy)).sum()) < 1e-10
+
+
+def test_relu_conv_chain_gradient_by_central_differences():
+    """L(u) = <dy, conv(relu(u), w)>: dL/du = conv_bwd_data(dy, w) * [u > 0]; convolution is linear, so central
+    differences are exact up to rounding as long as no element crosses zero (|u| >= 0.5, step 1e-3)."""
+    a = Attrs(n=1, c=2, h=6, w=5, k=3, r=3, s=3, sh=1, sw=2, pbh=1, pbw=1, pah=1, paw=0)
+    _, w, dy = _random_tensors(a)
+    u = rng.uniform(0.5, 1.5, (a.n, a.c, a.h, a.w)) * rng.choice([-1.0, 1.0], (a.n, a.c, a.h, a.w))
+    loss = lambda t: float((oracle.conv_fwd(a, np.maximum(t, 0.0), w) * dy).sum())
+    grad = oracle.conv_bwd_data_relu(a, dy, w, np.maximum(u, 0.0))
+    assert np.all(grad[u < 0] == 0)
+    eps = 1e-3
+    for idx in itertools.islice(np.ndindex(u.shape), 0, None, 7):
+        up, dn = u.copy(), u.copy()
+        up[idx] += eps; dn[idx] -= eps
+        fd = (loss(up) - loss(dn)) / (2 * eps)
+        assert abs(fd - grad[idx]) < 1e-9, (idx, fd, grad[idx])
