@@ -75,7 +75,7 @@ typedef enum { NGC_F32 = 0, NGC_BF16 = 1 } ngc_dtype;
 typedef enum { NGC_NCHW = 0, NGC_NCHW16C = 1 } ngc_data_layout;
 typedef enum { NGC_KCRS = 0, NGC_BLOCKED_FWD = 1, NGC_BLOCKED_BWD = 2 } ngc_filter_layout;
 enum { NGC_EPI_NONE = 0, NGC_EPI_BIAS = 1, NGC_EPI_RELU = 2 };   /* bit flags, forward only */
-enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2 };
+enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2, NGC_OP_BIAS_GRAD = 3 };
 
 /* Constant attributes of one Convolution node and of its two derivative nodes. */
 typedef struct {
@@ -111,6 +111,23 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
  * every element overwritten (0 where no window reaches).  No epilogue. */
 int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w,
                       void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ConvolutionBackpropData compounded with the backprop of the ReLU that produced the convolution's
+ * data input (Abstract: compounding of operations; Sec. 3: the derivative graph of a ReLU-convolution
+ * chain has exactly this pair of nodes): dx = ConvolutionBackpropData(dy, w) where x_in > 0, +0
+ * elsewhere (x_in <= 0, -0 and NaN block the gradient).  x_in: the forward data input of the node,
+ * same shape, layout and element type as dx; it must not alias dx.  Other arguments, workspace
+ * (NGC_OP_BWD_DATA) and errors as ngc_conv_bwd_data; NGC_BAD_ARG if x_in is NULL or misaligned. */
+int ngc_conv_bwd_data_relu(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in,
+                           void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Bias gradient of the compounded bias epilogue (Sec. 3: adjoint of broadcasting the bias):
+ * db[k] = sum over n, p, q of dy[n,k,p,q], accumulated and written in fp32, db: [K] device floats,
+ * overwritten.  dy: [N,K,P,Q] in y_layout.  Two-stage fixed-order reduction through `ws`
+ * (ngc_conv_workspace_bytes(desc, NGC_OP_BIAS_GRAD) bytes; NGC_WORKSPACE_TOO_SMALL otherwise):
+ * the result does not depend on timing. */
+int ngc_bias_grad(const ngc_conv_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes,
+                  void *hip_stream);
 
 /* ConvolutionBackpropFilters (Sec. 3, derivative w.r.t. the filters input).
  * x in x_layout, dy in y_layout; dw: fp32 [K][C][R][S], overwritten.  The cross-workgroup

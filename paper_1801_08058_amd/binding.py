@@ -20,10 +20,10 @@ NGC_F32, NGC_BF16 = 0, 1
 NGC_NCHW, NGC_NCHW16C = 0, 1
 NGC_KCRS, NGC_BLOCKED_FWD, NGC_BLOCKED_BWD = 0, 1, 2
 NGC_EPI_NONE, NGC_EPI_BIAS, NGC_EPI_RELU = 0, 1, 2
-NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS = 0, 1, 2
+NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD = 0, 1, 2, 3
 
 EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
-           "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
+           "ngc_conv_bwd_data_relu", "ngc_bias_grad", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string")
 
 
@@ -67,6 +67,10 @@ def _load() -> ctypes.CDLL:
     lib.ngc_conv_fwd.restype = ctypes.c_int
     lib.ngc_conv_bwd_data.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_data.restype = ctypes.c_int
+    lib.ngc_conv_bwd_data_relu.argtypes = [D, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv_bwd_data_relu.restype = ctypes.c_int
+    lib.ngc_bias_grad.argtypes = [D, vp, vp, vp, sz, vp]
+    lib.ngc_bias_grad.restype = ctypes.c_int
     lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_filters.restype = ctypes.c_int
     lib.ngc_layout_convert.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp]
@@ -157,6 +161,16 @@ def ngc_conv_fwd(desc, x, w, bias, y, ws=None, stream=None, check: bool = True) 
 def ngc_conv_bwd_data(desc, dy, w, dx, ws=None, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_conv_bwd_data(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), _nbytes(ws),
                                          _stream(stream)), "ngc_conv_bwd_data", check)
+
+
+def ngc_conv_bwd_data_relu(desc, dy, w, x_in, dx, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_data_relu(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_in), _ptr(dx), _ptr(ws),
+                                              _nbytes(ws), _stream(stream)), "ngc_conv_bwd_data_relu", check)
+
+
+def ngc_bias_grad(desc, dy, db, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_bias_grad(ctypes.byref(desc), _ptr(dy), _ptr(db), _ptr(ws), _nbytes(ws),
+                                     _stream(stream)), "ngc_bias_grad", check)
 
 
 def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = True) -> int:

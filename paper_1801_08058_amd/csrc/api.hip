@@ -618,6 +618,7 @@ void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *spl
 
 size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
+    if (op == NGC_OP_BIAS_GRAD) return round256((size_t)bias_grad_parts(*d, P, Q) * ((d->k + 15) / 16 * 16) * sizeof(float));
     if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
@@ -711,6 +712,11 @@ size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
 
 const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
 {
+    if (op == NGC_OP_BIAS_GRAD) {
+        int P, Q;
+        if (validate(desc, &P, &Q) != NGC_OK) return "invalid";
+        return (desc->dtype == NGC_BF16 && desc->y_layout == NGC_NCHW16C) ? "bias_grad_blocked_bf16" : "bias_grad_generic";
+    }
     switch (pick(desc, op)) {
     case V_UNSUPPORTED: return "unsupported";
     case V_DIRECT: return "direct";
@@ -821,18 +827,23 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
     return launch_status(launch_igemm(p, v == V_IGEMM_128 ? 128 : 64, p.cls[0].M, st));
 }
 
-int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
-                      void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// ConvolutionBackpropData; mask (may be null): same shape / layout / type as dx, dx = (mask > 0) ? dx : 0
+int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, const void *mask, void *dx, void *ws,
+                  size_t ws_bytes, void *hip_stream)
 {
     int P, Q;
     const int vs = validate(desc, &P, &Q);
     if (vs != NGC_OK) return vs;
     if (!dy || !w || !dx) return NGC_BAD_ARG;
-    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws)) return NGC_BAD_ARG;
+    if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws) || !aligned16(mask)) return NGC_BAD_ARG;
     const Variant v = pick(desc, NGC_OP_BWD_DATA);
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, dx, st));
+    if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, mask, dx, st));
     if (v == V_STEM_BWD) {
         StemBwdPlan pl;
         if (!stem_bwd_plan(desc, P, Q, &pl)) return NGC_UNSUPPORTED;
@@ -845,6 +856,7 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         pl.sp.in = static_cast<const uint16_t *>(dy);
         pl.sp.wt = static_cast<const uint16_t *>(ws);
         pl.sp.out = static_cast<uint16_t *>(dx);
+        pl.sp.mask = static_cast<const uint16_t *>(mask);
         pl.sp.bias = nullptr;
         pl.sp.relu = 0;
         return launch_status(launch_strip(pl.sp, pl.nf, pl.lds, st));
@@ -871,6 +883,7 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
             sp.in = static_cast<const uint16_t *>(dy);
             sp.wt = static_cast<const uint16_t *>(wt);
             sp.out = static_cast<uint16_t *>(dx);
+            sp.mask = static_cast<const uint16_t *>(mask);
             sp.bias = nullptr;
             sp.relu = 0;
             const int rc = launch_status(launch_strip(sp, nf, lds, st));
@@ -890,6 +903,7 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
         gp.in = static_cast<const uint16_t *>(dy);
         gp.wt = static_cast<const uint16_t *>(wt);
         gp.out = static_cast<uint16_t *>(dx);
+        gp.mask = static_cast<const uint16_t *>(mask);
         return launch_status(launch_gemm1x1(gp, st));
     }
     IgemmParams p;
@@ -897,6 +911,7 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
     p.in = static_cast<const uint16_t *>(dy);
     p.wt = static_cast<const uint16_t *>(wt);
     p.out = static_cast<uint16_t *>(dx);
+    p.mask = static_cast<const uint16_t *>(mask);
     p.bias = nullptr;
     p.N = desc->n; p.Cin = desc->k; p.Hin = P; p.Win = Q;
     p.Cout = desc->c; p.Hout = desc->h; p.Wout = desc->w;
@@ -930,6 +945,37 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, 
             if (c.M > max_m) max_m = c.M;
         }
     return launch_status(launch_igemm(p, v == V_IGEMM_128 ? 128 : 64, max_m, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
+                      void *hip_stream)
+{
+    return bwd_data_impl(desc, dy, w, nullptr, dx, ws, ws_bytes, hip_stream);
+}
+
+int ngc_conv_bwd_data_relu(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in, void *dx, void *ws,
+                           size_t ws_bytes, void *hip_stream)
+{
+    if (!x_in) return NGC_BAD_ARG;
+    return bwd_data_impl(desc, dy, w, x_in, dx, ws, ws_bytes, hip_stream);
+}
+
+int ngc_bias_grad(const ngc_conv_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!dy || !db || !ws) return dy && db ? NGC_WORKSPACE_TOO_SMALL : NGC_BAD_ARG;
+    if (!aligned16(dy) || !aligned16(db) || !aligned16(ws)) return NGC_BAD_ARG;
+    if ((size_t)desc->n * P * Q >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
+    const int nparts = bias_grad_parts(*desc, P, Q);
+    if (ws_bytes < workspace_bytes(desc, NGC_OP_BIAS_GRAD, V_DIRECT, P, Q)) return NGC_WORKSPACE_TOO_SMALL;
+    return launch_status(launch_bias_grad(*desc, P, Q, dy, db, static_cast<float *>(ws), nparts,
+                                          static_cast<hipStream_t>(hip_stream)));
 }
 
 int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw, void *ws,

@@ -76,6 +76,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
 }
 
 // ---- element index functions for the public layouts ----
+// ReLU backprop on packed bf16: keep the halves of v whose counterpart in m is > 0 (as a float
+// comparison: +0, -0, negatives and NaN block), zero the others.
+__device__ __forceinline__ uint32_t relu_keep2(uint32_t v, uint32_t m)
+{
+    const float lo = __uint_as_float(m << 16), hi = __uint_as_float(m & 0xFFFF0000u);
+    return v & ((lo > 0.f ? 0x0000FFFFu : 0u) | (hi > 0.f ? 0xFFFF0000u : 0u));
+}
+__device__ __forceinline__ uint4 relu_keep8(uint4 v, uint4 m)
+{
+    return make_uint4(relu_keep2(v.x, m.x), relu_keep2(v.y, m.y), relu_keep2(v.z, m.z), relu_keep2(v.w, m.w));
+}
+
 __host__ __device__ inline size_t data_index(int layout, int C, int H, int W, int n, int c, int h, int w)
 {
     if (layout == NGC_NCHW) return (((size_t)n * C + c) * H + h) * W + w;
@@ -117,6 +129,7 @@ struct IgemmParams {
     const uint16_t *wt;
     uint16_t *out;
     const float *bias;         // may be null
+    const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
     int32_t os_h, os_w, is_h, is_w;
     int32_t relu;
@@ -133,6 +146,7 @@ struct StripParams {
     const uint16_t *wt;
     uint16_t *out;
     const float *bias;         // may be null
+    const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
     int32_t TN, TP;            // images and output rows per workgroup
     int32_t groups, strips;    // ceil(N/TN), ceil(Hout/TP)
@@ -249,6 +263,7 @@ struct Gemm1x1Params {
     const uint16_t *wt;        // [Cin/16][Cout][16]
     uint16_t *out;
     const float *bias;         // may be null
+    const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t Cin, Hin, Win, Cout, Hout, Wout;
     int32_t is_h, is_w, dh, dw;        // input pixel of lattice position (i,j): (i*is_h + dh, j*is_w + dw)
     int32_t os_h, os_w, oa_h, oa_w;    // output pixel: (i*os_h + oa_h, j*os_w + oa_w)
@@ -286,7 +301,10 @@ hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int 
 hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x, const void *w,
                              const float *bias, void *y, hipStream_t st);
 hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w,
-                                  void *dx, hipStream_t st);
+                                  const void *mask, void *dx, hipStream_t st);
+hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy, float *db, float *partial, int nparts,
+                            hipStream_t st);
+int bias_grad_parts(const ngc_conv_desc &d, int P, int Q);
 hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const void *x, const void *dy,
                                      float *dw, hipStream_t st);
 hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,

@@ -195,9 +195,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
-                const uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
+                uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
                 }
             }

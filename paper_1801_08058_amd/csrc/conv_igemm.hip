@@ -228,9 +228,10 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
                 const uint32_t s0 = lg ? p0 : p2, s1 = lg ? p1 : p3;
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
-                const uint4 o = lg ? make_uint4(r0, r1, p2, p3) : make_uint4(p0, p1, r0, r1);
+                uint4 o = lg ? make_uint4(r0, r1, p2, p3) : make_uint4(p0, p1, r0, r1);
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
                 }
             }

@@ -243,8 +243,10 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
             const int ti = (int)fd_div((uint32_t)tc, p.div_subc), c = tc - ti * p.sub_C;
             const int n = n0 + ti, y = p.sub_BH * p0 + lrow;
             if (n < p.N && y < p.sub_H && lrow < vrows) {
-                const uint4 val = *reinterpret_cast<const uint4 *>(ob + (size_t)row * WP + ch * 8);
-                *reinterpret_cast<uint4 *>(p.out + (((size_t)n * p.sub_C + c) * p.sub_H + y) * p.sub_W + ch * 8) = val;
+                uint4 val = *reinterpret_cast<const uint4 *>(ob + (size_t)row * WP + ch * 8);
+                const size_t off = (((size_t)n * p.sub_C + c) * p.sub_H + y) * p.sub_W + ch * 8;
+                if (p.mask) val = relu_keep8(val, *reinterpret_cast<const uint4 *>(p.mask + off));
+                *reinterpret_cast<uint4 *>(p.out + off) = val;
             }
         }
         return;
@@ -275,9 +277,12 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                         const int ab = col / p.sub_C, c = col - ab * p.sub_C;
                         const int a2 = ab / p.sub_BW;
                         const int hh = p.sub_BH * oh + a2, ww = p.sub_BW * (int)q + (ab - a2 * p.sub_BW);
-                        if (hh < p.sub_H && ww < p.sub_W)
-                            p.out[(((size_t)n * p.sub_C + c) * p.sub_H + hh) * p.sub_W + ww] =
-                                (uint16_t)(pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu);
+                        if (hh < p.sub_H && ww < p.sub_W) {
+                            const size_t off = (((size_t)n * p.sub_C + c) * p.sub_H + hh) * p.sub_W + ww;
+                            uint32_t bits = pack_bf16x2_hw(acc[i][a][v], 0.f) & 0xFFFFu;
+                            if (p.mask) bits = relu_keep2(bits, p.mask[off]);
+                            p.out[off] = (uint16_t)bits;
+                        }
                     }
                 }
             continue;
@@ -304,9 +309,10 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
-                const uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
+                uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
                 }
             }

@@ -147,6 +147,31 @@ class Run:
         self.last_desc, self.last_raw = d, dx
         return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
 
+    def bwd_data_relu(self, dy, w, x_in):
+        """ConvolutionBackpropData compounded with the backprop of the ReLU that produced x_in."""
+        a = self.a
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_BWD)
+        d = desc_of(a, self.dtype, self.xl, self.yl, wl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        xin = data_to_device(x_in, self.dtype, self.xl)
+        dx = out_tensor(d, 0, self.dtype)
+        ws = workspace(d, ng.NGC_OP_BWD_DATA)
+        ng.ngc_conv_bwd_data_relu(d, dyd, wd, xin, dx, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, dx
+        return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
+
+    def bias_grad(self, dy):
+        a = self.a
+        d = desc_of(a, self.dtype, self.xl, self.yl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        db = torch.full((a.k,), float("nan"), dtype=torch.float32, device="cuda")
+        ws = workspace(d, ng.NGC_OP_BIAS_GRAD)
+        ng.ngc_bias_grad(d, dyd, db, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, db
+        return db.cpu().numpy().astype(np.float64)
+
     def bwd_filters(self, x, dy):
         a = self.a
         d = desc_of(a, self.dtype, self.xl, self.yl)

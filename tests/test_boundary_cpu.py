@@ -91,6 +91,27 @@ def test_null_pointers_missing_bias_and_workspace():
     assert ng.ngc_filter_convert(d, fake, fake, ng.NGC_KCRS, None, check=False) == ng.NGC_BAD_ARG
 
 
+def test_backward_compounds_validate_before_launch():
+    d = _good(w_layout=ng.NGC_BLOCKED_BWD)
+    fake = 0x1000
+    assert ng.ngc_conv_bwd_data_relu(d, fake, fake, None, fake, None, None, check=False) == ng.NGC_BAD_ARG   # no x_in
+    assert ng.ngc_conv_bwd_data_relu(d, fake, fake, fake + 2, fake, None, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_conv_bwd_data_relu(d, None, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_ARG
+    bad = _good(stride=(0, 1))
+    assert ng.ngc_conv_bwd_data_relu(bad, fake, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_bias_grad(bad, fake, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_bias_grad(d, None, fake, None, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_bias_grad(d, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    # one fp32 partial per (position chunk, channel), channels padded to 16
+    big = _good(n=64, h=56, w=56)
+    nb = ng.ngc_conv_workspace_bytes(big, ng.NGC_OP_BIAS_GRAD)
+    assert nb % 256 == 0 and 64 * 4 <= nb <= 4096 * 64 * 4
+    assert ng.ngc_conv_variant(big, ng.NGC_OP_BIAS_GRAD) == "bias_grad_blocked_bf16"
+    assert ng.ngc_conv_variant(_good(dtype=ng.NGC_F32, x_layout=ng.NGC_NCHW, y_layout=ng.NGC_NCHW), ng.NGC_OP_BIAS_GRAD) \
+        == "bias_grad_generic"
+    assert ng.ngc_conv_variant(bad, ng.NGC_OP_BIAS_GRAD) == "invalid"
+
+
 def test_unsupported_is_reported_not_routed_elsewhere():
     # blocked filters with a shape only the direct kernels cover
     d = _good(c=5, k=7, w_layout=ng.NGC_BLOCKED_FWD)

@@ -29,6 +29,21 @@ def _tensors(a: Attrs, dtype: str, seed: int):
     return x, w, b, dy
 
 
+def _check_backward_compounds(run, a, x_in, w, dy, ref_dx, tol):
+    """Backprop-data compounded with the ReLU backprop of its data input (x_in doubles as the forward
+    input of the node: about half of its elements are <= 0), and the bias gradient."""
+    dxr = run.bwd_data_relu(dy, w, x_in)
+    ref = oracle.relu_bwd_mask(ref_dx, x_in)
+    e = oracle.max_normalised_error(dxr, ref)
+    assert e <= tol, f"bwd_data_relu err {e}"
+    blocked = ~(x_in > 0)
+    assert np.all(dxr[blocked] == 0) and not np.signbit(dxr[blocked]).any(), "gradient leaked through x_in <= 0"
+    db = run.bias_grad(dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BIAS_GRAD).startswith("bias_grad")
+    e = oracle.max_normalised_error(db, oracle.bias_grad(dy))
+    assert e <= 1e-5, f"bias_grad err {e}"
+
+
 def _check_all(a: Attrs, dtype: str, xl: int, yl: int, pre: bool, seed: int, expect_variant=None):
     print(f"case attrs={a} dtype={dtype} xl={xl} yl={yl} pre={pre} seed={seed}", flush=True)
     x, w, b, dy = _tensors(a, dtype, seed)
@@ -47,8 +62,10 @@ def _check_all(a: Attrs, dtype: str, xl: int, yl: int, pre: bool, seed: int, exp
     if expect_variant:
         assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect_variant[1]), \
             ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA)
-    e = oracle.max_normalised_error(dx, oracle.conv_bwd_data(a, dy, w))
+    ref_dx = oracle.conv_bwd_data(a, dy, w)
+    e = oracle.max_normalised_error(dx, ref_dx)
     assert e <= tol, f"bwd_data err {e}"
+    _check_backward_compounds(run, a, x, w, dy, ref_dx, tol)
     dw = run.bwd_filters(x, dy)
     if expect_variant:
         assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS).startswith(expect_variant[2])
@@ -362,6 +379,13 @@ def _sampled_layer_check(L, n_y=100_000, n_dw=2048, convert_x_on_device=False):
         ref = oracle.conv_bwd_data_at(a, dy64, w64, idx)
         assert oracle.max_normalised_error(dx.reshape(-1)[idx], ref) <= 2e-2, "bwd_data"
         assert np.isfinite(dx).all()
+        dxr = run.bwd_data_relu(t["dy"], t["w"], t["x"])
+        xs = x64.reshape(-1)[idx]
+        assert oracle.max_normalised_error(dxr.reshape(-1)[idx], oracle.relu_bwd_mask(ref, xs)) <= 2e-2, "bwd_data_relu"
+        keep = t["x"] > 0
+        assert np.array_equal(dxr[keep], dx[keep]) and not dxr[~keep].any(), "mask applied to the same gradient"
+        db = run.bias_grad(t["dy"])
+        assert oracle.max_normalised_error(db, oracle.bias_grad(dy64)) <= 1e-5, "bias_grad"
     if "bwd_filters" in L.ops:
         dw = run.bwd_filters(t["x"], t["dy"])
         idx = rng.integers(0, dw.size, min(n_dw, dw.size))
