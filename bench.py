@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
@@ -46,6 +45,9 @@ def parse():
                     help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
                          "of equal (default) priority, so that independent ops overlap their launch gaps and tails; "
                          "1: everything on one stream")
+    ap.add_argument("--backward-compounds", action="store_true",
+                    help="also time ngc_conv_bwd_data_relu and ngc_bias_grad of every layer on their own (reported under "
+                         "backward_compound_kernels; never part of the timed step)")
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
@@ -54,38 +56,55 @@ def parse():
 
 
 class LayerBench:
-    """Device buffers and launch closures of one layer (all ops through the C ABI)."""
+    """Device buffers and launch closures of one layer (all ops through the C ABI).  Inputs are
+    uploaded as NCHW bf16 and brought into the blocked layout by the library's own conversion."""
 
-    def __init__(self, L, ng, torch, gpu_util, nchw_input=False, sets=1):
+    def __init__(self, L, ng, torch, nchw_input=False, sets=1):
         import numpy as np
-        import oracle  # host-side input preparation only (layout of the uploaded tensors)
+        import synth_inputs
         self.L, self.ng, self.torch = L, ng, torch
-        a = gpu_util.attrs_of(L)
-        self.a = a
-        t = __import__("synth_inputs").layer_tensors(L)
+        t = synth_inputs.layer_tensors(L)
         blocked_in = L.c % 16 == 0
         self.xl = ng.NGC_NCHW16C if blocked_in else ng.NGC_NCHW
         self.yl = ng.NGC_NCHW16C
         epi = (ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU) if L.bias_relu else ng.NGC_EPI_NONE
-        mk = gpu_util.desc_of
-        self.d_fwd = mk(a, "bf16", self.xl, self.yl, ng.NGC_BLOCKED_FWD if blocked_in else ng.NGC_KCRS, epi)
-        self.d_bwd = mk(a, "bf16", self.xl, self.yl, ng.NGC_BLOCKED_BWD if blocked_in else ng.NGC_KCRS)
-        self.d_wg = mk(a, "bf16", self.xl, self.yl)
-        wbits = gpu_util.encode(t["w"], "bf16")
-        self.w_kcrs = gpu_util.dev(wbits)
+        cur = torch.cuda.current_stream().cuda_stream
+
+        def mk(w_layout=ng.NGC_KCRS, epilogue=ng.NGC_EPI_NONE):
+            return ng.make_desc(L.n, L.c, L.h, L.w, L.k, L.r, L.s, (L.stride, L.stride), (L.dil, L.dil),
+                                (L.pad, L.pad), (L.pad, L.pad), ng.NGC_BF16, self.xl, self.yl, w_layout, epilogue)
+
+        def dev_bits(values_f32):
+            bits = synth_inputs.f32_to_bf16_bits(values_f32)      # values of bf16 configs are exactly representable
+            return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+
+        def to_layout(nchw, c, h, w, layout):
+            if layout == ng.NGC_NCHW:
+                return nchw
+            out = torch.empty(L.n * ((c + 15) // 16) * h * w * 16, dtype=torch.int16, device="cuda")
+            ng.ngc_layout_convert(ng.NGC_BF16, L.n, c, h, w, nchw, ng.NGC_NCHW, out, ng.NGC_NCHW16C, cur)
+            torch.cuda.synchronize()
+            return out
+
+        self.d_fwd = mk(ng.NGC_BLOCKED_FWD if blocked_in else ng.NGC_KCRS, epi)
+        self.d_bwd = mk(ng.NGC_BLOCKED_BWD if blocked_in else ng.NGC_KCRS)
+        self.d_wg = mk()
+        self.w_kcrs = dev_bits(t["w"])
         if blocked_in:
             self.w_fwd = torch.empty(ng.ngc_filter_elems(self.d_fwd, ng.NGC_BLOCKED_FWD), dtype=torch.int16, device="cuda")
             self.w_bwd = torch.empty(ng.ngc_filter_elems(self.d_fwd, ng.NGC_BLOCKED_BWD), dtype=torch.int16, device="cuda")
-            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_fwd, ng.NGC_BLOCKED_FWD, gpu_util.stream())
-            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_bwd, ng.NGC_BLOCKED_BWD, gpu_util.stream())
+            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_fwd, ng.NGC_BLOCKED_FWD, cur)
+            ng.ngc_filter_convert(self.d_fwd, self.w_kcrs, self.w_bwd, ng.NGC_BLOCKED_BWD, cur)
         else:
             self.w_fwd = self.w_bwd = self.w_kcrs
-        self.bias = gpu_util.dev(np.asarray(t["bias"], dtype=np.float32))
+        self.bias = torch.from_numpy(np.ascontiguousarray(t["bias"], dtype=np.float32)).cuda()
         self.nchw_input = nchw_input
         self.sets = []
-        x0 = gpu_util.data_to_device(t["x"], "bf16", self.xl)
-        dy0 = gpu_util.data_to_device(t["dy"], "bf16", self.yl)
-        x_nchw0 = gpu_util.dev(gpu_util.encode(t["x"], "bf16")) if nchw_input else None
+        x_nchw0 = dev_bits(t["x"])
+        x0 = to_layout(x_nchw0, L.c, L.h, L.w, self.xl)
+        dy0 = to_layout(dev_bits(t["dy"]), L.k, L.p, L.q, self.yl)
+        if not nchw_input:
+            x_nchw0 = None
         for i in range(sets):
             s = {"x": x0 if i == 0 else x0.clone(), "dy": dy0 if i == 0 else dy0.clone(),
                  "y": torch.empty(ng.ngc_data_elems(self.d_fwd, 1), dtype=torch.int16, device="cuda"),
@@ -94,11 +113,11 @@ class LayerBench:
             if nchw_input:
                 s["x_nchw"] = x_nchw0 if i == 0 else x_nchw0.clone()
             self.sets.append(s)
-        self.ws = {op: gpu_util.workspace(d, op) for op, d in
-                   ((ng.NGC_OP_FWD, self.d_fwd), (ng.NGC_OP_BWD_DATA, self.d_bwd), (ng.NGC_OP_BWD_FILTERS, self.d_wg),
-                    (ng.NGC_OP_BIAS_GRAD, self.d_wg))}
+        self.ws = {op: torch.empty(max(ng.ngc_conv_workspace_bytes(d, op), 16), dtype=torch.uint8, device="cuda")
+                   for op, d in ((ng.NGC_OP_FWD, self.d_fwd), (ng.NGC_OP_BWD_DATA, self.d_bwd),
+                                 (ng.NGC_OP_BWD_FILTERS, self.d_wg), (ng.NGC_OP_BIAS_GRAD, self.d_wg))}
         self.db = torch.empty(L.k, dtype=torch.float32, device="cuda")
-        self.stream = gpu_util.stream()
+        self.stream = cur
         self.ops = list(L.ops)
         if nchw_input:
             self.ops = ["convert"] + self.ops
@@ -162,8 +181,7 @@ def cpu_baseline(L):
     import numpy as np
     import oracle
     import synth_inputs
-    from gpu_util import attrs_of
-    a = attrs_of(L)
+    a = oracle.Attrs(L.n, L.c, L.h, L.w, L.k, L.r, L.s, L.stride, L.stride, L.dil, L.dil, L.pad, L.pad, L.pad, L.pad)
     t = synth_inputs.layer_tensors(L)
     x, w, dy = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
     t0 = time.perf_counter()
@@ -190,7 +208,6 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     import paper_1801_08058_amd as ng
-    import gpu_util
     import synth_inputs
 
     cfg = int(args.workload[3:])
@@ -199,7 +216,7 @@ def main():
     if args.cold:
         per_set = sum(2 * 2 * (L.n * L.c * L.h * L.w + L.n * L.k * L.p * L.q) for L in layers[:1])
         sets = max(2, int(600e6 // per_set) + 1)
-    benches = [LayerBench(L, ng, torch, gpu_util, nchw_input=(cfg == 3), sets=sets) for L in layers]
+    benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets) for L in layers]
     torch.cuda.synchronize()
 
     # The ops of a layer read and write disjoint buffers (each has its own inputs, outputs and
@@ -243,7 +260,7 @@ def main():
                 "count": b.L.count}
     # backward compounds (ReLU backprop fused into backprop-data; bias gradient): same buffers, timed alone
     extra = {}
-    for b in benches:
+    for b in (benches if args.backward_compounds else []):
         for op in (["bwd_data_relu"] if "bwd_data" in b.ops else []) + ["bias_grad"]:
             ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps)
             flop = b.L.flop_per_op if op == "bwd_data_relu" else 0.0
@@ -287,8 +304,9 @@ def main():
         "gflop_per_step": round(flop_step / 1e9, 2),
         "roofline": roof,
         "kernels": kern,
-        "backward_compound_kernels": extra,
     }
+    if args.backward_compounds:
+        out["backward_compound_kernels"] = extra
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(synth_inputs.config_layers(2)[0])
     print(json.dumps(out))

@@ -85,8 +85,10 @@ __global__ __launch_bounds__(256) void bias_grad_reduce(const float *__restrict_
     const int tid = threadIdx.x;
     const int k = blockIdx.x * 16 + (tid & 15);
     float acc = 0.f;
-    if (k < K)
+    if (k < K) {
+#pragma unroll 8
         for (int s = tid >> 4; s < nparts; s += 16) acc += partial[(size_t)s * KP + k];
+    }
     sm[tid] = acc;
     __syncthreads();
     for (int stride = 128; stride >= 16; stride >>= 1) {
@@ -96,13 +98,14 @@ __global__ __launch_bounds__(256) void bias_grad_reduce(const float *__restrict_
     if (tid < 16 && k < K) db[k] = sm[tid];
 }
 
-// position chunks: enough workgroups to fill the chip, chunks of at least 128 positions
+// position chunks: enough workgroups to fill the chip, at most 256 chunks of at least 128 positions
 int bias_grad_parts(const ngc_conv_desc &d, int P, int Q)
 {
     const uint32_t M = (uint32_t)d.n * P * Q;
     const bool blocked = d.dtype == NGC_BF16 && d.y_layout == NGC_NCHW16C;
     const uint32_t rows = blocked ? (uint32_t)(d.k + 15) / 16 : (uint32_t)d.k;
     uint32_t parts = (2048 + rows - 1) / rows;
+    if (parts > 256) parts = 256;                       // keeps the second stage short
     const uint32_t max_parts = (M + 127) / 128;
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;
