@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--backward-compounds", action="store_true",
                     help="also time ngc_conv_bwd_data_relu and ngc_bias_grad of every layer on their own (reported under "
                          "backward_compound_kernels; never part of the timed step)")
+    ap.add_argument("--propagate-layout", action="store_true",
+                    help="cfg3 only: no conversion pass; the three ops read x from / write dx to the NCHW tensor directly")
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
@@ -59,13 +61,13 @@ class LayerBench:
     """Device buffers and launch closures of one layer (all ops through the C ABI).  Inputs are
     uploaded as NCHW bf16 and brought into the blocked layout by the library's own conversion."""
 
-    def __init__(self, L, ng, torch, nchw_input=False, sets=1):
+    def __init__(self, L, ng, torch, nchw_input=False, sets=1, propagate=False):
         import numpy as np
         import synth_inputs
         self.L, self.ng, self.torch = L, ng, torch
         t = synth_inputs.layer_tensors(L)
-        blocked_in = L.c % 16 == 0
-        self.xl = ng.NGC_NCHW16C if blocked_in else ng.NGC_NCHW
+        blocked_in = L.c % 16 == 0                      # blocked filters; x blocked too unless the NCHW layout is propagated
+        self.xl = ng.NGC_NCHW16C if blocked_in and not propagate else ng.NGC_NCHW
         self.yl = ng.NGC_NCHW16C
         epi = (ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU) if L.bias_relu else ng.NGC_EPI_NONE
         cur = torch.cuda.current_stream().cuda_stream
@@ -119,7 +121,7 @@ class LayerBench:
         self.db = torch.empty(L.k, dtype=torch.float32, device="cuda")
         self.stream = cur
         self.ops = list(L.ops)
-        if nchw_input:
+        if nchw_input and not propagate:
             self.ops = ["convert"] + self.ops
 
     def launch(self, op, i=0, streams=None):
@@ -216,7 +218,10 @@ def main():
     if args.cold:
         per_set = sum(2 * 2 * (L.n * L.c * L.h * L.w + L.n * L.k * L.p * L.q) for L in layers[:1])
         sets = max(2, int(600e6 // per_set) + 1)
-    benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets) for L in layers]
+    if args.propagate_layout and cfg != 3:
+        print("bench.py: --propagate-layout applies to --workload cfg3", file=sys.stderr)
+        sys.exit(2)
+    benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets, propagate=args.propagate_layout) for L in layers]
     torch.cuda.synchronize()
 
     # The ops of a layer read and write disjoint buffers (each has its own inputs, outputs and
@@ -299,7 +304,8 @@ def main():
                                 4: "configs[3]: stem 7x7/2 N=64 C=3 K=64 224x224 bf16, fwd(+bias+ReLU) + bwd_filters",
                                 5: "configs[4]: ResNet-50 conv stack N=128 bf16, 53 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
                    "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
-                   "streams": 3 if streams else 1},
+                   "streams": 3 if streams else 1,
+                   **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {})},
         "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "gflop_per_step": round(flop_step / 1e9, 2),
         "roofline": roof,

@@ -41,6 +41,11 @@
  *   - Results are run-to-run identical (no floating-point atomics).
  *   - Each tensor must hold fewer than 2^31 elements.
  *
+ * Every op accepts every combination of data layouts; which combinations run on the MFMA kernels
+ * (bf16) and which on the slow direct kernels is a property of the build: blocked x and y for all
+ * shapes with C and K multiples of 64, NCHW x of the 3-channel stem, and NCHW x and / or y of 1x1
+ * layers with stride 1, no padding and H*W a multiple of 8 (ngc_conv_variant names the choice).
+ *
  * Element layouts
  *   NGC_NCHW      x[n][c][h][w]
  *   NGC_NCHW16C   x[n][cb][h][w][ci], c = 16*cb + ci, cb < ceil(C/16); lanes with

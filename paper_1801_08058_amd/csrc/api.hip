@@ -470,11 +470,22 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
 {
     const char *force = getenv("NGC_WGRAD_GEMM");
     if (force && atoi(force) == 0) return false;
-    if (d->c % 64 != 0 || d->k % 64 != 0 || d->r * d->s > 64) return false;
+    if (d->c % 64 != 0 || d->k % 64 != 0 || d->r * d->s > 64 || d->dtype != NGC_BF16) return false;
     const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * P * Q * 2;
     if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
     WgradGemmParams q;
     memset(&q, 0, sizeof(q));
+    // layout propagation: either operand may be NCHW when positions map one to one (1x1, stride 1, no
+    // padding) and 8 consecutive positions never straddle two images
+    q.x_nchw = d->x_layout == NGC_NCHW;
+    q.dy_nchw = d->y_layout == NGC_NCHW;
+    if (q.x_nchw || q.dy_nchw) {
+        const char *lp = getenv("NGC_G1_NCHW");          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
+        if (lp && atoi(lp) == 0) return false;
+        if (d->r != 1 || d->s != 1 || d->stride_h != 1 || d->stride_w != 1 || d->pad_below_h || d->pad_below_w ||
+            d->pad_above_h || d->pad_above_w || (d->h * d->w) % 8 != 0)
+            return false;
+    }
     q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q; q.R = d->r; q.S = d->s;
     q.sh = d->stride_h; q.sw = d->stride_w; q.dil_h = d->dil_h; q.dil_w = d->dil_w;
     q.pbh = d->pad_below_h; q.pbw = d->pad_below_w;
@@ -517,10 +528,21 @@ bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *g
     if (d->r != 1 || d->s != 1) return false;
     const bool fwd = op == NGC_OP_FWD;
     const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
-    if (Cin % 64 != 0 || Cout % 64 != 0) return false;
+    if (Cin % 64 != 0 || Cout % 64 != 0 || d->dtype != NGC_BF16) return false;
     Gemm1x1Params q;
     memset(&q, 0, sizeof(q));
     q.Cin = Cin; q.Cout = Cout;
+    // layout propagation: either side may be NCHW when positions map one to one (stride 1, no padding)
+    // and 8 consecutive positions never straddle two images
+    q.in_nchw = (fwd ? d->x_layout : d->y_layout) == NGC_NCHW;
+    q.out_nchw = (fwd ? d->y_layout : d->x_layout) == NGC_NCHW;
+    if (q.in_nchw || q.out_nchw) {
+        const char *lp = getenv("NGC_G1_NCHW");          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
+        if (lp && atoi(lp) == 0) return false;
+        if (d->stride_h != 1 || d->stride_w != 1 || d->pad_below_h || d->pad_below_w || d->pad_above_h || d->pad_above_w ||
+            (d->h * d->w) % 8 != 0)
+            return false;
+    }
     int OP, OQ;
     bool z = false;
     if (fwd) {
@@ -564,27 +586,29 @@ Variant pick(const ngc_conv_desc *d, int op)
     if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
     if (op == NGC_OP_FWD) {
         if (stem_fwd_plan(d, P, Q, nullptr, nullptr)) return V_STEM_FWD;
-        const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD);
+        const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD;
+        const bool base = blocked_bf16(d) && wl;
         const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
         if (base && strip_plan(d, op, P, Q)) return V_STRIP;
-        if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
+        if (wl && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_DATA) {
         if (stem_bwd_plan(d, P, Q, nullptr)) return V_STEM_BWD;
-        const bool base = blocked_bf16(d) && (d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD);
+        const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD;
+        const bool base = blocked_bf16(d) && wl;
         const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
                         d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
         if (base && strip_plan(d, op, P, Q)) return V_STRIP;
-        if (base && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
+        if (wl && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
     }
     if (op == NGC_OP_BWD_FILTERS) {
         if (wgrad_stem_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STEM;
         if (blocked_bf16(d) && wgrad_strip_plan(d, P, Q, nullptr, nullptr)) return V_WGRAD_STRIP;
-        if (blocked_bf16(d) && wgrad_gemm_plan(d, P, Q, nullptr)) return V_WGRAD_GEMM;
+        if ((blocked_bf16(d) || d->r * d->s == 1) && wgrad_gemm_plan(d, P, Q, nullptr)) return V_WGRAD_GEMM;
         if (blocked_bf16(d) && d->c % 64 == 0 && d->k % 64 == 0 && d->r * d->s <= 65535) return V_WGRAD_64;
         return V_DIRECT;
     }

@@ -250,6 +250,7 @@ struct WgradGemmParams {
     int32_t sh, sw, dil_h, dil_w, pbh, pbw;
     int32_t wk, wc;            // 64-wide sub-tiles of k and c per workgroup
     int32_t sp;                // positions per LDS stage (128 or 64)
+    int32_t x_nchw, dy_nchw;   // operand read from an NCHW tensor (1x1, stride 1, no padding, H*W % 8 == 0)
     int32_t ctiles;            // C / (64 wc)
     int32_t nparts;
     uint32_t M, chunk;         // N*P*Q, positions per part (multiple of 128)
@@ -265,6 +266,7 @@ struct Gemm1x1Params {
     const float *bias;         // may be null
     const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t Cin, Hin, Win, Cout, Hout, Wout;
+    int32_t in_nchw, out_nchw;         // activations read from / result written to NCHW (stride 1, no padding, H*W % 8 == 0)
     int32_t is_h, is_w, dh, dw;        // input pixel of lattice position (i,j): (i*is_h + dh, j*is_w + dw)
     int32_t os_h, os_w, oa_h, oa_w;    // output pixel: (i*os_h + oa_h, j*os_w + oa_w)
     int32_t relu;

@@ -14,6 +14,14 @@
 //
 // Workgroups that share an activation tile (different output-channel tiles) are given ids that
 // land on the same XCD (id % 8), so the tile is fetched into one L2 only.
+//
+// Layout propagation (stride 1, no padding, H*W % 8 == 0): with XN the activations are read from an
+// NCHW tensor, with YN the result is written to one, so a layer at the edge of the blocked part of a
+// graph needs no conversion pass.  XN: a load instruction brings 4 channels x 128 positions to LDS
+// as [16 positions][4 channels][16 positions] blocks and the MFMA operand (8 channels of one position
+// per lane) comes from two ds_read_b64_tr_b16 of a 4 x 16 block each (conflict-free: a block is 128
+// contiguous bytes).  YN: the wave tile goes through LDS ([channel][64 positions], rows padded to
+// 144 bytes) and leaves as 16-byte pieces of 8 consecutive positions.
 #include "common.h"
 
 #include <stdlib.h>
@@ -22,14 +30,27 @@ namespace ngc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4_q __attribute__((ext_vector_type(4)));
+typedef short s16x8_q __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void lds_void_q;
+typedef __attribute__((address_space(3))) s16x4_q lds_s16x4_q;
+
+// rows lo: channels c..c+3, rows hi: channels c+4..c+7 of 16 positions -> this lane's 8 channels of its position
+__device__ __forceinline__ bf16x8 tr_frag_q(const unsigned char *lo, const unsigned char *hi)
+{
+    const s16x4_q a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_q *)lo);
+    const s16x4_q b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_q *)hi);
+    const s16x8_q r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
 
 constexpr unsigned G1_OOB = 0x80000000u;
 
 // NS = ring depth; KB = 16-channel blocks per stage (4 or 2): a stage holds 2 KB planes (8-channel halves) per operand.
 // NL = loader waves (1 or 2); WM x WN MFMA waves; FA = 32-channel output fragments per MFMA wave
 // (2: 64 x 64 wave tiles; 4: 64 positions x 128 channels, 6 instead of 8 LDS operand fetches per 8 MFMAs).
-template <int WM, int WN, int NS, int KB, int NL, int FA>
+// XN / YN: activations read from / result written to an NCHW tensor (else 16-channel blocked)
+template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN>
 __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 {
     constexpr int BM = 64 * WM, BN = 32 * FA * WN;
@@ -39,7 +60,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     constexpr int STAGE = NPL * XPLANE + NPL * WPLANE;
     constexpr int NCW = WM * WN;                      // MFMA waves
     constexpr int PPL = NPL / NL;                     // planes per loader wave
-    constexpr int LPL = PPL * (WM + WB);              // loads per loader wave per stage
+    constexpr int LPL = PPL * (WM + WB);              // loads per loader wave per stage (same count with XN)
+    constexpr int NH128 = BM / 128;                   // XN: 128-position pieces of the tile
+    constexpr int QPL = 4 * KB / NL;                  // XN: 4-channel groups per loader wave and stage
+    constexpr int YROW = 144;                         // YN: bytes per channel row of a wave's staging tile
+    static_assert(QPL * NH128 == PPL * WM, "XN load count");
     static_assert((NCW == 8 || NCW == 4) && (NL == 1 || NL == 2), "wave roles");
     static_assert(NS >= 2 && NS <= 4 && (KB == 2 || KB == 4), "ring depth / stage size");
     static_assert(LPL * (NS - 2) < 64, "vmcnt range");
@@ -71,8 +96,24 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
         __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
         unsigned xvoff[WM];
+        if constexpr (XN) {
+            // lane = 16-byte unit: channel (lane / 2) % 4 of the group, positions (lane / 8) * 16 + (lane % 2) * 8 + 0..7
+            const int chq = (lane >> 1) & 3;
+            const int poff = (lane >> 3) * 16 + (lane & 1) * 8;
+#pragma unroll
+            for (int h = 0; h < NH128; ++h) {
+                const uint32_t m = m0 + (uint32_t)(h * 128 + poff);
+                xvoff[h] = G1_OOB;
+                if (m < p.M) {
+                    const uint32_t n = fd_div(m, p.div_pq);
+                    const uint32_t pp = m - n * p.div_pq.d;
+                    xvoff[h] = (unsigned)((((size_t)n * p.Cin + chq) * HWin + pp) * 2);
+                }
+            }
+        }
 #pragma unroll
         for (int b = 0; b < WM; ++b) {
+            if constexpr (XN) break;
             const uint32_t m = m0 + (uint32_t)(b * 64 + lane);
             xvoff[b] = G1_OOB;
             if (m < p.M) {
@@ -91,6 +132,17 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         auto issue_loads = [&](int s, int buf) {
             unsigned char *xs = smem + buf * STAGE;
             unsigned char *ws = xs + NPL * XPLANE;
+            if constexpr (XN) {
+#pragma unroll
+                for (int q = 0; q < QPL; ++q) {
+                    const int quad = lw * QPL + q;                     // 4-channel group of the stage
+                    const unsigned soff_x = (unsigned)((s * 16 * KB + 4 * quad) * HWin * 2);
+#pragma unroll
+                    for (int h = 0; h < NH128; ++h)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + quad * (BM * 8) + h * 1024), 16,
+                                                                 (int)xvoff[h], (int)soff_x, 0, 0);
+                }
+            }
 #pragma unroll
             for (int q = 0; q < PPL; ++q) {
                 const int pl = lw * PPL + q;
@@ -99,6 +151,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 const unsigned soff_w = (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16);
 #pragma unroll
                 for (int b = 0; b < WM; ++b) {
+                    if constexpr (XN) break;
                     const unsigned v = (xvoff[b] == G1_OOB) ? G1_OOB : xvoff[b] + (pl & 1) * 16;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + pl * XPLANE + b * 1024), 16, (int)v,
                                                              (int)soff_x, 0, 0);
@@ -121,6 +174,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
             wg_barrier_nofence();                      // stage s visible to all; buffer of stage s-1 is free
             if (s + NS - 1 < nsteps) issue_loads(s + NS - 1, (s + NS - 1) % NS);
         }
+        if constexpr (YN) wg_barrier_nofence();        // the ring becomes the staging area of the stores
         return;
     }
 
@@ -140,7 +194,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 
     for (int s = 0; s < nsteps; ++s) {
         wg_barrier_nofence();
-        const unsigned char *xs = smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;
+        const unsigned char *xs = XN
+            ? smem + (s % NS) * STAGE + (wm * 4 + ((lane >> 4) & 1)) * 128 + ((lane & 15) >> 2) * 32 + (lane & 3) * 8
+            : smem + (s % NS) * STAGE + lg * XPLANE + (wm * 64 + l32) * 16;
         const unsigned char *ws = smem + (s % NS) * STAGE + NPL * XPLANE + lg * WPLANE + (wn * 32 * FA + l32) * 16;
 #pragma unroll
         for (int ks = 0; ks < KB; ++ks) {
@@ -148,7 +204,14 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 #pragma unroll
             for (int a = 0; a < FA; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(ws + (2 * ks) * WPLANE + a * 512);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(xs + (2 * ks) * XPLANE + b * 512);
+            for (int b = 0; b < 2; ++b) {
+                if constexpr (XN) {
+                    const unsigned char *q0 = xs + (ks * 4 + 2 * lg) * (BM * 8) + b * 256;
+                    fb[b] = tr_frag_q(q0, q0 + BM * 8);
+                } else {
+                    fb[b] = *reinterpret_cast<const bf16x8 *>(xs + (2 * ks) * XPLANE + b * 512);
+                }
+            }
 #pragma unroll
             for (int a = 0; a < FA; ++a)
 #pragma unroll
@@ -157,9 +220,43 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         }
     }
 
+    const int HWout = p.Hout * p.Wout;
+    if constexpr (YN) {
+        // ---- NCHW epilogue: bias, ReLU, one RNE rounding, wave tile -> LDS [channel][64 positions] -> 16-byte stores
+        wg_barrier_nofence();                          // every wave is done with the ring
+        unsigned char *st = smem + wave * (32 * FA * YROW);
+#pragma unroll
+        for (int a = 0; a < FA; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int ch = a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+                    float val = acc[a][b][v];
+                    if (p.bias) val += p.bias[n0 + wn * 32 * FA + ch];
+                    if (p.relu) val = fmaxf(val, 0.f);
+                    *reinterpret_cast<uint16_t *>(st + ch * YROW + (b * 32 + l32) * 2) =
+                        (uint16_t)(pack_bf16x2_hw(val, 0.f) & 0xFFFFu);
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own writes only: no other wave touches this region
+        const int piece = lane & 7;
+        const uint32_t m = m0 + (uint32_t)(wm * 64 + piece * 8);
+        if (m < p.M) {                                 // M % 8 == 0: a piece is valid as a whole
+            const uint32_t n = fd_div(m, p.div_pq);
+            const uint32_t pp = m - n * p.div_pq.d;
+#pragma unroll
+            for (int it = 0; it < 4 * FA; ++it) {
+                const int ch = it * 8 + (lane >> 3);
+                uint4 o = *reinterpret_cast<const uint4 *>(st + ch * YROW + piece * 16);
+                const size_t off = ((size_t)n * p.Cout + (n0 + wn * 32 * FA + ch)) * HWout + pp;
+                if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + off));
+                *reinterpret_cast<uint4 *>(p.out + off) = o;
+            }
+        }
+        return;
+    }
     // ---- epilogue: bias, ReLU, one RNE rounding, lane-pair exchange, 16-byte stores
     const int CBout = p.Cout >> 4;
-    const int HWout = p.Hout * p.Wout;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const uint32_t m = m0 + (uint32_t)(wm * 64 + b * 32 + l32);
@@ -223,12 +320,12 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int WM, int WN, int NS, int KB, int NL, int FA = 2>
-static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
+template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN>
+static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -237,11 +334,29 @@ static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
     constexpr size_t stage = (size_t)2 * KB * ((BM * 16 + 128) + (BN * 16 + 128));
     // short reductions use fewer ring buffers than NS: less LDS, more workgroups per compute unit
     const int nsteps = p.Cin / (16 * KB);
-    const size_t lds = (size_t)(nsteps < NS ? nsteps : NS) * stage;
+    size_t lds = (size_t)(nsteps < NS ? nsteps : NS) * stage;
+    constexpr size_t staging = (size_t)WM * WN * 32 * FA * 144;        // YN: one [channel][64 positions] tile per MFMA wave
+    if (YN && lds < staging) lds = staging;
     const unsigned mtiles = (p.M + BM - 1) / BM;
     const unsigned grid = ((mtiles + 7) / 8) * 8 * (p.Cout / BN);
-    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
+    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
     return hipGetLastError();
+}
+
+// the NCHW modes exist for the dispatcher's own tile choices (FA = 2)
+template <int WM, int WN, int NS, int KB, int NL, int FA = 2>
+static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
+{
+    constexpr bool dispatcher_tile = FA == 2 && KB == 2 &&
+        ((WM == 4 && WN == 2 && NS == 3 && NL == 2) || (WM == 2 && WN == 2 && NS == 3 && NL == 1) ||
+         (WM == 8 && WN == 1 && NS == 2 && NL == 2) || (WM == 4 && WN == 1 && NS == 3 && NL == 1));
+    if constexpr (dispatcher_tile) {
+        if (p.in_nchw && p.out_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, true, true>(p, st);
+        if (p.in_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, true, false>(p, st);
+        if (p.out_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, false, true>(p, st);
+    }
+    if (p.in_nchw || p.out_nchw) return hipErrorInvalidValue;
+    return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, false, false>(p, st);
 }
 
 // 32-channel stages in a ring of 3 (75 KB of LDS): two workgroups per compute unit, so one's
@@ -254,6 +369,12 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
     int variant = ev ? atoi(ev) : 0;
+    if (p.in_nchw || p.out_nchw) {
+        if (variant != 3) variant = 0;
+        if (variant == 0 && p.Cout % 128 == 0 && ((p.M + 255) / 256) * (unsigned)(p.Cout / 128) < 2 * 256) variant = 3;
+        if (p.Cout % 128 == 0) return variant == 3 ? launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st) : launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
+        return variant == 3 ? launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st) : launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
+    }
     if (p.Cout % 128 == 0) {
         if (variant == 0) {
             const unsigned tiles = ((p.M + 255) / 256) * (unsigned)(p.Cout / 128);

@@ -13,6 +13,11 @@
 // fetched with the LDS transpose load ds_read_b64_tr_b16.  Two stages, one barrier per stage.
 // Partials go to the workspace in register order; wgrad_gemm_reduce adds the parts in index
 // order (deterministic) and writes dw as [K][C][R][S].
+// Layout propagation (1x1, stride 1, no padding, H*W % 8 == 0): with XN / DN the x / dy operand is
+// read from an NCHW tensor.  Positions are contiguous there, so a load unit is 8 positions of one
+// channel, a 32-position block of a plane sits in LDS as [16 positions][16 channels][16 positions]
+// and the operand is two plain ds_read_b64 (the same position-to-lane assignment as the transposed
+// loads of the other operand; 64 lanes cover 512 contiguous bytes).
 #include "common.h"
 
 namespace ngc {
@@ -35,8 +40,20 @@ __device__ __forceinline__ bf16x8 tr_frag_g(const unsigned char *lo)
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// SP = positions per stage (128, or 64: half the LDS, two workgroups per compute unit)
-template <int WK, int WC, int SP>
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4_n;
+
+__device__ __forceinline__ bf16x8 nchw_frag_g(const unsigned char *lo)
+{
+    // positions +0..3 and +16..19 of this lane's channel row
+    const s16x4 a = *(const lds_s16x4_n *)lo;
+    const s16x4 b = *(const lds_s16x4_n *)(lo + 512);
+    const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// SP = positions per stage (128, or 64: half the LDS, two workgroups per compute unit);
+// XN / DN: x / dy is an NCHW tensor (else 16-channel blocked)
+template <int WK, int WC, int SP, bool XN, bool DN>
 __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 {
     constexpr int NW = 8;
@@ -98,15 +115,31 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
         const unsigned half = (lane & 1) * 16;
         const unsigned dy_off = (unsigned)(((n * KB + kb0) * PQ + rem) * 32) + half;
         const unsigned x_off = (unsigned)(((n * CB + cb0) * HW + h * p.W + w) * 32) + half;
+        // NCHW operands: lane = channel (lane / 2) % 16 of the plane, positions 16 (lane / 32) + 8 (lane % 2) + 0..7
+        // of the block (one tap, stride 1, no padding: the input pixel is the output position)
+        bool inn = false;
+        unsigned dyn_off = 0, xn_off = 0;
+        if constexpr (XN || DN) {
+            const uint32_t m2 = m_begin + (uint32_t)(s * WGG_SP + my_blk * 32 + 16 * (lane >> 5) + 8 * (lane & 1));
+            inn = m2 < m_end;                                            // chunk ends are multiples of 8
+            const uint32_t mm2 = inn ? m2 : 0;
+            const uint32_t n2 = fd_div(mm2, p.div_pq);
+            const uint32_t pp2 = mm2 - n2 * p.div_pq.d;
+            const uint32_t ch = (uint32_t)((lane >> 1) & 15);
+            dyn_off = (unsigned)((((size_t)n2 * p.K + kb0 * 16 + ch) * PQ + pp2) * 2);
+            xn_off = (unsigned)((((size_t)n2 * p.C + cb0 * 16 + ch) * HW + pp2) * 2);
+        }
 #pragma unroll
         for (int j = 0; j < NITEM; ++j) {
             const int pl = wave / BLK + (NW / BLK) * j;                  // plane index of item wave + 8 j
             unsigned char *dst = base + pl * WGG_PLANE + my_blk * 1024;
             if (pl < 4 * WK) {
-                const unsigned off = in ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
+                unsigned off = in ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
+                if constexpr (DN) off = inn ? dyn_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
             } else {
-                const unsigned off = xin ? x_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
+                unsigned off = xin ? x_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
+                if constexpr (XN) off = inn ? xn_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
             }
         }
@@ -123,19 +156,22 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     // this lane's byte offset inside a plane for step j: positions 32 j + 4 grp + L/4 (+16), column group
     // L%4; the 64 lanes of one load cover 512 contiguous bytes (no bank conflicts)
     const int lane_off = (grp * 4 + (L >> 2)) * 32 + (L & 3) * 8;
+    const int lane_off_n = L * 32 + grp * 8;           // NCHW planes: channel row L, positions 4 grp (+16)
 
     if (nstages > 0) issue_loads(0, 0);
     for (int s = 0; s < nstages; ++s) {
         __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's loads of stage s have landed
         __syncthreads();
         if (s + 1 < nstages) issue_loads(s + 1, (s + 1) & 1);
-        const unsigned char *dys = smem + (s & 1) * STAGE + (4 * wk) * WGG_PLANE + lane_off;
-        const unsigned char *xs = smem + (s & 1) * STAGE + (4 * WK + 4 * wc) * WGG_PLANE + lane_off;
+        const unsigned char *dys = smem + (s & 1) * STAGE + (4 * wk) * WGG_PLANE + (DN ? lane_off_n : lane_off);
+        const unsigned char *xs = smem + (s & 1) * STAGE + (4 * WK + 4 * wc) * WGG_PLANE + (XN ? lane_off_n : lane_off);
         auto fetch = [&](int j, bf16x8 (&a)[4], bf16x8 (&b)[4]) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = tr_frag_g(dys + i * WGG_PLANE + j * 1024);
+            for (int i = 0; i < 4; ++i)
+                a[i] = DN ? nchw_frag_g(dys + i * WGG_PLANE + j * 1024) : tr_frag_g(dys + i * WGG_PLANE + j * 1024);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) b[i] = tr_frag_g(xs + i * WGG_PLANE + j * 1024);
+            for (int i = 0; i < 4; ++i)
+                b[i] = XN ? nchw_frag_g(xs + i * WGG_PLANE + j * 1024) : tr_frag_g(xs + i * WGG_PLANE + j * 1024);
         };
         auto multiply = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[4]) {
 #pragma unroll
@@ -233,12 +269,12 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
     }
 }
 
-template <int WK, int WC, int SP>
-static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
+template <int WK, int WC, int SP, bool XN, bool DN>
+static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -246,8 +282,17 @@ static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
     dim3 grid(p.nparts, (p.K / (64 * WK)) * p.ctiles, p.R * p.S);
-    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP>), grid, dim3(512), lds, st, p);
+    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
+}
+
+template <int WK, int WC, int SP>
+static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
+{
+    if (p.x_nchw && p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, true>(p, st);
+    if (p.x_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, false>(p, st);
+    if (p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, false, true>(p, st);
+    return launch_wgrad_gemm_l<WK, WC, SP, false, false>(p, st);
 }
 
 template <int SP>

@@ -305,6 +305,33 @@ def test_gemm1x1_kernel(case, pre, variant, monkeypatch):
     _check_all(a, "bf16", BLK, BLK, pre, 7000 + case, ("gemm1x1", "gemm1x1", "wgrad"))
 
 
+NCHW_1X1_CASES = [
+    # n  c    h   w   k    r  s  sh sw dh dw pads      stride 1, no padding, H*W % 8 == 0
+    Attrs(2, 128, 8, 12, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 192 positions: one ragged tile
+    Attrs(3, 64, 16, 16, 128, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),     # 768 positions, tiles straddle images
+    Attrs(5, 256, 8, 8, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),       # 320 positions of a 512-position tile; 8 stages
+    Attrs(2, 64, 28, 28, 256, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),     # 1568 positions, ragged last tile
+    Attrs(9, 192, 4, 6, 320, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 24-position images: 10.7 images per 256-position tile
+]
+
+
+@pytest.mark.parametrize("case", range(len(NCHW_1X1_CASES)))
+@pytest.mark.parametrize("xl,yl", [(NCHW, BLK), (BLK, NCHW), (NCHW, NCHW)])
+@pytest.mark.parametrize("pre,variant", [(True, 0), (False, 0), (True, 3)])
+def test_gemm1x1_reads_and_writes_nchw(case, xl, yl, pre, variant, monkeypatch):
+    """Layout propagation: the 1x1 GEMM reads its activations from / writes its result to NCHW tensors."""
+    monkeypatch.setenv("NGC_G1_VARIANT", str(variant))
+    a = NCHW_1X1_CASES[case]
+    _check_all(a, "bf16", xl, yl, pre, 7300 + case, ("gemm1x1", "gemm1x1", "wgrad_gemm"))
+
+
+def test_nchw_1x1_outside_the_fast_path_takes_the_direct_kernel():
+    a = Attrs(2, 64, 7, 7, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0)       # 49 positions per image: not a multiple of 8
+    _check_all(a, "bf16", NCHW, BLK, False, 7400, ("direct", "direct", "direct"))
+    b = Attrs(2, 64, 8, 8, 64, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0)       # stride 2
+    _check_all(b, "bf16", BLK, NCHW, False, 7401, ("direct", "direct", "direct"))
+
+
 @pytest.mark.parametrize("case", [0, 3, 4, 5])
 def test_one_tap_gather_kernel_still_matches(case, monkeypatch):
     """1x1 shapes through the gather implicit-GEMM kernel (the pipelined GEMM switched off)."""
