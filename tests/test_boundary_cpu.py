@@ -133,6 +133,20 @@ def test_kernel_selection_and_sizes():
     assert ng.ngc_conv_variant(one, ng.NGC_OP_FWD) == "gemm1x1_bf16"
     assert ng.ngc_conv_variant(one, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
     assert ng.ngc_conv_variant(d, ng.NGC_OP_BWD_FILTERS).startswith("wgrad")
+    # layout propagation: 1x1, stride 1, no padding, H*W % 8 == 0 runs on the GEMM kernels with NCHW tensors
+    for xl, yl in ((ng.NGC_NCHW, ng.NGC_NCHW16C), (ng.NGC_NCHW16C, ng.NGC_NCHW), (ng.NGC_NCHW, ng.NGC_NCHW)):
+        kw = dict(n=64, c=256, h=56, w=56, r=1, s=1, pad_below=(0, 0), pad_above=(0, 0), x_layout=xl, y_layout=yl)
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **kw), ng.NGC_OP_FWD) == "gemm1x1_bf16"
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_BWD, **kw), ng.NGC_OP_BWD_DATA) == "gemm1x1_bf16"
+        assert ng.ngc_conv_variant(_good(**kw), ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
+        kw7 = dict(kw, h=7, w=7)                                              # 49 positions per image
+        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_FWD) == "direct"
+        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_BWD_FILTERS) == "direct"
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **kw7), ng.NGC_OP_FWD) == "unsupported"
+        kws = dict(kw, stride=(2, 2))
+        assert ng.ngc_conv_variant(_good(**kws), ng.NGC_OP_BWD_DATA) == "direct"
+    three = _good(n=8, h=56, w=56, x_layout=ng.NGC_NCHW)                      # 3x3 with NCHW x: not propagated
+    assert [ng.ngc_conv_variant(three, o) for o in range(3)] == ["direct"] * 3
     assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56
     assert ng.ngc_filter_elems(d, ng.NGC_BLOCKED_FWD) == 9 * 4 * 64 * 16
     f32 = _good(dtype=ng.NGC_F32, x_layout=ng.NGC_NCHW, y_layout=ng.NGC_NCHW)
