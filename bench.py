@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
                     help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
@@ -73,8 +73,9 @@ class LayerBench:
         cur = torch.cuda.current_stream().cuda_stream
 
         def mk(w_layout=ng.NGC_KCRS, epilogue=ng.NGC_EPI_NONE):
-            return ng.make_desc(L.n, L.c, L.h, L.w, L.k, L.r, L.s, (L.stride, L.stride), (L.dil, L.dil),
-                                (L.pad, L.pad), (L.pad, L.pad), ng.NGC_BF16, self.xl, self.yl, w_layout, epilogue)
+            n, c, h, w, k, r, s, sh, sw, dh, dw, pbh, pbw, pah, paw = L.attrs15
+            return ng.make_desc(n, c, h, w, k, r, s, (sh, sw), (dh, dw), (pbh, pbw), (pah, paw), ng.NGC_BF16,
+                                self.xl, self.yl, w_layout, epilogue)
 
         def dev_bits(values_f32):
             bits = synth_inputs.f32_to_bf16_bits(values_f32)      # values of bf16 configs are exactly representable
@@ -183,7 +184,7 @@ def cpu_baseline(L):
     import numpy as np
     import oracle
     import synth_inputs
-    a = oracle.Attrs(L.n, L.c, L.h, L.w, L.k, L.r, L.s, L.stride, L.stride, L.dil, L.dil, L.pad, L.pad, L.pad, L.pad)
+    a = oracle.Attrs(*L.attrs15)
     t = synth_inputs.layer_tensors(L)
     x, w, dy = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
     t0 = time.perf_counter()
@@ -302,7 +303,9 @@ def main():
         "config": {"workload": {2: "configs[1]: 3x3 conv N=64 C=K=64 56x56 s1 p1 bf16, fwd(+bias+ReLU) + bwd_data + bwd_filters",
                                 3: "configs[2]: 1x1 conv N=64 C=256 K=64 56x56 bf16, NCHW->nChw16c convert + fwd + bwd_data + bwd_filters",
                                 4: "configs[3]: stem 7x7/2 N=64 C=3 K=64 224x224 bf16, fwd(+bias+ReLU) + bwd_filters",
-                                5: "configs[4]: ResNet-50 conv stack N=128 bf16, 53 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
+                                5: "configs[4]: ResNet-50 conv stack N=128 bf16, 53 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)",
+                                6: "general-attribute layers (dilation, padding below != above, 5x5 / 1x7 / 7x1 / 2x2 windows, "
+                                   "per-axis strides) N=32 bf16, 8 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
                    "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
                    "streams": 3 if streams else 1,
                    **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {})},

@@ -25,7 +25,7 @@ import math
 import os
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
-from typing import Dict, List, Tuple
+from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
@@ -150,14 +150,30 @@ class ConvLayer:
     w_dist: Tuple = ("he",)
     seed: int = 0
     count: int = 1                  # multiplicity inside the configuration
+    # per-axis / per-side attributes where they differ from the scalars above: (h, w) pairs
+    strides: Optional[Tuple[int, int]] = None
+    dilation: Optional[Tuple[int, int]] = None
+    pad_below: Optional[Tuple[int, int]] = None
+    pad_above: Optional[Tuple[int, int]] = None
+
+    @property
+    def attrs15(self) -> Tuple[int, ...]:
+        """(n, c, h, w, k, r, s, sh, sw, dh, dw, pbh, pbw, pah, paw): the constant attributes of the node."""
+        sh, sw = self.strides or (self.stride, self.stride)
+        dh, dw = self.dilation or (self.dil, self.dil)
+        pbh, pbw = self.pad_below or (self.pad, self.pad)
+        pah, paw = self.pad_above or (self.pad, self.pad)
+        return (self.n, self.c, self.h, self.w, self.k, self.r, self.s, sh, sw, dh, dw, pbh, pbw, pah, paw)
 
     @property
     def p(self) -> int:
-        return (self.h + 2 * self.pad - self.dil * (self.r - 1) - 1) // self.stride + 1
+        _, _, h, _, _, r, _, sh, _, dh, _, pbh, _, pah, _ = self.attrs15
+        return (h + pbh + pah - dh * (r - 1) - 1) // sh + 1
 
     @property
     def q(self) -> int:
-        return (self.w + 2 * self.pad - self.dil * (self.s - 1) - 1) // self.stride + 1
+        _, _, _, w, _, _, s, _, sw, _, dw, _, pbw, _, paw = self.attrs15
+        return (w + pbw + paw - dw * (s - 1) - 1) // sw + 1
 
     @property
     def flop_per_op(self) -> float:
@@ -202,8 +218,27 @@ def _resnet50_layers(n: int) -> List[ConvLayer]:
     return out
 
 
+def _general_attribute_layers(n: int) -> List[ConvLayer]:
+    """Layers that exercise the attributes the ResNet stack does not: window dilation, padding that
+    differs below / above, rectangular and larger windows, per-axis strides (shapes in the style of
+    atrous segmentation heads and of factorised 1x7 / 7x1 and 5x5 inception branches)."""
+    mk = lambda i, name, **kw: ConvLayer(name, n, seed=BASE_SEED + 6 + 1000 * i, **kw)
+    return [
+        mk(0, "g_3x3_dil2_c256", c=256, h=28, w=28, k=256, r=3, s=3, pad=2, dil=2),
+        mk(1, "g_3x3_dil4_c128", c=128, h=56, w=56, k=128, r=3, s=3, pad=4, dil=4),
+        mk(2, "g_5x5_c64k128", c=64, h=28, w=28, k=128, r=5, s=5, pad=2),
+        mk(3, "g_1x7_c128k192", c=128, h=17, w=17, k=192, r=1, s=7, pad_below=(0, 3), pad_above=(0, 3)),
+        mk(4, "g_7x1_c128k192", c=128, h=17, w=17, k=192, r=7, s=1, pad_below=(3, 0), pad_above=(3, 0)),
+        mk(5, "g_3x3_s2_padabove", c=128, h=56, w=56, k=128, r=3, s=3, stride=2, pad_below=(0, 0), pad_above=(1, 1)),
+        mk(6, "g_2x2_s2_c64k128", c=64, h=56, w=56, k=128, r=2, s=2, stride=2),
+        mk(7, "g_3x3_s1x2_dil2x1", c=64, h=30, w=40, k=64, r=3, s=3, strides=(1, 2), dilation=(2, 1),
+           pad_below=(2, 1), pad_above=(2, 0)),
+    ]
+
+
 def config_layers(cfg: int, batch: int | None = None) -> List[ConvLayer]:
-    """Layer list of benchmark configuration `cfg` (1..5).  `batch` overrides N
+    """Layer list of benchmark configuration `cfg` (1..5; 6 = general-attribute layers, not one of the
+    headline configurations).  `batch` overrides N
     (used by tests that want the same recipe at a size the oracle finishes)."""
     if cfg == 1:
         return [ConvLayer("cfg1_f32_3x3", batch or 2, 16, 16, 16, 32, 3, 3, 1, 1, dtype="f32",
@@ -220,6 +255,8 @@ def config_layers(cfg: int, batch: int | None = None) -> List[ConvLayer]:
                           seed=BASE_SEED + 4)]
     if cfg == 5:
         return _resnet50_layers(batch or 128)
+    if cfg == 6:
+        return _general_attribute_layers(batch or 32)
     raise ValueError(f"unknown configuration {cfg}")
 
 

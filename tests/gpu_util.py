@@ -17,8 +17,7 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
 def attrs_of(L: ConvLayer) -> oracle.Attrs:
-    return oracle.Attrs(L.n, L.c, L.h, L.w, L.k, L.r, L.s, L.stride, L.stride, L.dil, L.dil,
-                        L.pad, L.pad, L.pad, L.pad)
+    return oracle.Attrs(*L.attrs15)
 
 
 def desc_of(a: oracle.Attrs, dtype: str, x_layout, y_layout, w_layout=ng.NGC_KCRS, epilogue=ng.NGC_EPI_NONE):

@@ -502,3 +502,19 @@ def test_cfg5_shapes_full_batch(idx):
 def test_cfg5_shapes_reduced_batch(idx):
     L = synth_inputs.config_layers(5, batch=4)[idx]
     _sampled_layer_check(L, n_y=20_000, n_dw=256)
+
+
+# ------------------------------------------------------------------ general-attribute layers (dilation, padding
+# below != above, 5x5 / 1x7 / 7x1 / 2x2 windows, per-axis strides) at the sizes bench.py --workload cfg6 times
+@pytest.mark.parametrize("idx", range(8))
+def test_general_attribute_layers_full_batch(idx):
+    L = synth_inputs.config_layers(6)[idx]
+    _sampled_layer_check(L, n_y=20_000, n_dw=256)
+    d = Run(attrs_of(L), "bf16", BLK, BLK, True)
+    assert L.p == d.P and L.q == d.Q
+
+
+@pytest.mark.parametrize("idx", range(8))
+def test_general_attribute_layers_whole_tensors(idx):
+    L = synth_inputs.config_layers(6, batch=2)[idx]
+    _check_all(attrs_of(L), "bf16", BLK, BLK, True, 9000 + idx, ("strip", "strip", "wgrad"))
