@@ -43,7 +43,7 @@
  *
  * Every op accepts every combination of data layouts; which combinations run on the MFMA kernels
  * (bf16) and which on the slow direct kernels is a property of the build: blocked x and y for all
- * shapes with C and K multiples of 64, NCHW x of the 3-channel stem, and NCHW x and / or y of 1x1
+ * shapes with C and K multiples of 16, NCHW x of the 3-channel stem, and NCHW x and / or y of 1x1
  * layers with stride 1, no padding and H*W a multiple of 8 (ngc_conv_variant names the choice).
  *
  * Element layouts

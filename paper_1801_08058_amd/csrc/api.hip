@@ -119,7 +119,7 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
         q.div_q = make_fastdiv((uint32_t)Wout);
         q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
         q.div_pc = make_fastdiv((uint32_t)q.PC);
-        const long wgs = (long)q.groups * q.strips * (Cout / 64);
+        const long wgs = (long)q.groups * q.strips * ((Cout + 63) / 64);
         // the patch limit may leave the strip smaller than the candidate: smallest variant that holds it
         int nf_eff = nf;
         if (forced_nf <= 0) {
@@ -147,7 +147,7 @@ bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int
     if (all_taps < 2 || all_taps > STRIP_MAX_TAPS) return false;
     const bool fwd = op == NGC_OP_FWD;
     const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
-    if (Cin % 16 != 0 || Cout % 64 != 0) return false;
+    if (Cin % 16 != 0 || Cout % 16 != 0) return false;       // the last 64-channel tile of the output may be partial
     const int Hin = fwd ? d->h : P, Win = fwd ? d->w : Q;
     const int Hfull = fwd ? P : d->h, Wfull = fwd ? Q : d->w;
     const size_t in_bytes = (size_t)d->n * Cin * Hin * Win * 2;
@@ -470,7 +470,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
 {
     const char *force = getenv("NGC_WGRAD_GEMM");
     if (force && atoi(force) == 0) return false;
-    if (d->c % 64 != 0 || d->k % 64 != 0 || d->r * d->s > 64 || d->dtype != NGC_BF16) return false;
+    if (d->c % 16 != 0 || d->k % 16 != 0 || d->r * d->s > 64 || d->dtype != NGC_BF16) return false;
     const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * P * Q * 2;
     if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
     WgradGemmParams q;
@@ -489,11 +489,14 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q; q.R = d->r; q.S = d->s;
     q.sh = d->stride_h; q.sw = d->stride_w; q.dil_h = d->dil_h; q.dil_w = d->dil_w;
     q.pbh = d->pad_below_h; q.pbw = d->pad_below_w;
-    q.wk = d->k % 128 == 0 ? 2 : 1;
-    q.wc = d->c % 128 == 0 ? 2 : 1;
-    q.ctiles = d->c / (64 * q.wc);
+    // 128-wide tiles when they waste no more of a partial last tile than 64-wide ones (channel counts % 16 == 0)
+    auto wide = [](int ch) { return ch > 64 && (ch + 127) / 128 * 128 <= (ch + 63) / 64 * 64; };
+    q.wk = wide(d->k) ? 2 : 1;
+    q.wc = wide(d->c) ? 2 : 1;
+    q.ktiles = (d->k + 64 * q.wk - 1) / (64 * q.wk);
+    q.ctiles = (d->c + 64 * q.wc - 1) / (64 * q.wc);
     q.M = (uint32_t)d->n * P * Q;
-    const uint32_t tiles = (uint32_t)(d->k / (64 * q.wk)) * q.ctiles * d->r * d->s;
+    const uint32_t tiles = (uint32_t)q.ktiles * q.ctiles * d->r * d->s;
     // Stage size: 64-position stages take half the LDS, so two workgroups fit a compute unit and
     // twice as many position chunks are cut.  That pays when there are many (tile, tap) pairs, i.e.
     // few chunks and little extra partial traffic, and for multi-tap layers; the large-image 1x1
@@ -528,7 +531,7 @@ bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *g
     if (d->r != 1 || d->s != 1) return false;
     const bool fwd = op == NGC_OP_FWD;
     const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
-    if (Cin % 64 != 0 || Cout % 64 != 0 || d->dtype != NGC_BF16) return false;
+    if (Cin % 16 != 0 || Cout % 16 != 0 || d->dtype != NGC_BF16) return false;   // partial last tiles / stages are masked
     Gemm1x1Params q;
     memset(&q, 0, sizeof(q));
     q.Cin = Cin; q.Cout = Cout;
@@ -660,7 +663,7 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_GEMM) {
         WgradGemmParams wp;
         wgrad_gemm_plan(d, P, Q, &wp);
-        return round256((size_t)wp.nparts * d->r * d->s * d->k * d->c * sizeof(float));
+        return round256((size_t)wp.nparts * d->r * d->s * wp.ktiles * wp.ctiles * wp.wk * wp.wc * 64 * 64 * sizeof(float));
     }
     if (op == NGC_OP_BWD_FILTERS && v == V_WGRAD_STRIP) {
         WgradStripParams wp;

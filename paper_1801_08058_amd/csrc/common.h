@@ -251,7 +251,7 @@ struct WgradGemmParams {
     int32_t wk, wc;            // 64-wide sub-tiles of k and c per workgroup
     int32_t sp;                // positions per LDS stage (128 or 64)
     int32_t x_nchw, dy_nchw;   // operand read from an NCHW tensor (1x1, stride 1, no padding, H*W % 8 == 0)
-    int32_t ctiles;            // C / (64 wc)
+    int32_t ktiles, ctiles;    // tiles of 64 wk output and 64 wc input channels (the last of each may be partial)
     int32_t nparts;
     uint32_t M, chunk;         // N*P*Q, positions per part (multiple of 128)
     uint32_t x_bytes, dy_bytes;

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // XCD-aware tile order: id = xcd + 8 * (mgroup * NT + ntile), m-tile = mgroup * 8 + xcd
-    const int NT = p.Cout / BN;
+    const int NT = (p.Cout + BN - 1) / BN;             // the last tile may be partial (Cout % 16 == 0)
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
     const int ntile = slot % NT;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     const uint32_t m0 = (uint32_t)mtile * BM;
     if (m0 >= p.M) return;                             // uniform per workgroup
     const int n0 = ntile * BN;
-    const int nsteps = p.Cin / (16 * KB);
+    const int nsteps = (p.Cin + 16 * KB - 1) / (16 * KB);   // channel blocks past Cin (% 16 == 0) are loaded as zeros
 
     if (wave >= NCW) {
         // ---- loader waves (the last NL): all global->LDS traffic of the workgroup.  A wave whose loads are
@@ -136,23 +136,25 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 #pragma unroll
                 for (int q = 0; q < QPL; ++q) {
                     const int quad = lw * QPL + q;                     // 4-channel group of the stage
-                    const unsigned soff_x = (unsigned)((s * 16 * KB + 4 * quad) * HWin * 2);
+                    const bool live = s * 16 * KB + 4 * quad < p.Cin;
+                    const unsigned soff_x = live ? (unsigned)((s * 16 * KB + 4 * quad) * HWin * 2) : 0u;
 #pragma unroll
                     for (int h = 0; h < NH128; ++h)
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + quad * (BM * 8) + h * 1024), 16,
-                                                                 (int)xvoff[h], (int)soff_x, 0, 0);
+                                                                 (int)(live ? xvoff[h] : G1_OOB), (int)soff_x, 0, 0);
                 }
             }
 #pragma unroll
             for (int q = 0; q < PPL; ++q) {
                 const int pl = lw * PPL + q;
                 const int cb = s * KB + (pl >> 1);
-                const unsigned soff_x = (unsigned)(cb * HWin * 32);
-                const unsigned soff_w = (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16);
+                const bool live = cb < CBin;                          // wave-uniform
+                const unsigned soff_x = live ? (unsigned)(cb * HWin * 32) : 0u;
+                const unsigned soff_w = (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16);   // past the end for cb >= CBin: zeros
 #pragma unroll
                 for (int b = 0; b < WM; ++b) {
                     if constexpr (XN) break;
-                    const unsigned v = (xvoff[b] == G1_OOB) ? G1_OOB : xvoff[b] + (pl & 1) * 16;
+                    const unsigned v = (xvoff[b] == G1_OOB || !live) ? G1_OOB : xvoff[b] + (pl & 1) * 16;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_in, (lds_void_q *)(xs + pl * XPLANE + b * 1024), 16, (int)v,
                                                              (int)soff_x, 0, 0);
                 }
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 for (int v = 0; v < 16; ++v) {
                     const int ch = a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
                     float val = acc[a][b][v];
-                    if (p.bias) val += p.bias[n0 + wn * 32 * FA + ch];
+                    if (p.bias && n0 + wn * 32 * FA + ch < p.Cout) val += p.bias[n0 + wn * 32 * FA + ch];
                     if (p.relu) val = fmaxf(val, 0.f);
                     *reinterpret_cast<uint16_t *>(st + ch * YROW + (b * 32 + l32) * 2) =
                         (uint16_t)(pack_bf16x2_hw(val, 0.f) & 0xFFFFu);
@@ -247,6 +249,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 #pragma unroll
             for (int it = 0; it < 4 * FA; ++it) {
                 const int ch = it * 8 + (lane >> 3);
+                if (n0 + wn * 32 * FA + ch >= p.Cout) continue;
                 uint4 o = *reinterpret_cast<const uint4 *>(st + ch * YROW + piece * 16);
                 const size_t off = ((size_t)n * p.Cout + (n0 + wn * 32 * FA + ch)) * HWout + pp;
                 if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + off));
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 float v[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = acc[a][b][8 * h + e];
-                if (p.bias) {
+                if (p.bias && co_base + 16 * h < p.Cout) {
                     const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 4 * lg);
                     const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 8 + 4 * lg);
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
                 uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
-                if (ok) {
+                if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
@@ -333,12 +336,12 @@ static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
     constexpr int BM = 64 * WM, BN = 32 * FA * WN;
     constexpr size_t stage = (size_t)2 * KB * ((BM * 16 + 128) + (BN * 16 + 128));
     // short reductions use fewer ring buffers than NS: less LDS, more workgroups per compute unit
-    const int nsteps = p.Cin / (16 * KB);
+    const int nsteps = (p.Cin + 16 * KB - 1) / (16 * KB);
     size_t lds = (size_t)(nsteps < NS ? nsteps : NS) * stage;
     constexpr size_t staging = (size_t)WM * WN * 32 * FA * 144;        // YN: one [channel][64 positions] tile per MFMA wave
     if (YN && lds < staging) lds = staging;
     const unsigned mtiles = (p.M + BM - 1) / BM;
-    const unsigned grid = ((mtiles + 7) / 8) * 8 * (p.Cout / BN);
+    const unsigned grid = ((mtiles + 7) / 8) * 8 * ((p.Cout + BN - 1) / BN);
     NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
     return hipGetLastError();
 }
@@ -369,15 +372,18 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
     int variant = ev ? atoi(ev) : 0;
+    // 128-channel tiles when they waste no more of a partial last tile than 64-channel tiles would (Cout % 16 == 0)
+    const int c128 = (p.Cout + 127) / 128, c64 = (p.Cout + 63) / 64;
+    const bool wide = p.Cout > 64 && c128 * 128 <= c64 * 64;
     if (p.in_nchw || p.out_nchw) {
         if (variant != 3) variant = 0;
-        if (variant == 0 && p.Cout % 128 == 0 && ((p.M + 255) / 256) * (unsigned)(p.Cout / 128) < 2 * 256) variant = 3;
-        if (p.Cout % 128 == 0) return variant == 3 ? launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st) : launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
+        if (variant == 0 && wide && ((p.M + 255) / 256) * (unsigned)c128 < 2 * 256) variant = 3;
+        if (wide) return variant == 3 ? launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st) : launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
         return variant == 3 ? launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st) : launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
     }
-    if (p.Cout % 128 == 0) {
+    if (wide) {
         if (variant == 0) {
-            const unsigned tiles = ((p.M + 255) / 256) * (unsigned)(p.Cout / 128);
+            const unsigned tiles = ((p.M + 255) / 256) * (unsigned)c128;
             // long reductions over enough 256 x 256 tiles: 64 x 128 wave tiles (fewer LDS operand fetches
             // per MFMA; one workgroup per compute unit, which short reductions do not amortise)
             if (p.Cout % 256 == 0 && p.Cin >= 512 && tiles / 2 >= 192) variant = 6;

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (p.bias) {
+            if (p.bias && k0 + a * 32 + 16 * h < p.Cout) {       // the last 64-channel tile may be partial (Cout % 16 == 0)
                 bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
                 bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
             }
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
                 const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
                 uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
-                if (ok) {
+                if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
@@ -331,7 +331,7 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid(p.groups * p.strips, p.Cout / 64);
+    dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
     NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }

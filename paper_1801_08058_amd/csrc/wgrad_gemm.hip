@@ -133,13 +133,16 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
         for (int j = 0; j < NITEM; ++j) {
             const int pl = wave / BLK + (NW / BLK) * j;                  // plane index of item wave + 8 j
             unsigned char *dst = base + pl * WGG_PLANE + my_blk * 1024;
+            // channel blocks past K / C (multiples of 16; the last tile may be partial) are loaded as zeros
             if (pl < 4 * WK) {
-                unsigned off = in ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
-                if constexpr (DN) off = inn ? dyn_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
+                const bool live = kb0 + pl < KB;
+                unsigned off = (in && live) ? dy_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
+                if constexpr (DN) off = (inn && live) ? dyn_off + (unsigned)(pl * PQ * 32) : WGG_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
             } else {
-                unsigned off = xin ? x_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
-                if constexpr (XN) off = inn ? xn_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
+                const bool live = cb0 + (pl - 4 * WK) < CB;
+                unsigned off = (xin && live) ? x_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
+                if constexpr (XN) off = (inn && live) ? xn_off + (unsigned)((pl - 4 * WK) * HW * 32) : WGG_OOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_g *)dst, 16, (int)off, 0, 0, 0);
             }
         }
@@ -232,12 +235,13 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 }
 
 // dw[k][c][tap] = sum over parts (index order).  Element i (float4) of a part:
-// i = ((((tap * tiles + tile) * WK*WC + sub) * 4 + kb) * 4 + cq) * 64 + lane.
+// i = ((((tap * tiles + tile) * WK*WC + sub) * 4 + kb) * 4 + cq) * 64 + lane; tiles cover K and C rounded up
+// to the tile size, elements outside [K] x [C] are dropped here.
 __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
-                                                        int nparts, int K, int C, int RS, int ctiles, int WK, int WC)
+                                                        int nparts, int K, int C, int RS, int ktiles, int ctiles, int WK, int WC)
 {
     __shared__ f32x4 sm[8][32];
-    const size_t per4 = (size_t)RS * K * C / 4;
+    const size_t per4 = (size_t)RS * ktiles * ctiles * WK * WC * (64 * 64 / 4);
     const int o = threadIdx.x & 31;
     const int sl = threadIdx.x >> 5;
     const size_t i = (size_t)blockIdx.x * 32 + o;
@@ -257,15 +261,17 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
         const int cq = (int)(u & 3); u >>= 2;
         const int kb = (int)(u & 3); u >>= 2;
         const int sub = (int)(u % (WK * WC)); u /= (WK * WC);
-        const int tiles = (K / (64 * WK)) * ctiles;
+        const int tiles = ktiles * ctiles;
         const int tile = (int)(u % tiles);
         const int tap = (int)(u / tiles);
         const int kt = tile / ctiles, ct = tile - kt * ctiles;
         const int wk = sub / WC, wc = sub - wk * WC;
         const int k = (kt * WK + wk) * 64 + kb * 16 + 4 * (lane >> 4);
         const int c = (ct * WC + wc) * 64 + cq * 16 + (lane & 15);
+        if (c < C && k < K) {                                // K % 4 == 0
 #pragma unroll
-        for (int v = 0; v < 4; ++v) dw[((size_t)(k + v) * C + c) * RS + tap] = r[v];
+            for (int v = 0; v < 4; ++v) dw[((size_t)(k + v) * C + c) * RS + tap] = r[v];
+        }
     }
 }
 
@@ -281,7 +287,7 @@ static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
     }
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
-    dim3 grid(p.nparts, (p.K / (64 * WK)) * p.ctiles, p.R * p.S);
+    dim3 grid(p.nparts, p.ktiles * p.ctiles, p.R * p.S);
     NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
 }
@@ -309,9 +315,9 @@ hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
 {
     const hipError_t e = p.sp == 64 ? launch_wgrad_gemm_sp<64>(p, st) : launch_wgrad_gemm_sp<128>(p, st);
     if (e != hipSuccess) return e;
-    const size_t per4 = (size_t)p.R * p.S * p.K * p.C / 4;
+    const size_t per4 = (size_t)p.R * p.S * p.ktiles * p.ctiles * p.wk * p.wc * (64 * 64 / 4);
     NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
-               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.R * p.S, p.ctiles, p.wk, p.wc);
+               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.R * p.S, p.ktiles, p.ctiles, p.wk, p.wc);
     return hipGetLastError();
 }
 

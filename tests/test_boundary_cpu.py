@@ -145,6 +145,19 @@ def test_kernel_selection_and_sizes():
         assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **kw7), ng.NGC_OP_FWD) == "unsupported"
         kws = dict(kw, stride=(2, 2))
         assert ng.ngc_conv_variant(_good(**kws), ng.NGC_OP_BWD_DATA) == "direct"
+    # channel counts: multiples of 16 run on the MFMA kernels (partial last tiles), anything else on the direct kernels
+    for c, k in ((48, 96), (80, 16), (16, 208)):
+        t3 = dict(n=8, c=c, k=k, h=28, w=28)
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **t3), ng.NGC_OP_FWD) == "strip_bf16"
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_BWD, **t3), ng.NGC_OP_BWD_DATA) == "strip_bf16"
+        assert ng.ngc_conv_variant(_good(**t3), ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
+        t1 = dict(t3, r=1, s=1, pad_below=(0, 0), pad_above=(0, 0))
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **t1), ng.NGC_OP_FWD) == "gemm1x1_bf16"
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_BWD, **t1), ng.NGC_OP_BWD_DATA) == "gemm1x1_bf16"
+        ws = ng.ngc_conv_workspace_bytes(_good(**t1), ng.NGC_OP_BWD_FILTERS)
+        assert ws >= ((k + 63) // 64) * ((c + 63) // 64) * 64 * 64 * 4      # partials cover whole tiles
+    odd = dict(n=8, c=40, k=72, h=28, w=28)
+    assert [ng.ngc_conv_variant(_good(**odd), o) for o in range(3)] == ["direct"] * 3
     three = _good(n=8, h=56, w=56, x_layout=ng.NGC_NCHW)                      # 3x3 with NCHW x: not propagated
     assert [ng.ngc_conv_variant(three, o) for o in range(3)] == ["direct"] * 3
     assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56

@@ -205,12 +205,12 @@ def test_mfma_kernels_small(case, pre, nf, strip_nf):
     # residue class of the stride unless a class has no tap at all (case 5: odd rows of dx stay zero)
     strip_ok = a.r * a.s > 1 and nf != 0
     bwd_strip_ok = strip_ok and case != 5
-    one_tap = a.r * a.s == 1 and a.c % 64 == 0 and a.k % 64 == 0
-    fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 64 == 0) else "gemm1x1" if one_tap else \
+    one_tap = a.r * a.s == 1 and a.c % 16 == 0 and a.k % 16 == 0
+    fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 16 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.c % 32 == 0 and a.k % 64 == 0) else "direct"
-    bwd_v = "strip" if (bwd_strip_ok and a.k % 16 == 0 and a.c % 64 == 0) else "gemm1x1" if one_tap else \
+    bwd_v = "strip" if (bwd_strip_ok and a.k % 16 == 0 and a.c % 16 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.k % 32 == 0 and a.c % 64 == 0) else "direct"
-    wg_v = "wgrad" if (a.c % 64 == 0 and a.k % 64 == 0) else "direct"
+    wg_v = "wgrad" if (a.c % 16 == 0 and a.k % 16 == 0) else "direct"
     _check_all(a, "bf16", BLK, BLK, pre, 2000 + case, (fwd_v, bwd_v, wg_v))
 
 
@@ -303,6 +303,35 @@ def test_gemm1x1_kernel(case, pre, variant, monkeypatch):
     monkeypatch.setenv("NGC_G1_VARIANT", str(variant))
     a = GEMM1X1_CASES[case]
     _check_all(a, "bf16", BLK, BLK, pre, 7000 + case, ("gemm1x1", "gemm1x1", "wgrad"))
+
+
+CHANNEL_TAIL_CASES = [
+    # n  c    h   w   k    r  s  sh sw dh dw pads      channel counts that are multiples of 16 but not of 64
+    Attrs(2, 48, 14, 14, 96, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # strip: second 64-channel tile half empty
+    Attrs(3, 80, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),        # one output block of a 64-channel tile
+    Attrs(2, 16, 12, 12, 48, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # one input chunk
+    Attrs(2, 48, 16, 16, 80, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),      # strided: per-class backprop-data launches
+    Attrs(2, 48, 8, 8, 96, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),        # 1x1: partial last stage (48 = 32 + 16) and tile
+    Attrs(3, 80, 10, 10, 16, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 1x1: 16 outputs of a 64-channel tile
+    Attrs(2, 144, 7, 7, 208, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 1x1: 128-wide tiles, the second 80 / 128 full
+    Attrs(2, 96, 8, 8, 48, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),        # 1x1 stride 2
+    Attrs(2, 112, 12, 12, 160, 5, 5, 1, 1, 1, 1, 2, 2, 2, 2),    # 5x5, both channel counts partial
+]
+
+
+@pytest.mark.parametrize("case", range(len(CHANNEL_TAIL_CASES)))
+@pytest.mark.parametrize("pre", [True, False])
+def test_channel_counts_not_multiples_of_64(case, pre):
+    a = CHANNEL_TAIL_CASES[case]
+    fb = "gemm1x1" if a.r * a.s == 1 else "strip"
+    _check_all(a, "bf16", BLK, BLK, pre, 7500 + case, (fb, fb, "wgrad_gemm"))
+
+
+@pytest.mark.parametrize("xl,yl", [(NCHW, BLK), (BLK, NCHW), (NCHW, NCHW)])
+def test_channel_tails_with_nchw_tensors(xl, yl):
+    _check_all(CHANNEL_TAIL_CASES[4], "bf16", xl, yl, True, 7600, ("gemm1x1", "gemm1x1", "wgrad_gemm"))
+    _check_all(Attrs(2, 80, 4, 6, 208, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0), "bf16", xl, yl, True, 7601,
+               ("gemm1x1", "gemm1x1", "wgrad_gemm"))
 
 
 NCHW_1X1_CASES = [
