@@ -1,4 +1,4 @@
-"""CPU oracle for the Convolution op family -- TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for the Convolution op family and Softmax -- TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import
 this package; the product (paper_1801_08058_amd) never does.
@@ -9,3 +9,4 @@ from .conv_oracle import (  # noqa: F401
     blocked16_to_nchw, f32_to_bf16_bits_rne, bf16_bits_to_f64, max_normalised_error,
     relu_bwd_mask, bias_grad, conv_bwd_data_relu,
 )
+from .softmax_oracle import softmax, softmax_bwd  # noqa: F401

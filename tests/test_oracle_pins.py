@@ -346,3 +346,74 @@ def test_relu_conv_chain_gradient_by_central_differences():
         up[idx] += eps; dn[idx] -= eps
         fd = (loss(up) - loss(dn)) / (2 * eps)
         assert abs(fd - grad[idx]) < 1e-9, (idx, fd, grad[idx])
+
+
+# ---------------------------------------------------------------- P13 softmax and its backprop
+def test_softmax_closed_forms():
+    # constant rows -> 1/n whatever the constant (also where exp would overflow without the shift)
+    for n in (1, 2, 7, 1000):
+        for c in (0.0, -3.5, 800.0, -800.0):
+            np.testing.assert_allclose(oracle.softmax(np.full((2, n), c)), np.full((2, n), 1.0 / n), rtol=1e-15)
+    # two elements: the logistic function of the difference
+    a, b = rng.normal(size=50) * 5, rng.normal(size=50) * 5
+    y = oracle.softmax(np.stack([a, b], axis=-1))
+    np.testing.assert_allclose(y[:, 0], 1.0 / (1.0 + np.exp(b - a)), rtol=1e-14)
+    np.testing.assert_allclose(y[:, 1], 1.0 / (1.0 + np.exp(a - b)), rtol=1e-14)
+    # arithmetic progression x_j = j t: geometric series, y_j = q^j (q - 1) / (q^n - 1), q = e^t
+    n, t = 9, 0.37
+    q = np.exp(t)
+    np.testing.assert_allclose(oracle.softmax(t * np.arange(n)), q ** np.arange(n) * (q - 1) / (q ** n - 1), rtol=1e-13)
+    # one dominant element
+    x = np.array([0.0, 50.0, -2.0])
+    y = oracle.softmax(x)
+    assert abs(y[1] - 1.0) < 1e-20 + 2e-16 and abs(y[0] - np.exp(-50.0)) < 1e-30 and y.argmax() == 1
+
+
+def test_softmax_matches_the_unshifted_definition_and_scipy():
+    import scipy.special
+    x = rng.normal(size=(6, 4, 33)) * 3
+    direct = np.exp(x) / np.exp(x).sum(axis=-1, keepdims=True)           # no overflow at this magnitude
+    np.testing.assert_allclose(oracle.softmax(x), direct, rtol=1e-13)
+    np.testing.assert_allclose(oracle.softmax(x), scipy.special.softmax(x, axis=-1), rtol=1e-13)
+    # the last axis is the one normalised, not another one
+    assert not np.allclose(oracle.softmax(x), scipy.special.softmax(x, axis=1))
+    big = rng.normal(size=(5, 100)) * 200 + 3000
+    np.testing.assert_allclose(oracle.softmax(big), scipy.special.softmax(big, axis=-1), rtol=1e-12)
+
+
+def test_softmax_invariants():
+    x = rng.normal(size=(17, 301)) * 4
+    y = oracle.softmax(x)
+    np.testing.assert_allclose(y.sum(axis=-1), 1.0, rtol=1e-14)
+    assert (y > 0).all() and (y < 1).all()
+    np.testing.assert_allclose(oracle.softmax(x + rng.normal(size=(17, 1)) * 100), y, rtol=1e-11)     # shift invariance
+    # order preserving, and ratios are exp of differences
+    assert np.array_equal(np.argsort(x, axis=-1), np.argsort(y, axis=-1))
+    np.testing.assert_allclose(y[:, 5] / y[:, 9], np.exp(x[:, 5] - x[:, 9]), rtol=1e-12)
+    # rows are independent
+    x2 = x.copy(); x2[3] += rng.normal(size=301)
+    y2 = oracle.softmax(x2)
+    assert np.array_equal(np.delete(y2, 3, axis=0), np.delete(y, 3, axis=0)) and not np.allclose(y2[3], y[3])
+
+
+def test_softmax_bwd_is_the_transposed_jacobian_and_matches_central_differences():
+    n = 6
+    x = rng.normal(size=(3, n))
+    y = oracle.softmax(x)
+    dy = rng.normal(size=(3, n))
+    dx = oracle.softmax_bwd(y, dy)
+    for i in range(3):
+        jac = np.diag(y[i]) - np.outer(y[i], y[i])                        # d y_j / d x_k
+        np.testing.assert_allclose(dx[i], jac.T @ dy[i], rtol=1e-13, atol=1e-16)
+    loss = lambda t: float((oracle.softmax(t) * dy).sum())
+    eps = 1e-5
+    for idx in np.ndindex(x.shape):
+        up, dn = x.copy(), x.copy()
+        up[idx] += eps; dn[idx] -= eps
+        fd = (loss(up) - loss(dn)) / (2 * eps)
+        assert abs(fd - dx[idx]) < 1e-9, (idx, fd, dx[idx])
+    # a constant delta has no effect (rows of y sum to one), and dx rows sum to zero
+    np.testing.assert_allclose(oracle.softmax_bwd(y, np.full_like(y, 2.5)), 0.0, atol=1e-15)
+    np.testing.assert_allclose(dx.sum(axis=-1), 0.0, atol=1e-15)
+    # hand-worked: y = (1/2, 1/2), dy = (1, 0): s = 1/2, dx = (1/4, -1/4)
+    np.testing.assert_allclose(oracle.softmax_bwd(np.array([0.5, 0.5]), np.array([1.0, 0.0])), [0.25, -0.25], rtol=1e-15)
