@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "softmax"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
                     help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
@@ -179,6 +179,59 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+def softmax_main(args, torch, ng, synth_inputs):
+    """Softmax workloads (the other kernel the paper names): forward + backprop per case, HBM-bound."""
+    import numpy as np
+    cur = torch.cuda.current_stream().cuda_stream
+    cases = synth_inputs.softmax_cases()
+    bufs = []
+    for c in cases:
+        t = synth_inputs.softmax_tensors(c)
+        if c.dtype == "bf16":
+            up = lambda v: torch.from_numpy(np.ascontiguousarray(synth_inputs.f32_to_bf16_bits(v)).view(np.int16)).cuda()
+        else:
+            up = lambda v: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
+        x, dy = up(t["x"]), up(t["dy"])
+        bufs.append((c, ng.NGC_BF16 if c.dtype == "bf16" else ng.NGC_F32, x, dy, torch.empty_like(x), torch.empty_like(x)))
+
+    def step(_i):
+        for c, code, x, dy, y, dx in bufs:
+            ng.ngc_softmax(code, c.rows, c.cols, x, y, cur)
+            ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern = {}
+    reps = max(20, min(args.steps, 200))
+    total_bytes = 0
+    for c, code, x, dy, y, dx in bufs:
+        nbytes = c.rows * c.cols * (2 if c.dtype == "bf16" else 4)
+        total_bytes += 5 * nbytes
+        for op, fn, nb in (("fwd", lambda i: ng.ngc_softmax(code, c.rows, c.cols, x, y, cur), 2 * nbytes),
+                           ("bwd", lambda i: ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur), 3 * nbytes)):
+            ms = event_time_ms(torch, fn, reps)
+            kern[f"{c.name}:{op}"] = {"us": round(ms * 1e3, 2), "gbs": round(nb / (ms * 1e-3) / 1e9, 1), "bytes": nb,
+                                      "variant": ng.ngc_softmax_variant(code, c.cols, op == "bwd"), "count": 1}
+    dom_name = max(kern, key=lambda k: kern[k]["us"])
+    dom = kern[dom_name]
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "softmax forward + backprop, algorithmic GB/s over 4 workloads, 1 GPU", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "softmax over the last axis: [32768,1000], [262144,512], [4096,32000] bf16 and [65536,1024] fp32, "
+                               "forward + backprop each", "streams": 1},
+        "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom_name},
+        "kernels": kern}))
+
+
 def cpu_baseline(L):
     """The oracle as it stands, one pass over the full cfg2 tensors, timed on the host cores."""
     import numpy as np
@@ -213,6 +266,9 @@ def main():
     import paper_1801_08058_amd as ng
     import synth_inputs
 
+    if args.workload == "softmax":
+        softmax_main(args, torch, ng, synth_inputs)
+        return
     cfg = int(args.workload[3:])
     layers = synth_inputs.config_layers(cfg)
     sets = 1

@@ -134,6 +134,23 @@ int ngc_conv_bwd_data_relu(const ngc_conv_desc *desc, const void *dy, const void
 int ngc_bias_grad(const ngc_conv_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes,
                   void *hip_stream);
 
+/* Softmax over the last axis of a dense [rows, cols] tensor of `dtype` (the other kernel the paper
+ * names as supplied by a backend library, Sec. 4): y[i][j] = exp(x[i][j]) / sum_k exp(x[i][k]),
+ * evaluated with the row maximum subtracted, fp32 arithmetic, one rounding.  x, y: device pointers,
+ * element aligned (16-byte aligned tensors with cols a multiple of 16 bytes take the one-pass
+ * kernel); y may be x.  Inputs must be finite.  1 <= rows < 2^31, rows * cols < 2^40.
+ * NGC_BAD_ARG: bad dtype, NULL or misaligned pointer; NGC_BAD_SHAPE: bad sizes. */
+int ngc_softmax(int32_t dtype, int64_t rows, int32_t cols, const void *x, void *y, void *hip_stream);
+
+/* Backprop of ngc_softmax (Sec. 3: derivative graph of the forward op): dx[i][j] = y[i][j] *
+ * (dy[i][j] - sum_k dy[i][k] y[i][k]), y the forward result.  dx may be y or dy.  Same conditions. */
+int ngc_softmax_bwd(int32_t dtype, int64_t rows, int32_t cols, const void *y, const void *dy, void *dx,
+                    void *hip_stream);
+
+/* Name of the kernel ngc_softmax (bwd = 0) / ngc_softmax_bwd (bwd = 1) runs for 16-byte aligned
+ * tensors of this row length ("invalid" for bad arguments). */
+const char *ngc_softmax_variant(int32_t dtype, int32_t cols, int32_t bwd);
+
 /* ConvolutionBackpropFilters (Sec. 3, derivative w.r.t. the filters input).
  * x in x_layout, dy in y_layout; dw: fp32 [K][C][R][S], overwritten.  The cross-workgroup
  * reduction goes through `ws` (partials) and a fixed-order second stage. */

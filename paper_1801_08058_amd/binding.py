@@ -23,7 +23,7 @@ NGC_EPI_NONE, NGC_EPI_BIAS, NGC_EPI_RELU = 0, 1, 2
 NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD = 0, 1, 2, 3
 
 EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
-           "ngc_conv_bwd_data_relu", "ngc_bias_grad", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
+           "ngc_conv_bwd_data_relu", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string")
 
 
@@ -71,6 +71,12 @@ def _load() -> ctypes.CDLL:
     lib.ngc_conv_bwd_data_relu.restype = ctypes.c_int
     lib.ngc_bias_grad.argtypes = [D, vp, vp, vp, sz, vp]
     lib.ngc_bias_grad.restype = ctypes.c_int
+    lib.ngc_softmax.argtypes = [i32, ctypes.c_int64, i32, vp, vp, vp]
+    lib.ngc_softmax.restype = ctypes.c_int
+    lib.ngc_softmax_bwd.argtypes = [i32, ctypes.c_int64, i32, vp, vp, vp, vp]
+    lib.ngc_softmax_bwd.restype = ctypes.c_int
+    lib.ngc_softmax_variant.argtypes = [i32, i32, i32]
+    lib.ngc_softmax_variant.restype = ctypes.c_char_p
     lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_filters.restype = ctypes.c_int
     lib.ngc_layout_convert.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp]
@@ -171,6 +177,19 @@ def ngc_conv_bwd_data_relu(desc, dy, w, x_in, dx, ws=None, stream=None, check: b
 def ngc_bias_grad(desc, dy, db, ws=None, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_bias_grad(ctypes.byref(desc), _ptr(dy), _ptr(db), _ptr(ws), _nbytes(ws),
                                      _stream(stream)), "ngc_bias_grad", check)
+
+
+def ngc_softmax(dtype, rows, cols, x, y, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_softmax(dtype, rows, cols, _ptr(x), _ptr(y), _stream(stream)), "ngc_softmax", check)
+
+
+def ngc_softmax_bwd(dtype, rows, cols, y, dy, dx, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_softmax_bwd(dtype, rows, cols, _ptr(y), _ptr(dy), _ptr(dx), _stream(stream)),
+                  "ngc_softmax_bwd", check)
+
+
+def ngc_softmax_variant(dtype, cols, bwd=False) -> str:
+    return _lib.ngc_softmax_variant(dtype, cols, 1 if bwd else 0).decode()
 
 
 def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = True) -> int:

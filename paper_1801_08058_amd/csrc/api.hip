@@ -1005,6 +1005,44 @@ int ngc_bias_grad(const ngc_conv_desc *desc, const void *dy, float *db, void *ws
                                           static_cast<hipStream_t>(hip_stream)));
 }
 
+}  // extern "C"
+
+namespace {
+
+int softmax_impl(int32_t dtype, int64_t rows, int32_t cols, bool bwd, const void *a, const void *b, void *out, void *hip_stream)
+{
+    if (dtype != NGC_F32 && dtype != NGC_BF16) return NGC_BAD_ARG;
+    if (rows < 1 || cols < 1 || rows > 0x7fffffffll || (unsigned long long)rows * (unsigned long long)cols >= (1ull << 40))
+        return NGC_BAD_SHAPE;
+    if (!a || !out || (bwd && !b)) return NGC_BAD_ARG;
+    const uintptr_t esz = dtype == NGC_BF16 ? 2 : 4;
+    const uintptr_t all = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(out) | (bwd ? reinterpret_cast<uintptr_t>(b) : 0);
+    if (all & (esz - 1)) return NGC_BAD_ARG;
+    const int V = softmax_vectors(dtype, cols, bwd, (all & 15) == 0);
+    return launch_status(launch_softmax(dtype, bwd, a, b, out, (uint32_t)rows, cols, V, static_cast<hipStream_t>(hip_stream)));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ngc_softmax(int32_t dtype, int64_t rows, int32_t cols, const void *x, void *y, void *hip_stream)
+{
+    return softmax_impl(dtype, rows, cols, false, x, nullptr, y, hip_stream);
+}
+
+int ngc_softmax_bwd(int32_t dtype, int64_t rows, int32_t cols, const void *y, const void *dy, void *dx, void *hip_stream)
+{
+    return softmax_impl(dtype, rows, cols, true, y, dy, dx, hip_stream);
+}
+
+const char *ngc_softmax_variant(int32_t dtype, int32_t cols, int32_t bwd)
+{
+    if ((dtype != NGC_F32 && dtype != NGC_BF16) || cols < 1) return "invalid";
+    const int v = softmax_vectors(dtype, cols, bwd != 0, true);
+    return v == 0 ? "softmax_rows_block" : v > 256 ? "softmax_rows_wg" : "softmax_rows_wave";
+}
+
 int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw, void *ws,
                          size_t ws_bytes, void *hip_stream)
 {

@@ -304,6 +304,9 @@ hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x
                              const float *bias, void *y, hipStream_t st);
 hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w,
                                   const void *mask, void *dx, hipStream_t st);
+int softmax_vectors(int dtype, int cols, bool bwd, bool aligned);
+hipError_t launch_softmax(int dtype, bool bwd, const void *a, const void *b, void *out, uint32_t rows, int cols, int V,
+                          hipStream_t st);
 hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy, float *db, float *partial, int nparts,
                             hipStream_t st);
 int bias_grad_parts(const ngc_conv_desc &d, int P, int Q);

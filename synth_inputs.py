@@ -260,6 +260,34 @@ def config_layers(cfg: int, batch: int | None = None) -> List[ConvLayer]:
     raise ValueError(f"unknown configuration {cfg}")
 
 
+@dataclass
+class SoftmaxCase:
+    """One softmax workload: a dense [rows, cols] tensor, softmax over cols."""
+    name: str
+    rows: int
+    cols: int
+    dtype: str = "bf16"
+    seed: int = 0
+
+
+def softmax_cases(scale: int = 1) -> List[SoftmaxCase]:
+    """Softmax workloads: classifier logits, attention-score rows, a vocabulary-sized row (longer than the
+    one-pass kernel holds in registers) and an fp32 case.  `scale` divides the row counts (tests)."""
+    mk = lambda i, name, rows, cols, dtype="bf16": SoftmaxCase(name, max(1, rows // scale), cols, dtype,
+                                                             BASE_SEED + 7 + 1000 * i)
+    return [mk(0, "sm_logits_1000", 32768, 1000), mk(1, "sm_attn_512", 262144, 512),
+            mk(2, "sm_vocab_32000", 4096, 32000), mk(3, "sm_f32_1024", 65536, 1024, "f32")]
+
+
+def softmax_tensors(c: SoftmaxCase) -> Dict[str, np.ndarray]:
+    """x ~ N(0, 3^2) (logit-like spread), dy ~ N(0, 0.1^2); bf16 cases hold bf16-representable values."""
+    x = normal(c.seed, TENSOR_X, (c.rows, c.cols), 0.0, 3.0)
+    dy = normal(c.seed, TENSOR_DY, (c.rows, c.cols), 0.0, 0.1)
+    if c.dtype == "bf16":
+        x, dy = bf16_bits_to_f32(f32_to_bf16_bits(x)), bf16_bits_to_f32(f32_to_bf16_bits(dy))
+    return {"x": x, "dy": dy}
+
+
 def _draw(dist: Tuple, seed: int, tid: int, shape, fan_in: int) -> np.ndarray:
     if dist[0] == "uniform":
         return uniform(seed, tid, shape, dist[1], dist[2])

@@ -112,6 +112,29 @@ def test_backward_compounds_validate_before_launch():
     assert ng.ngc_conv_variant(bad, ng.NGC_OP_BIAS_GRAD) == "invalid"
 
 
+def test_softmax_validates_before_launch():
+    fake = 0x1000
+    assert ng.ngc_softmax(ng.NGC_BF16, 0, 8, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_softmax(ng.NGC_BF16, 4, 0, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_softmax(ng.NGC_BF16, 1 << 31, 8, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_softmax(ng.NGC_BF16, 1 << 30, 1 << 12, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_softmax(7, 4, 8, fake, fake, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_softmax(ng.NGC_BF16, 4, 8, None, fake, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_softmax(ng.NGC_BF16, 4, 8, fake + 1, fake, None, check=False) == ng.NGC_BAD_ARG      # not element aligned
+    assert ng.ngc_softmax(ng.NGC_F32, 4, 8, fake, fake + 2, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_softmax_bwd(ng.NGC_F32, 4, 8, fake, None, fake, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 1000) == "softmax_rows_wave"
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 2048) == "softmax_rows_wave"            # 4 vectors of 8 per lane
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 2056) == "softmax_rows_wg"
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 32768, True) == "softmax_rows_wg"       # 16 vectors per thread, 256 threads
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 32776) == "softmax_rows_block"
+    assert ng.ngc_softmax_variant(ng.NGC_BF16, 1001) == "softmax_rows_block"           # rows off the 16-byte grid
+    assert ng.ngc_softmax_variant(ng.NGC_F32, 1024) == "softmax_rows_wave"
+    assert ng.ngc_softmax_variant(ng.NGC_F32, 16384) == "softmax_rows_wg"
+    assert ng.ngc_softmax_variant(ng.NGC_F32, 16388) == "softmax_rows_block"
+    assert ng.ngc_softmax_variant(9, 8) == "invalid"
+
+
 def test_unsupported_is_reported_not_routed_elsewhere():
     # blocked filters with a shape only the direct kernels cover
     d = _good(c=5, k=7, w_layout=ng.NGC_BLOCKED_FWD)
