@@ -207,6 +207,7 @@ struct WgradStripParams {
     int32_t ncq;               // 16-channel groups of c per workgroup (4, 2 or 1)
     int32_t nring;             // LDS stage buffers (2 or 3)
     int32_t G;                 // whole images per stage (small images; 1 = row blocks of one image)
+    int32_t late_mask;         // bit w: wave w issues the loads of a later stage after its MFMAs instead of before
     int32_t ctiles;            // C / (16 * ncq)
     uint32_t x_bytes, dy_bytes;
     FastDiv div_q, div_pc, div_pq, div_patch;

@@ -231,13 +231,18 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     const int total_stages = MULTI ? (nimg + G - 1) / G : nimg * p.nstages;
     const int lpw = (items - wave + NW - 1) / NW;
     const int ahead = p.nring - 1;
+    // Waves of the late group issue the loads of stage s + ahead after their MFMAs of stage s instead of
+    // before: a wave is held at issue while the memory system takes its loads, and with one wave of each
+    // SIMD in either group the other one's MFMAs run meanwhile.  Counting is unchanged (per wave, in order).
+    const bool late = (p.late_mask >> wave) & 1;
     for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s, s);
     int buf = 0;                                            // s % nring
     for (int s = 0; s < total_stages; ++s) {
         const int later = (total_stages - 1 - s < ahead - 1) ? total_stages - 1 - s : ahead - 1;
         wait_vmcnt(later * lpw);
         wg_barrier_nofence();                                 // stage s complete for everybody; buffer of s-1 is free
-        if (s + ahead < total_stages) issue_loads(s + ahead, (buf + ahead) % p.nring);
+        const int nbuf = (buf + ahead) % p.nring;
+        if (!late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
         int rows = rows_strip - (s % p.nstages) * p.SR;
         if (rows > p.SR) rows = p.SR;
         int gv = nimg - s * G;
@@ -293,6 +298,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             }
             step_body(std::false_type{});
         }
+        if (late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
     }
     __syncthreads();                                        // all stage buffers are free
 

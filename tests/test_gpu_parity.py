@@ -230,11 +230,15 @@ def test_wgrad_per_tap_kernel_still_matches(case, monkeypatch):
 
 
 @pytest.mark.parametrize("case", [12, 13, 14])
-@pytest.mark.parametrize("ncq,ring", [(1, 3), (2, 3), (4, 3), (2, 2)])
-def test_wgrad_all_taps_channel_group_variants(case, ncq, ring, monkeypatch):
-    """Channel-group splits and LDS ring depths (3 buffers are used when they fit, 2 otherwise / when forced)."""
+@pytest.mark.parametrize("ncq,ring,late", [(1, 3, None), (2, 3, None), (4, 3, None), (2, 2, None), (2, 3, "0"), (2, 2, "0xFF"),
+                                           (4, 3, "0x5A")])
+def test_wgrad_all_taps_channel_group_variants(case, ncq, ring, late, monkeypatch):
+    """Channel-group splits, LDS ring depths (3 buffers are used when they fit, 2 otherwise / when forced) and
+    which waves issue their loads after their MFMAs (default: waves 4-7)."""
     monkeypatch.setenv("NGC_WGRAD_NCQ", str(ncq))
     monkeypatch.setenv("NGC_WGRAD_RING", str(ring))
+    if late is not None:
+        monkeypatch.setenv("NGC_WGRAD_LATE", late)
     a = MFMA_CASES[case]
     x, w, b, dy = _tensors(a, "bf16", 4000 + case)
     run = Run(a, "bf16", BLK, BLK, True)
