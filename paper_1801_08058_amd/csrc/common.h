@@ -75,6 +75,30 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n; waiting for fewer outstanding loads than
+// necessary is always correct, so counts beyond the table fall back to vmcnt(0).
+__device__ __forceinline__ void wait_vmcnt(int n)
+{
+    switch (n) {
+    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
+    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
+    case 15: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    }
+}
+
 // ---- element index functions for the public layouts ----
 // ReLU backprop on packed bf16: keep the halves of v whose counterpart in m is > 0 (as a float
 // comparison: +0, -0, negatives and NaN block), zero the others.

@@ -58,30 +58,6 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigne
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// s_waitcnt vmcnt(n) for a wave-uniform run-time n; waiting for fewer outstanding loads than
-// necessary is always correct, so counts beyond the table fall back to vmcnt(0).
-__device__ __forceinline__ void wait_vmcnt(int n)
-{
-    switch (n) {
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    case 15: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    }
-}
-
 // NCQ = 16-channel groups of c per workgroup (4, 2 or 1); the 8 waves are NCQ channel groups x
 // NH = 8/NCQ interleaved step streams.  Fewer channels per workgroup means fewer, longer position
 // chunks for the same number of workgroups, i.e. fewer partial copies of dw to write and re-read.
