@@ -118,8 +118,10 @@ class LayerBench:
             self.sets.append(s)
         self.ws = {op: torch.empty(max(ng.ngc_conv_workspace_bytes(d, op), 16), dtype=torch.uint8, device="cuda")
                    for op, d in ((ng.NGC_OP_FWD, self.d_fwd), (ng.NGC_OP_BWD_DATA, self.d_bwd),
-                                 (ng.NGC_OP_BWD_FILTERS, self.d_wg), (ng.NGC_OP_BIAS_GRAD, self.d_wg))}
+                                 (ng.NGC_OP_BWD_FILTERS, self.d_wg), (ng.NGC_OP_BIAS_GRAD, self.d_wg),
+                                 (ng.NGC_OP_BWD_DATA_DB, self.d_bwd))}
         self.db = torch.empty(L.k, dtype=torch.float32, device="cuda")
+        self.db_prev = torch.empty(L.c, dtype=torch.float32, device="cuda")
         self.stream = cur
         self.ops = list(L.ops)
         if nchw_input and not propagate:
@@ -141,6 +143,9 @@ class LayerBench:
             ng.ngc_conv_bwd_filters(self.d_wg, s["x"], s["dy"], s["dw"], self.ws[ng.NGC_OP_BWD_FILTERS], st)
         elif op == "bwd_data_relu":       # backward compounds: timed on their own, not part of the step
             ng.ngc_conv_bwd_data_relu(self.d_bwd, s["dy"], self.w_bwd, s["x"], s["dx"], self.ws[ng.NGC_OP_BWD_DATA], st)
+        elif op == "bwd_data_relu_db":    # ... and the channel sums of dx (bias gradient of the producing layer)
+            ng.ngc_conv_bwd_data_relu_db(self.d_bwd, s["dy"], self.w_bwd, s["x"], s["dx"], self.db_prev,
+                                         self.ws[ng.NGC_OP_BWD_DATA_DB], st)
         elif op == "bias_grad":
             ng.ngc_bias_grad(self.d_wg, s["dy"], self.db, self.ws[ng.NGC_OP_BIAS_GRAD], st)
         else:
@@ -162,8 +167,8 @@ class LayerBench:
             return xb + yb + wb + 4 * L.k
         if op == "bwd_data":
             return xb + yb + wb
-        if op == "bwd_data_relu":
-            return 2 * xb + yb + wb
+        if op in ("bwd_data_relu", "bwd_data_relu_db"):
+            return 2 * xb + yb + wb + (4 * L.c if op.endswith("_db") else 0)
         if op == "bias_grad":
             return yb + 4 * L.k
         return xb + yb + 2 * wb          # bwd_filters: dw fp32
@@ -323,14 +328,14 @@ def main():
     # backward compounds (ReLU backprop fused into backprop-data; bias gradient): same buffers, timed alone
     extra = {}
     for b in (benches if args.backward_compounds else []):
-        for op in (["bwd_data_relu"] if "bwd_data" in b.ops else []) + ["bias_grad"]:
+        for op in (["bwd_data_relu", "bwd_data_relu_db"] if "bwd_data" in b.ops else []) + ["bias_grad"]:
             ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps)
-            flop = b.L.flop_per_op if op == "bwd_data_relu" else 0.0
+            flop = b.L.flop_per_op if op.startswith("bwd_data_relu") else 0.0
             extra[f"{b.L.name}:{op}"] = {
                 "us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
                 "gbs": round(b.algorithmic_bytes(op) / (ms * 1e-3) / 1e9, 1),
-                "variant": ng.ngc_conv_variant(b.d_bwd, 1) + "+relu_bwd" if op == "bwd_data_relu"
-                else ng.ngc_conv_variant(b.d_wg, ng.NGC_OP_BIAS_GRAD), "count": b.L.count}
+                "variant": ng.ngc_conv_variant(b.d_bwd, 1) + {"bwd_data_relu": "+relu_bwd", "bwd_data_relu_db": "+relu_bwd+db"}[op]
+                if op.startswith("bwd_data_relu") else ng.ngc_conv_variant(b.d_wg, ng.NGC_OP_BIAS_GRAD), "count": b.L.count}
     if args.calibrate_copy:
         # 64 x 256 x 56 x 56 bf16 = 102.8 MB read + 102.8 MB written per launch: larger than the
         # 8 x 4 MB of L2, so FETCH_SIZE sees (almost) every byte of the source

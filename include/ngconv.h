@@ -80,7 +80,7 @@ typedef enum { NGC_F32 = 0, NGC_BF16 = 1 } ngc_dtype;
 typedef enum { NGC_NCHW = 0, NGC_NCHW16C = 1 } ngc_data_layout;
 typedef enum { NGC_KCRS = 0, NGC_BLOCKED_FWD = 1, NGC_BLOCKED_BWD = 2 } ngc_filter_layout;
 enum { NGC_EPI_NONE = 0, NGC_EPI_BIAS = 1, NGC_EPI_RELU = 2 };   /* bit flags, forward only */
-enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2, NGC_OP_BIAS_GRAD = 3 };
+enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2, NGC_OP_BIAS_GRAD = 3, NGC_OP_BWD_DATA_DB = 4 };
 
 /* Constant attributes of one Convolution node and of its two derivative nodes. */
 typedef struct {
@@ -125,6 +125,17 @@ int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w,
  * (NGC_OP_BWD_DATA) and errors as ngc_conv_bwd_data; NGC_BAD_ARG if x_in is NULL or misaligned. */
 int ngc_conv_bwd_data_relu(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in,
                            void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ngc_conv_bwd_data_relu that also returns the bias gradient of the layer that produced x_in (three
+ * nodes of the derivative graph of a conv -> bias -> ReLU -> conv chain in one call, Sec. 3 and the
+ * Abstract's compounding): db[c] = sum over n, h, w of the dx written (the stored, rounded values),
+ * fp32, [C] device floats, overwritten.  Where the backprop-data kernel can (blocked dx on the strip
+ * and 1x1 GEMM kernels) its workgroups emit the partial sums themselves, otherwise a second pass
+ * reads dx; either way the result is a fixed-order reduction.  Workspace:
+ * ngc_conv_workspace_bytes(desc, NGC_OP_BWD_DATA_DB).  Errors as ngc_conv_bwd_data_relu; NGC_BAD_ARG
+ * also for a NULL or misaligned db. */
+int ngc_conv_bwd_data_relu_db(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in,
+                              void *dx, float *db, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Bias gradient of the compounded bias epilogue (Sec. 3: adjoint of broadcasting the bias):
  * db[k] = sum over n, p, q of dy[n,k,p,q], accumulated and written in fp32, db: [K] device floats,

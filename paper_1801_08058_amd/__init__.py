@@ -7,7 +7,7 @@ from .binding import *  # noqa: F401,F403
 from .binding import (  # noqa: F401
     ngc_conv_desc, make_desc, NgcError, LIB_PATH, EXPORTS,
     ngc_conv_out_shape, ngc_conv_workspace_bytes, ngc_conv_fwd, ngc_conv_bwd_data,
-    ngc_conv_bwd_data_relu, ngc_bias_grad, ngc_softmax, ngc_softmax_bwd, ngc_softmax_variant,
+    ngc_conv_bwd_data_relu, ngc_conv_bwd_data_relu_db, ngc_bias_grad, ngc_softmax, ngc_softmax_bwd, ngc_softmax_variant,
     ngc_conv_bwd_filters, ngc_layout_convert, ngc_filter_convert, ngc_data_elems,
     ngc_filter_elems, ngc_conv_variant, ngc_status_string,
 )

@@ -20,10 +20,10 @@ NGC_F32, NGC_BF16 = 0, 1
 NGC_NCHW, NGC_NCHW16C = 0, 1
 NGC_KCRS, NGC_BLOCKED_FWD, NGC_BLOCKED_BWD = 0, 1, 2
 NGC_EPI_NONE, NGC_EPI_BIAS, NGC_EPI_RELU = 0, 1, 2
-NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD = 0, 1, 2, 3
+NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD, NGC_OP_BWD_DATA_DB = 0, 1, 2, 3, 4
 
 EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
-           "ngc_conv_bwd_data_relu", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
+           "ngc_conv_bwd_data_relu", "ngc_conv_bwd_data_relu_db", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string")
 
 
@@ -69,6 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.ngc_conv_bwd_data.restype = ctypes.c_int
     lib.ngc_conv_bwd_data_relu.argtypes = [D, vp, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_data_relu.restype = ctypes.c_int
+    lib.ngc_conv_bwd_data_relu_db.argtypes = [D, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv_bwd_data_relu_db.restype = ctypes.c_int
     lib.ngc_bias_grad.argtypes = [D, vp, vp, vp, sz, vp]
     lib.ngc_bias_grad.restype = ctypes.c_int
     lib.ngc_softmax.argtypes = [i32, ctypes.c_int64, i32, vp, vp, vp]
@@ -172,6 +174,11 @@ def ngc_conv_bwd_data(desc, dy, w, dx, ws=None, stream=None, check: bool = True)
 def ngc_conv_bwd_data_relu(desc, dy, w, x_in, dx, ws=None, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_conv_bwd_data_relu(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_in), _ptr(dx), _ptr(ws),
                                               _nbytes(ws), _stream(stream)), "ngc_conv_bwd_data_relu", check)
+
+
+def ngc_conv_bwd_data_relu_db(desc, dy, w, x_in, dx, db, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_data_relu_db(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_in), _ptr(dx), _ptr(db),
+                                                 _ptr(ws), _nbytes(ws), _stream(stream)), "ngc_conv_bwd_data_relu_db", check)
 
 
 def ngc_bias_grad(desc, dy, db, ws=None, stream=None, check: bool = True) -> int:

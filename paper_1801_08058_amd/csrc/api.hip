@@ -418,6 +418,8 @@ bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size
     q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q;
     q.pbh = d->pad_below_h;
     q.TP = P < 8 ? P : 8;
+    const char *ftp = getenv("NGC_STEM_TP");                            // tests / benchmarks only: output rows per workgroup
+    if (ftp && atoi(ftp) >= 1 && atoi(ftp) <= 8 && atoi(ftp) <= P) q.TP = atoi(ftp);
     q.tiles_per_img = (P + q.TP - 1) / q.TP;
     q.div_q = make_fastdiv((uint32_t)Q);
     const size_t patch = (size_t)d->c * (2 * q.TP + 5) * (2 * d->w + 16);
@@ -647,8 +649,58 @@ void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *spl
     *splits = (int)((M + ch - 1) / ch);
 }
 
+// descriptor of "dx seen as a gradient tensor": its channel sums are what ngc_bias_grad computes for dy
+ngc_conv_desc dx_as_dy(const ngc_conv_desc *d)
+{
+    ngc_conv_desc t = *d;
+    t.k = d->c;
+    t.y_layout = d->x_layout;
+    return t;
+}
+
+bool db_fusable(const ngc_conv_desc *d, Variant v)
+{
+    if (getenv("NGC_DB_FUSE") && atoi(getenv("NGC_DB_FUSE")) == 0) return false;   // tests / benchmarks only
+    if (v == V_STRIP) return getenv("NGC_STRIP_1WAVE") == nullptr;
+    if (v == V_GEMM1X1) return d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
+    return false;
+}
+
+// rows of partial channel sums the fused launches write
+int db_fused_rows(const ngc_conv_desc *d, Variant v, int P, int Q)
+{
+    int rows = 0;
+    if (v == V_STRIP) {
+        const int ncls = strip_classes(d, NGC_OP_BWD_DATA);
+        for (int c = 0; c < ncls; ++c) {
+            StripParams sp;
+            int nf;
+            size_t lds;
+            bool empty;
+            if (!strip_plan_class(d, NGC_OP_BWD_DATA, c / d->stride_w, c % d->stride_w, P, Q, &sp, &nf, &lds, &empty)) return 0;
+            if (!empty) rows += sp.groups * sp.strips * 8;                // one row per wave
+        }
+    } else if (v == V_GEMM1X1) {
+        Gemm1x1Params gp;
+        if (!gemm1x1_plan(d, NGC_OP_BWD_DATA, P, Q, &gp, nullptr)) return 0;
+        gp.dbp = reinterpret_cast<float *>(1);
+        const int bm = gemm1x1_dbp_tile_m(gp);
+        rows = (int)((gp.M + bm - 1) / bm) * (bm / 64);                  // one row per MFMA wave row
+    }
+    return rows;
+}
+
 size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
+    if (op == NGC_OP_BWD_DATA_DB) {
+        // backprop-data part, then the partial channel sums of dx: rows of the fused launches, or the
+        // partials of a second pass over dx where the kernel does not produce them
+        const size_t base = workspace_bytes(d, NGC_OP_BWD_DATA, v, P, Q);
+        if (db_fusable(d, v))
+            return base + round256((size_t)db_fused_rows(d, v, P, Q) * ((d->c + 63) / 64 * 64) * sizeof(float));
+        const ngc_conv_desc t = dx_as_dy(d);
+        return base + round256((size_t)bias_grad_parts(t, d->h, d->w) * ((d->c + 15) / 16 * 16) * sizeof(float));
+    }
     if (op == NGC_OP_BIAS_GRAD) return round256((size_t)bias_grad_parts(*d, P, Q) * ((d->k + 15) / 16 * 16) * sizeof(float));
     if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
@@ -738,7 +790,7 @@ size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
 {
     int P, Q;
     if (validate(desc, &P, &Q) != NGC_OK) return 0;
-    return workspace_bytes(desc, op, pick(desc, op), P, Q);
+    return workspace_bytes(desc, op, pick(desc, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op), P, Q);
 }
 
 const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
@@ -862,9 +914,19 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
 
 namespace {
 
-// ConvolutionBackpropData; mask (may be null): same shape / layout / type as dx, dx = (mask > 0) ? dx : 0
-int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, const void *mask, void *dx, void *ws,
-                  size_t ws_bytes, void *hip_stream)
+// Channel sums of dx (the bias gradient of the layer that produced the data input) from the backprop-data
+// launches themselves: the strip and 1x1 GEMM kernels with blocked dx write one row of per-channel partial
+// sums per workgroup; `rows` counts them.
+struct DbFuse {
+    float *partial;            // [rows][ld] fp32
+    int ld;                    // C rounded up to 64
+    int rows;                  // rows written by the launches (out)
+};
+
+// ConvolutionBackpropData; mask (may be null): same shape / layout / type as dx, dx = (mask > 0) ? dx : 0;
+// fuse (may be null): also write the partial channel sums of dx
+int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, const void *mask, void *dx, void *ws,
+                  size_t ws_bytes, void *hip_stream, DbFuse *fuse)
 {
     int P, Q;
     const int vs = validate(desc, &P, &Q);
@@ -917,6 +979,12 @@ int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, cons
             sp.mask = static_cast<const uint16_t *>(mask);
             sp.bias = nullptr;
             sp.relu = 0;
+            if (fuse) {
+                sp.dbp = fuse->partial;
+                sp.dbp_row0 = fuse->rows / 8;                            // the kernel writes rows (row0 + workgroup) * 8 + wave
+                sp.dbp_ld = fuse->ld;
+                fuse->rows += sp.groups * sp.strips * 8;
+            }
             const int rc = launch_status(launch_strip(sp, nf, lds, st));
             if (rc != NGC_OK) return rc;
         }
@@ -935,6 +1003,13 @@ int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         gp.wt = static_cast<const uint16_t *>(wt);
         gp.out = static_cast<uint16_t *>(dx);
         gp.mask = static_cast<const uint16_t *>(mask);
+        if (fuse) {
+            gp.dbp = fuse->partial;
+            gp.dbp_row0 = 0;
+            gp.dbp_ld = fuse->ld;
+            const int bm = gemm1x1_dbp_tile_m(gp);
+            fuse->rows = (int)((gp.M + bm - 1) / bm) * (bm / 64);
+        }
         return launch_status(launch_gemm1x1(gp, st));
     }
     IgemmParams p;
@@ -978,6 +1053,36 @@ int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, cons
     return launch_status(launch_igemm(p, v == V_IGEMM_128 ? 128 : 64, max_m, st));
 }
 
+// db (may be null): [C] fp32 channel sums of the dx written; the workspace then holds the partial sums behind
+// the backprop-data part
+int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, const void *mask, void *dx, float *db, void *ws,
+                  size_t ws_bytes, void *hip_stream)
+{
+    if (!db) return bwd_data_core(desc, dy, w, mask, dx, ws, ws_bytes, hip_stream, nullptr);
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!aligned16(db) || !aligned16(ws)) return NGC_BAD_ARG;
+    if ((size_t)desc->n * desc->h * desc->w >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
+    const Variant v = pick(desc, NGC_OP_BWD_DATA);
+    if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
+    const size_t base = workspace_bytes(desc, NGC_OP_BWD_DATA, v, P, Q);
+    const size_t need = workspace_bytes(desc, NGC_OP_BWD_DATA_DB, v, P, Q);
+    if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (db_fusable(desc, v)) {
+        DbFuse f{partial, (desc->c + 63) / 64 * 64, 0};
+        const int rc = bwd_data_core(desc, dy, w, mask, dx, ws, base, hip_stream, &f);
+        if (rc != NGC_OK) return rc;
+        return launch_status(launch_bias_grad_reduce(partial, db, f.rows, desc->c, f.ld, st));
+    }
+    const int rc = bwd_data_core(desc, dy, w, mask, dx, ws, base, hip_stream, nullptr);
+    if (rc != NGC_OK) return rc;
+    const ngc_conv_desc t = dx_as_dy(desc);                 // second pass over dx
+    return launch_status(launch_bias_grad(t, desc->h, desc->w, dx, db, partial, bias_grad_parts(t, desc->h, desc->w), st));
+}
+
 }  // namespace
 
 extern "C" {
@@ -985,14 +1090,21 @@ extern "C" {
 int ngc_conv_bwd_data(const ngc_conv_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
                       void *hip_stream)
 {
-    return bwd_data_impl(desc, dy, w, nullptr, dx, ws, ws_bytes, hip_stream);
+    return bwd_data_impl(desc, dy, w, nullptr, dx, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int ngc_conv_bwd_data_relu_db(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in, void *dx, float *db,
+                              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!x_in || !db) return NGC_BAD_ARG;
+    return bwd_data_impl(desc, dy, w, x_in, dx, db, ws, ws_bytes, hip_stream);
 }
 
 int ngc_conv_bwd_data_relu(const ngc_conv_desc *desc, const void *dy, const void *w, const void *x_in, void *dx, void *ws,
                            size_t ws_bytes, void *hip_stream)
 {
     if (!x_in) return NGC_BAD_ARG;
-    return bwd_data_impl(desc, dy, w, x_in, dx, ws, ws_bytes, hip_stream);
+    return bwd_data_impl(desc, dy, w, x_in, dx, nullptr, ws, ws_bytes, hip_stream);
 }
 
 int ngc_bias_grad(const ngc_conv_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes, void *hip_stream)

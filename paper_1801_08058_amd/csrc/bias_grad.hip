@@ -75,27 +75,40 @@ __global__ __launch_bounds__(256) void bias_grad_generic(const T *__restrict__ d
     if (tid == 0) partial[(size_t)blockIdx.x * KP + k] = sm[0];
 }
 
-// db[k] = sum over parts; KP = channels per part row of `partial`.  One workgroup per 16 channels:
-// thread (lane = tid / 16, c = tid % 16) adds parts lane, lane + 16, ... in index order (independent
-// loads, so they pipeline), then a fixed LDS tree joins the 16 lanes.
+// db[k] = sum over parts; KP = channels per part row of `partial` (a multiple of 16, rows 64-byte aligned).
+// One workgroup per 16 channels: thread (lane = tid / 4, quad = tid % 4) adds the float4 of channels
+// 4 quad .. 4 quad + 3 of parts lane, lane + 64, ... in index order (independent 16-byte loads, so they
+// pipeline), then a fixed LDS tree joins the 64 lanes.
 __global__ __launch_bounds__(256) void bias_grad_reduce(const float *__restrict__ partial, float *__restrict__ db, int nparts,
                                                         int K, int KP)
 {
-    __shared__ float sm[256];
+    __shared__ float4 sm[256];
     const int tid = threadIdx.x;
-    const int k = blockIdx.x * 16 + (tid & 15);
-    float acc = 0.f;
-    if (k < K) {
+    const int c0 = blockIdx.x * 16 + (tid & 3) * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 8
-        for (int s = tid >> 4; s < nparts; s += 16) acc += partial[(size_t)s * KP + k];
+    for (int s = tid >> 2; s < nparts; s += 64) {
+        const float4 v = *reinterpret_cast<const float4 *>(partial + (size_t)s * KP + c0);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
     sm[tid] = acc;
     __syncthreads();
-    for (int stride = 128; stride >= 16; stride >>= 1) {
-        if (tid < stride) sm[tid] += sm[tid + stride];
+    for (int stride = 128; stride >= 4; stride >>= 1) {
+        if (tid < stride) {
+            const float4 o = sm[tid + stride];
+            float4 m = sm[tid];
+            m.x += o.x; m.y += o.y; m.z += o.z; m.w += o.w;
+            sm[tid] = m;
+        }
         __syncthreads();
     }
-    if (tid < 16 && k < K) db[k] = sm[tid];
+    if (tid < 4) {
+        const float4 r = sm[tid];
+        const float out[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (c0 + e < K) db[c0 + e] = out[e];
+    }
 }
 
 // position chunks: enough workgroups to fill the chip, at most 256 chunks of at least 128 positions
@@ -112,6 +125,13 @@ int bias_grad_parts(const ngc_conv_desc &d, int P, int Q)
     return (int)parts;
 }
 
+// db[k] = sum of nparts rows of `partial` (row pitch KP floats)
+hipError_t launch_bias_grad_reduce(const float *partial, float *db, int nparts, int K, int KP, hipStream_t st)
+{
+    NGC_LAUNCH(bias_grad_reduce, dim3((K + 15) / 16), dim3(256), 0, st, partial, db, nparts, K, KP);
+    return hipGetLastError();
+}
+
 hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy, float *db, float *partial, int nparts,
                             hipStream_t st)
 {
@@ -120,7 +140,7 @@ hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy
     const FastDiv div_pq = make_fastdiv((uint32_t)(P * Q)), div_q = make_fastdiv((uint32_t)Q);
     const bool blocked = d.dtype == NGC_BF16 && d.y_layout == NGC_NCHW16C;
     const int KB = (d.k + 15) / 16;
-    const int KP = blocked ? KB * 16 : d.k;
+    const int KP = KB * 16;                             // row pitch of the partials: K rounded up to 16
     if (blocked)
         NGC_LAUNCH(bias_grad_blocked_bf16, dim3(nparts, KB), dim3(256), 0, st, static_cast<const uint16_t *>(dy), partial, KB,
                    P * Q, M, chunk, div_pq);

@@ -99,6 +99,36 @@ __device__ __forceinline__ void wait_vmcnt(int n)
     }
 }
 
+// Each lane of a 32-lane half-wave holds v[0..31]; returns, in lane l (l = lane % 32), the sum over the 32
+// lanes of v[j(l)], j(l) = ((l % 16) << 1) | (l / 16).  A butterfly that halves the values a lane carries
+// at every step (16 + 8 + 4 + 2 + 1 exchanges instead of 32 x 5), in a fixed order.  The four large steps
+// are DPP lane permutations inside a row of 16 (mirror, half mirror, quad swaps: one VALU operation each;
+// LDS-based shuffles here cost a 1x1 layer more than a second pass over its output); the mirrored partners
+// come first because they also flip the lower lane bits, which no step has used by then.
+template <int CTRL>
+__device__ __forceinline__ float dpp_perm_f32(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float half_wave_transpose_sum32(float (&v)[32], int l32)
+{
+    constexpr int ROW_MIRROR = 0x140, ROW_HALF_MIRROR = 0x141, QUAD_XOR2 = 0x4E, QUAD_XOR1 = 0xB1;
+    bool up = (l32 & 8) != 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = (up ? v[i + 16] : v[i]) + dpp_perm_f32<ROW_MIRROR>(up ? v[i] : v[i + 16]);
+    up = (l32 & 4) != 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (up ? v[i + 8] : v[i]) + dpp_perm_f32<ROW_HALF_MIRROR>(up ? v[i] : v[i + 8]);
+    up = (l32 & 2) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (up ? v[i + 4] : v[i]) + dpp_perm_f32<QUAD_XOR2>(up ? v[i] : v[i + 4]);
+    up = (l32 & 1) != 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) v[i] = (up ? v[i + 2] : v[i]) + dpp_perm_f32<QUAD_XOR1>(up ? v[i] : v[i + 2]);
+    up = (l32 & 16) != 0;
+    return (up ? v[1] : v[0]) + __shfl_xor(up ? v[0] : v[1], 16, 64);
+}
+
 // ---- element index functions for the public layouts ----
 // ReLU backprop on packed bf16: keep the halves of v whose counterpart in m is > 0 (as a float
 // comparison: +0, -0, negatives and NaN block), zero the others.
@@ -171,6 +201,9 @@ struct StripParams {
     uint16_t *out;
     const float *bias;         // may be null
     const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
+    float *dbp;                // may be null; else [rows][dbp_ld] fp32: channel sums of what each workgroup stored
+                               // (row dbp_row0 + blockIdx.x): partials of a bias gradient of the stored tensor
+    int32_t dbp_row0, dbp_ld;  // first row of this launch, row pitch in floats
     int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
     int32_t TN, TP;            // images and output rows per workgroup
     int32_t groups, strips;    // ceil(N/TN), ceil(Hout/TP)
@@ -291,6 +324,8 @@ struct Gemm1x1Params {
     const float *bias;         // may be null
     const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t Cin, Hin, Win, Cout, Hout, Wout;
+    float *dbp;                        // may be null; else [rows][dbp_ld] fp32: channel sums of what each workgroup stored
+    int32_t dbp_row0, dbp_ld;          // row of m-tile t: dbp_row0 + t; row pitch in floats
     int32_t in_nchw, out_nchw;         // activations read from / result written to NCHW (stride 1, no padding, H*W % 8 == 0)
     int32_t is_h, is_w, dh, dw;        // input pixel of lattice position (i,j): (i*is_h + dh, j*is_w + dw)
     int32_t os_h, os_w, oa_h, oa_w;    // output pixel: (i*os_h + oa_h, j*os_w + oa_w)
@@ -329,12 +364,14 @@ hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x
                              const float *bias, void *y, hipStream_t st);
 hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w,
                                   const void *mask, void *dx, hipStream_t st);
+int gemm1x1_dbp_tile_m(const Gemm1x1Params &p);
 int softmax_vectors(int dtype, int cols, bool bwd, bool aligned);
 hipError_t launch_softmax(int dtype, bool bwd, const void *a, const void *b, void *out, uint32_t rows, int cols, int V,
                           hipStream_t st);
 hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy, float *db, float *partial, int nparts,
                             hipStream_t st);
 int bias_grad_parts(const ngc_conv_desc &d, int P, int Q);
+hipError_t launch_bias_grad_reduce(const float *partial, float *db, int nparts, int K, int KP, hipStream_t st);
 hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const void *x, const void *dy,
                                      float *dw, hipStream_t st);
 hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, const void *src, int src_layout,

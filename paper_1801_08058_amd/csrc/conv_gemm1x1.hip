@@ -49,8 +49,11 @@ constexpr unsigned G1_OOB = 0x80000000u;
 // NS = ring depth; KB = 16-channel blocks per stage (4 or 2): a stage holds 2 KB planes (8-channel halves) per operand.
 // NL = loader waves (1 or 2); WM x WN MFMA waves; FA = 32-channel output fragments per MFMA wave
 // (2: 64 x 64 wave tiles; 4: 64 positions x 128 channels, 6 instead of 8 LDS operand fetches per 8 MFMAs).
-// XN / YN: activations read from / result written to an NCHW tensor (else 16-channel blocked)
-template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN>
+// XN / YN: activations read from / result written to an NCHW tensor (else 16-channel blocked).
+// DB (blocked result only): every MFMA wave also writes the per-channel sums over its positions of the values
+// it stored (fp32, fixed order) to row (p.dbp_row0 + m-tile) * WM + wm of p.dbp: partials of a bias gradient
+// of the result.
+template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN, bool DB = false>
 __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 {
     constexpr int BM = 64 * WM, BN = 32 * FA * WN;
@@ -260,6 +263,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     }
     // ---- epilogue: bias, ReLU, one RNE rounding, lane-pair exchange, 16-byte stores
     const int CBout = p.Cout >> 4;
+    float csum[DB ? FA : 1][2][8];                        // DB: channel sums of this lane's stored values
+#pragma unroll
+    for (int a = 0; a < (DB ? FA : 1); ++a)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) csum[a][h][e] = 0.f;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const uint32_t m = m0 + (uint32_t)(wm * 64 + b * 32 + l32);
@@ -300,9 +310,30 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    if (DB) {                                            // the rounded, masked values as stored
+                        const uint32_t w4[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            csum[DB ? a : 0][h][2 * j] += __uint_as_float(w4[j] << 16);
+                            csum[DB ? a : 0][h][2 * j + 1] += __uint_as_float(w4[j] & 0xFFFF0000u);
+                        }
+                    }
                 }
             }
         }
+    }
+    if (DB) {
+        // lanes of a 32-lane half hold different positions of the same 8 channels: transpose-sum over the
+        // half (no LDS, no barrier: a wave that is done leaves), one row of 64 channel sums per MFMA wave row
+        // wm; value index j = a*16 + h*8 + e is channel n0 + wn*64 + a*32 + 16 h + 8 lg + e
+        static_assert(!DB || FA == 2, "channel sums: 64-channel wave tiles");
+        float flat[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) flat[j] = csum[DB ? (j >> 4) : 0][(j >> 3) & 1][j & 7];
+        const float mine = half_wave_transpose_sum32(flat, l32);
+        const int j = ((l32 & 15) << 1) | (l32 >> 4);
+        const int ch = n0 + wn * 64 + (j >> 4) * 32 + ((j >> 3) & 1) * 16 + 8 * lg + (j & 7);
+        if (ch < p.Cout) p.dbp[((size_t)(p.dbp_row0 + mtile) * WM + wm) * p.dbp_ld + ch] = mine;
     }
 }
 
@@ -323,12 +354,12 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN>
+template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN, bool DB = false>
 static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN, DB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -342,7 +373,7 @@ static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
     if (YN && lds < staging) lds = staging;
     const unsigned mtiles = (p.M + BM - 1) / BM;
     const unsigned grid = ((mtiles + 7) / 8) * 8 * ((p.Cout + BN - 1) / BN);
-    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
+    NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN, DB>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
     return hipGetLastError();
 }
 
@@ -354,11 +385,15 @@ static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
         ((WM == 4 && WN == 2 && NS == 3 && NL == 2) || (WM == 2 && WN == 2 && NS == 3 && NL == 1) ||
          (WM == 8 && WN == 1 && NS == 2 && NL == 2) || (WM == 4 && WN == 1 && NS == 3 && NL == 1));
     if constexpr (dispatcher_tile) {
+        if (p.dbp) {
+            if (p.in_nchw || p.out_nchw) return hipErrorInvalidValue;
+            return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, false, false, true>(p, st);
+        }
         if (p.in_nchw && p.out_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, true, true>(p, st);
         if (p.in_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, true, false>(p, st);
         if (p.out_nchw) return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, false, true>(p, st);
     }
-    if (p.in_nchw || p.out_nchw) return hipErrorInvalidValue;
+    if (p.in_nchw || p.out_nchw || p.dbp) return hipErrorInvalidValue;
     return launch_gemm1x1_l<WM, WN, NS, KB, NL, FA, false, false>(p, st);
 }
 
@@ -368,16 +403,40 @@ static hipError_t launch_gemm1x1_t(const Gemm1x1Params &p, hipStream_t st)
 // waves + 1 loader, three workgroups per compute unit).  NGC_G1_VARIANT (experiments only) forces
 // 64-channel stages (1), a ring of 4 (2), the 128x128 tile with a ring of 3 (3) / 4 (4), or the
 // 256x128 tile whatever the size (5), or the 256x256 tile with 64x128 wave tiles (6; needs Cout % 256 == 0).
+// 128-channel tiles when they waste no more of a partial last tile than 64-channel tiles would (Cout % 16 == 0)
+static bool wide_tiles(const Gemm1x1Params &p)
+{
+    const int c128 = (p.Cout + 127) / 128, c64 = (p.Cout + 63) / 64;
+    return p.Cout > 64 && c128 * 128 <= c64 * 64;
+}
+
+// tile choice of the NCHW / channel-sum modes (they exist for the dispatcher's own tiles): 0 = large, 3 = small
+static int special_mode_variant(const Gemm1x1Params &p)
+{
+    const char *ev = getenv("NGC_G1_VARIANT");
+    int variant = ev && atoi(ev) == 3 ? 3 : 0;
+    const int c128 = (p.Cout + 127) / 128;
+    if (variant == 0 && wide_tiles(p) && ((p.M + 255) / 256) * (unsigned)c128 < 2 * 256) variant = 3;
+    return variant;
+}
+
+// positions per row of p.dbp (64: one row per MFMA wave row of a tile) of the launch launch_gemm1x1 makes when
+// p.dbp is set, and positions per tile: rows written = ceil(M / tile) * (tile / 64)
+int gemm1x1_dbp_tile_m(const Gemm1x1Params &p)
+{
+    const int variant = special_mode_variant(p);
+    if (wide_tiles(p)) return variant == 3 ? 128 : 256;
+    return variant == 3 ? 256 : 512;
+}
+
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
     int variant = ev ? atoi(ev) : 0;
-    // 128-channel tiles when they waste no more of a partial last tile than 64-channel tiles would (Cout % 16 == 0)
-    const int c128 = (p.Cout + 127) / 128, c64 = (p.Cout + 63) / 64;
-    const bool wide = p.Cout > 64 && c128 * 128 <= c64 * 64;
-    if (p.in_nchw || p.out_nchw) {
-        if (variant != 3) variant = 0;
-        if (variant == 0 && wide && ((p.M + 255) / 256) * (unsigned)c128 < 2 * 256) variant = 3;
+    const int c128 = (p.Cout + 127) / 128;
+    const bool wide = wide_tiles(p);
+    if (p.in_nchw || p.out_nchw || p.dbp) {
+        variant = special_mode_variant(p);
         if (wide) return variant == 3 ? launch_gemm1x1_t<2, 2, 3, 2, 1>(p, st) : launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
         return variant == 3 ? launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st) : launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
     }

@@ -45,7 +45,10 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // SUB = 1 only the lower 32 of the tile's 64 output columns are in use: one filter plane per tap (32
 // rows of g = 0, then 32 rows of g = 1) and no upper MFMA.  The store modes are separate
 // instantiations so that the blocked-output kernel carries none of the sub-pixel code.
-template <int NF, int NW, int SUB = 0>
+// DB (blocked output only): every wave also writes the sums over its positions of the values it
+// stored, per output channel (fp32, fixed order), to row (p.dbp_row0 + blockIdx.x) * NW + wave of
+// p.dbp - the partials of a bias gradient of the stored tensor.  A separate instantiation.
+template <int NF, int NW, int SUB = 0, bool DB = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
     constexpr bool HALF = SUB == 1;
@@ -195,6 +198,13 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                 bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
             }
         }
+    float csum[DB ? 2 : 1][2][8];                         // DB: channel sums of this lane's stored values
+#pragma unroll
+    for (int a = 0; a < (DB ? 2 : 1); ++a)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) csum[a][h][e] = 0.f;
     if (SUB != 0 && p.sub_stage) {
         // Sub-pixel NCHW store through LDS: column col = (a*BW+b)*C + c of position (tp, q) of image ti is
         // pixel (BH tp + a, BW q + b) of channel c; the strip's pixels are assembled as [ti][c][row][WP]
@@ -314,26 +324,56 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    if (DB) {                                            // the rounded, masked values as stored
+                        const uint32_t w4[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            csum[DB ? a : 0][h][2 * j] += __uint_as_float(w4[j] << 16);
+                            csum[DB ? a : 0][h][2 * j + 1] += __uint_as_float(w4[j] & 0xFFFF0000u);
+                        }
+                    }
                 }
             }
         }
     }
+    if (DB) {
+        // lanes of a 32-lane half hold different positions of the same 8 channels: transpose-sum over the
+        // half (no LDS, no barrier: a wave that is done leaves), one row of 64 channel sums per wave;
+        // value index j = a*16 + h*8 + e is channel k0 + a*32 + 16 h + 8 lg + e
+        float flat[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) flat[j] = csum[DB ? (j >> 4) : 0][(j >> 3) & 1][j & 7];
+        const float mine = half_wave_transpose_sum32(flat, l32);
+        const int j = ((l32 & 15) << 1) | (l32 >> 4);
+        const int ch = k0 + (j >> 4) * 32 + ((j >> 3) & 1) * 16 + 8 * lg + (j & 7);
+        if (ch < p.Cout) p.dbp[((size_t)(p.dbp_row0 + blockIdx.x) * NW + wave) * p.dbp_ld + ch] = mine;
+    }
 }
 
 
-template <int NF, int NW, int SUB = 0>
-static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
+template <int NF, int NW, int SUB, bool DB>
+static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static bool attr_set = false;                   // raise the dynamic LDS limit once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
-    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB>), grid, dim3(NW * 64), lds_bytes, st, p);
+    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
+}
+
+template <int NF, int NW, int SUB = 0>
+static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
+{
+    if constexpr (SUB == 0 && NW == 8) {
+        if (p.dbp) return launch_strip_d<NF, NW, SUB, true>(p, lds_bytes, st);
+    }
+    if (p.dbp) return hipErrorInvalidValue;          // channel sums exist for the blocked-output 8-wave kernels only
+    return launch_strip_d<NF, NW, SUB, false>(p, lds_bytes, st);
 }
 
 // nf = 32-position fragments per SIMD (7, 4 or 2); the fragments of a SIMD are spread over

@@ -160,6 +160,21 @@ class Run:
         self.last_desc, self.last_raw = d, dx
         return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
 
+    def bwd_data_relu_db(self, dy, w, x_in):
+        """The compound above that also returns the channel sums of the dx it wrote (fp32 [C])."""
+        a = self.a
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_BWD)
+        d = desc_of(a, self.dtype, self.xl, self.yl, wl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        xin = data_to_device(x_in, self.dtype, self.xl)
+        dx = out_tensor(d, 0, self.dtype)
+        db = torch.full((a.c,), float("nan"), dtype=torch.float32, device="cuda")
+        ws = workspace(d, ng.NGC_OP_BWD_DATA_DB)
+        ng.ngc_conv_bwd_data_relu_db(d, dyd, wd, xin, dx, db, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, dx
+        return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w)), db.cpu().numpy().astype(np.float64)
+
     def bias_grad(self, dy):
         a = self.a
         d = desc_of(a, self.dtype, self.xl, self.yl)

@@ -100,6 +100,12 @@ def test_backward_compounds_validate_before_launch():
     bad = _good(stride=(0, 1))
     assert ng.ngc_conv_bwd_data_relu(bad, fake, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_SHAPE
     assert ng.ngc_bias_grad(bad, fake, fake, fake, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_conv_bwd_data_relu_db(d, fake, fake, fake, fake, None, None, None, check=False) == ng.NGC_BAD_ARG   # no db
+    assert ng.ngc_conv_bwd_data_relu_db(d, fake, fake, None, fake, fake, None, None, check=False) == ng.NGC_BAD_ARG   # no x_in
+    assert ng.ngc_conv_bwd_data_relu_db(bad, fake, fake, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_conv_bwd_data_relu_db(d, fake, fake, fake, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    # partial channel sums sit behind the backprop-data part of the workspace
+    assert ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_DATA_DB) >= ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_DATA) + 64 * 4
     assert ng.ngc_bias_grad(d, None, fake, None, None, check=False) == ng.NGC_BAD_ARG
     assert ng.ngc_bias_grad(d, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
     # one fp32 partial per (position chunk, channel), channels padded to 16

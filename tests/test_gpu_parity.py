@@ -38,6 +38,12 @@ def _check_backward_compounds(run, a, x_in, w, dy, ref_dx, tol):
     assert e <= tol, f"bwd_data_relu err {e}"
     blocked = ~(x_in > 0)
     assert np.all(dxr[blocked] == 0) and not np.signbit(dxr[blocked]).any(), "gradient leaked through x_in <= 0"
+    # the same compound returning the bias gradient of the producing layer as well: dx identical, db = channel
+    # sums of the dx the device stored (its own rounded output is what the next op reads)
+    dx2, dbp = run.bwd_data_relu_db(dy, w, x_in)
+    assert np.array_equal(dx2, dxr), "fused channel sums changed dx"
+    e = oracle.max_normalised_error(dbp, oracle.bias_grad(dxr))
+    assert e <= 1e-5, f"bwd_data_relu_db err {e}"
     db = run.bias_grad(dy)
     assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BIAS_GRAD).startswith("bias_grad")
     e = oracle.max_normalised_error(db, oracle.bias_grad(dy))
@@ -338,6 +344,22 @@ def test_channel_tails_with_nchw_tensors(xl, yl):
                ("gemm1x1", "gemm1x1", "wgrad_gemm"))
 
 
+@pytest.mark.parametrize("case,cases", [(0, "mfma"), (3, "mfma"), (2, "mfma"), (4, "mfma"), (0, "tail"), (6, "tail")])
+def test_channel_sums_second_pass_matches_fused(case, cases, monkeypatch):
+    """NGC_DB_FUSE=0: the channel sums come from a second pass over dx instead of the backprop-data workgroups."""
+    a = (MFMA_CASES if cases == "mfma" else CHANNEL_TAIL_CASES)[case]
+    x, w, b, dy = _tensors(a, "bf16", 7700 + case)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dx1, db1 = run.bwd_data_relu_db(dy, w, x)
+    ws_fused = ng.ngc_conv_workspace_bytes(run.last_desc, ng.NGC_OP_BWD_DATA_DB)
+    monkeypatch.setenv("NGC_DB_FUSE", "0")
+    dx0, db0 = run.bwd_data_relu_db(dy, w, x)
+    assert np.array_equal(dx0, dx1)
+    assert oracle.max_normalised_error(db1, db0) <= 1e-6                 # same values, different summation order
+    assert oracle.max_normalised_error(db0, oracle.bias_grad(dx0)) <= 1e-5
+    assert ws_fused > 0 and ng.ngc_conv_workspace_bytes(run.last_desc, ng.NGC_OP_BWD_DATA_DB) > 0
+
+
 NCHW_1X1_CASES = [
     # n  c    h   w   k    r  s  sh sw dh dw pads      stride 1, no padding, H*W % 8 == 0
     Attrs(2, 128, 8, 12, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0),      # 192 positions: one ragged tile
@@ -444,6 +466,8 @@ def _sampled_layer_check(L, n_y=100_000, n_dw=2048, convert_x_on_device=False):
         assert oracle.max_normalised_error(dxr.reshape(-1)[idx], oracle.relu_bwd_mask(ref, xs)) <= 2e-2, "bwd_data_relu"
         keep = t["x"] > 0
         assert np.array_equal(dxr[keep], dx[keep]) and not dxr[~keep].any(), "mask applied to the same gradient"
+        dx2, dbp = run.bwd_data_relu_db(t["dy"], t["w"], t["x"])
+        assert np.array_equal(dx2, dxr) and oracle.max_normalised_error(dbp, oracle.bias_grad(dxr)) <= 1e-5, "bwd_data_relu_db"
         db = run.bias_grad(t["dy"])
         assert oracle.max_normalised_error(db, oracle.bias_grad(dy64)) <= 1e-5, "bias_grad"
     if "bwd_filters" in L.ops:
