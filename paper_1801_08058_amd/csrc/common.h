@@ -129,6 +129,18 @@ __device__ __forceinline__ float half_wave_transpose_sum32(float (&v)[32], int l
     return (up ? v[1] : v[0]) + __shfl_xor(up ? v[0] : v[1], 16, 64);
 }
 
+// Lanes l and l + 32 of a 32x32 MFMA accumulator hold, for one position, the two 4-channel halves of two
+// 8-channel groups: (q0, q1) of group 0 and (q2, q3) of group 1, each 2 packed bf16.  After the exchange
+// lane l has all 8 channels of group 0 and lane l + 32 those of group 1 (16 bytes to store).
+// v_permlane32_swap (gfx950) swaps the upper 32 lanes of one register with the lower 32 of another: two
+// VALU operations instead of two LDS-based shuffles and four selects.
+__device__ __forceinline__ uint4 lane_pair_exchange(uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3)
+{
+    const auto a = __builtin_amdgcn_permlane32_swap(q0, q2, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(q1, q3, false, false);
+    return make_uint4(a[0], b[0], a[1], b[1]);
+}
+
 // ---- element index functions for the public layouts ----
 // ReLU backprop on packed bf16: keep the halves of v whose counterpart in m is > 0 (as a float
 // comparison: +0, -0, negatives and NaN block), zero the others.

@@ -225,10 +225,7 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
                 const uint32_t p2 = pack_bf16x2_hw(v[4], v[5]), p3 = pack_bf16x2_hw(v[6], v[7]);
                 // lg=0 owns channels {0-3, 8-11}, lg=1 owns {4-7, 12-15}; swap so that
                 // lg=0 ends with 0-7 and lg=1 with 8-15
-                const uint32_t s0 = lg ? p0 : p2, s1 = lg ? p1 : p3;
-                const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
-                const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
-                uint4 o = lg ? make_uint4(r0, r1, p2, p3) : make_uint4(p0, p1, r0, r1);
+                uint4 o = lane_pair_exchange(p0, p1, p2, p3);
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));

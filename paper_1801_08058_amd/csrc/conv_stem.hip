@@ -151,10 +151,7 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
                 }
                 const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
                 const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
-                const uint32_t s0 = lg ? q0 : q2, s1 = lg ? q1 : q3;
-                const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
-                const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
-                const uint4 o = lg ? make_uint4(r0, r1, q2, q3) : make_uint4(q0, q1, r0, r1);
+                const uint4 o = lane_pair_exchange(q0, q1, q2, q3);
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * PQ;
                     *reinterpret_cast<uint4 *>(p.y + blk * 16 + lg * 8) = o;
