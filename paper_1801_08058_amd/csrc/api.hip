@@ -173,7 +173,10 @@ bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int
             tdh[ntaps] = dh; tdw[ntaps] = dw; tslab[ntaps] = r * d->s + s2;
             ++ntaps;
         }
-    if (ntaps == 0) return false;                                        // class without taps: zero pixels, not handled here
+    if (ntaps == 0) {                                                    // backprop-data class no tap reaches: its pixels are
+        if (empty) *empty = true;                                        // zero (strip_zero_fill), nothing to launch
+        return true;
+    }
     int min_dh = tdh[0], max_dh = tdh[0], min_dw = tdw[0], max_dw = tdw[0];
     for (int t = 1; t < ntaps; ++t) {
         if (tdh[t] < min_dh) min_dh = tdh[t];
@@ -211,6 +214,24 @@ bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int
 
 // number of residue classes of backprop-data launches (1 for forward)
 int strip_classes(const ngc_conv_desc *d, int op) { return op == NGC_OP_FWD ? 1 : d->stride_h * d->stride_w; }
+
+// backprop-data: true if some residue class of the stride is reached by no tap (stride larger than the
+// dilated window covers); dx is then cleared before the launches of the other classes
+bool strip_zero_fill(const ngc_conv_desc *d)
+{
+    const int sh = d->stride_h, sw = d->stride_w;
+    for (int ca = 0; ca < sh; ++ca)
+        for (int cb = 0; cb < sw; ++cb) {
+            bool any = false;
+            for (int r = 0; r < d->r && !any; ++r)
+                for (int s2 = 0; s2 < d->s && !any; ++s2) {
+                    const int vh = ca + d->pad_below_h - r * d->dil_h, vw = cb + d->pad_below_w - s2 * d->dil_w;
+                    any = ((vh % sh) + sh) % sh == 0 && ((vw % sw) + sw) % sw == 0;
+                }
+            if (!any) return true;
+        }
+    return false;
+}
 
 // true if every launch of the op can go through the strip kernel
 bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q)
@@ -964,6 +985,10 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         wt = ws;
     }
     if (v == V_STRIP) {
+        if (strip_zero_fill(desc)) {
+            const hipError_t e = launch_zero_fill(dx, (size_t)desc->n * desc->c * desc->h * desc->w * 2, st);
+            if (e != hipSuccess) return launch_status(e);
+        }
         const int ncls = strip_classes(desc, NGC_OP_BWD_DATA);
         for (int c = 0; c < ncls; ++c) {                                 // one launch per residue class of the stride
             StripParams sp;
@@ -1067,8 +1092,8 @@ int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, cons
     const Variant v = pick(desc, NGC_OP_BWD_DATA);
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
     const size_t base = workspace_bytes(desc, NGC_OP_BWD_DATA, v, P, Q);
-    const size_t need = workspace_bytes(desc, NGC_OP_BWD_DATA_DB, v, P, Q);
-    if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    const size_t need = workspace_bytes(desc, NGC_OP_BWD_DATA_DB, v, P, Q);     // 0 if no class of a strided layer launches
+    if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
     float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (db_fusable(desc, v)) {

@@ -155,9 +155,11 @@ def test_kernel_selection_and_sizes():
     assert ng.ngc_conv_variant(s2, ng.NGC_OP_FWD) == "strip_bf16"            # strided strips
     s2b = _good(n=64, h=56, w=56, stride=(2, 2), w_layout=ng.NGC_BLOCKED_BWD)
     assert ng.ngc_conv_variant(s2b, ng.NGC_OP_BWD_DATA) == "strip_bf16"      # one launch per residue class
-    # stride 2 with dilation 2: the odd rows of dx have no tap -> the gather kernel (it writes their zeros)
+    # stride 2 with dilation 2: no tap reaches the odd rows of dx -> cleared, the other classes run as strips
     s2d = _good(n=2, h=15, w=9, stride=(2, 1), dilation=(2, 1), pad_below=(2, 0), w_layout=ng.NGC_BLOCKED_BWD)
-    assert ng.ngc_conv_variant(s2d, ng.NGC_OP_BWD_DATA).startswith("igemm")
+    assert ng.ngc_conv_variant(s2d, ng.NGC_OP_BWD_DATA) == "strip_bf16"
+    big = _good(n=2, h=40, w=40, r=7, s=7, pad_below=(3, 3), pad_above=(3, 3), w_layout=ng.NGC_BLOCKED_BWD)   # 49 taps
+    assert ng.ngc_conv_variant(big, ng.NGC_OP_BWD_DATA).startswith("igemm")
     one = _good(n=64, h=56, w=56, r=1, s=1, pad_below=(0, 0), pad_above=(0, 0), w_layout=ng.NGC_BLOCKED_FWD)
     assert ng.ngc_conv_variant(one, ng.NGC_OP_FWD) == "gemm1x1_bf16"
     assert ng.ngc_conv_variant(one, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"

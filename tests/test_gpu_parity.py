@@ -208,9 +208,9 @@ def test_mfma_kernels_small(case, pre, nf, strip_nf):
         pytest.skip("strip kernel covers stride-1 multi-tap shapes; one filter-layout mode is enough for forced sizes")
     strip_nf(nf)
     # multi-tap layers go through the strip kernel: forward with any stride, backprop-data one launch per
-    # residue class of the stride unless a class has no tap at all (case 5: odd rows of dx stay zero)
+    # residue class of the stride (case 5: no tap reaches the odd rows of dx, which are cleared first)
     strip_ok = a.r * a.s > 1 and nf != 0
-    bwd_strip_ok = strip_ok and case != 5
+    bwd_strip_ok = strip_ok
     one_tap = a.r * a.s == 1 and a.c % 16 == 0 and a.k % 16 == 0
     fwd_v = "strip" if (strip_ok and a.c % 16 == 0 and a.k % 16 == 0) else "gemm1x1" if one_tap else \
         "igemm" if (a.c % 32 == 0 and a.k % 64 == 0) else "direct"
@@ -575,3 +575,53 @@ def test_general_attribute_layers_full_batch(idx):
 def test_general_attribute_layers_whole_tensors(idx):
     L = synth_inputs.config_layers(6, batch=2)[idx]
     _check_all(attrs_of(L), "bf16", BLK, BLK, True, 9000 + idx, ("strip", "strip", "wgrad"))
+
+
+# ------------------------------------------------------------------ randomized descriptors (seeded)
+def _random_attrs(rng, channel_step):
+    while True:
+        r, s = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        h, w = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        pbh, pah = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        pbw, paw = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        a = Attrs(int(rng.integers(1, 5)), channel_step * int(rng.integers(1, 11)), h, w,
+                  channel_step * int(rng.integers(1, 11)), r, s, sh, sw, dh, dw, pbh, pbw, pah, paw)
+        P, Q = oracle.out_shape(a)
+        if P >= 1 and Q >= 1:
+            return a
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_random_descriptors_blocked_bf16(seed):
+    """Whatever kernel the dispatcher picks for a random node (window, strides, dilation, one-sided padding,
+    channel counts that are multiples of 16): all ops and backward compounds against the oracle."""
+    rng = np.random.default_rng(424200 + seed)
+    a = _random_attrs(rng, 16)
+    _check_all(a, "bf16", BLK, BLK, bool(seed & 1), 9100 + seed)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_descriptors_other_types_and_layouts(seed):
+    """fp32 / NCHW / odd channel counts: the direct kernels (and the NCHW 1x1 paths where they apply)."""
+    rng = np.random.default_rng(434300 + seed)
+    a = _random_attrs(rng, 1 if seed % 2 else 16)
+    dtype = "f32" if seed % 4 == 0 else "bf16"
+    xl, yl = [(NCHW, NCHW), (NCHW, BLK), (BLK, NCHW), (BLK, BLK)][(seed // 2) % 4]
+    _check_all(a, dtype, xl, yl, False, 9200 + seed)
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_descriptors_larger_images(seed):
+    """Images of up to 64 x 64 pixels, batch up to 8: several tiles, strips, stages and position chunks per launch."""
+    rng = np.random.default_rng(444400 + seed)
+    while True:
+        r, s = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        a = Attrs(int(rng.integers(1, 9)), 16 * int(rng.integers(1, 5)), int(rng.integers(8, 65)), int(rng.integers(8, 65)),
+                  16 * int(rng.integers(1, 5)), r, s, int(rng.integers(1, 3)), int(rng.integers(1, 3)),
+                  int(rng.integers(1, 3)), int(rng.integers(1, 3)), *(int(v) for v in rng.integers(0, 3, 4)))
+        P, Q = oracle.out_shape(a)
+        if P >= 1 and Q >= 1:
+            break
+    _check_all(a, "bf16", BLK, BLK, bool(seed & 1), 9300 + seed)
