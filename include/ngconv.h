@@ -1,5 +1,5 @@
 /*
- * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family.
+ * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family (and Softmax, at the end).
  *
  * The library plays the part of the kernels a backend "transformer" selects
  * for an IR graph (paper Sec. 4, "Transformers": tensor-element layout and
