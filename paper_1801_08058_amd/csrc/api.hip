@@ -821,7 +821,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
         if (validate(desc, &P, &Q) != NGC_OK) return "invalid";
         return (desc->dtype == NGC_BF16 && desc->y_layout == NGC_NCHW16C) ? "bias_grad_blocked_bf16" : "bias_grad_generic";
     }
-    switch (pick(desc, op)) {
+    switch (pick(desc, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op)) {
     case V_UNSUPPORTED: return "unsupported";
     case V_DIRECT: return "direct";
     case V_IGEMM_128: return "igemm_bf16_128x128";

@@ -104,6 +104,7 @@ def test_backward_compounds_validate_before_launch():
     assert ng.ngc_conv_bwd_data_relu_db(d, fake, fake, None, fake, fake, None, None, check=False) == ng.NGC_BAD_ARG   # no x_in
     assert ng.ngc_conv_bwd_data_relu_db(bad, fake, fake, fake, fake, fake, None, None, check=False) == ng.NGC_BAD_SHAPE
     assert ng.ngc_conv_bwd_data_relu_db(d, fake, fake, fake, fake, fake, None, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv_variant(d, ng.NGC_OP_BWD_DATA_DB) == ng.ngc_conv_variant(d, ng.NGC_OP_BWD_DATA)
     # partial channel sums sit behind the backprop-data part of the workspace
     assert ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_DATA_DB) >= ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_DATA) + 64 * 4
     assert ng.ngc_bias_grad(d, None, fake, None, None, check=False) == ng.NGC_BAD_ARG
