@@ -172,6 +172,23 @@ __host__ __device__ inline size_t filter_index(int layout, int K, int C, int R, 
     return ((((size_t)(r * S + s)) * KB + (k >> 4)) * C + c) * 16 + (k & 15);
 }
 
+// Raises a kernel's dynamic-LDS limit to the 160 KB of a gfx950 compute unit, once per device (the
+// attribute belongs to the device the kernel's module is loaded on; the library runs on whatever device is
+// current).  One object per kernel (template instantiation).
+struct LdsLimitOnce {
+    bool done[16] = {};
+    hipError_t raise(const void *kernel)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 16 && done[dev]) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess && dev >= 0 && dev < 16) done[dev] = true;
+        return e;
+    }
+};
+
 // ---- implicit-GEMM (MFMA) forward / backprop-data: generalised gather convolution ----
 // out[n, co, i*os_h+oa_h, j*os_w+oa_w] = sum_{tap t in class} sum_ci
 //        in[n, ci, i*is_h + t.dh, j*is_w + t.dw] * wt[t.slab][ci/16][co][ci%16]

@@ -354,12 +354,10 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
 template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN, bool DB = false>
 static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN, DB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimitOnce lds_limit;                  // per template instantiation
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN, DB>));
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     constexpr int BM = 64 * WM, BN = 32 * FA * WN;
     constexpr size_t stage = (size_t)2 * KB * ((BM * 16 + 128) + (BN * 16 + 128));

@@ -351,12 +351,10 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 template <int NF, int NW, int SUB, bool DB>
 static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
-    static bool attr_set = false;                   // raise the dynamic LDS limit once per process
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimitOnce lds_limit;                  // per template instantiation
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB>));
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
     NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB>), grid, dim3(NW * 64), lds_bytes, st, p);

@@ -278,12 +278,10 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
 template <int WK, int WC, int SP, bool XN, bool DN>
 static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimitOnce lds_limit;                  // per template instantiation
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN>));
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree

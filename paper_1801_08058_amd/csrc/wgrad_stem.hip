@@ -271,12 +271,10 @@ __global__ __launch_bounds__(256) void wgrad_stem_reduce(const f32x4 *__restrict
 
 hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_stem_bf16),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimitOnce lds_limit;                  // per template instantiation
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_stem_bf16));
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.N * p.strips, p.K / 64);
     NGC_LAUNCH(wgrad_stem_bf16, grid, dim3(512), lds_bytes, st, p);

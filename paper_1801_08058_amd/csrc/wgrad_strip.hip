@@ -351,12 +351,10 @@ __global__ __launch_bounds__(256) void wgrad_strip_reduce(const f32x4 *__restric
 template <int NCQ, bool MULTI>
 static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ, MULTI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimitOnce lds_limit;                  // per template instantiation
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ, MULTI>));
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
     NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI>), grid, dim3(512), lds_bytes, st, p);
