@@ -409,10 +409,12 @@ static bool wide_tiles(const Gemm1x1Params &p)
 static int special_mode_variant(const Gemm1x1Params &p)
 {
     const char *ev = getenv("NGC_G1_VARIANT");
-    int variant = ev && atoi(ev) == 3 ? 3 : 0;
+    if (ev && atoi(ev) == 3) return 3;
+    if (ev && atoi(ev) == 5) return 0;
+    if (!wide_tiles(p)) return 3;                      // same rules as the plain launches
     const int c128 = (p.Cout + 127) / 128;
-    if (variant == 0 && wide_tiles(p) && ((p.M + 255) / 256) * (unsigned)c128 < 2 * 256) variant = 3;
-    return variant;
+    const unsigned tiles = ((p.M + 255) / 256) * (unsigned)c128;
+    return ((tiles < 2 * 256 && c128 >= 3) || p.Cin <= 64) ? 3 : 0;
 }
 
 // positions per row of p.dbp (64: one row per MFMA wave row of a tile) of the launch launch_gemm1x1 makes when
@@ -440,8 +442,11 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
             const unsigned tiles = ((p.M + 255) / 256) * (unsigned)c128;
             // long reductions over enough 256 x 256 tiles: 64 x 128 wave tiles (fewer LDS operand fetches
             // per MFMA; one workgroup per compute unit, which short reductions do not amortise)
+            // measured on the ResNet-50 layers: with few tiles the 128 x 128 tile pays only from three channel tiles
+            // on (the same activations feed that many workgroups); a one- or two-stage reduction (Cin <= 64) has
+            // too little work per 256 x 128 tile to hide its start-up and stores behind
             if (p.Cout % 256 == 0 && p.Cin >= 512 && tiles / 2 >= 192) variant = 6;
-            else if (tiles < 2 * 256 || p.is_h > 1 || p.is_w > 1) variant = 3;
+            else if ((tiles < 2 * 256 && c128 >= 3) || p.is_h > 1 || p.is_w > 1 || p.Cin <= 64) variant = 3;
         }
         if (variant == 1) return launch_gemm1x1_t<4, 2, 3, 4, 2>(p, st);
         if (variant == 2) return launch_gemm1x1_t<4, 2, 4, 2, 2>(p, st);
@@ -450,10 +455,11 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
         if (variant == 6 && p.Cout % 256 == 0) return launch_gemm1x1_t<4, 2, 3, 2, 2, 4>(p, st);
         return launch_gemm1x1_t<4, 2, 3, 2, 2>(p, st);
     }
+    // 64 output channels: 256 x 64 tiles (4 MFMA waves + 1 loader, ring of 3) beat 512 x 64 on every layer measured
     if (variant == 1) return launch_gemm1x1_t<8, 1, 2, 4, 2>(p, st);
     if (variant == 2) return launch_gemm1x1_t<8, 1, 3, 2, 2>(p, st);
-    if (variant == 3 || variant == 4) return launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st);
-    return launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
+    if (variant == 5) return launch_gemm1x1_t<8, 1, 2, 2, 2>(p, st);
+    return launch_gemm1x1_t<4, 1, 3, 2, 1>(p, st);
 }
 
 }  // namespace ngc
