@@ -529,7 +529,11 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // few chunks and little extra partial traffic, and for multi-tap layers; the large-image 1x1
     // layers are HBM-bound and keep 128-position stages.  NGC_WGG_SP (experiments only) forces 64 / 128.
     const char *fsp = getenv("NGC_WGG_SP");
-    q.sp = (d->r * d->s > 1 || tiles >= 32) ? 64 : 128;
+    // Measured per layer over the ResNet-50 stack (reproducible to 1 %): 64 wins from 16 tiles on, and
+    // by 20-24 % where one operand is read by a single tile row / column and the other by four or more
+    // (128 -> 512 and 512 -> 128 at 28x28); with 2 x 4 tiles it loses 35-65 %.
+    const int tmin = q.ktiles < q.ctiles ? q.ktiles : q.ctiles, tmax = q.ktiles < q.ctiles ? q.ctiles : q.ktiles;
+    q.sp = (d->r * d->s > 1 || tiles >= 16 || (tmin == 1 && tmax >= 4)) ? 64 : 128;
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
     const uint32_t slots = q.sp == 64 ? 2 * NUM_CUS : NUM_CUS;
     uint32_t parts = (slots + tiles - 1) / tiles;
