@@ -520,6 +520,11 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     auto wide = [](int ch) { return ch > 64 && (ch + 127) / 128 * 128 <= (ch + 63) / 64 * 64; };
     q.wk = wide(d->k) ? 2 : 1;
     q.wc = wide(d->c) ? 2 : 1;
+    const char *ft = getenv("NGC_WGG_TILE");                             // tests / benchmarks only: "11", "12", "21", "22"
+    if (ft && (ft[0] == '1' || ft[0] == '2') && (ft[1] == '1' || ft[1] == '2')) {
+        q.wk = ft[0] - '0';
+        q.wc = ft[1] - '0';
+    }
     q.ktiles = (d->k + 64 * q.wk - 1) / (64 * q.wk);
     q.ctiles = (d->c + 64 * q.wc - 1) / (64 * q.wc);
     q.M = (uint32_t)d->n * P * Q;
@@ -535,8 +540,13 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     const int tmin = q.ktiles < q.ctiles ? q.ktiles : q.ctiles, tmax = q.ktiles < q.ctiles ? q.ctiles : q.ktiles;
     q.sp = (d->r * d->s > 1 || tiles >= 16 || (tmin == 1 && tmax >= 4)) ? 64 : 128;
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
-    const uint32_t slots = q.sp == 64 ? 2 * NUM_CUS : NUM_CUS;
+    uint32_t slots = q.sp == 64 ? 2 * NUM_CUS : NUM_CUS;
+    const char *fs = getenv("NGC_WGG_SLOTS");                            // tests / benchmarks only: workgroups aimed at
+    if (fs && atoi(fs) >= 32 && atoi(fs) <= 4096) slots = (uint32_t)atoi(fs);
     uint32_t parts = (slots + tiles - 1) / tiles;
+    // many (tile, tap) pairs: a few workgroups more than the slots cost a whole extra round of long workgroups
+    // (3x3 stride 2, 512 -> 512: 576 workgroups 78 us, 432 workgroups 57 us), so round down there
+    if (tiles >= 64 && slots / tiles >= 1) parts = slots / tiles;
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;
