@@ -1004,7 +1004,14 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
             if (e != hipSuccess) return launch_status(e);
         }
         const int ncls = strip_classes(desc, NGC_OP_BWD_DATA);
-        for (int c = 0; c < ncls; ++c) {                                 // one launch per residue class of the stride
+        // the residue classes of the stride: one launch each, or (up to 4 classes, 8-wave kernels) all in one grid
+        const bool merge = !(getenv("NGC_STRIP_MERGE") && atoi(getenv("NGC_STRIP_MERGE")) == 0) &&
+                                  getenv("NGC_STRIP_1WAVE") == nullptr;
+        StripMulti mp;
+        mp.n = 0;
+        int nf_max = 0;
+        size_t lds_max = 0;
+        for (int c = 0; c < ncls; ++c) {
             StripParams sp;
             int nf;
             size_t lds;
@@ -1024,9 +1031,19 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
                 sp.dbp_ld = fuse->ld;
                 fuse->rows += sp.groups * sp.strips * 8;
             }
+            if (merge && ncls > 1 && ncls <= STRIP_MULTI_MAX) {
+                mp.c[mp.n] = sp;
+                mp.wg_end[mp.n] = (mp.n ? mp.wg_end[mp.n - 1] : 0) + sp.groups * sp.strips;
+                ++mp.n;
+                if (nf > nf_max) nf_max = nf;
+                if (lds > lds_max) lds_max = lds;
+                continue;
+            }
             const int rc = launch_status(launch_strip(sp, nf, lds, st));
             if (rc != NGC_OK) return rc;
         }
+        if (mp.n == 1) return launch_status(launch_strip(mp.c[0], nf_max, lds_max, st));
+        if (mp.n > 1) return launch_status(launch_strip_multi(mp, nf_max, lds_max, st));
         return NGC_OK;
     }
     if (v == V_GEMM1X1) {

@@ -382,6 +382,15 @@ hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st);
 hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
+
+// up to 4 launches of the strip kernel (blocked output, same Cout) in one grid
+constexpr int STRIP_MULTI_MAX = 4;
+struct StripMulti {
+    int32_t n;
+    int32_t wg_end[STRIP_MULTI_MAX];   // prefix sums of groups * strips
+    StripParams c[STRIP_MULTI_MAX];
+};
+hipError_t launch_strip_multi(const StripMulti &mp, int nf, size_t lds_bytes, hipStream_t st);
 hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st);

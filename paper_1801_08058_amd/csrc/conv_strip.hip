@@ -48,8 +48,9 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // DB (blocked output only): every wave also writes the sums over its positions of the values it
 // stored, per output channel (fp32, fixed order), to row (p.dbp_row0 + blockIdx.x) * NW + wave of
 // p.dbp - the partials of a bias gradient of the stored tensor.  A separate instantiation.
-template <int NF, int NW, int SUB = 0, bool DB = false>
-__global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
+// bx = workgroup index inside the launch's (group, strip) grid
+template <int NF, int NW, int SUB, bool DB>
+__device__ __forceinline__ void conv_strip_body(const StripParams &p, const int bx)
 {
     constexpr bool HALF = SUB == 1;
     constexpr int MAXXB = STRIP_MAXBLOCKS / NW;         // patch blocks per wave
@@ -61,8 +62,8 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
     const int l32 = lane & 31;
     const int lg = lane >> 5;
 
-    const int grp = blockIdx.x / p.strips;
-    const int strip = blockIdx.x - grp * p.strips;
+    const int grp = bx / p.strips;
+    const int strip = bx - grp * p.strips;
     const int n0 = grp * p.TN;
     const int p0 = strip * p.TP;
     const int k0 = blockIdx.y * 64;
@@ -343,10 +344,28 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         const float mine = half_wave_transpose_sum32(flat, l32);
         const int j = ((l32 & 15) << 1) | (l32 >> 4);
         const int ch = k0 + (j >> 4) * 32 + ((j >> 3) & 1) * 16 + 8 * lg + (j & 7);
-        if (ch < p.Cout) p.dbp[((size_t)(p.dbp_row0 + blockIdx.x) * NW + wave) * p.dbp_ld + ch] = mine;
+        if (ch < p.Cout) p.dbp[((size_t)(p.dbp_row0 + bx) * NW + wave) * p.dbp_ld + ch] = mine;
     }
 }
 
+
+template <int NF, int NW, int SUB = 0, bool DB = false>
+__global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
+{
+    conv_strip_body<NF, NW, SUB, DB>(p, blockIdx.x);
+}
+
+// Several launches of the kernel above in one grid (the residue classes of a strided backprop-data: each has
+// its own tap list and geometry): workgroups [wg_end[i-1], wg_end[i]) run launch i.  Small classes then share
+// the chip with large ones instead of leaving it half empty, and three launch gaps go away.
+template <int NF, int NW, bool DB>
+__global__ __launch_bounds__(NW * 64) void conv_strip_multi_bf16(const StripMulti mp)
+{
+    int cls = 0;
+    while (cls + 1 < mp.n && (int)blockIdx.x >= mp.wg_end[cls]) ++cls;   // uniform per workgroup
+    const int bx = (int)blockIdx.x - (cls ? mp.wg_end[cls - 1] : 0);
+    conv_strip_body<NF, NW, 0, DB>(mp.c[cls], bx);
+}
 
 template <int NF, int NW, int SUB, bool DB>
 static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStream_t st)
@@ -396,6 +415,31 @@ hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStrea
     case 7: return two_waves ? launch_strip_nf<4, 8>(p, lds_bytes, st) : launch_strip_nf<7, 4>(p, lds_bytes, st);
     case 4: return two_waves ? launch_strip_nf<2, 8>(p, lds_bytes, st) : launch_strip_nf<4, 4>(p, lds_bytes, st);
     case 2: return two_waves ? launch_strip_nf<1, 8>(p, lds_bytes, st) : launch_strip_nf<2, 4>(p, lds_bytes, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int NF, bool DB>
+static hipError_t launch_strip_multi_t(const StripMulti &mp, size_t lds_bytes, hipStream_t st)
+{
+    static LdsLimitOnce lds_limit;
+    {
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_multi_bf16<NF, 8, DB>));
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(mp.wg_end[mp.n - 1], (mp.c[0].Cout + 63) / 64);
+    NGC_LAUNCH((conv_strip_multi_bf16<NF, 8, DB>), grid, dim3(8 * 64), lds_bytes, st, mp);
+    return hipGetLastError();
+}
+
+// nf = the largest strip size (7, 4 or 2) among the launches, lds_bytes the largest stage buffers; blocked output
+hipError_t launch_strip_multi(const StripMulti &mp, int nf, size_t lds_bytes, hipStream_t st)
+{
+    const bool db = mp.c[0].dbp != nullptr;
+    switch (nf) {
+    case 7: return db ? launch_strip_multi_t<4, true>(mp, lds_bytes, st) : launch_strip_multi_t<4, false>(mp, lds_bytes, st);
+    case 4: return db ? launch_strip_multi_t<2, true>(mp, lds_bytes, st) : launch_strip_multi_t<2, false>(mp, lds_bytes, st);
+    case 2: return db ? launch_strip_multi_t<1, true>(mp, lds_bytes, st) : launch_strip_multi_t<1, false>(mp, lds_bytes, st);
     default: return hipErrorInvalidValue;
     }
 }

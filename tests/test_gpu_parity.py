@@ -413,6 +413,13 @@ def test_strided_strip_kernel(case, pre):
     _check_all(a, "bf16", BLK, BLK, pre, 8000 + case, ("strip", "strip", "wgrad"))
 
 
+@pytest.mark.parametrize("case", range(len(STRIDED_STRIP_CASES)))
+def test_strided_strip_one_launch_per_class(case, monkeypatch):
+    """NGC_STRIP_MERGE=0: the residue classes of backprop-data as separate launches instead of one grid."""
+    monkeypatch.setenv("NGC_STRIP_MERGE", "0")
+    _check_all(STRIDED_STRIP_CASES[case], "bf16", BLK, BLK, True, 8050 + case, ("strip", "strip", "wgrad"))
+
+
 @pytest.mark.parametrize("case", [0, 3])
 def test_strided_gather_kernel_still_matches(case, monkeypatch):
     """Strided multi-tap shapes through the gather implicit-GEMM kernel (strided strips switched off)."""
