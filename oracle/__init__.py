@@ -10,3 +10,7 @@ from .conv_oracle import (  # noqa: F401
     relu_bwd_mask, bias_grad, conv_bwd_data_relu,
 )
 from .softmax_oracle import softmax, softmax_bwd  # noqa: F401
+from .conv3d_oracle import (  # noqa: F401
+    Attrs3, out_shape3, conv3d_fwd, conv3d_bwd_data, conv3d_bwd_filters, conv3d_fwd_at,
+    conv3d_bwd_data_at, conv3d_bwd_filters_at,
+)

@@ -417,3 +417,117 @@ def test_softmax_bwd_is_the_transposed_jacobian_and_matches_central_differences(
     np.testing.assert_allclose(dx.sum(axis=-1), 0.0, atol=1e-15)
     # hand-worked: y = (1/2, 1/2), dy = (1, 0): s = 1/2, dx = (1/4, -1/4)
     np.testing.assert_allclose(oracle.softmax_bwd(np.array([0.5, 0.5]), np.array([1.0, 0.0])), [0.25, -0.25], rtol=1e-15)
+
+
+# ---------------------------------------------------------------- P14 convolution over three spatial axes
+from oracle import Attrs3  # noqa: E402
+
+
+def _rand3(a: Attrs3, g):
+    O, P, Q = oracle.out_shape3(a)
+    x = g.integers(-3, 4, size=(a.n, a.c, a.d, a.h, a.w)).astype(float)
+    w = g.integers(-3, 4, size=(a.k, a.c, a.t, a.r, a.s)).astype(float)
+    dy = g.integers(-3, 4, size=(a.n, a.k, O, P, Q)).astype(float)
+    return x, w, dy
+
+
+# (extent, taps, stride, dilation, pad below, pad above) of two active axes; the third has extent 1
+_PAIR_CASES = [((7, 3, 1, 1, 1, 1), (6, 2, 2, 1, 0, 1)), ((9, 3, 2, 2, 2, 0), (8, 3, 1, 1, 0, 2)),
+               ((5, 1, 1, 1, 0, 0), (11, 4, 3, 2, 3, 1))]
+
+
+@pytest.mark.parametrize("axes", [(0, 1), (0, 2), (1, 2), (1, 0), (2, 0)])
+@pytest.mark.parametrize("case", _PAIR_CASES)
+def test_conv3d_on_two_axes_is_the_rank2_oracle(axes, case):
+    """With one spatial axis of extent 1 (window 1, no padding) the rank-3 ops are the rank-2 ones on the
+    other two axes, whichever pair that is and in either order: pins the stride / dilation / padding
+    handling of each axis, per side, against the C oracle."""
+    g = np.random.default_rng(7 + 10 * axes[0] + axes[1])
+    ext, taps, st, dil, pb, pa = ([1] * 3 for _ in range(6))
+    st, dil = [1] * 3, [1] * 3
+    pb, pa = [0] * 3, [0] * 3
+    for ax, (e, t_, s_, d_, b_, a_) in zip(axes, case):
+        ext[ax], taps[ax], st[ax], dil[ax], pb[ax], pa[ax] = e, t_, s_, d_, b_, a_
+    a3 = Attrs3(2, 3, ext[0], ext[1], ext[2], 4, taps[0], taps[1], taps[2], st[0], st[1], st[2],
+                dil[0], dil[1], dil[2], pb[0], pb[1], pb[2], pa[0], pa[1], pa[2])
+    (e0, t0, s0, d0, b0, p0), (e1, t1, s1, d1, b1, p1) = case
+    a2 = Attrs(2, 3, e0, e1, 4, t0, t1, s0, s1, d0, d1, b0, b1, p0, p1)
+    x, w, dy = _rand3(a3, g)
+    # move the two active axes (in the order given) to the front of the spatial axes and drop the third
+    idle = ({0, 1, 2} - set(axes)).pop()
+    perm = [0, 1, 2 + axes[0], 2 + axes[1], 2 + idle]
+    to2 = lambda v: np.transpose(v, perm)[..., 0]
+    bias = g.integers(-5, 6, size=4).astype(float)
+    assert oracle.out_shape3(a3)[axes[0]] == oracle.out_shape(a2)[0] and oracle.out_shape3(a3)[axes[1]] == oracle.out_shape(a2)[1]
+    assert np.array_equal(to2(oracle.conv3d_fwd(a3, x, w, bias, True)), oracle.conv_fwd(a2, to2(x), to2(w), bias, True))
+    assert np.array_equal(to2(oracle.conv3d_bwd_data(a3, dy, w)), oracle.conv_bwd_data(a2, to2(dy), to2(w)))
+    assert np.array_equal(to2(oracle.conv3d_bwd_filters(a3, x, dy)), oracle.conv_bwd_filters(a2, to2(x), to2(dy)))
+
+
+def _brute3(a: Attrs3, x, w, dy):
+    """Scalar loops from the definition, with bounds tests instead of a padded copy."""
+    O, P, Q = oracle.out_shape3(a)
+    y = np.zeros((a.n, a.k, O, P, Q)); dx = np.zeros_like(x); dw = np.zeros_like(w)
+    for n, k, o, p, q, c, t, r, s in itertools.product(range(a.n), range(a.k), range(O), range(P), range(Q),
+                                                       range(a.c), range(a.t), range(a.r), range(a.s)):
+        z, i, j = o * a.sd - a.pbd + t * a.dd, p * a.sh - a.pbh + r * a.dh, q * a.sw - a.pbw + s * a.dw
+        if not (0 <= z < a.d and 0 <= i < a.h and 0 <= j < a.w):
+            continue
+        y[n, k, o, p, q] += x[n, c, z, i, j] * w[k, c, t, r, s]
+        dx[n, c, z, i, j] += dy[n, k, o, p, q] * w[k, c, t, r, s]
+        dw[k, c, t, r, s] += dy[n, k, o, p, q] * x[n, c, z, i, j]
+    return y, dx, dw
+
+
+_TINY3 = [Attrs3(1, 2, 4, 5, 3, 2, 2, 3, 2, 1, 2, 1, 2, 1, 1, 1, 0, 1, 0, 2, 0),
+          Attrs3(2, 1, 5, 4, 6, 2, 3, 2, 3, 2, 1, 2, 1, 1, 2, 2, 1, 3, 1, 0, 2),
+          Attrs3(1, 2, 3, 3, 3, 1, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("a", _TINY3)
+def test_conv3d_brute_force_tiny(a):
+    g = np.random.default_rng(a.d * 100 + a.h * 10 + a.w)
+    x, w, dy = _rand3(a, g)
+    y, dx, dw = _brute3(a, x, w, dy)
+    assert np.array_equal(oracle.conv3d_fwd(a, x, w), y)
+    assert np.array_equal(oracle.conv3d_bwd_data(a, dy, w), dx)
+    assert np.array_equal(oracle.conv3d_bwd_filters(a, x, dy), dw)
+    O, P, Q = oracle.out_shape3(a)
+    assert np.array_equal(oracle.conv3d_fwd_at(a, x, w, np.arange(y.size)), y.reshape(-1))
+    assert np.array_equal(oracle.conv3d_bwd_data_at(a, dy, w, np.arange(dx.size)), dx.reshape(-1))
+    assert np.array_equal(oracle.conv3d_bwd_filters_at(a, x, dy, np.arange(dw.size)), dw.reshape(-1))
+
+
+def test_conv3d_single_channel_is_scipy_correlate():
+    from scipy.signal import correlate
+    g = np.random.default_rng(5)
+    a = Attrs3(1, 1, 6, 7, 8, 1, 3, 2, 4)
+    x, w, _ = _rand3(a, g)
+    assert np.array_equal(oracle.conv3d_fwd(a, x, w)[0, 0], correlate(x[0, 0], w[0, 0], mode="valid", method="direct"))
+    # full zero padding on both sides of every axis = scipy's "full" mode
+    af = Attrs3(1, 1, 6, 7, 8, 1, 3, 2, 4, 1, 1, 1, 1, 1, 1, 2, 1, 3, 2, 1, 3)
+    assert np.array_equal(oracle.conv3d_fwd(af, x, w)[0, 0], correlate(x[0, 0], w[0, 0], mode="full", method="direct"))
+
+
+@pytest.mark.parametrize("a", [Attrs3(2, 3, 6, 5, 7, 4, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1),
+                               Attrs3(2, 3, 7, 6, 5, 4, 3, 2, 3, 2, 1, 2, 1, 2, 1, 1, 0, 2, 2, 1, 0)])
+def test_conv3d_adjoint_identities(a):
+    g = np.random.default_rng(11)
+    x, w, dy = _rand3(a, g)
+    ip = (oracle.conv3d_fwd(a, x, w) * dy).sum()
+    assert ip == (x * oracle.conv3d_bwd_data(a, dy, w)).sum() == (w * oracle.conv3d_bwd_filters(a, x, dy)).sum()
+
+
+def test_conv3d_closed_forms():
+    # all ones, stride 1, one voxel of padding all round: y = C * (taps inside the volume)
+    a = Attrs3(1, 2, 4, 4, 4, 1, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1)
+    y = oracle.conv3d_fwd(a, np.ones((1, 2, 4, 4, 4)), np.ones((1, 2, 3, 3, 3)))[0, 0]
+    side = np.array([2, 3, 3, 2])
+    assert np.array_equal(y, 2.0 * side[:, None, None] * side[None, :, None] * side[None, None, :])
+    # an off-centre delta filter is a shift: no flip on any axis
+    w = np.zeros((1, 1, 3, 3, 3)); w[0, 0, 2, 0, 1] = 1.0
+    x = np.arange(4 * 4 * 4, dtype=float).reshape(1, 1, 4, 4, 4)
+    a1 = Attrs3(1, 1, 4, 4, 4, 1, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1)
+    y = oracle.conv3d_fwd(a1, x, w)[0, 0]
+    want = np.zeros((4, 4, 4)); want[:3, 1:, :] = x[0, 0, 1:, :3, :]
+    assert np.array_equal(y, want)
