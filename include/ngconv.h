@@ -1,5 +1,6 @@
 /*
- * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family (and Softmax, at the end).
+ * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family over two and three spatial axes
+ * (and Softmax).
  *
  * The library plays the part of the kernels a backend "transformer" selects
  * for an IR graph (paper Sec. 4, "Transformers": tensor-element layout and
@@ -189,6 +190,69 @@ size_t ngc_filter_elems(const ngc_conv_desc *desc, int32_t layout);
 /* Name of the kernel variant the dispatcher picks for (desc, op): a static string such as
  * "igemm_bf16_128x128" or "direct"; "unsupported" / "invalid" otherwise.  Host only. */
 const char *ngc_conv_variant(const ngc_conv_desc *desc, int op);
+
+/* ---- Convolution over three spatial axes (N, C, D, H, W) --------------------------------------
+ * The IR is rank-general (Sec. 2: tensors of any rank, an op is its inputs plus constant
+ * attributes); this is the same op with one more window axis:
+ *   O = floor((D + pad_below_d + pad_above_d - dil_d*(T-1) - 1) / stride_d) + 1, P, Q likewise
+ *   y[n,k,o,p,q] = sum_{c,t,r,s} X(n,c, o*stride_d - pad_below_d + t*dil_d, p*stride_h - ...,
+ *                                        q*stride_w - ...) * w[k,c,t,r,s],  X = 0 outside the volume
+ * with the epilogue, the two adjoints (Sec. 3), the element types, the error behaviour and the
+ * calling conventions of the rank-2 entry points above.
+ * Layouts: NGC_NCHW = x[n][c][d][h][w]; NGC_NCHW16C = x[n][cb][d][h][w][ci]; filters NGC_KCRS =
+ * w[k][c][t][r][s], NGC_BLOCKED_FWD = w[t][r][s][cb][k][ci], NGC_BLOCKED_BWD = w[t][r][s][kb][c][ki]
+ * (ngc_conv3d_filter_convert).  Data tensors convert with ngc_layout_convert(dtype, n, c, d*h, w, ...):
+ * both layouts keep (d, h, w) contiguous in that order.
+ * Kernels: a window that moves over at most one group of adjacent axes ((T,1,1), (1,1,S), 1x1x1)
+ * is the rank-2 op on a reshaped tensor and runs on the rank-2 kernels; other bf16 blocked shapes
+ * with C and K multiples of 64 (forward / backprop-data) or 16 (backprop-filters) run on the MFMA
+ * gather kernels with a depth axis; everything else on direct kernels (KCRS filters only).
+ */
+typedef struct {
+    int32_t n, c, d, h, w;         /* data batch shape, logical axes N,C,D,H,W                      */
+    int32_t k, t, r, s;            /* filters: K x C x T x R x S                                    */
+    int32_t stride_d, stride_h, stride_w;
+    int32_t dil_d, dil_h, dil_w;
+    int32_t pad_below_d, pad_below_h, pad_below_w;
+    int32_t pad_above_d, pad_above_h, pad_above_w;
+    int32_t dtype;                 /* ngc_dtype of x, w, y, dy, dx (bias and dw are always fp32)    */
+    int32_t x_layout, y_layout;    /* ngc_data_layout                                               */
+    int32_t w_layout;              /* ngc_filter_layout of the filter argument of fwd / bwd_data    */
+    int32_t epilogue;              /* NGC_EPI_* flags, forward only                                 */
+} ngc_conv3d_desc;
+
+/* Output extents O, P, Q.  Host only.  NGC_OK, NGC_BAD_ARG (null) or NGC_BAD_SHAPE. */
+int ngc_conv3d_out_shape(const ngc_conv3d_desc *desc, int32_t *o, int32_t *p, int32_t *q);
+
+/* Workspace bytes of op NGC_OP_FWD / NGC_OP_BWD_DATA / NGC_OP_BWD_FILTERS; 0 if none or invalid. */
+size_t ngc_conv3d_workspace_bytes(const ngc_conv3d_desc *desc, int op);
+
+/* Forward with the compounded bias / ReLU epilogue.  x: [N,C,D,H,W] in x_layout; w in w_layout
+ * (KCRS or BLOCKED_FWD); bias fp32 [K] or NULL; y: [N,K,O,P,Q] in y_layout, overwritten. */
+int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, const float *bias,
+                   void *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backprop-data.  dy: [N,K,O,P,Q] in y_layout; w in w_layout (KCRS or BLOCKED_BWD); dx in x_layout,
+ * every element overwritten (0 where no window reaches). */
+int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void *w,
+                        void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backprop-filters.  dw: fp32 [K][C][T][R][S], overwritten; fixed-order reduction through `ws`. */
+int ngc_conv3d_bwd_filters(const ngc_conv3d_desc *desc, const void *x, const void *dy,
+                           float *dw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Filter re-layout: w [K][C][T][R][S] of desc->dtype -> NGC_BLOCKED_FWD / NGC_BLOCKED_BWD
+ * (ngc_conv3d_filter_elems elements, padded lanes +0).  Bit exact. */
+int ngc_conv3d_filter_convert(const ngc_conv3d_desc *desc, const void *w_kctrs, void *w_blocked,
+                              int32_t dst_layout, void *hip_stream);
+size_t ngc_conv3d_filter_elems(const ngc_conv3d_desc *desc, int32_t layout);
+
+/* Element counts of x/dx (which = 0) and y/dy (which = 1) in their layouts.  Host only. */
+size_t ngc_conv3d_data_elems(const ngc_conv3d_desc *desc, int which);
+
+/* Name of the kernel variant picked for (desc, op): "rank2:<rank-2 variant>" for windows that
+ * reduce to the rank-2 op, "igemm3_bf16_*", "wgrad_gemm3_bf16", "direct3", "unsupported", "invalid". */
+const char *ngc_conv3d_variant(const ngc_conv3d_desc *desc, int op);
 
 /* Static description of a status code. */
 const char *ngc_status_string(int status);

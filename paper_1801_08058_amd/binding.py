@@ -24,7 +24,10 @@ NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD, NGC_OP_BWD_DA
 
 EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
            "ngc_conv_bwd_data_relu", "ngc_conv_bwd_data_relu_db", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
-           "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string")
+           "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string",
+           "ngc_conv3d_out_shape", "ngc_conv3d_workspace_bytes", "ngc_conv3d_fwd", "ngc_conv3d_bwd_data",
+           "ngc_conv3d_bwd_filters", "ngc_conv3d_filter_convert", "ngc_conv3d_filter_elems", "ngc_conv3d_data_elems",
+           "ngc_conv3d_variant")
 
 
 class ngc_conv_desc(ctypes.Structure):
@@ -36,6 +39,17 @@ class ngc_conv_desc(ctypes.Structure):
 
     def __repr__(self):
         return "ngc_conv_desc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"
+
+
+class ngc_conv3d_desc(ctypes.Structure):
+    """Mirror of the C struct: constant attributes of a Convolution node over three spatial axes."""
+    _fields_ = [(name, ctypes.c_int32) for name in (
+        "n", "c", "d", "h", "w", "k", "t", "r", "s", "stride_d", "stride_h", "stride_w", "dil_d", "dil_h", "dil_w",
+        "pad_below_d", "pad_below_h", "pad_below_w", "pad_above_d", "pad_above_h", "pad_above_w",
+        "dtype", "x_layout", "y_layout", "w_layout", "epilogue")]
+
+    def __repr__(self):
+        return "ngc_conv3d_desc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"
 
 
 class NgcError(RuntimeError):
@@ -93,6 +107,25 @@ def _load() -> ctypes.CDLL:
     lib.ngc_conv_variant.restype = ctypes.c_char_p
     lib.ngc_status_string.argtypes = [ctypes.c_int]
     lib.ngc_status_string.restype = ctypes.c_char_p
+    D3 = ctypes.POINTER(ngc_conv3d_desc)
+    lib.ngc_conv3d_out_shape.argtypes = [D3, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.ngc_conv3d_out_shape.restype = ctypes.c_int
+    lib.ngc_conv3d_workspace_bytes.argtypes = [D3, ctypes.c_int]
+    lib.ngc_conv3d_workspace_bytes.restype = sz
+    lib.ngc_conv3d_fwd.argtypes = [D3, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_fwd.restype = ctypes.c_int
+    lib.ngc_conv3d_bwd_data.argtypes = [D3, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_bwd_data.restype = ctypes.c_int
+    lib.ngc_conv3d_bwd_filters.argtypes = [D3, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_bwd_filters.restype = ctypes.c_int
+    lib.ngc_conv3d_filter_convert.argtypes = [D3, vp, vp, i32, vp]
+    lib.ngc_conv3d_filter_convert.restype = ctypes.c_int
+    lib.ngc_conv3d_filter_elems.argtypes = [D3, i32]
+    lib.ngc_conv3d_filter_elems.restype = sz
+    lib.ngc_conv3d_data_elems.argtypes = [D3, ctypes.c_int]
+    lib.ngc_conv3d_data_elems.restype = sz
+    lib.ngc_conv3d_variant.argtypes = [D3, ctypes.c_int]
+    lib.ngc_conv3d_variant.restype = ctypes.c_char_p
     return lib
 
 
@@ -212,3 +245,58 @@ def ngc_layout_convert(dtype, n, c, h, w, src, src_layout, dst, dst_layout, stre
 def ngc_filter_convert(desc, w_kcrs, w_blocked, dst_layout, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_filter_convert(ctypes.byref(desc), _ptr(w_kcrs), _ptr(w_blocked), dst_layout,
                                           _stream(stream)), "ngc_filter_convert", check)
+
+
+# ---- Convolution over three spatial axes
+
+def make_desc3(n, c, d, h, w, k, t, r, s, stride=(1, 1, 1), dilation=(1, 1, 1), pad_below=(0, 0, 0), pad_above=(0, 0, 0),
+               dtype=NGC_BF16, x_layout=NGC_NCHW16C, y_layout=NGC_NCHW16C, w_layout=NGC_KCRS,
+               epilogue=NGC_EPI_NONE) -> ngc_conv3d_desc:
+    return ngc_conv3d_desc(n, c, d, h, w, k, t, r, s, *stride, *dilation, *pad_below, *pad_above,
+                           dtype, x_layout, y_layout, w_layout, epilogue)
+
+
+def ngc_conv3d_out_shape(desc: ngc_conv3d_desc, check: bool = True):
+    o, p, q = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    st = _lib.ngc_conv3d_out_shape(ctypes.byref(desc), ctypes.byref(o), ctypes.byref(p), ctypes.byref(q))
+    if st != NGC_OK:
+        if check:
+            raise NgcError(st, "ngc_conv3d_out_shape")
+        return st
+    return o.value, p.value, q.value
+
+
+def ngc_conv3d_workspace_bytes(desc: ngc_conv3d_desc, op: int) -> int:
+    return int(_lib.ngc_conv3d_workspace_bytes(ctypes.byref(desc), op))
+
+
+def ngc_conv3d_data_elems(desc: ngc_conv3d_desc, which: int) -> int:
+    return int(_lib.ngc_conv3d_data_elems(ctypes.byref(desc), which))
+
+
+def ngc_conv3d_filter_elems(desc: ngc_conv3d_desc, layout: int) -> int:
+    return int(_lib.ngc_conv3d_filter_elems(ctypes.byref(desc), layout))
+
+
+def ngc_conv3d_variant(desc: ngc_conv3d_desc, op: int) -> str:
+    return _lib.ngc_conv3d_variant(ctypes.byref(desc), op).decode()
+
+
+def ngc_conv3d_fwd(desc, x, w, bias, y, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_fwd(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(ws), _nbytes(ws),
+                                      _stream(stream)), "ngc_conv3d_fwd", check)
+
+
+def ngc_conv3d_bwd_data(desc, dy, w, dx, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_bwd_data(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), _nbytes(ws),
+                                           _stream(stream)), "ngc_conv3d_bwd_data", check)
+
+
+def ngc_conv3d_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_bwd_filters(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), _nbytes(ws),
+                                              _stream(stream)), "ngc_conv3d_bwd_filters", check)
+
+
+def ngc_conv3d_filter_convert(desc, w_kctrs, w_blocked, dst_layout, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_filter_convert(ctypes.byref(desc), _ptr(w_kctrs), _ptr(w_blocked), dst_layout,
+                                                 _stream(stream)), "ngc_conv3d_filter_convert", check)

@@ -1,0 +1,446 @@
+// C ABI of the Convolution op family over three spatial axes (include/ngconv.h, second part):
+// validation, kernel selection, workspace layout, launches.
+//
+// Selection per op:
+//   1. the window moves over at most one group of adjacent axes while the others are idle (window 1,
+//      stride 1, no padding): the op equals the rank-2 op on a reshaped tensor ((D, H*W) with a
+//      (T,1) window, or (D*H, W) with a (1,S) window; 1x1x1 is the first with T = 1) and goes to
+//      the rank-2 entry point, i.e. to the strip / 1x1 GEMM / per-tap kernels;
+//   2. bf16, blocked tensors: the gather kernel (forward / backprop-data; Cin % 32, Cout % 64) and
+//      the per-tap backprop-filters GEMM (C % 16, K % 16), each with a depth axis;
+//   3. the direct kernels (filters [K][C][T][R][S] only).
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+
+using namespace ngc;
+
+constexpr size_t MAX_ELEMS3 = (size_t)1 << 31;
+constexpr int NUM_CUS3 = 256;
+
+int out_dim3(int extent, int below, int above, int dil, int taps, int stride)
+{
+    const long long span = (long long)extent + below + above - (long long)dil * (taps - 1) - 1;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+bool layout_ok3(int l) { return l == NGC_NCHW || l == NGC_NCHW16C; }
+
+size_t phys3(int layout, int n, int c, int d, int h, int w)
+{
+    return (size_t)n * (layout == NGC_NCHW ? c : (c + 15) / 16 * 16) * d * h * w;
+}
+
+int validate3(const ngc_conv3d_desc *d, int *O, int *P, int *Q)
+{
+    if (!d) return NGC_BAD_ARG;
+    if (d->dtype != NGC_F32 && d->dtype != NGC_BF16) return NGC_BAD_ARG;
+    if (!layout_ok3(d->x_layout) || !layout_ok3(d->y_layout)) return NGC_BAD_ARG;
+    if (d->w_layout != NGC_KCRS && d->w_layout != NGC_BLOCKED_FWD && d->w_layout != NGC_BLOCKED_BWD) return NGC_BAD_ARG;
+    if (d->epilogue & ~(NGC_EPI_BIAS | NGC_EPI_RELU)) return NGC_BAD_ARG;
+    if (d->n < 1 || d->c < 1 || d->d < 1 || d->h < 1 || d->w < 1 || d->k < 1 || d->t < 1 || d->r < 1 || d->s < 1)
+        return NGC_BAD_SHAPE;
+    if (d->stride_d < 1 || d->stride_h < 1 || d->stride_w < 1 || d->dil_d < 1 || d->dil_h < 1 || d->dil_w < 1) return NGC_BAD_SHAPE;
+    if (d->pad_below_d < 0 || d->pad_below_h < 0 || d->pad_below_w < 0 || d->pad_above_d < 0 || d->pad_above_h < 0 ||
+        d->pad_above_w < 0)
+        return NGC_BAD_SHAPE;
+    // keep every intermediate index comfortably inside int32
+    const int big[] = {d->d, d->h, d->w, d->pad_below_d, d->pad_below_h, d->pad_below_w, d->pad_above_d, d->pad_above_h, d->pad_above_w};
+    for (int v : big)
+        if (v > (1 << 20)) return NGC_BAD_SHAPE;
+    const int small[] = {d->t, d->r, d->s, d->dil_d, d->dil_h, d->dil_w, d->stride_d, d->stride_h, d->stride_w};
+    for (int v : small)
+        if (v > 1024) return NGC_BAD_SHAPE;
+    const int o = out_dim3(d->d, d->pad_below_d, d->pad_above_d, d->dil_d, d->t, d->stride_d);
+    const int p = out_dim3(d->h, d->pad_below_h, d->pad_above_h, d->dil_h, d->r, d->stride_h);
+    const int q = out_dim3(d->w, d->pad_below_w, d->pad_above_w, d->dil_w, d->s, d->stride_w);
+    if (o < 1 || p < 1 || q < 1) return NGC_BAD_SHAPE;
+    if ((double)d->n * ((d->c + 15) / 16 * 16) * d->d * d->h * d->w >= (double)MAX_ELEMS3) return NGC_BAD_SHAPE;
+    if ((double)d->n * ((d->k + 15) / 16 * 16) * o * p * q >= (double)MAX_ELEMS3) return NGC_BAD_SHAPE;
+    if ((double)((d->k + 15) / 16 * 16) * ((d->c + 15) / 16 * 16) * d->t * d->r * d->s >= (double)MAX_ELEMS3) return NGC_BAD_SHAPE;
+    *O = o; *P = p; *Q = q;
+    return NGC_OK;
+}
+
+bool aligned16_3(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+size_t round256_3(size_t b) { return (b + 255) & ~(size_t)255; }
+
+int status3(hipError_t e)
+{
+    if (e == hipSuccess) return NGC_OK;
+    fprintf(stderr, "ngconv: HIP launch failed: %s\n", hipGetErrorString(e));   // error path only
+    return NGC_LAUNCH_FAILED;
+}
+
+bool idle_axis(int taps, int stride, int below, int above) { return taps == 1 && stride == 1 && below == 0 && above == 0; }
+
+// The rank-2 node this node equals on a reshaped tensor, if there is one.
+bool as_rank2(const ngc_conv3d_desc *d, int O, int P, int Q, ngc_conv_desc *out)
+{
+    const char *sw = getenv("NGC_CONV3D_RANK2");         // tests / benchmarks only: 0 = always the rank-3 kernels
+    if (sw && atoi(sw) == 0) return false;
+    const bool id = idle_axis(d->t, d->stride_d, d->pad_below_d, d->pad_above_d);
+    const bool ih = idle_axis(d->r, d->stride_h, d->pad_below_h, d->pad_above_h);
+    const bool iw = idle_axis(d->s, d->stride_w, d->pad_below_w, d->pad_above_w);
+    ngc_conv_desc t;
+    memset(&t, 0, sizeof(t));
+    t.n = d->n; t.c = d->c; t.k = d->k;
+    t.dtype = d->dtype; t.x_layout = d->x_layout; t.y_layout = d->y_layout; t.w_layout = d->w_layout; t.epilogue = d->epilogue;
+    t.stride_h = t.stride_w = t.dil_h = t.dil_w = 1;
+    t.r = t.s = 1;
+    if (ih && iw) {                                       // (T,1,1): rows = depth slices, columns = H*W
+        if ((long long)d->h * d->w > (1 << 20)) return false;
+        t.h = d->d; t.w = d->h * d->w;
+        t.r = d->t; t.stride_h = d->stride_d; t.dil_h = d->dil_d;
+        t.pad_below_h = d->pad_below_d; t.pad_above_h = d->pad_above_d;
+    } else if (id && ih) {                                // (1,1,S): rows = D*H, columns = W
+        if ((long long)d->d * d->h > (1 << 20)) return false;
+        t.h = d->d * d->h; t.w = d->w;
+        t.s = d->s; t.stride_w = d->stride_w; t.dil_w = d->dil_w;
+        t.pad_below_w = d->pad_below_w; t.pad_above_w = d->pad_above_w;
+    } else {
+        return false;
+    }
+    (void)O; (void)P; (void)Q;
+    *out = t;
+    return true;
+}
+
+enum Variant3 { V3_INVALID, V3_UNSUPPORTED, V3_RANK2, V3_IGEMM_128, V3_IGEMM_64, V3_WGRAD_GEMM, V3_DIRECT };
+
+bool blocked_bf16_3(const ngc_conv3d_desc *d)
+{
+    return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
+}
+
+// tile shape and split of the position axis of the per-tap backprop-filters GEMM
+bool wgrad_gemm3_plan(const ngc_conv3d_desc *d, int O, int P, int Q, WgradGemmParams *wp)
+{
+    const int taps = d->t * d->r * d->s;
+    if (!blocked_bf16_3(d) || d->c % 16 != 0 || d->k % 16 != 0 || taps > 64) return false;
+    const size_t x_bytes = (size_t)d->n * d->c * d->d * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * O * P * Q * 2;
+    if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
+    WgradGemmParams q;
+    memset(&q, 0, sizeof(q));
+    q.r3 = 1;
+    q.N = d->n; q.C = d->c; q.D = d->d; q.H = d->h; q.W = d->w; q.K = d->k; q.O = O; q.P = P; q.Q = Q;
+    q.T = d->t; q.R = d->r; q.S = d->s;
+    q.sd = d->stride_d; q.sh = d->stride_h; q.sw = d->stride_w;
+    q.dil_d = d->dil_d; q.dil_h = d->dil_h; q.dil_w = d->dil_w;
+    q.pbd = d->pad_below_d; q.pbh = d->pad_below_h; q.pbw = d->pad_below_w;
+    // 128-wide tiles when they waste no more of a partial last tile than 64-wide ones
+    auto wide = [](int ch) { return ch > 64 && (ch + 127) / 128 * 128 <= (ch + 63) / 64 * 64; };
+    q.wk = wide(d->k) ? 2 : 1;
+    q.wc = wide(d->c) ? 2 : 1;
+    q.ktiles = (d->k + 64 * q.wk - 1) / (64 * q.wk);
+    q.ctiles = (d->c + 64 * q.wc - 1) / (64 * q.wc);
+    q.M = (uint32_t)((size_t)d->n * O * P * Q);
+    const uint32_t tiles = (uint32_t)q.ktiles * q.ctiles * taps;
+    q.sp = (taps > 1 || tiles >= 16) ? 64 : 128;         // the stage-size rule of the rank-2 layers
+    const char *fsp = getenv("NGC_WGG_SP");              // tests / benchmarks only
+    if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
+    const uint32_t slots = q.sp == 64 ? 2 * NUM_CUS3 : NUM_CUS3;
+    uint32_t parts = (slots + tiles - 1) / tiles;
+    if (tiles >= 64 && slots / tiles >= 1) parts = slots / tiles;
+    const uint32_t max_parts = (q.M + 127) / 128;
+    if (parts > max_parts) parts = max_parts;
+    if (parts < 1) parts = 1;
+    uint32_t chunk = (q.M + parts - 1) / parts;
+    chunk = (chunk + 127) / 128 * 128;
+    q.chunk = chunk;
+    q.nparts = (int)((q.M + chunk - 1) / chunk);
+    q.x_bytes = (uint32_t)x_bytes;
+    q.dy_bytes = (uint32_t)dy_bytes;
+    q.div_opq = make_fastdiv((uint32_t)(O * P * Q));
+    q.div_pq = make_fastdiv((uint32_t)(P * Q));
+    q.div_q = make_fastdiv((uint32_t)Q);
+    if (wp) *wp = q;
+    return true;
+}
+
+Variant3 pick3(const ngc_conv3d_desc *d, int op, ngc_conv_desc *r2)
+{
+    int O, P, Q;
+    if (validate3(d, &O, &P, &Q) != NGC_OK) return V3_INVALID;
+    if (op != NGC_OP_FWD && op != NGC_OP_BWD_DATA && op != NGC_OP_BWD_FILTERS) return V3_INVALID;
+    ngc_conv_desc t;
+    if (as_rank2(d, O, P, Q, &t)) {
+        if (r2) *r2 = t;
+        return V3_RANK2;
+    }
+    const int taps = d->t * d->r * d->s;
+    const bool direct_ok = d->w_layout == NGC_KCRS;
+    if (op == NGC_OP_FWD) {
+        const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD;
+        if (blocked_bf16_3(d) && wl && d->c % 32 == 0 && d->k % 64 == 0 && taps <= IGEMM_MAX_TAPS)
+            return d->k % 128 == 0 ? V3_IGEMM_128 : V3_IGEMM_64;
+        return direct_ok ? V3_DIRECT : V3_UNSUPPORTED;
+    }
+    if (op == NGC_OP_BWD_DATA) {
+        const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_BWD;
+        if (blocked_bf16_3(d) && wl && d->k % 32 == 0 && d->c % 64 == 0 && taps <= IGEMM_MAX_TAPS &&
+            d->stride_d * d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES)
+            return d->c % 128 == 0 ? V3_IGEMM_128 : V3_IGEMM_64;
+        return direct_ok ? V3_DIRECT : V3_UNSUPPORTED;
+    }
+    if (wgrad_gemm3_plan(d, O, P, Q, nullptr)) return V3_WGRAD_GEMM;
+    return V3_DIRECT;
+}
+
+size_t filter_elems3(const ngc_conv3d_desc *d, int layout)
+{
+    const size_t taps = (size_t)d->t * d->r * d->s;
+    if (layout == NGC_KCRS) return (size_t)d->k * d->c * taps;
+    if (layout == NGC_BLOCKED_FWD) return taps * ((d->c + 15) / 16) * d->k * 16;
+    if (layout == NGC_BLOCKED_BWD) return taps * ((d->k + 15) / 16) * d->c * 16;
+    return 0;
+}
+
+size_t workspace3(const ngc_conv3d_desc *d, int op, Variant3 v, const ngc_conv_desc *r2, int O, int P, int Q)
+{
+    if (v == V3_RANK2) return ngc_conv_workspace_bytes(r2, op);
+    if (v == V3_IGEMM_128 || v == V3_IGEMM_64) {
+        if (d->w_layout != NGC_KCRS) return 0;
+        return round256_3(filter_elems3(d, op == NGC_OP_FWD ? NGC_BLOCKED_FWD : NGC_BLOCKED_BWD) * 2);
+    }
+    if (v == V3_WGRAD_GEMM) {
+        WgradGemmParams wp;
+        if (!wgrad_gemm3_plan(d, O, P, Q, &wp)) return 0;
+        return round256_3((size_t)wp.nparts * d->t * d->r * d->s * wp.ktiles * wp.ctiles * wp.wk * wp.wc * 64 * 64 * sizeof(float));
+    }
+    return 0;
+}
+
+void fill_class3(IgemmClass &c, int oa_d, int oa_h, int oa_w, int OD, int OP, int OQ, int tap_begin, int tap_count, int N)
+{
+    c.oa_d = oa_d; c.oa_h = oa_h; c.oa_w = oa_w;
+    c.OD = OD; c.OP = OP; c.OQ = OQ;
+    c.tap_begin = tap_begin;
+    c.tap_count = tap_count;
+    const bool empty = OD <= 0 || OP <= 0 || OQ <= 0;
+    c.M = empty ? 0u : (uint32_t)((size_t)N * OD * OP * OQ);
+    c.div_opq = make_fastdiv(empty ? 1u : (uint32_t)(OD * OP * OQ));
+    c.div_pq = make_fastdiv(empty ? 1u : (uint32_t)(OP * OQ));
+    c.div_q = make_fastdiv(empty ? 1u : (uint32_t)OQ);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ngc_conv3d_out_shape(const ngc_conv3d_desc *desc, int32_t *o, int32_t *p, int32_t *q)
+{
+    if (!desc || !o || !p || !q) return NGC_BAD_ARG;
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    *o = O; *p = P; *q = Q;
+    return NGC_OK;
+}
+
+size_t ngc_conv3d_workspace_bytes(const ngc_conv3d_desc *desc, int op)
+{
+    int O, P, Q;
+    if (validate3(desc, &O, &P, &Q) != NGC_OK) return 0;
+    ngc_conv_desc r2;
+    const Variant3 v = pick3(desc, op, &r2);
+    if (v == V3_INVALID || v == V3_UNSUPPORTED) return 0;
+    return workspace3(desc, op, v, &r2, O, P, Q);
+}
+
+size_t ngc_conv3d_filter_elems(const ngc_conv3d_desc *desc, int32_t layout)
+{
+    int O, P, Q;
+    if (validate3(desc, &O, &P, &Q) != NGC_OK) return 0;
+    return filter_elems3(desc, layout);
+}
+
+size_t ngc_conv3d_data_elems(const ngc_conv3d_desc *desc, int which)
+{
+    int O, P, Q;
+    if (validate3(desc, &O, &P, &Q) != NGC_OK) return 0;
+    if (which == 0) return phys3(desc->x_layout, desc->n, desc->c, desc->d, desc->h, desc->w);
+    if (which == 1) return phys3(desc->y_layout, desc->n, desc->k, O, P, Q);
+    return 0;
+}
+
+int ngc_conv3d_filter_convert(const ngc_conv3d_desc *desc, const void *w_kctrs, void *w_blocked, int32_t dst_layout,
+                              void *hip_stream)
+{
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!w_kctrs || !w_blocked || (dst_layout != NGC_BLOCKED_FWD && dst_layout != NGC_BLOCKED_BWD)) return NGC_BAD_ARG;
+    if (!aligned16_3(w_kctrs) || !aligned16_3(w_blocked)) return NGC_BAD_ARG;
+    // the blocked layouts keep the taps outermost in (t, r, s) order: the rank-2 re-layout with T*R rows of S taps
+    return status3(launch_filter_convert(desc->dtype == NGC_BF16 ? 2 : 4, desc->k, desc->c, desc->t * desc->r, desc->s, w_kctrs,
+                                         w_blocked, dst_layout, static_cast<hipStream_t>(hip_stream)));
+}
+
+const char *ngc_conv3d_variant(const ngc_conv3d_desc *desc, int op)
+{
+    static thread_local char name[96];
+    ngc_conv_desc r2;
+    switch (pick3(desc, op, &r2)) {
+    case V3_RANK2: snprintf(name, sizeof(name), "rank2:%s", ngc_conv_variant(&r2, op)); return name;
+    case V3_IGEMM_128: return "igemm3_bf16_128x128";
+    case V3_IGEMM_64: return "igemm3_bf16_256x64";
+    case V3_WGRAD_GEMM: return "wgrad_gemm3_bf16";
+    case V3_DIRECT: return "direct3";
+    case V3_UNSUPPORTED: return "unsupported";
+    default: return "invalid";
+    }
+}
+
+int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, const float *bias, void *y, void *ws,
+                   size_t ws_bytes, void *hip_stream)
+{
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!x || !w || !y) return NGC_BAD_ARG;
+    if ((desc->epilogue & NGC_EPI_BIAS) && !bias) return NGC_BAD_ARG;
+    if (!aligned16_3(x) || !aligned16_3(w) || !aligned16_3(y) || !aligned16_3(ws) || !aligned16_3(bias)) return NGC_BAD_ARG;
+    ngc_conv_desc r2;
+    const Variant3 v = pick3(desc, NGC_OP_FWD, &r2);
+    if (v == V3_RANK2) return ngc_conv_fwd(&r2, x, w, bias, y, ws, ws_bytes, hip_stream);
+    if (v == V3_UNSUPPORTED) return NGC_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const float *b = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+    if (v == V3_DIRECT) return status3(launch_direct3_fwd(*desc, O, P, Q, x, w, b, y, st));
+
+    const size_t need = workspace3(desc, NGC_OP_FWD, v, nullptr, O, P, Q);
+    if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
+    const void *wt = w;
+    if (desc->w_layout == NGC_KCRS) {
+        const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->t * desc->r, desc->s, w, ws, NGC_BLOCKED_FWD, st);
+        if (e != hipSuccess) return status3(e);
+        wt = ws;
+    }
+    IgemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.in = static_cast<const uint16_t *>(x);
+    p.wt = static_cast<const uint16_t *>(wt);
+    p.out = static_cast<uint16_t *>(y);
+    p.bias = b;
+    p.N = desc->n; p.Cin = desc->c; p.Din = desc->d; p.Hin = desc->h; p.Win = desc->w;
+    p.Cout = desc->k; p.Dout = O; p.Hout = P; p.Wout = Q;
+    p.os_d = p.os_h = p.os_w = 1;
+    p.is_d = desc->stride_d; p.is_h = desc->stride_h; p.is_w = desc->stride_w;
+    p.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+    p.ncls = 1;
+    int n = 0;
+    for (int t = 0; t < desc->t; ++t)
+        for (int r = 0; r < desc->r; ++r)
+            for (int s = 0; s < desc->s; ++s) {
+                p.taps[n].dd = t * desc->dil_d - desc->pad_below_d;
+                p.taps[n].dh = r * desc->dil_h - desc->pad_below_h;
+                p.taps[n].dw = s * desc->dil_w - desc->pad_below_w;
+                p.taps[n].slab = n;
+                ++n;
+            }
+    fill_class3(p.cls[0], 0, 0, 0, O, P, Q, 0, n, desc->n);
+    return status3(launch_igemm3(p, v == V3_IGEMM_128 ? 128 : 64, p.cls[0].M, st));
+}
+
+int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
+                        void *hip_stream)
+{
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!dy || !w || !dx) return NGC_BAD_ARG;
+    if (!aligned16_3(dy) || !aligned16_3(w) || !aligned16_3(dx) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    ngc_conv_desc r2;
+    const Variant3 v = pick3(desc, NGC_OP_BWD_DATA, &r2);
+    if (v == V3_RANK2) return ngc_conv_bwd_data(&r2, dy, w, dx, ws, ws_bytes, hip_stream);
+    if (v == V3_UNSUPPORTED) return NGC_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V3_DIRECT) return status3(launch_direct3_bwd_data(*desc, O, P, Q, dy, w, dx, st));
+
+    const size_t need = workspace3(desc, NGC_OP_BWD_DATA, v, nullptr, O, P, Q);
+    if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
+    const void *wt = w;
+    if (desc->w_layout == NGC_KCRS) {
+        const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->t * desc->r, desc->s, w, ws, NGC_BLOCKED_BWD, st);
+        if (e != hipSuccess) return status3(e);
+        wt = ws;
+    }
+    IgemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.in = static_cast<const uint16_t *>(dy);
+    p.wt = static_cast<const uint16_t *>(wt);
+    p.out = static_cast<uint16_t *>(dx);
+    p.N = desc->n; p.Cin = desc->k; p.Din = O; p.Hin = P; p.Win = Q;
+    p.Cout = desc->c; p.Dout = desc->d; p.Hout = desc->h; p.Wout = desc->w;
+    const int sd = desc->stride_d, sh = desc->stride_h, sw = desc->stride_w;
+    p.os_d = sd; p.os_h = sh; p.os_w = sw;
+    p.is_d = p.is_h = p.is_w = 1;
+    p.ncls = sd * sh * sw;
+    // One class per residue (a, b, c) of the dx voxel modulo the strides: its taps are those with
+    // (a + pad_below - t dil) divisible by the stride on every axis, and the quotient is the offset into dy.
+    // A class without taps still runs and writes the zeros no window reaches.
+    int n = 0;
+    uint32_t max_m = 0;
+    auto lattice = [](int extent, int a, int stride) { return a < extent ? (extent - a + stride - 1) / stride : 0; };
+    auto hits = [](int v, int stride) { return ((v % stride) + stride) % stride == 0; };
+    for (int a = 0; a < sd; ++a)
+        for (int b = 0; b < sh; ++b)
+            for (int c = 0; c < sw; ++c) {
+                const int begin = n;
+                for (int t = 0; t < desc->t; ++t) {
+                    const int vd = a + desc->pad_below_d - t * desc->dil_d;
+                    if (!hits(vd, sd)) continue;
+                    for (int r = 0; r < desc->r; ++r) {
+                        const int vh = b + desc->pad_below_h - r * desc->dil_h;
+                        if (!hits(vh, sh)) continue;
+                        for (int s = 0; s < desc->s; ++s) {
+                            const int vw = c + desc->pad_below_w - s * desc->dil_w;
+                            if (!hits(vw, sw)) continue;
+                            p.taps[n].dd = vd / sd;              // exact
+                            p.taps[n].dh = vh / sh;
+                            p.taps[n].dw = vw / sw;
+                            p.taps[n].slab = (t * desc->r + r) * desc->s + s;
+                            ++n;
+                        }
+                    }
+                }
+                IgemmClass &cl = p.cls[(a * sh + b) * sw + c];
+                fill_class3(cl, a, b, c, lattice(desc->d, a, sd), lattice(desc->h, b, sh), lattice(desc->w, c, sw), begin,
+                            n - begin, desc->n);
+                if (cl.M > max_m) max_m = cl.M;
+            }
+    return status3(launch_igemm3(p, v == V3_IGEMM_128 ? 128 : 64, max_m, st));
+}
+
+int ngc_conv3d_bwd_filters(const ngc_conv3d_desc *desc, const void *x, const void *dy, float *dw, void *ws, size_t ws_bytes,
+                           void *hip_stream)
+{
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!x || !dy || !dw) return NGC_BAD_ARG;
+    if (!aligned16_3(x) || !aligned16_3(dy) || !aligned16_3(dw) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    ngc_conv_desc r2;
+    const Variant3 v = pick3(desc, NGC_OP_BWD_FILTERS, &r2);
+    if (v == V3_RANK2) return ngc_conv_bwd_filters(&r2, x, dy, dw, ws, ws_bytes, hip_stream);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V3_DIRECT) return status3(launch_direct3_bwd_filters(*desc, O, P, Q, x, dy, dw, st));
+    if (v != V3_WGRAD_GEMM) return NGC_UNSUPPORTED;
+    WgradGemmParams wp;
+    if (!wgrad_gemm3_plan(desc, O, P, Q, &wp)) return NGC_UNSUPPORTED;
+    const size_t need = workspace3(desc, NGC_OP_BWD_FILTERS, v, nullptr, O, P, Q);
+    if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    wp.x = static_cast<const uint16_t *>(x);
+    wp.dy = static_cast<const uint16_t *>(dy);
+    wp.partial = static_cast<float *>(ws);
+    wp.dw = dw;
+    return status3(launch_wgrad_gemm(wp, st));
+}
+
+}  // extern "C"

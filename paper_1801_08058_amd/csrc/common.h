@@ -192,19 +192,23 @@ struct LdsLimitOnce {
 // ---- implicit-GEMM (MFMA) forward / backprop-data: generalised gather convolution ----
 // out[n, co, i*os_h+oa_h, j*os_w+oa_w] = sum_{tap t in class} sum_ci
 //        in[n, ci, i*is_h + t.dh, j*is_w + t.dw] * wt[t.slab][ci/16][co][ci%16]
-constexpr int IGEMM_MAX_TAPS = 49;
+// Rank-3 spatial tensors [N][C/16][D][H][W][16] add a depth coordinate to every term (template flag R3 of the
+// kernel): input slice o*is_d + t.dd, output slice o*os_d + oa_d; rank-2 launches leave those fields 0 / 1.
+constexpr int IGEMM_MAX_TAPS = 64;
 constexpr int IGEMM_MAX_CLASSES = 16;
 
 struct IgemmTap {
-    int32_t dh, dw, slab;
+    int32_t dh, dw, slab, dd;
 };
 
 struct IgemmClass {
     int32_t oa_h, oa_w;        // output offset of the class inside the output-stride lattice
     int32_t OP, OQ;            // lattice extents of the class
     int32_t tap_begin, tap_count;
-    uint32_t M;                // N*OP*OQ
+    uint32_t M;                // N*OP*OQ (rank 3: N*OD*OP*OQ)
     FastDiv div_pq, div_q;     // divide by OP*OQ and by OQ
+    int32_t oa_d, OD;          // rank 3: depth offset and lattice extent of the class
+    FastDiv div_opq;           // rank 3: divide by OD*OP*OQ
 };
 
 struct IgemmParams {
@@ -215,6 +219,7 @@ struct IgemmParams {
     const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
     int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
     int32_t os_h, os_w, is_h, is_w;
+    int32_t Din, Dout, os_d, is_d;     // rank 3 only
     int32_t relu;
     int32_t ncls;
     IgemmClass cls[IGEMM_MAX_CLASSES];
@@ -343,6 +348,10 @@ struct WgradGemmParams {
     uint32_t M, chunk;         // N*P*Q, positions per part (multiple of 128)
     uint32_t x_bytes, dy_bytes;
     FastDiv div_pq, div_q;
+    // rank-3 spatial tensors (r3 != 0): x [N][C/16][D][H][W][16], dy [N][K/16][O][P][Q][16], dw [K][C][T][R][S],
+    // M = N*O*P*Q, taps = T*R*S
+    int32_t r3, D, O, T, sd, dil_d, pbd;
+    FastDiv div_opq;           // divide by O*P*Q
 };
 
 // ---- one-tap (1x1) forward / backprop-data as a pipelined GEMM ----
@@ -381,6 +390,7 @@ __device__ __forceinline__ void wg_barrier_nofence()
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st);
 hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);
+hipError_t launch_igemm3(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);    // rank-3 spatial
 hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st);
 
 // up to 4 launches of the strip kernel (blocked output, same Cout) in one grid
@@ -402,6 +412,12 @@ hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x
                              const float *bias, void *y, hipStream_t st);
 hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w,
                                   const void *mask, void *dx, hipStream_t st);
+hipError_t launch_direct3_fwd(const ngc_conv3d_desc &d, int O, int P, int Q, const void *x, const void *w, const float *bias,
+                              void *y, hipStream_t st);
+hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, void *dx,
+                                   hipStream_t st);
+hipError_t launch_direct3_bwd_filters(const ngc_conv3d_desc &d, int O, int P, int Q, const void *x, const void *dy, float *dw,
+                                      hipStream_t st);
 int gemm1x1_dbp_tile_m(const Gemm1x1Params &p);
 int softmax_vectors(int dtype, int cols, bool bwd, bool aligned);
 hipError_t launch_softmax(int dtype, bool bwd, const void *a, const void *b, void *out, uint32_t rows, int cols, int V,

@@ -41,6 +41,8 @@ namespace ngc {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+static_assert(sizeof(IgemmParams) <= 4096, "kernel arguments are passed by value: at most 4 KB");
+
 template <int BM, int BN>
 struct IgemmCfg {
     static constexpr int WM = BM / 64;                  // waves along positions
@@ -53,7 +55,9 @@ struct IgemmCfg {
     static_assert(WM * WN == 4, "4 waves per workgroup");
 };
 
-template <int BM, int BN>
+// R3: rank-3 spatial tensors [N][C/16][D][H][W][16]; positions are (n, o, i, j) and every tap carries a
+// depth offset as well.
+template <int BM, int BN, bool R3>
 __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
 {
     using Cfg = IgemmCfg<BM, BN>;
@@ -74,23 +78,33 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
 
     const int CBin = p.Cin >> 4;
     const int HWin = p.Hin * p.Win;
+    const int DHWin = R3 ? p.Din * HWin : HWin;          // pixel blocks per 16-channel plane of an image
 
     // ---- gather bookkeeping: this thread loads position rows (tid/2 + 128 e), half g = tid&1
     const int ldg = tid & 1;
-    int ld_ih0[Cfg::XE], ld_iw0[Cfg::XE], ld_base[Cfg::XE];
+    int ld_ih0[Cfg::XE], ld_iw0[Cfg::XE], ld_base[Cfg::XE], ld_id0[Cfg::XE];
     bool ld_ok[Cfg::XE];
 #pragma unroll
     for (int e = 0; e < Cfg::XE; ++e) {
         const uint32_t m = m0 + (tid >> 1) + 128 * e;
         ld_ok[e] = m < cl.M;
         const uint32_t mm = ld_ok[e] ? m : 0;
-        const uint32_t n = fd_div(mm, cl.div_pq);
-        const uint32_t rem = mm - n * cl.div_pq.d;
+        uint32_t n, rem, o = 0;
+        if constexpr (R3) {
+            n = fd_div(mm, cl.div_opq);
+            const uint32_t rem3 = mm - n * cl.div_opq.d;
+            o = fd_div(rem3, cl.div_pq);
+            rem = rem3 - o * cl.div_pq.d;
+        } else {
+            n = fd_div(mm, cl.div_pq);
+            rem = mm - n * cl.div_pq.d;
+        }
         const uint32_t i = fd_div(rem, cl.div_q);
         const uint32_t j = rem - i * cl.div_q.d;
         ld_ih0[e] = (int)i * p.is_h;
         ld_iw0[e] = (int)j * p.is_w;
-        ld_base[e] = (int)n * CBin * HWin;               // in units of 16-channel pixel blocks
+        ld_id0[e] = R3 ? (int)o * p.is_d : 0;
+        ld_base[e] = (int)n * CBin * DHWin;              // in units of 16-channel pixel blocks
     }
     // filter units: unit q = tid + 256 u -> g = q&1, row = (q/2) % BN, cbi = (q/2) / BN
     const int w_row = (tid >> 1) % BN;
@@ -108,12 +122,18 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
         for (int e = 0; e < Cfg::XE; ++e) {
             const int ih = ld_ih0[e] + tp.dh;
             const int iw = ld_iw0[e] + tp.dw;
-            const bool ok = ld_ok[e] && (unsigned)ih < (unsigned)p.Hin && (unsigned)iw < (unsigned)p.Win;
+            bool ok = ld_ok[e] && (unsigned)ih < (unsigned)p.Hin && (unsigned)iw < (unsigned)p.Win;
+            int slice = 0;
+            if constexpr (R3) {
+                const int id = ld_id0[e] + tp.dd;
+                ok = ok && (unsigned)id < (unsigned)p.Din;
+                slice = id * HWin;
+            }
 #pragma unroll
             for (int cbi = 0; cbi < 2; ++cbi) {
                 uint4 v = make_uint4(0, 0, 0, 0);
                 if (ok) {
-                    const size_t blk = (size_t)(ld_base[e] + (c32 * 2 + cbi) * HWin + ih * p.Win + iw);
+                    const size_t blk = (size_t)(ld_base[e] + (c32 * 2 + cbi) * DHWin + slice + ih * p.Win + iw);
                     v = *reinterpret_cast<const uint4 *>(p.in + blk * 16 + ldg * 8);
                 }
                 xr[e][cbi] = v;
@@ -189,19 +209,29 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
 
     // ---- epilogue: bias, ReLU, one RNE rounding, 16-byte stores into the blocked output
     const int CBout = p.Cout >> 4;
-    const int HWout = p.Hout * p.Wout;
+    const int HWplane = p.Hout * p.Wout;
+    const int HWout = R3 ? p.Dout * HWplane : HWplane;   // pixel blocks per 16-channel plane of an image
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const uint32_t m = m0 + wm * 64 + b * 32 + l32;
         const bool ok = m < cl.M;
         const uint32_t mm = ok ? m : 0;
-        const uint32_t n = fd_div(mm, cl.div_pq);
-        const uint32_t rem = mm - n * cl.div_pq.d;
+        uint32_t n, rem, o = 0;
+        if constexpr (R3) {
+            n = fd_div(mm, cl.div_opq);
+            const uint32_t rem3 = mm - n * cl.div_opq.d;
+            o = fd_div(rem3, cl.div_pq);
+            rem = rem3 - o * cl.div_pq.d;
+        } else {
+            n = fd_div(mm, cl.div_pq);
+            rem = mm - n * cl.div_pq.d;
+        }
         const uint32_t i = fd_div(rem, cl.div_q);
         const uint32_t j = rem - i * cl.div_q.d;
         const int oh = (int)i * p.os_h + cl.oa_h;
         const int ow = (int)j * p.os_w + cl.oa_w;
-        const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + ow;
+        size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + ow;
+        if constexpr (R3) pix += (size_t)((int)o * p.os_d + cl.oa_d) * HWplane;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             const int co_base = n0 + wn * 64 + a * 32;     // first output channel of this 32-row fragment
@@ -236,16 +266,27 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
     }
 }
 
-hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st)
+template <bool R3>
+static hipError_t launch_igemm_r(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st)
 {
     if (bn == 128) {
         dim3 grid((max_m + 127) / 128, p.Cout / 128, p.ncls);
-        NGC_LAUNCH((igemm_bf16<128, 128>), grid, dim3(256), 0, st, p);
+        NGC_LAUNCH((igemm_bf16<128, 128, R3>), grid, dim3(256), 0, st, p);
     } else {
         dim3 grid((max_m + 255) / 256, p.Cout / 64, p.ncls);
-        NGC_LAUNCH((igemm_bf16<256, 64>), grid, dim3(256), 0, st, p);
+        NGC_LAUNCH((igemm_bf16<256, 64, R3>), grid, dim3(256), 0, st, p);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st)
+{
+    return launch_igemm_r<false>(p, bn, max_m, st);
+}
+
+hipError_t launch_igemm3(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st)
+{
+    return launch_igemm_r<true>(p, bn, max_m, st);
 }
 
 }  // namespace ngc

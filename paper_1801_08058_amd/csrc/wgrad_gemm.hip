@@ -52,10 +52,12 @@ __device__ __forceinline__ bf16x8 nchw_frag_g(const unsigned char *lo)
 }
 
 // SP = positions per stage (128, or 64: half the LDS, two workgroups per compute unit);
-// XN / DN: x / dy is an NCHW tensor (else 16-channel blocked)
-template <int WK, int WC, int SP, bool XN, bool DN>
+// XN / DN: x / dy is an NCHW tensor (else 16-channel blocked); R3: rank-3 spatial tensors (blocked), positions
+// (n, o, p, q) and taps (t, r, s)
+template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false>
 __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 {
+    static_assert(!(R3 && (XN || DN)), "rank-3 tensors are read blocked");
     constexpr int NW = 8;
     constexpr int NH = NW / (WK * WC);
     constexpr int NPL = 4 * (WK + WC);            // 16-channel planes per stage: dy first, then x
@@ -81,7 +83,13 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     const int kt = blockIdx.y / p.ctiles;
     const int ct = blockIdx.y - kt * p.ctiles;
     const int tap = blockIdx.z;
-    const int tr = tap / p.S, ts = tap - tr * p.S;
+    int tap2 = tap, dd_off = 0;
+    if constexpr (R3) {
+        const int tt = tap / (p.R * p.S);
+        tap2 = tap - tt * (p.R * p.S);
+        dd_off = tt * p.dil_d - p.pbd;
+    }
+    const int tr = tap2 / p.S, ts = tap2 - tr * p.S;
     const int dh_off = tr * p.dil_h - p.pbh;
     const int dw_off = ts * p.dil_w - p.pbw;
 
@@ -89,8 +97,8 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     const uint32_t m_end = (m_begin + p.chunk < p.M) ? m_begin + p.chunk : p.M;
     const int nstages = (m_begin < m_end) ? (int)((m_end - m_begin + WGG_SP - 1) / WGG_SP) : 0;
 
-    const int PQ = p.P * p.Q;
-    const int HW = p.H * p.W;
+    const int PQ = R3 ? p.O * p.P * p.Q : p.P * p.Q;     // positions / pixels per 16-channel plane of an image
+    const int HW = R3 ? p.D * p.H * p.W : p.H * p.W;
     const int KB = p.K >> 4, CB = p.C >> 4;
     const int kb0 = kt * 4 * WK, cb0 = ct * 4 * WC;
 
@@ -105,16 +113,30 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
         const uint32_t m = m_begin + (uint32_t)(s * WGG_SP + my_blk * 32 + (lane >> 1));
         const bool in = m < m_end;
         const uint32_t mm = in ? m : 0;
-        const uint32_t n = fd_div(mm, p.div_pq);
-        const uint32_t rem = mm - n * p.div_pq.d;
-        const uint32_t pp = fd_div(rem, p.div_q);
-        const uint32_t qq = rem - pp * p.div_q.d;
+        uint32_t n, rem, rem2;
+        int slice = 0;                                                   // first pixel of the depth slice read
+        bool zin = true;
+        if constexpr (R3) {
+            n = fd_div(mm, p.div_opq);
+            rem = mm - n * p.div_opq.d;
+            const uint32_t o = fd_div(rem, p.div_pq);
+            rem2 = rem - o * p.div_pq.d;
+            const int z = (int)o * p.sd + dd_off;
+            zin = (unsigned)z < (unsigned)p.D;
+            slice = z * p.H * p.W;
+        } else {
+            n = fd_div(mm, p.div_pq);
+            rem = mm - n * p.div_pq.d;
+            rem2 = rem;
+        }
+        const uint32_t pp = fd_div(rem2, p.div_q);
+        const uint32_t qq = rem2 - pp * p.div_q.d;
         const int h = (int)pp * p.sh + dh_off;
         const int w = (int)qq * p.sw + dw_off;
-        const bool xin = in && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
+        const bool xin = in && zin && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W;
         const unsigned half = (lane & 1) * 16;
         const unsigned dy_off = (unsigned)(((n * KB + kb0) * PQ + rem) * 32) + half;
-        const unsigned x_off = (unsigned)(((n * CB + cb0) * HW + h * p.W + w) * 32) + half;
+        const unsigned x_off = (unsigned)(((n * CB + cb0) * HW + slice + h * p.W + w) * 32) + half;
         // NCHW operands: lane = channel (lane / 2) % 16 of the plane, positions 16 (lane / 32) + 8 (lane % 2) + 0..7
         // of the block (one tap, stride 1, no padding: the input pixel is the output position)
         bool inn = false;
@@ -275,24 +297,30 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
     }
 }
 
-template <int WK, int WC, int SP, bool XN, bool DN>
+static int wgrad_gemm_taps(const WgradGemmParams &p) { return (p.r3 ? p.T : 1) * p.R * p.S; }
+
+template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false>
 static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;                  // per template instantiation
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3>));
         if (e != hipSuccess) return e;
     }
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
-    dim3 grid(p.nparts, p.ktiles * p.ctiles, p.R * p.S);
-    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN>), grid, dim3(512), lds, st, p);
+    dim3 grid(p.nparts, p.ktiles * p.ctiles, wgrad_gemm_taps(p));
+    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
 }
 
 template <int WK, int WC, int SP>
 static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
 {
+    if (p.r3) {
+        if (p.x_nchw || p.dy_nchw) return hipErrorInvalidValue;
+        return launch_wgrad_gemm_l<WK, WC, SP, false, false, true>(p, st);
+    }
     if (p.x_nchw && p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, true>(p, st);
     if (p.x_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, false>(p, st);
     if (p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, false, true>(p, st);
@@ -313,9 +341,10 @@ hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
 {
     const hipError_t e = p.sp == 64 ? launch_wgrad_gemm_sp<64>(p, st) : launch_wgrad_gemm_sp<128>(p, st);
     if (e != hipSuccess) return e;
-    const size_t per4 = (size_t)p.R * p.S * p.ktiles * p.ctiles * p.wk * p.wc * (64 * 64 / 4);
+    const int taps = wgrad_gemm_taps(p);
+    const size_t per4 = (size_t)taps * p.ktiles * p.ctiles * p.wk * p.wc * (64 * 64 / 4);
     NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
-               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.R * p.S, p.ktiles, p.ctiles, p.wk, p.wc);
+               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
     return hipGetLastError();
 }
 

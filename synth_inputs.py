@@ -318,3 +318,88 @@ def layer_tensors(L: ConvLayer, which=("x", "w", "bias", "dy")) -> Dict[str, np.
             if name in out:
                 out[name] = bf16_bits_to_f32(f32_to_bf16_bits(out[name]))
     return out
+
+
+# ---------------------------------------------------------------- convolution over three spatial axes
+@dataclass
+class Conv3dLayer:
+    """One convolution layer over (D, H, W), logical NCDHW axes; per-axis attributes as (d, h, w) triples."""
+    name: str
+    n: int
+    c: int
+    d: int
+    h: int
+    w: int
+    k: int
+    t: int
+    r: int
+    s: int
+    strides: Tuple[int, int, int] = (1, 1, 1)
+    dilation: Tuple[int, int, int] = (1, 1, 1)
+    pad_below: Tuple[int, int, int] = (0, 0, 0)
+    pad_above: Tuple[int, int, int] = (0, 0, 0)
+    dtype: str = "bf16"
+    bias_relu: bool = True
+    x_dist: Tuple = ("normal", 0.0, 1.0)
+    dy_dist: Tuple = ("normal", 0.0, 0.1)
+    w_dist: Tuple = ("he",)
+    seed: int = 0
+    count: int = 1
+
+    @property
+    def attrs21(self) -> Tuple[int, ...]:
+        """(n, c, d, h, w, k, t, r, s, strides, dilation, pad below, pad above): the constant attributes of the node."""
+        return (self.n, self.c, self.d, self.h, self.w, self.k, self.t, self.r, self.s, *self.strides, *self.dilation,
+                *self.pad_below, *self.pad_above)
+
+    @property
+    def opq(self) -> Tuple[int, int, int]:
+        ext, taps = (self.d, self.h, self.w), (self.t, self.r, self.s)
+        return tuple((ext[i] + self.pad_below[i] + self.pad_above[i] - self.dilation[i] * (taps[i] - 1) - 1) // self.strides[i] + 1
+                     for i in range(3))
+
+    @property
+    def flop_per_op(self) -> float:
+        o, p, q = self.opq
+        return 2.0 * self.n * self.k * o * p * q * self.c * self.t * self.r * self.s
+
+
+def video_layers(n: int | None = None, scale: int = 1) -> List[Conv3dLayer]:
+    """Configuration 7: layers in the shapes of video networks on 16-frame clips (full 3x3x3 windows,
+    a strided 3x3x3, the 1x3x3 + 3x1x1 pair of factorised space / time blocks, a 1x1x1 projection) and
+    one layer with per-axis strides, dilation and one-sided padding.  `scale` divides the clip length and
+    the image sides (tests that want the same recipe at a size the oracle finishes in seconds)."""
+    n = n or 8
+    f = lambda v: max(v // scale, 3)
+    mk = lambda i, name, **kw: Conv3dLayer(name, n, seed=BASE_SEED + 7 + 1000 * i, **kw)
+    return [
+        mk(0, "v_3x3x3_c64k128", c=64, d=f(16), h=f(56), w=f(56), k=128, t=3, r=3, s=3, pad_below=(1, 1, 1), pad_above=(1, 1, 1)),
+        mk(1, "v_3x3x3_c128k256", c=128, d=f(8), h=f(28), w=f(28), k=256, t=3, r=3, s=3, pad_below=(1, 1, 1), pad_above=(1, 1, 1)),
+        mk(2, "v_3x3x3_s2_c128", c=128, d=f(8), h=f(28), w=f(28), k=128, t=3, r=3, s=3, strides=(2, 2, 2),
+           pad_below=(1, 1, 1), pad_above=(1, 1, 1)),
+        mk(3, "v_1x3x3_c64k128", c=64, d=f(16), h=f(56), w=f(56), k=128, t=1, r=3, s=3, pad_below=(0, 1, 1), pad_above=(0, 1, 1)),
+        mk(4, "v_3x1x1_c128k64", c=128, d=f(16), h=f(56), w=f(56), k=64, t=3, r=1, s=1, pad_below=(1, 0, 0), pad_above=(1, 0, 0)),
+        mk(5, "v_1x1x1_c256k64", c=256, d=f(8), h=f(28), w=f(28), k=64, t=1, r=1, s=1, bias_relu=False),
+        mk(6, "v_3x3x3_general", c=64, d=f(8), h=f(20), w=f(24), k=64, t=3, r=3, s=3, strides=(1, 2, 1), dilation=(2, 1, 2),
+           pad_below=(2, 0, 1), pad_above=(1, 1, 3)),
+    ]
+
+
+def layer3_tensors(L: Conv3dLayer, which=("x", "w", "bias", "dy")) -> Dict[str, np.ndarray]:
+    """Synthetic tensors of a layer, logical NCDHW / KCTRS axis order, fp32 arrays; for bf16 layers x, w and dy
+    hold values exactly representable in bf16 (rounded once here)."""
+    out: Dict[str, np.ndarray] = {}
+    fan_in = L.c * L.t * L.r * L.s
+    if "x" in which:
+        out["x"] = _draw(L.x_dist, L.seed, TENSOR_X, (L.n, L.c, L.d, L.h, L.w), fan_in)
+    if "w" in which:
+        out["w"] = _draw(L.w_dist, L.seed, TENSOR_W, (L.k, L.c, L.t, L.r, L.s), fan_in)
+    if "bias" in which:
+        out["bias"] = uniform(L.seed, TENSOR_BIAS, (L.k,), -0.1, 0.1)
+    if "dy" in which:
+        out["dy"] = _draw(L.dy_dist, L.seed, TENSOR_DY, (L.n, L.k, *L.opq), fan_in)
+    if L.dtype == "bf16":
+        for name in ("x", "w", "dy"):
+            if name in out:
+                out[name] = bf16_bits_to_f32(f32_to_bf16_bits(out[name]))
+    return out

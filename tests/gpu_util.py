@@ -197,3 +197,90 @@ class Run:
         torch.cuda.synchronize()
         self.last_desc, self.last_raw = d, dw
         return dw.cpu().numpy().astype(np.float64).reshape(a.k, a.c, a.r, a.s)
+
+
+# ---------------------------------------------------------------- convolution over three spatial axes
+def attrs3_of(L: synth_inputs.Conv3dLayer) -> oracle.Attrs3:
+    return oracle.Attrs3(*L.attrs21)
+
+
+def desc3_of(a: oracle.Attrs3, dtype: str, x_layout, y_layout, w_layout=ng.NGC_KCRS, epilogue=ng.NGC_EPI_NONE):
+    return ng.make_desc3(a.n, a.c, a.d, a.h, a.w, a.k, a.t, a.r, a.s, (a.sd, a.sh, a.sw), (a.dd, a.dh, a.dw),
+                         (a.pbd, a.pbh, a.pbw), (a.pad, a.pah, a.paw), ng.NGC_F32 if dtype == "f32" else ng.NGC_BF16,
+                         x_layout, y_layout, w_layout, epilogue)
+
+
+def data3_to_device(values_f32: np.ndarray, dtype: str, layout: int) -> torch.Tensor:
+    """[N,C,D,H,W] host values -> device tensor in `layout`; both layouts keep (d, h, w) contiguous, so the
+    rank-2 permutation with D*H rows is the rank-3 one."""
+    n, c, d, h, w = values_f32.shape
+    return data_to_device(values_f32.reshape(n, c, d * h, w), dtype, layout)
+
+
+def data3_from_device(t: torch.Tensor, dtype: str, layout: int, shape) -> np.ndarray:
+    n, c, d, h, w = shape
+    return data_from_device(t, dtype, layout, (n, c, d * h, w)).reshape(n, c, d, h, w)
+
+
+def poisoned(nelem: int, dtype: str) -> torch.Tensor:
+    t = torch.empty(nelem, dtype=torch.float32 if dtype == "f32" else torch.int16, device="cuda")
+    t.fill_(float("nan") if dtype == "f32" else 0x7FC0)
+    return t
+
+
+class Run3:
+    """Runs the three ops of one rank-3 layer through the C ABI and returns fp64 results."""
+
+    def __init__(self, a: oracle.Attrs3, dtype: str, x_layout: int, y_layout: int, pre_block_filters: bool = False):
+        self.a, self.dtype, self.xl, self.yl, self.pre = a, dtype, x_layout, y_layout, pre_block_filters
+        self.O, self.P, self.Q = oracle.out_shape3(a)
+
+    def _ws(self, d, op):
+        nbytes = ng.ngc_conv3d_workspace_bytes(d, op)
+        return torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+
+    def _filter(self, w_f32, layout):
+        """Filters through ngc_conv3d_filter_convert when asked for and a kernel takes them, else [K][C][T][R][S]."""
+        wd = dev(encode(w_f32, self.dtype))
+        op = ng.NGC_OP_FWD if layout == ng.NGC_BLOCKED_FWD else ng.NGC_OP_BWD_DATA
+        d = desc3_of(self.a, self.dtype, self.xl, self.yl, layout)
+        if self.pre and self.dtype == "bf16" and "unsupported" not in ng.ngc_conv3d_variant(d, op):
+            wb = torch.empty(ng.ngc_conv3d_filter_elems(d, layout), dtype=torch.int16, device="cuda")
+            ng.ngc_conv3d_filter_convert(d, wd, wb, layout, stream())
+            return wb, layout
+        return wd, ng.NGC_KCRS
+
+    def fwd(self, x, w, bias=None, relu=False):
+        a = self.a
+        epi = (ng.NGC_EPI_BIAS if bias is not None else 0) | (ng.NGC_EPI_RELU if relu else 0)
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_FWD)
+        d = desc3_of(a, self.dtype, self.xl, self.yl, wl, epi)
+        xd = data3_to_device(x, self.dtype, self.xl)
+        bd = dev(np.asarray(bias, dtype=np.float32)) if bias is not None else None
+        y = poisoned(ng.ngc_conv3d_data_elems(d, 1), self.dtype)
+        ng.ngc_conv3d_fwd(d, xd, wd, bd, y, self._ws(d, ng.NGC_OP_FWD), stream())
+        torch.cuda.synchronize()
+        self.last_desc = d
+        return data3_from_device(y, self.dtype, self.yl, (a.n, a.k, self.O, self.P, self.Q))
+
+    def bwd_data(self, dy, w):
+        a = self.a
+        wd, wl = self._filter(w, ng.NGC_BLOCKED_BWD)
+        d = desc3_of(a, self.dtype, self.xl, self.yl, wl)
+        dyd = data3_to_device(dy, self.dtype, self.yl)
+        dx = poisoned(ng.ngc_conv3d_data_elems(d, 0), self.dtype)
+        ng.ngc_conv3d_bwd_data(d, dyd, wd, dx, self._ws(d, ng.NGC_OP_BWD_DATA), stream())
+        torch.cuda.synchronize()
+        self.last_desc = d
+        return data3_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.d, a.h, a.w))
+
+    def bwd_filters(self, x, dy):
+        a = self.a
+        d = desc3_of(a, self.dtype, self.xl, self.yl)
+        xd = data3_to_device(x, self.dtype, self.xl)
+        dyd = data3_to_device(dy, self.dtype, self.yl)
+        dw = torch.full((a.k * a.c * a.t * a.r * a.s,), float("nan"), dtype=torch.float32, device="cuda")
+        ng.ngc_conv3d_bwd_filters(d, xd, dyd, dw, self._ws(d, ng.NGC_OP_BWD_FILTERS), stream())
+        torch.cuda.synchronize()
+        self.last_desc = d
+        return dw.cpu().numpy().astype(np.float64).reshape(a.k, a.c, a.t, a.r, a.s)

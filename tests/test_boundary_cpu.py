@@ -26,7 +26,7 @@ def _good(**kw):
 def test_library_exports_every_declared_symbol():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(ngc_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(ngc_[a-z0-9_]+)\s*\(", text))
     assert declared == set(ng.EXPORTS), declared ^ set(ng.EXPORTS)
     lib = ctypes.CDLL(ng.LIB_PATH)
     for name in declared:
@@ -236,3 +236,101 @@ int main() {
                                os.path.join(ROOT, "paper_1801_08058_amd", "csrc"), "-o", exe, cpp],
                               stderr=subprocess.DEVNULL)
         assert subprocess.run([exe], capture_output=True, text=True).stdout.strip() == "0"
+
+
+# ---------------------------------------------------------------- convolution over three spatial axes
+def _good3(**kw):
+    base = dict(n=2, c=64, d=6, h=10, w=10, k=64, t=3, r=3, s=3, pad_below=(1, 1, 1), pad_above=(1, 1, 1))
+    base.update(kw)
+    return ng.make_desc3(**base)
+
+
+def test_conv3d_struct_matches_header():
+    body = re.search(r"typedef struct \{((?:(?!typedef struct).)*?)\} ngc_conv3d_desc;", open(HEADER).read(), re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = [n.strip() for f in re.findall(r"int32_t\s+([a-z_, ]+);", body) for n in f.split(",")]
+    assert names == [n for n, _ in ng.ngc_conv3d_desc._fields_]
+    assert ctypes.sizeof(ng.ngc_conv3d_desc) == 4 * len(names)
+
+
+def test_conv3d_out_shape_matches_oracle():
+    rng = np.random.default_rng(33)
+    for _ in range(200):
+        ext = [int(v) for v in rng.integers(1, 20, 3)]
+        taps = [int(v) for v in rng.integers(1, 6, 3)]
+        st = [int(v) for v in rng.integers(1, 4, 3)]
+        dil = [int(v) for v in rng.integers(1, 4, 3)]
+        pb = [int(v) for v in rng.integers(0, 4, 3)]
+        pa = [int(v) for v in rng.integers(0, 4, 3)]
+        a = oracle.Attrs3(1, 3, *ext, 4, *taps, *st, *dil, *pb, *pa)
+        want = oracle.out_shape3(a)
+        got = ng.ngc_conv3d_out_shape(ng.make_desc3(1, 3, *ext, 4, *taps, st, dil, pb, pa), check=False)
+        assert got == (ng.NGC_BAD_SHAPE if min(want) < 1 else want)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d=0), ng.NGC_BAD_SHAPE), (dict(t=0), ng.NGC_BAD_SHAPE), (dict(stride=(1, 0, 1)), ng.NGC_BAD_SHAPE),
+    (dict(dilation=(0, 1, 1)), ng.NGC_BAD_SHAPE), (dict(pad_below=(-1, 0, 0)), ng.NGC_BAD_SHAPE),
+    (dict(d=2, t=5, pad_below=(0, 1, 1), pad_above=(0, 1, 1)), ng.NGC_BAD_SHAPE), (dict(dtype=7), ng.NGC_BAD_ARG),
+    (dict(x_layout=3), ng.NGC_BAD_ARG), (dict(w_layout=9), ng.NGC_BAD_ARG), (dict(epilogue=8), ng.NGC_BAD_ARG),
+    (dict(n=4096, c=1024, d=64, h=64, w=64), ng.NGC_BAD_SHAPE),
+])
+def test_conv3d_invalid_descriptors_are_rejected_before_launch(kw, status):
+    d = _good3(**kw)
+    assert ng.ngc_conv3d_out_shape(d, check=False) == status
+    assert ng.ngc_conv3d_workspace_bytes(d, ng.NGC_OP_FWD) == 0
+    assert ng.ngc_conv3d_variant(d, ng.NGC_OP_FWD) == "invalid"
+    # non-null, aligned dummies: validation must fail before anything could touch them
+    assert ng.ngc_conv3d_fwd(d, 4096, 4096, None, 4096, None, check=False) == status
+    assert ng.ngc_conv3d_bwd_data(d, 4096, 4096, 4096, None, check=False) == status
+    assert ng.ngc_conv3d_bwd_filters(d, 4096, 4096, 4096, None, check=False) == status
+
+
+def test_conv3d_null_pointers_bias_and_workspace():
+    d = _good3(epilogue=ng.NGC_EPI_BIAS)
+    assert ng.ngc_conv3d_fwd(d, None, 4096, 4096, 4096, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_conv3d_fwd(d, 4096, 4096, None, 4096, None, check=False) == ng.NGC_BAD_ARG      # bias flag without bias
+    assert ng.ngc_conv3d_fwd(d, 4096, 4100, 4096, 4096, None, check=False) == ng.NGC_BAD_ARG      # misaligned
+    d = _good3()
+    assert ng.ngc_conv3d_workspace_bytes(d, ng.NGC_OP_FWD) > 0                                    # filter re-layout
+    assert ng.ngc_conv3d_fwd(d, 4096, 4096, None, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv3d_bwd_data(d, 4096, 4096, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv3d_bwd_filters(d, 4096, 4096, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv3d_filter_convert(d, 4096, 4096, ng.NGC_KCRS, check=False) == ng.NGC_BAD_ARG
+
+
+def test_conv3d_kernel_selection_and_sizes():
+    F, B, W = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS
+    d = _good3()
+    assert [ng.ngc_conv3d_variant(d, op) for op in (F, B, W)] == ["igemm3_bf16_256x64", "igemm3_bf16_256x64", "wgrad_gemm3_bf16"]
+    d = _good3(c=128, k=128)
+    assert [ng.ngc_conv3d_variant(d, op) for op in (F, B)] == ["igemm3_bf16_128x128"] * 2
+    # pre-blocked filters: no workspace for forward / backprop-data
+    assert ng.ngc_conv3d_workspace_bytes(_good3(w_layout=ng.NGC_BLOCKED_FWD), F) == 0
+    assert ng.ngc_conv3d_workspace_bytes(_good3(w_layout=ng.NGC_BLOCKED_BWD), B) == 0
+    assert ng.ngc_conv3d_workspace_bytes(d, F) == 27 * 128 * 128 * 2
+    # windows over one group of adjacent axes go to the rank-2 kernels
+    t = _good3(t=3, r=1, s=1, pad_below=(1, 0, 0), pad_above=(1, 0, 0))
+    assert ng.ngc_conv3d_variant(t, F).startswith("rank2:") and "unsupported" not in ng.ngc_conv3d_variant(t, F)
+    p = _good3(t=1, r=1, s=1, pad_below=(0, 0, 0), pad_above=(0, 0, 0))
+    assert ng.ngc_conv3d_variant(p, F) == "rank2:gemm1x1_bf16" and ng.ngc_conv3d_variant(p, W).startswith("rank2:wgrad_gemm")
+    s_ = _good3(t=1, r=1, s=5, pad_below=(0, 0, 2), pad_above=(0, 0, 2))
+    assert ng.ngc_conv3d_variant(s_, B).startswith("rank2:")
+    assert ng.ngc_conv3d_workspace_bytes(t, F) == ng.ngc_conv_workspace_bytes(
+        ng.make_desc(2, 64, 6, 100, 64, 3, 1, pad_below=(1, 0), pad_above=(1, 0)), F)
+    # a 1x3x3 window keeps the depth axis: rank-3 kernels
+    assert ng.ngc_conv3d_variant(_good3(t=1, pad_below=(0, 1, 1), pad_above=(0, 1, 1)), F).startswith("igemm3")
+    # fp32, NCDHW and odd channel counts: direct kernels; blocked filters without an MFMA kernel: unsupported
+    assert ng.ngc_conv3d_variant(_good3(dtype=ng.NGC_F32), F) == "direct3"
+    assert ng.ngc_conv3d_variant(_good3(x_layout=ng.NGC_NCHW), B) == "direct3"
+    assert ng.ngc_conv3d_variant(_good3(c=20), W) == "direct3"
+    assert ng.ngc_conv3d_variant(_good3(c=20, w_layout=ng.NGC_BLOCKED_FWD), F) == "unsupported"
+    assert ng.ngc_conv3d_fwd(_good3(c=20, w_layout=ng.NGC_BLOCKED_FWD), 4096, 4096, None, 4096, None, check=False) == ng.NGC_UNSUPPORTED
+    # more classes than the gather kernel holds
+    assert ng.ngc_conv3d_variant(_good3(stride=(3, 3, 2)), B) == "direct3"
+    # element counts
+    d = _good3(c=20, k=7)
+    assert ng.ngc_conv3d_data_elems(d, 0) == 2 * 32 * 6 * 10 * 10 and ng.ngc_conv3d_data_elems(d, 1) == 2 * 16 * 6 * 10 * 10
+    assert ng.ngc_conv3d_filter_elems(d, ng.NGC_KCRS) == 7 * 20 * 27
+    assert ng.ngc_conv3d_filter_elems(d, ng.NGC_BLOCKED_FWD) == 27 * 2 * 7 * 16
+    assert ng.ngc_conv3d_filter_elems(d, ng.NGC_BLOCKED_BWD) == 27 * 1 * 20 * 16

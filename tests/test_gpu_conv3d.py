@@ -1,0 +1,197 @@
+"""GPU parity of Convolution over three spatial axes (ngc_conv3d_*) against the fp64 oracle
+(oracle/conv3d_oracle.py), through the C ABI.  Tolerances as for the rank-2 ops: 1e-5 (fp32),
+2e-2 (bf16), max-normalised."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1801_08058_amd as ng
+import synth_inputs
+from oracle import Attrs3
+from gpu_util import TOL, Run3, attrs3_of, desc3_of, dev, encode, host, stream
+
+pytestmark = pytest.mark.gpu
+NCHW, BLK = ng.NGC_NCHW, ng.NGC_NCHW16C
+OPS = (ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS)
+
+
+def _tensors3(a: Attrs3, dtype: str, seed: int):
+    L = synth_inputs.Conv3dLayer("t", a.n, a.c, a.d, a.h, a.w, a.k, a.t, a.r, a.s, (a.sd, a.sh, a.sw), (a.dd, a.dh, a.dw),
+                                 (a.pbd, a.pbh, a.pbw), (a.pad, a.pah, a.paw), dtype=dtype, seed=seed)
+    t = synth_inputs.layer3_tensors(L)
+    return t["x"], t["w"], t["bias"], t["dy"]
+
+
+def _check3(a: Attrs3, dtype: str, xl: int, yl: int, pre: bool, seed: int, expect=None):
+    print(f"case attrs={a} dtype={dtype} xl={xl} yl={yl} pre={pre} seed={seed}", flush=True)
+    x, w, b, dy = _tensors3(a, dtype, seed)
+    run = Run3(a, dtype, xl, yl, pre)
+    tol = TOL[dtype]
+    y = run.fwd(x, w, bias=b, relu=True)
+    if expect:
+        assert ng.ngc_conv3d_variant(run.last_desc, ng.NGC_OP_FWD).startswith(expect[0]), ng.ngc_conv3d_variant(run.last_desc, 0)
+    e = oracle.max_normalised_error(y, oracle.conv3d_fwd(a, x, w, bias=b, relu=True))
+    assert e <= tol, f"fwd+bias+relu err {e}"
+    e = oracle.max_normalised_error(run.fwd(x, w), oracle.conv3d_fwd(a, x, w))
+    assert e <= tol, f"fwd err {e}"
+    dx = run.bwd_data(dy, w)
+    if expect:
+        assert ng.ngc_conv3d_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect[1]), ng.ngc_conv3d_variant(run.last_desc, 1)
+    e = oracle.max_normalised_error(dx, oracle.conv3d_bwd_data(a, dy, w))
+    assert e <= tol, f"bwd_data err {e}"
+    dw = run.bwd_filters(x, dy)
+    if expect:
+        assert ng.ngc_conv3d_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS).startswith(expect[2]), ng.ngc_conv3d_variant(run.last_desc, 2)
+    e = oracle.max_normalised_error(dw, oracle.conv3d_bwd_filters(a, x, dy))
+    assert e <= (1e-5 if dtype == "f32" else tol), f"bwd_filters err {e}"
+
+
+MFMA3 = ("igemm3", "igemm3", "wgrad_gemm3")
+
+# the video configuration at a quarter of the clip length / image side, batch 2: several tiles, ragged tails
+@pytest.mark.parametrize("i", range(7))
+@pytest.mark.parametrize("pre", [False, True])
+def test_video_layers_reduced(i, pre):
+    L = synth_inputs.video_layers(2, scale=4)[i]
+    expect = ("rank2", "rank2", "rank2") if L.name in ("v_3x1x1_c128k64", "v_1x1x1_c256k64") else MFMA3
+    _check3(attrs3_of(L), "bf16", BLK, BLK, pre, L.seed, expect)
+
+
+GATHER_CASES = [
+    # n  c   d  h  w   k   t  r  s  strides    dilation   pad below  pad above
+    (1, 32, 5, 9, 11, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), (1, 1, 1)),
+    (2, 64, 4, 7, 9, 128, 2, 3, 1, (1, 2, 1), (1, 1, 1), (0, 1, 0), (1, 0, 0)),
+    (1, 96, 6, 6, 6, 192, 3, 1, 3, (2, 1, 2), (1, 1, 2), (1, 0, 2), (0, 0, 1)),
+    (3, 64, 7, 5, 8, 64, 1, 3, 3, (1, 1, 1), (1, 2, 1), (0, 2, 1), (0, 2, 1)),
+    (1, 128, 9, 8, 7, 128, 3, 3, 3, (2, 2, 2), (1, 1, 1), (1, 1, 1), (1, 1, 1)),
+    (2, 64, 8, 9, 10, 64, 4, 2, 2, (3, 2, 2), (1, 1, 1), (0, 0, 0), (0, 0, 0)),       # stride > window on depth: untouched voxels
+    (1, 64, 3, 4, 5, 64, 3, 3, 3, (1, 1, 1), (2, 2, 2), (3, 3, 3), (3, 3, 3)),       # windows mostly in the padding
+    (1, 64, 6, 6, 6, 64, 1, 1, 1, (2, 2, 2), (1, 1, 1), (0, 0, 0), (0, 0, 0)),       # 1x1x1 strided: 7 of 8 classes without taps
+]
+
+
+@pytest.mark.parametrize("case", GATHER_CASES)
+def test_gather_kernels_with_depth(case):
+    n, c, d, h, w, k, t, r, s, st, dil, pb, pa = case
+    # the gather kernel takes reductions over multiples of 32 channels into multiples of 64
+    expect = ("igemm3" if c % 32 == 0 and k % 64 == 0 else "direct3", "igemm3" if k % 32 == 0 and c % 64 == 0 else "direct3",
+              "wgrad_gemm3")
+    _check3(Attrs3(n, c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa), "bf16", BLK, BLK, False, 300 + c + d, expect)
+
+
+# channel counts the gather kernel does not take: forward / backprop-data on the direct kernels,
+# backprop-filters still on the per-tap GEMM (multiples of 16)
+@pytest.mark.parametrize("ck", [(16, 48), (48, 80), (80, 16)])
+def test_channel_multiples_of_16(ck):
+    c, k = ck
+    a = Attrs3(2, c, 4, 6, 7, k, 3, 2, 3, 1, 1, 2, 1, 1, 1, 1, 0, 1, 1, 1, 1)
+    _check3(a, "bf16", BLK, BLK, False, 400 + c, ("direct3", "direct3", "wgrad_gemm3"))
+
+
+DIRECT_CASES = [("f32", NCHW, NCHW), ("f32", BLK, BLK), ("bf16", NCHW, NCHW), ("bf16", NCHW, BLK), ("f32", BLK, NCHW)]
+
+
+@pytest.mark.parametrize("dtype,xl,yl", DIRECT_CASES)
+def test_direct_kernels(dtype, xl, yl):
+    a = Attrs3(2, 5, 4, 6, 5, 7, 2, 3, 2, 1, 2, 1, 2, 1, 1, 1, 0, 1, 0, 1, 0)
+    _check3(a, dtype, xl, yl, False, 500, ("direct3",) * 3)
+    a = Attrs3(1, 20, 3, 5, 6, 18, 3, 1, 3, 2, 1, 1, 1, 1, 1, 1, 0, 1, 1, 0, 1)
+    _check3(a, dtype, xl, yl, False, 501, ("direct3",) * 3)
+
+
+# windows that move over one group of adjacent axes: the rank-2 kernels on the reshaped tensor, and the
+# same node forced onto the rank-3 kernels (NGC_CONV3D_RANK2=0) gives the same tensors
+RANK2_CASES = [
+    (2, 64, 6, 5, 7, 64, 3, 1, 1, (1, 1, 1), (1, 1, 1), (1, 0, 0), (1, 0, 0)),
+    (2, 64, 9, 4, 4, 128, 3, 1, 1, (2, 1, 1), (2, 1, 1), (2, 0, 0), (1, 0, 0)),
+    (1, 128, 4, 6, 8, 64, 1, 1, 1, (1, 1, 1), (1, 1, 1), (0, 0, 0), (0, 0, 0)),
+    (2, 64, 3, 5, 12, 64, 1, 1, 5, (1, 1, 2), (1, 1, 1), (0, 0, 2), (0, 0, 1)),
+]
+
+
+@pytest.mark.parametrize("case", RANK2_CASES)
+@pytest.mark.parametrize("layouts", [(BLK, BLK), (NCHW, NCHW)])
+def test_windows_that_reduce_to_rank2(case, layouts, monkeypatch):
+    n, c, d, h, w, k, t, r, s, st, dil, pb, pa = case
+    a = Attrs3(n, c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa)
+    _check3(a, "bf16", layouts[0], layouts[1], False, 600 + d, ("rank2",) * 3)
+    monkeypatch.setenv("NGC_CONV3D_RANK2", "0")
+    native = MFMA3 if layouts == (BLK, BLK) else ("direct3",) * 3
+    _check3(a, "bf16", layouts[0], layouts[1], False, 600 + d, native)
+
+
+def test_random_descriptors():
+    """Randomised attributes on the MFMA kernels (channel multiples of 64) and on the direct kernels."""
+    g = np.random.default_rng(20180126)
+    done = 0
+    while done < 40:
+        mf = done % 4 != 3
+        t, r, s = (int(v) for v in g.integers(1, 4, size=3))
+        st = tuple(int(v) for v in g.integers(1, 3, size=3))
+        dil = tuple(int(v) for v in g.integers(1, 3, size=3))
+        pb = tuple(int(v) for v in g.integers(0, 3, size=3))
+        pa = tuple(int(v) for v in g.integers(0, 3, size=3))
+        d, h, w = (int(v) for v in g.integers(2, 9, size=3))
+        c = int(g.choice([32, 64, 96])) if mf else int(g.integers(1, 24))
+        k = int(g.choice([64, 128])) if mf else int(g.integers(1, 24))
+        a = Attrs3(int(g.integers(1, 3)), c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa)
+        if min((d + pb[0] + pa[0] - dil[0] * (t - 1) - 1), (h + pb[1] + pa[1] - dil[1] * (r - 1) - 1),
+               (w + pb[2] + pa[2] - dil[2] * (s - 1) - 1)) < 0:
+            continue
+        dtype = "bf16" if mf else ("f32" if done % 8 == 3 else "bf16")
+        _check3(a, dtype, BLK if mf else (NCHW if done % 8 == 3 else BLK), BLK if mf else NCHW, bool(done % 2), 700 + done)
+        done += 1
+
+
+def test_filter_convert_is_the_stated_layout():
+    a = Attrs3(1, 40, 3, 3, 3, 24, 2, 3, 2)
+    g = np.random.default_rng(3)
+    bits = g.integers(1, 0xFFFF, size=(a.k, a.c, a.t, a.r, a.s), dtype=np.uint16)
+    src = dev(bits)
+    for layout in (ng.NGC_BLOCKED_FWD, ng.NGC_BLOCKED_BWD):
+        d = desc3_of(a, "bf16", BLK, BLK, layout)
+        dst = torch.full((ng.ngc_conv3d_filter_elems(d, layout),), -1, dtype=torch.int16, device="cuda")
+        ng.ngc_conv3d_filter_convert(d, src, dst, layout, stream())
+        torch.cuda.synchronize()
+        got = host(dst, np.uint16)
+        if layout == ng.NGC_BLOCKED_FWD:
+            pad = np.zeros((a.k, 48, a.t, a.r, a.s), np.uint16); pad[:, :a.c] = bits
+            want = pad.reshape(a.k, 3, 16, a.t, a.r, a.s).transpose(3, 4, 5, 1, 0, 2)
+        else:
+            pad = np.zeros((32, a.c, a.t, a.r, a.s), np.uint16); pad[:a.k] = bits
+            want = pad.reshape(2, 16, a.c, a.t, a.r, a.s).transpose(3, 4, 5, 0, 2, 1)
+        assert np.array_equal(got, np.ascontiguousarray(want).reshape(-1))
+
+
+@pytest.mark.parametrize("i", [0, 2, 6])
+def test_video_layers_full_size_sampled(i):
+    """The timed shapes (batch 8): 256 sampled elements per op against the oracle's per-element routines, and
+    every element of the outputs finite (the buffers start poisoned)."""
+    L = synth_inputs.video_layers()[i]
+    a = attrs3_of(L)
+    print(f"case {L.name}", flush=True)
+    t = synth_inputs.layer3_tensors(L)
+    run = Run3(a, "bf16", BLK, BLK, True)
+    g = np.random.default_rng(L.seed)
+    O, P, Q = oracle.out_shape3(a)
+    y = run.fwd(t["x"], t["w"], bias=t["bias"], relu=True)
+    assert np.isfinite(y).all()
+    idx = g.integers(0, y.size, size=256)
+    ref = oracle.conv3d_fwd_at(a, t["x"], t["w"], idx, bias=t["bias"], relu=True)
+    scale = max(np.abs(ref).max(), np.abs(y).max() * 0.25)
+    assert np.abs(y.reshape(-1)[idx] - ref).max() / scale <= 2e-2
+    del y
+    dx = run.bwd_data(t["dy"], t["w"])
+    assert np.isfinite(dx).all()
+    idx = g.integers(0, dx.size, size=256)
+    ref = oracle.conv3d_bwd_data_at(a, t["dy"], t["w"], idx)
+    scale = max(np.abs(ref).max(), np.abs(dx).max() * 0.25)
+    assert np.abs(dx.reshape(-1)[idx] - ref).max() / scale <= 2e-2
+    del dx
+    dw = run.bwd_filters(t["x"], t["dy"])
+    assert np.isfinite(dw).all()
+    idx = g.integers(0, dw.size, size=64)
+    ref = oracle.conv3d_bwd_filters_at(a, t["x"], t["dy"], idx)
+    scale = max(np.abs(ref).max(), np.abs(dw).max() * 0.25)
+    assert np.abs(dw.reshape(-1)[idx] - ref).max() / scale <= 2e-2
