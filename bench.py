@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "softmax"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg7", "softmax"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
                     help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
@@ -237,6 +237,82 @@ def softmax_main(args, torch, ng, synth_inputs):
         "kernels": kern}))
 
 
+def conv3d_main(args, torch, ng, synth_inputs):
+    """Video-shaped layers over three spatial axes: forward (+bias+ReLU), backprop-data and backprop-filters of each."""
+    import numpy as np
+    cur = torch.cuda.current_stream().cuda_stream
+    F, B, W = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS
+    items = []
+    for L in synth_inputs.video_layers():
+        t = synth_inputs.layer3_tensors(L)
+        o, p, q = L.opq
+        epi = (ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU) if L.bias_relu else ng.NGC_EPI_NONE
+        mk = lambda wl, e=ng.NGC_EPI_NONE: ng.make_desc3(L.n, L.c, L.d, L.h, L.w, L.k, L.t, L.r, L.s, L.strides, L.dilation,
+                                                         L.pad_below, L.pad_above, ng.NGC_BF16, ng.NGC_NCHW16C, ng.NGC_NCHW16C, wl, e)
+        d_f, d_b, d_w = mk(ng.NGC_BLOCKED_FWD, epi), mk(ng.NGC_BLOCKED_BWD), mk(ng.NGC_KCRS)
+        up = lambda v: torch.from_numpy(np.ascontiguousarray(synth_inputs.f32_to_bf16_bits(v)).view(np.int16)).cuda()
+
+        def blocked(v, c, dd, h, w):          # upload as [N][C][D][H][W], convert on the device (D*H rows)
+            src = up(v)
+            dst = torch.empty(L.n * ((c + 15) // 16) * dd * h * w * 16, dtype=torch.int16, device="cuda")
+            ng.ngc_layout_convert(ng.NGC_BF16, L.n, c, dd * h, w, src, ng.NGC_NCHW, dst, ng.NGC_NCHW16C, cur)
+            torch.cuda.synchronize()
+            return dst
+
+        x, dy = blocked(t["x"], L.c, L.d, L.h, L.w), blocked(t["dy"], L.k, o, p, q)
+        wk = up(t["w"])
+        wf = torch.empty(ng.ngc_conv3d_filter_elems(d_f, ng.NGC_BLOCKED_FWD), dtype=torch.int16, device="cuda")
+        wb = torch.empty(ng.ngc_conv3d_filter_elems(d_f, ng.NGC_BLOCKED_BWD), dtype=torch.int16, device="cuda")
+        ng.ngc_conv3d_filter_convert(d_f, wk, wf, ng.NGC_BLOCKED_FWD, cur)
+        ng.ngc_conv3d_filter_convert(d_f, wk, wb, ng.NGC_BLOCKED_BWD, cur)
+        bias = torch.from_numpy(np.ascontiguousarray(t["bias"], dtype=np.float32)).cuda() if L.bias_relu else None
+        y, dx = torch.empty_like(dy), torch.empty_like(x)
+        dw = torch.empty(L.k * L.c * L.t * L.r * L.s, dtype=torch.float32, device="cuda")
+        ws = {op: torch.empty(max(ng.ngc_conv3d_workspace_bytes(d, op), 16), dtype=torch.uint8, device="cuda")
+              for op, d in ((F, d_f), (B, d_b), (W, d_w))}
+        xb, yb, wbytes = 2 * L.n * L.c * L.d * L.h * L.w, 2 * L.n * L.k * o * p * q, 2 * L.k * L.c * L.t * L.r * L.s
+        ops = {"fwd": (lambda i, a=(d_f, x, wf, bias, y, ws[F]): ng.ngc_conv3d_fwd(*a, cur), d_f, F, xb + yb + wbytes),
+               "bwd_data": (lambda i, a=(d_b, dy, wb, dx, ws[B]): ng.ngc_conv3d_bwd_data(*a, cur), d_b, B, xb + yb + wbytes),
+               "bwd_filters": (lambda i, a=(d_w, x, dy, dw, ws[W]): ng.ngc_conv3d_bwd_filters(*a, cur), d_w, W, xb + yb + 2 * wbytes)}
+        items.append((L, ops))
+    torch.cuda.synchronize()
+
+    def step(i):
+        for _, ops in items:
+            for fn, _, _, _ in ops.values():
+                fn(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern = {}
+    reps = max(5, min(args.steps, 50))
+    for L, ops in items:
+        for name, (fn, d, op, nbytes) in ops.items():
+            ms = event_time_ms(torch, fn, reps)
+            kern[f"{L.name}:{name}"] = {"us": round(ms * 1e3, 2), "tflops": round(L.flop_per_op / (ms * 1e-3) / 1e12, 1),
+                                        "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1), "variant": ng.ngc_conv3d_variant(d, op),
+                                        "count": 1}
+    flop = 3 * sum(L.flop_per_op for L, _ in items)
+    dom_name = max(kern, key=lambda k: kern[k]["us"])
+    dom = kern[dom_name]
+    print(json.dumps({
+        "metric": "conv3d fwd+bwd TFLOP/s over 7 video-shaped layers, 1 GPU", "value": round(flop / (ms_per_step * 1e-3) / 1e12, 1),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "7 layers over (D,H,W), N=8 clips of 16 frames: 3x3x3 64->128 16x56x56, 3x3x3 128->256 8x28x28, "
+                               "3x3x3/2 128->128, 1x3x3 64->128, 3x1x1 128->64, 1x1x1 256->64, 3x3x3 with per-axis strides / "
+                               "dilation / one-sided padding; fwd(+bias+ReLU) + bwd_data + bwd_filters each", "streams": 1},
+        "roofline": {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": dom_name},
+        "kernels": kern}))
+
+
 def cpu_baseline(L):
     """The oracle as it stands, one pass over the full cfg2 tensors, timed on the host cores."""
     import numpy as np
@@ -273,6 +349,9 @@ def main():
 
     if args.workload == "softmax":
         softmax_main(args, torch, ng, synth_inputs)
+        return
+    if args.workload == "cfg7":
+        conv3d_main(args, torch, ng, synth_inputs)
         return
     cfg = int(args.workload[3:])
     layers = synth_inputs.config_layers(cfg)
