@@ -212,6 +212,18 @@ bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int
     return true;
 }
 
+}  // namespace
+
+namespace ngc {
+bool strip_plan_for_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
+                          size_t *lds_out, bool *empty)
+{
+    return strip_plan_class(d, op, ca, cb, P, Q, sp, nf_out, lds_out, empty);
+}
+}  // namespace ngc
+
+namespace {
+
 // number of residue classes of backprop-data launches (1 for forward)
 int strip_classes(const ngc_conv_desc *d, int op) { return op == NGC_OP_FWD ? 1 : d->stride_h * d->stride_w; }
 

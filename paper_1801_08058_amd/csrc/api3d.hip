@@ -6,8 +6,9 @@
 //      stride 1, no padding): the op equals the rank-2 op on a reshaped tensor ((D, H*W) with a
 //      (T,1) window, or (D*H, W) with a (1,S) window; 1x1x1 is the first with T = 1) and goes to
 //      the rank-2 entry point, i.e. to the strip / 1x1 GEMM / per-tap kernels;
-//   2. bf16, blocked tensors: the gather kernel (forward / backprop-data; Cin % 32, Cout % 64) and
-//      the per-tap backprop-filters GEMM (C % 16, K % 16), each with a depth axis;
+//   2. bf16, blocked tensors: the strip kernel with a depth axis (forward / backprop-data; windows of 2..25
+//      taps in (h, w), up to 7 depth taps, Cin % 16, Cout % 16), else the gather kernel with a depth axis
+//      (Cin % 32, Cout % 64); the per-tap backprop-filters GEMM with a depth axis (C % 16, K % 16);
 //   3. the direct kernels (filters [K][C][T][R][S] only).
 #include <cstdio>
 #include <cstdlib>
@@ -111,11 +112,99 @@ bool as_rank2(const ngc_conv3d_desc *d, int O, int P, int Q, ngc_conv_desc *out)
     return true;
 }
 
-enum Variant3 { V3_INVALID, V3_UNSUPPORTED, V3_RANK2, V3_IGEMM_128, V3_IGEMM_64, V3_WGRAD_GEMM, V3_DIRECT };
+enum Variant3 { V3_INVALID, V3_UNSUPPORTED, V3_RANK2, V3_STRIP, V3_IGEMM_128, V3_IGEMM_64, V3_WGRAD_GEMM, V3_DIRECT };
 
 bool blocked_bf16_3(const ngc_conv3d_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
+}
+
+// Launches of the strip kernel for forward (one) or backprop-data (one per residue class (a, b, c) of the dx voxel
+// modulo the strides that has voxels and taps).  The (h, w) part of every launch is planned as the rank-2 node
+// over N * OD images; the depth part is the list of depth taps of the class.
+struct Strip3Launch {
+    StripParams sp;
+    int nf;
+    size_t lds;
+};
+
+struct Strip3Plan {
+    int n;
+    Strip3Launch l[IGEMM_MAX_CLASSES];
+    bool zero;                 // backprop-data: some class with voxels has no tap, dx is cleared first
+};
+
+bool strip3_plan(const ngc_conv3d_desc *d, int op, int O, int P, int Q, Strip3Plan *out)
+{
+    const char *sw = getenv("NGC_CONV3D_STRIP");          // tests / benchmarks only: 0 = the gather kernel instead
+    if (sw && atoi(sw) == 0) return false;
+    const bool fwd = op == NGC_OP_FWD;
+    if (!blocked_bf16_3(d)) return false;
+    if (d->w_layout != NGC_KCRS && d->w_layout != (fwd ? NGC_BLOCKED_FWD : NGC_BLOCKED_BWD)) return false;
+    const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
+    if (Cin % 16 != 0 || Cout % 16 != 0 || d->t > STRIP_MAX_DT) return false;
+    const int sd = d->stride_d, sh = d->stride_h, swd = d->stride_w;
+    if (!fwd && sd * sh * swd > IGEMM_MAX_CLASSES) return false;
+    const size_t in_bytes = fwd ? (size_t)d->n * d->c * d->d * d->h * d->w * 2 : (size_t)d->n * d->k * O * P * Q * 2;
+    const size_t wt_bytes = (size_t)d->t * d->r * d->s * Cin * Cout * 2;
+    if (in_bytes >= ((size_t)1 << 31) || wt_bytes >= ((size_t)1 << 31)) return false;
+
+    ngc_conv_desc d2;                                     // the (h, w) part; n is set per launch
+    memset(&d2, 0, sizeof(d2));
+    d2.c = d->c; d2.h = d->h; d2.w = d->w; d2.k = d->k; d2.r = d->r; d2.s = d->s;
+    d2.stride_h = sh; d2.stride_w = swd; d2.dil_h = d->dil_h; d2.dil_w = d->dil_w;
+    d2.pad_below_h = d->pad_below_h; d2.pad_below_w = d->pad_below_w;
+    d2.pad_above_h = d->pad_above_h; d2.pad_above_w = d->pad_above_w;
+    d2.dtype = d->dtype; d2.x_layout = d->x_layout; d2.y_layout = d->y_layout; d2.w_layout = d->w_layout;
+
+    Strip3Plan pl;
+    pl.n = 0;
+    pl.zero = false;
+    const int rs = d->r * d->s;
+    for (int a = 0; a < (fwd ? 1 : sd); ++a) {
+        int ndt = 0, dt_off[STRIP_MAX_DT], dt_slab[STRIP_MAX_DT];
+        for (int t = 0; t < d->t; ++t) {
+            if (fwd) {
+                dt_off[ndt] = t * d->dil_d - d->pad_below_d;
+            } else {
+                const int v = a + d->pad_below_d - t * d->dil_d;
+                if (((v % sd) + sd) % sd != 0) continue;
+                dt_off[ndt] = v / sd;                     // exact
+            }
+            dt_slab[ndt++] = t * rs;
+        }
+        const int OD = fwd ? O : (a < d->d ? (d->d - a + sd - 1) / sd : 0);
+        if (OD == 0) continue;
+        if ((long long)d->n * OD > (1 << 24)) return false;
+        d2.n = d->n * OD;
+        for (int bc = 0; bc < (fwd ? 1 : sh * swd); ++bc) {
+            Strip3Launch L;
+            bool empty = false;
+            if (!strip_plan_for_class(&d2, op, bc / swd, bc % swd, P, Q, &L.sp, &L.nf, &L.lds, &empty)) return false;
+            if (empty || ndt == 0) {
+                // no voxel, or voxels no tap reaches (the planner reports both as empty; clearing dx covers the second)
+                pl.zero = true;
+                continue;
+            }
+            StripParams &q = L.sp;
+            q.r3 = 1;
+            q.Din = fwd ? d->d : O;
+            q.Dfull = fwd ? O : d->d;
+            q.OD = OD;
+            q.is_d = fwd ? sd : 1;
+            q.os_d = fwd ? 1 : sd;
+            q.oa_d = fwd ? 0 : a;
+            q.ndt = ndt;
+            for (int i = 0; i < ndt; ++i) { q.dt_off[i] = dt_off[i]; q.dt_slab[i] = dt_slab[i]; }
+            q.div_od = make_fastdiv((uint32_t)OD);
+            q.in_bytes = (uint32_t)in_bytes;
+            q.wt_bytes = (uint32_t)wt_bytes;
+            pl.l[pl.n++] = L;
+        }
+    }
+    if (fwd) pl.zero = false;
+    if (out) *out = pl;
+    return true;
 }
 
 // tile shape and split of the position axis of the per-tap backprop-filters GEMM
@@ -175,6 +264,7 @@ Variant3 pick3(const ngc_conv3d_desc *d, int op, ngc_conv_desc *r2)
     }
     const int taps = d->t * d->r * d->s;
     const bool direct_ok = d->w_layout == NGC_KCRS;
+    if ((op == NGC_OP_FWD || op == NGC_OP_BWD_DATA) && strip3_plan(d, op, O, P, Q, nullptr)) return V3_STRIP;
     if (op == NGC_OP_FWD) {
         const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD;
         if (blocked_bf16_3(d) && wl && d->c % 32 == 0 && d->k % 64 == 0 && taps <= IGEMM_MAX_TAPS)
@@ -204,7 +294,7 @@ size_t filter_elems3(const ngc_conv3d_desc *d, int layout)
 size_t workspace3(const ngc_conv3d_desc *d, int op, Variant3 v, const ngc_conv_desc *r2, int O, int P, int Q)
 {
     if (v == V3_RANK2) return ngc_conv_workspace_bytes(r2, op);
-    if (v == V3_IGEMM_128 || v == V3_IGEMM_64) {
+    if (v == V3_IGEMM_128 || v == V3_IGEMM_64 || v == V3_STRIP) {
         if (d->w_layout != NGC_KCRS) return 0;
         return round256_3(filter_elems3(d, op == NGC_OP_FWD ? NGC_BLOCKED_FWD : NGC_BLOCKED_BWD) * 2);
     }
@@ -288,6 +378,7 @@ const char *ngc_conv3d_variant(const ngc_conv3d_desc *desc, int op)
     ngc_conv_desc r2;
     switch (pick3(desc, op, &r2)) {
     case V3_RANK2: snprintf(name, sizeof(name), "rank2:%s", ngc_conv_variant(&r2, op)); return name;
+    case V3_STRIP: return "strip3_bf16";
     case V3_IGEMM_128: return "igemm3_bf16_128x128";
     case V3_IGEMM_64: return "igemm3_bf16_256x64";
     case V3_WGRAD_GEMM: return "wgrad_gemm3_bf16";
@@ -321,6 +412,17 @@ int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, co
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->t * desc->r, desc->s, w, ws, NGC_BLOCKED_FWD, st);
         if (e != hipSuccess) return status3(e);
         wt = ws;
+    }
+    if (v == V3_STRIP) {
+        Strip3Plan pl;
+        if (!strip3_plan(desc, NGC_OP_FWD, O, P, Q, &pl) || pl.n != 1) return NGC_UNSUPPORTED;
+        StripParams &sp = pl.l[0].sp;
+        sp.in = static_cast<const uint16_t *>(x);
+        sp.wt = static_cast<const uint16_t *>(wt);
+        sp.out = static_cast<uint16_t *>(y);
+        sp.bias = b;
+        sp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+        return status3(launch_strip(sp, pl.l[0].nf, pl.l[0].lds, st));
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));
@@ -370,6 +472,35 @@ int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void 
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->t * desc->r, desc->s, w, ws, NGC_BLOCKED_BWD, st);
         if (e != hipSuccess) return status3(e);
         wt = ws;
+    }
+    if (v == V3_STRIP) {
+        Strip3Plan pl;
+        if (!strip3_plan(desc, NGC_OP_BWD_DATA, O, P, Q, &pl)) return NGC_UNSUPPORTED;
+        if (pl.zero) {
+            const hipError_t e = launch_zero_fill(dx, (size_t)desc->n * desc->c * desc->d * desc->h * desc->w * 2, st);
+            if (e != hipSuccess) return status3(e);
+        }
+        // the classes share grids, up to STRIP_MULTI_MAX launches each
+        for (int first = 0; first < pl.n; first += STRIP_MULTI_MAX) {
+            const int cnt = pl.n - first < STRIP_MULTI_MAX ? pl.n - first : STRIP_MULTI_MAX;
+            StripMulti mp;
+            mp.n = cnt;
+            int nf_max = 0;
+            size_t lds_max = 0;
+            for (int i = 0; i < cnt; ++i) {
+                StripParams &sp = pl.l[first + i].sp;
+                sp.in = static_cast<const uint16_t *>(dy);
+                sp.wt = static_cast<const uint16_t *>(wt);
+                sp.out = static_cast<uint16_t *>(dx);
+                mp.c[i] = sp;
+                mp.wg_end[i] = (i ? mp.wg_end[i - 1] : 0) + sp.groups * sp.strips;
+                if (pl.l[first + i].nf > nf_max) nf_max = pl.l[first + i].nf;
+                if (pl.l[first + i].lds > lds_max) lds_max = pl.l[first + i].lds;
+            }
+            const hipError_t e = cnt == 1 ? launch_strip(mp.c[0], nf_max, lds_max, st) : launch_strip_multi(mp, nf_max, lds_max, st);
+            if (e != hipSuccess) return status3(e);
+        }
+        return NGC_OK;
     }
     IgemmParams p;
     memset(&p, 0, sizeof(p));

@@ -228,6 +228,7 @@ struct IgemmParams {
 
 // ---- output-stationary strip kernel (stride-1 forward / backprop-data) ----
 constexpr int STRIP_MAX_TAPS = 25;
+constexpr int STRIP_MAX_DT = 7;       // depth taps of a rank-3 launch
 
 struct StripParams {
     const uint16_t *in;
@@ -265,6 +266,13 @@ struct StripParams {
     // one launch per residue class (oa_h, oa_w) of the stride os).
     int32_t sh, sw, os_h, os_w, oa_h, oa_w, Hfull, Wfull;
     FastDiv div_tpq, div_q, div_prpc, div_pc;
+    // Rank-3 spatial tensors (r3 != 0; template flag R3 of the kernel): an "image" of the fields above is a pair
+    // (n, o) of a batch element and a slice of the depth lattice, N = batch * OD; the reduction runs over
+    // (depth tap, 16-channel chunk) pairs.  Image (n, o) reads input slice o*is_d + dt_off[td] (zeros outside
+    // [0, Din)) with filter slab dt_slab[td] + tap_slab[t], and is stored to slice o*os_d + oa_d of Dfull.
+    int32_t r3, Din, Dfull, OD, is_d, os_d, oa_d, ndt;
+    int32_t dt_off[STRIP_MAX_DT], dt_slab[STRIP_MAX_DT];
+    FastDiv div_od;
 };
 
 // ---- MFMA backprop-filters ----
@@ -400,7 +408,12 @@ struct StripMulti {
     int32_t wg_end[STRIP_MULTI_MAX];   // prefix sums of groups * strips
     StripParams c[STRIP_MULTI_MAX];
 };
+static_assert(sizeof(StripMulti) <= 4096, "kernel arguments are passed by value: at most 4 KB");
 hipError_t launch_strip_multi(const StripMulti &mp, int nf, size_t lds_bytes, hipStream_t st);
+// plan of the strip kernel for forward (op 0) or residue class (ca, cb) of backprop-data (op 1) of a rank-2
+// node (csrc/api.hip); false if the kernel does not take it, *empty if the class has nothing to launch
+bool strip_plan_for_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
+                          size_t *lds_out, bool *empty);
 hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st);
 hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st);

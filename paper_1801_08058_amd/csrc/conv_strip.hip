@@ -48,10 +48,14 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // DB (blocked output only): every wave also writes the sums over its positions of the values it
 // stored, per output channel (fp32, fixed order), to row (p.dbp_row0 + blockIdx.x) * NW + wave of
 // p.dbp - the partials of a bias gradient of the stored tensor.  A separate instantiation.
+// R3 (blocked output, no DB): rank-3 spatial tensors; images are (batch element, depth slice) pairs and the
+// chunk loop runs over (depth tap, 16-channel chunk) pairs, the patch of a chunk coming from the depth slice
+// the tap reads (zeros outside the volume).
 // bx = workgroup index inside the launch's (group, strip) grid
-template <int NF, int NW, int SUB, bool DB>
+template <int NF, int NW, int SUB, bool DB, bool R3 = false>
 __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int bx)
 {
+    static_assert(!R3 || (SUB == 0 && !DB), "rank-3 launches store blocked tensors and no channel sums");
     constexpr bool HALF = SUB == 1;
     constexpr int MAXXB = STRIP_MAXBLOCKS / NW;         // patch blocks per wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -82,11 +86,13 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // ---- loader bookkeeping: wave w loads patch blocks b = w, w+4, ... of both planes
     const int nblocks = (p.npatch + 63) >> 6;
     unsigned xoff[MAXXB];
+    int xz[R3 ? MAXXB : 1];                              // R3: input slice of the pixel's image at depth offset 0
 #pragma unroll
     for (int i = 0; i < MAXXB; ++i) {
         const int b = wave + NW * i;
         const uint32_t pi = (uint32_t)(b * 64 + lane);
         unsigned off = STRIP_OOB;
+        if (R3) xz[R3 ? i : 0] = 0;
         if (b < nblocks && pi < (uint32_t)p.npatch) {
             const uint32_t ti = fd_div(pi, p.div_prpc);
             const uint32_t rem = pi - ti * p.div_prpc.d;
@@ -95,8 +101,15 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             const int n = n0 + (int)ti;
             const int h = p0 * p.sh + p.min_dh + (int)pr;
             const int w = p.min_dw + (int)pc;
-            if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)w < (unsigned)p.Win)
-                off = (unsigned)((n * CB * HWin + h * p.Win + w) * 32);
+            if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)w < (unsigned)p.Win) {
+                if constexpr (R3) {
+                    const int nb = (int)fd_div((uint32_t)n, p.div_od);
+                    xz[i] = (n - nb * p.OD) * p.is_d;
+                    off = (unsigned)((nb * CB * p.Din * HWin + h * p.Win + w) * 32);      // without the depth slice
+                } else {
+                    off = (unsigned)((n * CB * HWin + h * p.Win + w) * 32);
+                }
+            }
         }
         xoff[i] = off;
     }
@@ -106,17 +119,30 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 #pragma unroll
     for (int i = 0; i < NF; ++i) nfrag += ((wave + NW * i) * 32 < p.npix) ? 1 : 0;
 
+    // R3: the loads are issued chunk after chunk; (ld_td, ld_cb) is the (depth tap, channel chunk) pair of the next call
+    int ld_td = 0, ld_cb = 0;
     auto issue_loads = [&](int chunk, int stage) {
         unsigned char *xs = smem + stage * stage_bytes;
         unsigned char *ws = xs + 2 * xplane;
-        const unsigned soff_x = (unsigned)(chunk * HWin * 32);
+        if constexpr (R3) chunk = ld_cb;
+        const unsigned soff_x = (unsigned)(chunk * (R3 ? p.Din * HWin : HWin) * 32);
+        int dz = 0, slab0 = 0;
+        if constexpr (R3) {
+            dz = p.dt_off[ld_td];
+            slab0 = p.dt_slab[ld_td];
+        }
 #pragma unroll
         for (int i = 0; i < MAXXB; ++i) {
             const int b = wave + NW * i;
             if (b < nblocks) {                                           // wave-uniform
+                unsigned base = xoff[i];
+                if constexpr (R3) {
+                    const int z = xz[i] + dz;
+                    base = (base == STRIP_OOB || (unsigned)z >= (unsigned)p.Din) ? STRIP_OOB : base + (unsigned)(z * HWin * 32);
+                }
 #pragma unroll
                 for (int g = 0; g < 2; ++g) {
-                    const unsigned v = (xoff[i] == STRIP_OOB) ? STRIP_OOB : xoff[i] + 16 * g;
+                    const unsigned v = (base == STRIP_OOB) ? STRIP_OOB : base + 16 * g;
                     load_lds16(rs_in, xs + g * xplane + b * 1024, v, soff_x);
                 }
             }
@@ -129,9 +155,12 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         } else {
             for (int j = wave; j < 2 * p.ntaps; j += NW) {                // plane j = tap*2 + g
                 const int t = j >> 1, g = j & 1;
-                const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32 + 16 * g);
+                const unsigned soff_w = (unsigned)((((slab0 + p.tap_slab[t]) * CB + chunk) * p.Cout) * 32 + 16 * g);
                 load_lds16(rs_wt, ws + j * STRIP_WPITCH, woff_lane, soff_w);
             }
+        }
+        if constexpr (R3) {
+            if (++ld_cb == CB) { ld_cb = 0; ++ld_td; }
         }
     };
 
@@ -161,7 +190,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 
     // the sub-pixel store mode may use no more than 32 of the 64 output columns: skip the upper MFMA
     constexpr bool upper = !HALF;
-    const int nchunks = CB;
+    const int nchunks = R3 ? p.ndt * CB : CB;
     issue_loads(0, 0);
     for (int c = 0; c < nchunks; ++c) {
         __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's loads of chunk c have landed
@@ -188,6 +217,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // ---- epilogue
     const int CBout = p.Cout >> 4;
     const int HWout = p.Hfull * p.Wfull;
+    const int plane_out = R3 ? p.Dfull * HWout : HWout;  // pixel blocks per 16-channel plane of a batch element
     float4 bv[2][2][2];                                   // [a][h][which quad]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -275,7 +305,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         const int n = n0 + (int)ti;
         const int oh = p0 + (int)tp;
         ok = ok && n < p.N && oh < p.Hout;
-        const size_t pix = (size_t)n * CBout * HWout + (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
+        size_t pix = (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
+        if constexpr (R3) {
+            const int nb = (int)fd_div((uint32_t)(ok ? n : 0), p.div_od);
+            const int o = (ok ? n : 0) - nb * p.OD;
+            pix += (size_t)nb * CBout * plane_out + (size_t)(o * p.os_d + p.oa_d) * HWout;
+        } else {
+            pix += (size_t)n * CBout * HWout;
+        }
         if (SUB != 0) {
             // sub-pixel NCHW store: column col = (a*BW+b)*C + c -> pixel (BH oh + a, BW q + b) of channel c
             const int ncol = p.sub_BH * p.sub_BW * p.sub_C;
@@ -319,7 +356,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
                 uint4 o = lane_pair_exchange(q0, q1, q2, q3);
                 if (ok && (co_base >> 4) + h < CBout) {
-                    const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
+                    const size_t blk = pix + (size_t)((co_base >> 4) + h) * plane_out;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
                     if (DB) {                                            // the rounded, masked values as stored
@@ -349,34 +386,34 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 }
 
 
-template <int NF, int NW, int SUB = 0, bool DB = false>
+template <int NF, int NW, int SUB = 0, bool DB = false, bool R3 = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
-    conv_strip_body<NF, NW, SUB, DB>(p, blockIdx.x);
+    conv_strip_body<NF, NW, SUB, DB, R3>(p, blockIdx.x);
 }
 
 // Several launches of the kernel above in one grid (the residue classes of a strided backprop-data: each has
 // its own tap list and geometry): workgroups [wg_end[i-1], wg_end[i]) run launch i.  Small classes then share
 // the chip with large ones instead of leaving it half empty, and three launch gaps go away.
-template <int NF, int NW, bool DB>
+template <int NF, int NW, bool DB, bool R3 = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_multi_bf16(const StripMulti mp)
 {
     int cls = 0;
     while (cls + 1 < mp.n && (int)blockIdx.x >= mp.wg_end[cls]) ++cls;   // uniform per workgroup
     const int bx = (int)blockIdx.x - (cls ? mp.wg_end[cls - 1] : 0);
-    conv_strip_body<NF, NW, 0, DB>(mp.c[cls], bx);
+    conv_strip_body<NF, NW, 0, DB, R3>(mp.c[cls], bx);
 }
 
-template <int NF, int NW, int SUB, bool DB>
+template <int NF, int NW, int SUB, bool DB, bool R3 = false>
 static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;                  // per template instantiation
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB, R3>));
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
-    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB>), grid, dim3(NW * 64), lds_bytes, st, p);
+    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB, R3>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
 
@@ -384,8 +421,13 @@ template <int NF, int NW, int SUB = 0>
 static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     if constexpr (SUB == 0 && NW == 8) {
+        if (p.r3) {
+            if (p.dbp || p.mask) return hipErrorInvalidValue;
+            return launch_strip_d<NF, NW, SUB, false, true>(p, lds_bytes, st);
+        }
         if (p.dbp) return launch_strip_d<NF, NW, SUB, true>(p, lds_bytes, st);
     }
+    if (p.r3) return hipErrorInvalidValue;           // rank-3 launches exist for the blocked-output 8-wave kernels only
     if (p.dbp) return hipErrorInvalidValue;          // channel sums exist for the blocked-output 8-wave kernels only
     return launch_strip_d<NF, NW, SUB, false>(p, lds_bytes, st);
 }
@@ -419,16 +461,16 @@ hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStrea
     }
 }
 
-template <int NF, bool DB>
+template <int NF, bool DB, bool R3 = false>
 static hipError_t launch_strip_multi_t(const StripMulti &mp, size_t lds_bytes, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_multi_bf16<NF, 8, DB>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_multi_bf16<NF, 8, DB, R3>));
         if (e != hipSuccess) return e;
     }
     dim3 grid(mp.wg_end[mp.n - 1], (mp.c[0].Cout + 63) / 64);
-    NGC_LAUNCH((conv_strip_multi_bf16<NF, 8, DB>), grid, dim3(8 * 64), lds_bytes, st, mp);
+    NGC_LAUNCH((conv_strip_multi_bf16<NF, 8, DB, R3>), grid, dim3(8 * 64), lds_bytes, st, mp);
     return hipGetLastError();
 }
 
@@ -436,6 +478,15 @@ static hipError_t launch_strip_multi_t(const StripMulti &mp, size_t lds_bytes, h
 hipError_t launch_strip_multi(const StripMulti &mp, int nf, size_t lds_bytes, hipStream_t st)
 {
     const bool db = mp.c[0].dbp != nullptr;
+    if (mp.c[0].r3) {                                // all launches of a grid are of one rank
+        if (db) return hipErrorInvalidValue;
+        switch (nf) {
+        case 7: return launch_strip_multi_t<4, false, true>(mp, lds_bytes, st);
+        case 4: return launch_strip_multi_t<2, false, true>(mp, lds_bytes, st);
+        case 2: return launch_strip_multi_t<1, false, true>(mp, lds_bytes, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (nf) {
     case 7: return db ? launch_strip_multi_t<4, true>(mp, lds_bytes, st) : launch_strip_multi_t<4, false>(mp, lds_bytes, st);
     case 4: return db ? launch_strip_multi_t<2, true>(mp, lds_bytes, st) : launch_strip_multi_t<2, false>(mp, lds_bytes, st);

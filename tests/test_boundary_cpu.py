@@ -299,12 +299,17 @@ def test_conv3d_null_pointers_bias_and_workspace():
     assert ng.ngc_conv3d_filter_convert(d, 4096, 4096, ng.NGC_KCRS, check=False) == ng.NGC_BAD_ARG
 
 
-def test_conv3d_kernel_selection_and_sizes():
+def test_conv3d_kernel_selection_and_sizes(monkeypatch):
     F, B, W = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS
     d = _good3()
-    assert [ng.ngc_conv3d_variant(d, op) for op in (F, B, W)] == ["igemm3_bf16_256x64", "igemm3_bf16_256x64", "wgrad_gemm3_bf16"]
+    assert [ng.ngc_conv3d_variant(d, op) for op in (F, B, W)] == ["strip3_bf16", "strip3_bf16", "wgrad_gemm3_bf16"]
+    monkeypatch.setenv("NGC_CONV3D_STRIP", "0")
+    assert [ng.ngc_conv3d_variant(d, op) for op in (F, B)] == ["igemm3_bf16_256x64"] * 2
     d = _good3(c=128, k=128)
     assert [ng.ngc_conv3d_variant(d, op) for op in (F, B)] == ["igemm3_bf16_128x128"] * 2
+    monkeypatch.delenv("NGC_CONV3D_STRIP")
+    # one tap in (h, w) with a stride there: not a rank-2 node, not a strip window -> gather kernel
+    assert ng.ngc_conv3d_variant(_good3(r=1, s=1, stride=(1, 2, 2), pad_below=(1, 0, 0), pad_above=(1, 0, 0)), F).startswith("igemm3")
     # pre-blocked filters: no workspace for forward / backprop-data
     assert ng.ngc_conv3d_workspace_bytes(_good3(w_layout=ng.NGC_BLOCKED_FWD), F) == 0
     assert ng.ngc_conv3d_workspace_bytes(_good3(w_layout=ng.NGC_BLOCKED_BWD), B) == 0
@@ -319,11 +324,12 @@ def test_conv3d_kernel_selection_and_sizes():
     assert ng.ngc_conv3d_workspace_bytes(t, F) == ng.ngc_conv_workspace_bytes(
         ng.make_desc(2, 64, 6, 100, 64, 3, 1, pad_below=(1, 0), pad_above=(1, 0)), F)
     # a 1x3x3 window keeps the depth axis: rank-3 kernels
-    assert ng.ngc_conv3d_variant(_good3(t=1, pad_below=(0, 1, 1), pad_above=(0, 1, 1)), F).startswith("igemm3")
+    assert ng.ngc_conv3d_variant(_good3(t=1, pad_below=(0, 1, 1), pad_above=(0, 1, 1)), F) == "strip3_bf16"
     # fp32, NCDHW and odd channel counts: direct kernels; blocked filters without an MFMA kernel: unsupported
     assert ng.ngc_conv3d_variant(_good3(dtype=ng.NGC_F32), F) == "direct3"
     assert ng.ngc_conv3d_variant(_good3(x_layout=ng.NGC_NCHW), B) == "direct3"
     assert ng.ngc_conv3d_variant(_good3(c=20), W) == "direct3"
+    assert ng.ngc_conv3d_variant(_good3(c=48), F) == "strip3_bf16"
     assert ng.ngc_conv3d_variant(_good3(c=20, w_layout=ng.NGC_BLOCKED_FWD), F) == "unsupported"
     assert ng.ngc_conv3d_fwd(_good3(c=20, w_layout=ng.NGC_BLOCKED_FWD), 4096, 4096, None, 4096, None, check=False) == ng.NGC_UNSUPPORTED
     # more classes than the gather kernel holds

@@ -47,15 +47,27 @@ def _check3(a: Attrs3, dtype: str, xl: int, yl: int, pre: bool, seed: int, expec
     assert e <= (1e-5 if dtype == "f32" else tol), f"bwd_filters err {e}"
 
 
-MFMA3 = ("igemm3", "igemm3", "wgrad_gemm3")
+def _expect_blocked(a: Attrs3, strip=True):
+    """Kernel names for bf16 blocked tensors: the strip kernel takes windows of 2..25 taps in (h, w) with up to 7
+    depth taps and channel multiples of 16, the gather kernel reductions over multiples of 32 channels into
+    multiples of 64, the per-tap backprop-filters GEMM multiples of 16."""
+    s3 = strip and 2 <= a.r * a.s <= 25 and a.t <= 7 and a.c % 16 == 0 and a.k % 16 == 0
+    fwd = "strip3" if s3 else ("igemm3" if a.c % 32 == 0 and a.k % 64 == 0 else "direct3")
+    bwd = "strip3" if s3 else ("igemm3" if a.k % 32 == 0 and a.c % 64 == 0 and a.sd * a.sh * a.sw <= 16 else "direct3")
+    return fwd, bwd, "wgrad_gemm3" if a.c % 16 == 0 and a.k % 16 == 0 else "direct3"
+
 
 # the video configuration at a quarter of the clip length / image side, batch 2: several tiles, ragged tails
 @pytest.mark.parametrize("i", range(7))
 @pytest.mark.parametrize("pre", [False, True])
-def test_video_layers_reduced(i, pre):
+@pytest.mark.parametrize("strip", [True, False])
+def test_video_layers_reduced(i, pre, strip, monkeypatch):
+    if not strip:
+        monkeypatch.setenv("NGC_CONV3D_STRIP", "0")          # the gather kernel with a depth axis instead
     L = synth_inputs.video_layers(2, scale=4)[i]
-    expect = ("rank2", "rank2", "rank2") if L.name in ("v_3x1x1_c128k64", "v_1x1x1_c256k64") else MFMA3
-    _check3(attrs3_of(L), "bf16", BLK, BLK, pre, L.seed, expect)
+    a = attrs3_of(L)
+    expect = ("rank2", "rank2", "rank2") if L.name in ("v_3x1x1_c128k64", "v_1x1x1_c256k64") else _expect_blocked(a, strip)
+    _check3(a, "bf16", BLK, BLK, pre, L.seed, expect)
 
 
 GATHER_CASES = [
@@ -72,20 +84,23 @@ GATHER_CASES = [
 
 
 @pytest.mark.parametrize("case", GATHER_CASES)
-def test_gather_kernels_with_depth(case):
+@pytest.mark.parametrize("strip", [True, False])
+def test_mfma_kernels_with_depth(case, strip, monkeypatch):
+    if not strip:
+        monkeypatch.setenv("NGC_CONV3D_STRIP", "0")
     n, c, d, h, w, k, t, r, s, st, dil, pb, pa = case
-    # the gather kernel takes reductions over multiples of 32 channels into multiples of 64
-    expect = ("igemm3" if c % 32 == 0 and k % 64 == 0 else "direct3", "igemm3" if k % 32 == 0 and c % 64 == 0 else "direct3",
-              "wgrad_gemm3")
-    _check3(Attrs3(n, c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa), "bf16", BLK, BLK, False, 300 + c + d, expect)
+    a = Attrs3(n, c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa)
+    _check3(a, "bf16", BLK, BLK, False, 300 + c + d, _expect_blocked(a, strip))
 
 
-# channel counts the gather kernel does not take: forward / backprop-data on the direct kernels,
-# backprop-filters still on the per-tap GEMM (multiples of 16)
+# channel counts the gather kernel does not take: the strip kernel (multiples of 16), without it the direct
+# kernels; backprop-filters on the per-tap GEMM (multiples of 16)
 @pytest.mark.parametrize("ck", [(16, 48), (48, 80), (80, 16)])
-def test_channel_multiples_of_16(ck):
+def test_channel_multiples_of_16(ck, monkeypatch):
     c, k = ck
     a = Attrs3(2, c, 4, 6, 7, k, 3, 2, 3, 1, 1, 2, 1, 1, 1, 1, 0, 1, 1, 1, 1)
+    _check3(a, "bf16", BLK, BLK, False, 400 + c, ("strip3", "strip3", "wgrad_gemm3"))
+    monkeypatch.setenv("NGC_CONV3D_STRIP", "0")
     _check3(a, "bf16", BLK, BLK, False, 400 + c, ("direct3", "direct3", "wgrad_gemm3"))
 
 
@@ -117,12 +132,12 @@ def test_windows_that_reduce_to_rank2(case, layouts, monkeypatch):
     a = Attrs3(n, c, d, h, w, k, t, r, s, *st, *dil, *pb, *pa)
     _check3(a, "bf16", layouts[0], layouts[1], False, 600 + d, ("rank2",) * 3)
     monkeypatch.setenv("NGC_CONV3D_RANK2", "0")
-    native = MFMA3 if layouts == (BLK, BLK) else ("direct3",) * 3
+    native = _expect_blocked(a) if layouts == (BLK, BLK) else ("direct3",) * 3
     _check3(a, "bf16", layouts[0], layouts[1], False, 600 + d, native)
 
 
 def test_random_descriptors():
-    """Randomised attributes on the MFMA kernels (channel multiples of 64) and on the direct kernels."""
+    """Randomised attributes on the MFMA kernels (channel multiples of 32 / 64) and on the direct kernels."""
     g = np.random.default_rng(20180126)
     done = 0
     while done < 40:
@@ -141,6 +156,25 @@ def test_random_descriptors():
             continue
         dtype = "bf16" if mf else ("f32" if done % 8 == 3 else "bf16")
         _check3(a, dtype, BLK if mf else (NCHW if done % 8 == 3 else BLK), BLK if mf else NCHW, bool(done % 2), 700 + done)
+        done += 1
+
+
+def test_random_descriptors_gather_kernel(monkeypatch):
+    """The same draw of MFMA descriptors with the strip kernel switched off."""
+    monkeypatch.setenv("NGC_CONV3D_STRIP", "0")
+    g = np.random.default_rng(20180127)
+    done = 0
+    while done < 20:
+        t, r, s = (int(v) for v in g.integers(1, 4, size=3))
+        st = tuple(int(v) for v in g.integers(1, 3, size=3))
+        dil = tuple(int(v) for v in g.integers(1, 3, size=3))
+        pb = tuple(int(v) for v in g.integers(0, 3, size=3))
+        pa = tuple(int(v) for v in g.integers(0, 3, size=3))
+        d, h, w = (int(v) for v in g.integers(2, 9, size=3))
+        a = Attrs3(int(g.integers(1, 3)), 64, d, h, w, int(g.choice([64, 128])), t, r, s, *st, *dil, *pb, *pa)
+        if min(oracle.out_shape3(a)) < 1:
+            continue
+        _check3(a, "bf16", BLK, BLK, bool(done % 2), 800 + done)
         done += 1
 
 
