@@ -233,9 +233,12 @@ bool wgrad_gemm3_plan(const ngc_conv3d_desc *d, int O, int P, int Q, WgradGemmPa
     q.sp = (taps > 1 || tiles >= 16) ? 64 : 128;         // the stage-size rule of the rank-2 layers
     const char *fsp = getenv("NGC_WGG_SP");              // tests / benchmarks only
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
-    const uint32_t slots = q.sp == 64 ? 2 * NUM_CUS3 : NUM_CUS3;
-    uint32_t parts = (slots + tiles - 1) / tiles;
-    if (tiles >= 64 && slots / tiles >= 1) parts = slots / tiles;
+    // The kernel keeps the workgroups of a position chunk on one XCD (chunk % 8): chunks come in multiples of 8,
+    // as many per XCD as its workgroup slots (32 compute units x 1 or 2) hold (tile, tap) sets
+    const uint32_t xcd_slots = (q.sp == 64 ? 2 : 1) * NUM_CUS3 / 8;
+    uint32_t parts = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
+    const char *fp = getenv("NGC_WGG3_PARTS");            // tests / benchmarks only
+    if (fp && atoi(fp) >= 1 && atoi(fp) <= 4096) parts = (uint32_t)atoi(fp);
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;

@@ -79,10 +79,22 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     const int L = lane & 15;
     const int grp = lane >> 4;
 
-    const int part = blockIdx.x;
-    const int kt = blockIdx.y / p.ctiles;
-    const int ct = blockIdx.y - kt * p.ctiles;
-    const int tap = blockIdx.z;
+    // R3: one-dimensional grid.  Workgroup ids go round-robin to the 8 XCDs (one L2 each): position chunk `part`
+    // lives on XCD part % 8 and its (tile, tap) workgroups are consecutive there, so the taps of a chunk share its
+    // x and dy through that L2 instead of every XCD streaming every tensor once per tap.
+    int part = blockIdx.x, tile_id = blockIdx.y, tap = blockIdx.z, ntap_grid = gridDim.z, ntile_grid = gridDim.y;
+    if constexpr (R3) {
+        ntap_grid = p.T * p.R * p.S;
+        ntile_grid = p.ktiles * p.ctiles;
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per = ntap_grid * ntile_grid;
+        const int pl = j / per, r = j - pl * per;
+        part = pl * 8 + xcd;
+        if (part >= p.nparts) return;                    // uniform per workgroup
+        tile_id = r / ntap_grid;
+        tap = r - tile_id * ntap_grid;
+    }
+    const int kt = tile_id / p.ctiles;
+    const int ct = tile_id - kt * p.ctiles;
     int tap2 = tap, dd_off = 0;
     if constexpr (R3) {
         const int tt = tap / (p.R * p.S);
@@ -246,9 +258,9 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     }
     if (wh == 0) {
         // partial[part][tap][tile][sub][kb][cq][lane] (float4 per lane)
-        const size_t tile = (size_t)blockIdx.y;
+        const size_t tile = (size_t)tile_id;
         f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
-                     ((((size_t)part * gridDim.z + tap) * gridDim.y + tile) * (WK * WC) + sub) * (16 * 64);
+                     ((((size_t)part * ntap_grid + tap) * ntile_grid + tile) * (WK * WC) + sub) * (16 * 64);
 #pragma unroll
         for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -310,6 +322,7 @@ static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
     dim3 grid(p.nparts, p.ktiles * p.ctiles, wgrad_gemm_taps(p));
+    if (R3) grid = dim3(8 * ((p.nparts + 7) / 8) * p.ktiles * p.ctiles * wgrad_gemm_taps(p));
     NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
 }
