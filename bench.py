@@ -54,6 +54,7 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
                          "[64,256,56,56] bf16 tensor: 102.8 MB read + 102.8 MB written) so that HBM counters can be scaled")
+    ap.add_argument("--layer", default=None, help="cfg7 only: time this one layer of the set (e.g. v_3x3x3_c64k128)")
     return ap.parse_args()
 
 
@@ -243,7 +244,11 @@ def conv3d_main(args, torch, ng, synth_inputs):
     cur = torch.cuda.current_stream().cuda_stream
     F, B, W = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS
     items = []
-    for L in synth_inputs.video_layers():
+    layers = [L for L in synth_inputs.video_layers() if args.layer in (None, L.name)]
+    if not layers:
+        print(f"bench.py: no layer {args.layer} in cfg7", file=sys.stderr)
+        sys.exit(2)
+    for L in layers:
         t = synth_inputs.layer3_tensors(L)
         o, p, q = L.opq
         epi = (ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU) if L.bias_relu else ng.NGC_EPI_NONE
@@ -298,11 +303,19 @@ def conv3d_main(args, torch, ng, synth_inputs):
             kern[f"{L.name}:{name}"] = {"us": round(ms * 1e3, 2), "tflops": round(L.flop_per_op / (ms * 1e-3) / 1e12, 1),
                                         "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1), "variant": ng.ngc_conv3d_variant(d, op),
                                         "count": 1}
+    if args.calibrate_copy:
+        # a plain copy of known size (102.8 MB read + 102.8 MB written per launch) to scale the HBM counters by
+        src = torch.zeros(64 * 256 * 56 * 56, dtype=torch.int16, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            ng.ngc_layout_convert(ng.NGC_BF16, 64, 256, 56, 56, src, ng.NGC_NCHW, dst, ng.NGC_NCHW, cur)
+        torch.cuda.synchronize()
     flop = 3 * sum(L.flop_per_op for L, _ in items)
     dom_name = max(kern, key=lambda k: kern[k]["us"])
     dom = kern[dom_name]
     print(json.dumps({
-        "metric": "conv3d fwd+bwd TFLOP/s over 7 video-shaped layers, 1 GPU", "value": round(flop / (ms_per_step * 1e-3) / 1e12, 1),
+        "metric": "conv3d fwd+bwd TFLOP/s over 7 video-shaped layers, 1 GPU" if args.layer is None
+        else f"conv3d fwd+bwd TFLOP/s, layer {args.layer}, 1 GPU", "value": round(flop / (ms_per_step * 1e-3) / 1e12, 1),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "7 layers over (D,H,W), N=8 clips of 16 frames: 3x3x3 64->128 16x56x56, 3x3x3 128->256 8x28x28, "

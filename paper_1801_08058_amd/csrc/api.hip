@@ -559,6 +559,13 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // many (tile, tap) pairs: a few workgroups more than the slots cost a whole extra round of long workgroups
     // (3x3 stride 2, 512 -> 512: 576 workgroups 78 us, 432 workgroups 57 us), so round down there
     if (tiles >= 64 && slots / tiles >= 1) parts = slots / tiles;
+    // NGC_WGG_XCD (experiments): 1 = XCD-ordered grid for multi-tap layers, chunk count in multiples of 8
+    const char *fx = getenv("NGC_WGG_XCD");
+    if (fx && atoi(fx) == 1 && d->r * d->s > 1 && !q.x_nchw && !q.dy_nchw) {
+        q.xcd_order = 1;
+        const uint32_t xcd_slots = slots / 8;
+        parts = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
+    }
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;

@@ -360,6 +360,7 @@ struct WgradGemmParams {
     // M = N*O*P*Q, taps = T*R*S
     int32_t r3, D, O, T, sd, dil_d, pbd;
     FastDiv div_opq;           // divide by O*P*Q
+    int32_t xcd_order;         // rank 2, blocked operands: one-dimensional grid with the workgroups of a position chunk on one XCD
 };
 
 // ---- one-tap (1x1) forward / backprop-data as a pipelined GEMM ----

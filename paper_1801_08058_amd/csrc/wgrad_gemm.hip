@@ -54,10 +54,12 @@ __device__ __forceinline__ bf16x8 nchw_frag_g(const unsigned char *lo)
 // SP = positions per stage (128, or 64: half the LDS, two workgroups per compute unit);
 // XN / DN: x / dy is an NCHW tensor (else 16-channel blocked); R3: rank-3 spatial tensors (blocked), positions
 // (n, o, p, q) and taps (t, r, s)
-template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false>
+// XO: XCD-ordered one-dimensional grid (always with R3)
+template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false, bool XO = R3>
 __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 {
     static_assert(!(R3 && (XN || DN)), "rank-3 tensors are read blocked");
+    static_assert(XO || !R3, "rank-3 launches use the XCD-ordered grid");
     constexpr int NW = 8;
     constexpr int NH = NW / (WK * WC);
     constexpr int NPL = 4 * (WK + WC);            // 16-channel planes per stage: dy first, then x
@@ -79,12 +81,12 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
     const int L = lane & 15;
     const int grp = lane >> 4;
 
-    // R3: one-dimensional grid.  Workgroup ids go round-robin to the 8 XCDs (one L2 each): position chunk `part`
+    // XO: one-dimensional grid.  Workgroup ids go round-robin to the 8 XCDs (one L2 each): position chunk `part`
     // lives on XCD part % 8 and its (tile, tap) workgroups are consecutive there, so the taps of a chunk share its
     // x and dy through that L2 instead of every XCD streaming every tensor once per tap.
     int part = blockIdx.x, tile_id = blockIdx.y, tap = blockIdx.z, ntap_grid = gridDim.z, ntile_grid = gridDim.y;
-    if constexpr (R3) {
-        ntap_grid = p.T * p.R * p.S;
+    if constexpr (XO) {
+        ntap_grid = (R3 ? p.T : 1) * p.R * p.S;
         ntile_grid = p.ktiles * p.ctiles;
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, per = ntap_grid * ntile_grid;
         const int pl = j / per, r = j - pl * per;
@@ -311,19 +313,19 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
 
 static int wgrad_gemm_taps(const WgradGemmParams &p) { return (p.r3 ? p.T : 1) * p.R * p.S; }
 
-template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false>
+template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false, bool XO = R3>
 static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;                  // per template instantiation
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3, XO>));
         if (e != hipSuccess) return e;
     }
     size_t lds = (size_t)2 * 4 * (WK + WC) * (SP * 32 + 128);
     if (lds < 65536) lds = 65536;                                       // final cross-wave tree
     dim3 grid(p.nparts, p.ktiles * p.ctiles, wgrad_gemm_taps(p));
-    if (R3) grid = dim3(8 * ((p.nparts + 7) / 8) * p.ktiles * p.ctiles * wgrad_gemm_taps(p));
-    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3>), grid, dim3(512), lds, st, p);
+    if (XO) grid = dim3(8 * ((p.nparts + 7) / 8) * p.ktiles * p.ctiles * wgrad_gemm_taps(p));
+    NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3, XO>), grid, dim3(512), lds, st, p);
     return hipGetLastError();
 }
 
@@ -337,6 +339,7 @@ static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
     if (p.x_nchw && p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, true>(p, st);
     if (p.x_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, false>(p, st);
     if (p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, false, true>(p, st);
+    if (p.xcd_order) return launch_wgrad_gemm_l<WK, WC, SP, false, false, false, true>(p, st);
     return launch_wgrad_gemm_l<WK, WC, SP, false, false>(p, st);
 }
 

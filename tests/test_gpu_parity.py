@@ -632,3 +632,17 @@ def test_random_descriptors_larger_images(seed):
         if P >= 1 and Q >= 1:
             break
     _check_all(a, "bf16", BLK, BLK, bool(seed & 1), 9300 + seed)
+
+
+@pytest.mark.parametrize("a", [Attrs(3, 128, 17, 17, 192, 1, 7, 1, 1, 1, 1, 0, 3, 0, 3),
+                               Attrs(4, 128, 20, 20, 128, 3, 3, 2, 2, 1, 1, 0, 0, 1, 1),
+                               Attrs(2, 48, 9, 11, 80, 2, 3, 1, 2, 2, 1, 1, 0, 0, 2)])
+def test_per_tap_backprop_filters_xcd_ordered_grid(a, monkeypatch):
+    """NGC_WGG_XCD=1 (an experiment switch): one-dimensional grid of the per-tap kernel with the workgroups of a
+    position chunk on one XCD, chunk count in multiples of 8."""
+    monkeypatch.setenv("NGC_WGG_XCD", "1")
+    x, w, b, dy = _tensors(a, "bf16", 9100 + a.c)
+    run = Run(a, "bf16", BLK, BLK, True)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
+    assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
