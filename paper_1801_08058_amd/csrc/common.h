@@ -273,6 +273,7 @@ struct StripParams {
     int32_t r3, Din, Dfull, OD, is_d, os_d, oa_d, ndt;
     int32_t dt_off[STRIP_MAX_DT], dt_slab[STRIP_MAX_DT];
     FastDiv div_od;
+    int32_t xcd_order;         // single launches: one-dimensional grid, the output-channel tiles of a strip on one XCD
 };
 
 // ---- MFMA backprop-filters ----

@@ -53,7 +53,7 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // the tap reads (zeros outside the volume).
 // bx = workgroup index inside the launch's (group, strip) grid
 template <int NF, int NW, int SUB, bool DB, bool R3 = false>
-__device__ __forceinline__ void conv_strip_body(const StripParams &p, const int bx)
+__device__ __forceinline__ void conv_strip_body(const StripParams &p, const int bx, const int by)
 {
     static_assert(!R3 || (SUB == 0 && !DB), "rank-3 launches store blocked tensors and no channel sums");
     constexpr bool HALF = SUB == 1;
@@ -70,7 +70,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const int strip = bx - grp * p.strips;
     const int n0 = grp * p.TN;
     const int p0 = strip * p.TP;
-    const int k0 = blockIdx.y * 64;
+    const int k0 = by * 64;
 
     const int CB = p.Cin >> 4;
     const int HWin = p.Hin * p.Win;
@@ -389,7 +389,18 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 template <int NF, int NW, int SUB = 0, bool DB = false, bool R3 = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
-    conv_strip_body<NF, NW, SUB, DB, R3>(p, blockIdx.x);
+    if (p.xcd_order) {
+        // one-dimensional grid: workgroup ids go round-robin to the 8 XCDs (one L2 each); strip bx lives on XCD
+        // bx % 8 and its output-channel tiles are consecutive there, so they share the strip's input through that L2
+        const int nk = (p.Cout + 63) >> 6;
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int sl = j / nk;
+        const int bx = sl * 8 + xcd;
+        if (bx >= p.groups * p.strips) return;           // uniform per workgroup
+        conv_strip_body<NF, NW, SUB, DB, R3>(p, bx, j - sl * nk);
+        return;
+    }
+    conv_strip_body<NF, NW, SUB, DB, R3>(p, blockIdx.x, blockIdx.y);
 }
 
 // Several launches of the kernel above in one grid (the residue classes of a strided backprop-data: each has
@@ -401,7 +412,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_multi_bf16(const StripMult
     int cls = 0;
     while (cls + 1 < mp.n && (int)blockIdx.x >= mp.wg_end[cls]) ++cls;   // uniform per workgroup
     const int bx = (int)blockIdx.x - (cls ? mp.wg_end[cls - 1] : 0);
-    conv_strip_body<NF, NW, 0, DB, R3>(mp.c[cls], bx);
+    conv_strip_body<NF, NW, 0, DB, R3>(mp.c[cls], bx, blockIdx.y);
 }
 
 template <int NF, int NW, int SUB, bool DB, bool R3 = false>
@@ -413,6 +424,7 @@ static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStre
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
+    if (p.xcd_order) grid = dim3(8 * ((p.groups * p.strips + 7) / 8) * ((p.Cout + 63) / 64));
     NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB, R3>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
@@ -434,9 +446,15 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
 
 // nf = 32-position fragments per SIMD (7, 4 or 2); the fragments of a SIMD are spread over
 // `waves_per_simd` waves so that one wave's LDS latency hides behind the other's MFMAs
-hipError_t launch_strip(const StripParams &p, int nf, size_t lds_bytes, hipStream_t st)
+hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipStream_t st)
 {
     static const int two_waves = getenv("NGC_STRIP_1WAVE") ? 0 : 1;
+    StripParams p = p_in;
+    // several output-channel tiles: XCD-ordered grid, so that the tiles of a strip read its input through one L2
+    // (strided forward layers of the ResNet-50 stack 58 -> 55 us, others 0-2 %; NGC_STRIP_XCD=0: two-dimensional grid)
+    const char *xo = getenv("NGC_STRIP_XCD");
+    const int gx = p.groups * p.strips;                  // strips per XCD must come out even: a multiple of 8, or many
+    if (p.Cout > 64 && (gx % 8 == 0 || gx >= 64) && !(xo && atoi(xo) == 0)) p.xcd_order = 1;
     if (p.out_mode == 1 && p.half_cols) {
         switch (nf) {
         case 7: return launch_strip_nf<4, 8, 1>(p, lds_bytes, st);

@@ -646,3 +646,11 @@ def test_per_tap_backprop_filters_xcd_ordered_grid(a, monkeypatch):
     dw = run.bwd_filters(x, dy)
     assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
     assert oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy)) <= 2e-2
+
+
+def test_strip_two_dimensional_grid_switch(monkeypatch):
+    """NGC_STRIP_XCD=0: the strip kernel's launches with several output-channel tiles on the two-dimensional grid
+    (default: one-dimensional, the tiles of a strip on one XCD)."""
+    monkeypatch.setenv("NGC_STRIP_XCD", "0")
+    a = Attrs(5, 64, 19, 21, 192, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1)
+    _check_all(a, "bf16", BLK, BLK, True, 9200, ("strip", "strip", "wgrad"))
