@@ -84,10 +84,39 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
     for (int nf : nfs) {
         if (forced_nf > 0 && nf != forced_nf) continue;
         const int maxpix = 4 * nf * 32;
-        if (Wout > maxpix) continue;
         StripParams q = out;
+        q.ncolt = 1;
+        q.BW = Wout;
         q.PC = (Wout - 1) * sw + span_w + 1;
         const int pr_full = (Hout - 1) * sh + span_h + 1;
+        if (Wout > maxpix || MAXPATCH / q.PC < span_h + 1) {
+            // Rows wider than a strip (or its patch) holds: column tiles.  Of the tile widths (multiples of 8 lattice
+            // columns) take the one whose strips read the fewest patch pixels over the image.
+            if (out.out_mode != 0) continue;
+            long best_cost = -1;
+            int best_bw = 0, best_tp = 0;
+            for (int bw = 8; bw <= maxpix && bw < Wout + 8; bw += 8) {
+                const int pc = (bw - 1) * sw + span_w + 1;
+                int tp = maxpix / bw;
+                const int prows = MAXPATCH / pc;
+                if (prows < span_h + 1) break;
+                const int rows_patch = (prows - span_h - 1) / sh + 1;
+                if (tp > rows_patch) tp = rows_patch;
+                if (tp > Hout) tp = Hout;
+                if (tp < 1) continue;
+                const long tiles = (long)((Hout + tp - 1) / tp) * ((Wout + bw - 1) / bw);
+                const long cost = tiles * ((long)(tp - 1) * sh + span_h + 1) * pc;
+                if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_bw = bw; best_tp = tp; }
+            }
+            if (best_cost < 0) continue;
+            q.BW = best_bw;
+            q.ncolt = (Wout + best_bw - 1) / best_bw;
+            q.PC = (best_bw - 1) * sw + span_w + 1;
+            q.TN = 1;
+            const int rstrips = (Hout + best_tp - 1) / best_tp;
+            q.TP = (Hout + rstrips - 1) / rstrips;
+            q.strips = ((Hout + q.TP - 1) / q.TP) * q.ncolt;
+        } else {
         int tn = maxpix / (Hout * Wout);
         if (tn > MAXPATCH / (pr_full * q.PC)) tn = MAXPATCH / (pr_full * q.PC);
         if (tn >= 1) {
@@ -106,17 +135,19 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
             q.TP = (Hout + q.strips - 1) / q.strips;
             q.strips = (Hout + q.TP - 1) / q.TP;
         }
+        }
+        q.div_ncolt = make_fastdiv((uint32_t)q.ncolt);
         q.groups = (N + q.TN - 1) / q.TN;
         q.PR = (q.TP - 1) * sh + span_h + 1;
-        q.npix = q.TN * q.TP * Wout;
+        q.npix = q.TN * q.TP * q.BW;
         q.npatch = q.TN * q.PR * q.PC;
         const int nblocks = (q.npatch + 63) / 64;
         if (nblocks > 24) continue;
         q.xpitch = nblocks * 1024 + 128;
         const size_t lds = 2 * ((size_t)2 * q.xpitch + (size_t)(out.half_cols ? 1 : 2) * ntaps * (64 * 16 + 128));
         if (lds > LDS_LIMIT) continue;
-        q.div_tpq = make_fastdiv((uint32_t)(q.TP * Wout));
-        q.div_q = make_fastdiv((uint32_t)Wout);
+        q.div_tpq = make_fastdiv((uint32_t)(q.TP * q.BW));
+        q.div_q = make_fastdiv((uint32_t)q.BW);
         q.div_prpc = make_fastdiv((uint32_t)(q.PR * q.PC));
         q.div_pc = make_fastdiv((uint32_t)q.PC);
         const long wgs = (long)q.groups * q.strips * ((Cout + 63) / 64);
@@ -226,6 +257,19 @@ namespace {
 
 // number of residue classes of backprop-data launches (1 for forward)
 int strip_classes(const ngc_conv_desc *d, int op) { return op == NGC_OP_FWD ? 1 : d->stride_h * d->stride_w; }
+
+// true if some launch of the op cuts its rows into column tiles
+bool strip_col_tiles(const ngc_conv_desc *d, int op, int P, int Q)
+{
+    const int ncls = strip_classes(d, op);
+    for (int c = 0; c < ncls; ++c) {
+        StripParams sp;
+        bool empty = false;
+        if (strip_plan_class(d, op, c / d->stride_w, c % d->stride_w, P, Q, &sp, nullptr, nullptr, &empty) && !empty && sp.ncolt > 1)
+            return true;
+    }
+    return false;
+}
 
 // backprop-data: true if some residue class of the stride is reached by no tap (stride larger than the
 // dilated window covers); dx is then cleared before the launches of the other classes
@@ -715,7 +759,10 @@ ngc_conv_desc dx_as_dy(const ngc_conv_desc *d)
 bool db_fusable(const ngc_conv_desc *d, Variant v)
 {
     if (getenv("NGC_DB_FUSE") && atoi(getenv("NGC_DB_FUSE")) == 0) return false;   // tests / benchmarks only
-    if (v == V_STRIP) return getenv("NGC_STRIP_1WAVE") == nullptr;
+    if (v == V_STRIP) {                                   // the kernels with column tiles write no channel sums
+        int P, Q;
+        return getenv("NGC_STRIP_1WAVE") == nullptr && validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
+    }
     if (v == V_GEMM1X1) return d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
     return false;
 }
@@ -1030,6 +1077,7 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         mp.n = 0;
         int nf_max = 0;
         size_t lds_max = 0;
+        const bool col_tiles = strip_col_tiles(desc, NGC_OP_BWD_DATA, P, Q);    // then one launch per class
         for (int c = 0; c < ncls; ++c) {
             StripParams sp;
             int nf;
@@ -1050,7 +1098,7 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
                 sp.dbp_ld = fuse->ld;
                 fuse->rows += sp.groups * sp.strips * 8;
             }
-            if (merge && ncls > 1 && ncls <= STRIP_MULTI_MAX) {
+            if (merge && ncls > 1 && ncls <= STRIP_MULTI_MAX && !col_tiles) {
                 mp.c[mp.n] = sp;
                 mp.wg_end[mp.n] = (mp.n ? mp.wg_end[mp.n - 1] : 0) + sp.groups * sp.strips;
                 ++mp.n;

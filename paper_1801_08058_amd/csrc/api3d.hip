@@ -483,9 +483,12 @@ int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void 
             const hipError_t e = launch_zero_fill(dx, (size_t)desc->n * desc->c * desc->d * desc->h * desc->w * 2, st);
             if (e != hipSuccess) return status3(e);
         }
-        // the classes share grids, up to STRIP_MULTI_MAX launches each
-        for (int first = 0; first < pl.n; first += STRIP_MULTI_MAX) {
-            const int cnt = pl.n - first < STRIP_MULTI_MAX ? pl.n - first : STRIP_MULTI_MAX;
+        // the classes share grids, up to STRIP_MULTI_MAX launches each (launches with column tiles go alone)
+        bool col_tiles = false;
+        for (int i = 0; i < pl.n; ++i) col_tiles = col_tiles || pl.l[i].sp.ncolt > 1;
+        const int per_grid = col_tiles ? 1 : STRIP_MULTI_MAX;
+        for (int first = 0; first < pl.n; first += per_grid) {
+            const int cnt = pl.n - first < per_grid ? pl.n - first : per_grid;
             StripMulti mp;
             mp.n = cnt;
             int nf_max = 0;

@@ -274,6 +274,11 @@ struct StripParams {
     int32_t dt_off[STRIP_MAX_DT], dt_slab[STRIP_MAX_DT];
     FastDiv div_od;
     int32_t xcd_order;         // single launches: one-dimensional grid, the output-channel tiles of a strip on one XCD
+    // Column tiles (rows wider than a strip holds): a strip covers BW of the Wout lattice columns; `strips` counts
+    // (row strip, column tile) pairs, column tile fastest; the geometry fields and divisors above are those of a
+    // BW-wide lattice.  ncolt = 1: BW = Wout.
+    int32_t ncolt, BW;
+    FastDiv div_ncolt;
 };
 
 // ---- MFMA backprop-filters ----

@@ -52,10 +52,13 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // chunk loop runs over (depth tap, 16-channel chunk) pairs, the patch of a chunk coming from the depth slice
 // the tap reads (zeros outside the volume).
 // bx = workgroup index inside the launch's (group, strip) grid
-template <int NF, int NW, int SUB, bool DB, bool R3 = false>
+// CT (blocked output, no DB): column tiles - a strip covers p.BW of the p.Wout lattice columns (rows wider than a
+// strip holds); a separate instantiation so that the full-width kernels carry none of it.
+template <int NF, int NW, int SUB, bool DB, bool R3 = false, bool CT = false>
 __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int bx, const int by)
 {
     static_assert(!R3 || (SUB == 0 && !DB), "rank-3 launches store blocked tensors and no channel sums");
+    static_assert(!CT || (SUB == 0 && !DB), "column tiles exist for blocked tensors without channel sums");
     constexpr bool HALF = SUB == 1;
     constexpr int MAXXB = STRIP_MAXBLOCKS / NW;         // patch blocks per wave
     extern __shared__ __align__(16) unsigned char smem[];
@@ -67,7 +70,13 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const int lg = lane >> 5;
 
     const int grp = bx / p.strips;
-    const int strip = bx - grp * p.strips;
+    int strip = bx - grp * p.strips;
+    int q0 = 0;                                          // first lattice column of the strip's column tile
+    if constexpr (CT) {
+        const int rs = (int)fd_div((uint32_t)strip, p.div_ncolt);
+        q0 = (strip - rs * p.ncolt) * p.BW;
+        strip = rs;
+    }
     const int n0 = grp * p.TN;
     const int p0 = strip * p.TP;
     const int k0 = by * 64;
@@ -100,7 +109,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             const uint32_t pc = rem - pr * p.div_pc.d;
             const int n = n0 + (int)ti;
             const int h = p0 * p.sh + p.min_dh + (int)pr;
-            const int w = p.min_dw + (int)pc;
+            const int w = (CT ? q0 * p.sw : 0) + p.min_dw + (int)pc;
             if (n < p.N && (unsigned)h < (unsigned)p.Hin && (unsigned)w < (unsigned)p.Win) {
                 if constexpr (R3) {
                     const int nb = (int)fd_div((uint32_t)n, p.div_od);
@@ -305,7 +314,13 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         const int n = n0 + (int)ti;
         const int oh = p0 + (int)tp;
         ok = ok && n < p.N && oh < p.Hout;
-        size_t pix = (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
+        size_t pix;
+        if constexpr (CT) {
+            ok = ok && q0 + (int)q < p.Wout;
+            pix = (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + ((q0 + (int)q) * p.os_w + p.oa_w);
+        } else {
+            pix = (size_t)(oh * p.os_h + p.oa_h) * p.Wfull + (q * p.os_w + p.oa_w);
+        }
         if constexpr (R3) {
             const int nb = (int)fd_div((uint32_t)(ok ? n : 0), p.div_od);
             const int o = (ok ? n : 0) - nb * p.OD;
@@ -386,7 +401,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 }
 
 
-template <int NF, int NW, int SUB = 0, bool DB = false, bool R3 = false>
+template <int NF, int NW, int SUB = 0, bool DB = false, bool R3 = false, bool CT = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
     if (p.xcd_order) {
@@ -397,10 +412,10 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
         const int sl = j / nk;
         const int bx = sl * 8 + xcd;
         if (bx >= p.groups * p.strips) return;           // uniform per workgroup
-        conv_strip_body<NF, NW, SUB, DB, R3>(p, bx, j - sl * nk);
+        conv_strip_body<NF, NW, SUB, DB, R3, CT>(p, bx, j - sl * nk);
         return;
     }
-    conv_strip_body<NF, NW, SUB, DB, R3>(p, blockIdx.x, blockIdx.y);
+    conv_strip_body<NF, NW, SUB, DB, R3, CT>(p, blockIdx.x, blockIdx.y);
 }
 
 // Several launches of the kernel above in one grid (the residue classes of a strided backprop-data: each has
@@ -415,17 +430,17 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_multi_bf16(const StripMult
     conv_strip_body<NF, NW, 0, DB, R3>(mp.c[cls], bx, blockIdx.y);
 }
 
-template <int NF, int NW, int SUB, bool DB, bool R3 = false>
+template <int NF, int NW, int SUB, bool DB, bool R3 = false, bool CT = false>
 static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;                  // per template instantiation
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB, R3>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&conv_strip_bf16<NF, NW, SUB, DB, R3, CT>));
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
     if (p.xcd_order) grid = dim3(8 * ((p.groups * p.strips + 7) / 8) * ((p.Cout + 63) / 64));
-    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB, R3>), grid, dim3(NW * 64), lds_bytes, st, p);
+    NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB, R3, CT>), grid, dim3(NW * 64), lds_bytes, st, p);
     return hipGetLastError();
 }
 
@@ -433,13 +448,17 @@ template <int NF, int NW, int SUB = 0>
 static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
     if constexpr (SUB == 0 && NW == 8) {
+        if (p.ncolt > 1 && p.dbp) return hipErrorInvalidValue;
         if (p.r3) {
             if (p.dbp || p.mask) return hipErrorInvalidValue;
+            if (p.ncolt > 1) return launch_strip_d<NF, NW, SUB, false, true, true>(p, lds_bytes, st);
             return launch_strip_d<NF, NW, SUB, false, true>(p, lds_bytes, st);
         }
+        if (p.ncolt > 1) return launch_strip_d<NF, NW, SUB, false, false, true>(p, lds_bytes, st);
         if (p.dbp) return launch_strip_d<NF, NW, SUB, true>(p, lds_bytes, st);
     }
-    if (p.r3) return hipErrorInvalidValue;           // rank-3 launches exist for the blocked-output 8-wave kernels only
+    // rank-3 launches and column tiles exist for the blocked-output 8-wave kernels only
+    if (p.r3 || p.ncolt > 1) return hipErrorInvalidValue;
     if (p.dbp) return hipErrorInvalidValue;          // channel sums exist for the blocked-output 8-wave kernels only
     return launch_strip_d<NF, NW, SUB, false>(p, lds_bytes, st);
 }
@@ -496,6 +515,8 @@ static hipError_t launch_strip_multi_t(const StripMulti &mp, size_t lds_bytes, h
 hipError_t launch_strip_multi(const StripMulti &mp, int nf, size_t lds_bytes, hipStream_t st)
 {
     const bool db = mp.c[0].dbp != nullptr;
+    for (int i = 0; i < mp.n; ++i)
+        if (mp.c[i].ncolt > 1) return hipErrorInvalidValue;          // column tiles: single launches only
     if (mp.c[0].r3) {                                // all launches of a grid are of one rank
         if (db) return hipErrorInvalidValue;
         switch (nf) {

@@ -229,3 +229,9 @@ def test_video_layers_full_size_sampled(i):
     ref = oracle.conv3d_bwd_filters_at(a, t["x"], t["dy"], idx)
     scale = max(np.abs(ref).max(), np.abs(dw).max() * 0.25)
     assert np.abs(dw.reshape(-1)[idx] - ref).max() / scale <= 2e-2
+
+
+def test_temporal_window_on_large_slices_runs_on_the_strip_kernel():
+    """A (3,1,1) window is the rank-2 node over (D, H*W); rows of H*W = 1600 pixels are cut into column tiles."""
+    a = Attrs3(2, 64, 6, 40, 40, 64, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 0, 0)
+    _check3(a, "bf16", BLK, BLK, True, 900, ("rank2:strip", "rank2:strip", "rank2:"))

@@ -654,3 +654,26 @@ def test_strip_two_dimensional_grid_switch(monkeypatch):
     monkeypatch.setenv("NGC_STRIP_XCD", "0")
     a = Attrs(5, 64, 19, 21, 192, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1)
     _check_all(a, "bf16", BLK, BLK, True, 9200, ("strip", "strip", "wgrad"))
+
+
+WIDE_ROW_CASES = [
+    # n  c   h   w     k   r  s  sh sw dh dw pbh pbw pah paw      rows wider than a strip holds: column tiles
+    Attrs(1, 32, 5, 1000, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),
+    Attrs(2, 64, 12, 3136, 64, 3, 1, 1, 1, 1, 1, 1, 0, 1, 0),     # a 3x1x1 temporal window seen as a rank-2 node
+    Attrs(1, 64, 9, 1500, 128, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1),     # stride 2: four residue classes, ragged last tile
+    Attrs(1, 48, 4, 2051, 80, 1, 5, 1, 1, 1, 2, 0, 4, 0, 4),      # odd width, dilated 1x5, channel tails
+    Attrs(1, 64, 30, 901, 64, 5, 5, 1, 1, 1, 1, 2, 2, 2, 2),      # one column past a strip, 25 taps
+    Attrs(1, 64, 3, 700, 64, 3, 3, 1, 1, 1, 40, 1, 40, 1, 40),    # patch wider than LDS holds although 700 positions fit
+]
+
+
+@pytest.mark.parametrize("a", WIDE_ROW_CASES)
+def test_strip_column_tiles(a):
+    _check_all(a, "bf16", BLK, BLK, True, 9300 + a.w, ("strip", "strip", "wgrad"))
+
+
+def test_strip_column_tiles_strided_classes_and_channel_sums():
+    """Lattice rows of a strided backprop-data that are wider than a strip: one launch per residue class (no shared
+    grid), and the channel sums of ngc_conv_bwd_data_relu_db come from the second pass."""
+    a = Attrs(1, 64, 6, 2000, 64, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1)
+    _check_all(a, "bf16", BLK, BLK, True, 9400, ("strip", "strip", "wgrad"))
