@@ -603,12 +603,22 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // many (tile, tap) pairs: a few workgroups more than the slots cost a whole extra round of long workgroups
     // (3x3 stride 2, 512 -> 512: 576 workgroups 78 us, 432 workgroups 57 us), so round down there
     if (tiles >= 64 && slots / tiles >= 1) parts = slots / tiles;
-    // NGC_WGG_XCD (experiments): 1 = XCD-ordered grid for multi-tap layers, chunk count in multiples of 8
-    const char *fx = getenv("NGC_WGG_XCD");
-    if (fx && atoi(fx) == 1 && d->r * d->s > 1 && !q.x_nchw && !q.dy_nchw) {
-        q.xcd_order = 1;
+    // Multi-tap layers on large tensors: XCD-ordered one-dimensional grid (the (tile, tap) workgroups of a position
+    // chunk on one XCD, sharing the chunk through its L2 instead of re-reading it from HBM once per tap).  It needs
+    // the chunk count in multiples of 8, so only where that changes the workgroup count by at most a tenth.  Measured:
+    // (3,1) window over 16 x 3136 rows, 128 -> 64: 73 -> 59 us; 3x3/2 128 -> 128 at 56x56: 33 -> 25 us (N = 32),
+    // 47 -> 48 us (N = 128); small tensors and layers with 25-36 (tile, tap) pairs lose 3-40 %.
+    // NGC_WGG_XCD (tests / benchmarks only): 0 = never, 1 = every multi-tap layer.
+    if (d->r * d->s > 1 && !q.x_nchw && !q.dy_nchw) {
         const uint32_t xcd_slots = slots / 8;
-        parts = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
+        const uint32_t parts8 = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
+        const char *fx = getenv("NGC_WGG_XCD");
+        bool on = x_bytes + dy_bytes >= ((size_t)24 << 20) && parts8 * 10 >= parts * 9 && parts8 * 10 <= parts * 11;
+        if (fx) on = atoi(fx) == 1;
+        if (on) {
+            q.xcd_order = 1;
+            parts = parts8;
+        }
     }
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;

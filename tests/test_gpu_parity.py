@@ -638,8 +638,8 @@ def test_random_descriptors_larger_images(seed):
                                Attrs(4, 128, 20, 20, 128, 3, 3, 2, 2, 1, 1, 0, 0, 1, 1),
                                Attrs(2, 48, 9, 11, 80, 2, 3, 1, 2, 2, 1, 1, 0, 0, 2)])
 def test_per_tap_backprop_filters_xcd_ordered_grid(a, monkeypatch):
-    """NGC_WGG_XCD=1 (an experiment switch): one-dimensional grid of the per-tap kernel with the workgroups of a
-    position chunk on one XCD, chunk count in multiples of 8."""
+    """NGC_WGG_XCD=1 forces what large multi-tap layers get by default: the one-dimensional grid of the per-tap
+    kernel with the workgroups of a position chunk on one XCD, chunk count in multiples of 8."""
     monkeypatch.setenv("NGC_WGG_XCD", "1")
     x, w, b, dy = _tensors(a, "bf16", 9100 + a.c)
     run = Run(a, "bf16", BLK, BLK, True)
