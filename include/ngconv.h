@@ -205,8 +205,9 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op);
  * both layouts keep (d, h, w) contiguous in that order.
  * Kernels: a window that moves over at most one group of adjacent axes ((T,1,1), (1,1,S), 1x1x1)
  * is the rank-2 op on a reshaped tensor and runs on the rank-2 kernels; other bf16 blocked shapes
- * with C and K multiples of 64 (forward / backprop-data) or 16 (backprop-filters) run on the MFMA
- * gather kernels with a depth axis; everything else on direct kernels (KCRS filters only).
+ * with C and K multiples of 16 run on the MFMA kernels with a depth axis (forward / backprop-data:
+ * windows of 2..25 taps in (h, w) and up to 7 depth taps, else C and K multiples of 32 / 64);
+ * everything else on direct kernels (KCRS filters only).
  */
 typedef struct {
     int32_t n, c, d, h, w;         /* data batch shape, logical axes N,C,D,H,W                      */

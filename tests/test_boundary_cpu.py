@@ -340,3 +340,17 @@ def test_conv3d_kernel_selection_and_sizes(monkeypatch):
     assert ng.ngc_conv3d_filter_elems(d, ng.NGC_KCRS) == 7 * 20 * 27
     assert ng.ngc_conv3d_filter_elems(d, ng.NGC_BLOCKED_FWD) == 27 * 2 * 7 * 16
     assert ng.ngc_conv3d_filter_elems(d, ng.NGC_BLOCKED_BWD) == 27 * 1 * 20 * 16
+
+
+def test_wide_rows_stay_on_the_strip_kernel():
+    """Rows wider than a strip holds are cut into column tiles instead of falling to the gather kernel; the channel
+    sums of the backward compound then need the second pass (a larger workspace than the plain op)."""
+    F, B = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA
+    d = ng.make_desc(1, 64, 8, 2000, 64, 3, 3, pad_below=(1, 1), pad_above=(1, 1), w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv_variant(d, F) == "strip_bf16"
+    d = ng.make_desc(1, 64, 8, 2000, 64, 3, 3, pad_below=(1, 1), pad_above=(1, 1), w_layout=ng.NGC_BLOCKED_BWD)
+    assert ng.ngc_conv_variant(d, B) == "strip_bf16"
+    assert ng.ngc_conv_workspace_bytes(d, ng.NGC_OP_BWD_DATA_DB) > ng.ngc_conv_workspace_bytes(d, B)
+    # the temporal window of a video layer as the rank-2 node it is
+    t = ng.make_desc3(2, 64, 16, 56, 56, 64, 3, 1, 1, pad_below=(1, 0, 0), pad_above=(1, 0, 0), w_layout=ng.NGC_BLOCKED_FWD)
+    assert ng.ngc_conv3d_variant(t, F) == "rank2:strip_bf16"
