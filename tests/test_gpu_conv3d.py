@@ -235,3 +235,17 @@ def test_temporal_window_on_large_slices_runs_on_the_strip_kernel():
     """A (3,1,1) window is the rank-2 node over (D, H*W); rows of H*W = 1600 pixels are cut into column tiles."""
     a = Attrs3(2, 64, 6, 40, 40, 64, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 0, 0)
     _check3(a, "bf16", BLK, BLK, True, 900, ("rank2:strip", "rank2:strip", "rank2:"))
+
+
+FALLBACK_CASES = [
+    # more depth taps than the strip kernel holds -> gather kernel; more taps than that holds -> direct kernels
+    (Attrs3(1, 64, 12, 6, 5, 64, 9, 3, 1, 1, 1, 1, 1, 1, 1, 4, 1, 0, 4, 1, 0), ("igemm3", "igemm3", "wgrad_gemm3")),
+    (Attrs3(1, 32, 10, 6, 6, 64, 9, 3, 3, 1, 1, 1, 1, 1, 1, 4, 1, 1, 4, 1, 1), ("direct3", "direct3", "direct3")),
+    # more residue classes of the strides than either MFMA kernel holds -> direct backprop-data
+    (Attrs3(1, 64, 9, 9, 8, 64, 3, 3, 3, 3, 3, 2, 1, 1, 1, 1, 1, 1, 1, 1, 1), ("strip3", "direct3", "wgrad_gemm3")),
+]
+
+
+@pytest.mark.parametrize("a,expect", FALLBACK_CASES)
+def test_kernel_limits_fall_back(a, expect):
+    _check3(a, "bf16", BLK, BLK, False, 950 + a.t + a.sd, expect)
