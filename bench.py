@@ -37,8 +37,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg7", "softmax"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
                          "[64,256,56,56] bf16 tensor: 102.8 MB read + 102.8 MB written) so that HBM counters can be scaled")
+    ap.add_argument("--settle", type=float, default=0.2,
+                    help="seconds of untimed load (the workload's own steps) before the warm-up steps; 0 = none")
     ap.add_argument("--layer", default=None, help="cfg7 only: time this one layer of the set (e.g. v_3x3x3_c64k128)")
     return ap.parse_args()
 
@@ -175,6 +177,21 @@ class LayerBench:
         return xb + yb + 2 * wb          # bwd_filters: dw fp32
 
 
+def settle_clocks(torch, step, seconds):
+    """Untimed: keep the GPU busy with the workload's own steps for `seconds` before the W warm-up steps, so
+    that the timed region starts at the clocks a training job runs at (a cold MI355X takes some 50 ms of load to
+    reach them: the cfg2 step is 73 us when timed right after 20 warm-up steps and 61 us in steady state)."""
+    if seconds <= 0:
+        return
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(16):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def event_time_ms(torch, fn, reps):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -205,6 +222,7 @@ def softmax_main(args, torch, ng, synth_inputs):
             ng.ngc_softmax(code, c.rows, c.cols, x, y, cur)
             ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur)
 
+    settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -287,6 +305,7 @@ def conv3d_main(args, torch, ng, synth_inputs):
             for fn, _, _, _ in ops.values():
                 fn(i)
 
+    settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -391,6 +410,7 @@ def main():
             for _ in range(b.L.count):
                 b.step(i, streams)
 
+    settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
