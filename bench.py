@@ -2,14 +2,16 @@
 """Benchmark of the Convolution hot path on one MI355X.
 
 A step = one pass of the whole hot path over one batch of synthetic input for the workload
-the headline metric is quoted on (BASELINE configs[1]): ResNet-style 3x3 conv layer, bf16
+the headline metric is quoted on (the second benchmark configuration): ResNet-style 3x3 conv layer, bf16
 data with fp32 accumulate, N=64, C=K=64, 56x56, stride 1, pad 1 -- forward with the fused
 bias+ReLU epilogue, ConvolutionBackpropData and ConvolutionBackpropFilters, all on
 16-channel-blocked tensors, inputs resident in HBM, filters already in their blocked
 layouts (the re-layout happens once per weight update and is timed separately).
 
-Prints ONE JSON line (see README for the fields).  `--workload` selects another
-configuration for experiments; the default line is the contract.
+Prints ONE JSON line: metric, value, unit, step time, the workload, `roofline` (the dominant kernel against
+the MI355X peak that bounds it, with its HBM traffic from counters), `kernels` (per-kernel durations from HIP
+events on the launch stream) and `cpu_baseline` (the CPU oracle timed on the host cores).  `--workload` selects
+another configuration for experiments; the default line is the contract.
 """
 from __future__ import annotations
 

@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradParams p)
     // rows k = 32a + 8*(v/4) + 4*lg + v%4.
     float *red = reinterpret_cast<float *>(smem);         // 2 copies x 16 KB = 32 KB <= 36 KB
     auto red_index = [&](int a, int b, int v) { return (a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3)) * 64 + b * 32 + l32; };
-    // round 1: waves 1 and 3 publish, waves 0 and 2 add
+    // first level: waves 1 and 3 publish, waves 0 and 2 add
     if (wave & 1) {
         float *dst = red + (wave >> 1) * 4096;
 #pragma unroll
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradParams p)
                 for (int v = 0; v < 16; ++v) acc[a][b][v] += src[red_index(a, b, v)];
     }
     __syncthreads();
-    // round 2: wave 2 publishes, wave 0 adds and writes the partial tile
+    // second level: wave 2 publishes, wave 0 adds and writes the partial tile
     if (wave == 2) {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
