@@ -125,6 +125,8 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
             q.strips = 1;
         } else {
             int rows_fit = maxpix / Wout;
+            const char *fr = getenv("NGC_STRIP_ROWS");                   // experiments: cap on the rows of a strip
+            if (fr && atoi(fr) >= 1 && rows_fit > atoi(fr)) rows_fit = atoi(fr);
             const int prows = MAXPATCH / q.PC;                           // patch rows that fit
             if (prows < span_h + 1) continue;
             const int rows_patch = (prows - span_h - 1) / sh + 1;
