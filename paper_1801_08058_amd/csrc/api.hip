@@ -629,6 +629,14 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     chunk = (chunk + 127) / 128 * 128;
     q.chunk = chunk;
     q.nparts = (int)((q.M + chunk - 1) / chunk);
+    // One-tap layers with several tiles: the tiles of a chunk share x or dy; with many chunks whose count is no
+    // multiple of 8 the two-dimensional grid spreads them over the XCDs, the XCD-ordered grid does not.  Measured
+    // on the 56x56 layers of the ResNet-50 stack (126 chunks, two tiles): 64 -> 256 53.2 -> 49.7 us, 256 -> 64
+    // 52.4 -> 46.9 us, but 256 -> 128 (128 x 128 tiles) 72.0 -> 75.5 us, so not for that tile shape.
+    if (d->r * d->s == 1 && tiles > 1 && q.wk * q.wc < 4 && !q.x_nchw && !q.dy_nchw && q.nparts >= 64 && q.nparts % 8 != 0) {
+        const char *fx = getenv("NGC_WGG_XCD");
+        if (!(fx && atoi(fx) == 0)) q.xcd_order = 1;
+    }
     q.x_bytes = (uint32_t)x_bytes;
     q.dy_bytes = (uint32_t)dy_bytes;
     q.div_pq = make_fastdiv((uint32_t)(P * Q));
