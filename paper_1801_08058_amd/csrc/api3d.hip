@@ -233,10 +233,22 @@ bool wgrad_gemm3_plan(const ngc_conv3d_desc *d, int O, int P, int Q, WgradGemmPa
     q.sp = (taps > 1 || tiles >= 16) ? 64 : 128;         // the stage-size rule of the rank-2 layers
     const char *fsp = getenv("NGC_WGG_SP");              // tests / benchmarks only
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
-    // The kernel keeps the workgroups of a position chunk on one XCD (chunk % 8): chunks come in multiples of 8,
-    // as many per XCD as its workgroup slots (32 compute units x 1 or 2) hold (tile, tap) sets
+    // The kernel keeps the workgroups of a position chunk on one XCD (chunk % 8): chunks come in multiples of 8.
+    // Per XCD m chunks x (tile, tap) sets share its workgroup slots (32 compute units x 1 or 2): of the m that
+    // fit one round or leave a chunk at least 4096 positions, take the one that fills whole rounds of slots best (a single round
+    // at 84 % leaves compute units with one workgroup idle while others work off two: 3x3x3, 64 -> 128 at
+    // 16x56x56, 27 sets: 2 chunks per XCD 330 us, 7 chunks 294 us; with chunks of 900 positions 128 -> 256 at
+    // 8x28x28 loses 30 %).
     const uint32_t xcd_slots = (q.sp == 64 ? 2 : 1) * NUM_CUS3 / 8;
-    uint32_t parts = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
+    uint32_t best_m = 1;
+    double best_fill = 0.0;
+    const uint32_t one_round = xcd_slots / tiles > 0 ? xcd_slots / tiles : 1;      // always allowed: what one round holds
+    for (uint32_t m = 1; m <= 16 && (m <= one_round || q.M / (8 * m) >= 4096); ++m) {
+        const uint32_t wgs = m * tiles, rounds = (wgs + xcd_slots - 1) / xcd_slots;
+        const double fill = (double)wgs / (rounds * xcd_slots);
+        if (fill > best_fill + 0.02) { best_fill = fill; best_m = m; }
+    }
+    uint32_t parts = 8 * best_m;
     const char *fp = getenv("NGC_WGG3_PARTS");            // tests / benchmarks only
     if (fp && atoi(fp) >= 1 && atoi(fp) <= 4096) parts = (uint32_t)atoi(fp);
     const uint32_t max_parts = (q.M + 127) / 128;
