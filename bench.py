@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0
 # (profiles/cfg2_strip_wgrad_strip.txt), each scaled by what the same counter reads for a plain 102.8 MB copy
 # launched in the same run (FETCH_SIZE reads 0.5004 of the bytes copied, WRITE_SIZE 1.000).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_3x3_c64:fwd": int((14280.0 / 0.5004 + 25088.0) * 1024),
-    "cfg2_3x3_c64:bwd_data": int((14280.0 / 0.5004 + 25088.0) * 1024),
-    "cfg2_3x3_c64:bwd_filters": int(((25727.7 + 9228.5) / 0.5004 + 18432.0 + 576.0) * 1024),
+    "cfg2_3x3_c64:fwd": int((14302.5 / 0.5004 + 25088.0) * 1024),
+    "cfg2_3x3_c64:bwd_data": int((14302.5 / 0.5004 + 25088.0) * 1024),
+    "cfg2_3x3_c64:bwd_filters": int(((25727.5 + 9228.5) / 0.5004 + 18432.0 + 576.0) * 1024),
 }
 
 
