@@ -486,6 +486,9 @@ def main():
                    **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {})},
         "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "gflop_per_step": round(flop_step / 1e9, 2),
+        # the same flop over the sum of the single-stream kernel durations (no overlap between ops)
+        "kernel_sum": {"us": round(sum(v["us"] * v["count"] for v in kern.values()), 2),
+                       "tflops": round(flop_step / (sum(v["us"] * v["count"] for v in kern.values()) * 1e-6) / 1e12, 2)},
         "roofline": roof,
         "kernels": kern,
     }
