@@ -249,3 +249,11 @@ FALLBACK_CASES = [
 @pytest.mark.parametrize("a,expect", FALLBACK_CASES)
 def test_kernel_limits_fall_back(a, expect):
     _check3(a, "bf16", BLK, BLK, False, 950 + a.t + a.sd, expect)
+
+
+@pytest.mark.parametrize("a", [
+    Attrs3(1, 32, 3, 5, 1000, 64, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1),       # slices 1000 pixels wide
+    Attrs3(1, 64, 4, 4, 2001, 64, 2, 3, 3, 2, 1, 2, 1, 1, 1, 0, 1, 1, 1, 1, 1),       # strided: one launch per class
+])
+def test_strip_kernel_with_depth_and_column_tiles(a):
+    _check3(a, "bf16", BLK, BLK, True, 980 + a.w, ("strip3", "strip3", "wgrad_gemm3"))
