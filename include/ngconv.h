@@ -225,7 +225,7 @@ typedef struct {
 /* Output extents O, P, Q.  Host only.  NGC_OK, NGC_BAD_ARG (null) or NGC_BAD_SHAPE. */
 int ngc_conv3d_out_shape(const ngc_conv3d_desc *desc, int32_t *o, int32_t *p, int32_t *q);
 
-/* Workspace bytes of op NGC_OP_FWD / NGC_OP_BWD_DATA / NGC_OP_BWD_FILTERS; 0 if none or invalid. */
+/* Workspace bytes of op NGC_OP_*; 0 if none or invalid. */
 size_t ngc_conv3d_workspace_bytes(const ngc_conv3d_desc *desc, int op);
 
 /* Forward with the compounded bias / ReLU epilogue.  x: [N,C,D,H,W] in x_layout; w in w_layout
@@ -237,6 +237,18 @@ int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, co
  * every element overwritten (0 where no window reaches). */
 int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void *w,
                         void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* The backward compounds of the rank-2 family (ngc_conv_bwd_data_relu, ngc_conv_bwd_data_relu_db,
+ * ngc_bias_grad) for rank-3 tensors, same definitions, arguments and errors: dx = backprop-data where
+ * x_in > 0, +0 elsewhere; db[c] = sum over n, d, h, w of the dx written (fp32, a second pass over dx);
+ * ngc_conv3d_bias_grad: db[k] = sum over n, o, p, q of dy.  Workspaces:
+ * ngc_conv3d_workspace_bytes(desc, NGC_OP_BWD_DATA / NGC_OP_BWD_DATA_DB / NGC_OP_BIAS_GRAD). */
+int ngc_conv3d_bwd_data_relu(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *x_in,
+                             void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+int ngc_conv3d_bwd_data_relu_db(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *x_in,
+                                void *dx, float *db, void *ws, size_t ws_bytes, void *hip_stream);
+int ngc_conv3d_bias_grad(const ngc_conv3d_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes,
+                         void *hip_stream);
 
 /* Backprop-filters.  dw: fp32 [K][C][T][R][S], overwritten; fixed-order reduction through `ws`. */
 int ngc_conv3d_bwd_filters(const ngc_conv3d_desc *desc, const void *x, const void *dy,

@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     ngc_filter_elems, ngc_conv_variant, ngc_status_string,
     ngc_conv3d_desc, make_desc3, ngc_conv3d_out_shape, ngc_conv3d_workspace_bytes, ngc_conv3d_fwd, ngc_conv3d_bwd_data,
     ngc_conv3d_bwd_filters, ngc_conv3d_filter_convert, ngc_conv3d_filter_elems, ngc_conv3d_data_elems, ngc_conv3d_variant,
+    ngc_conv3d_bwd_data_relu, ngc_conv3d_bwd_data_relu_db, ngc_conv3d_bias_grad,
 )

@@ -27,7 +27,7 @@ EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ng
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string",
            "ngc_conv3d_out_shape", "ngc_conv3d_workspace_bytes", "ngc_conv3d_fwd", "ngc_conv3d_bwd_data",
            "ngc_conv3d_bwd_filters", "ngc_conv3d_filter_convert", "ngc_conv3d_filter_elems", "ngc_conv3d_data_elems",
-           "ngc_conv3d_variant")
+           "ngc_conv3d_variant", "ngc_conv3d_bwd_data_relu", "ngc_conv3d_bwd_data_relu_db", "ngc_conv3d_bias_grad")
 
 
 class ngc_conv_desc(ctypes.Structure):
@@ -124,6 +124,12 @@ def _load() -> ctypes.CDLL:
     lib.ngc_conv3d_filter_elems.restype = sz
     lib.ngc_conv3d_data_elems.argtypes = [D3, ctypes.c_int]
     lib.ngc_conv3d_data_elems.restype = sz
+    lib.ngc_conv3d_bwd_data_relu.argtypes = [D3, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_bwd_data_relu.restype = ctypes.c_int
+    lib.ngc_conv3d_bwd_data_relu_db.argtypes = [D3, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_bwd_data_relu_db.restype = ctypes.c_int
+    lib.ngc_conv3d_bias_grad.argtypes = [D3, vp, vp, vp, sz, vp]
+    lib.ngc_conv3d_bias_grad.restype = ctypes.c_int
     lib.ngc_conv3d_variant.argtypes = [D3, ctypes.c_int]
     lib.ngc_conv3d_variant.restype = ctypes.c_char_p
     return lib
@@ -300,3 +306,18 @@ def ngc_conv3d_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = 
 def ngc_conv3d_filter_convert(desc, w_kctrs, w_blocked, dst_layout, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_conv3d_filter_convert(ctypes.byref(desc), _ptr(w_kctrs), _ptr(w_blocked), dst_layout,
                                                  _stream(stream)), "ngc_conv3d_filter_convert", check)
+
+
+def ngc_conv3d_bwd_data_relu(desc, dy, w, x_in, dx, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_bwd_data_relu(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_in), _ptr(dx), _ptr(ws),
+                                                _nbytes(ws), _stream(stream)), "ngc_conv3d_bwd_data_relu", check)
+
+
+def ngc_conv3d_bwd_data_relu_db(desc, dy, w, x_in, dx, db, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_bwd_data_relu_db(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_in), _ptr(dx), _ptr(db),
+                                                   _ptr(ws), _nbytes(ws), _stream(stream)), "ngc_conv3d_bwd_data_relu_db", check)
+
+
+def ngc_conv3d_bias_grad(desc, dy, db, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv3d_bias_grad(ctypes.byref(desc), _ptr(dy), _ptr(db), _ptr(ws), _nbytes(ws),
+                                            _stream(stream)), "ngc_conv3d_bias_grad", check)

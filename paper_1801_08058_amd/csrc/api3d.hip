@@ -321,6 +321,23 @@ size_t workspace3(const ngc_conv3d_desc *d, int op, Variant3 v, const ngc_conv_d
     return 0;
 }
 
+// dx seen as a gradient tensor of [N, C, D*H, W]: its channel sums are a rank-2 bias gradient
+ngc_conv_desc dx_as_dy3(const ngc_conv3d_desc *d)
+{
+    ngc_conv_desc t;
+    memset(&t, 0, sizeof(t));
+    t.n = d->n; t.c = 1; t.h = d->d * d->h; t.w = d->w; t.k = d->c; t.r = t.s = 1;
+    t.stride_h = t.stride_w = t.dil_h = t.dil_w = 1;
+    t.dtype = d->dtype; t.x_layout = d->x_layout; t.y_layout = d->x_layout;
+    return t;
+}
+
+size_t db3_partial_bytes(const ngc_conv3d_desc *d)
+{
+    const ngc_conv_desc t = dx_as_dy3(d);
+    return round256_3((size_t)bias_grad_parts(t, t.h, t.w) * ((d->c + 15) / 16 * 16) * sizeof(float));
+}
+
 void fill_class3(IgemmClass &c, int oa_d, int oa_h, int oa_w, int OD, int OP, int OQ, int tap_begin, int tap_count, int N)
 {
     c.oa_d = oa_d; c.oa_h = oa_h; c.oa_w = oa_w;
@@ -352,6 +369,18 @@ size_t ngc_conv3d_workspace_bytes(const ngc_conv3d_desc *desc, int op)
 {
     int O, P, Q;
     if (validate3(desc, &O, &P, &Q) != NGC_OK) return 0;
+    if (op == NGC_OP_BIAS_GRAD) {
+        ngc_conv_desc t;
+        memset(&t, 0, sizeof(t));
+        t.n = desc->n; t.k = desc->k; t.dtype = desc->dtype; t.y_layout = desc->y_layout;
+        return round256_3((size_t)bias_grad_parts(t, O * P, Q) * ((desc->k + 15) / 16 * 16) * sizeof(float));
+    }
+    if (op == NGC_OP_BWD_DATA_DB) {
+        ngc_conv_desc r2t;
+        const Variant3 vb = pick3(desc, NGC_OP_BWD_DATA, &r2t);
+        if (vb == V3_INVALID || vb == V3_UNSUPPORTED) return 0;
+        return ngc_conv3d_workspace_bytes(desc, NGC_OP_BWD_DATA) + db3_partial_bytes(desc);
+    }
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, op, &r2);
     if (v == V3_INVALID || v == V3_UNSUPPORTED) return 0;
@@ -465,20 +494,27 @@ int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, co
     return status3(launch_igemm3(p, v == V3_IGEMM_128 ? 128 : 64, p.cls[0].M, st));
 }
 
-int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
-                        void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// ConvolutionBackpropData; mask (may be null): same shape / layout / type as dx, dx = (mask > 0) ? dx : 0
+int bwd_data3_core(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *mask, void *dx, void *ws,
+                   size_t ws_bytes, void *hip_stream)
 {
     int O, P, Q;
     const int vs = validate3(desc, &O, &P, &Q);
     if (vs != NGC_OK) return vs;
     if (!dy || !w || !dx) return NGC_BAD_ARG;
-    if (!aligned16_3(dy) || !aligned16_3(w) || !aligned16_3(dx) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    if (!aligned16_3(dy) || !aligned16_3(w) || !aligned16_3(dx) || !aligned16_3(ws) || !aligned16_3(mask)) return NGC_BAD_ARG;
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, NGC_OP_BWD_DATA, &r2);
-    if (v == V3_RANK2) return ngc_conv_bwd_data(&r2, dy, w, dx, ws, ws_bytes, hip_stream);
+    if (v == V3_RANK2)
+        return mask ? ngc_conv_bwd_data_relu(&r2, dy, w, mask, dx, ws, ws_bytes, hip_stream)
+                    : ngc_conv_bwd_data(&r2, dy, w, dx, ws, ws_bytes, hip_stream);
     if (v == V3_UNSUPPORTED) return NGC_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (v == V3_DIRECT) return status3(launch_direct3_bwd_data(*desc, O, P, Q, dy, w, dx, st));
+    if (v == V3_DIRECT) return status3(launch_direct3_bwd_data(*desc, O, P, Q, dy, w, mask, dx, st));
 
     const size_t need = workspace3(desc, NGC_OP_BWD_DATA, v, nullptr, O, P, Q);
     if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
@@ -510,6 +546,7 @@ int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void 
                 sp.in = static_cast<const uint16_t *>(dy);
                 sp.wt = static_cast<const uint16_t *>(wt);
                 sp.out = static_cast<uint16_t *>(dx);
+                sp.mask = static_cast<const uint16_t *>(mask);
                 mp.c[i] = sp;
                 mp.wg_end[i] = (i ? mp.wg_end[i - 1] : 0) + sp.groups * sp.strips;
                 if (pl.l[first + i].nf > nf_max) nf_max = pl.l[first + i].nf;
@@ -525,6 +562,7 @@ int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void 
     p.in = static_cast<const uint16_t *>(dy);
     p.wt = static_cast<const uint16_t *>(wt);
     p.out = static_cast<uint16_t *>(dx);
+    p.mask = static_cast<const uint16_t *>(mask);
     p.N = desc->n; p.Cin = desc->k; p.Din = O; p.Hin = P; p.Win = Q;
     p.Cout = desc->c; p.Dout = desc->d; p.Hout = desc->h; p.Wout = desc->w;
     const int sd = desc->stride_d, sh = desc->stride_h, sw = desc->stride_w;
@@ -565,6 +603,68 @@ int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void 
                 if (cl.M > max_m) max_m = cl.M;
             }
     return status3(launch_igemm3(p, v == V3_IGEMM_128 ? 128 : 64, max_m, st));
+}
+
+// db (may be null): [C] fp32 channel sums of the dx written, from a second pass over dx whose partials sit
+// in the workspace behind the backprop-data part
+int bwd_data3_impl(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *mask, void *dx, float *db, void *ws,
+                   size_t ws_bytes, void *hip_stream)
+{
+    if (!db) return bwd_data3_core(desc, dy, w, mask, dx, ws, ws_bytes, hip_stream);
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!aligned16_3(db) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    if ((size_t)desc->n * desc->d * desc->h * desc->w >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
+    const size_t base = ngc_conv3d_workspace_bytes(desc, NGC_OP_BWD_DATA);
+    const size_t need = base + db3_partial_bytes(desc);
+    if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;
+    const int rc = bwd_data3_core(desc, dy, w, mask, dx, ws, base, hip_stream);
+    if (rc != NGC_OK) return rc;
+    const ngc_conv_desc t = dx_as_dy3(desc);
+    float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
+    return status3(launch_bias_grad(t, t.h, t.w, dx, db, partial, bias_grad_parts(t, t.h, t.w), static_cast<hipStream_t>(hip_stream)));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ngc_conv3d_bwd_data(const ngc_conv3d_desc *desc, const void *dy, const void *w, void *dx, void *ws, size_t ws_bytes,
+                        void *hip_stream)
+{
+    return bwd_data3_impl(desc, dy, w, nullptr, dx, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int ngc_conv3d_bwd_data_relu(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *x_in, void *dx, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
+    if (!x_in) return NGC_BAD_ARG;
+    return bwd_data3_impl(desc, dy, w, x_in, dx, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int ngc_conv3d_bwd_data_relu_db(const ngc_conv3d_desc *desc, const void *dy, const void *w, const void *x_in, void *dx, float *db,
+                                void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!x_in || !db) return NGC_BAD_ARG;
+    return bwd_data3_impl(desc, dy, w, x_in, dx, db, ws, ws_bytes, hip_stream);
+}
+
+int ngc_conv3d_bias_grad(const ngc_conv3d_desc *desc, const void *dy, float *db, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int O, P, Q;
+    const int vs = validate3(desc, &O, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!dy || !db || !ws) return dy && db ? NGC_WORKSPACE_TOO_SMALL : NGC_BAD_ARG;
+    if (!aligned16_3(dy) || !aligned16_3(db) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    if ((size_t)desc->n * O * P * Q >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
+    if (ws_bytes < ngc_conv3d_workspace_bytes(desc, NGC_OP_BIAS_GRAD)) return NGC_WORKSPACE_TOO_SMALL;
+    // dy [N, K, O, P, Q] keeps (o, p, q) contiguous in both layouts: the rank-2 reduction over [N, K, O*P, Q]
+    ngc_conv_desc t;
+    memset(&t, 0, sizeof(t));
+    t.n = desc->n; t.k = desc->k; t.dtype = desc->dtype; t.y_layout = desc->y_layout;
+    return status3(launch_bias_grad(t, O * P, Q, dy, db, static_cast<float *>(ws), bias_grad_parts(t, O * P, Q),
+                                    static_cast<hipStream_t>(hip_stream)));
 }
 
 int ngc_conv3d_bwd_filters(const ngc_conv3d_desc *desc, const void *x, const void *dy, float *dw, void *ws, size_t ws_bytes,

@@ -434,8 +434,8 @@ hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const vo
                                   const void *mask, void *dx, hipStream_t st);
 hipError_t launch_direct3_fwd(const ngc_conv3d_desc &d, int O, int P, int Q, const void *x, const void *w, const float *bias,
                               void *y, hipStream_t st);
-hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, void *dx,
-                                   hipStream_t st);
+hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, const void *mask,
+                                   void *dx, hipStream_t st);
 hipError_t launch_direct3_bwd_filters(const ngc_conv3d_desc &d, int O, int P, int Q, const void *x, const void *dy, float *dw,
                                       hipStream_t st);
 int gemm1x1_dbp_tile_m(const Gemm1x1Params &p);

@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void direct3_fwd(ngc_conv3d_desc d, int O, int
 
 template <typename T>
 __global__ __launch_bounds__(256) void direct3_bwd_data(ngc_conv3d_desc d, int O, int P, int Q, const T *__restrict__ dy,
-                                                        const T *__restrict__ w, T *__restrict__ dx, size_t total)
+                                                        const T *__restrict__ w, const T *__restrict__ mask, T *__restrict__ dx,
+                                                        size_t total)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
@@ -101,6 +102,7 @@ __global__ __launch_bounds__(256) void direct3_bwd_data(ngc_conv3d_desc d, int O
                 }
             }
     }
+    if (mask && !(ld3(mask, i) > 0.f)) acc = 0.f;         // ReLU backprop: same shape / layout as dx
     st3(dx, i, acc);
 }
 
@@ -159,17 +161,17 @@ hipError_t launch_direct3_fwd(const ngc_conv3d_desc &d, int O, int P, int Q, con
     return hipGetLastError();
 }
 
-hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, void *dx,
-                                   hipStream_t stm)
+hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, const void *mask,
+                                   void *dx, hipStream_t stm)
 {
     const size_t total = phys3(d.x_layout, d.n, d.c, d.d, d.h, d.w);
     const unsigned blocks = (unsigned)((total + 255) / 256);
     if (d.dtype == NGC_F32)
         NGC_LAUNCH(direct3_bwd_data<float>, dim3(blocks), dim3(256), 0, stm, d, O, P, Q, static_cast<const float *>(dy),
-                   static_cast<const float *>(w), static_cast<float *>(dx), total);
+                   static_cast<const float *>(w), static_cast<const float *>(mask), static_cast<float *>(dx), total);
     else
         NGC_LAUNCH(direct3_bwd_data<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, O, P, Q, static_cast<const uint16_t *>(dy),
-                   static_cast<const uint16_t *>(w), static_cast<uint16_t *>(dx), total);
+                   static_cast<const uint16_t *>(w), static_cast<const uint16_t *>(mask), static_cast<uint16_t *>(dx), total);
     return hipGetLastError();
 }
 

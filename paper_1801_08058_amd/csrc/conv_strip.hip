@@ -450,7 +450,7 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
     if constexpr (SUB == 0 && NW == 8) {
         if (p.ncolt > 1 && p.dbp) return hipErrorInvalidValue;
         if (p.r3) {
-            if (p.dbp || p.mask) return hipErrorInvalidValue;
+            if (p.dbp) return hipErrorInvalidValue;
             if (p.ncolt > 1) return launch_strip_d<NF, NW, SUB, false, true, true>(p, lds_bytes, st);
             return launch_strip_d<NF, NW, SUB, false, true>(p, lds_bytes, st);
         }

@@ -284,3 +284,37 @@ class Run3:
         torch.cuda.synchronize()
         self.last_desc = d
         return dw.cpu().numpy().astype(np.float64).reshape(a.k, a.c, a.t, a.r, a.s)
+
+
+def _run3_bwd_data_relu(self, dy, w, x_in, with_db=False):
+    """ConvolutionBackpropData compounded with the backprop of the ReLU that produced x_in (and, with_db, the channel
+    sums of the dx written)."""
+    a = self.a
+    wd, wl = self._filter(w, ng.NGC_BLOCKED_BWD)
+    d = desc3_of(a, self.dtype, self.xl, self.yl, wl)
+    dyd = data3_to_device(dy, self.dtype, self.yl)
+    xin = data3_to_device(x_in, self.dtype, self.xl)
+    dx = poisoned(ng.ngc_conv3d_data_elems(d, 0), self.dtype)
+    self.last_desc = d
+    if with_db:
+        db = torch.full((a.c,), float("nan"), dtype=torch.float32, device="cuda")
+        ng.ngc_conv3d_bwd_data_relu_db(d, dyd, wd, xin, dx, db, self._ws(d, ng.NGC_OP_BWD_DATA_DB), stream())
+        torch.cuda.synchronize()
+        return (data3_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.d, a.h, a.w)), db.cpu().numpy().astype(np.float64))
+    ng.ngc_conv3d_bwd_data_relu(d, dyd, wd, xin, dx, self._ws(d, ng.NGC_OP_BWD_DATA), stream())
+    torch.cuda.synchronize()
+    return data3_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.d, a.h, a.w))
+
+
+def _run3_bias_grad(self, dy):
+    a = self.a
+    d = desc3_of(a, self.dtype, self.xl, self.yl)
+    dyd = data3_to_device(dy, self.dtype, self.yl)
+    db = torch.full((a.k,), float("nan"), dtype=torch.float32, device="cuda")
+    ng.ngc_conv3d_bias_grad(d, dyd, db, self._ws(d, ng.NGC_OP_BIAS_GRAD), stream())
+    torch.cuda.synchronize()
+    return db.cpu().numpy().astype(np.float64)
+
+
+Run3.bwd_data_relu = _run3_bwd_data_relu
+Run3.bias_grad = _run3_bias_grad

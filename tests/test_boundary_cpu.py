@@ -354,3 +354,20 @@ def test_wide_rows_stay_on_the_strip_kernel():
     # the temporal window of a video layer as the rank-2 node it is
     t = ng.make_desc3(2, 64, 16, 56, 56, 64, 3, 1, 1, pad_below=(1, 0, 0), pad_above=(1, 0, 0), w_layout=ng.NGC_BLOCKED_FWD)
     assert ng.ngc_conv3d_variant(t, F) == "rank2:strip_bf16"
+
+
+def test_conv3d_backward_compounds_validate_before_launch():
+    d = _good3()
+    B, DB, BG = ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_DATA_DB, ng.NGC_OP_BIAS_GRAD
+    assert ng.ngc_conv3d_workspace_bytes(d, DB) > ng.ngc_conv3d_workspace_bytes(d, B) > 0
+    assert ng.ngc_conv3d_workspace_bytes(d, BG) > 0
+    assert ng.ngc_conv3d_bwd_data_relu(d, 4096, 4096, None, 4096, None, check=False) == ng.NGC_BAD_ARG          # no x_in
+    assert ng.ngc_conv3d_bwd_data_relu(d, 4096, 4096, 4100, 4096, None, check=False) == ng.NGC_BAD_ARG          # misaligned
+    assert ng.ngc_conv3d_bwd_data_relu(d, 4096, 4096, 4096, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv3d_bwd_data_relu_db(d, 4096, 4096, 4096, 4096, None, None, check=False) == ng.NGC_BAD_ARG  # no db
+    assert ng.ngc_conv3d_bwd_data_relu_db(d, 4096, 4096, 4096, 4096, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    assert ng.ngc_conv3d_bias_grad(d, 4096, None, None, check=False) == ng.NGC_BAD_ARG
+    assert ng.ngc_conv3d_bias_grad(d, 4096, 4096, None, check=False) == ng.NGC_WORKSPACE_TOO_SMALL
+    bad = _good3(d=0)
+    assert ng.ngc_conv3d_bwd_data_relu_db(bad, 4096, 4096, 4096, 4096, 4096, None, check=False) == ng.NGC_BAD_SHAPE
+    assert ng.ngc_conv3d_bias_grad(bad, 4096, 4096, 4096, check=False) == ng.NGC_BAD_SHAPE

@@ -38,8 +38,23 @@ def _check3(a: Attrs3, dtype: str, xl: int, yl: int, pre: bool, seed: int, expec
     dx = run.bwd_data(dy, w)
     if expect:
         assert ng.ngc_conv3d_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(expect[1]), ng.ngc_conv3d_variant(run.last_desc, 1)
-    e = oracle.max_normalised_error(dx, oracle.conv3d_bwd_data(a, dy, w))
+    ref_dx = oracle.conv3d_bwd_data(a, dy, w)
+    e = oracle.max_normalised_error(dx, ref_dx)
     assert e <= tol, f"bwd_data err {e}"
+    # the backward compounds: ReLU backprop of the data input (x doubles as that input: about half of it is <= 0),
+    # the channel sums of the dx the device stored, and the bias gradient
+    dxr = run.bwd_data_relu(dy, w, x)
+    e = oracle.max_normalised_error(dxr, oracle.relu_bwd_mask(ref_dx, x))
+    assert e <= tol, f"bwd_data_relu err {e}"
+    blocked = ~(x > 0)
+    assert np.all(dxr[blocked] == 0) and not np.signbit(dxr[blocked]).any(), "gradient leaked through x_in <= 0"
+    dx2, dbp = run.bwd_data_relu(dy, w, x, with_db=True)
+    assert np.array_equal(dx2, dxr)
+    e = oracle.max_normalised_error(dbp, oracle.bias_grad(dxr.reshape(a.n, a.c, a.d * a.h, a.w)))
+    assert e <= 1e-5, f"bwd_data_relu_db err {e}"
+    db = run.bias_grad(dy)
+    e = oracle.max_normalised_error(db, oracle.bias_grad(dy.reshape(a.n, a.k, -1, dy.shape[-1])))
+    assert e <= 1e-5, f"bias_grad err {e}"
     dw = run.bwd_filters(x, dy)
     if expect:
         assert ng.ngc_conv3d_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS).startswith(expect[2]), ng.ngc_conv3d_variant(run.last_desc, 2)
