@@ -40,7 +40,8 @@
  *     which no kernel exists returns NGC_UNSUPPORTED; there is no CPU fallback.
  *   - Accumulation is always fp32.  bf16 results are rounded once, to nearest even.
  *   - Results are run-to-run identical (no floating-point atomics).
- *   - Each tensor must hold fewer than 2^31 elements.
+ *   - Each tensor must hold fewer than 2^31 elements.  A bf16 node with blocked tensors whose x or y
+ *     reaches 2 GiB runs as several launches over groups of images (ngc_conv_variant: "sliced:...").
  *
  * Every op accepts every combination of data layouts; which combinations run on the MFMA kernels
  * (bf16) and which on the slow direct kernels is a property of the build: blocked x and y for all

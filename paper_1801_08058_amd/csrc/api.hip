@@ -59,6 +59,34 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// Forward and backprop-data treat the images of a batch independently.  The MFMA kernels address an operand with
+// 32-bit byte offsets, so a bf16 node with blocked tensors whose x or y has 2 GiB or more runs as several
+// launches over groups of images that stay below.  Returns the images per group (d->n: one launch).
+struct BatchSlices {
+    int images;                // per group
+    size_t x_bytes, y_bytes;   // of one image
+};
+
+BatchSlices batch_slices(const ngc_conv_desc *d, int P, int Q)
+{
+    BatchSlices b;
+    b.images = d->n;
+    b.x_bytes = phys(d->x_layout, 1, d->c, d->h, d->w) * 2;
+    b.y_bytes = phys(d->y_layout, 1, d->k, P, Q) * 2;
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW16C || d->y_layout != NGC_NCHW16C) return b;
+    const size_t per = b.x_bytes > b.y_bytes ? b.x_bytes : b.y_bytes, lim = (size_t)1 << 31;
+    if ((size_t)d->n * per < lim || per >= lim) return b;             // small enough, or one image alone is too large
+    b.images = (int)((lim - 1) / per);
+    return b;
+}
+
+ngc_conv_desc with_batch(const ngc_conv_desc *d, int n)
+{
+    ngc_conv_desc t = *d;
+    t.n = n;
+    return t;
+}
+
 enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1 };
 
 constexpr int NUM_CUS = 256;                      // MI355X
@@ -911,6 +939,24 @@ size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
 {
     int P, Q;
     if (validate(desc, &P, &Q) != NGC_OK) return 0;
+    const BatchSlices bs = batch_slices(desc, P, Q);
+    if (bs.images < desc->n && op == NGC_OP_BWD_FILTERS) {
+        // one dw per group of images behind the workspace of a group's launch, added up in index order at the end
+        const ngc_conv_desc g = with_batch(desc, bs.images);
+        const size_t groups = (size_t)(desc->n + bs.images - 1) / bs.images;
+        const size_t row = ((size_t)desc->k * desc->c * desc->r * desc->s + 15) / 16 * 16;
+        return round256(workspace_bytes(&g, op, pick(&g, op), P, Q)) + round256(groups * row * sizeof(float));
+    }
+    if (bs.images < desc->n && (op == NGC_OP_FWD || op == NGC_OP_BWD_DATA || op == NGC_OP_BWD_DATA_DB)) {
+        // the launches of the groups reuse one workspace (the first group is the largest); the channel sums come
+        // from a second pass over the whole dx
+        const ngc_conv_desc g = with_batch(desc, bs.images);
+        const int gop = op == NGC_OP_FWD ? NGC_OP_FWD : NGC_OP_BWD_DATA;
+        const size_t base = workspace_bytes(&g, gop, pick(&g, gop), P, Q);
+        if (op != NGC_OP_BWD_DATA_DB) return base;
+        const ngc_conv_desc t = dx_as_dy(desc);
+        return base + round256((size_t)bias_grad_parts(t, desc->h, desc->w) * ((desc->c + 15) / 16 * 16) * sizeof(float));
+    }
     return workspace_bytes(desc, op, pick(desc, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op), P, Q);
 }
 
@@ -920,6 +966,19 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
         int P, Q;
         if (validate(desc, &P, &Q) != NGC_OK) return "invalid";
         return (desc->dtype == NGC_BF16 && desc->y_layout == NGC_NCHW16C) ? "bias_grad_blocked_bf16" : "bias_grad_generic";
+    }
+    {
+        int P, Q;
+        if (validate(desc, &P, &Q) == NGC_OK &&
+            (op == NGC_OP_FWD || op == NGC_OP_BWD_DATA || op == NGC_OP_BWD_DATA_DB || op == NGC_OP_BWD_FILTERS)) {
+            const BatchSlices bs = batch_slices(desc, P, Q);
+            if (bs.images < desc->n) {                       // groups of images: the kernel of a group
+                static thread_local char name[64];
+                const ngc_conv_desc g = with_batch(desc, bs.images);
+                snprintf(name, sizeof(name), "sliced:%s", ngc_conv_variant(&g, op));
+                return name;
+            }
+        }
     }
     switch (pick(desc, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op)) {
     case V_UNSUPPORTED: return "unsupported";
@@ -960,6 +1019,16 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
     if (!x || !w || !y) return NGC_BAD_ARG;
     if ((desc->epilogue & NGC_EPI_BIAS) && !bias) return NGC_BAD_ARG;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(ws)) return NGC_BAD_ARG;
+    const BatchSlices bs = batch_slices(desc, P, Q);
+    if (bs.images < desc->n) {                                // operands of 2 GiB or more: one launch per group of images
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images) {
+            const ngc_conv_desc g = with_batch(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const int rc = ngc_conv_fwd(&g, static_cast<const unsigned char *>(x) + (size_t)n0 * bs.x_bytes, w, bias,
+                                        static_cast<unsigned char *>(y) + (size_t)n0 * bs.y_bytes, ws, ws_bytes, hip_stream);
+            if (rc != NGC_OK) return rc;
+        }
+        return NGC_OK;
+    }
     const Variant v = pick(desc, NGC_OP_FWD);
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1201,10 +1270,32 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
 int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, const void *mask, void *dx, float *db, void *ws,
                   size_t ws_bytes, void *hip_stream)
 {
-    if (!db) return bwd_data_core(desc, dy, w, mask, dx, ws, ws_bytes, hip_stream, nullptr);
     int P, Q;
     const int vs = validate(desc, &P, &Q);
     if (vs != NGC_OK) return vs;
+    const BatchSlices bs = batch_slices(desc, P, Q);
+    if (bs.images < desc->n) {                                // operands of 2 GiB or more: one launch per group of images
+        if (!dy || !w || !dx) return NGC_BAD_ARG;
+        if (!aligned16(db) || !aligned16(ws)) return NGC_BAD_ARG;
+        if (db && (size_t)desc->n * desc->h * desc->w >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
+        const size_t base = ngc_conv_workspace_bytes(desc, NGC_OP_BWD_DATA);
+        const size_t need = db ? ngc_conv_workspace_bytes(desc, NGC_OP_BWD_DATA_DB) : base;
+        if (need > 0 && (!ws || ws_bytes < need)) return NGC_WORKSPACE_TOO_SMALL;
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images) {
+            const ngc_conv_desc g = with_batch(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const size_t xo = (size_t)n0 * bs.x_bytes, yo = (size_t)n0 * bs.y_bytes;
+            const int rc = bwd_data_core(&g, static_cast<const unsigned char *>(dy) + yo, w,
+                                         mask ? static_cast<const unsigned char *>(mask) + xo : nullptr,
+                                         static_cast<unsigned char *>(dx) + xo, ws, base, hip_stream, nullptr);
+            if (rc != NGC_OK) return rc;
+        }
+        if (!db) return NGC_OK;
+        const ngc_conv_desc t = dx_as_dy(desc);               // channel sums: a pass over the whole dx
+        float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
+        return launch_status(launch_bias_grad(t, desc->h, desc->w, dx, db, partial, bias_grad_parts(t, desc->h, desc->w),
+                                              static_cast<hipStream_t>(hip_stream)));
+    }
+    if (!db) return bwd_data_core(desc, dy, w, mask, dx, ws, ws_bytes, hip_stream, nullptr);
     if (!aligned16(db) || !aligned16(ws)) return NGC_BAD_ARG;
     if ((size_t)desc->n * desc->h * desc->w >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
     const Variant v = pick(desc, NGC_OP_BWD_DATA);
@@ -1310,8 +1401,26 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
     if (vs != NGC_OK) return vs;
     if (!x || !dy || !dw) return NGC_BAD_ARG;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(ws)) return NGC_BAD_ARG;
-    const Variant v = pick(desc, NGC_OP_BWD_FILTERS);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const BatchSlices bs = batch_slices(desc, P, Q);
+    if (bs.images < desc->n) {
+        // operands of 2 GiB or more: dw of each group of images into the workspace, then their sum in index order
+        const ngc_conv_desc g0 = with_batch(desc, bs.images);
+        const size_t base = round256(workspace_bytes(&g0, NGC_OP_BWD_FILTERS, pick(&g0, NGC_OP_BWD_FILTERS), P, Q));
+        if (!ws || ws_bytes < ngc_conv_workspace_bytes(desc, NGC_OP_BWD_FILTERS)) return NGC_WORKSPACE_TOO_SMALL;
+        const int elems = desc->k * desc->c * desc->r * desc->s, row = (elems + 15) / 16 * 16;
+        float *rows = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
+        int groups = 0;
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images, ++groups) {
+            const ngc_conv_desc g = with_batch(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const int rc = ngc_conv_bwd_filters(&g, static_cast<const unsigned char *>(x) + (size_t)n0 * bs.x_bytes,
+                                                static_cast<const unsigned char *>(dy) + (size_t)n0 * bs.y_bytes,
+                                                rows + (size_t)groups * row, ws, base, hip_stream);
+            if (rc != NGC_OK) return rc;
+        }
+        return launch_status(launch_bias_grad_reduce(rows, dw, groups, elems, row, st));
+    }
+    const Variant v = pick(desc, NGC_OP_BWD_FILTERS);
     if (v == V_DIRECT) return launch_status(launch_direct_bwd_filters(*desc, P, Q, x, dy, dw, st));
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);

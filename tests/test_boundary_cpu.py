@@ -371,3 +371,21 @@ def test_conv3d_backward_compounds_validate_before_launch():
     bad = _good3(d=0)
     assert ng.ngc_conv3d_bwd_data_relu_db(bad, 4096, 4096, 4096, 4096, 4096, None, check=False) == ng.NGC_BAD_SHAPE
     assert ng.ngc_conv3d_bias_grad(bad, 4096, 4096, 4096, check=False) == ng.NGC_BAD_SHAPE
+
+
+def test_operands_past_two_gib_run_in_groups_of_images():
+    """A bf16 node with blocked tensors whose x or y reaches 2 GiB keeps its kernels: the library launches them over
+    groups of images that stay below (workspace of one group; backprop-filters adds one dw per group)."""
+    F, B, W, DB = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS, ng.NGC_OP_BWD_DATA_DB
+    big = ng.make_desc(68, 64, 500, 500, 64, 3, 3, pad_below=(1, 1), pad_above=(1, 1))
+    grp = ng.make_desc(67, 64, 500, 500, 64, 3, 3, pad_below=(1, 1), pad_above=(1, 1))       # 67 images: 2^31 - 3.4 MB
+    assert [ng.ngc_conv_variant(big, op) for op in (F, B, W)] == ["sliced:" + ng.ngc_conv_variant(grp, op) for op in (F, B, W)]
+    assert ng.ngc_conv_variant(grp, F) == "strip_bf16"
+    assert ng.ngc_conv_workspace_bytes(big, F) == ng.ngc_conv_workspace_bytes(grp, F)
+    assert ng.ngc_conv_workspace_bytes(big, W) > ng.ngc_conv_workspace_bytes(grp, W)
+    assert ng.ngc_conv_workspace_bytes(big, DB) > ng.ngc_conv_workspace_bytes(big, B)
+    # NCHW tensors and fp32 are not sliced: the kernels that take them index with 64 bits
+    assert not ng.ngc_conv_variant(ng.make_desc(68, 64, 500, 500, 64, 3, 3, x_layout=ng.NGC_NCHW), F).startswith("sliced")
+    # one image of 2 GiB: nothing to slice
+    one = ng.make_desc(1, 64, 4100, 4100, 64, 3, 3)
+    assert ng.ngc_conv_variant(one, F) == "igemm_bf16_256x64"

@@ -1,7 +1,8 @@
 """Tensors of more than 2^31 bytes (just over 10^9 elements; the boundary allows fewer than 2^31 elements): the
-kernels that address with 32-bit byte offsets must hand such nodes on, and the ones that take them must index
-past 2 GiB correctly.  The batch is a seeded 4-image tensor repeated 17 times, so every image of the result has a
-twin in the first four, which are checked against the oracle on sampled elements."""
+kernels that address with 32-bit byte offsets run forward / backprop-data over groups of images that stay below
+2 GiB, backprop-filters adds up the dw of such groups; all must index past 2 GiB correctly.  The
+batch is a seeded 4-image tensor repeated 17 times, so every image of the result has a twin in the first four,
+which are checked against the oracle on sampled elements."""
 import numpy as np
 import pytest
 import torch
@@ -40,7 +41,7 @@ def test_three_ops_on_tensors_past_two_gib():
     d = mk(n, ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU)
     names = [ng.ngc_conv_variant(d, op) for op in (ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS)]
     print("variants", names, flush=True)
-    assert not any(v in ("unsupported", "invalid", "direct") for v in names)
+    assert names == ["sliced:strip_bf16", "sliced:strip_bf16", "sliced:wgrad_gemm_bf16"], names
     ws = lambda dd, op: torch.empty(max(ng.ngc_conv_workspace_bytes(dd, op), 16), dtype=torch.uint8, device="cuda")
     g = np.random.default_rng(5)
 
@@ -63,6 +64,15 @@ def test_three_ops_on_tensors_past_two_gib():
     ng.ngc_conv_bwd_data(d, dyd, wd, dx, ws(d, ng.NGC_OP_BWD_DATA), stream())
     torch.cuda.synchronize()
     check_twins_and_samples(dx, lambda idx: oracle.conv_bwd_data_at(a1, dy1, wt, idx), "bwd_data")
+    # the compound: ReLU backprop of the data input and the channel sums of the dx written (a pass over all of dx)
+    db = torch.full((c,), float("nan"), dtype=torch.float32, device="cuda")
+    ng.ngc_conv_bwd_data_relu_db(d, dyd, wd, xd, dx, db, ws(d, ng.NGC_OP_BWD_DATA_DB), stream())
+    torch.cuda.synchronize()
+    keep = (x1 > 0).reshape(-1)
+    check_twins_and_samples(dx, lambda idx: oracle.conv_bwd_data_at(a1, dy1, wt, idx) * keep[idx], "bwd_data_relu")
+    first = oracle.bf16_bits_to_f64(oracle.blocked16_to_nchw(host(dx, np.uint16).reshape(REPS, PERIOD, -1)[0].reshape(PERIOD, 4, h, w, 16), 64))
+    want = REPS * oracle.bias_grad(first)
+    assert np.abs(db.cpu().numpy() - want).max() / np.abs(want).max() <= 1e-5
     del dx
     # backprop-filters sums over the batch: 17 repetitions = 17 x the 4-image node
     dw = torch.empty(k * c * 9, dtype=torch.float32, device="cuda")
