@@ -78,6 +78,34 @@ int status3(hipError_t e)
     return NGC_LAUNCH_FAILED;
 }
 
+// Images per launch for operands of 2 GiB or more (bf16, blocked tensors): the ops treat the images of a batch
+// independently (backprop-filters up to a final sum), and the MFMA kernels address an operand with 32-bit byte
+// offsets.  images == d->n: one launch.
+struct BatchSlices3 {
+    int images;
+    size_t x_bytes, y_bytes;   // of one image
+};
+
+BatchSlices3 batch_slices3(const ngc_conv3d_desc *d, int O, int P, int Q)
+{
+    BatchSlices3 b;
+    b.images = d->n;
+    b.x_bytes = phys3(d->x_layout, 1, d->c, d->d, d->h, d->w) * 2;
+    b.y_bytes = phys3(d->y_layout, 1, d->k, O, P, Q) * 2;
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW16C || d->y_layout != NGC_NCHW16C) return b;
+    const size_t per = b.x_bytes > b.y_bytes ? b.x_bytes : b.y_bytes, lim = (size_t)1 << 31;
+    if ((size_t)d->n * per < lim || per >= lim) return b;
+    b.images = (int)((lim - 1) / per);
+    return b;
+}
+
+ngc_conv3d_desc with_batch3(const ngc_conv3d_desc *d, int n)
+{
+    ngc_conv3d_desc t = *d;
+    t.n = n;
+    return t;
+}
+
 bool idle_axis(int taps, int stride, int below, int above) { return taps == 1 && stride == 1 && below == 0 && above == 0; }
 
 // The rank-2 node this node equals on a reshaped tensor, if there is one.
@@ -381,6 +409,16 @@ size_t ngc_conv3d_workspace_bytes(const ngc_conv3d_desc *desc, int op)
         if (vb == V3_INVALID || vb == V3_UNSUPPORTED) return 0;
         return ngc_conv3d_workspace_bytes(desc, NGC_OP_BWD_DATA) + db3_partial_bytes(desc);
     }
+    const BatchSlices3 bs = batch_slices3(desc, O, P, Q);
+    if (bs.images < desc->n && (op == NGC_OP_FWD || op == NGC_OP_BWD_DATA || op == NGC_OP_BWD_FILTERS)) {
+        // groups of images reuse one workspace; backprop-filters keeps one dw per group behind it
+        const ngc_conv3d_desc g = with_batch3(desc, bs.images);
+        const size_t base = ngc_conv3d_workspace_bytes(&g, op);
+        if (op != NGC_OP_BWD_FILTERS) return base;
+        const size_t groups = (size_t)(desc->n + bs.images - 1) / bs.images;
+        const size_t row = ((size_t)desc->k * desc->c * desc->t * desc->r * desc->s + 15) / 16 * 16;
+        return round256_3(base) + round256_3(groups * row * sizeof(float));
+    }
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, op, &r2);
     if (v == V3_INVALID || v == V3_UNSUPPORTED) return 0;
@@ -420,6 +458,18 @@ const char *ngc_conv3d_variant(const ngc_conv3d_desc *desc, int op)
 {
     static thread_local char name[96];
     ngc_conv_desc r2;
+    {
+        int O, P, Q;
+        if (validate3(desc, &O, &P, &Q) == NGC_OK && (op == NGC_OP_FWD || op == NGC_OP_BWD_DATA || op == NGC_OP_BWD_FILTERS)) {
+            const BatchSlices3 bs = batch_slices3(desc, O, P, Q);
+            if (bs.images < desc->n) {                       // groups of images: the kernel of a group
+                static thread_local char sliced[112];
+                const ngc_conv3d_desc g = with_batch3(desc, bs.images);
+                snprintf(sliced, sizeof(sliced), "sliced:%s", ngc_conv3d_variant(&g, op));
+                return sliced;
+            }
+        }
+    }
     switch (pick3(desc, op, &r2)) {
     case V3_RANK2: snprintf(name, sizeof(name), "rank2:%s", ngc_conv_variant(&r2, op)); return name;
     case V3_STRIP: return "strip3_bf16";
@@ -441,6 +491,16 @@ int ngc_conv3d_fwd(const ngc_conv3d_desc *desc, const void *x, const void *w, co
     if (!x || !w || !y) return NGC_BAD_ARG;
     if ((desc->epilogue & NGC_EPI_BIAS) && !bias) return NGC_BAD_ARG;
     if (!aligned16_3(x) || !aligned16_3(w) || !aligned16_3(y) || !aligned16_3(ws) || !aligned16_3(bias)) return NGC_BAD_ARG;
+    const BatchSlices3 bs = batch_slices3(desc, O, P, Q);
+    if (bs.images < desc->n) {                                // operands of 2 GiB or more: one launch per group of images
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images) {
+            const ngc_conv3d_desc g = with_batch3(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const int rc = ngc_conv3d_fwd(&g, static_cast<const unsigned char *>(x) + (size_t)n0 * bs.x_bytes, w, bias,
+                                          static_cast<unsigned char *>(y) + (size_t)n0 * bs.y_bytes, ws, ws_bytes, hip_stream);
+            if (rc != NGC_OK) return rc;
+        }
+        return NGC_OK;
+    }
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, NGC_OP_FWD, &r2);
     if (v == V3_RANK2) return ngc_conv_fwd(&r2, x, w, bias, y, ws, ws_bytes, hip_stream);
@@ -507,6 +567,18 @@ int bwd_data3_core(const ngc_conv3d_desc *desc, const void *dy, const void *w, c
     if (vs != NGC_OK) return vs;
     if (!dy || !w || !dx) return NGC_BAD_ARG;
     if (!aligned16_3(dy) || !aligned16_3(w) || !aligned16_3(dx) || !aligned16_3(ws) || !aligned16_3(mask)) return NGC_BAD_ARG;
+    const BatchSlices3 bs = batch_slices3(desc, O, P, Q);
+    if (bs.images < desc->n) {                                // operands of 2 GiB or more: one launch per group of images
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images) {
+            const ngc_conv3d_desc g = with_batch3(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const size_t xo = (size_t)n0 * bs.x_bytes, yo = (size_t)n0 * bs.y_bytes;
+            const int rc = bwd_data3_core(&g, static_cast<const unsigned char *>(dy) + yo, w,
+                                          mask ? static_cast<const unsigned char *>(mask) + xo : nullptr,
+                                          static_cast<unsigned char *>(dx) + xo, ws, ws_bytes, hip_stream);
+            if (rc != NGC_OK) return rc;
+        }
+        return NGC_OK;
+    }
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, NGC_OP_BWD_DATA, &r2);
     if (v == V3_RANK2)
@@ -675,6 +747,24 @@ int ngc_conv3d_bwd_filters(const ngc_conv3d_desc *desc, const void *x, const voi
     if (vs != NGC_OK) return vs;
     if (!x || !dy || !dw) return NGC_BAD_ARG;
     if (!aligned16_3(x) || !aligned16_3(dy) || !aligned16_3(dw) || !aligned16_3(ws)) return NGC_BAD_ARG;
+    const BatchSlices3 bs = batch_slices3(desc, O, P, Q);
+    if (bs.images < desc->n) {
+        // operands of 2 GiB or more: dw of each group of images into the workspace, then their sum in index order
+        const ngc_conv3d_desc g0 = with_batch3(desc, bs.images);
+        const size_t base = round256_3(ngc_conv3d_workspace_bytes(&g0, NGC_OP_BWD_FILTERS));
+        if (!ws || ws_bytes < ngc_conv3d_workspace_bytes(desc, NGC_OP_BWD_FILTERS)) return NGC_WORKSPACE_TOO_SMALL;
+        const int elems = desc->k * desc->c * desc->t * desc->r * desc->s, row = (elems + 15) / 16 * 16;
+        float *rows = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);
+        int groups = 0;
+        for (int n0 = 0; n0 < desc->n; n0 += bs.images, ++groups) {
+            const ngc_conv3d_desc g = with_batch3(desc, desc->n - n0 < bs.images ? desc->n - n0 : bs.images);
+            const int rc = ngc_conv3d_bwd_filters(&g, static_cast<const unsigned char *>(x) + (size_t)n0 * bs.x_bytes,
+                                                  static_cast<const unsigned char *>(dy) + (size_t)n0 * bs.y_bytes,
+                                                  rows + (size_t)groups * row, ws, base, hip_stream);
+            if (rc != NGC_OK) return rc;
+        }
+        return status3(launch_bias_grad_reduce(rows, dw, groups, elems, row, static_cast<hipStream_t>(hip_stream)));
+    }
     ngc_conv_desc r2;
     const Variant3 v = pick3(desc, NGC_OP_BWD_FILTERS, &r2);
     if (v == V3_RANK2) return ngc_conv_bwd_filters(&r2, x, dy, dw, ws, ws_bytes, hip_stream);
