@@ -109,7 +109,7 @@ ngc_conv3d_desc with_batch3(const ngc_conv3d_desc *d, int n)
 bool idle_axis(int taps, int stride, int below, int above) { return taps == 1 && stride == 1 && below == 0 && above == 0; }
 
 // The rank-2 node this node equals on a reshaped tensor, if there is one.
-bool as_rank2(const ngc_conv3d_desc *d, int O, int P, int Q, ngc_conv_desc *out)
+bool as_rank2(const ngc_conv3d_desc *d, ngc_conv_desc *out)
 {
     const char *sw = getenv("NGC_CONV3D_RANK2");         // tests / benchmarks only: 0 = always the rank-3 kernels
     if (sw && atoi(sw) == 0) return false;
@@ -135,7 +135,6 @@ bool as_rank2(const ngc_conv3d_desc *d, int O, int P, int Q, ngc_conv_desc *out)
     } else {
         return false;
     }
-    (void)O; (void)P; (void)Q;
     *out = t;
     return true;
 }
@@ -301,7 +300,7 @@ Variant3 pick3(const ngc_conv3d_desc *d, int op, ngc_conv_desc *r2)
     if (validate3(d, &O, &P, &Q) != NGC_OK) return V3_INVALID;
     if (op != NGC_OP_FWD && op != NGC_OP_BWD_DATA && op != NGC_OP_BWD_FILTERS) return V3_INVALID;
     ngc_conv_desc t;
-    if (as_rank2(d, O, P, Q, &t)) {
+    if (as_rank2(d, &t)) {
         if (r2) *r2 = t;
         return V3_RANK2;
     }
