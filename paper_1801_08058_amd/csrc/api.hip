@@ -661,7 +661,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // multiple of 8 the two-dimensional grid spreads them over the XCDs, the XCD-ordered grid does not.  Measured
     // on the 56x56 layers of the ResNet-50 stack (126 chunks, two tiles): 64 -> 256 53.2 -> 49.7 us, 256 -> 64
     // 52.4 -> 46.9 us, but 256 -> 128 (128 x 128 tiles) 72.0 -> 75.5 us, so not for that tile shape.
-    if (d->r * d->s == 1 && tiles > 1 && q.wk * q.wc < 4 && !q.x_nchw && !q.dy_nchw && q.nparts >= 64 && q.nparts % 8 != 0) {
+    if (d->r * d->s == 1 && tiles > 1 && q.wk * q.wc < 4 && q.nparts >= 64 && q.nparts % 8 != 0) {
         const char *fx = getenv("NGC_WGG_XCD");
         if (!(fx && atoi(fx) == 0)) q.xcd_order = 1;
     }

@@ -336,10 +336,15 @@ static hipError_t launch_wgrad_gemm_t(const WgradGemmParams &p, hipStream_t st)
         if (p.x_nchw || p.dy_nchw) return hipErrorInvalidValue;
         return launch_wgrad_gemm_l<WK, WC, SP, false, false, true>(p, st);
     }
+    if (p.xcd_order) {
+        if (p.x_nchw && p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, true, false, true>(p, st);
+        if (p.x_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, false, false, true>(p, st);
+        if (p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, false, true, false, true>(p, st);
+        return launch_wgrad_gemm_l<WK, WC, SP, false, false, false, true>(p, st);
+    }
     if (p.x_nchw && p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, true>(p, st);
     if (p.x_nchw) return launch_wgrad_gemm_l<WK, WC, SP, true, false>(p, st);
     if (p.dy_nchw) return launch_wgrad_gemm_l<WK, WC, SP, false, true>(p, st);
-    if (p.xcd_order) return launch_wgrad_gemm_l<WK, WC, SP, false, false, false, true>(p, st);
     return launch_wgrad_gemm_l<WK, WC, SP, false, false>(p, st);
 }
 
