@@ -551,10 +551,19 @@ bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, 
     memset(&q, 0, sizeof(q));
     int sr = 1;
     while ((sr * Q) % 32 != 0) ++sr;                                    // <= 4 since Q % 8 == 0
-    while (2 * sr * Q <= 256 && 2 * sr <= P) sr *= 2;                   // about 224 positions per stage
+    // positions per stage (NGC_WSTEM_POS, experiments): a stage costs a load latency whatever its size
+    int stage_pos = 512;
+    const char *fp = getenv("NGC_WSTEM_POS");
+    if (fp && atoi(fp) >= 32 && atoi(fp) <= 1024) stage_pos = atoi(fp);
+    while (2 * sr * Q <= stage_pos && 2 * sr <= P) sr *= 2;
+    // the two stage buffers have to fit the LDS and the input rows 3 chunks per thread
+    while (sr > 1 && sr % 2 == 0 && ((sr / 2) * Q) % 32 == 0 &&
+           (2 * ((size_t)4 * ((sr * Q / 32) * 1024 + 128) + (size_t)d->c * (2 * sr + 5) * 2 * (d->w + 16) + 16) > LDS_LIMIT ||
+            d->c * (2 * sr + 5) * (d->w / 8) > 1536))
+        sr /= 2;
     q.SR = sr;
     const int rows_in = 2 * sr + 5;
-    if (d->c * rows_in * (d->w / 8) > 1024) return false;               // 2 x-chunks per thread
+    if (d->c * rows_in * (d->w / 8) > 1536) return false;               // 3 x-chunks per thread
     q.dyplane = (sr * Q / 32) * 1024 + 128;
     const size_t xbytes = (size_t)d->c * rows_in * 2 * (d->w + 16);
     size_t lds = 2 * ((size_t)4 * q.dyplane + ((xbytes + 15) & ~(size_t)15));

@@ -29,7 +29,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4_s;
 
 constexpr unsigned WST_OOB = 0x80000000u;
 constexpr int WST_NF = 6;            // column fragments per wave (second group uses 5)
-constexpr int WST_XCH = 2;           // 16-byte x chunks per thread per stage
+constexpr int WST_XCH = 3;           // 16-byte x chunks per thread per stage
 
 __device__ __forceinline__ bf16x8 tr_frag_s(const unsigned char *lo, const unsigned char *hi)
 {
