@@ -677,3 +677,22 @@ def test_strip_column_tiles_strided_classes_and_channel_sums():
     grid), and the channel sums of ngc_conv_bwd_data_relu_db come from the second pass."""
     a = Attrs(1, 64, 6, 2000, 64, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1)
     _check_all(a, "bf16", BLK, BLK, True, 9400, ("strip", "strip", "wgrad"))
+
+
+def test_random_wide_row_descriptors():
+    """Randomised windows, strides, dilation and padding on images 900-2600 pixels wide (column tiles, residue classes
+    with and without shared grids, channel tails)."""
+    g = np.random.default_rng(20180128)
+    done = 0
+    while done < 24:
+        r, s = (int(v) for v in g.integers(1, 6, size=2))
+        sh, sw = (int(v) for v in g.integers(1, 4, size=2))
+        dh, dw = (int(v) for v in g.integers(1, 4, size=2))
+        pb = [int(v) for v in g.integers(0, 4, size=4)]
+        a = Attrs(int(g.integers(1, 3)), int(g.choice([16, 48, 64, 128])), int(g.integers(1, 10)), int(g.integers(900, 2600)),
+                  int(g.choice([16, 64, 96, 128])), r, s, sh, sw, dh, dw, *pb)
+        P, Q = oracle.out_shape(a)
+        if P < 1 or Q < 1 or a.n * a.c * a.h * a.w > 5e6:
+            continue
+        _check_all(a, "bf16", BLK, BLK, bool(done % 2), 9500 + done)
+        done += 1
