@@ -121,9 +121,18 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
             // Rows wider than a strip (or its patch) holds: column tiles.  Of the tile widths (multiples of 8 lattice
             // columns) take the one whose strips read the fewest patch pixels over the image.
             if (out.out_mode != 0) continue;
+            // Among equal costs: the widest tile (longer contiguous runs per patch row), but for a node below half the
+            // machine balance in flop per tensor byte the widest whose strip fits the smallest kernel variant (256
+            // positions) - such a node wants many workgroups in flight, not large ones (3x1 window, 128 -> 64
+            // channels, rows of 3136 pixels: tiles of 8 / 16 / 32 / 56 columns cost the same patch traffic and run
+            // forward in 42 / 37 / 36 / 37 us, backprop-data in 49 / 37 / 38 / 43 us).
             long best_cost = -1;
             int best_bw = 0, best_tp = 0;
+            const bool mem_bound = (double)out.Cin * ntaps * Cout / (out.Cin + Cout) < 157.0;
+            auto rank = [&](int bw, int tp) { return mem_bound && bw * tp > 256 ? -bw : bw; };
+            const char *fbw = getenv("NGC_STRIP_BW");                    // tests / benchmarks only: tile width
             for (int bw = 8; bw <= maxpix && bw < Wout + 8; bw += 8) {
+                if (fbw && atoi(fbw) >= 8 && bw != atoi(fbw)) continue;
                 const int pc = (bw - 1) * sw + span_w + 1;
                 int tp = maxpix / bw;
                 const int prows = MAXPATCH / pc;
@@ -134,7 +143,9 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
                 if (tp < 1) continue;
                 const long tiles = (long)((Hout + tp - 1) / tp) * ((Wout + bw - 1) / bw);
                 const long cost = tiles * ((long)(tp - 1) * sh + span_h + 1) * pc;
-                if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_bw = bw; best_tp = tp; }
+                if (best_cost < 0 || cost < best_cost || (cost == best_cost && rank(bw, tp) > rank(best_bw, best_tp))) {
+                    best_cost = cost; best_bw = bw; best_tp = tp;
+                }
             }
             if (best_cost < 0) continue;
             q.BW = best_bw;
