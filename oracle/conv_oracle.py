@@ -249,7 +249,10 @@ def max_normalised_error(got, ref) -> float:
     if ref.size == 0:
         return 0.0
     denom = float(np.max(np.abs(ref)))
-    err = float(np.max(np.abs(got - ref)))
+    diff = np.abs(got - ref)
+    if not np.isfinite(diff).all():          # a NaN or an infinity in either tensor never passes a bound
+        return float("inf")
+    err = float(np.max(diff))
     if denom == 0.0:
         return 0.0 if err == 0.0 else float("inf")
     return err / denom

@@ -13,7 +13,23 @@ import paper_1801_08058_amd as ng
 import synth_inputs
 from synth_inputs import ConvLayer
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2}          # the contract: max normalised error per element type of the data
+
+# Bounds that follow from the arithmetic of the bf16 path; every parity assert uses these (they imply the contract's).
+#   y, dx: the fp32 accumulator (exact bf16 products, fp32 sums: relative error ~1e-6) is rounded once to bf16, whose
+#          half ulp is at most 2^-8 of the value, hence of max|ref|.  A dropped (c, r, s) term or a truncating
+#          conversion (error up to 2^-7) lands above it.
+#   dw:    fp32 from exact products with fp32 accumulation over N*P*Q terms in a fixed tree; observed 1e-7..5e-6 of
+#          max|dw|.  A dropped 32-position step, row or image tail moves dw by 1e-3..1e-2 of its maximum.
+BOUND_BF16 = {"act": 2.0 ** -8 * 1.01, "dw": 1e-4}
+
+
+def bound(dtype: str, kind: str) -> float:
+    """Largest max-normalised error accepted for an output of `kind` ("act": y / dx in the element type, "dw": the
+    fp32 filter gradient) computed from `dtype` data."""
+    b = TOL["f32"] if dtype == "f32" else BOUND_BF16[kind]
+    assert b <= TOL[dtype]
+    return b
 
 
 def attrs_of(L: ConvLayer) -> oracle.Attrs:

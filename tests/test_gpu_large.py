@@ -11,7 +11,7 @@ import oracle
 import paper_1801_08058_amd as ng
 import synth_inputs
 from oracle import Attrs
-from gpu_util import dev, host, stream
+from gpu_util import bound, dev, host, stream
 
 pytestmark = pytest.mark.gpu
 BLK = ng.NGC_NCHW16C
@@ -52,7 +52,7 @@ def test_three_ops_on_tensors_past_two_gib():
         first = oracle.bf16_bits_to_f64(oracle.blocked16_to_nchw(r[0].reshape(PERIOD, 4, h, w, 16), 64))
         idx = g.integers(0, first.size, size=256)
         ref = ref_at(idx)
-        assert np.abs(first.reshape(-1)[idx] - ref).max() / max(np.abs(ref).max(), 1e-30) <= 2e-2, what
+        assert np.abs(first.reshape(-1)[idx] - ref).max() / max(np.abs(ref).max(), 1e-30) <= bound("bf16", "act"), what
 
     y = torch.empty(ng.ngc_data_elems(d, 1), dtype=torch.int16, device="cuda")
     ng.ngc_conv_fwd(d, xd, wd, bd, y, ws(d, ng.NGC_OP_FWD), stream())
@@ -81,7 +81,7 @@ def test_three_ops_on_tensors_past_two_gib():
     idx = g.integers(0, k * c * 9, size=64)
     ref = REPS * oracle.conv_bwd_filters_at(a1, x1, dy1, idx)
     got = dw.cpu().numpy().astype(np.float64)[idx]
-    assert np.abs(got - ref).max() / np.abs(ref).max() <= 2e-2
+    assert np.abs(got - ref).max() / np.abs(ref).max() <= bound("bf16", "dw")
 
 
 @pytest.mark.timeout(600)
@@ -112,7 +112,7 @@ def test_rank3_ops_on_tensors_past_two_gib():
         first = oracle.bf16_bits_to_f64(oracle.blocked16_to_nchw(r[0].reshape(PERIOD, 4, dd * h, w, 16), 64))
         idx = g.integers(0, first.size, size=128)
         ref = ref_at(idx)
-        assert np.abs(first.reshape(-1)[idx] - ref).max() / max(np.abs(ref).max(), 1e-30) <= 2e-2, what
+        assert np.abs(first.reshape(-1)[idx] - ref).max() / max(np.abs(ref).max(), 1e-30) <= bound("bf16", "act"), what
 
     y = torch.empty(ng.ngc_conv3d_data_elems(d, 1), dtype=torch.int16, device="cuda")
     ng.ngc_conv3d_fwd(d, xd, wd, None, y, ws(ng.NGC_OP_FWD), stream())
@@ -129,4 +129,4 @@ def test_rank3_ops_on_tensors_past_two_gib():
     torch.cuda.synchronize()
     idx = g.integers(0, k * c * 27, size=32)
     ref = REPS * oracle.conv3d_bwd_filters_at(a1, x1, dy1, idx)
-    assert np.abs(dw.cpu().numpy().astype(np.float64)[idx] - ref).max() / np.abs(ref).max() <= 2e-2
+    assert np.abs(dw.cpu().numpy().astype(np.float64)[idx] - ref).max() / np.abs(ref).max() <= bound("bf16", "dw")

@@ -531,3 +531,43 @@ def test_conv3d_closed_forms():
     y = oracle.conv3d_fwd(a1, x, w)[0, 0]
     want = np.zeros((4, 4, 4)); want[:3, 1:, :] = x[0, 0, 1:, :3, :]
     assert np.array_equal(y, want)
+
+
+# ------------------------------------------------------------------ P15: the error metric every parity assert goes through
+def test_max_normalised_error_hand_vectors(oracle_mod):
+    """e = max|got - ref| / max|ref| on vectors worked by hand; the gate itself must not let a broken result through."""
+    o = oracle_mod
+    # largest difference 0.5 (third element), largest |ref| 4 (the negative one): 0.5 / 4
+    assert o.max_normalised_error([1.0, 2.0, 3.5, -4.0], [1.0, 2.0, 3.0, -4.0]) == 0.125
+    # normalised by the reference's norm, not element by element: an error of 1 on the element 0 is 1 / 10
+    assert o.max_normalised_error([1.0, 10.0], [0.0, 10.0]) == 0.1
+    # not by the result's norm either
+    assert o.max_normalised_error([100.0, 1.0], [0.0, 1.0]) == 100.0
+    assert o.max_normalised_error(np.full((2, 3), 7.0), np.full((2, 3), 7.0)) == 0.0
+    # sign matters: -x against x is an error of 2
+    assert o.max_normalised_error([-3.0], [3.0]) == 2.0
+    # tensors of any rank, compared element by element in place (a transposed result is an error)
+    a = np.arange(6.0).reshape(2, 3)
+    assert o.max_normalised_error(a, a) == 0.0
+    assert o.max_normalised_error(np.ascontiguousarray(a.T).reshape(2, 3), a) == 2.0 / 5.0
+
+
+def test_max_normalised_error_rejects_broken_results(oracle_mod):
+    o = oracle_mod
+    ref = np.array([1.0, -2.0, 0.5])
+    for bad in (np.nan, np.inf, -np.inf):
+        got = ref.copy()
+        got[1] = bad
+        e = o.max_normalised_error(got, ref)
+        assert e == float("inf") and not (e <= 2e-2)
+    # a non-finite reference is no licence either
+    assert o.max_normalised_error(ref, np.array([1.0, np.nan, 0.5])) == float("inf")
+    # zero reference: exact zeros pass, anything else is infinitely wrong
+    assert o.max_normalised_error(np.zeros(4), np.zeros(4)) == 0.0
+    assert o.max_normalised_error(np.array([0.0, 1e-30]), np.zeros(2)) == float("inf")
+    # shapes must agree: no broadcasting of a short result against the reference
+    with pytest.raises(ValueError):
+        o.max_normalised_error(np.zeros(3), np.zeros((3, 1)))
+    with pytest.raises(ValueError):
+        o.max_normalised_error(np.zeros(1), np.zeros(4))
+    assert o.max_normalised_error(np.zeros((0,)), np.zeros((0,))) == 0.0
