@@ -268,6 +268,12 @@ size_t ngc_conv3d_data_elems(const ngc_conv3d_desc *desc, int which);
  * reduce to the rank-2 op, "igemm3_bf16_*", "wgrad_gemm3_bf16", "direct3", "unsupported", "invalid". */
 const char *ngc_conv3d_variant(const ngc_conv3d_desc *desc, int op);
 
+/* Test hook.  The library reads its NGC_* environment switches (kernel-variant overrides for tests and
+ * experiments; NGC_DRY_RUN=1 skips every launch after the host-side planning) once per process, at first use,
+ * and caches the launch plan of every descriptor it has seen per thread.  This call reads the switches again and
+ * drops the cached plans.  Not meant for production code; not thread safe against calls in flight. */
+void ngc_reload_switches(void);
+
 /* Static description of a status code. */
 const char *ngc_status_string(int status);
 

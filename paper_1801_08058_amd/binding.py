@@ -27,7 +27,8 @@ EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ng
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string",
            "ngc_conv3d_out_shape", "ngc_conv3d_workspace_bytes", "ngc_conv3d_fwd", "ngc_conv3d_bwd_data",
            "ngc_conv3d_bwd_filters", "ngc_conv3d_filter_convert", "ngc_conv3d_filter_elems", "ngc_conv3d_data_elems",
-           "ngc_conv3d_variant", "ngc_conv3d_bwd_data_relu", "ngc_conv3d_bwd_data_relu_db", "ngc_conv3d_bias_grad")
+           "ngc_conv3d_variant", "ngc_conv3d_bwd_data_relu", "ngc_conv3d_bwd_data_relu_db", "ngc_conv3d_bias_grad",
+           "ngc_reload_switches")
 
 
 class ngc_conv_desc(ctypes.Structure):
@@ -95,6 +96,8 @@ def _load() -> ctypes.CDLL:
     lib.ngc_softmax_variant.restype = ctypes.c_char_p
     lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_filters.restype = ctypes.c_int
+    lib.ngc_reload_switches.argtypes = []
+    lib.ngc_reload_switches.restype = None
     lib.ngc_layout_convert.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp]
     lib.ngc_layout_convert.restype = ctypes.c_int
     lib.ngc_filter_convert.argtypes = [D, vp, vp, i32, vp]
@@ -241,6 +244,10 @@ def ngc_softmax_variant(dtype, cols, bwd=False) -> str:
 def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_conv_bwd_filters(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), _nbytes(ws),
                                             _stream(stream)), "ngc_conv_bwd_filters", check)
+
+
+def ngc_reload_switches() -> None:
+    _lib.ngc_reload_switches()
 
 
 def ngc_layout_convert(dtype, n, c, h, w, src, src_layout, dst, dst_layout, stream=None, check: bool = True) -> int:

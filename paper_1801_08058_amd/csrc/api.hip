@@ -10,9 +10,63 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <unordered_map>
+
 using namespace ngc;
 
 namespace {
+
+// ---- plan cache -------------------------------------------------------------------------------------------
+// Planning a launch (kernel selection, strip / tile geometry, split of a reduction) is a pure function of the
+// descriptor, a few integers and the environment switches.  Each planning function below keeps what it
+// computed per thread, keyed by its arguments, so that the second call with a descriptor costs a few table
+// look-ups instead of the geometry loops; ngc_reload_switches() invalidates everything.
+struct PlanKey {
+    ngc_conv_desc d;
+    int32_t a[4];
+};
+static_assert(sizeof(PlanKey) == 24 * sizeof(int32_t), "hashed and compared as 24 words, no padding");
+
+struct PlanKeyHash {
+    size_t operator()(const PlanKey &k) const
+    {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(&k);
+        uint64_t h = 0xcbf29ce484222325ull;
+        for (int i = 0; i < 24; ++i) h = (h ^ w[i]) * 0x100000001b3ull;
+        return (size_t)(h ^ (h >> 29));
+    }
+};
+struct PlanKeyEq {
+    bool operator()(const PlanKey &x, const PlanKey &y) const { return memcmp(&x, &y, sizeof(PlanKey)) == 0; }
+};
+
+PlanKey plan_key(const ngc_conv_desc *d, int a0 = 0, int a1 = 0, int a2 = 0, int a3 = 0)
+{
+    PlanKey k;
+    k.d = *d;
+    k.a[0] = a0; k.a[1] = a1; k.a[2] = a2; k.a[3] = a3;
+    return k;
+}
+
+template <class V>
+struct PlanCache {
+    std::unordered_map<PlanKey, V, PlanKeyHash, PlanKeyEq> map;
+    uint32_t epoch = 0xFFFFFFFFu;
+    V *find(const PlanKey &k)
+    {
+        if (epoch != sw_epoch()) {
+            map.clear();
+            epoch = sw_epoch();
+        }
+        auto it = map.find(k);
+        return it == map.end() ? nullptr : &it->second;
+    }
+    V &put(const PlanKey &k, const V &v)
+    {
+        if (map.size() >= 2048) map.clear();             // a process cycling through more nodes than that replans
+        return map[k] = v;
+    }
+};
 
 constexpr size_t MAX_ELEMS = (size_t)1 << 31;
 
@@ -100,7 +154,7 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
                     int *nf_out, size_t *lds_out)
 {
     // NGC_STRIP_NF (tests / benchmarks only): 0 disables this kernel, 7 / 4 / 2 forces a strip size
-    const char *force = getenv("NGC_STRIP_NF");
+    const char *force = env_switch(SW_STRIP_NF);
     const int forced_nf = force ? atoi(force) : -1;
     if (forced_nf == 0) return false;
     constexpr int MAXPATCH = 24 * 64;                                    // patch pixels per plane (24 blocks of 64)
@@ -130,7 +184,7 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
             int best_bw = 0, best_tp = 0;
             const bool mem_bound = (double)out.Cin * ntaps * Cout / (out.Cin + Cout) < 157.0;
             auto rank = [&](int bw, int tp) { return mem_bound && bw * tp > 256 ? -bw : bw; };
-            const char *fbw = getenv("NGC_STRIP_BW");                    // tests / benchmarks only: tile width
+            const char *fbw = env_switch(SW_STRIP_BW);                    // tests / benchmarks only: tile width
             for (int bw = 8; bw <= maxpix && bw < Wout + 8; bw += 8) {
                 if (fbw && atoi(fbw) >= 8 && bw != atoi(fbw)) continue;
                 const int pc = (bw - 1) * sw + span_w + 1;
@@ -164,7 +218,7 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
             q.strips = 1;
         } else {
             int rows_fit = maxpix / Wout;
-            const char *fr = getenv("NGC_STRIP_ROWS");                   // experiments: cap on the rows of a strip
+            const char *fr = env_switch(SW_STRIP_ROWS);                   // experiments: cap on the rows of a strip
             if (fr && atoi(fr) >= 1 && rows_fit > atoi(fr)) rows_fit = atoi(fr);
             const int prows = MAXPATCH / q.PC;                           // patch rows that fit
             if (prows < span_h + 1) continue;
@@ -211,8 +265,8 @@ bool strip_geometry(StripParams &out, int N, int Hout, int Wout, int span_h, int
 // Strip kernel for forward (op 0; any stride) or for residue class (ca, cb) of the output pixels of
 // backprop-data (op 1; stride-1 layers have the single class (0,0)) of a multi-tap convolution.
 // *empty is set when the class has no output pixel (nothing to launch).
-bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
-                      size_t *lds_out, bool *empty)
+bool strip_plan_class_uncached(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
+                               size_t *lds_out, bool *empty)
 {
     if (empty) *empty = false;
     const int all_taps = d->r * d->s;
@@ -284,6 +338,34 @@ bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int
     return true;
 }
 
+struct StripClassPlan {
+    bool ok, empty;
+    int nf;
+    size_t lds;
+    StripParams sp;
+};
+
+bool strip_plan_class(const ngc_conv_desc *d, int op, int ca, int cb, int P, int Q, StripParams *sp, int *nf_out,
+                      size_t *lds_out, bool *empty)
+{
+    static thread_local PlanCache<StripClassPlan> cache;
+    const PlanKey key = plan_key(d, op, ca, cb);
+    StripClassPlan *e = cache.find(key);
+    if (!e) {
+        StripClassPlan v;
+        memset(&v, 0, sizeof(v));
+        v.ok = strip_plan_class_uncached(d, op, ca, cb, P, Q, &v.sp, &v.nf, &v.lds, &v.empty);
+        e = &cache.put(key, v);
+    }
+    if (empty) *empty = e->empty;
+    if (e->ok && !e->empty) {
+        if (sp) *sp = e->sp;
+        if (nf_out) *nf_out = e->nf;
+        if (lds_out) *lds_out = e->lds;
+    }
+    return e->ok;
+}
+
 }  // namespace
 
 namespace ngc {
@@ -333,7 +415,7 @@ bool strip_zero_fill(const ngc_conv_desc *d)
 // true if every launch of the op can go through the strip kernel
 bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q)
 {
-    const char *sw = getenv("NGC_STRIP_STRIDED");                        // tests / benchmarks only: 0 = stride-1 layers only
+    const char *sw = env_switch(SW_STRIP_STRIDED);                        // tests / benchmarks only: 0 = stride-1 layers only
     if (sw && atoi(sw) == 0 && (d->stride_h != 1 || d->stride_w != 1)) return false;
     const int ncls = strip_classes(d, op);
     if (ncls > 16) return false;
@@ -357,7 +439,7 @@ struct StemBwdPlan {
     size_t wu_bytes;
 };
 
-bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
+bool stem_bwd_plan_uncached(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
 {
     if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_KCRS)
         return false;
@@ -366,7 +448,7 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
     StemBwdPlan pl;
     pl.BW = 2;
     pl.BH = (4 * 2 * d->c <= 32) ? 4 : 2;
-    const char *fb = getenv("NGC_STEM_BH");                               // tests / experiments only
+    const char *fb = env_switch(SW_STEM_BH);                               // tests / experiments only
     if (fb && atoi(fb) == 2) pl.BH = 2;
     if (pl.BH * pl.BW * d->c > 64) return false;
     int dr_min = INT_MAX, dr_max = INT_MIN, ds_min = INT_MAX, ds_max = INT_MIN;
@@ -438,9 +520,9 @@ bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
 }
 
 // Geometry of the all-taps backprop-filters kernel (stride 1, exactly 9 taps, C and K multiples of 64).
-bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp, size_t *lds_out)
+bool wgrad_strip_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp, size_t *lds_out)
 {
-    const char *force = getenv("NGC_WGRAD_STRIP");
+    const char *force = env_switch(SW_WGRAD_STRIP);
     if (force && atoi(force) == 0) return false;
     if (d->stride_h != 1 || d->stride_w != 1 || d->r * d->s != 9) return false;
     if (d->c % 64 != 0 || d->k % 64 != 0) return false;
@@ -457,7 +539,7 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     // channel groups per workgroup: few (k,c) tiles -> narrower c per workgroup, longer position chunks
     const int tiles64 = (d->k / 64) * (d->c / 64);
     q.ncq = tiles64 <= 4 ? 2 : 4;
-    const char *fq = getenv("NGC_WGRAD_NCQ");
+    const char *fq = env_switch(SW_WGRAD_NCQ);
     if (fq && (atoi(fq) == 1 || atoi(fq) == 2 || atoi(fq) == 4)) q.ncq = atoi(fq);
     // small images: several whole images per stage (a stage of one 7x7 image would be 1.5 steps),
     // as many as a workgroup's share of the batch allows
@@ -465,7 +547,7 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     {
         const int tiles_g = (d->k / 64) * (d->c / (16 * q.ncq));
         const int parts_g = tiles_g >= NUM_CUS ? 1 : (NUM_CUS + tiles_g - 1) / tiles_g;
-        const char *fg = getenv("NGC_WGRAD_G1");                        // tests / experiments only: one image per stage
+        const char *fg = env_switch(SW_WGRAD_G1);                        // tests / experiments only: one image per stage
         if (q.SR == P && 2 * P * Q <= 224 && parts_g <= d->n && !(fg && atoi(fg) == 1)) {
             q.G = 224 / (P * Q);
             if (q.G > d->n / parts_g) q.G = d->n / parts_g;
@@ -478,11 +560,11 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
     if (4 * nblk_dy + q.ncq * nblk_x > 80) return false;                // load items per stage (10 per wave)
     const size_t stage = (size_t)4 * q.dyplane + (size_t)q.ncq * q.xplane;
     q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
-    const char *fr = getenv("NGC_WGRAD_RING");                          // tests / benchmarks only
+    const char *fr = env_switch(SW_WGRAD_RING);                          // tests / benchmarks only
     if (fr && atoi(fr) == 2) q.nring = 2;
     // waves 4-7 (the second wave of each SIMD) issue their loads after their MFMAs; NGC_WGRAD_LATE (tests /
     // benchmarks only) sets another wave mask, 0 = every wave issues right after the barrier
-    const char *fl = getenv("NGC_WGRAD_LATE");
+    const char *fl = env_switch(SW_WGRAD_LATE);
     q.late_mask = fl ? (int)strtol(fl, nullptr, 0) & 0xFF : 0xF0;
     size_t lds = q.nring * stage;
     const size_t red = (size_t)4 * 144 * 64 * sizeof(float);           // final cross-wave sum
@@ -524,7 +606,7 @@ bool wgrad_strip_plan(const ngc_conv_desc *d, int P, int Q, WgradStripParams *wp
 }
 
 // low-channel stem forward: C <= 3, 7x7, stride 2, pad_below_w 3, NCHW input, blocked output
-bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size_t *lds_out)
+bool stem_fwd_plan_uncached(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size_t *lds_out)
 {
     if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_KCRS)
         return false;
@@ -536,7 +618,7 @@ bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size
     q.N = d->n; q.C = d->c; q.H = d->h; q.W = d->w; q.K = d->k; q.P = P; q.Q = Q;
     q.pbh = d->pad_below_h;
     q.TP = P < 8 ? P : 8;
-    const char *ftp = getenv("NGC_STEM_TP");                            // tests / benchmarks only: output rows per workgroup
+    const char *ftp = env_switch(SW_STEM_TP);                            // tests / benchmarks only: output rows per workgroup
     if (ftp && atoi(ftp) >= 1 && atoi(ftp) <= 8 && atoi(ftp) <= P) q.TP = atoi(ftp);
     q.tiles_per_img = (P + q.TP - 1) / q.TP;
     q.div_q = make_fastdiv((uint32_t)Q);
@@ -550,7 +632,7 @@ bool stem_fwd_plan(const ngc_conv_desc *d, int P, int Q, StemFwdParams *sp, size
 }
 
 // low-channel stem backprop-filters: same shapes as stem forward, plus Q % 8 == 0
-bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, size_t *lds_out)
+bool wgrad_stem_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, size_t *lds_out)
 {
     if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW || d->y_layout != NGC_NCHW16C) return false;
     if (d->c > 3 || d->r != 7 || d->s != 7 || d->stride_h != 2 || d->stride_w != 2 || d->dil_h != 1 || d->dil_w != 1)
@@ -564,7 +646,7 @@ bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, 
     while ((sr * Q) % 32 != 0) ++sr;                                    // <= 4 since Q % 8 == 0
     // positions per stage (NGC_WSTEM_POS, experiments): a stage costs a load latency whatever its size
     int stage_pos = 512;
-    const char *fp = getenv("NGC_WSTEM_POS");
+    const char *fp = env_switch(SW_WSTEM_POS);
     if (fp && atoi(fp) >= 32 && atoi(fp) <= 1024) stage_pos = atoi(fp);
     while (2 * sr * Q <= stage_pos && 2 * sr <= P) sr *= 2;
     // the two stage buffers have to fit the LDS and the input rows 3 chunks per thread
@@ -599,9 +681,9 @@ bool wgrad_stem_plan(const ngc_conv_desc *d, int P, int Q, WgradStemParams *wp, 
 }
 
 // backprop-filters as a per-tap GEMM over positions (1x1 layers, strided multi-tap layers)
-bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
+bool wgrad_gemm_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
 {
-    const char *force = getenv("NGC_WGRAD_GEMM");
+    const char *force = env_switch(SW_WGRAD_GEMM);
     if (force && atoi(force) == 0) return false;
     if (d->c % 16 != 0 || d->k % 16 != 0 || d->r * d->s > 64 || d->dtype != NGC_BF16) return false;
     const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2, dy_bytes = (size_t)d->n * d->k * P * Q * 2;
@@ -613,7 +695,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     q.x_nchw = d->x_layout == NGC_NCHW;
     q.dy_nchw = d->y_layout == NGC_NCHW;
     if (q.x_nchw || q.dy_nchw) {
-        const char *lp = getenv("NGC_G1_NCHW");          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
+        const char *lp = env_switch(SW_G1_NCHW);          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
         if (lp && atoi(lp) == 0) return false;
         if (d->r != 1 || d->s != 1 || d->stride_h != 1 || d->stride_w != 1 || d->pad_below_h || d->pad_below_w ||
             d->pad_above_h || d->pad_above_w || (d->h * d->w) % 8 != 0)
@@ -626,7 +708,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     auto wide = [](int ch) { return ch > 64 && (ch + 127) / 128 * 128 <= (ch + 63) / 64 * 64; };
     q.wk = wide(d->k) ? 2 : 1;
     q.wc = wide(d->c) ? 2 : 1;
-    const char *ft = getenv("NGC_WGG_TILE");                             // tests / benchmarks only: "11", "12", "21", "22"
+    const char *ft = env_switch(SW_WGG_TILE);                             // tests / benchmarks only: "11", "12", "21", "22"
     if (ft && (ft[0] == '1' || ft[0] == '2') && (ft[1] == '1' || ft[1] == '2')) {
         q.wk = ft[0] - '0';
         q.wc = ft[1] - '0';
@@ -639,7 +721,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // twice as many position chunks are cut.  That pays when there are many (tile, tap) pairs, i.e.
     // few chunks and little extra partial traffic, and for multi-tap layers; the large-image 1x1
     // layers are HBM-bound and keep 128-position stages.  NGC_WGG_SP (experiments only) forces 64 / 128.
-    const char *fsp = getenv("NGC_WGG_SP");
+    const char *fsp = env_switch(SW_WGG_SP);
     // Measured per layer over the ResNet-50 stack (reproducible to 1 %): 64 wins from 16 tiles on, and
     // by 20-24 % where one operand is read by a single tile row / column and the other by four or more
     // (128 -> 512 and 512 -> 128 at 28x28); with 2 x 4 tiles it loses 35-65 %.
@@ -647,7 +729,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     q.sp = (d->r * d->s > 1 || tiles >= 16 || (tmin == 1 && tmax >= 4)) ? 64 : 128;
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
     uint32_t slots = q.sp == 64 ? 2 * NUM_CUS : NUM_CUS;
-    const char *fs = getenv("NGC_WGG_SLOTS");                            // tests / benchmarks only: workgroups aimed at
+    const char *fs = env_switch(SW_WGG_SLOTS);                            // tests / benchmarks only: workgroups aimed at
     if (fs && atoi(fs) >= 32 && atoi(fs) <= 4096) slots = (uint32_t)atoi(fs);
     uint32_t parts = (slots + tiles - 1) / tiles;
     // many (tile, tap) pairs: a few workgroups more than the slots cost a whole extra round of long workgroups
@@ -662,7 +744,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     if (d->r * d->s > 1 && !q.x_nchw && !q.dy_nchw) {
         const uint32_t xcd_slots = slots / 8;
         const uint32_t parts8 = 8 * (xcd_slots / tiles > 0 ? xcd_slots / tiles : 1);
-        const char *fx = getenv("NGC_WGG_XCD");
+        const char *fx = env_switch(SW_WGG_XCD);
         bool on = x_bytes + dy_bytes >= ((size_t)24 << 20) && parts8 * 10 >= parts * 9 && parts8 * 10 <= parts * 11;
         if (fx) on = atoi(fx) == 1;
         if (on) {
@@ -682,7 +764,7 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
     // on the 56x56 layers of the ResNet-50 stack (126 chunks, two tiles): 64 -> 256 53.2 -> 49.7 us, 256 -> 64
     // 52.4 -> 46.9 us, but 256 -> 128 (128 x 128 tiles) 72.0 -> 75.5 us, so not for that tile shape.
     if (d->r * d->s == 1 && tiles > 1 && q.wk * q.wc < 4 && q.nparts >= 64 && q.nparts % 8 != 0) {
-        const char *fx = getenv("NGC_WGG_XCD");
+        const char *fx = env_switch(SW_WGG_XCD);
         if (!(fx && atoi(fx) == 0)) q.xcd_order = 1;
     }
     q.x_bytes = (uint32_t)x_bytes;
@@ -696,9 +778,9 @@ bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
 // One-tap GEMM kernel for forward (op 0) or backprop-data (op 1) of a 1x1 convolution, any stride.
 // Backprop-data with stride > 1 computes the one residue class of pixels the tap reaches; `zero`
 // reports that the rest of dx has to be cleared first.
-bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *gp, bool *zero)
+bool gemm1x1_plan_uncached(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *gp, bool *zero)
 {
-    const char *sw = getenv("NGC_GEMM1X1");              // tests / benchmarks only: 0 disables this kernel
+    const char *sw = env_switch(SW_GEMM1X1);              // tests / benchmarks only: 0 disables this kernel
     if (sw && atoi(sw) == 0) return false;
     if (d->r != 1 || d->s != 1) return false;
     const bool fwd = op == NGC_OP_FWD;
@@ -712,7 +794,7 @@ bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *g
     q.in_nchw = (fwd ? d->x_layout : d->y_layout) == NGC_NCHW;
     q.out_nchw = (fwd ? d->y_layout : d->x_layout) == NGC_NCHW;
     if (q.in_nchw || q.out_nchw) {
-        const char *lp = getenv("NGC_G1_NCHW");          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
+        const char *lp = env_switch(SW_G1_NCHW);          // tests / benchmarks only: 0 = NCHW tensors take the direct kernels
         if (lp && atoi(lp) == 0) return false;
         if (d->stride_h != 1 || d->stride_w != 1 || d->pad_below_h || d->pad_below_w || d->pad_above_h || d->pad_above_w ||
             (d->h * d->w) % 8 != 0)
@@ -750,12 +832,88 @@ bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *g
     return true;
 }
 
+// cached forms of the planning functions above (same signatures)
+template <class T>
+struct CachedPlan {
+    bool ok;
+    size_t lds;
+    bool flag;
+    T v;
+};
+
+bool stem_bwd_plan(const ngc_conv_desc *d, int P, int Q, StemBwdPlan *out)
+{
+    static thread_local PlanCache<CachedPlan<StemBwdPlan>> cache;
+    const PlanKey key = plan_key(d);
+    auto *e = cache.find(key);
+    if (!e) {
+        CachedPlan<StemBwdPlan> v;
+        memset(&v, 0, sizeof(v));
+        v.ok = stem_bwd_plan_uncached(d, P, Q, &v.v);
+        e = &cache.put(key, v);
+    }
+    if (e->ok && out) *out = e->v;
+    return e->ok;
+}
+
+#define NGC_CACHED_PLAN_LDS(NAME, TYPE)                                                  \
+    bool NAME(const ngc_conv_desc *d, int P, int Q, TYPE *out, size_t *lds_out)          \
+    {                                                                                    \
+        static thread_local PlanCache<CachedPlan<TYPE>> cache;                           \
+        const PlanKey key = plan_key(d);                                                 \
+        auto *e = cache.find(key);                                                       \
+        if (!e) {                                                                        \
+            CachedPlan<TYPE> v;                                                          \
+            memset(&v, 0, sizeof(v));                                                    \
+            v.ok = NAME##_uncached(d, P, Q, &v.v, &v.lds);                               \
+            e = &cache.put(key, v);                                                      \
+        }                                                                                \
+        if (e->ok && out) *out = e->v;                                                   \
+        if (e->ok && lds_out) *lds_out = e->lds;                                         \
+        return e->ok;                                                                    \
+    }
+NGC_CACHED_PLAN_LDS(wgrad_strip_plan, WgradStripParams)
+NGC_CACHED_PLAN_LDS(stem_fwd_plan, StemFwdParams)
+NGC_CACHED_PLAN_LDS(wgrad_stem_plan, WgradStemParams)
+#undef NGC_CACHED_PLAN_LDS
+
+bool wgrad_gemm_plan(const ngc_conv_desc *d, int P, int Q, WgradGemmParams *wp)
+{
+    static thread_local PlanCache<CachedPlan<WgradGemmParams>> cache;
+    const PlanKey key = plan_key(d);
+    auto *e = cache.find(key);
+    if (!e) {
+        CachedPlan<WgradGemmParams> v;
+        memset(&v, 0, sizeof(v));
+        v.ok = wgrad_gemm_plan_uncached(d, P, Q, &v.v);
+        e = &cache.put(key, v);
+    }
+    if (e->ok && wp) *wp = e->v;
+    return e->ok;
+}
+
+bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *gp, bool *zero)
+{
+    static thread_local PlanCache<CachedPlan<Gemm1x1Params>> cache;
+    const PlanKey key = plan_key(d, op);
+    auto *e = cache.find(key);
+    if (!e) {
+        CachedPlan<Gemm1x1Params> v;
+        memset(&v, 0, sizeof(v));
+        v.ok = gemm1x1_plan_uncached(d, op, P, Q, &v.v, &v.flag);
+        e = &cache.put(key, v);
+    }
+    if (e->ok && gp) *gp = e->v;
+    if (e->ok && zero) *zero = e->flag;
+    return e->ok;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
 }
 
-Variant pick(const ngc_conv_desc *d, int op)
+Variant pick_uncached(const ngc_conv_desc *d, int op)
 {
     int P, Q;
     if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
@@ -788,6 +946,15 @@ Variant pick(const ngc_conv_desc *d, int op)
         return V_DIRECT;
     }
     return V_INVALID;
+}
+
+Variant pick(const ngc_conv_desc *d, int op)
+{
+    static thread_local PlanCache<Variant> cache;
+    const PlanKey key = plan_key(d, op);
+    Variant *e = cache.find(key);
+    if (!e) e = &cache.put(key, pick_uncached(d, op));
+    return *e;
 }
 
 size_t filter_elems(const ngc_conv_desc *d, int layout)
@@ -826,10 +993,10 @@ ngc_conv_desc dx_as_dy(const ngc_conv_desc *d)
 
 bool db_fusable(const ngc_conv_desc *d, Variant v)
 {
-    if (getenv("NGC_DB_FUSE") && atoi(getenv("NGC_DB_FUSE")) == 0) return false;   // tests / benchmarks only
+    if (env_switch(SW_DB_FUSE) && atoi(env_switch(SW_DB_FUSE)) == 0) return false;   // tests / benchmarks only
     if (v == V_STRIP) {                                   // the kernels with column tiles write no channel sums
         int P, Q;
-        return getenv("NGC_STRIP_1WAVE") == nullptr && validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
+        return env_switch(SW_STRIP_1WAVE) == nullptr && validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
     }
     if (v == V_GEMM1X1) return d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
     return false;
@@ -859,7 +1026,9 @@ int db_fused_rows(const ngc_conv_desc *d, Variant v, int P, int Q)
     return rows;
 }
 
-size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
+size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q);
+
+size_t workspace_bytes_uncached(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
     if (op == NGC_OP_BWD_DATA_DB) {
         // backprop-data part, then the partial channel sums of dx: rows of the fused launches, or the
@@ -902,6 +1071,31 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
         return round256((size_t)splits * d->r * d->s * d->k * d->c * sizeof(float));
     }
     return 0;
+}
+
+size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
+{
+    static thread_local PlanCache<size_t> cache;
+    const PlanKey key = plan_key(d, op, (int)v);
+    size_t *e = cache.find(key);
+    if (!e) e = &cache.put(key, workspace_bytes_uncached(d, op, v, P, Q));
+    return *e;
+}
+
+// Workspace one group of a node that runs as several launches over groups of images needs: the groups reuse one
+// workspace, and the split of a backprop-filters reduction is not monotone in the batch, so the last (smaller)
+// group can need more than the full ones.
+size_t sliced_group_workspace(const ngc_conv_desc *d, int op, const BatchSlices &bs, int P, int Q)
+{
+    const ngc_conv_desc g = with_batch(d, bs.images);
+    size_t need = workspace_bytes(&g, op, pick(&g, op), P, Q);
+    const int rem = d->n % bs.images;
+    if (rem) {
+        const ngc_conv_desc r = with_batch(d, rem);
+        const size_t b = workspace_bytes(&r, op, pick(&r, op), P, Q);
+        if (b > need) need = b;
+    }
+    return need;
 }
 
 int launch_status(hipError_t e)
@@ -962,17 +1156,14 @@ size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
     const BatchSlices bs = batch_slices(desc, P, Q);
     if (bs.images < desc->n && op == NGC_OP_BWD_FILTERS) {
         // one dw per group of images behind the workspace of a group's launch, added up in index order at the end
-        const ngc_conv_desc g = with_batch(desc, bs.images);
         const size_t groups = (size_t)(desc->n + bs.images - 1) / bs.images;
         const size_t row = ((size_t)desc->k * desc->c * desc->r * desc->s + 15) / 16 * 16;
-        return round256(workspace_bytes(&g, op, pick(&g, op), P, Q)) + round256(groups * row * sizeof(float));
+        return round256(sliced_group_workspace(desc, op, bs, P, Q)) + round256(groups * row * sizeof(float));
     }
     if (bs.images < desc->n && (op == NGC_OP_FWD || op == NGC_OP_BWD_DATA || op == NGC_OP_BWD_DATA_DB)) {
-        // the launches of the groups reuse one workspace (the first group is the largest); the channel sums come
-        // from a second pass over the whole dx
-        const ngc_conv_desc g = with_batch(desc, bs.images);
+        // the launches of the groups reuse one workspace; the channel sums come from a second pass over the whole dx
         const int gop = op == NGC_OP_FWD ? NGC_OP_FWD : NGC_OP_BWD_DATA;
-        const size_t base = workspace_bytes(&g, gop, pick(&g, gop), P, Q);
+        const size_t base = sliced_group_workspace(desc, gop, bs, P, Q);
         if (op != NGC_OP_BWD_DATA_DB) return base;
         const ngc_conv_desc t = dx_as_dy(desc);
         return base + round256((size_t)bias_grad_parts(t, desc->h, desc->w) * ((desc->c + 15) / 16 * 16) * sizeof(float));
@@ -1180,8 +1371,8 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         }
         const int ncls = strip_classes(desc, NGC_OP_BWD_DATA);
         // the residue classes of the stride: one launch each, or (up to 4 classes, 8-wave kernels) all in one grid
-        const bool merge = !(getenv("NGC_STRIP_MERGE") && atoi(getenv("NGC_STRIP_MERGE")) == 0) &&
-                                  getenv("NGC_STRIP_1WAVE") == nullptr;
+        const bool merge = !(env_switch(SW_STRIP_MERGE) && atoi(env_switch(SW_STRIP_MERGE)) == 0) &&
+                                  env_switch(SW_STRIP_1WAVE) == nullptr;
         StripMulti mp;
         mp.n = 0;
         int nf_max = 0;
@@ -1425,8 +1616,7 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
     const BatchSlices bs = batch_slices(desc, P, Q);
     if (bs.images < desc->n) {
         // operands of 2 GiB or more: dw of each group of images into the workspace, then their sum in index order
-        const ngc_conv_desc g0 = with_batch(desc, bs.images);
-        const size_t base = round256(workspace_bytes(&g0, NGC_OP_BWD_FILTERS, pick(&g0, NGC_OP_BWD_FILTERS), P, Q));
+        const size_t base = round256(sliced_group_workspace(desc, NGC_OP_BWD_FILTERS, bs, P, Q));
         if (!ws || ws_bytes < ngc_conv_workspace_bytes(desc, NGC_OP_BWD_FILTERS)) return NGC_WORKSPACE_TOO_SMALL;
         const int elems = desc->k * desc->c * desc->r * desc->s, row = (elems + 15) / 16 * 16;
         float *rows = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + base);

@@ -111,7 +111,7 @@ bool idle_axis(int taps, int stride, int below, int above) { return taps == 1 &&
 // The rank-2 node this node equals on a reshaped tensor, if there is one.
 bool as_rank2(const ngc_conv3d_desc *d, ngc_conv_desc *out)
 {
-    const char *sw = getenv("NGC_CONV3D_RANK2");         // tests / benchmarks only: 0 = always the rank-3 kernels
+    const char *sw = env_switch(SW_CONV3D_RANK2);         // tests / benchmarks only: 0 = always the rank-3 kernels
     if (sw && atoi(sw) == 0) return false;
     const bool id = idle_axis(d->t, d->stride_d, d->pad_below_d, d->pad_above_d);
     const bool ih = idle_axis(d->r, d->stride_h, d->pad_below_h, d->pad_above_h);
@@ -163,7 +163,7 @@ struct Strip3Plan {
 
 bool strip3_plan(const ngc_conv3d_desc *d, int op, int O, int P, int Q, Strip3Plan *out)
 {
-    const char *sw = getenv("NGC_CONV3D_STRIP");          // tests / benchmarks only: 0 = the gather kernel instead
+    const char *sw = env_switch(SW_CONV3D_STRIP);          // tests / benchmarks only: 0 = the gather kernel instead
     if (sw && atoi(sw) == 0) return false;
     const bool fwd = op == NGC_OP_FWD;
     if (!blocked_bf16_3(d)) return false;
@@ -258,7 +258,7 @@ bool wgrad_gemm3_plan(const ngc_conv3d_desc *d, int O, int P, int Q, WgradGemmPa
     q.M = (uint32_t)((size_t)d->n * O * P * Q);
     const uint32_t tiles = (uint32_t)q.ktiles * q.ctiles * taps;
     q.sp = (taps > 1 || tiles >= 16) ? 64 : 128;         // the stage-size rule of the rank-2 layers
-    const char *fsp = getenv("NGC_WGG_SP");              // tests / benchmarks only
+    const char *fsp = env_switch(SW_WGG_SP);              // tests / benchmarks only
     if (fsp && (atoi(fsp) == 64 || atoi(fsp) == 128)) q.sp = atoi(fsp);
     // The kernel keeps the workgroups of a position chunk on one XCD (chunk % 8): chunks come in multiples of 8.
     // Per XCD m chunks x (tile, tap) sets share its workgroup slots (32 compute units x 1 or 2): of the m that
@@ -276,7 +276,7 @@ bool wgrad_gemm3_plan(const ngc_conv3d_desc *d, int O, int P, int Q, WgradGemmPa
         if (fill > best_fill + 0.02) { best_fill = fill; best_m = m; }
     }
     uint32_t parts = 8 * best_m;
-    const char *fp = getenv("NGC_WGG3_PARTS");            // tests / benchmarks only
+    const char *fp = env_switch(SW_WGG3_PARTS);            // tests / benchmarks only
     if (fp && atoi(fp) >= 1 && atoi(fp) <= 4096) parts = (uint32_t)atoi(fp);
     const uint32_t max_parts = (q.M + 127) / 128;
     if (parts > max_parts) parts = max_parts;

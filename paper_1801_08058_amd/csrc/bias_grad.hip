@@ -129,7 +129,7 @@ int bias_grad_parts(const ngc_conv_desc &d, int P, int Q)
 hipError_t launch_bias_grad_reduce(const float *partial, float *db, int nparts, int K, int KP, hipStream_t st)
 {
     NGC_LAUNCH(bias_grad_reduce, dim3((K + 15) / 16), dim3(256), 0, st, partial, db, nparts, K, KP);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy, float *db, float *partial, int nparts,
@@ -150,10 +150,10 @@ hipError_t launch_bias_grad(const ngc_conv_desc &d, int P, int Q, const void *dy
     else
         NGC_LAUNCH(bias_grad_generic<uint16_t>, dim3(nparts, d.k), dim3(256), 0, st, static_cast<const uint16_t *>(dy),
                    partial, d.y_layout, d.k, KP, P, Q, M, chunk, div_pq, div_q);
-    hipError_t e = hipGetLastError();
+    hipError_t e = ngc::launch_result();
     if (e != hipSuccess) return e;
     NGC_LAUNCH(bias_grad_reduce, dim3((d.k + 15) / 16), dim3(256), 0, st, partial, db, nparts, d.k, KP);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

@@ -9,11 +9,24 @@
 // hipErrorNotReady there), so it is cleared before the launch and read right after it.
 #define NGC_LAUNCH(...)            \
     do {                           \
+        if (ngc::dry_run()) break; \
         (void)hipGetLastError();   \
         hipLaunchKernelGGL(__VA_ARGS__); \
     } while (0)
 
 namespace ngc {
+
+// ---- environment switches (tests and experiments only; the default build path reads none of them per call) ----
+// The NGC_* variables are read once per process, at the first use, into a table; env_switch(SW_X) returns the value of
+// NGC_X or nullptr.  ngc_reload_switches() (exported for the test suite) reads them again and bumps the epoch, which
+// also drops every cached plan.
+enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_DRY_RUN, SW_COUNT };
+const char *env_switch(Switch s);
+uint32_t sw_epoch();
+// NGC_DRY_RUN=1: every launch is skipped after the host-side planning (host-path timing without a GPU)
+bool dry_run();
+// what a launcher returns right after NGC_LAUNCH
+inline hipError_t launch_result() { return dry_run() ? hipSuccess : hipGetLastError(); }
 
 // ---- exact unsigned division by a runtime constant (round-up multiplier method) ----
 // q = n / d for every 32-bit n: t = mulhi(mul, n); q = (t + ((n - t) >> sh1)) >> sh2.
@@ -179,6 +192,7 @@ struct LdsLimitOnce {
     bool done[16] = {};
     hipError_t raise(const void *kernel)
     {
+        if (dry_run()) return hipSuccess;
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
@@ -401,7 +415,7 @@ __device__ __forceinline__ void wg_barrier_nofence()
     asm volatile("" ::: "memory");
 }
 
-// launchers (each returns hipGetLastError() after the launch)
+// launchers (each returns launch_result() after the launch)
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st);
 hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st);

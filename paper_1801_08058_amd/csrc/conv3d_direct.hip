@@ -158,7 +158,7 @@ hipError_t launch_direct3_fwd(const ngc_conv3d_desc &d, int O, int P, int Q, con
     else
         NGC_LAUNCH(direct3_fwd<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, O, P, Q, static_cast<const uint16_t *>(x),
                    static_cast<const uint16_t *>(w), bias, static_cast<uint16_t *>(y), total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q, const void *dy, const void *w, const void *mask,
@@ -172,7 +172,7 @@ hipError_t launch_direct3_bwd_data(const ngc_conv3d_desc &d, int O, int P, int Q
     else
         NGC_LAUNCH(direct3_bwd_data<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, O, P, Q, static_cast<const uint16_t *>(dy),
                    static_cast<const uint16_t *>(w), static_cast<const uint16_t *>(mask), static_cast<uint16_t *>(dx), total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_direct3_bwd_filters(const ngc_conv3d_desc &d, int O, int P, int Q, const void *x, const void *dy, float *dw,
@@ -185,7 +185,7 @@ hipError_t launch_direct3_bwd_filters(const ngc_conv3d_desc &d, int O, int P, in
     else
         NGC_LAUNCH(direct3_bwd_filters<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, O, P, Q, static_cast<const uint16_t *>(x),
                    static_cast<const uint16_t *>(dy), dw);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

@@ -141,7 +141,7 @@ hipError_t launch_direct_fwd(const ngc_conv_desc &d, int P, int Q, const void *x
         NGC_LAUNCH(direct_fwd<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), bias,
                            static_cast<uint16_t *>(y), total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const void *dy, const void *w, const void *mask,
@@ -157,7 +157,7 @@ hipError_t launch_direct_bwd_data(const ngc_conv_desc &d, int P, int Q, const vo
         NGC_LAUNCH(direct_bwd_data<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(dy), static_cast<const uint16_t *>(w),
                            static_cast<const uint16_t *>(mask), static_cast<uint16_t *>(dx), total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const void *x, const void *dy, float *dw,
@@ -170,7 +170,7 @@ hipError_t launch_direct_bwd_filters(const ngc_conv_desc &d, int P, int Q, const
     else
         NGC_LAUNCH(direct_bwd_filters<uint16_t>, dim3(blocks), dim3(256), 0, stm, d, P, Q,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(dy), dw);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

@@ -153,7 +153,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 const int cb = s * KB + (pl >> 1);
                 const bool live = cb < CBin;                          // wave-uniform
                 const unsigned soff_x = live ? (unsigned)(cb * HWin * 32) : 0u;
-                const unsigned soff_w = (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16);   // past the end for cb >= CBin: zeros
+                // Filter rows past Cout and channel blocks past Cin must read as zeros.  Only the per-lane offset
+                // takes part in the range check of a buffer load (the scalar offset is added to the base unchecked), so
+                // those lanes get the out-of-range constant rather than an address behind the caller's filter tensor.
+                const unsigned soff_w = live ? (unsigned)(cb * p.Cout * 32 + (pl & 1) * 16) : 0u;
 #pragma unroll
                 for (int b = 0; b < WM; ++b) {
                     if constexpr (XN) break;
@@ -164,7 +167,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 #pragma unroll
                 for (int b = 0; b < WB; ++b)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wt, (lds_void_q *)(ws + pl * WPLANE + b * 1024), 16,
-                                                             (int)(wvoff + b * 64 * 32), (int)soff_w, 0, 0);
+                                                             (int)((live && n0 + lane + b * 64 < p.Cout) ? wvoff + b * 64 * 32 : G1_OOB),
+                                                             (int)soff_w, 0, 0);
             }
         };
 #pragma unroll
@@ -348,7 +352,7 @@ hipError_t launch_zero_fill(void *dst, size_t bytes, hipStream_t st)
     unsigned blocks = (unsigned)((n16 + 255) / 256);
     if (blocks > 4096) blocks = 4096;
     NGC_LAUNCH(zero_fill16, dim3(blocks), dim3(256), 0, st, static_cast<uint4 *>(dst), n16);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN, bool DB = false>
@@ -369,7 +373,7 @@ static hipError_t launch_gemm1x1_l(const Gemm1x1Params &p, hipStream_t st)
     const unsigned mtiles = (p.M + BM - 1) / BM;
     const unsigned grid = ((mtiles + 7) / 8) * 8 * ((p.Cout + BN - 1) / BN);
     NGC_LAUNCH((conv_gemm1x1_bf16<WM, WN, NS, KB, NL, FA, XN, YN, DB>), dim3(grid), dim3(64 * (WM * WN + NL)), lds, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 // the NCHW modes exist for the dispatcher's own tile choices (FA = 2)
@@ -408,7 +412,7 @@ static bool wide_tiles(const Gemm1x1Params &p)
 // tile choice of the NCHW / channel-sum modes (they exist for the dispatcher's own tiles): 0 = large, 3 = small
 static int special_mode_variant(const Gemm1x1Params &p)
 {
-    const char *ev = getenv("NGC_G1_VARIANT");
+    const char *ev = env_switch(SW_G1_VARIANT);
     if (ev && atoi(ev) == 3) return 3;
     if (ev && atoi(ev) == 5) return 0;
     if (!wide_tiles(p)) return 3;                      // same rules as the plain launches
@@ -428,7 +432,7 @@ int gemm1x1_dbp_tile_m(const Gemm1x1Params &p)
 
 hipError_t launch_gemm1x1(const Gemm1x1Params &p, hipStream_t st)
 {
-    const char *ev = getenv("NGC_G1_VARIANT");
+    const char *ev = env_switch(SW_G1_VARIANT);
     int variant = ev ? atoi(ev) : 0;
     const int c128 = (p.Cout + 127) / 128;
     const bool wide = wide_tiles(p);

@@ -276,7 +276,7 @@ static hipError_t launch_igemm_r(const IgemmParams &p, int bn, uint32_t max_m, h
         dim3 grid((max_m + 255) / 256, p.Cout / 64, p.ncls);
         NGC_LAUNCH((igemm_bf16<256, 64, R3>), grid, dim3(256), 0, st, p);
     }
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_igemm(const IgemmParams &p, int bn, uint32_t max_m, hipStream_t st)

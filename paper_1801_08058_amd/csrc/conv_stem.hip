@@ -165,7 +165,7 @@ hipError_t launch_stem_fwd(const StemFwdParams &p, size_t lds_bytes, hipStream_t
 {
     dim3 grid(p.N * p.tiles_per_img, p.K / 64);
     NGC_LAUNCH(conv_stem_fwd_bf16, grid, dim3(256), lds_bytes, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

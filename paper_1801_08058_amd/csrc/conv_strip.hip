@@ -21,11 +21,11 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
 // `waves_per_simd` waves so that one wave's LDS latency hides behind the other's MFMAs
 hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipStream_t st)
 {
-    static const int two_waves = getenv("NGC_STRIP_1WAVE") ? 0 : 1;
+    const int two_waves = env_switch(SW_STRIP_1WAVE) ? 0 : 1;
     StripParams p = p_in;
     // several output-channel tiles: XCD-ordered grid, so that the tiles of a strip read its input through one L2
     // (strided forward layers of the ResNet-50 stack 58 -> 55 us, others 0-2 %; NGC_STRIP_XCD=0: two-dimensional grid)
-    const char *xo = getenv("NGC_STRIP_XCD");
+    const char *xo = env_switch(SW_STRIP_XCD);
     const int gx = p.groups * p.strips;                  // strips per XCD must come out even: a multiple of 8, or many
     if (p.Cout > 64 && (gx % 8 == 0 || gx >= 64) && !(xo && atoi(xo) == 0)) p.xcd_order = 1;
     if (p.r3) {                                          // blocked output, two waves per SIMD; a code object of its own

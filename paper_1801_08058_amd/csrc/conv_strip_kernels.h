@@ -171,7 +171,10 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         xoff[i] = off;
     }
-    const unsigned woff_lane = (unsigned)((k0 + lane) * 32);           // row of the filter slab
+    // Row of the filter slab.  Rows past Cout (partial last tile) get the out-of-range constant and read as zeros:
+    // only this per-lane offset takes part in the range check of a buffer load, the scalar slab / chunk offset is
+    // added to the base unchecked, so a row index past the slab would read the next slab or past the tensor.
+    const unsigned woff_lane = (k0 + lane < p.Cout) ? (unsigned)((k0 + lane) * 32) : STRIP_OOB;
     // fragments of this wave that hold at least one position of the strip (wave-uniform)
     int nfrag = 0;
 #pragma unroll
@@ -208,7 +211,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         if (HALF) {
             for (int t = wave; t < p.ntaps; t += NW) {                   // lanes 0-31: g = 0, lanes 32-63: g = 1
                 const unsigned soff_w = (unsigned)(((p.tap_slab[t] * CB + chunk) * p.Cout) * 32);
-                load_lds16(rs_wt, ws + t * STRIP_WPITCH, (unsigned)((k0 + l32) * 32 + lg * 16), soff_w);
+                load_lds16(rs_wt, ws + t * STRIP_WPITCH, (k0 + l32 < p.Cout) ? (unsigned)((k0 + l32) * 32 + lg * 16) : STRIP_OOB,
+                           soff_w);
             }
         } else {
             for (int j = wave; j < 2 * p.ntaps; j += NW) {                // plane j = tap*2 + g
@@ -508,7 +512,7 @@ static hipError_t launch_strip_d(const StripParams &p, size_t lds_bytes, hipStre
     dim3 grid(p.groups * p.strips, (p.Cout + 63) / 64);
     if (p.xcd_order) grid = dim3(8 * ((p.groups * p.strips + 7) / 8) * ((p.Cout + 63) / 64));
     NGC_LAUNCH((conv_strip_bf16<NF, NW, SUB, DB, R3, CT>), grid, dim3(NW * 64), lds_bytes, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 template <int NF, bool DB, bool R3 = false>
@@ -521,7 +525,7 @@ static hipError_t launch_strip_multi_t(const StripMulti &mp, size_t lds_bytes, h
     }
     dim3 grid(mp.wg_end[mp.n - 1], (mp.c[0].Cout + 63) / 64);
     NGC_LAUNCH((conv_strip_multi_bf16<NF, 8, DB, R3>), grid, dim3(8 * 64), lds_bytes, st, mp);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 // rank-3 launches: defined in conv_strip3.hip

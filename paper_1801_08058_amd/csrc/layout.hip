@@ -217,7 +217,7 @@ hipError_t launch_subpixel_filter(int K, int C, int R, int S, int pbh, int pbw, 
     const size_t total = (size_t)ndr * nds * K * 64;
     NGC_LAUNCH(subpixel_filter, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w_kcrs, wu, K, C, R, S, pbh, pbw,
                dr_min, ds_min, nds, BH, BW, sh, sw, total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 static bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -245,7 +245,7 @@ hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, con
             else if (v == 2) NGC_LAUNCH(blocked16_to_nchw_b16<2>, grid, block, 0, st, s, d, c, HW);
             else NGC_LAUNCH(blocked16_to_nchw_b16<1>, grid, block, 0, st, s, d, c, HW);
         }
-        return hipGetLastError();
+        return ngc::launch_result();
     }
     const size_t total = (dst_layout == NGC_NCHW) ? (size_t)n * c * HW : (size_t)n * CB * HW * 16;
     const unsigned blocks = (unsigned)((total + 255) / 256);
@@ -255,7 +255,7 @@ hipError_t launch_layout_convert(int elem_bytes, int n, int c, int h, int w, con
     else
         NGC_LAUNCH(layout_generic<uint32_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint32_t *>(src),
                            static_cast<uint32_t *>(dst), n, c, h, w, src_layout, dst_layout, total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, const void *w_kcrs, void *dst,
@@ -272,7 +272,7 @@ hipError_t launch_filter_convert(int elem_bytes, int K, int C, int R, int S, con
         NGC_LAUNCH(filter_to_blocked<uint32_t>, dim3(blocks), dim3(256), 0, st,
                            static_cast<const uint32_t *>(w_kcrs), static_cast<uint32_t *>(dst), K, C, R, S, dst_layout,
                            total);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

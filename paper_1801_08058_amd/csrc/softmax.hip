@@ -211,7 +211,7 @@ static hipError_t launch_softmax_t(const T *a, const T *b, T *out, uint32_t rows
     case 0: NGC_LAUNCH((softmax_rows_block<T, BWD>), grid_r, block, 0, st, a, b, out, rows, cols); break;
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_softmax(int dtype, bool bwd, const void *a, const void *b, void *out, uint32_t rows, int cols, int V, hipStream_t st)

@@ -216,7 +216,7 @@ hipError_t launch_wgrad(const WgradParams &p, hipStream_t st)
 {
     dim3 grid(p.splits, (p.K / 64) * (p.C / 64), p.R * p.S);
     NGC_LAUNCH(wgrad_bf16, grid, dim3(256), 0, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int K, int C, int R, int S, hipStream_t st)
@@ -224,7 +224,7 @@ hipError_t launch_wgrad_reduce(const float *partial, float *dw, int splits, int 
     const size_t per = (size_t)R * S * K * C;
     NGC_LAUNCH(wgrad_reduce, dim3((unsigned)((per + 255) / 256)), dim3(256), 0, st, partial, dw, splits, K, C,
                        R * S);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

@@ -326,7 +326,7 @@ static hipError_t launch_wgrad_gemm_l(const WgradGemmParams &p, hipStream_t st)
     dim3 grid(p.nparts, p.ktiles * p.ctiles, wgrad_gemm_taps(p));
     if (XO) grid = dim3(8 * ((p.nparts + 7) / 8) * p.ktiles * p.ctiles * wgrad_gemm_taps(p));
     NGC_LAUNCH((wgrad_gemm_bf16<WK, WC, SP, XN, DN, R3, XO>), grid, dim3(512), lds, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 template <int WK, int WC, int SP>
@@ -366,7 +366,7 @@ hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
     const size_t per4 = (size_t)taps * p.ktiles * p.ctiles * p.wk * p.wc * (64 * 64 / 4);
     NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
                reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

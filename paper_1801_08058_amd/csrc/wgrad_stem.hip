@@ -278,12 +278,12 @@ hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStre
     }
     dim3 grid(p.N * p.strips, p.K / 64);
     NGC_LAUNCH(wgrad_stem_bf16, grid, dim3(512), lds_bytes, st, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = ngc::launch_result();
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)(p.K / 64) * 2 * 4 * WST_NF * 64;
     NGC_LAUNCH(wgrad_stem_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
                reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.N * p.strips, p.K, p.C);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

@@ -358,7 +358,7 @@ static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_b
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
     NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI>), grid, dim3(512), lds_bytes, st, p);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
@@ -379,7 +379,7 @@ hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipSt
     const size_t per4 = (size_t)WS_NT * p.K * p.C / 4;
     NGC_LAUNCH(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
                        reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
-    return hipGetLastError();
+    return ngc::launch_result();
 }
 
 }  // namespace ngc

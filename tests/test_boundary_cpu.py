@@ -389,3 +389,89 @@ def test_operands_past_two_gib_run_in_groups_of_images():
     # one image of 2 GiB: nothing to slice
     one = ng.make_desc(1, 64, 4100, 4100, 64, 3, 3)
     assert ng.ngc_conv_variant(one, F) == "igemm_bf16_256x64"
+
+
+def test_sliced_nodes_size_their_workspace_for_every_group():
+    """A node that runs as launches over groups of images (tensors of 2 GiB or more) hands every group the same
+    workspace; the split of a backprop-filters reduction is not monotone in the batch, so the remainder group can need
+    more than a full one (n = 215, C = K = 128, 200x200: 209 + 6 images).  The size the library reports must cover
+    both, for every op."""
+    F, B, W, DB = ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS, ng.NGC_OP_BWD_DATA_DB
+    mk = lambda n, c=128, k=128, hw=200, wl=ng.NGC_KCRS: ng.make_desc(n, c, hw, hw, k, 3, 3, pad_below=(1, 1), pad_above=(1, 1), w_layout=wl)
+    per_image = 128 * 200 * 200 * 2
+    full = ((1 << 31) - 1) // per_image
+    checked = 0
+    for n in list(range(full + 1, full + 40)) + [215, 2 * full + 3, 3 * full - 1]:
+        d = mk(n)
+        if not ng.ngc_conv_variant(d, W).startswith("sliced"):
+            continue
+        rem = n % full
+        row = (128 * 128 * 9 + 15) // 16 * 16 * 4
+        groups = (n + full - 1) // full
+        dw_rows = (groups * row + 255) // 256 * 256
+        for op in (F, B, W):
+            total = ng.ngc_conv_workspace_bytes(d, op)
+            base = total - (dw_rows if op == W else 0)
+            for g in ([full] + ([rem] if rem else [])):
+                need = ng.ngc_conv_workspace_bytes(mk(g), op)
+                assert need <= base, (n, op, g, need, base)
+        checked += 1
+    assert checked >= 30
+
+
+def test_host_time_per_dispatch_with_launches_stubbed():
+    """Kernel selection is meant to be negligible next to kernels of 10-20 us: with NGC_DRY_RUN=1 (every launch
+    skipped after the planning) a call through the C ABI with a descriptor the library has seen before has to stay
+    under 2 us of host time.  Plain C program against the built library, 10^4 calls per entry point."""
+    src = r'''
+#include "ngconv.h"
+#include <stdio.h>
+#include <stdlib.h>
+#include <time.h>
+static double now_us(void) { struct timespec t; clock_gettime(CLOCK_MONOTONIC, &t); return t.tv_sec * 1e6 + t.tv_nsec * 1e-3; }
+static ngc_conv_desc mk(int n, int c, int hw, int k, int r, int stride, int wl, int epi) {
+    ngc_conv_desc d = {n, c, hw, hw, k, r, r, stride, stride, 1, 1, r / 2, r / 2, r / 2, r / 2, NGC_BF16, NGC_NCHW16C, NGC_NCHW16C, wl, epi};
+    return d;
+}
+int main(void) {
+    setenv("NGC_DRY_RUN", "1", 1);
+    void *p = (void *)(size_t)0x100000;                     /* never dereferenced: nothing is launched */
+    const size_t big = (size_t)1 << 40;
+    const int shapes[6][5] = {{64, 64, 56, 64, 3}, {128, 256, 56, 64, 1}, {128, 128, 28, 128, 3}, {128, 512, 14, 512, 3},
+                              {128, 1024, 14, 2048, 1}, {128, 128, 56, 128, 3}};
+    double worst = 0;
+    for (int s = 0; s < 6; ++s) {
+        const int stride = s >= 4 ? 2 : 1;
+        ngc_conv_desc f = mk(shapes[s][0], shapes[s][1], shapes[s][2], shapes[s][3], shapes[s][4], stride, NGC_BLOCKED_FWD, NGC_EPI_BIAS | NGC_EPI_RELU);
+        ngc_conv_desc b = mk(shapes[s][0], shapes[s][1], shapes[s][2], shapes[s][3], shapes[s][4], stride, NGC_BLOCKED_BWD, 0);
+        ngc_conv_desc w = mk(shapes[s][0], shapes[s][1], shapes[s][2], shapes[s][3], shapes[s][4], stride, NGC_KCRS, 0);
+        for (int op = 0; op < 4; ++op) {
+            double t0 = 0;
+            for (int i = -100; i < 10000; ++i) {
+                if (i == 0) t0 = now_us();
+                int rc = op == 0 ? ngc_conv_fwd(&f, p, p, (const float *)p, p, p, big, 0)
+                       : op == 1 ? ngc_conv_bwd_data(&b, p, p, p, p, big, 0)
+                       : op == 2 ? ngc_conv_bwd_filters(&w, p, p, (float *)p, p, big, 0)
+                                 : ngc_bias_grad(&w, p, (float *)p, p, big, 0);
+                if (rc != NGC_OK) { printf("rc %d shape %d op %d\n", rc, s, op); return 2; }
+            }
+            const double us = (now_us() - t0) / 10000.0;
+            if (us > worst) worst = us;
+            printf("shape %d op %d: %.3f us per call\n", s, op, us);
+        }
+    }
+    printf("worst %.3f\n", worst);
+    return 0;
+}
+'''
+    with tempfile.TemporaryDirectory() as td:
+        c = os.path.join(td, "disp.c")
+        open(c, "w").write(src)
+        exe = os.path.join(td, "disp")
+        libdir = os.path.dirname(ng.LIB_PATH)
+        subprocess.check_call(["gcc", "-O1", "-D_GNU_SOURCE", "-I", os.path.join(ROOT, "include"), "-o", exe, c, "-L", libdir,
+                               "-l:libngconv.so", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"])
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0, r.stdout + r.stderr
+        worst = float(r.stdout.strip().splitlines()[-1].split()[1])
+        assert worst < 2.0, r.stdout
