@@ -75,7 +75,8 @@ typedef enum {
                                      tensor with >= 2^31 elements */
     NGC_UNSUPPORTED = -3,         /* valid descriptor, but no kernel for this dtype/layout combination */
     NGC_WORKSPACE_TOO_SMALL = -4, /* ws_bytes < ngc_conv_workspace_bytes(...) or ws null when needed */
-    NGC_LAUNCH_FAILED = -5        /* the HIP runtime refused a launch (hipGetLastError != success) */
+    NGC_LAUNCH_FAILED = -5,       /* the HIP runtime refused a launch (hipGetLastError != success) */
+    NGC_SCRATCH_EXCEEDED = -6     /* ngc_conv_bwd_filters_noalloc: the node needs more than NGC_STATIC_SCRATCH_BYTES */
 } ngc_status;
 
 typedef enum { NGC_F32 = 0, NGC_BF16 = 1 } ngc_dtype;
@@ -169,6 +170,18 @@ const char *ngc_softmax_variant(int32_t dtype, int32_t cols, int32_t bwd);
  * reduction goes through `ws` (partials) and a fixed-order second stage. */
 int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy,
                          float *dw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ngc_conv_bwd_filters for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same result (bit for bit), same
+ * kernels, same argument rules; the split-reduction partials go to an array of NGC_STATIC_SCRATCH_BYTES that is
+ * part of the library's device image (each GPU the library runs on holds one copy until the process ends).  The
+ * call allocates and frees nothing.  A node whose ngc_conv_workspace_bytes(desc, NGC_OP_BWD_FILTERS) exceeds the
+ * array is refused with NGC_SCRATCH_EXCEEDED before anything is launched.  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (two streams, two threads) race on it; calls on one stream are safe. */
+#define NGC_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int ngc_conv_bwd_filters_noalloc(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw,
+                                 void *hip_stream);
+size_t ngc_static_scratch_bytes(void);
 
 /* Data layout conversion (Abstract / Sec. 2: data layout abstraction): copies bit patterns
  * between NGC_NCHW and NGC_NCHW16C for an [n,c,h,w] tensor of `dtype`; tail lanes of a blocked

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libngconv.so")
 
 # enums of include/ngconv.h
 NGC_OK, NGC_BAD_ARG, NGC_BAD_SHAPE, NGC_UNSUPPORTED, NGC_WORKSPACE_TOO_SMALL, NGC_LAUNCH_FAILED = 0, -1, -2, -3, -4, -5
+NGC_SCRATCH_EXCEEDED = -6
 NGC_F32, NGC_BF16 = 0, 1
 NGC_NCHW, NGC_NCHW16C = 0, 1
 NGC_KCRS, NGC_BLOCKED_FWD, NGC_BLOCKED_BWD = 0, 1, 2
@@ -28,7 +29,7 @@ EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ng
            "ngc_conv3d_out_shape", "ngc_conv3d_workspace_bytes", "ngc_conv3d_fwd", "ngc_conv3d_bwd_data",
            "ngc_conv3d_bwd_filters", "ngc_conv3d_filter_convert", "ngc_conv3d_filter_elems", "ngc_conv3d_data_elems",
            "ngc_conv3d_variant", "ngc_conv3d_bwd_data_relu", "ngc_conv3d_bwd_data_relu_db", "ngc_conv3d_bias_grad",
-           "ngc_reload_switches")
+           "ngc_conv_bwd_filters_noalloc", "ngc_static_scratch_bytes", "ngc_reload_switches")
 
 
 class ngc_conv_desc(ctypes.Structure):
@@ -96,8 +97,12 @@ def _load() -> ctypes.CDLL:
     lib.ngc_softmax_variant.restype = ctypes.c_char_p
     lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_filters.restype = ctypes.c_int
+    lib.ngc_conv_bwd_filters_noalloc.argtypes = [D, vp, vp, vp, vp]
+    lib.ngc_conv_bwd_filters_noalloc.restype = ctypes.c_int
     lib.ngc_reload_switches.argtypes = []
     lib.ngc_reload_switches.restype = None
+    lib.ngc_static_scratch_bytes.argtypes = []
+    lib.ngc_static_scratch_bytes.restype = sz
     lib.ngc_layout_convert.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, i32, vp]
     lib.ngc_layout_convert.restype = ctypes.c_int
     lib.ngc_filter_convert.argtypes = [D, vp, vp, i32, vp]
@@ -246,8 +251,17 @@ def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = Tr
                                             _stream(stream)), "ngc_conv_bwd_filters", check)
 
 
+def ngc_conv_bwd_filters_noalloc(desc, x, dy, dw, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_filters_noalloc(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _stream(stream)),
+                  "ngc_conv_bwd_filters_noalloc", check)
+
+
 def ngc_reload_switches() -> None:
     _lib.ngc_reload_switches()
+
+
+def ngc_static_scratch_bytes() -> int:
+    return int(_lib.ngc_static_scratch_bytes())
 
 
 def ngc_layout_convert(dtype, n, c, h, w, src, src_layout, dst, dst_layout, stream=None, check: bool = True) -> int:

@@ -1217,6 +1217,7 @@ const char *ngc_status_string(int status)
     case NGC_UNSUPPORTED: return "no kernel for this element type / layout combination";
     case NGC_WORKSPACE_TOO_SMALL: return "workspace too small or missing";
     case NGC_LAUNCH_FAILED: return "HIP launch failed";
+    case NGC_SCRATCH_EXCEEDED: return "the node needs more scratch memory than the library's static array holds (use the entry point with a workspace)";
     default: return "unknown status";
     }
 }
