@@ -141,7 +141,7 @@ ngc_conv_desc with_batch(const ngc_conv_desc *d, int n)
     return t;
 }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1 };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1, V_ROWS };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -421,6 +421,90 @@ bool strip_plan(const ngc_conv_desc *d, int op, int P, int Q)
     if (ncls > 16) return false;
     for (int c = 0; c < ncls; ++c)
         if (!strip_plan_class(d, op, c / d->stride_w, c % d->stride_w, P, Q, nullptr, nullptr, nullptr, nullptr)) return false;
+    return true;
+}
+
+// Filter-resident strip kernel: stride-1 forward (op 0) or backprop-data (op 1) of a multi-tap node whose filter
+// tile (all taps x Cin x 64 output channels) fits the LDS next to three stage buffers of the input patch.
+bool rows_plan_uncached(const ngc_conv_desc *d, int op, int P, int Q, RowsParams *rp, size_t *lds_out)
+{
+    // Built and measured, not selected by default: on the 56x56, 64 -> 64 layers it is level with the strip kernel at
+    // batch 128 (40.1 / 40.4 us against 42.0 / 40.2 us) and behind it at batch 64 (22.5 against 21.3 / 19.9 us).
+    // NGC_ROWS=1 selects it (tests / experiments).
+    const char *sw = env_switch(SW_ROWS);
+    if (!sw || atoi(sw) != 1) return false;
+    if (env_switch(SW_STRIP_NF) || env_switch(SW_STRIP_1WAVE)) return false;   // forced strip-kernel variants
+    if (d->stride_h != 1 || d->stride_w != 1) return false;
+    const int ntaps = d->r * d->s;
+    if (ntaps != 9) return false;                                        // the kernel's tap loop is unrolled for 9 taps
+    const bool fwd = op == NGC_OP_FWD;
+    const int Cin = fwd ? d->c : d->k, Cout = fwd ? d->k : d->c;
+    if (Cin % 16 != 0 || Cout % 16 != 0) return false;
+    const int Hin = fwd ? d->h : P, Win = fwd ? d->w : Q;
+    const int Hout = fwd ? P : d->h, Wout = fwd ? Q : d->w;
+    const size_t in_bytes = (size_t)d->n * Cin * Hin * Win * 2, wt_bytes = (size_t)ntaps * Cin * Cout * 2;
+    if (in_bytes >= ((size_t)1 << 31) || wt_bytes >= ((size_t)1 << 31)) return false;
+    const int CB = Cin / 16;
+    const size_t filter_lds = (size_t)CB * ntaps * 2 * (64 * 16 + 128);
+    if (filter_lds > 96 * 1024) return false;
+    if (Wout < 8 || Hout < 2) return false;
+    RowsParams q;
+    memset(&q, 0, sizeof(q));
+    int min_dh = INT_MAX, max_dh = INT_MIN, min_dw = INT_MAX, max_dw = INT_MIN;
+    int tdh[STRIP_MAX_TAPS], tdw[STRIP_MAX_TAPS];
+    int t = 0;
+    for (int r = 0; r < d->r; ++r)
+        for (int s2 = 0; s2 < d->s; ++s2) {
+            tdh[t] = fwd ? r * d->dil_h - d->pad_below_h : d->pad_below_h - r * d->dil_h;
+            tdw[t] = fwd ? s2 * d->dil_w - d->pad_below_w : d->pad_below_w - s2 * d->dil_w;
+            if (tdh[t] < min_dh) min_dh = tdh[t];
+            if (tdh[t] > max_dh) max_dh = tdh[t];
+            if (tdw[t] < min_dw) min_dw = tdw[t];
+            if (tdw[t] > max_dw) max_dw = tdw[t];
+            q.tap_slab[t] = r * d->s + s2;
+            ++t;
+        }
+    const int span_h = max_dh - min_dh, span_w = max_dw - min_dw;
+    q.PC = Wout + span_w;
+    // rows per sub-strip: at most 512 positions, a patch of at most 24 blocks of 64 pixels, everything in the LDS
+    int srb = 0, nblocks = 0;
+    for (int cand = 512 / Wout < Hout ? 512 / Wout : Hout; cand >= 1; --cand) {
+        const int nb = ((cand + span_h) * q.PC + 63) / 64;
+        if (nb > 24) continue;
+        if (filter_lds + (size_t)ROWS_NBUF * 2 * ((size_t)nb * 1024 + 128) + 256 > LDS_LIMIT) continue;   // + bias
+        srb = cand;
+        nblocks = nb;
+        break;
+    }
+    // worth it only while the halo rows of a sub-strip stay a minor part of its patch (wide images: strip kernel)
+    if (srb < 1 || srb * Wout < 64 || srb < 2 * span_h) return false;
+    // workgroups per image: enough to fill the chip, strips of whole sub-strips where possible
+    const int ktiles = (Cout + 63) / 64;
+    int strips = (NUM_CUS + d->n * ktiles - 1) / (d->n * ktiles);
+    const int max_strips = (Hout + srb - 1) / srb;
+    if (strips > max_strips) strips = max_strips;
+    if (strips < 1) strips = 1;
+    q.TP = (Hout + strips - 1) / strips;
+    q.strips = (Hout + q.TP - 1) / q.TP;
+    q.SRB = srb;
+    q.N = d->n; q.Cin = Cin; q.Hin = Hin; q.Win = Win; q.Cout = Cout; q.Hout = Hout; q.Wout = Wout;
+    q.min_dh = min_dh; q.min_dw = min_dw; q.span_h = span_h;
+    q.nblocks = nblocks;
+    q.xpitch = nblocks * 1024 + 128;
+    q.ntaps = ntaps;
+    for (int i = 0; i < ntaps; ++i) q.tap_off[i] = (tdh[i] - min_dh) * q.PC + (tdw[i] - min_dw);
+    q.in_bytes = (uint32_t)in_bytes;
+    q.wt_bytes = (uint32_t)wt_bytes;
+    const size_t out_bytes = (size_t)d->n * Cout * Hout * Wout * 2;
+    if (out_bytes >= ((size_t)1 << 31)) return false;
+    q.out_bytes = (uint32_t)out_bytes;
+    const char *fl = env_switch(SW_ROWS_LATE);                          // tests / experiments only: wave mask
+    q.late_mask = fl ? (int)strtol(fl, nullptr, 0) & 0xFF : 0;
+    q.div_q = make_fastdiv((uint32_t)Wout);
+    q.div_pc = make_fastdiv((uint32_t)q.PC);
+    if ((size_t)d->n * q.strips > 0x7FFFFFFF) return false;
+    if (rp) *rp = q;
+    if (lds_out) *lds_out = filter_lds + (size_t)ROWS_NBUF * 2 * q.xpitch;
     return true;
 }
 
@@ -908,6 +992,22 @@ bool gemm1x1_plan(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1Params *g
     return e->ok;
 }
 
+bool rows_plan(const ngc_conv_desc *d, int op, int P, int Q, RowsParams *rp, size_t *lds_out)
+{
+    static thread_local PlanCache<CachedPlan<RowsParams>> cache;
+    const PlanKey key = plan_key(d, op);
+    auto *e = cache.find(key);
+    if (!e) {
+        CachedPlan<RowsParams> v;
+        memset(&v, 0, sizeof(v));
+        v.ok = rows_plan_uncached(d, op, P, Q, &v.v, &v.lds);
+        e = &cache.put(key, v);
+    }
+    if (e->ok && rp) *rp = e->v;
+    if (e->ok && lds_out) *lds_out = e->lds;
+    return e->ok;
+}
+
 bool blocked_bf16(const ngc_conv_desc *d)
 {
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
@@ -922,7 +1022,7 @@ Variant pick_uncached(const ngc_conv_desc *d, int op)
         const bool wl = d->w_layout == NGC_KCRS || d->w_layout == NGC_BLOCKED_FWD;
         const bool base = blocked_bf16(d) && wl;
         const bool mf = base && d->c % 32 == 0 && d->k % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS;
-        if (base && strip_plan(d, op, P, Q)) return V_STRIP;
+        if (base && strip_plan(d, op, P, Q)) return rows_plan(d, op, P, Q, nullptr, nullptr) ? V_ROWS : V_STRIP;
         if (wl && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->k % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
@@ -933,7 +1033,7 @@ Variant pick_uncached(const ngc_conv_desc *d, int op)
         const bool base = blocked_bf16(d) && wl;
         const bool mf = base && d->k % 32 == 0 && d->c % 64 == 0 && d->r * d->s <= IGEMM_MAX_TAPS &&
                         d->stride_h * d->stride_w <= IGEMM_MAX_CLASSES;
-        if (base && strip_plan(d, op, P, Q)) return V_STRIP;
+        if (base && strip_plan(d, op, P, Q)) return rows_plan(d, op, P, Q, nullptr, nullptr) ? V_ROWS : V_STRIP;
         if (wl && gemm1x1_plan(d, op, P, Q, nullptr, nullptr)) return V_GEMM1X1;
         if (mf) return d->c % 128 == 0 ? V_IGEMM_128 : V_IGEMM_64;
         return d->w_layout == NGC_KCRS ? V_DIRECT : V_UNSUPPORTED;
@@ -994,6 +1094,7 @@ ngc_conv_desc dx_as_dy(const ngc_conv_desc *d)
 bool db_fusable(const ngc_conv_desc *d, Variant v)
 {
     if (env_switch(SW_DB_FUSE) && atoi(env_switch(SW_DB_FUSE)) == 0) return false;   // tests / benchmarks only
+    if (v == V_ROWS) v = V_STRIP;                         // channel sums come from the strip kernel's launches
     if (v == V_STRIP) {                                   // the kernels with column tiles write no channel sums
         int P, Q;
         return env_switch(SW_STRIP_1WAVE) == nullptr && validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
@@ -1006,6 +1107,7 @@ bool db_fusable(const ngc_conv_desc *d, Variant v)
 int db_fused_rows(const ngc_conv_desc *d, Variant v, int P, int Q)
 {
     int rows = 0;
+    if (v == V_ROWS) v = V_STRIP;
     if (v == V_STRIP) {
         const int ncls = strip_classes(d, NGC_OP_BWD_DATA);
         for (int c = 0; c < ncls; ++c) {
@@ -1040,9 +1142,9 @@ size_t workspace_bytes_uncached(const ngc_conv_desc *d, int op, Variant v, int P
         return base + round256((size_t)bias_grad_parts(t, d->h, d->w) * ((d->c + 15) / 16 * 16) * sizeof(float));
     }
     if (op == NGC_OP_BIAS_GRAD) return round256((size_t)bias_grad_parts(*d, P, Q) * ((d->k + 15) / 16 * 16) * sizeof(float));
-    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
+    if (op == NGC_OP_FWD && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_ROWS || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_FWD) * 2) : 0;
-    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_GEMM1X1))
+    if (op == NGC_OP_BWD_DATA && (v == V_IGEMM_128 || v == V_IGEMM_64 || v == V_STRIP || v == V_ROWS || v == V_GEMM1X1))
         return d->w_layout == NGC_KCRS ? round256(filter_elems(d, NGC_BLOCKED_BWD) * 2) : 0;
     if (op == NGC_OP_BWD_DATA && v == V_STEM_BWD) {
         StemBwdPlan pl;
@@ -1198,6 +1300,7 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_IGEMM_64: return "igemm_bf16_256x64";
     case V_WGRAD_64: return "wgrad_bf16_64x64";
     case V_STRIP: return "strip_bf16";
+    case V_ROWS: return "strip_rows_bf16";
     case V_WGRAD_STRIP: return "wgrad_strip_bf16";
     case V_STEM_FWD: return "stem_fwd_bf16";
     case V_WGRAD_STEM: return "wgrad_stem_bf16";
@@ -1265,6 +1368,17 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_FWD, st);
         if (e != hipSuccess) return NGC_LAUNCH_FAILED;
         wt = ws;
+    }
+    if (v == V_ROWS) {
+        RowsParams rp;
+        size_t lds;
+        if (!rows_plan(desc, NGC_OP_FWD, P, Q, &rp, &lds)) return NGC_UNSUPPORTED;
+        rp.in = static_cast<const uint16_t *>(x);
+        rp.wt = static_cast<const uint16_t *>(wt);
+        rp.out = static_cast<uint16_t *>(y);
+        rp.bias = (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr;
+        rp.relu = (desc->epilogue & NGC_EPI_RELU) ? 1 : 0;
+        return launch_status(launch_rows(rp, lds, st));
     }
     if (v == V_STRIP) {
         StripParams sp;
@@ -1335,8 +1449,9 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
     if (vs != NGC_OK) return vs;
     if (!dy || !w || !dx) return NGC_BAD_ARG;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws) || !aligned16(mask)) return NGC_BAD_ARG;
-    const Variant v = pick(desc, NGC_OP_BWD_DATA);
+    Variant v = pick(desc, NGC_OP_BWD_DATA);
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
+    if (v == V_ROWS && fuse) v = V_STRIP;                  // the channel sums of dx come from the strip kernel
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, mask, dx, st));
     if (v == V_STEM_BWD) {
@@ -1364,6 +1479,16 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         const hipError_t e = launch_filter_convert(2, desc->k, desc->c, desc->r, desc->s, w, ws, NGC_BLOCKED_BWD, st);
         if (e != hipSuccess) return NGC_LAUNCH_FAILED;
         wt = ws;
+    }
+    if (v == V_ROWS) {
+        RowsParams rp;
+        size_t lds;
+        if (!rows_plan(desc, NGC_OP_BWD_DATA, P, Q, &rp, &lds)) return NGC_UNSUPPORTED;
+        rp.in = static_cast<const uint16_t *>(dy);
+        rp.wt = static_cast<const uint16_t *>(wt);
+        rp.out = static_cast<uint16_t *>(dx);
+        rp.mask = static_cast<const uint16_t *>(mask);
+        return launch_status(launch_rows(rp, lds, st));
     }
     if (v == V_STRIP) {
         if (strip_zero_fill(desc)) {

@@ -20,7 +20,7 @@ namespace ngc {
 // The NGC_* variables are read once per process, at the first use, into a table; env_switch(SW_X) returns the value of
 // NGC_X or nullptr.  ngc_reload_switches() (exported for the test suite) reads them again and bumps the epoch, which
 // also drops every cached plan.
-enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_DRY_RUN, SW_COUNT };
+enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_ROWS, SW_ROWS_LATE, SW_DRY_RUN, SW_COUNT };
 const char *env_switch(Switch s);
 uint32_t sw_epoch();
 // NGC_DRY_RUN=1: every launch is skipped after the host-side planning (host-path timing without a GPU)
@@ -92,24 +92,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
 // necessary is always correct, so counts beyond the table fall back to vmcnt(0).
 __device__ __forceinline__ void wait_vmcnt(int n)
 {
+    // the count is a 6-bit field split over bits 3:0 and 15:14 of the immediate; the other counters stay unconstrained
+#define NGC_VMCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
     switch (n) {
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    case 15: __builtin_amdgcn_s_waitcnt(0x0F7F); break;
+        NGC_VMCNT_CASE(1) NGC_VMCNT_CASE(2) NGC_VMCNT_CASE(3) NGC_VMCNT_CASE(4) NGC_VMCNT_CASE(5) NGC_VMCNT_CASE(6)
+        NGC_VMCNT_CASE(7) NGC_VMCNT_CASE(8) NGC_VMCNT_CASE(9) NGC_VMCNT_CASE(10) NGC_VMCNT_CASE(11) NGC_VMCNT_CASE(12)
+        NGC_VMCNT_CASE(13) NGC_VMCNT_CASE(14) NGC_VMCNT_CASE(15) NGC_VMCNT_CASE(16) NGC_VMCNT_CASE(17) NGC_VMCNT_CASE(18)
+        NGC_VMCNT_CASE(19) NGC_VMCNT_CASE(20) NGC_VMCNT_CASE(21) NGC_VMCNT_CASE(22) NGC_VMCNT_CASE(23) NGC_VMCNT_CASE(24)
+        NGC_VMCNT_CASE(25) NGC_VMCNT_CASE(26) NGC_VMCNT_CASE(27) NGC_VMCNT_CASE(28) NGC_VMCNT_CASE(29) NGC_VMCNT_CASE(30)
+        NGC_VMCNT_CASE(31)
     default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
     }
+#undef NGC_VMCNT_CASE
 }
 
 // Each lane of a 32-lane half-wave holds v[0..31]; returns, in lane l (l = lane % 32), the sum over the 32
@@ -294,6 +288,31 @@ struct StripParams {
     int32_t ncolt, BW;
     FastDiv div_ncolt;
 };
+
+// ---- filter-resident strip kernel (stride-1 forward / backprop-data with a filter that fits the LDS) ----
+struct RowsParams {
+    const uint16_t *in;
+    const uint16_t *wt;
+    uint16_t *out;
+    const float *bias;         // may be null
+    const uint16_t *mask;      // may be null; else same shape / layout as out: out = (mask > 0) ? out : 0
+    int32_t N, Cin, Hin, Win, Cout, Hout, Wout;
+    int32_t TP, strips;        // output rows per workgroup, workgroups per image
+    int32_t SRB;               // output rows per sub-strip (SRB * Wout <= 512 positions)
+    int32_t PC;                // patch columns (Wout + window span in w)
+    int32_t min_dh, min_dw, span_h;
+    int32_t nblocks;           // 64-pixel blocks of the input patch of a full sub-strip
+    int32_t xpitch;            // bytes per 8-channel plane of a stage buffer
+    int32_t relu;
+    int32_t ntaps;
+    int32_t tap_off[STRIP_MAX_TAPS];    // patch-pixel offset of the tap
+    int32_t tap_slab[STRIP_MAX_TAPS];   // filter slab (r * S + s) the tap reads
+    uint32_t in_bytes, wt_bytes, out_bytes;
+    int32_t late_mask;         // bit w: wave w issues the loads of a later stage after its MFMAs instead of before
+    FastDiv div_q, div_pc;
+};
+constexpr int ROWS_NBUF = 3;             // stage buffers of the input patch (prefetch two stages ahead)
+hipError_t launch_rows(const RowsParams &p, size_t lds_bytes, hipStream_t st);
 
 // ---- MFMA backprop-filters ----
 struct WgradParams {

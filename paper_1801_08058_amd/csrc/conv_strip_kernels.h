@@ -242,6 +242,20 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         pbase[i] = pb * 16;
     }
 
+    // bias values of this lane's channels, requested before the chunk loop so that the epilogue does not start with
+    // a round trip to memory
+    float4 bv[2][2][2];                                   // [a][h][which quad]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.bias && k0 + a * 32 + 16 * h < p.Cout) {       // the last 64-channel tile may be partial (Cout % 16 == 0)
+                bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
+                bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
+            }
+        }
+
     f32x16 acc[NF][2];
 #pragma unroll
     for (int i = 0; i < NF; ++i)
@@ -286,29 +300,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             }
         }
     };
-    if constexpr (R3) {
-        if (nfrag == NF) chunk_loop(std::integral_constant<int, NF>{});
-        else if (NF > 1 && nfrag == NF - 1) chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{});
-        else chunk_loop(std::integral_constant<int, 0>{});
-    } else {
-        chunk_loop(std::integral_constant<int, 0>{});
-    }
+    if (nfrag == NF) chunk_loop(std::integral_constant<int, NF>{});
+    else if (NF > 1 && nfrag == NF - 1) chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{});
+    else chunk_loop(std::integral_constant<int, 0>{});
 
     // ---- epilogue
     const int CBout = p.Cout >> 4;
     const int HWout = p.Hfull * p.Wfull;
     const int plane_out = R3 ? p.Dfull * HWout : HWout;  // pixel blocks per 16-channel plane of a batch element
-    float4 bv[2][2][2];                                   // [a][h][which quad]
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (p.bias && k0 + a * 32 + 16 * h < p.Cout) {       // the last 64-channel tile may be partial (Cout % 16 == 0)
-                bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
-                bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
-            }
-        }
     float csum[DB ? 2 : 1][2][8];                         // DB: channel sums of this lane's stored values
 #pragma unroll
     for (int a = 0; a < (DB ? 2 : 1); ++a)

@@ -49,7 +49,7 @@ def test_bottleneck_chain_forward_backward(n, hw, c0, c1, c3):
         wf.append(dev(filter_blocked_host(wbits, ng.NGC_BLOCKED_FWD)))
         wb.append(dev(filter_blocked_host(wbits, ng.NGC_BLOCKED_BWD)))
         descs.append((d_f, desc_of(a, "bf16", xl, yl, ng.NGC_BLOCKED_BWD), desc_of(a, "bf16", xl, yl)))
-        assert ng.ngc_conv_variant(d_f, ng.NGC_OP_FWD) in ("gemm1x1_bf16", "strip_bf16")
+        assert ng.ngc_conv_variant(d_f, ng.NGC_OP_FWD) in ("gemm1x1_bf16", "strip_bf16", "strip_rows_bf16")
         y = torch.empty(ng.ngc_data_elems(d_f, 1), dtype=torch.int16, device="cuda")
         ng.ngc_conv_fwd(d_f, acts_dev[-1], wf[i], dev(np.asarray(bs_[i], dtype=np.float32)), y, workspace(d_f, ng.NGC_OP_FWD), st)
         torch.cuda.synchronize()

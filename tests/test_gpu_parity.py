@@ -745,7 +745,7 @@ EPILOGUE_BIT_CASES = [
 
 
 @pytest.mark.parametrize("case", range(len(EPILOGUE_BIT_CASES)))
-def test_epilogue_bias_relu_single_rne_rounding_bit_exact(case):
+def test_epilogue_bias_relu_single_rne_rounding_bit_exact(case, expect=None):
     """Bias, then ReLU, then exactly one round-to-nearest-even conversion of the fp32 value.  The filter is a single
     tap of ones on c == k mod C, so the fp32 accumulator of every kernel equals one input element exactly; the input
     values and the fp32 biases are chosen so that x + b lands on exact ties of the bf16 grid (both parities of the kept
@@ -769,7 +769,7 @@ def test_epilogue_bias_relu_single_rne_rounding_bit_exact(case):
         w[k, k % a.c, r0, s0] = 1.0
     run = Run(a, "bf16", xl, yl, True)
     run.fwd(x, w, bias=b, relu=True)
-    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD).startswith(variant), ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD).startswith(expect or variant), ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD)
     raw = host(run.last_raw, np.uint16)
     if yl == BLK:
         got = oracle.blocked16_to_nchw(raw.reshape(a.n, (a.k + 15) // 16, P, Q, 16), a.k)
@@ -794,3 +794,26 @@ def test_epilogue_bias_relu_single_rne_rounding_bit_exact(case):
     bad = np.argwhere(got_cmp != want)
     assert bad.size == 0, (f"{len(bad)} elements differ, first at {bad[0]}: got {got[tuple(bad[0])]:#06x} want "
                            f"{want[tuple(bad[0])]:#06x} from fp32 bits {v.view(np.uint32)[tuple(bad[0])]:#010x}")
+
+
+# ------------------------------------------------------------------ filter-resident strip kernel (opt-in)
+ROWS_CASES = [
+    Attrs(3, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # the headline shape: sub-strips of 8 + 8 + ... rows
+    Attrs(2, 64, 30, 20, 48, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # ragged fragments, partial channel tile (forward)
+    Attrs(2, 32, 17, 56, 64, 3, 3, 1, 1, 1, 1, 0, 2, 2, 0),      # one-sided padding, strips that end inside a sub-strip
+    Attrs(2, 16, 9, 12, 16, 3, 3, 1, 1, 2, 2, 2, 2, 2, 2),       # one chunk, dilation 2
+    Attrs(5, 48, 14, 14, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),      # three chunks, small images
+]
+
+
+@pytest.mark.parametrize("case", range(len(ROWS_CASES)))
+def test_filter_resident_strip_kernel(case, monkeypatch):
+    """NGC_ROWS=1 selects the filter-resident form of the strip kernel for stride-1 3x3 nodes whose filter tile fits the
+    LDS (forward and backprop-data, with the ReLU-backprop mask); everything else of the node runs as usual."""
+    monkeypatch.setenv("NGC_ROWS", "1")
+    _check_all(ROWS_CASES[case], "bf16", BLK, BLK, True, 9800 + case, ("strip_rows", "strip_rows", "wgrad"))
+
+
+def test_filter_resident_strip_kernel_epilogue_bits(monkeypatch):
+    monkeypatch.setenv("NGC_ROWS", "1")
+    test_epilogue_bias_relu_single_rne_rounding_bit_exact(0, expect="strip_rows_bf16")
