@@ -421,6 +421,30 @@ struct Gemm1x1Params {
     FastDiv div_pq, div_q;
 };
 
+// Direct global->LDS load of 16 bytes per lane (lane l lands at lds_dst + 16 l, lanes whose offset is out of range
+// deliver zeros), written as an instruction sequence the compiler does not interpret.  With the builtin form the
+// compiler knows that an LDS write is in flight and makes every later LDS read of the wave it cannot tell apart from
+// it (the transpose loads, for one) wait for vmcnt(0), i.e. for every stage the wave has prefetched: a ring of
+// stage buffers then runs as a single buffer.  Callers order their accesses themselves, as they do anyway:
+// wait_vmcnt(n) for the stage about to be read, then the workgroup barrier.
+// rsrc: buffer descriptor words {base[31:0], base[47:32], bytes, 0x00020000}.
+typedef unsigned ngc_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ ngc_u32x4 make_rsrc_words(const void *base, unsigned bytes)
+{
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    ngc_u32x4 r = {(unsigned)b, (unsigned)(b >> 32) & 0xFFFFu, bytes, 0x00020000u};
+    return r;
+}
+__device__ __forceinline__ void dma_load_lds16(ngc_u32x4 rsrc, const void *lds_dst_uniform, unsigned voff, unsigned soff)
+{
+    typedef __attribute__((address_space(3))) const void lds_cvoid;
+    const unsigned m0v = (unsigned)reinterpret_cast<unsigned long long>((lds_cvoid *)lds_dst_uniform) ;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(m0v), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+}
+
 // Workgroup barrier without the memory fence of __syncthreads().  The fence waits for every
 // outstanding global->LDS load of the wave (s_waitcnt vmcnt(0)), which would serialise a
 // multi-stage prefetch ring.  Callers order their LDS traffic themselves: s_waitcnt vmcnt(n) for

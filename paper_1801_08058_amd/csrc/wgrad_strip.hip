@@ -45,6 +45,18 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+#ifdef NGC_TIMELINE
+// development builds only: time stamps (100 MHz counter) of lane 0 of every wave in 4 KB of LDS behind the stage ring
+__device__ unsigned long long g_ws_timeline[1024 * 8 * 64];
+#define WS_TL()                                                                                   \
+    do {                                                                                          \
+        if (lane == 0 && tl_n < 64) tl_lds[wave * 64 + tl_n] = wall_clock64();                    \
+        ++tl_n;                                                                                   \
+    } while (0)
+#else
+#define WS_TL() do { } while (0)
+#endif
+
 constexpr unsigned WS_OOB = 0x80000000u;
 constexpr int WS_NT = 9;
 constexpr int WS_MAXI = 10;                        // load items per wave and stage (host guarantees items <= 80)
@@ -91,9 +103,19 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     const int HW = p.H * p.W;
     const int KB = p.K >> 4, CB = p.C >> 4;
     const int stage_bytes = 4 * p.dyplane + NCQ * p.xplane;
+#ifdef NGC_TIMELINE
+    int tl_n = 0;
+    unsigned long long *tl_lds = reinterpret_cast<unsigned long long *>(smem + p.nring * stage_bytes);
+    WS_TL();
+#endif
 
+#ifdef NGC_EXP_BUILTIN_DMA
     __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
+#else
+    const ngc_u32x4 rs_dy = make_rsrc_words(p.dy, p.dy_bytes);
+    const ngc_u32x4 rs_x = make_rsrc_words(p.x, p.x_bytes);
+#endif
 
     // G > 1: a stage holds G whole (small) images: positions and patch pixels are numbered image after
     // image (G = 1: one image, SR of its rows)
@@ -161,16 +183,24 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             if (it < items_dy) {                                         // wave-uniform
                 const int pln = it / nblk_dy, blk = it - pln * nblk_dy;
                 const unsigned off = (item_row[i] < nvalid) ? dy_org + (unsigned)(pln * PQ * 32) + item_off[i] : WS_OOB;
+#ifdef NGC_EXP_BUILTIN_DMA
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_t *)(base + pln * p.dyplane + blk * 1024), 16,
                                                          (int)off, 0, 0, 0);
+#else
+                dma_load_lds16(rs_dy, base + pln * p.dyplane + blk * 1024, off, 0);
+#endif
             } else if (it < items) {
                 const int itx = it - items_dy;
                 const int pln = itx / nblk_x, blk = itx - pln * nblk_x;
                 const bool ok = item_off[i] != WS_OOB &&
                                 (MULTI ? item_row[i] < gvalid : (unsigned)(h0 + item_row[i]) < (unsigned)p.H);
                 const unsigned off = ok ? x_org + (unsigned)(pln * HW * 32) + item_off[i] : WS_OOB;
+#ifdef NGC_EXP_BUILTIN_DMA
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(base + 4 * p.dyplane + pln * p.xplane + blk * 1024),
                                                          16, (int)off, 0, 0, 0);
+#else
+                dma_load_lds16(rs_x, base + 4 * p.dyplane + pln * p.xplane + blk * 1024, off, 0);
+#endif
             }
         }
     };
@@ -211,14 +241,18 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     // before: a wave is held at issue while the memory system takes its loads, and with one wave of each
     // SIMD in either group the other one's MFMAs run meanwhile.  Counting is unchanged (per wave, in order).
     const bool late = (p.late_mask >> wave) & 1;
+    WS_TL();
     for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s, s);
+    WS_TL();
     int buf = 0;                                            // s % nring
     for (int s = 0; s < total_stages; ++s) {
         const int later = (total_stages - 1 - s < ahead - 1) ? total_stages - 1 - s : ahead - 1;
         wait_vmcnt(later * lpw);
         wg_barrier_nofence();                                 // stage s complete for everybody; buffer of s-1 is free
+        WS_TL();
         const int nbuf = (buf + ahead) % p.nring;
         if (!late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
+        WS_TL();
         int rows = rows_strip - (s % p.nstages) * p.SR;
         if (rows > p.SR) rows = p.SR;
         int gv = nimg - s * G;
@@ -274,9 +308,12 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             }
             step_body(std::false_type{});
         }
+        WS_TL();
         if (late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
     }
+    WS_TL();
     __syncthreads();                                        // all stage buffers are free
+    WS_TL();
 
     // ---- sum the step-parity copies (waves h=1 publish, h=0 add) and write the partial tile.
     // Accumulator register v of tile (kb, t): k = 16 kb + 4*(lane/16) + v, c = 16 cq + lane%16.
@@ -302,6 +339,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         }
         __syncthreads();
     }
+    WS_TL();
     if (wh == 0) {
         f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
                      (((size_t)blockIdx.x * gridDim.y + blockIdx.y) * NCQ + cq) * (4 * WS_NT * 64);
@@ -310,6 +348,13 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
 #pragma unroll
             for (int t = 0; t < WS_NT; ++t) out[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
     }
+#ifdef NGC_TIMELINE
+    WS_TL();
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    WS_TL();
+    if (lane == 0 && blockIdx.x < 512 && blockIdx.y < 2)
+        for (int i = 0; i < 64; ++i) g_ws_timeline[((blockIdx.y * 512 + blockIdx.x) * 8 + wave) * 64 + i] = i < tl_n ? tl_lds[wave * 64 + i] : 0;
+#endif
 }
 
 // dw[k][c][tap] = sum over workgroup partials (index order) of partial[part][tile][cq][kb][tap][lane][v].
@@ -357,9 +402,19 @@ static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_b
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
+#ifdef NGC_TIMELINE
+    lds_bytes += 4096;
+#endif
     NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI>), grid, dim3(512), lds_bytes, st, p);
     return ngc::launch_result();
 }
+
+#ifdef NGC_TIMELINE
+extern "C" int ngc_debug_ws_timeline(unsigned long long *host_dst, size_t count)
+{
+    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_ws_timeline), count * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
