@@ -641,7 +641,7 @@ bool wgrad_strip_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStripP
     const int nblk_dy = (q.G > 1 ? q.G * P * Q + 31 : q.SR * Q + 31) / 32;   // 32-position steps per stage
     q.dyplane = nblk_dy * 1024 + 128;
     q.xplane = nblk_x * 1024 + 128;
-    if (4 * nblk_dy + q.ncq * nblk_x > 80) return false;                // load items per stage (10 per wave)
+    if (nblk_dy > 7 || q.ncq * nblk_x > 56) return false;               // load slots per wave and stage: 4 of dy, 7 of x
     const size_t stage = (size_t)4 * q.dyplane + (size_t)q.ncq * q.xplane;
     q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
     const char *fr = env_switch(SW_WGRAD_RING);                          // tests / benchmarks only

@@ -59,7 +59,8 @@ __device__ unsigned long long g_ws_timeline[1024 * 8 * 64];
 
 constexpr unsigned WS_OOB = 0x80000000u;
 constexpr int WS_NT = 9;
-constexpr int WS_MAXI = 10;                        // load items per wave and stage (host guarantees items <= 80)
+constexpr int WS_MAXDY = 4;                        // dy load slots per wave and stage: 4 planes x at most 7 blocks over 8 waves
+constexpr int WS_MAXX = 7;                         // x load slots per wave and stage (the host plan keeps NCQ * blocks <= 56)
 
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigned char *hi)
 {
@@ -109,13 +110,8 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     WS_TL();
 #endif
 
-#ifdef NGC_EXP_BUILTIN_DMA
-    __amdgpu_buffer_rsrc_t rs_dy = __builtin_amdgcn_make_buffer_rsrc((void *)p.dy, 0, (int)p.dy_bytes, 0x00020000);
-    __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
-#else
     const ngc_u32x4 rs_dy = make_rsrc_words(p.dy, p.dy_bytes);
     const ngc_u32x4 rs_x = make_rsrc_words(p.x, p.x_bytes);
-#endif
 
     // G > 1: a stage holds G whole (small) images: positions and patch pixels are numbered image after
     // image (G = 1: one image, SR of its rows)
@@ -127,82 +123,86 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     const int steps_full = (stage_pos + 31) >> 5;           // 32-position steps of a full stage
     const int nblk_dy = steps_full;
 
-    // load items of a stage: (plane, 32-position block) pairs, 4 dy planes then NCQ x planes,
-    // dealt round-robin to the 8 waves.  What does not change from stage to stage is computed once
-    // per lane and item (the address arithmetic would otherwise cost more issue cycles than the MFMAs
-    // of a stage): item_off = byte offset relative to the stage origin (WS_OOB if the lane never
-    // loads), item_row = what decides validity in a given stage: the position (dy), the patch row
-    // (x, G = 1) or the image inside the stage (x, G > 1; rows are then always the whole image).
-    const int items_dy = 4 * nblk_dy;
-    const int items = items_dy + NCQ * nblk_x;
-    unsigned item_off[WS_MAXI];
-    int item_row[WS_MAXI];
+    // load items of a stage: (plane, 32-position block) pairs, 4 dy planes and NCQ x planes, each kind dealt
+    // round-robin to the 8 waves (slot i of a wave = item wave + 8 i of the kind).  What does not change from
+    // stage to stage is computed once: per slot the LDS destination and the plane's byte offset (wave-uniform;
+    // the latter goes into the load's scalar offset), per slot and lane the offset inside the stage and what
+    // decides validity in a given stage.  A stage then costs a handful of instructions per load: the address
+    // arithmetic would otherwise take more issue cycles than the MFMAs of the stage.
+    const int items_dy = 4 * nblk_dy, items_x = NCQ * nblk_x;
+    const int ndy = (items_dy - wave + NW - 1) / NW;                     // this wave's dy / x slots in use
+    const int nx = (items_x - wave + NW - 1) / NW;
+    const int lane_half = lane >> 1;
+    int dy_lds[WS_MAXDY], dy_pos0[WS_MAXDY];
+    unsigned dy_soff[WS_MAXDY], dy_voff[MULTI ? WS_MAXDY : 1];
 #pragma unroll
-    for (int i = 0; i < WS_MAXI; ++i) {
-        const int it = wave + NW * i;
-        item_off[i] = WS_OOB;
-        item_row[i] = 0;
-        if (it < items_dy) {
-            const int blk = it % nblk_dy;
-            const int pos = blk * 32 + (lane >> 1);
-            const uint32_t g = MULTI ? fd_div((uint32_t)pos, p.div_pq) : 0;     // image inside the stage
-            item_off[i] = (unsigned)(((int)g * (KB - 1) * PQ + pos) * 32 + (lane & 1) * 16);
-            item_row[i] = pos;
-        } else if (it < items) {
-            const int blk = (it - items_dy) % nblk_x;
-            const uint32_t px = (uint32_t)(blk * 32 + (lane >> 1));
-            const uint32_t g = MULTI ? fd_div(px, p.div_patch) : 0;
-            const uint32_t px1 = px - g * (uint32_t)npatch1;
-            const uint32_t pr = fd_div(px1, p.div_pc);
-            const uint32_t pc = px1 - pr * p.div_pc.d;
-            const int w = p.min_dw + (int)pc;
-            bool ok = px < (uint32_t)npatch && (unsigned)w < (unsigned)p.W;
-            if (MULTI) ok = ok && (unsigned)(p.min_dh + (int)pr) < (unsigned)p.H;   // stage = whole images: rows fixed
-            if (ok) item_off[i] = (unsigned)((((int)g * CB * p.H + (int)pr) * p.W + (int)pc) * 32 + (lane & 1) * 16);
-            item_row[i] = MULTI ? (int)g : (int)pr;
+    for (int i = 0; i < WS_MAXDY; ++i) {
+        const int it = (i < ndy) ? wave + NW * i : 0;
+        const int pln = it / nblk_dy, blk = it - pln * nblk_dy;
+        dy_lds[i] = pln * p.dyplane + blk * 1024;
+        dy_pos0[i] = blk * 32;                                           // the lane's position is dy_pos0 + lane / 2
+        // G = 1: positions of a stage are contiguous in a plane; G > 1: image g of the stage is KB planes further on
+        dy_soff[i] = (unsigned)(pln * PQ * 32) + (MULTI ? 0u : (unsigned)(blk * 1024));
+        if constexpr (MULTI) {
+            const int pos = blk * 32 + lane_half;
+            const uint32_t g = fd_div((uint32_t)pos, p.div_pq);
+            dy_voff[i] = (unsigned)(((int)g * (KB - 1) * PQ + pos) * 32 + (lane & 1) * 16);
         }
     }
-    auto issue_loads = [&](int stage_lin, int buf) {
-        // stages run image by image (G = 1: nstages row blocks per image; G > 1: G images per stage)
-        const int img = n0 + (MULTI ? stage_lin * G : stage_lin / p.nstages);
-        const int stage_i = MULTI ? 0 : stage_lin - (stage_lin / p.nstages) * p.nstages;
+    // x: x_row = the patch row (G = 1) or the image inside the stage (G > 1, rows are then always the whole
+    // image); lanes that never load (beyond the patch, or a column outside the image) get a row no stage accepts
+    int x_lds[WS_MAXX], x_row[WS_MAXX];
+    unsigned x_soff[WS_MAXX], x_off[WS_MAXX];
+#pragma unroll
+    for (int j = 0; j < WS_MAXX; ++j) {
+        const int it = (j < nx) ? wave + NW * j : 0;
+        const int pln = it / nblk_x, blk = it - pln * nblk_x;
+        x_lds[j] = 4 * p.dyplane + pln * p.xplane + blk * 1024;
+        x_soff[j] = (unsigned)(pln * HW * 32);
+        const uint32_t px = (uint32_t)(blk * 32 + lane_half);
+        const uint32_t g = MULTI ? fd_div(px, p.div_patch) : 0;
+        const uint32_t px1 = px - g * (uint32_t)npatch1;
+        const uint32_t pr = fd_div(px1, p.div_pc);
+        const uint32_t pc = px1 - pr * p.div_pc.d;
+        const int w = p.min_dw + (int)pc;
+        bool ok = px < (uint32_t)npatch && (unsigned)w < (unsigned)p.W;
+        if (MULTI) ok = ok && (unsigned)(p.min_dh + (int)pr) < (unsigned)p.H;   // stage = whole images: rows fixed
+        x_off[j] = (unsigned)((((int)g * CB * p.H + (int)pr) * p.W + (int)pc) * 32 + (lane & 1) * 16);
+        x_row[j] = ok ? (MULTI ? (int)g : (int)pr) : 0x40000000;
+    }
+    // Stages are issued in order, one call each: the (image, row block) of the next one is carried along.
+    int is_img = n0, is_stage = 0;
+    auto issue_loads = [&](int buf) {
         unsigned char *base = smem + buf * stage_bytes;
-        const int r0 = stage_i * p.SR;                                   // first strip row of the stage
+        const int r0 = is_stage * p.SR;                                  // first strip row of the stage (G = 1)
         int rows = rows_strip - r0;
         if (rows > p.SR) rows = p.SR;
-        int gvalid = nimg - stage_lin * G;                               // images of the stage that exist (G > 1)
+        int gvalid = nimg - (is_img - n0);                               // images of the stage that exist (G > 1)
         if (gvalid > G) gvalid = G;
         const int nvalid = MULTI ? gvalid * PQ : rows * p.Q;             // positions of the stage that exist
         const int h0 = p0 + r0 + p.min_dh;
         // stage origins (x: pixel (h0, min_dw), possibly outside the image; valid lanes end up in range)
-        const unsigned dy_org = (unsigned)((((img * KB + kt * 4) * PQ) + (p0 + r0) * p.Q) * 32);
-        const unsigned x_org = (unsigned)(((img * CB + ct * NCQ) * HW + h0 * p.W + p.min_dw) * 32);
+        const unsigned dy_org = (unsigned)((((is_img * KB + kt * 4) * PQ) + (p0 + r0) * p.Q) * 32);
+        const unsigned x_org = (unsigned)(((is_img * CB + ct * NCQ) * HW + h0 * p.W + p.min_dw) * 32);
+        const unsigned dy_lane = dy_org + (unsigned)(lane * 16);
+        const int radd = MULTI ? 0 : h0;                                 // x lane valid: (unsigned)(x_row + radd) < rlim
+        const unsigned rlim = MULTI ? (unsigned)gvalid : (unsigned)p.H;
 #pragma unroll
-        for (int i = 0; i < WS_MAXI; ++i) {
-            const int it = wave + NW * i;
-            if (it < items_dy) {                                         // wave-uniform
-                const int pln = it / nblk_dy, blk = it - pln * nblk_dy;
-                const unsigned off = (item_row[i] < nvalid) ? dy_org + (unsigned)(pln * PQ * 32) + item_off[i] : WS_OOB;
-#ifdef NGC_EXP_BUILTIN_DMA
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_dy, (lds_void_t *)(base + pln * p.dyplane + blk * 1024), 16,
-                                                         (int)off, 0, 0, 0);
-#else
-                dma_load_lds16(rs_dy, base + pln * p.dyplane + blk * 1024, off, 0);
-#endif
-            } else if (it < items) {
-                const int itx = it - items_dy;
-                const int pln = itx / nblk_x, blk = itx - pln * nblk_x;
-                const bool ok = item_off[i] != WS_OOB &&
-                                (MULTI ? item_row[i] < gvalid : (unsigned)(h0 + item_row[i]) < (unsigned)p.H);
-                const unsigned off = ok ? x_org + (unsigned)(pln * HW * 32) + item_off[i] : WS_OOB;
-#ifdef NGC_EXP_BUILTIN_DMA
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (lds_void_t *)(base + 4 * p.dyplane + pln * p.xplane + blk * 1024),
-                                                         16, (int)off, 0, 0, 0);
-#else
-                dma_load_lds16(rs_x, base + 4 * p.dyplane + pln * p.xplane + blk * 1024, off, 0);
-#endif
+        for (int i = 0; i < WS_MAXDY; ++i)
+            if (i < ndy) {                                               // wave-uniform
+                const bool ok = lane_half < nvalid - dy_pos0[i];
+                const unsigned off = ok ? (MULTI ? dy_org + dy_voff[MULTI ? i : 0] : dy_lane) : WS_OOB;
+                dma_load_lds16(rs_dy, base + dy_lds[i], off, dy_soff[i]);
             }
-        }
+#pragma unroll
+        for (int j = 0; j < WS_MAXX; ++j)
+            if (j < nx) {
+                const bool ok = (unsigned)(x_row[j] + radd) < rlim;
+                const unsigned off = ok ? x_org + x_off[j] : WS_OOB;
+                dma_load_lds16(rs_x, base + x_lds[j], off, x_soff[j]);
+            }
+        if (MULTI) is_img += G;
+        else if (++is_stage == p.nstages) { is_stage = 0; ++is_img; }
     };
 
     f32x4 acc[4][WS_NT];
@@ -235,14 +235,14 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     // Ring of p.nring (2 or 3) stage buffers.  Every stage costs this wave the same number of
     // loads (lpw), so "stage s has landed" is vmcnt <= lpw * (stages issued after s).
     const int total_stages = MULTI ? (nimg + G - 1) / G : nimg * p.nstages;
-    const int lpw = (items - wave + NW - 1) / NW;
+    const int lpw = ndy + nx;
     const int ahead = p.nring - 1;
     // Waves of the late group issue the loads of stage s + ahead after their MFMAs of stage s instead of
     // before: a wave is held at issue while the memory system takes its loads, and with one wave of each
     // SIMD in either group the other one's MFMAs run meanwhile.  Counting is unchanged (per wave, in order).
     const bool late = (p.late_mask >> wave) & 1;
     WS_TL();
-    for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s, s);
+    for (int s = 0; s < ahead && s < total_stages; ++s) issue_loads(s);
     WS_TL();
     int buf = 0;                                            // s % nring
     for (int s = 0; s < total_stages; ++s) {
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         wg_barrier_nofence();                                 // stage s complete for everybody; buffer of s-1 is free
         WS_TL();
         const int nbuf = (buf + ahead) % p.nring;
-        if (!late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
+        if (!late && s + ahead < total_stages) issue_loads(nbuf);
         WS_TL();
         int rows = rows_strip - (s % p.nstages) * p.SR;
         if (rows > p.SR) rows = p.SR;
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
             step_body(std::false_type{});
         }
         WS_TL();
-        if (late && s + ahead < total_stages) issue_loads(s + ahead, nbuf);
+        if (late && s + ahead < total_stages) issue_loads(nbuf);
     }
     WS_TL();
     __syncthreads();                                        // all stage buffers are free
