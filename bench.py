@@ -8,16 +8,24 @@ bias+ReLU epilogue, ConvolutionBackpropData and ConvolutionBackpropFilters, all 
 16-channel-blocked tensors, inputs resident in HBM, filters already in their blocked
 layouts (the re-layout happens once per weight update and is timed separately).
 
-Prints ONE JSON line: metric, value, unit, step time, the workload, `roofline` (the dominant kernel against
-the MI355X peak that bounds it, with its HBM traffic from counters), `kernels` (per-kernel durations from HIP
-events on the launch stream) and `cpu_baseline` (the CPU oracle timed on the host cores).  `--workload` selects
-another configuration for experiments; the default line is the contract.
+Prints ONE JSON line.  Everything is launched on one HIP stream.  After W warm-up steps the step loop is timed in
+`--batches` batches of K steps (`ms_per_step` = the median batch), then every kernel of the step is timed on its
+own with HIP events on the launch stream, again in batches of back-to-back launches, and `kernels` holds the
+median per launch.  `value` = nominal flop of the step / sum of those kernel medians (`kernel_sum`), the
+definition the metric is judged by; `step_wall` gives the same flop over the wall time of the step loop (launch
+gaps included) and `three_stream_step` over a step whose three ops go to three streams (an extra, not `value`).
+`roofline` is the dominant kernel against the MI355X peak that bounds it; its `traffic` is read from the
+committed counter summary under profiles/ when there is one for this workload (null otherwise).
+`cpu_baseline` is the CPU oracle timed on the host cores (all threads, and one thread on a smaller sample).
+`--workload` selects another configuration for experiments; the default line is the contract.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -26,14 +34,22 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch (fetch + write) of the cfg2 kernels from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
-# (profiles/cfg2_strip_wgrad_strip.txt), each scaled by what the same counter reads for a plain 102.8 MB copy
-# launched in the same run (FETCH_SIZE reads 0.5004 of the bytes copied, WRITE_SIZE 1.000).
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_3x3_c64:fwd": int((14302.5 / 0.5004 + 25088.0) * 1024),
-    "cfg2_3x3_c64:bwd_data": int((14302.5 / 0.5004 + 25088.0) * 1024),
-    "cfg2_3x3_c64:bwd_filters": int(((25727.5 + 9228.5) / 0.5004 + 18432.0 + 576.0) * 1024),
-}
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "cfg2_hbm_traffic.txt")
+
+
+def measured_traffic(kernel_name):
+    """HBM bytes per launch (fetch + write) of a cfg2 op from the committed counter summary: lines of the form
+    `traffic_bytes <workload>:<op> <bytes>` written from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of
+    this file (the summary states the commands and the copy-kernel scale factors).  None when there is no such line."""
+    try:
+        with open(TRAFFIC_SUMMARY) as f:
+            for line in f:
+                m = re.match(r"traffic_bytes\s+(\S+)\s+(\d+)\s*$", line)
+                if m and m.group(1) == kernel_name:
+                    return int(m.group(2))
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -43,10 +59,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6", "cfg7", "softmax"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=3, choices=[1, 3],
-                    help="3 (default): forward, backprop-data and backprop-filters launches go to three HIP streams "
-                         "of equal (default) priority, so that independent ops overlap their launch gaps and tails; "
-                         "1: everything on one stream")
+    ap.add_argument("--batches", type=int, default=5, help="timed batches of --steps steps; the median is reported")
+    ap.add_argument("--kernel-reps", type=int, default=200,
+                    help="back-to-back launches per batch when a kernel is timed on its own (at least --steps)")
+    ap.add_argument("--no-three-stream", action="store_true",
+                    help="skip the extra leg that issues forward, backprop-data and backprop-filters to three HIP "
+                         "streams of equal (default) priority")
     ap.add_argument("--backward-compounds", action="store_true",
                     help="also time ngc_conv_bwd_data_relu and ngc_bias_grad of every layer on their own (reported under "
                          "backward_compound_kernels; never part of the timed step)")
@@ -56,7 +74,7 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
                          "[64,256,56,56] bf16 tensor: 102.8 MB read + 102.8 MB written) so that HBM counters can be scaled")
-    ap.add_argument("--settle", type=float, default=0.2,
+    ap.add_argument("--settle", type=float, default=0.5,
                     help="seconds of untimed load (the workload's own steps) before the warm-up steps; 0 = none")
     ap.add_argument("--layer", default=None, help="cfg7 only: time this one layer of the set (e.g. v_3x3x3_c64k128)")
     return ap.parse_args()
@@ -194,18 +212,37 @@ def settle_clocks(torch, step, seconds):
         torch.cuda.synchronize()
 
 
-def event_time_ms(torch, fn, reps):
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(reps):
-        fn(i)
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
+def event_time_ms(torch, fn, reps, batches=5):
+    """Median over `batches` of (HIP-event time of `reps` back-to-back launches on the current stream) / reps."""
+    per = []
+    for b in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(b * reps + i)
+        e1.record()
+        torch.cuda.synchronize()
+        per.append(e0.elapsed_time(e1) / reps)
+    return statistics.median(per)
+
+
+def timed_steps_ms(torch, step, steps, batches):
+    """`batches` batches of exactly `steps` steps, each bracketed by a device synchronisation; per-step wall time of
+    every batch (ms)."""
+    per = []
+    for b in range(batches):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(b * steps + i)
+        torch.cuda.synchronize()
+        per.append((time.perf_counter() - t0) * 1e3 / steps)
+    return per
 
 
 def softmax_main(args, torch, ng, synth_inputs):
-    """Softmax workloads (the other kernel the paper names): forward + backprop per case, HBM-bound."""
+    """Softmax workloads (the other kernel the paper names): forward + backprop per case, HBM-bound.
+    --cold: every case rotates over enough buffer sets (> 600 MB) that no launch finds its operands in a cache."""
     import numpy as np
     cur = torch.cuda.current_stream().cuda_stream
     cases = synth_inputs.softmax_cases()
@@ -217,42 +254,60 @@ def softmax_main(args, torch, ng, synth_inputs):
         else:
             up = lambda v: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
         x, dy = up(t["x"]), up(t["dy"])
-        bufs.append((c, ng.NGC_BF16 if c.dtype == "bf16" else ng.NGC_F32, x, dy, torch.empty_like(x), torch.empty_like(x)))
+        nbytes = c.rows * c.cols * (2 if c.dtype == "bf16" else 4)
+        nsets = max(2, int(600e6 // (4 * nbytes)) + 1) if args.cold else 1
+        sets = [(x, dy, torch.empty_like(x), torch.empty_like(x))]
+        for _ in range(nsets - 1):
+            sets.append((x.clone(), dy.clone(), torch.empty_like(x), torch.empty_like(x)))
+        for x_, dy_, y_, _dx in sets[1:]:                                   # backprop reads y: make every set's y valid
+            ng.ngc_softmax(ng.NGC_BF16 if c.dtype == "bf16" else ng.NGC_F32, c.rows, c.cols, x_, y_, cur)
+        bufs.append((c, ng.NGC_BF16 if c.dtype == "bf16" else ng.NGC_F32, sets))
+    torch.cuda.synchronize()
 
-    def step(_i):
-        for c, code, x, dy, y, dx in bufs:
+    def step(i):
+        for c, code, sets in bufs:
+            x, dy, y, dx = sets[i % len(sets)]
             ng.ngc_softmax(code, c.rows, c.cols, x, y, cur)
             ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur)
 
     settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    per = timed_steps_ms(torch, step, args.steps, args.batches)
+    ms_per_step = statistics.median(per)
     kern = {}
-    reps = max(20, min(args.steps, 200))
+    reps = max(args.kernel_reps, args.steps)
     total_bytes = 0
-    for c, code, x, dy, y, dx in bufs:
+    for c, code, sets in bufs:
         nbytes = c.rows * c.cols * (2 if c.dtype == "bf16" else 4)
         total_bytes += 5 * nbytes
-        for op, fn, nb in (("fwd", lambda i: ng.ngc_softmax(code, c.rows, c.cols, x, y, cur), 2 * nbytes),
-                           ("bwd", lambda i: ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur), 3 * nbytes)):
-            ms = event_time_ms(torch, fn, reps)
+
+        def fwd(i, c=c, code=code, sets=sets):
+            x, dy, y, dx = sets[i % len(sets)]
+            ng.ngc_softmax(code, c.rows, c.cols, x, y, cur)
+
+        def bwd(i, c=c, code=code, sets=sets):
+            x, dy, y, dx = sets[i % len(sets)]
+            ng.ngc_softmax_bwd(code, c.rows, c.cols, y, dy, dx, cur)
+
+        for op, fn, nb in (("fwd", fwd, 2 * nbytes), ("bwd", bwd, 3 * nbytes)):
+            ms = event_time_ms(torch, fn, reps, args.batches)
             kern[f"{c.name}:{op}"] = {"us": round(ms * 1e3, 2), "gbs": round(nb / (ms * 1e-3) / 1e9, 1), "bytes": nb,
                                       "variant": ng.ngc_softmax_variant(code, c.cols, op == "bwd"), "count": 1}
     dom_name = max(kern, key=lambda k: kern[k]["us"])
     dom = kern[dom_name]
-    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+    ksum_us = sum(v["us"] for v in kern.values())
+    value = total_bytes / (ksum_us * 1e-6) / 1e9
     print(json.dumps({
         "metric": "softmax forward + backprop, algorithmic GB/s over 4 workloads, 1 GPU", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "batches": args.batches, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "softmax over the last axis: [32768,1000], [262144,512], [4096,32000] bf16 and [65536,1024] fp32, "
-                               "forward + backprop each", "streams": 1},
+                               "forward + backprop each", "streams": 1, "cache": "cold" if args.cold else "warm"},
+        "value_basis": "algorithmic bytes / sum of the kernel medians (kernel_sum)",
+        "kernel_sum": {"us": round(ksum_us, 2)},
+        "step_wall": {"ms_per_step_batches": [round(v, 5) for v in per],
+                      "gbs": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom_name},
         "kernels": kern}))
@@ -310,17 +365,13 @@ def conv3d_main(args, torch, ng, synth_inputs):
     settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    per = timed_steps_ms(torch, step, args.steps, args.batches)
+    ms_per_step = statistics.median(per)
     kern = {}
     reps = max(5, min(args.steps, 50))
     for L, ops in items:
         for name, (fn, d, op, nbytes) in ops.items():
-            ms = event_time_ms(torch, fn, reps)
+            ms = event_time_ms(torch, fn, reps, args.batches)
             kern[f"{L.name}:{name}"] = {"us": round(ms * 1e3, 2), "tflops": round(L.flop_per_op / (ms * 1e-3) / 1e12, 1),
                                         "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1), "variant": ng.ngc_conv3d_variant(d, op),
                                         "count": 1}
@@ -334,10 +385,15 @@ def conv3d_main(args, torch, ng, synth_inputs):
     flop = 3 * sum(L.flop_per_op for L, _ in items)
     dom_name = max(kern, key=lambda k: kern[k]["us"])
     dom = kern[dom_name]
+    ksum_us = sum(v["us"] for v in kern.values())
     print(json.dumps({
         "metric": "conv3d fwd+bwd TFLOP/s over 7 video-shaped layers, 1 GPU" if args.layer is None
-        else f"conv3d fwd+bwd TFLOP/s, layer {args.layer}, 1 GPU", "value": round(flop / (ms_per_step * 1e-3) / 1e12, 1),
-        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        else f"conv3d fwd+bwd TFLOP/s, layer {args.layer}, 1 GPU", "value": round(flop / (ksum_us * 1e-6) / 1e12, 1),
+        "value_basis": "nominal flop / sum of the kernel medians (kernel_sum)", "kernel_sum": {"us": round(ksum_us, 2)},
+        "step_wall": {"ms_per_step_batches": [round(v, 5) for v in per],
+                      "tflops": round(flop / (ms_per_step * 1e-3) / 1e12, 1)},
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "batches": args.batches,
+        "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "7 layers over (D,H,W), N=8 clips of 16 frames: 3x3x3 64->128 16x56x56, 3x3x3 128->256 8x28x28, "
                                "3x3x3/2 128->128, 1x3x3 64->128, 3x1x1 128->64, 1x1x1 256->64, 3x3x3 with per-axis strides / "
@@ -347,24 +403,84 @@ def conv3d_main(args, torch, ng, synth_inputs):
         "kernels": kern}))
 
 
+def cpu_model_name():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(L):
-    """The oracle as it stands, one pass over the full cfg2 tensors, timed on the host cores."""
+    """The oracle as it stands, timed on the host cores: one pass over the full cfg2 tensors with every thread the
+    box gives this job, then one pass over the first 4 images with one thread."""
+    import ctypes
+    import dataclasses
     import numpy as np
     import oracle
     import synth_inputs
-    a = oracle.Attrs(*L.attrs15)
-    t = synth_inputs.layer_tensors(L)
-    x, w, dy = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
-    t0 = time.perf_counter()
-    oracle.conv_fwd(a, x, w, bias=t["bias"], relu=True)
-    oracle.conv_bwd_data_gather(a, dy, w)
-    oracle.conv_bwd_filters(a, x, dy)
-    dt = time.perf_counter() - t0
+
+    def one_pass(layer):
+        a = oracle.Attrs(*layer.attrs15)
+        t = synth_inputs.layer_tensors(layer)
+        x, w, dy = (t[k].astype(np.float64) for k in ("x", "w", "dy"))
+        t0 = time.perf_counter()
+        oracle.conv_fwd(a, x, w, bias=t["bias"], relu=True)
+        oracle.conv_bwd_data_gather(a, dy, w)
+        oracle.conv_bwd_filters(a, x, dy)
+        return time.perf_counter() - t0
+
     cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
-    return {"value": 3 * L.flop_per_op / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "seconds": round(dt, 3),
-            "sample": f"one full pass (fwd+bias+ReLU, backprop-data gather form, backprop-filters) over the "
-                      f"N={L.n} {L.name} tensors in fp64"}
+    dt = one_pass(L)
+    out = {"value": 3 * L.flop_per_op / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+           "cpu_model": cpu_model_name(), "seconds": round(dt, 3),
+           "sample": f"one full pass (fwd+bias+ReLU, backprop-data gather form, backprop-filters) over the "
+                     f"N={L.n} {L.name} tensors in fp64"}
+    # one thread: the OpenMP runtime the oracle's C library runs on is told to use one (its code is untouched)
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        small = dataclasses.replace(L, n=4)
+        gomp.omp_set_num_threads(1)
+        try:
+            dt1 = one_pass(small)
+        finally:
+            gomp.omp_set_num_threads(cores)
+        out["one_thread"] = {"value": 3 * small.flop_per_op / dt1 / 1e12, "unit": "TFLOP/s", "cores": 1,
+                             "seconds": round(dt1, 3), "sample": f"the same pass over the first {small.n} images"}
+    except (OSError, AttributeError, TypeError) as e:
+        out["one_thread"] = {"value": None, "error": str(e)}
+    return out
+
+
+def cfg1_latency(torch, ng, synth_inputs, batches):
+    """The small fp32 NCHW correctness configuration: microseconds per launch of its three ops (latency only)."""
+    import numpy as np
+    L = synth_inputs.config_layers(1)[0]
+    t = synth_inputs.layer_tensors(L)
+    cur = torch.cuda.current_stream().cuda_stream
+    n, c, h, w, k, r, s, sh, sw, dh, dw, pbh, pbw, pah, paw = L.attrs15
+    mk = lambda e: ng.make_desc(n, c, h, w, k, r, s, (sh, sw), (dh, dw), (pbh, pbw), (pah, paw), ng.NGC_F32,
+                                ng.NGC_NCHW, ng.NGC_NCHW, ng.NGC_KCRS, e)
+    d_f, d_b = mk(ng.NGC_EPI_BIAS | ng.NGC_EPI_RELU), mk(ng.NGC_EPI_NONE)
+    up = lambda v: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
+    x, wt, dy, bias = up(t["x"]), up(t["w"]), up(t["dy"]), up(t["bias"])
+    y, dx, dwt = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(wt)
+    ws = {op: torch.empty(max(ng.ngc_conv_workspace_bytes(d_b, op), 16), dtype=torch.uint8, device="cuda")
+          for op in (ng.NGC_OP_FWD, ng.NGC_OP_BWD_DATA, ng.NGC_OP_BWD_FILTERS)}
+    ops = {"fwd": lambda i: ng.ngc_conv_fwd(d_f, x, wt, bias, y, ws[ng.NGC_OP_FWD], cur),
+           "bwd_data": lambda i: ng.ngc_conv_bwd_data(d_b, dy, wt, dx, ws[ng.NGC_OP_BWD_DATA], cur),
+           "bwd_filters": lambda i: ng.ngc_conv_bwd_filters(d_b, x, dy, dwt, ws[ng.NGC_OP_BWD_FILTERS], cur)}
+    out = {}
+    for name, fn in ops.items():
+        for i in range(20):
+            fn(i)
+        out[name] = round(event_time_ms(torch, fn, 200, batches) * 1e3, 2)
+    out["variant"] = ng.ngc_conv_variant(d_f, 0)
+    out["note"] = "configs[0], fp32 NCHW N=2 C=16 16x16 K=32 3x3: us per launch back to back; latency only, no roofline claim"
+    return out
 
 
 def main():
@@ -399,38 +515,27 @@ def main():
     benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets, propagate=args.propagate_layout) for L in layers]
     torch.cuda.synchronize()
 
-    # The ops of a layer read and write disjoint buffers (each has its own inputs, outputs and
-    # workspace), so with --streams 3 they are issued to one stream per op kind; cfg3's layout
-    # conversion feeds the forward op and stays single-stream.
-    streams = None
-    if args.streams == 3 and cfg != 3:
-        extra = [torch.cuda.Stream() for _ in range(2)]                 # default priority
-        streams = {"fwd": benches[0].stream, "bwd_data": extra[0].cuda_stream, "bwd_filters": extra[1].cuda_stream}
+    def make_step(streams):
+        def step(i):
+            for b in benches:
+                for _ in range(b.L.count):
+                    b.step(i, streams)
+        return step
 
-    def step(i):
-        for b in benches:
-            for _ in range(b.L.count):
-                b.step(i, streams)
-
+    step = make_step(None)                                              # everything on the current stream
     settle_clocks(torch, step, args.settle)
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
+    per = timed_steps_ms(torch, step, args.steps, args.batches)
+    ms_per_step = statistics.median(per)
     flop_step = sum(L.flop_per_op * len(L.ops) * L.count for L in layers)
-    value = flop_step / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel durations (HIP events on the launch stream around back-to-back launches)
+    # per-kernel durations (HIP events on the launch stream around back-to-back launches, median of the batches)
     kern = {}
-    reps = max(20, min(args.steps, 200))
+    reps = max(args.kernel_reps, args.steps) if cfg != 5 else max(20, min(args.steps, 200))
     for b in benches:
         for op in b.ops:
-            ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps)
+            ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps, args.batches)
             flop = 0.0 if op == "convert" else b.L.flop_per_op
             kern[f"{b.L.name}:{op}"] = {
                 "us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
@@ -439,6 +544,24 @@ def main():
                             "bwd_data": ng.ngc_conv_variant(b.d_bwd, 1),
                             "bwd_filters": ng.ngc_conv_variant(b.d_wg, 2)}[op],
                 "count": b.L.count}
+    ksum_us = sum(v["us"] * v["count"] for v in kern.values())
+    value = flop_step / (ksum_us * 1e-6) / 1e12
+
+    # Extra leg: the ops of a layer read and write disjoint buffers (each has its own inputs, outputs and
+    # workspace), so they may be issued to one stream per op kind and overlap their launch gaps and tails;
+    # cfg3's layout conversion feeds the forward op and stays single-stream.
+    three = None
+    if not args.no_three_stream and cfg != 3:
+        extra_streams = [torch.cuda.Stream() for _ in range(2)]         # default priority
+        step3 = make_step({"fwd": benches[0].stream, "bwd_data": extra_streams[0].cuda_stream,
+                           "bwd_filters": extra_streams[1].cuda_stream})
+        for i in range(max(args.warmup, 5)):
+            step3(i)
+        per3 = timed_steps_ms(torch, step3, args.steps, args.batches)
+        ms3 = statistics.median(per3)
+        three = {"ms_per_step": round(ms3, 5), "tflops": round(flop_step / (ms3 * 1e-3) / 1e12, 2),
+                 "note": "fwd / bwd_data / bwd_filters on three streams of default priority; not the headline value"}
+
     # backward compounds (ReLU backprop fused into backprop-data; bias gradient): same buffers, timed alone
     extra = {}
     for b in (benches if args.backward_compounds else []):
@@ -464,7 +587,8 @@ def main():
     if cfg in (2,):
         roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dom_name), "traffic_unit": "bytes per launch (HBM fetch + write)",
+                "traffic": None if args.cold else measured_traffic(dom_name),
+                "traffic_unit": "bytes per launch (HBM fetch + write), from profiles/cfg2_hbm_traffic.txt",
                 "algorithmic_bytes": benches[0].algorithmic_bytes(dom_name.split(":")[1]), "kernel": dom_name}
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -473,8 +597,8 @@ def main():
     out = {
         "metric": "conv TFLOP/s fwd+bwd (ResNet 3x3 bf16 layer) and % of MFMA peak, 1 GPU",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "batches": args.batches, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": {2: "configs[1]: 3x3 conv N=64 C=K=64 56x56 s1 p1 bf16, fwd(+bias+ReLU) + bwd_data + bwd_filters",
                                 3: "configs[2]: 1x1 conv N=64 C=256 K=64 56x56 bf16, NCHW->nChw16c convert + fwd + bwd_data + bwd_filters",
                                 4: "configs[3]: stem 7x7/2 N=64 C=3 K=64 224x224 bf16, fwd(+bias+ReLU) + bwd_filters",
@@ -482,18 +606,24 @@ def main():
                                 6: "general-attribute layers (dilation, padding below != above, 5x5 / 1x7 / 7x1 / 2x2 windows, "
                                    "per-axis strides) N=32 bf16, 8 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
                    "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
-                   "streams": 3 if streams else 1,
+                   "streams": 1,
                    **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {})},
+        "value_basis": "nominal flop of the step / sum of the single-stream kernel medians (kernel_sum.us)",
         "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "gflop_per_step": round(flop_step / 1e9, 2),
-        # the same flop over the sum of the single-stream kernel durations (no overlap between ops)
-        "kernel_sum": {"us": round(sum(v["us"] * v["count"] for v in kern.values()), 2),
-                       "tflops": round(flop_step / (sum(v["us"] * v["count"] for v in kern.values()) * 1e-6) / 1e12, 2)},
+        "kernel_sum": {"us": round(ksum_us, 2), "tflops": round(value, 2)},
+        # the same flop over the wall time of the single-stream step loop (launch gaps between kernels included)
+        "step_wall": {"ms_per_step_batches": [round(v, 5) for v in per],
+                      "tflops": round(flop_step / (ms_per_step * 1e-3) / 1e12, 2)},
         "roofline": roof,
         "kernels": kern,
     }
+    if three:
+        out["three_stream_step"] = three
     if args.backward_compounds:
         out["backward_compound_kernels"] = extra
+    if cfg == 2 and not args.cold:
+        out["cfg1_us"] = cfg1_latency(torch, ng, synth_inputs, args.batches)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(synth_inputs.config_layers(2)[0])
     print(json.dumps(out))
