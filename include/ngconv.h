@@ -2,26 +2,27 @@
  * ngconv.h -- C ABI of the MI355X (gfx950) Convolution op family over two and three spatial axes
  * (and Softmax).
  *
- * The library plays the part of the kernels a backend "transformer" selects
- * for an IR graph (paper Sec. 4, "Transformers": tensor-element layout and
- * shape management combined with backend kernel selection; convolution named
- * as a common backend kernel) behind the "allocation and execution API" the
- * paper's Sec. 1 describes: the caller allocates, the library executes.
- * An op is a stateless node; its inputs and constant attributes determine the
- * output shape and element type (Sec. 2, "Intermediate Representation").  The
- * attributes here are the Convolution op's: window movement strides, padding
- * below / above, window dilation, plus the element type and the element
- * layout of each tensor (Sec. 2: no fixed relation between axis order and
- * element layout for tensors the user does not see).
+ * The library stands where a backend's kernels stand in the paper's stack: the
+ * per-backend translation step (Sec. 4, "Transformers") decides how tensor
+ * elements are laid out and which backend kernel runs each node, with
+ * convolution among the kernels it names, and the framework side only
+ * allocates tensors and asks for execution (Sec. 1).  Here the caller
+ * allocates and the library executes.  An op is a stateless node whose output
+ * shape and element type follow from its inputs and constant attributes
+ * (Sec. 2, "Intermediate Representation").  The attributes here are those of
+ * the Convolution op: window movement strides, padding below / above, window
+ * dilation, plus the element type and the element layout of each tensor (per
+ * Sec. 2 the layout of a tensor the user never sees is the backend's choice,
+ * whatever its axis order).
  *
  * Definitions (cross-correlation, no filter flip; floor output size):
  *   P = floor((H + pad_below_h + pad_above_h - dil_h*(R-1) - 1) / stride_h) + 1, Q likewise
  *   forward         y[n,k,p,q]  = sum_{c,r,s} X(n,c, p*stride_h - pad_below_h + r*dil_h,
  *                                                   q*stride_w - pad_below_w + s*dil_w) * w[k,c,r,s]
  *                   X = x inside the image, 0 outside
- *   epilogue        z = y (+ bias[k]) ; z = max(z,0)     (the compounded op, Abstract:
- *                   "HW-specific compounding of operations"), applied on the fp32
- *                   accumulator before the single rounding to the output type
+ *   epilogue        z = y (+ bias[k]) ; z = max(z,0)     (ops compounded for the hardware,
+ *                   one of the backend optimisations the Abstract lists), applied on the
+ *                   fp32 accumulator before the single rounding to the output type
  *   backprop-data   dx = adjoint of forward w.r.t. x applied to dy  (Sec. 3: derivative
  *                   ops come from autodiff of the forward op); elements of dx that no
  *                   window touches are written as 0

@@ -1,8 +1,9 @@
 // C ABI of libngconv: argument validation, shape inference, kernel selection, launches.
-// Host code only.  Kernel selection is the small analogue of the paper's Sec. 4 "combining of
-// tensor-element layout and shape management with backend kernel selection": the descriptor
-// (shape, attributes, element type, layouts) picks a hand-written kernel variant; a descriptor
-// without a kernel is reported as NGC_UNSUPPORTED, never routed to a CPU path.
+// Host code only.  Kernel selection is the small analogue of what the paper's Sec. 4 gives the
+// backend transformer to do (layout and shape decisions taken together with the choice of a
+// backend kernel): the descriptor (shape, attributes, element type, layouts) picks a hand-written
+// kernel variant; a descriptor without a kernel is reported as NGC_UNSUPPORTED, never routed to
+// a CPU path.
 #include "common.h"
 
 #include <limits.h>

@@ -1,0 +1,269 @@
+"""Sanitizer tier (CPU only): the oracle's C code and the library's host code (validation, shape inference, kernel
+selection, workspace sizing, launch set-up) run under AddressSanitizer + UndefinedBehaviorSanitizer.
+
+* The oracle: `oracle/conv_ref.c` is compiled together with a C driver that calls every exported function on small
+  tensors held in exactly sized heap blocks (strides, dilation, one-sided padding, channel counts off the block
+  size, index lists that touch the first and the last element), so a read or write one element off either end of
+  any tensor, or a signed overflow in an index expression, ends the run.
+* The host path: the library's sources are compiled for the host only (no device code) with the sanitizers on, and a
+  driver walks the C ABI with launches stubbed (`NGC_DRY_RUN=1`): every entry point, the benchmark shapes and a
+  pseudo-random sweep of attributes, valid and invalid.  Pointers are never dereferenced by host code, so fake ones do.
+"""
+import glob
+import os
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_1801_08058_amd", "csrc")
+HIPCC = "/opt/rocm/bin/hipcc"
+SAN_ENV = {"ASAN_OPTIONS": "detect_leaks=1:abort_on_error=0:halt_on_error=1", "UBSAN_OPTIONS": "halt_on_error=1:print_stacktrace=1"}
+
+ORACLE_DRIVER = r'''
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+typedef struct { int32_t n, c, h, w, k, r, s, sh, sw, dh, dw, pbh, pbw, pah, paw; } ref_attrs;
+int32_t ref_out_dim(int32_t, int32_t, int32_t, int32_t, int32_t, int32_t);
+void ref_conv_fwd(const ref_attrs *, const double *, const double *, const double *, int, double *);
+void ref_conv_fwd_at(const ref_attrs *, const double *, const double *, const double *, int, int64_t, const int64_t *, double *);
+void ref_conv_bwd_data(const ref_attrs *, const double *, const double *, double *);
+void ref_conv_bwd_data_gather(const ref_attrs *, const double *, const double *, double *);
+void ref_conv_bwd_data_at(const ref_attrs *, const double *, const double *, int64_t, const int64_t *, double *);
+void ref_conv_bwd_filters(const ref_attrs *, const double *, const double *, double *);
+void ref_conv_bwd_filters_at(const ref_attrs *, const double *, const double *, int64_t, const int64_t *, double *);
+void ref_nchw_to_blocked16(int32_t, int32_t, int32_t, int32_t, int32_t, const void *, void *);
+void ref_blocked16_to_nchw(int32_t, int32_t, int32_t, int32_t, int32_t, const void *, void *);
+void ref_f32_to_bf16_rne_array(int64_t, const uint32_t *, uint16_t *);
+void ref_relu_bwd_mask(int64_t, const double *, const double *, double *);
+void ref_bias_grad(int32_t, int32_t, int32_t, int32_t, const double *, double *);
+
+static uint64_t st = 88172645463325252ull;
+static double rnd(void) { st ^= st << 13; st ^= st >> 7; st ^= st << 17; return (double)(st >> 11) / 9007199254740992.0 - 0.5; }
+static double *vec(size_t n) { double *p = malloc((n ? n : 1) * sizeof(double)); for (size_t i = 0; i < n; ++i) p[i] = rnd(); return p; }
+
+int main(void)
+{
+    const ref_attrs cases[] = {
+        {2, 3, 7, 9, 4, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1},      /* same padding */
+        {1, 5, 11, 8, 6, 3, 2, 2, 3, 1, 1, 0, 2, 1, 0},     /* per-axis strides, one-sided padding */
+        {2, 2, 12, 12, 3, 3, 3, 1, 2, 2, 3, 2, 3, 2, 3},    /* dilation */
+        {1, 17, 5, 5, 33, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0},    /* 1x1 */
+        {1, 3, 15, 15, 4, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3},    /* stem-like */
+        {1, 1, 4, 4, 1, 5, 5, 1, 1, 1, 1, 0, 0, 0, 0},      /* window larger than the image: empty output */
+    };
+    for (size_t ci = 0; ci < sizeof(cases) / sizeof(cases[0]); ++ci) {
+        const ref_attrs a = cases[ci];
+        const int P = ref_out_dim(a.h, a.pbh, a.pah, a.dh, a.r, a.sh), Q = ref_out_dim(a.w, a.pbw, a.paw, a.dw, a.s, a.sw);
+        const size_t nx = (size_t)a.n * a.c * a.h * a.w, nw = (size_t)a.k * a.c * a.r * a.s, ny = (size_t)a.n * a.k * P * Q;
+        double *x = vec(nx), *w = vec(nw), *dy = vec(ny), *bias = vec(a.k);
+        double *y = vec(ny), *dx = vec(nx), *dx2 = vec(nx), *dw = vec(nw);
+        ref_conv_fwd(&a, x, w, bias, 1, y);
+        ref_conv_fwd(&a, x, w, NULL, 0, y);
+        ref_conv_bwd_data(&a, dy, w, dx);
+        ref_conv_bwd_data_gather(&a, dy, w, dx2);
+        ref_conv_bwd_filters(&a, x, dy, dw);
+        for (size_t i = 0; i < nx; ++i)
+            if (dx[i] - dx2[i] > 1e-9 || dx2[i] - dx[i] > 1e-9) { printf("scatter/gather differ, case %zu\n", ci); return 3; }
+        if (ny) {
+            const int64_t fy[3] = {0, (int64_t)ny / 2, (int64_t)ny - 1}, fx[3] = {0, (int64_t)nx / 2, (int64_t)nx - 1};
+            const int64_t fw[3] = {0, (int64_t)nw / 2, (int64_t)nw - 1};
+            double out[3];
+            ref_conv_fwd_at(&a, x, w, bias, 1, 3, fy, out);
+            ref_conv_bwd_data_at(&a, dy, w, 3, fx, out);
+            ref_conv_bwd_filters_at(&a, x, dy, 3, fw, out);
+            double *db = vec(a.k);
+            ref_bias_grad(a.n, a.k, P, Q, dy, db);
+            ref_relu_bwd_mask((int64_t)ny, dy, y, y);
+            free(db);
+        }
+        free(x); free(w); free(dy); free(bias); free(y); free(dx); free(dx2); free(dw);
+    }
+    const int cs[4] = {1, 5, 16, 37};
+    for (int eb = 2; eb <= 4; eb += 2)
+        for (int i = 0; i < 4; ++i) {
+            const int n = 2, c = cs[i], h = 3, w = 5, CB = (c + 15) / 16;
+            const size_t a = (size_t)n * c * h * w * eb, b = (size_t)n * CB * h * w * 16 * eb;
+            unsigned char *src = malloc(a), *blk = malloc(b), *back = malloc(a);
+            for (size_t j = 0; j < a; ++j) src[j] = (unsigned char)(j * 37 + 1);
+            ref_nchw_to_blocked16(n, c, h, w, eb, src, blk);
+            ref_blocked16_to_nchw(n, c, h, w, eb, blk, back);
+            if (memcmp(src, back, a)) { printf("layout round trip differs, c=%d eb=%d\n", c, eb); return 4; }
+            free(src); free(blk); free(back);
+        }
+    uint32_t *f = malloc(1000 * sizeof(uint32_t)); uint16_t *h16 = malloc(1000 * sizeof(uint16_t));
+    for (int i = 0; i < 1000; ++i) f[i] = (uint32_t)(st = st * 6364136223846793005ull + 1442695040888963407ull);
+    f[0] = 0x7F7FFFFFu; f[1] = 0xFFFFFFFFu; f[2] = 0x00008000u; f[3] = 0x7F800000u;
+    ref_f32_to_bf16_rne_array(1000, f, h16);
+    free(f); free(h16);
+    puts("oracle clean");
+    return 0;
+}
+'''
+
+HOST_DRIVER = r'''
+#include "ngconv.h"
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+static unsigned long long st = 0x9E3779B97F4A7C15ull;
+static int rnd(int n) { st ^= st << 13; st ^= st >> 7; st ^= st << 17; return (int)((st >> 33) % (unsigned)n); }
+static void *P = (void *)(size_t)0x7000000000;                  /* never dereferenced: nothing is launched */
+static const size_t BIG = (size_t)1 << 42;
+static long calls = 0, ok = 0;
+
+static void run2(ngc_conv_desc d)
+{
+    int32_t p = 0, q = 0;
+    ngc_conv_out_shape(&d, &p, &q);
+    for (int op = 0; op < 6; ++op) (void)ngc_conv_workspace_bytes(&d, op);
+    for (int op = 0; op < 5; ++op) (void)ngc_conv_variant(&d, op);
+    (void)ngc_data_elems(&d, 0); (void)ngc_data_elems(&d, 1);
+    for (int l = -1; l < 4; ++l) (void)ngc_filter_elems(&d, l);
+    int rc[9];
+    rc[0] = ngc_conv_fwd(&d, P, P, (const float *)P, P, P, BIG, 0);
+    rc[1] = ngc_conv_bwd_data(&d, P, P, P, P, BIG, 0);
+    rc[2] = ngc_conv_bwd_data_relu(&d, P, P, P, P, P, BIG, 0);
+    rc[3] = ngc_conv_bwd_data_relu_db(&d, P, P, P, P, (float *)P, P, BIG, 0);
+    rc[4] = ngc_bias_grad(&d, P, (float *)P, P, BIG, 0);
+    rc[5] = ngc_conv_bwd_filters(&d, P, P, (float *)P, P, BIG, 0);
+    rc[6] = ngc_conv_fwd(&d, P, P, NULL, P, NULL, 0, 0);         /* no bias, no workspace: an error or not needed */
+    rc[7] = ngc_conv_bwd_filters(&d, P, P, (float *)P, P, 16, 0);
+    rc[8] = ngc_filter_convert(&d, P, P, d.w_layout, 0);
+    for (int i = 0; i < 9; ++i) { ++calls; ok += rc[i] == NGC_OK; (void)ngc_status_string(rc[i]); }
+}
+
+static void run3(ngc_conv3d_desc d)
+{
+    int32_t o = 0, p = 0, q = 0;
+    ngc_conv3d_out_shape(&d, &o, &p, &q);
+    for (int op = 0; op < 6; ++op) { (void)ngc_conv3d_workspace_bytes(&d, op); (void)ngc_conv3d_variant(&d, op); }
+    (void)ngc_conv3d_data_elems(&d, 0); (void)ngc_conv3d_data_elems(&d, 1); (void)ngc_conv3d_filter_elems(&d, d.w_layout);
+    int rc[7];
+    rc[0] = ngc_conv3d_fwd(&d, P, P, (const float *)P, P, P, BIG, 0);
+    rc[1] = ngc_conv3d_bwd_data(&d, P, P, P, P, BIG, 0);
+    rc[2] = ngc_conv3d_bwd_data_relu(&d, P, P, P, P, P, BIG, 0);
+    rc[3] = ngc_conv3d_bwd_data_relu_db(&d, P, P, P, P, (float *)P, P, BIG, 0);
+    rc[4] = ngc_conv3d_bias_grad(&d, P, (float *)P, P, BIG, 0);
+    rc[5] = ngc_conv3d_bwd_filters(&d, P, P, (float *)P, P, BIG, 0);
+    rc[6] = ngc_conv3d_filter_convert(&d, P, P, d.w_layout, 0);
+    for (int i = 0; i < 7; ++i) { ++calls; ok += rc[i] == NGC_OK; }
+}
+
+int main(void)
+{
+    setenv("NGC_DRY_RUN", "1", 1);
+    ngc_reload_switches();
+    /* the benchmark shapes: (n, c, hw, k, r, stride) */
+    const int shapes[][6] = {{64, 64, 56, 64, 3, 1}, {64, 256, 56, 64, 1, 1}, {64, 3, 224, 64, 7, 2}, {128, 128, 56, 128, 3, 2},
+                             {128, 256, 56, 512, 1, 2}, {128, 512, 7, 512, 3, 1}, {128, 2048, 7, 512, 1, 1}, {128, 256, 14, 256, 3, 1},
+                             {2, 16, 16, 32, 3, 1}, {32, 48, 28, 80, 5, 1}, {2000, 512, 56, 512, 3, 1}};
+    for (size_t i = 0; i < sizeof(shapes) / sizeof(shapes[0]); ++i)
+        for (int dt = 0; dt < 2; ++dt)
+            for (int xl = 0; xl < 2; ++xl)
+                for (int yl = 0; yl < 2; ++yl)
+                    for (int wl = 0; wl < 3; ++wl) {
+                        const int *s = shapes[i];
+                        ngc_conv_desc d = {s[0], s[1], s[2], s[2], s[3], s[4], s[4], s[5], s[5], 1, 1, s[4] / 2, s[4] / 2, s[4] / 2, s[4] / 2,
+                                           dt, xl, yl, wl, NGC_EPI_BIAS | NGC_EPI_RELU};
+                        run2(d);
+                    }
+    /* attribute sweep: mostly valid nodes, one attribute in about fifteen out of range */
+#define GE1(n) (rnd(15) ? 1 + rnd(n) : rnd(2) - 1)
+#define GE0(n) (rnd(15) ? rnd(n) : -1)
+#define ENUM(n) (rnd(15) ? rnd(n) : (n) + rnd(2))
+#define CH() (16 * (1 + rnd(8)) + (rnd(4) ? 0 : rnd(16)) - (rnd(15) ? 0 : 200))
+    for (int it = 0; it < 4000; ++it) {
+        ngc_conv_desc d;
+        d.n = GE1(70); d.c = CH(); d.h = GE1(60); d.w = GE1(60); d.k = CH(); d.r = GE1(7); d.s = GE1(7);
+        d.stride_h = GE1(3); d.stride_w = GE1(3); d.dil_h = GE1(3); d.dil_w = GE1(3);
+        d.pad_below_h = GE0(5); d.pad_below_w = GE0(5); d.pad_above_h = GE0(5); d.pad_above_w = GE0(5);
+        d.dtype = ENUM(2); d.x_layout = ENUM(2); d.y_layout = ENUM(2); d.w_layout = ENUM(3); d.epilogue = rnd(15) ? rnd(4) : 4 + rnd(4);
+        run2(d);
+    }
+    for (int it = 0; it < 1500; ++it) {
+        ngc_conv3d_desc d;
+        d.n = GE1(8); d.c = CH(); d.d = GE1(18); d.h = GE1(30); d.w = GE1(30); d.k = CH(); d.t = GE1(4); d.r = GE1(4); d.s = GE1(4);
+        d.stride_d = GE1(2); d.stride_h = GE1(2); d.stride_w = GE1(2); d.dil_d = GE1(2); d.dil_h = GE1(2); d.dil_w = GE1(2);
+        d.pad_below_d = GE0(3); d.pad_below_h = GE0(3); d.pad_below_w = GE0(3);
+        d.pad_above_d = GE0(3); d.pad_above_h = GE0(3); d.pad_above_w = GE0(3);
+        d.dtype = ENUM(2); d.x_layout = ENUM(2); d.y_layout = ENUM(2); d.w_layout = ENUM(3); d.epilogue = rnd(4);
+        run3(d);
+    }
+    /* the calls without a descriptor */
+    for (int dt = -1; dt < 3; ++dt)
+        for (int cols = 0; cols < 40000; cols = cols * 3 + 1) {
+            (void)ngc_softmax(dt, 1000, cols, P, P, 0);
+            (void)ngc_softmax_bwd(dt, 1000, cols, P, P, P, 0);
+            (void)ngc_softmax_variant(dt, cols, 0); (void)ngc_softmax_variant(dt, cols, 1);
+            (void)ngc_layout_convert(dt, 3, cols, 5, 8, P, NGC_NCHW, P, NGC_NCHW16C, 0);
+            (void)ngc_layout_convert(dt, 3, cols, 5, 7, P, NGC_NCHW16C, P, NGC_NCHW, 0);
+        }
+    (void)ngc_conv_fwd(NULL, P, P, NULL, P, P, 0, 0);
+    (void)ngc_conv_workspace_bytes(NULL, 0);
+    (void)ngc_static_scratch_bytes();
+    for (int s = -9; s < 3; ++s) (void)ngc_status_string(s);
+    printf("host clean: %ld calls, %ld accepted\n", calls, ok);
+    return ok > 5000 ? 0 : 5;
+}
+'''
+
+
+def _run(cmd, **kw):
+    r = subprocess.run(cmd, capture_output=True, text=True, **kw)
+    assert r.returncode == 0, f"{' '.join(cmd)}\n{r.stdout[-3000:]}\n{r.stderr[-6000:]}"
+    return r
+
+
+def test_oracle_c_code_is_clean_under_asan_and_ubsan():
+    with tempfile.TemporaryDirectory() as td:
+        drv = os.path.join(td, "drv.c")
+        with open(drv, "w") as f:
+            f.write(ORACLE_DRIVER)
+        exe = os.path.join(td, "drv")
+        _run(["gcc", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+              "-o", exe, drv, os.path.join(ROOT, "oracle", "conv_ref.c"), "-lm"], timeout=300)
+        r = _run([exe], env={**os.environ, **SAN_ENV, "OMP_NUM_THREADS": "4"}, timeout=300)
+        assert "oracle clean" in r.stdout
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not installed")
+def test_host_dispatch_is_clean_under_asan_and_ubsan_with_launches_stubbed():
+    """Host-only objects of every translation unit (hipcc --cuda-host-only: kernels become launch stubs that the dry
+    run never calls), linked with the driver into one sanitized executable."""
+    from concurrent.futures import ThreadPoolExecutor
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all"]
+    with tempfile.TemporaryDirectory() as td:
+        srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+
+        def compile_one(src):
+            obj = os.path.join(td, os.path.basename(src).replace(".hip", ".o"))
+            _run([HIPCC, "--offload-arch=gfx950", "--cuda-host-only", "-O1", "-g", "-std=c++17", "-fPIC", "-Wno-unused-command-line-argument",
+                  "-Wno-inline-asm", "-Wno-unknown-cuda-version", *san, "-c", src, "-o", obj], timeout=900)
+            return obj
+
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            objs = list(ex.map(compile_one, srcs))
+        drv = os.path.join(td, "drv.c")
+        with open(drv, "w") as f:
+            f.write(HOST_DRIVER)
+        drv_o = os.path.join(td, "drv.o")
+        clang = "/opt/rocm/lib/llvm/bin/clang"
+        _run([clang, "-O1", "-g", "-D_GNU_SOURCE", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-I", os.path.join(ROOT, "include"),
+              "-c", drv, "-o", drv_o], timeout=300)
+        # a host-only object still refers to the device image its launch stubs would register: give each an empty one
+        # (the runtime only looks inside an image when a kernel of it is launched, which the dry run never does)
+        undef = _run(["nm", "-u", *objs]).stdout.split()
+        images = sorted({sym for sym in undef if sym.startswith("__hip_fatbin_")})
+        stub = os.path.join(td, "images.c")
+        with open(stub, "w") as f:
+            f.write("".join(f"const unsigned char {sym}[4096] __attribute__((aligned(4096))) = {{0}};\n" for sym in images))
+        stub_o = os.path.join(td, "images.o")
+        _run([clang, "-c", stub, "-o", stub_o])
+        exe = os.path.join(td, "drv")
+        _run([HIPCC, "-fsanitize=address,undefined", "-fno-gpu-sanitize", "-o", exe, drv_o, stub_o, *objs], timeout=600)
+        r = _run([exe], env={**os.environ, **SAN_ENV, "NGC_DRY_RUN": "1"}, timeout=600)
+        assert "host clean" in r.stdout, r.stdout
