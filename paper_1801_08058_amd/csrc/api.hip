@@ -330,6 +330,10 @@ bool strip_plan_class_uncached(const ngc_conv_desc *d, int op, int ca, int cb, i
     q.ntaps = ntaps;
     q.in_bytes = (uint32_t)in_bytes;
     q.wt_bytes = (uint32_t)wt_bytes;
+    {
+        const size_t out_bytes = (size_t)d->n * ((Cout + 15) / 16) * Hfull * Wfull * 32;
+        q.out_bytes = out_bytes < ((size_t)1 << 31) ? (uint32_t)out_bytes : 0;
+    }
     if (!strip_geometry(q, d->n, Hout, Wout, max_dh - min_dh, max_dw - min_dw, ntaps, Cout, nf_out, lds_out)) return false;
     for (int t = 0; t < ntaps; ++t) {
         q.tap_off[t] = (tdh[t] - min_dh) * q.PC + (tdw[t] - min_dw);

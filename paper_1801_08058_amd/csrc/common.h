@@ -81,6 +81,15 @@ __host__ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 }
 
 // two fp32 -> packed bf16x2 with the hardware conversion (v_cvt_pk_bf16_f32, round-to-nearest-even)
+// max(v, 0) in one instruction.  fmaxf() costs two here (the compiler first canonicalises its operand with a
+// v_max_f32 v, v); the result is the same for every input, NaN included (v_max_f32 returns the other operand).
+__device__ __forceinline__ float relu_f32(float v)
+{
+    float r;
+    asm("v_max_f32 %0, 0, %1" : "=v"(r) : "v"(v));
+    return r;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
 {
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -259,6 +268,8 @@ struct StripParams {
     int32_t tap_off[STRIP_MAX_TAPS];    // patch-pixel offset of the tap
     int32_t tap_slab[STRIP_MAX_TAPS];
     uint32_t in_bytes, wt_bytes;
+    uint32_t out_bytes;        // out_mode 0, rank 2: bytes of the stored tensor if below 2 GiB (stores then take 32-bit
+                               // offsets into a buffer descriptor), else 0
     // out_mode 0: 16-channel-blocked [N][Cout/16][Hout][Wout][16].
     // out_mode 1: "sub-pixel" NCHW: output channel col = (a*sub_BW + b)*sub_C + c of position (i,j) is
     //             pixel (sub_BH*i + a, sub_BW*j + b) of channel c of an [N][sub_C][sub_H][sub_W] tensor.

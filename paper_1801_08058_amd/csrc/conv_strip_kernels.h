@@ -371,6 +371,11 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         return;
     }
+    // blocked rank-2 output below 2 GiB: 16-byte stores with 32-bit offsets into a buffer descriptor, lanes that
+    // must not store get an out-of-range offset (no 64-bit address arithmetic, no divergent branch per store)
+    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
+    __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
+    const int relu_on = p.relu;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         if (i >= nfrag) break;
@@ -433,13 +438,21 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                     v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
                 }
-                if (p.relu) {
+                if (relu_on) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                    for (int e = 0; e < 8; ++e) v[e] = relu_f32(v[e]);
                 }
                 const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
                 const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
                 uint4 o = lane_pair_exchange(q0, q1, q2, q3);
+                if (store32 && !DB) {
+                    const bool st = ok && (co_base >> 4) + h < CBout;
+                    const unsigned off = st ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * plane_out)) * 32u + (unsigned)(lg * 16)
+                                            : STRIP_OOB;
+                    ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
+                    __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
+                    continue;
+                }
                 if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * plane_out;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
