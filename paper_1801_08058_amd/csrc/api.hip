@@ -711,6 +711,12 @@ bool stem_fwd_plan_uncached(const ngc_conv_desc *d, int P, int Q, StemFwdParams 
     if (ftp && atoi(ftp) >= 1 && atoi(ftp) <= 8 && atoi(ftp) <= P) q.TP = atoi(ftp);
     q.tiles_per_img = (P + q.TP - 1) / q.TP;
     q.div_q = make_fastdiv((uint32_t)Q);
+    q.div_cpr = make_fastdiv((uint32_t)(d->w / 8));
+    q.div_rows = make_fastdiv((uint32_t)(2 * q.TP + 5));
+    {
+        const size_t y_bytes = (size_t)d->n * d->k * P * Q * 2;
+        q.y_bytes = y_bytes < ((size_t)1 << 31) ? (uint32_t)y_bytes : 0;
+    }
     const size_t patch = (size_t)d->c * (2 * q.TP + 5) * (2 * d->w + 16);
     const size_t lds = ((patch + 15) & ~(size_t)15) + (size_t)64 * d->c * 49 * 2;
     if (lds > 64 * 1024) return false;

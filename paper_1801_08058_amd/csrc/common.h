@@ -372,7 +372,9 @@ struct StemFwdParams {
     int32_t pbh;
     int32_t relu;
     int32_t TP, tiles_per_img;
+    uint32_t y_bytes;          // bytes of y if below 2 GiB (stores then take 32-bit offsets into a buffer descriptor), else 0
     FastDiv div_q;
+    FastDiv div_cpr, div_rows; // patch loader: 16-byte chunks per input row (W / 8), input rows per channel (2 TP + 5)
 };
 
 // ---- low-channel stem backprop-filters ----

@@ -54,9 +54,9 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
         const int cpr = p.W >> 3;                     // 16-byte chunks per input row
         const int total = p.C * rows_in * cpr;
         for (int i = tid; i < total; i += 256) {
-            const int ch = i % cpr;
-            const int rr = i / cpr;                   // c * rows_in + row
-            const int c = rr / rows_in;
+            const int rr = (int)fd_div((uint32_t)i, p.div_cpr);          // c * rows_in + row
+            const int ch = i - rr * cpr;
+            const int c = (int)fd_div((uint32_t)rr, p.div_rows);
             const int row = rr - c * rows_in;
             const int h = 2 * p0 - p.pbh + row;
             uint4 v = make_uint4(0, 0, 0, 0);
@@ -109,6 +109,11 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
             }
         }
 
+    // y below 2 GiB: 16-byte stores with 32-bit offsets into a buffer descriptor, positions outside the tile get an
+    // out-of-range offset (no 64-bit address arithmetic, no divergent branch per store)
+    const bool store32 = p.y_bytes != 0;
+    __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc((void *)p.y, 0, (int)p.y_bytes, 0x00020000);
+    const int relu_on = p.relu;
     for (int f = wave; f < nfrags; f += 4) {
         const uint32_t m = (uint32_t)(f * 32 + l32);
         bool ok = m < (uint32_t)npos;
@@ -145,14 +150,19 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
                 const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
                 v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                 v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                if (p.relu) {
+                if (relu_on) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                    for (int e = 0; e < 8; ++e) v[e] = relu_f32(v[e]);
                 }
                 const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
                 const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
                 const uint4 o = lane_pair_exchange(q0, q1, q2, q3);
-                if (ok) {
+                if (store32) {
+                    const unsigned off = ok ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * PQ)) * 32u + (unsigned)(lg * 16)
+                                            : 0x80000000u;
+                    ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
+                    __builtin_amdgcn_raw_buffer_store_b128(ov, rs_y, (int)off, 0, 0);
+                } else if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * PQ;
                     *reinterpret_cast<uint4 *>(p.y + blk * 16 + lg * 8) = o;
                 }
