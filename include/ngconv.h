@@ -84,7 +84,8 @@ typedef enum { NGC_F32 = 0, NGC_BF16 = 1 } ngc_dtype;
 typedef enum { NGC_NCHW = 0, NGC_NCHW16C = 1 } ngc_data_layout;
 typedef enum { NGC_KCRS = 0, NGC_BLOCKED_FWD = 1, NGC_BLOCKED_BWD = 2 } ngc_filter_layout;
 enum { NGC_EPI_NONE = 0, NGC_EPI_BIAS = 1, NGC_EPI_RELU = 2 };   /* bit flags, forward only */
-enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2, NGC_OP_BIAS_GRAD = 3, NGC_OP_BWD_DATA_DB = 4 };
+enum { NGC_OP_FWD = 0, NGC_OP_BWD_DATA = 1, NGC_OP_BWD_FILTERS = 2, NGC_OP_BIAS_GRAD = 3, NGC_OP_BWD_DATA_DB = 4,
+       NGC_OP_BWD_DATA_FILTERS = 5 };
 
 /* Constant attributes of one Convolution node and of its two derivative nodes. */
 typedef struct {
@@ -183,6 +184,19 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
 int ngc_conv_bwd_filters_noalloc(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw,
                                  void *hip_stream);
 size_t ngc_static_scratch_bytes(void);
+
+/* ConvolutionBackpropData and ConvolutionBackpropFilters of one node in a single pass (Sec. 3: the
+ * derivative graph holds one op per input of the forward op, and both consume the same adjoint dy;
+ * Sec. 4 leaves it to the backend to run several ops of the graph as one kernel).  dx and dw are what
+ * ngc_conv_bwd_data and ngc_conv_bwd_filters produce (dx rounded once from fp32; dw fp32, [K,C,R,S],
+ * run-to-run identical), dy is read from memory once instead of twice.
+ * Built for: bf16, x / dx and dy blocked (NGC_NCHW16C), w_layout NGC_BLOCKED_BWD, 1x1 window, stride 1,
+ * no padding, C a multiple of 64, K = 64, 128 or 256, tensors below 2 GiB; any other descriptor returns
+ * NGC_UNSUPPORTED (the caller then makes the two calls).  ngc_conv_variant(desc, NGC_OP_BWD_DATA_FILTERS)
+ * names the kernel or says "unsupported".  ws: ngc_conv_workspace_bytes(desc, NGC_OP_BWD_DATA_FILTERS) bytes
+ * (0 for unsupported descriptors; NGC_WORKSPACE_TOO_SMALL otherwise).  Errors as ngc_conv_bwd_data. */
+int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w,
+                              void *dx, float *dw, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Data layout conversion (Abstract / Sec. 2: data layout abstraction): copies bit patterns
  * between NGC_NCHW and NGC_NCHW16C for an [n,c,h,w] tensor of `dtype`; tail lanes of a blocked

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libngconv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "layout.hip", "conv_direct.hip", "conv_igemm.hip", "conv_strip.hip", "conv_rows.hip", "conv_strip3.hip", "conv_stem.hip", "wgrad.hip", "wgrad_strip.hip", "wgrad_stem.hip", "wgrad_gemm.hip", "conv_gemm1x1.hip", "bias_grad.hip", "softmax.hip", "conv3d_direct.hip", "api3d.hip", "static_scratch.hip", "switches.hip"]
+SOURCES = ["api.hip", "layout.hip", "conv_direct.hip", "conv_igemm.hip", "conv_strip.hip", "conv_rows.hip", "conv_strip3.hip", "conv_stem.hip", "wgrad.hip", "wgrad_strip.hip", "wgrad_stem.hip", "wgrad_gemm.hip", "conv_gemm1x1.hip", "bias_grad.hip", "softmax.hip", "conv3d_direct.hip", "api3d.hip", "static_scratch.hip", "switches.hip", "bwd1x1_fused.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1262,10 +1262,40 @@ size_t ngc_filter_elems(const ngc_conv_desc *desc, int32_t layout)
     return filter_elems(desc, layout);
 }
 
+// Both derivative ops of a 1x1 stride-1 node in one pass over dy (bwd1x1_fused.hip)
+static bool bwd1x1_fused_plan(const ngc_conv_desc *d, int P, int Q, Bwd1x1FusedParams *fp)
+{
+    if (d->dtype != NGC_BF16 || d->x_layout != NGC_NCHW16C || d->y_layout != NGC_NCHW16C || d->w_layout != NGC_BLOCKED_BWD)
+        return false;
+    if (d->r != 1 || d->s != 1 || d->stride_h != 1 || d->stride_w != 1) return false;
+    if (d->pad_below_h || d->pad_below_w || d->pad_above_h || d->pad_above_w) return false;
+    if (d->c % 64 != 0 || (d->k != 64 && d->k != 128 && d->k != 256)) return false;
+    const size_t hw = (size_t)P * Q, m = (size_t)d->n * hw;
+    const size_t x_bytes = m * d->c * 2, dy_bytes = m * d->k * 2;
+    if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;
+    Bwd1x1FusedParams q;
+    memset(&q, 0, sizeof(q));
+    q.N = d->n; q.C = d->c; q.K = d->k; q.HW = (int32_t)hw; q.M = (uint32_t)m;
+    q.nstages = (int32_t)((m + 63) / 64);
+    const int ctiles = d->c / 64;
+    int parts = (NUM_CUS + ctiles - 1) / ctiles;
+    if (parts > q.nstages) parts = q.nstages;
+    q.stages_per_part = (q.nstages + parts - 1) / parts;
+    q.nparts = (q.nstages + q.stages_per_part - 1) / q.stages_per_part;
+    q.x_bytes = (uint32_t)x_bytes; q.dy_bytes = (uint32_t)dy_bytes;
+    q.div_hw = make_fastdiv((uint32_t)hw);
+    if (fp) *fp = q;
+    return true;
+}
+
 size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
 {
     int P, Q;
     if (validate(desc, &P, &Q) != NGC_OK) return 0;
+    if (op == NGC_OP_BWD_DATA_FILTERS) {
+        Bwd1x1FusedParams fp;
+        return bwd1x1_fused_plan(desc, P, Q, &fp) ? round256((size_t)fp.nparts * fp.K * fp.C * sizeof(float)) : 0;
+    }
     const BatchSlices bs = batch_slices(desc, P, Q);
     if (bs.images < desc->n && op == NGC_OP_BWD_FILTERS) {
         // one dw per group of images behind the workspace of a group's launch, added up in index order at the end
@@ -1286,6 +1316,11 @@ size_t ngc_conv_workspace_bytes(const ngc_conv_desc *desc, int op)
 
 const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
 {
+    if (op == NGC_OP_BWD_DATA_FILTERS) {
+        int P, Q;
+        if (validate(desc, &P, &Q) != NGC_OK) return "invalid";
+        return bwd1x1_fused_plan(desc, P, Q, nullptr) ? "bwd1x1_fused_bf16" : "unsupported";
+    }
     if (op == NGC_OP_BIAS_GRAD) {
         int P, Q;
         if (validate(desc, &P, &Q) != NGC_OK) return "invalid";
@@ -1739,6 +1774,26 @@ const char *ngc_softmax_variant(int32_t dtype, int32_t cols, int32_t bwd)
     if ((dtype != NGC_F32 && dtype != NGC_BF16) || cols < 1) return "invalid";
     const int v = softmax_vectors(dtype, cols, bwd != 0, true);
     return v == 0 ? "softmax_rows_block" : v > 256 ? "softmax_rows_wg" : "softmax_rows_wave";
+}
+
+int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w, void *dx, float *dw,
+                              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int P, Q;
+    const int vs = validate(desc, &P, &Q);
+    if (vs != NGC_OK) return vs;
+    if (!x || !dy || !w || !dx || !dw) return NGC_BAD_ARG;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(dw) || !aligned16(ws)) return NGC_BAD_ARG;
+    Bwd1x1FusedParams fp;
+    if (!bwd1x1_fused_plan(desc, P, Q, &fp)) return NGC_UNSUPPORTED;
+    if (!ws || ws_bytes < round256((size_t)fp.nparts * fp.K * fp.C * sizeof(float))) return NGC_WORKSPACE_TOO_SMALL;
+    fp.x = static_cast<const uint16_t *>(x);
+    fp.dy = static_cast<const uint16_t *>(dy);
+    fp.w = static_cast<const uint16_t *>(w);
+    fp.dx = static_cast<uint16_t *>(dx);
+    fp.partial = static_cast<float *>(ws);
+    fp.dw = dw;
+    return launch_status(launch_bwd1x1_fused(fp, static_cast<hipStream_t>(hip_stream)));
 }
 
 int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw, void *ws,

@@ -415,6 +415,23 @@ struct WgradGemmParams {
     int32_t xcd_order;         // rank 2, blocked operands: one-dimensional grid with the workgroups of a position chunk on one XCD
 };
 
+// ---- both derivative ops of a 1x1 stride-1 node in one pass over dy ----
+struct Bwd1x1FusedParams {
+    const uint16_t *x;         // blocked [N][C/16][HW][16]
+    const uint16_t *dy;        // blocked [N][K/16][HW][16]
+    const uint16_t *w;         // [K/16][C][16]: the backprop-data filter layout
+    uint16_t *dx;              // blocked, same shape as x
+    float *partial;            // [part][K][C]
+    float *dw;                 // [K][C]
+    int32_t N, C, K, HW;
+    uint32_t M;                // N * HW positions
+    int32_t nstages;           // stages of 64 positions
+    int32_t stages_per_part, nparts;
+    uint32_t x_bytes, dy_bytes;
+    FastDiv div_hw;
+};
+hipError_t launch_bwd1x1_fused(const Bwd1x1FusedParams &p, hipStream_t st);
+
 // ---- one-tap (1x1) forward / backprop-data as a pipelined GEMM ----
 struct Gemm1x1Params {
     const uint16_t *in;

@@ -162,6 +162,23 @@ class Run:
         self.last_desc, self.last_raw = d, dx
         return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
 
+    def bwd_data_filters(self, x, dy, w):
+        """Both derivative ops of the node in one call (blocked tensors, filters in the backprop-data layout):
+        (dx, dw) as fp64, and the raw device tensors in self.last_raw."""
+        a = self.a
+        d = desc_of(a, self.dtype, self.xl, self.yl, ng.NGC_BLOCKED_BWD)
+        wd = dev(filter_blocked_host(encode(w, self.dtype), ng.NGC_BLOCKED_BWD))
+        xd = data_to_device(x, self.dtype, self.xl)
+        dyd = data_to_device(dy, self.dtype, self.yl)
+        dx = out_tensor(d, 0, self.dtype)
+        dw = torch.full((a.k * a.c * a.r * a.s,), float("nan"), dtype=torch.float32, device="cuda")
+        ws = workspace(d, ng.NGC_OP_BWD_DATA_FILTERS)
+        ng.ngc_conv_bwd_data_filters(d, xd, dyd, wd, dx, dw, ws, stream())
+        torch.cuda.synchronize()
+        self.last_desc, self.last_raw = d, (dx, dw)
+        return (data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w)),
+                dw.cpu().numpy().astype(np.float64).reshape(a.k, a.c, a.r, a.s))
+
     def bwd_data_relu(self, dy, w, x_in):
         """ConvolutionBackpropData compounded with the backprop of the ReLU that produced x_in."""
         a = self.a
