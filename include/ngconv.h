@@ -191,7 +191,7 @@ size_t ngc_static_scratch_bytes(void);
  * ngc_conv_bwd_data and ngc_conv_bwd_filters produce (dx rounded once from fp32; dw fp32, [K,C,R,S],
  * run-to-run identical), dy is read from memory once instead of twice.
  * Built for: bf16, x / dx and dy blocked (NGC_NCHW16C), w_layout NGC_BLOCKED_BWD, 1x1 window, stride 1,
- * no padding, C a multiple of 64, K = 64, 128 or 256, tensors below 2 GiB; any other descriptor returns
+ * no padding, C a multiple of 64, K = 64, 128, 256 or 512, tensors below 2 GiB; any other descriptor returns
  * NGC_UNSUPPORTED (the caller then makes the two calls).  ngc_conv_variant(desc, NGC_OP_BWD_DATA_FILTERS)
  * names the kernel or says "unsupported".  ws: ngc_conv_workspace_bytes(desc, NGC_OP_BWD_DATA_FILTERS) bytes
  * (0 for unsupported descriptors; NGC_WORKSPACE_TOO_SMALL otherwise).  Errors as ngc_conv_bwd_data. */

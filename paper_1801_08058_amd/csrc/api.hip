@@ -1269,7 +1269,7 @@ static bool bwd1x1_fused_plan(const ngc_conv_desc *d, int P, int Q, Bwd1x1FusedP
         return false;
     if (d->r != 1 || d->s != 1 || d->stride_h != 1 || d->stride_w != 1) return false;
     if (d->pad_below_h || d->pad_below_w || d->pad_above_h || d->pad_above_w) return false;
-    if (d->c % 64 != 0 || (d->k != 64 && d->k != 128 && d->k != 256)) return false;
+    if (d->c % 64 != 0 || (d->k != 64 && d->k != 128 && d->k != 256 && d->k != 512)) return false;
     const size_t hw = (size_t)P * Q, m = (size_t)d->n * hw;
     const size_t x_bytes = m * d->c * 2, dy_bytes = m * d->k * 2;
     if (x_bytes >= ((size_t)1 << 31) || dy_bytes >= ((size_t)1 << 31)) return false;

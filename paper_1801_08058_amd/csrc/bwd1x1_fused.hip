@@ -30,7 +30,6 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4_f;
 constexpr unsigned BF_OOB = 0x80000000u;
 constexpr int BF_SP = 64;                         // positions per stage
 constexpr int BF_PLANE = BF_SP * 32 + 128;        // bytes per 16-channel plane of a stage
-constexpr int BF_NBUF = 3;
 
 __device__ __forceinline__ bf16x8 tr_frag_f(const unsigned char *lo)
 {
@@ -41,10 +40,12 @@ __device__ __forceinline__ bf16x8 tr_frag_f(const unsigned char *lo)
     return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int KT>
+// NBUF = stage buffers of the ring (3; 2 for K = 512, whose stages are 78 KB)
+template <int KT, int NBUF>
 __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams p)
 {
     constexpr int NW = 8;
+    constexpr int BF_NBUF = NBUF;
     constexpr int KB = 4 * KT;                    // 16-channel planes of dy
     constexpr int NPL = KB + 4;                   // planes per stage: dy, then the 4 planes of the x tile
     constexpr int STAGE = NPL * BF_PLANE;
@@ -71,16 +72,22 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
     const int s_end = (s_begin + p.stages_per_part < p.nstages) ? s_begin + p.stages_per_part : p.nstages;
     const int nst = s_end > s_begin ? s_end - s_begin : 0;
 
-    // ---- dx: wave (c32, pos16) owns channels 32 c32 .. +31 of the tile and positions 16 pos16 .. +15 of a stage
-    const int c32 = wave & 1, pos16 = wave >> 1;
+    // ---- dx: two 16 c x 16 position tiles of a stage per wave.  K <= 256: wave (c32, pos16) holds channel blocks
+    // 2 c32, 2 c32 + 1 of the tile for position block pos16 (two filter operand sets, one dy operand per step);
+    // K = 512 (WIDE): wave (c16, pos32) holds channel block c16 for position blocks 2 pos32, 2 pos32 + 1 (one
+    // filter operand set of 64 registers instead of two, two dy operands per step).
+    constexpr bool WIDE = KT == 8;
+    constexpr int NWA = WIDE ? 1 : 2;
+    const int cblk0 = WIDE ? (wave & 3) : 2 * (wave & 1);               // first 16-channel block (inside the tile)
+    const int pblk0 = WIDE ? 2 * (wave >> 2) : (wave >> 1);             // first 16-position block
     // filter operands: rows = channels c (lane L of 16), 8 consecutive k per lane group (w is [k/16][c][k%16])
-    bf16x8 wa[2][KSTEPS];
+    bf16x8 wa[NWA][KSTEPS];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < NWA; ++a)
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const int kb = 2 * ks + (grp >> 1);
-            const int c = ct * 64 + c32 * 32 + a * 16 + L;
+            const int c = ct * 64 + (cblk0 + a) * 16 + L;
             wa[a][ks] = *reinterpret_cast<const bf16x8 *>(p.w + ((size_t)kb * p.C + c) * 16 + (grp & 1) * 8);
         }
 
@@ -119,17 +126,17 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
 
     // byte offset of this lane inside a plane for the transposed reads of a 32-position step
     const int lane_off = (grp * 4 + (L >> 2)) * 32 + (L & 3) * 8;
-    // ... and for the dy operand of the dx contraction: position 16 pos16 + L, 8 channels (grp & 1) of block (grp >> 1)
-    const int dxb_off = (grp >> 1) * BF_PLANE + (pos16 * 16 + L) * 32 + (grp & 1) * 16;
+    // ... and for the dy operand of the dx contraction: position 16 pblk0 + L, 8 channels (grp & 1) of block (grp >> 1)
+    const int dxb_off = (grp >> 1) * BF_PLANE + (pblk0 * 16 + L) * 32 + (grp & 1) * 16;
 
     for (int s = 0; s < BF_NBUF - 1 && s < nst; ++s) issue_loads(s, s);
     int buf = 0;
     for (int s = 0; s < nst; ++s) {
         // This wave's vector-memory operations complete in the order they were issued, loads and stores alike.  After
-        // the loads of stage s it has issued: the 2 stores of stage s - 2, the loads of stage s + 1 (if there is one)
-        // and the 2 stores of stage s - 1.
+        // the loads of stage s it has issued the loads of the `later` stages that follow (NBUF - 2 of them, fewer at
+        // the end) and the 2 stores of each of the stages s - NBUF + 1 .. s - 1 that exist.
         const int later = (nst - 1 - s < BF_NBUF - 2) ? nst - 1 - s : BF_NBUF - 2;
-        wait_vmcnt(later * LPW + (s == 0 ? 0 : s == 1 ? 2 : 4));
+        wait_vmcnt(later * LPW + 2 * (s < BF_NBUF - 1 ? s : BF_NBUF - 1));
         wg_barrier_nofence();                                            // stage s complete; buffer of stage s - 1 is free
         {
             const int nb = buf + BF_NBUF - 1 >= BF_NBUF ? buf - 1 : buf + BF_NBUF - 1;
@@ -139,13 +146,18 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
         const unsigned char *xs = dys + KB * BF_PLANE;
         buf = (buf + 1 == BF_NBUF) ? 0 : buf + 1;
 
-        // dx tile of the stage
+        // dx tiles of the stage
         f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = d0;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const bf16x8 b = *reinterpret_cast<const bf16x8 *>(dys + 2 * ks * BF_PLANE + dxb_off);
             d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0][ks], b, d0, 0, 0, 0);
-            d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1][ks], b, d1, 0, 0, 0);
+            if constexpr (WIDE) {
+                const bf16x8 b1 = *reinterpret_cast<const bf16x8 *>(dys + 2 * ks * BF_PLANE + dxb_off + 16 * 32);
+                d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0][ks], b1, d1, 0, 0, 0);
+            } else {
+                d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[NWA - 1][ks], b, d1, 0, 0, 0);
+            }
         }
         // dw: two 32-position steps
 #pragma unroll
@@ -160,17 +172,25 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
 #pragma unroll
                 for (int k = 0; k < CBW; ++k) acc[i][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[k], acc[i][k], 0, 0, 0);
         }
-        // store dx: this lane holds channels 4 grp .. +3 of blocks (2 c32, 2 c32 + 1) of the tile for position pos16*16 + L
+        // store dx: this lane holds channels 4 grp .. +3 of a 16-channel block for position 16 (position block) + L;
+        // d1 is the next channel block at the same position, or (WIDE) the same block 16 positions on
         {
-            const uint32_t m = (uint32_t)((s_begin + s) * BF_SP + pos16 * 16 + L);
-            const bool in = m < p.M;
-            const uint32_t n = fd_div(in ? m : 0, p.div_hw);
-            const uint32_t pq = (in ? m : 0) - n * p.div_hw.d;
-            const unsigned o0 = in ? (unsigned)(((n * CBt + ct * 4 + c32 * 2) * HW + pq) * 32 + grp * 8) : BF_OOB;
-            const unsigned o1 = in ? o0 + (unsigned)(HW * 32) : BF_OOB;
             typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
             const u32x2 v0 = {pack_bf16x2_hw(d0[0], d0[1]), pack_bf16x2_hw(d0[2], d0[3])};
             const u32x2 v1 = {pack_bf16x2_hw(d1[0], d1[1]), pack_bf16x2_hw(d1[2], d1[3])};
+            const uint32_t m = (uint32_t)((s_begin + s) * BF_SP + pblk0 * 16 + L);
+            const bool in = m < p.M;
+            const uint32_t n = fd_div(in ? m : 0, p.div_hw);
+            const uint32_t pq = (in ? m : 0) - n * p.div_hw.d;
+            const unsigned o0 = in ? (unsigned)(((n * CBt + ct * 4 + cblk0) * HW + pq) * 32 + grp * 8) : BF_OOB;
+            unsigned o1 = in ? o0 + (unsigned)(HW * 32) : BF_OOB;
+            if constexpr (WIDE) {
+                const uint32_t m1 = m + 16;
+                const bool in1 = m1 < p.M;
+                const uint32_t n1 = fd_div(in1 ? m1 : 0, p.div_hw);
+                const uint32_t pq1 = (in1 ? m1 : 0) - n1 * p.div_hw.d;
+                o1 = in1 ? (unsigned)(((n1 * CBt + ct * 4 + cblk0) * HW + pq1) * 32 + grp * 8) : BF_OOB;
+            }
             __builtin_amdgcn_raw_buffer_store_b64(v0, rs_dx, (int)o0, 0, 0);
             __builtin_amdgcn_raw_buffer_store_b64(v1, rs_dx, (int)o1, 0, 0);
         }
@@ -187,36 +207,48 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
                 out[(size_t)(16 * (kb_w0 + i) + 4 * grp + v) * p.C + 16 * (cb_w0 + j) + L] = acc[i][j][v];
 }
 
-// dw[i] = sum over parts (index order) of partial[part][i], i over K*C (float4 units).  256 threads = 32 outputs x
-// 8 part slices; the slices are summed through LDS in a fixed tree.
+// dw[i] = sum over parts of partial[part][i], i over K*C (float4 units), in a fixed order.  256 threads = 16 outputs
+// x 16 part slices (slice s adds parts s, s + 16, ... in two interleaved chains); the slices are summed through LDS
+// in a fixed tree.
 __global__ __launch_bounds__(256) void bwd1x1_fused_reduce(const f32x4 *__restrict__ partial, f32x4 *__restrict__ dw, int nparts, int n4)
 {
-    __shared__ f32x4 sm[8][32];
-    const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
-    const int i = blockIdx.x * 32 + o;
-    f32x4 t = {0.f, 0.f, 0.f, 0.f};
-    if (i < n4)
-        for (int sp = sl; sp < nparts; sp += 8) t += partial[(size_t)sp * n4 + i];
-    sm[sl][o] = t;
+    __shared__ f32x4 sm[16][16];
+    const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int i = blockIdx.x * 16 + o;
+    f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
+    if (i < n4) {
+        int sp = sl;
+        for (; sp + 16 < nparts; sp += 32) {
+            t0 += partial[(size_t)sp * n4 + i];
+            t1 += partial[(size_t)(sp + 16) * n4 + i];
+        }
+        if (sp < nparts) t0 += partial[(size_t)sp * n4 + i];
+    }
+    sm[sl][o] = t0 + t1;
     __syncthreads();
-    if (sl == 0 && i < n4)
-        dw[i] = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+    if (sl == 0 && i < n4) {
+        f32x4 r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = sm[2 * j][o] + sm[2 * j + 1][o];
+        dw[i] = ((r[0] + r[1]) + (r[2] + r[3])) + ((r[4] + r[5]) + (r[6] + r[7]));
+    }
 }
 
 template <int KT>
 static hipError_t launch_kt(const Bwd1x1FusedParams &p, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)BF_NBUF * (4 * KT + 4) * BF_PLANE;
+    constexpr int NBUF = KT == 8 ? 2 : 3;
+    constexpr size_t lds = (size_t)NBUF * (4 * KT + 4) * BF_PLANE;
     static LdsLimitOnce lds_limit;
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&bwd1x1_fused_bf16<KT>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&bwd1x1_fused_bf16<KT, NBUF>));
         if (e != hipSuccess) return e;
     }
-    NGC_LAUNCH((bwd1x1_fused_bf16<KT>), dim3(p.nparts, p.C / 64), dim3(512), lds, st, p);
+    NGC_LAUNCH((bwd1x1_fused_bf16<KT, NBUF>), dim3(p.nparts, p.C / 64), dim3(512), lds, st, p);
     hipError_t e = ngc::launch_result();
     if (e != hipSuccess) return e;
     const int n4 = p.K * p.C / 4;
-    NGC_LAUNCH(bwd1x1_fused_reduce, dim3((n4 + 31) / 32), dim3(256), 0, st, reinterpret_cast<const f32x4 *>(p.partial),
+    NGC_LAUNCH(bwd1x1_fused_reduce, dim3((n4 + 15) / 16), dim3(256), 0, st, reinterpret_cast<const f32x4 *>(p.partial),
                reinterpret_cast<f32x4 *>(p.dw), p.nparts, n4);
     return ngc::launch_result();
 }
@@ -227,6 +259,7 @@ hipError_t launch_bwd1x1_fused(const Bwd1x1FusedParams &p, hipStream_t st)
     case 1: return launch_kt<1>(p, st);
     case 2: return launch_kt<2>(p, st);
     case 4: return launch_kt<4>(p, st);
+    case 8: return launch_kt<8>(p, st);
     default: return hipErrorInvalidValue;
     }
 }

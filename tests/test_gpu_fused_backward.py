@@ -29,7 +29,7 @@ def _tensors(a, seed):
 # (n, c, hw, k[, w]): stages of 64 positions that end inside an image (7x7, 9x5), straddle images, cover several
 # channel tiles, every K the kernel is built for, one stage per workgroup and many, a ragged last stage
 CASES = [(3, 64, 7, 64), (2, 64, 8, 128), (5, 128, 7, 256), (1, 64, 56, 256), (4, 192, 14, 128), (3, 64, 9, 64, 5),
-         (2, 256, 28, 64), (64, 64, 3, 256), (1, 64, 1, 64)]
+         (2, 256, 28, 64), (64, 64, 3, 256), (1, 64, 1, 64), (3, 128, 7, 512), (2, 64, 28, 512)]
 
 
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "n%dc%dhw%dk%d" % c[:4])
@@ -63,7 +63,7 @@ def test_fused_backward_is_run_to_run_identical_and_agrees_with_the_separate_ops
 def test_fused_backward_refuses_what_it_is_not_built_for():
     for a, wl in ((Attrs(2, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1), ng.NGC_BLOCKED_BWD),      # 3x3
                   (Attrs(2, 64, 8, 8, 64, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0), ng.NGC_BLOCKED_BWD),      # stride 2
-                  (_attrs(2, 64, 8, 512), ng.NGC_BLOCKED_BWD),                                     # K beyond the kernel
+                  (_attrs(2, 64, 8, 1024), ng.NGC_BLOCKED_BWD),                                    # K beyond the kernel
                   (_attrs(2, 48, 8, 64), ng.NGC_BLOCKED_BWD),                                      # C not a multiple of 64
                   (_attrs(2, 64, 8, 64), ng.NGC_KCRS)):                                            # filters not in the backprop-data layout
         d = desc_of(a, "bf16", BLK, BLK, wl)
