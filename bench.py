@@ -70,6 +70,9 @@ def parse():
                          "backward_compound_kernels; never part of the timed step)")
     ap.add_argument("--propagate-layout", action="store_true",
                     help="cfg3 only: no conversion pass; the three ops read x from / write dx to the NCHW tensor directly")
+    ap.add_argument("--fused-backward", action="store_true",
+                    help="1x1 stride-1 layers with blocked tensors: backprop-data and backprop-filters as one call "
+                         "(ngc_conv_bwd_data_filters, dy read once); same nominal flop, reported under its own config key")
     ap.add_argument("--cold", action="store_true", help="rotate over buffer sets (> 512 MB) between steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy kernel of known size (same-layout ngc_layout_convert of the "
@@ -84,7 +87,7 @@ class LayerBench:
     """Device buffers and launch closures of one layer (all ops through the C ABI).  Inputs are
     uploaded as NCHW bf16 and brought into the blocked layout by the library's own conversion."""
 
-    def __init__(self, L, ng, torch, nchw_input=False, sets=1, propagate=False):
+    def __init__(self, L, ng, torch, nchw_input=False, sets=1, propagate=False, fused_backward=False):
         import numpy as np
         import synth_inputs
         self.L, self.ng, self.torch = L, ng, torch
@@ -147,6 +150,13 @@ class LayerBench:
         self.db_prev = torch.empty(L.c, dtype=torch.float32, device="cuda")
         self.stream = cur
         self.ops = list(L.ops)
+        # --fused-backward: where the library has the one-pass kernel for the node (1x1, stride 1, blocked tensors),
+        # backprop-data and backprop-filters are one call that reads dy once
+        if (fused_backward and "bwd_data" in self.ops and "bwd_filters" in self.ops and blocked_in and not propagate
+                and ng.ngc_conv_variant(self.d_bwd, ng.NGC_OP_BWD_DATA_FILTERS) == "bwd1x1_fused_bf16"):
+            self.ops = [op for op in self.ops if op not in ("bwd_data", "bwd_filters")] + ["bwd_fused"]
+            self.ws[ng.NGC_OP_BWD_DATA_FILTERS] = torch.empty(ng.ngc_conv_workspace_bytes(self.d_bwd, ng.NGC_OP_BWD_DATA_FILTERS),
+                                                              dtype=torch.uint8, device="cuda")
         if nchw_input and not propagate:
             self.ops = ["convert"] + self.ops
 
@@ -164,6 +174,9 @@ class LayerBench:
             ng.ngc_conv_bwd_data(self.d_bwd, s["dy"], self.w_bwd, s["dx"], self.ws[ng.NGC_OP_BWD_DATA], st)
         elif op == "bwd_filters":
             ng.ngc_conv_bwd_filters(self.d_wg, s["x"], s["dy"], s["dw"], self.ws[ng.NGC_OP_BWD_FILTERS], st)
+        elif op == "bwd_fused":
+            ng.ngc_conv_bwd_data_filters(self.d_bwd, s["x"], s["dy"], self.w_bwd, s["dx"], s["dw"],
+                                         self.ws[ng.NGC_OP_BWD_DATA_FILTERS], st)
         elif op == "bwd_data_relu":       # backward compounds: timed on their own, not part of the step
             ng.ngc_conv_bwd_data_relu(self.d_bwd, s["dy"], self.w_bwd, s["x"], s["dx"], self.ws[ng.NGC_OP_BWD_DATA], st)
         elif op == "bwd_data_relu_db":    # ... and the channel sums of dx (bias gradient of the producing layer)
@@ -194,6 +207,8 @@ class LayerBench:
             return 2 * xb + yb + wb + (4 * L.c if op.endswith("_db") else 0)
         if op == "bias_grad":
             return yb + 4 * L.k
+        if op == "bwd_fused":
+            return 2 * xb + yb + 3 * wb  # dy once, x in, dx out, w in, dw (fp32) out
         return xb + yb + 2 * wb          # bwd_filters: dw fp32
 
 
@@ -512,7 +527,8 @@ def main():
     if args.propagate_layout and cfg != 3:
         print("bench.py: --propagate-layout applies to --workload cfg3", file=sys.stderr)
         sys.exit(2)
-    benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets, propagate=args.propagate_layout) for L in layers]
+    benches = [LayerBench(L, ng, torch, nchw_input=(cfg == 3), sets=sets, propagate=args.propagate_layout,
+                          fused_backward=args.fused_backward) for L in layers]
     torch.cuda.synchronize()
 
     def make_step(streams):
@@ -536,12 +552,13 @@ def main():
     for b in benches:
         for op in b.ops:
             ms = event_time_ms(torch, lambda i, b=b, op=op: b.launch(op, i), reps, args.batches)
-            flop = 0.0 if op == "convert" else b.L.flop_per_op
+            flop = 0.0 if op == "convert" else (2 if op == "bwd_fused" else 1) * b.L.flop_per_op
             kern[f"{b.L.name}:{op}"] = {
                 "us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
                 "gbs": round(b.algorithmic_bytes(op) / (ms * 1e-3) / 1e9, 1),
                 "variant": {"convert": "layout", "fwd": ng.ngc_conv_variant(b.d_fwd, 0),
                             "bwd_data": ng.ngc_conv_variant(b.d_bwd, 1),
+                            "bwd_fused": ng.ngc_conv_variant(b.d_bwd, ng.NGC_OP_BWD_DATA_FILTERS),
                             "bwd_filters": ng.ngc_conv_variant(b.d_wg, 2)}[op],
                 "count": b.L.count}
     ksum_us = sum(v["us"] * v["count"] for v in kern.values())
@@ -554,7 +571,7 @@ def main():
     if not args.no_three_stream and cfg != 3:
         extra_streams = [torch.cuda.Stream() for _ in range(2)]         # default priority
         step3 = make_step({"fwd": benches[0].stream, "bwd_data": extra_streams[0].cuda_stream,
-                           "bwd_filters": extra_streams[1].cuda_stream})
+                           "bwd_filters": extra_streams[1].cuda_stream, "bwd_fused": extra_streams[0].cuda_stream})
         for i in range(max(args.warmup, 5)):
             step3(i)
         per3 = timed_steps_ms(torch, step3, args.steps, args.batches)
@@ -612,7 +629,8 @@ def main():
                                    "per-axis strides) N=32 bf16, 8 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
                    "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
                    "streams": 1,
-                   **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {})},
+                   **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {}),
+                   **({"fused_backward": "bwd_data + bwd_filters of the 1x1 stride-1 layers as one call"} if args.fused_backward else {})},
         "value_basis": "nominal flop of the step / sum of the single-stream kernel medians (kernel_sum.us)",
         "pct_of_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "gflop_per_step": round(flop_step / 1e9, 2),
