@@ -238,22 +238,27 @@ __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
 __global__ __launch_bounds__(256) void wgrad_stem_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
                                                         int nparts, int K, int C)
 {
-    __shared__ f32x4 sm[8][32];
+    // 256 threads = 8 outputs x 32 part slices (few outputs, many parts: the slices keep enough loads in flight);
+    // slice s adds parts s, s + 32, ... in index order, the slices are summed in a fixed tree
+    __shared__ f32x4 sm[32][8];
     const size_t per4 = (size_t)(K / 64) * 2 * 4 * WST_NF * 64;
-    const int o = threadIdx.x & 31;
-    const int sl = threadIdx.x >> 5;
-    const size_t i = (size_t)blockIdx.x * 32 + o;
+    const int o = threadIdx.x & 7;
+    const int sl = threadIdx.x >> 3;
+    const size_t i = (size_t)blockIdx.x * 8 + o;
     f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
     int sp = sl;
-    for (; sp + 8 < nparts; sp += 16) {
+    for (; sp + 32 < nparts; sp += 64) {
         t0 += partial[(size_t)sp * per4 + i];
-        t1 += partial[(size_t)(sp + 8) * per4 + i];
+        t1 += partial[(size_t)(sp + 32) * per4 + i];
     }
     if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
     sm[sl][o] = t0 + t1;
     __syncthreads();
     if (sl == 0) {
-        const f32x4 r = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+        f32x4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = (sm[4 * j][o] + sm[4 * j + 1][o]) + (sm[4 * j + 2][o] + sm[4 * j + 3][o]);
+        const f32x4 r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
         const int lane = (int)(i & 63);
         size_t u = i >> 6;
         const int f = (int)(u % WST_NF); u /= WST_NF;
@@ -281,7 +286,7 @@ hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStre
     hipError_t e = ngc::launch_result();
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)(p.K / 64) * 2 * 4 * WST_NF * 64;
-    NGC_LAUNCH(wgrad_stem_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+    NGC_LAUNCH(wgrad_stem_reduce, dim3((unsigned)(per4 / 8)), dim3(256), 0, st,
                reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.N * p.strips, p.K, p.C);
     return ngc::launch_result();
 }
