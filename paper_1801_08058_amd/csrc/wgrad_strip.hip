@@ -205,6 +205,9 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         else if (++is_stage == p.nstages) { is_stage = 0; ++is_img; }
     };
 
+    // Accumulator block i of this wave holds k block i ^ kbm: the streams number their blocks differently so that the
+    // exchange at the end moves the same registers in every wave (sends blocks 2-3, then block 1; keeps block 0)
+    const int kbm = NH == 4 ? (((wh & 1) << 1) | (wh >> 1)) : NH == 2 ? ((wh & 1) << 1) : 0;
     f32x4 acc[4][WS_NT];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -263,7 +266,8 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         buf = (buf + 1 == p.nring) ? 0 : buf + 1;
         auto load_a = [&](const int (&dyoff)[2], bf16x8 (&a)[4]) {
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) a[kb] = tr_frag(dys + kb * p.dyplane + dyoff[0], dys + kb * p.dyplane + dyoff[1]);
+            for (int kb = 0; kb < 4; ++kb)
+                a[kb] = tr_frag(dys + (kb ^ kbm) * p.dyplane + dyoff[0], dys + (kb ^ kbm) * p.dyplane + dyoff[1]);
         };
         auto load_b = [&](const int (&xoff)[2], int t) {
             return tr_frag(xs + xoff[0] + p.tap_off[t] * 32, xs + xoff[1] + p.tap_off[t] * 32);
@@ -315,38 +319,75 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     __syncthreads();                                        // all stage buffers are free
     WS_TL();
 
-    // ---- sum the step-parity copies (waves h=1 publish, h=0 add) and write the partial tile.
+    // ---- sum the NH step-stream copies of the tile and write the partial.
     // Accumulator register v of tile (kb, t): k = 16 kb + 4*(lane/16) + v, c = 16 cq + lane%16.
     // The partial is stored in register order, [tile][cq][kb][tap][lane][v] (16 bytes per lane,
     // 1 KB per store instruction); wgrad_strip_reduce maps it back to [K][C][R][S].
     f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+    f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
+                 (((size_t)blockIdx.x * gridDim.y + blockIdx.y) * NCQ + cq) * (4 * WS_NT * 64);
+    if constexpr (NH == 2 || NH == 4) {
+        // Butterfly over the streams: in every round each wave hands half of the k blocks it still owns to the
+        // partner stream and adds the partner's copy of the half it keeps, so all eight waves move data in every
+        // round and each ends up owning 4 / NH k blocks of the sum (k block kbm, and kbm + 1 for NH = 2), which it
+        // stores itself.  The block numbering per stream (kbm) makes a wave's kept blocks its partner's sent ones.
+        // Outbox of wave w: 18 tiles of 1 KB at red + w * 18 * 64.
+        f32x4 *outbox = red + wave * (18 * 64);
+        const f32x4 *inbox1 = red + (cq + NCQ * (wh ^ 1)) * (18 * 64);
 #pragma unroll
-    for (int stride = NH / 2; stride >= 1; stride >>= 1) {
-        if (wh >= stride && wh < 2 * stride) {
-            f32x4 *dst = red + ((wh - stride) * NCQ + cq) * (4 * WS_NT * 64);
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) outbox[(i * WS_NT + t) * 64 + lane] = acc[2 + i][t];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) acc[i][t] += inbox1[(i * WS_NT + t) * 64 + lane];
+        if constexpr (NH == 4) {
+            __syncthreads();                                        // outboxes are free again
+            const f32x4 *inbox2 = red + (cq + NCQ * (wh ^ 2)) * (18 * 64);
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) outbox[t * 64 + lane] = acc[1][t];
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) acc[0][t] += inbox2[t * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < WS_NT; ++t) out[(kbm * WS_NT + t) * 64 + lane] = acc[0][t];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int t = 0; t < WS_NT; ++t) out[((kbm + i) * WS_NT + t) * 64 + lane] = acc[i][t];
+        }
+        WS_TL();
+    } else {
+        // eight streams (NCQ = 1): plain tree, waves of the upper half publish, the lower half adds
+#pragma unroll
+        for (int stride = NH / 2; stride >= 1; stride >>= 1) {
+            if (wh >= stride && wh < 2 * stride) {
+                f32x4 *dst = red + ((wh - stride) * NCQ + cq) * (4 * WS_NT * 64);
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int t = 0; t < WS_NT; ++t) dst[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
+            }
+            __syncthreads();
+            if (wh < stride) {
+                const f32x4 *src = red + (wh * NCQ + cq) * (4 * WS_NT * 64);
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int t = 0; t < WS_NT; ++t) acc[kb][t] += src[(kb * WS_NT + t) * 64 + lane];
+            }
+            __syncthreads();
+        }
+        WS_TL();
+        if (wh == 0) {
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int t = 0; t < WS_NT; ++t) dst[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
+                for (int t = 0; t < WS_NT; ++t) out[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
         }
-        __syncthreads();
-        if (wh < stride) {
-            const f32x4 *src = red + (wh * NCQ + cq) * (4 * WS_NT * 64);
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                for (int t = 0; t < WS_NT; ++t) acc[kb][t] += src[(kb * WS_NT + t) * 64 + lane];
-        }
-        __syncthreads();
-    }
-    WS_TL();
-    if (wh == 0) {
-        f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
-                     (((size_t)blockIdx.x * gridDim.y + blockIdx.y) * NCQ + cq) * (4 * WS_NT * 64);
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-            for (int t = 0; t < WS_NT; ++t) out[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
     }
 #ifdef NGC_TIMELINE
     WS_TL();
