@@ -516,6 +516,15 @@ def _sampled_layer_check(L, n_y=100_000, n_dw=2048, convert_x_on_device=False):
         ref = oracle.conv_bwd_filters_at(a, x64, dy64, idx)
         assert oracle.max_normalised_error(dw.reshape(-1)[idx], ref) <= bound("bf16", "dw"), "bwd_filters"
         assert np.isfinite(dw).all()
+    if ("bwd_data" in L.ops and "bwd_filters" in L.ops and blocked_ok and
+            ng.ngc_conv_variant(desc_of(a, "bf16", BLK, BLK, ng.NGC_BLOCKED_BWD), ng.NGC_OP_BWD_DATA_FILTERS) == "bwd1x1_fused_bf16"):
+        # both derivative ops in one pass over dy, at the launch configuration `bench.py --fused-backward` times
+        dxf, dwf = run.bwd_data_filters(t["x"], t["dy"], t["w"])
+        idx = rng.integers(0, dxf.size, n_y)
+        assert oracle.max_normalised_error(dxf.reshape(-1)[idx], oracle.conv_bwd_data_at(a, dy64, w64, idx)) <= bound("bf16", "act"), "fused dx"
+        idx = rng.integers(0, dwf.size, min(n_dw, dwf.size))
+        assert oracle.max_normalised_error(dwf.reshape(-1)[idx], oracle.conv_bwd_filters_at(a, x64, dy64, idx)) <= bound("bf16", "dw"), "fused dw"
+        assert np.isfinite(dxf).all() and np.isfinite(dwf).all()
 
 
 def test_cfg2_full_size_sampled():
