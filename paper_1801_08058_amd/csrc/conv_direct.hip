@@ -71,21 +71,23 @@ __global__ __launch_bounds__(256) void direct_bwd_data(ngc_conv_desc d, int P, i
     decode(d.x_layout, d.c, d.h, d.w, i, n, c, h, ww);
     float acc = 0.f;
     if (c < d.c) {
-        for (int k = 0; k < d.k; ++k)
-            for (int r = 0; r < d.r; ++r) {
-                const int pn = h + d.pad_below_h - r * d.dil_h;
-                if (pn < 0 || pn % d.stride_h != 0) continue;
-                const int p = pn / d.stride_h;
-                if (p >= P) continue;
-                for (int s = 0; s < d.s; ++s) {
-                    const int qn = ww + d.pad_below_w - s * d.dil_w;
-                    if (qn < 0 || qn % d.stride_w != 0) continue;
-                    const int q = qn / d.stride_w;
-                    if (q >= Q) continue;
-                    acc = fmaf(ld(dy, data_index(d.y_layout, d.k, P, Q, n, k, p, q)),
-                               ld(w, (((size_t)k * d.c + c) * d.r + r) * d.s + s), acc);
-                }
+        // taps outermost: which output position a tap reaches (two integer divisions) is decided once per tap, not
+        // once per tap and output channel
+        for (int r = 0; r < d.r; ++r) {
+            const int pn = h + d.pad_below_h - r * d.dil_h;
+            if (pn < 0 || pn % d.stride_h != 0) continue;
+            const int p = pn / d.stride_h;
+            if (p >= P) continue;
+            for (int s = 0; s < d.s; ++s) {
+                const int qn = ww + d.pad_below_w - s * d.dil_w;
+                if (qn < 0 || qn % d.stride_w != 0) continue;
+                const int q = qn / d.stride_w;
+                if (q >= Q) continue;
+                const size_t wrs = ((size_t)c * d.r + r) * d.s + s, wk = (size_t)d.c * d.r * d.s;
+                for (int k = 0; k < d.k; ++k)
+                    acc = fmaf(ld(dy, data_index(d.y_layout, d.k, P, Q, n, k, p, q)), ld(w, k * wk + wrs), acc);
             }
+        }
     }
     if (mask && !(ld(mask, i) > 0.f)) acc = 0.f;          // ReLU backprop: same shape / layout as dx
     st(dx, i, acc);
