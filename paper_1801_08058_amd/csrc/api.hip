@@ -651,10 +651,10 @@ bool wgrad_strip_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStripP
     q.nring = 3 * stage <= LDS_LIMIT ? 3 : 2;
     const char *fr = env_switch(SW_WGRAD_RING);                          // tests / benchmarks only
     if (fr && atoi(fr) == 2) q.nring = 2;
-    // waves 4-7 (the second wave of each SIMD) issue their loads after their MFMAs; NGC_WGRAD_LATE (tests /
-    // benchmarks only) sets another wave mask, 0 = every wave issues right after the barrier
+    // waves 0-3 (one wave of each SIMD) issue their loads after their MFMAs, waves 4-7 right after the barrier;
+    // NGC_WGRAD_LATE (tests / benchmarks only) sets another wave mask, 0 = every wave issues right after the barrier
     const char *fl = env_switch(SW_WGRAD_LATE);
-    q.late_mask = fl ? (int)strtol(fl, nullptr, 0) & 0xFF : 0xF0;
+    q.late_mask = fl ? (int)strtol(fl, nullptr, 0) & 0xFF : 0x0F;
     size_t lds = q.nring * stage;
     const size_t red = (size_t)4 * 144 * 64 * sizeof(float);           // final cross-wave sum
     if (lds < red) lds = red;
