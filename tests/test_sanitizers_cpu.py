@@ -120,10 +120,11 @@ static void run2(ngc_conv_desc d)
     int32_t p = 0, q = 0;
     ngc_conv_out_shape(&d, &p, &q);
     for (int op = 0; op < 6; ++op) (void)ngc_conv_workspace_bytes(&d, op);
-    for (int op = 0; op < 5; ++op) (void)ngc_conv_variant(&d, op);
+    for (int op = 0; op < 6; ++op) (void)ngc_conv_variant(&d, op);
     (void)ngc_data_elems(&d, 0); (void)ngc_data_elems(&d, 1);
     for (int l = -1; l < 4; ++l) (void)ngc_filter_elems(&d, l);
-    int rc[9];
+    int rc[10];
+    rc[9] = ngc_conv_bwd_data_filters(&d, P, P, P, P, (float *)P, P, BIG, 0);
     rc[0] = ngc_conv_fwd(&d, P, P, (const float *)P, P, P, BIG, 0);
     rc[1] = ngc_conv_bwd_data(&d, P, P, P, P, BIG, 0);
     rc[2] = ngc_conv_bwd_data_relu(&d, P, P, P, P, P, BIG, 0);
@@ -133,7 +134,7 @@ static void run2(ngc_conv_desc d)
     rc[6] = ngc_conv_fwd(&d, P, P, NULL, P, NULL, 0, 0);         /* no bias, no workspace: an error or not needed */
     rc[7] = ngc_conv_bwd_filters(&d, P, P, (float *)P, P, 16, 0);
     rc[8] = ngc_filter_convert(&d, P, P, d.w_layout, 0);
-    for (int i = 0; i < 9; ++i) { ++calls; ok += rc[i] == NGC_OK; (void)ngc_status_string(rc[i]); }
+    for (int i = 0; i < 10; ++i) { ++calls; ok += rc[i] == NGC_OK; (void)ngc_status_string(rc[i]); }
 }
 
 static void run3(ngc_conv3d_desc d)
