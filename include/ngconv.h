@@ -198,6 +198,11 @@ size_t ngc_static_scratch_bytes(void);
 int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w,
                               void *dx, float *dw, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The same with the backprop of the ReLU that produced the node's data input compounded into the dx store, as in
+ * ngc_conv_bwd_data_relu with x_in = x: dx[i] = x[i] > 0 ? dx[i] : +0 (dw is unchanged: it uses x as it is). */
+int ngc_conv_bwd_data_filters_relu(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w,
+                                   void *dx, float *dw, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Data layout conversion (Abstract / Sec. 2: data layout abstraction): copies bit patterns
  * between NGC_NCHW and NGC_NCHW16C for an [n,c,h,w] tensor of `dtype`; tail lanes of a blocked
  * destination are written as +0.  src_layout == dst_layout is a plain copy.  Bit exact. */

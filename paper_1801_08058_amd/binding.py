@@ -24,7 +24,7 @@ NGC_EPI_NONE, NGC_EPI_BIAS, NGC_EPI_RELU = 0, 1, 2
 NGC_OP_FWD, NGC_OP_BWD_DATA, NGC_OP_BWD_FILTERS, NGC_OP_BIAS_GRAD, NGC_OP_BWD_DATA_DB, NGC_OP_BWD_DATA_FILTERS = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("ngc_conv_out_shape", "ngc_conv_workspace_bytes", "ngc_conv_fwd", "ngc_conv_bwd_data",
-           "ngc_conv_bwd_data_relu", "ngc_conv_bwd_data_relu_db", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_conv_bwd_data_filters", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
+           "ngc_conv_bwd_data_relu", "ngc_conv_bwd_data_relu_db", "ngc_bias_grad", "ngc_softmax", "ngc_softmax_bwd", "ngc_softmax_variant", "ngc_conv_bwd_filters", "ngc_conv_bwd_data_filters", "ngc_conv_bwd_data_filters_relu", "ngc_layout_convert", "ngc_filter_convert", "ngc_data_elems",
            "ngc_filter_elems", "ngc_conv_variant", "ngc_status_string",
            "ngc_conv3d_out_shape", "ngc_conv3d_workspace_bytes", "ngc_conv3d_fwd", "ngc_conv3d_bwd_data",
            "ngc_conv3d_bwd_filters", "ngc_conv3d_filter_convert", "ngc_conv3d_filter_elems", "ngc_conv3d_data_elems",
@@ -97,8 +97,9 @@ def _load() -> ctypes.CDLL:
     lib.ngc_softmax_variant.restype = ctypes.c_char_p
     lib.ngc_conv_bwd_filters.argtypes = [D, vp, vp, vp, vp, sz, vp]
     lib.ngc_conv_bwd_filters.restype = ctypes.c_int
-    lib.ngc_conv_bwd_data_filters.argtypes = [D, vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.ngc_conv_bwd_data_filters.restype = ctypes.c_int
+    for f in (lib.ngc_conv_bwd_data_filters, lib.ngc_conv_bwd_data_filters_relu):
+        f.argtypes = [D, vp, vp, vp, vp, vp, vp, sz, vp]
+        f.restype = ctypes.c_int
     lib.ngc_conv_bwd_filters_noalloc.argtypes = [D, vp, vp, vp, vp]
     lib.ngc_conv_bwd_filters_noalloc.restype = ctypes.c_int
     lib.ngc_reload_switches.argtypes = []
@@ -256,6 +257,11 @@ def ngc_conv_bwd_filters(desc, x, dy, dw, ws=None, stream=None, check: bool = Tr
 def ngc_conv_bwd_data_filters(desc, x, dy, w, dx, dw, ws=None, stream=None, check: bool = True) -> int:
     return _check(_lib.ngc_conv_bwd_data_filters(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(w), _ptr(dx), _ptr(dw), _ptr(ws),
                                                  _nbytes(ws), _stream(stream)), "ngc_conv_bwd_data_filters", check)
+
+
+def ngc_conv_bwd_data_filters_relu(desc, x, dy, w, dx, dw, ws=None, stream=None, check: bool = True) -> int:
+    return _check(_lib.ngc_conv_bwd_data_filters_relu(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(w), _ptr(dx), _ptr(dw), _ptr(ws),
+                                                      _nbytes(ws), _stream(stream)), "ngc_conv_bwd_data_filters_relu", check)
 
 
 def ngc_conv_bwd_filters_noalloc(desc, x, dy, dw, stream=None, check: bool = True) -> int:

@@ -1776,8 +1776,8 @@ const char *ngc_softmax_variant(int32_t dtype, int32_t cols, int32_t bwd)
     return v == 0 ? "softmax_rows_block" : v > 256 ? "softmax_rows_wg" : "softmax_rows_wave";
 }
 
-int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w, void *dx, float *dw,
-                              void *ws, size_t ws_bytes, void *hip_stream)
+static int bwd_data_filters_core(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w, void *dx, float *dw,
+                                 void *ws, size_t ws_bytes, void *hip_stream, int relu_mask)
 {
     int P, Q;
     const int vs = validate(desc, &P, &Q);
@@ -1793,7 +1793,20 @@ int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const vo
     fp.dx = static_cast<uint16_t *>(dx);
     fp.partial = static_cast<float *>(ws);
     fp.dw = dw;
+    fp.relu_mask = relu_mask;
     return launch_status(launch_bwd1x1_fused(fp, static_cast<hipStream_t>(hip_stream)));
+}
+
+int ngc_conv_bwd_data_filters(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w, void *dx, float *dw,
+                              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return bwd_data_filters_core(desc, x, dy, w, dx, dw, ws, ws_bytes, hip_stream, 0);
+}
+
+int ngc_conv_bwd_data_filters_relu(const ngc_conv_desc *desc, const void *x, const void *dy, const void *w, void *dx, float *dw,
+                                   void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return bwd_data_filters_core(desc, x, dy, w, dx, dw, ws, ws_bytes, hip_stream, 1);
 }
 
 int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *dy, float *dw, void *ws,

@@ -17,6 +17,8 @@
 // 4 (or 2) blocks of c as 16x16 tiles that live in registers for the whole kernel; operands come
 // through the LDS transpose load (8 positions per lane).  Partial sums of dw go to the workspace as
 // [part][K][C] fp32; bwd1x1_fused_reduce adds the parts in index order (deterministic).
+// p.relu_mask: dx is masked with x > 0 (the backprop of the ReLU that produced the node's data input, compounded
+// into the store: x is in LDS anyway).
 #include "common.h"
 
 namespace ngc {
@@ -176,8 +178,17 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
         // d1 is the next channel block at the same position, or (WIDE) the same block 16 positions on
         {
             typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-            const u32x2 v0 = {pack_bf16x2_hw(d0[0], d0[1]), pack_bf16x2_hw(d0[2], d0[3])};
-            const u32x2 v1 = {pack_bf16x2_hw(d1[0], d1[1]), pack_bf16x2_hw(d1[2], d1[3])};
+            u32x2 v0 = {pack_bf16x2_hw(d0[0], d0[1]), pack_bf16x2_hw(d0[2], d0[3])};
+            u32x2 v1 = {pack_bf16x2_hw(d1[0], d1[1]), pack_bf16x2_hw(d1[2], d1[3])};
+            if (p.relu_mask) {
+                // ReLU backprop of the node's data input: x sits in the stage buffer, the same 4 channels of the same
+                // position are 8 bytes of its plane
+                const unsigned char *xm = xs + cblk0 * BF_PLANE + (pblk0 * 16 + L) * 32 + grp * 8;
+                const u32x2 m0 = *reinterpret_cast<const u32x2 *>(xm);
+                const u32x2 m1 = *reinterpret_cast<const u32x2 *>(xm + (WIDE ? 16 * 32 : BF_PLANE));
+                v0[0] = relu_keep2(v0[0], m0[0]); v0[1] = relu_keep2(v0[1], m0[1]);
+                v1[0] = relu_keep2(v1[0], m1[0]); v1[1] = relu_keep2(v1[1], m1[1]);
+            }
             const uint32_t m = (uint32_t)((s_begin + s) * BF_SP + pblk0 * 16 + L);
             const bool in = m < p.M;
             const uint32_t n = fd_div(in ? m : 0, p.div_hw);

@@ -427,6 +427,7 @@ struct Bwd1x1FusedParams {
     uint32_t M;                // N * HW positions
     int32_t nstages;           // stages of 64 positions
     int32_t stages_per_part, nparts;
+    int32_t relu_mask;         // dx = (x > 0) ? dx : 0
     uint32_t x_bytes, dy_bytes;
     FastDiv div_hw;
 };

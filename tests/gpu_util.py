@@ -162,7 +162,7 @@ class Run:
         self.last_desc, self.last_raw = d, dx
         return data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w))
 
-    def bwd_data_filters(self, x, dy, w):
+    def bwd_data_filters(self, x, dy, w, relu=False):
         """Both derivative ops of the node in one call (blocked tensors, filters in the backprop-data layout):
         (dx, dw) as fp64, and the raw device tensors in self.last_raw."""
         a = self.a
@@ -173,7 +173,7 @@ class Run:
         dx = out_tensor(d, 0, self.dtype)
         dw = torch.full((a.k * a.c * a.r * a.s,), float("nan"), dtype=torch.float32, device="cuda")
         ws = workspace(d, ng.NGC_OP_BWD_DATA_FILTERS)
-        ng.ngc_conv_bwd_data_filters(d, xd, dyd, wd, dx, dw, ws, stream())
+        (ng.ngc_conv_bwd_data_filters_relu if relu else ng.ngc_conv_bwd_data_filters)(d, xd, dyd, wd, dx, dw, ws, stream())
         torch.cuda.synchronize()
         self.last_desc, self.last_raw = d, (dx, dw)
         return (data_from_device(dx, self.dtype, self.xl, (a.n, a.c, a.h, a.w)),

@@ -44,6 +44,12 @@ def test_fused_backward_matches_the_oracle(case):
     assert e <= bound("bf16", "act"), f"dx err {e}"
     e = oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy))
     assert e <= bound("bf16", "dw"), f"dw err {e}"
+    # the ReLU backprop of the node's input compounded into the store: the same dx where x > 0, +0 elsewhere; dw unchanged
+    raw_dw = run.last_raw[1].clone()
+    dxr, dwr = run.bwd_data_filters(x, dy, w, relu=True)
+    keep = x > 0
+    assert np.array_equal(dxr[keep], dx[keep]) and not dxr[~keep].any() and not np.signbit(dxr[~keep]).any()
+    assert torch.equal(raw_dw.view(torch.int32), run.last_raw[1].view(torch.int32))
 
 
 def test_fused_backward_is_run_to_run_identical_and_agrees_with_the_separate_ops():
