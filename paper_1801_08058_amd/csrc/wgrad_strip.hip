@@ -399,26 +399,32 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
 }
 
 // dw[k][c][tap] = sum over workgroup partials (index order) of partial[part][tile][cq][kb][tap][lane][v].
-// 256 threads = 32 float4 outputs x 8 interleaved partial streams, joined in a fixed order.
+// 256 threads = 256 / SL float4 outputs x SL interleaved partial streams (two chains each), joined in a fixed order.
+// SL = 16 when there are many parts (few (k, c) tiles: more loads in flight per output), 8 otherwise.
+template <int SL>
 __global__ __launch_bounds__(256) void wgrad_strip_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
                                                          int nparts, int K, int C, int ctiles, int ncq)
 {
-    __shared__ f32x4 sm[8][32];
+    constexpr int NO = 256 / SL;
+    __shared__ f32x4 sm[SL][NO];
     const size_t per4 = (size_t)WS_NT * K * C / 4;          // float4 elements of one partial
-    const int o = threadIdx.x & 31;
-    const int sl = threadIdx.x >> 5;
-    const size_t i = (size_t)blockIdx.x * 32 + o;           // per4 is a multiple of 32
+    const int o = threadIdx.x % NO;
+    const int sl = threadIdx.x / NO;
+    const size_t i = (size_t)blockIdx.x * NO + o;           // per4 is a multiple of 32
     f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
     int sp = sl;
-    for (; sp + 8 < nparts; sp += 16) {
+    for (; sp + SL < nparts; sp += 2 * SL) {
         t0 += partial[(size_t)sp * per4 + i];
-        t1 += partial[(size_t)(sp + 8) * per4 + i];
+        t1 += partial[(size_t)(sp + SL) * per4 + i];
     }
     if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
     sm[sl][o] = t0 + t1;
     __syncthreads();
     if (sl == 0) {
-        const f32x4 r = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+        f32x4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = SL == 16 ? sm[2 * j][o] + sm[(2 * j + 1) % SL][o] : sm[j][o];
+        const f32x4 r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
         // decode register order: i = (((tile*ncq + cq)*4 + kb)*9 + t)*64 + lane
         const int lane = (int)(i & 63);
         size_t u = i >> 6;
@@ -473,8 +479,12 @@ hipError_t launch_wgrad_strip(const WgradStripParams &p, size_t lds_bytes, hipSt
     }
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)WS_NT * p.K * p.C / 4;
-    NGC_LAUNCH(wgrad_strip_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
-                       reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
+    if (p.nparts >= 16)
+        NGC_LAUNCH(wgrad_strip_reduce<16>, dim3((unsigned)(per4 / 16)), dim3(256), 0, st,
+                   reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
+    else
+        NGC_LAUNCH(wgrad_strip_reduce<8>, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+                   reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, p.ctiles, p.ncq);
     return ngc::launch_result();
 }
 
