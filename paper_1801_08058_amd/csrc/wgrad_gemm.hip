@@ -273,25 +273,32 @@ __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 // dw[k][c][tap] = sum over parts (index order).  Element i (float4) of a part:
 // i = ((((tap * tiles + tile) * WK*WC + sub) * 4 + kb) * 4 + cq) * 64 + lane; tiles cover K and C rounded up
 // to the tile size, elements outside [K] x [C] are dropped here.
+// 256 threads = 256 / SL outputs x SL interleaved part slices (SL = 16 when there are 16 parts or more: more loads
+// in flight per output; 8 otherwise), joined in a fixed tree.
+template <int SL>
 __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict__ partial, float *__restrict__ dw,
                                                         int nparts, int K, int C, int RS, int ktiles, int ctiles, int WK, int WC)
 {
-    __shared__ f32x4 sm[8][32];
+    constexpr int NO = 256 / SL;
+    __shared__ f32x4 sm[SL][NO];
     const size_t per4 = (size_t)RS * ktiles * ctiles * WK * WC * (64 * 64 / 4);
-    const int o = threadIdx.x & 31;
-    const int sl = threadIdx.x >> 5;
-    const size_t i = (size_t)blockIdx.x * 32 + o;
+    const int o = threadIdx.x % NO;
+    const int sl = threadIdx.x / NO;
+    const size_t i = (size_t)blockIdx.x * NO + o;
     f32x4 t0 = {0.f, 0.f, 0.f, 0.f}, t1 = t0;
     int sp = sl;
-    for (; sp + 8 < nparts; sp += 16) {
+    for (; sp + SL < nparts; sp += 2 * SL) {
         t0 += partial[(size_t)sp * per4 + i];
-        t1 += partial[(size_t)(sp + 8) * per4 + i];
+        t1 += partial[(size_t)(sp + SL) * per4 + i];
     }
     if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
     sm[sl][o] = t0 + t1;
     __syncthreads();
     if (sl == 0) {
-        const f32x4 r = ((sm[0][o] + sm[1][o]) + (sm[2][o] + sm[3][o])) + ((sm[4][o] + sm[5][o]) + (sm[6][o] + sm[7][o]));
+        f32x4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = SL == 16 ? sm[2 * j][o] + sm[(2 * j + 1) % SL][o] : sm[j][o];
+        const f32x4 r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
         const int lane = (int)(i & 63);
         size_t u = i >> 6;
         const int cq = (int)(u & 3); u >>= 2;
@@ -364,8 +371,12 @@ hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
     if (e != hipSuccess) return e;
     const int taps = wgrad_gemm_taps(p);
     const size_t per4 = (size_t)taps * p.ktiles * p.ctiles * p.wk * p.wc * (64 * 64 / 4);
-    NGC_LAUNCH(wgrad_gemm_reduce, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
-               reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
+    if (p.nparts >= 16)
+        NGC_LAUNCH(wgrad_gemm_reduce<16>, dim3((unsigned)(per4 / 16)), dim3(256), 0, st,
+                   reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
+    else
+        NGC_LAUNCH(wgrad_gemm_reduce<8>, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+                   reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
     return ngc::launch_result();
 }
 
