@@ -47,7 +47,10 @@
  * Every op accepts every combination of data layouts; which combinations run on the MFMA kernels
  * (bf16) and which on the slow direct kernels is a property of the build: blocked x and y for all
  * shapes with C and K multiples of 16, NCHW x of the 3-channel stem, and NCHW x and / or y of 1x1
- * layers with stride 1, no padding and H*W a multiple of 8 (ngc_conv_variant names the choice).
+ * layers with stride 1, no padding and H*W a multiple of 8 are read and written in place; any other
+ * bf16 node with NCHW tensors whose blocked form has an MFMA kernel runs on blocked copies that the
+ * library keeps at the front of the workspace (ngc_conv_workspace_bytes counts them; the variant is
+ * then named "staged:<kernel>").  ngc_conv_variant names the choice.
  *
  * Element layouts
  *   NGC_NCHW      x[n][c][h][w]

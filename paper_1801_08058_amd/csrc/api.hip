@@ -112,6 +112,8 @@ int validate(const ngc_conv_desc *d, int *P, int *Q)
     return NGC_OK;
 }
 
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // Forward and backprop-data treat the images of a batch independently.  The MFMA kernels address an operand with
@@ -142,7 +144,7 @@ ngc_conv_desc with_batch(const ngc_conv_desc *d, int n)
     return t;
 }
 
-enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1, V_ROWS };
+enum Variant { V_INVALID, V_UNSUPPORTED, V_DIRECT, V_IGEMM_128, V_IGEMM_64, V_WGRAD_64, V_STRIP, V_WGRAD_STRIP, V_STEM_FWD, V_WGRAD_STEM, V_STEM_BWD, V_WGRAD_GEMM, V_GEMM1X1, V_ROWS, V_STAGED };
 
 constexpr int NUM_CUS = 256;                      // MI355X
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -1024,7 +1026,7 @@ bool blocked_bf16(const ngc_conv_desc *d)
     return d->dtype == NGC_BF16 && d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
 }
 
-Variant pick_uncached(const ngc_conv_desc *d, int op)
+Variant pick_base(const ngc_conv_desc *d, int op)
 {
     int P, Q;
     if (validate(d, &P, &Q) != NGC_OK) return V_INVALID;
@@ -1059,6 +1061,63 @@ Variant pick_uncached(const ngc_conv_desc *d, int op)
     return V_INVALID;
 }
 
+// ---- NCHW tensors that no MFMA kernel reads or writes in place ----------------------------------------------
+// The layout a kernel works in is the backend's choice, and the conversion at a node's boundary is the backend's job
+// (Sec. 2, Sec. 4).  A bf16 node whose NCHW tensors would otherwise leave only the one-thread-per-output kernels
+// (several taps, strides, images whose H*W is not a multiple of 8) runs on blocked copies in the workspace: the inputs
+// are converted, the node runs with blocked tensors, the result is converted back.  Only the tensors that have to
+// change are copied (the low-channel stem kernels read an NCHW x themselves).
+bool fast_variant(Variant v) { return v != V_INVALID && v != V_UNSUPPORTED && v != V_DIRECT && v != V_STAGED; }
+
+struct StagedPlan {
+    ngc_conv_desc inner;       // the node as it runs
+    bool cx, cy;               // x / y have a blocked copy
+    size_t x_off, y_off, m_off;    // of the copies in the workspace (m: the ReLU mask of backprop-data, x-shaped)
+    size_t inner_off;          // the inner node's own workspace starts here
+};
+
+bool staged_plan(const ngc_conv_desc *d, int op, StagedPlan *out)
+{
+    if (d->dtype != NGC_BF16) return false;
+    if (env_switch(SW_STAGED) && atoi(env_switch(SW_STAGED)) == 0) return false;    // tests / benchmarks only
+    const bool xn = d->x_layout == NGC_NCHW, yn = d->y_layout == NGC_NCHW;
+    for (int cand = 0; cand < 3; ++cand) {
+        const bool cx = cand != 0, cy = cand != 1;
+        if ((cx && !xn) || (cy && !yn)) continue;
+        StagedPlan sp;
+        sp.inner = *d;
+        if (cx) sp.inner.x_layout = NGC_NCHW16C;
+        if (cy) sp.inner.y_layout = NGC_NCHW16C;
+        int P, Q;
+        if (validate(&sp.inner, &P, &Q) != NGC_OK) continue;
+        // operands of 2 GiB or more run as groups of images: what counts is the kernel of a group
+        const ngc_conv_desc g = with_batch(&sp.inner, batch_slices(&sp.inner, P, Q).images);
+        if (!fast_variant(pick_base(&g, op))) continue;
+        sp.cx = cx;
+        sp.cy = cy;
+        size_t off = 0;
+        const size_t xb = round256(phys(NGC_NCHW16C, d->n, d->c, d->h, d->w) * 2);
+        const size_t yb = round256(phys(NGC_NCHW16C, d->n, d->k, P, Q) * 2);
+        sp.x_off = off;
+        if (cx) off += xb;
+        sp.y_off = off;
+        if (cy) off += yb;
+        sp.m_off = off;
+        if (cx && op == NGC_OP_BWD_DATA) off += xb;
+        sp.inner_off = off;
+        if (out) *out = sp;
+        return true;
+    }
+    return false;
+}
+
+Variant pick_uncached(const ngc_conv_desc *d, int op)
+{
+    const Variant v = pick_base(d, op);
+    if ((v == V_DIRECT || v == V_UNSUPPORTED) && staged_plan(d, op, nullptr)) return V_STAGED;
+    return v;
+}
+
 Variant pick(const ngc_conv_desc *d, int op)
 {
     static thread_local PlanCache<Variant> cache;
@@ -1075,8 +1134,6 @@ size_t filter_elems(const ngc_conv_desc *d, int layout)
     if (layout == NGC_BLOCKED_BWD) return (size_t)d->r * d->s * ((d->k + 15) / 16) * d->c * 16;
     return 0;
 }
-
-size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 // split of the N*P*Q reduction of backprop-filters over workgroups
 void wgrad_split(const ngc_conv_desc *d, int P, int Q, uint32_t *chunk, int *splits)
@@ -1143,6 +1200,12 @@ size_t workspace_bytes(const ngc_conv_desc *d, int op, Variant v, int P, int Q);
 
 size_t workspace_bytes_uncached(const ngc_conv_desc *d, int op, Variant v, int P, int Q)
 {
+    if (v == V_STAGED) {
+        // the blocked copies, then whatever the node needs when it runs on them
+        StagedPlan sp;
+        if (!staged_plan(d, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op, &sp)) return 0;
+        return sp.inner_off + ngc_conv_workspace_bytes(&sp.inner, op);
+    }
     if (op == NGC_OP_BWD_DATA_DB) {
         // backprop-data part, then the partial channel sums of dx: rows of the fused launches, or the
         // partials of a second pass over dx where the kernel does not produce them
@@ -1353,6 +1416,13 @@ const char *ngc_conv_variant(const ngc_conv_desc *desc, int op)
     case V_STEM_BWD: return "stem_bwd_strip_bf16";
     case V_WGRAD_GEMM: return "wgrad_gemm_bf16";
     case V_GEMM1X1: return "gemm1x1_bf16";
+    case V_STAGED: {                                         // blocked copies in the workspace: the kernel that runs on them
+        static thread_local char name[64];
+        StagedPlan sp;
+        if (!staged_plan(desc, op == NGC_OP_BWD_DATA_DB ? NGC_OP_BWD_DATA : op, &sp)) return "invalid";
+        snprintf(name, sizeof(name), "staged:%s", ngc_conv_variant(&sp.inner, op));
+        return name;
+    }
     default: return "invalid";
     }
 }
@@ -1393,6 +1463,23 @@ int ngc_conv_fwd(const ngc_conv_desc *desc, const void *x, const void *w, const 
     const Variant v = pick(desc, NGC_OP_FWD);
     if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (v == V_STAGED) {
+        StagedPlan sp;
+        if (!staged_plan(desc, NGC_OP_FWD, &sp)) return NGC_UNSUPPORTED;
+        if (!ws || ws_bytes < workspace_bytes(desc, NGC_OP_FWD, v, P, Q)) return NGC_WORKSPACE_TOO_SMALL;
+        unsigned char *base = static_cast<unsigned char *>(ws);
+        const void *xin = x;
+        void *yout = y;
+        if (sp.cx) {
+            const hipError_t e = launch_layout_convert(2, desc->n, desc->c, desc->h, desc->w, x, NGC_NCHW, base + sp.x_off, NGC_NCHW16C, st);
+            if (e != hipSuccess) return launch_status(e);
+            xin = base + sp.x_off;
+        }
+        if (sp.cy) yout = base + sp.y_off;
+        const int rc = ngc_conv_fwd(&sp.inner, xin, w, bias, yout, base + sp.inner_off, ws_bytes - sp.inner_off, hip_stream);
+        if (rc != NGC_OK || !sp.cy) return rc;
+        return launch_status(launch_layout_convert(2, desc->n, desc->k, P, Q, yout, NGC_NCHW16C, y, NGC_NCHW, st));
+    }
     if (v == V_DIRECT)
         return launch_status(launch_direct_fwd(*desc, P, Q, x, w, (desc->epilogue & NGC_EPI_BIAS) ? bias : nullptr, y, st));
     if (v == V_STEM_FWD) {
@@ -1496,7 +1583,7 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
     if (!dy || !w || !dx) return NGC_BAD_ARG;
     if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws) || !aligned16(mask)) return NGC_BAD_ARG;
     Variant v = pick(desc, NGC_OP_BWD_DATA);
-    if (v == V_UNSUPPORTED) return NGC_UNSUPPORTED;
+    if (v == V_UNSUPPORTED || v == V_STAGED) return NGC_UNSUPPORTED;    // blocked copies are the caller's part
     if (v == V_ROWS && fuse) v = V_STRIP;                  // the channel sums of dx come from the strip kernel
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (v == V_DIRECT) return launch_status(launch_direct_bwd_data(*desc, P, Q, dy, w, mask, dx, st));
@@ -1678,6 +1765,31 @@ int bwd_data_impl(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         return launch_status(launch_bias_grad(t, desc->h, desc->w, dx, db, partial, bias_grad_parts(t, desc->h, desc->w),
                                               static_cast<hipStream_t>(hip_stream)));
     }
+    if (pick(desc, NGC_OP_BWD_DATA) == V_STAGED) {
+        if (!dy || !w || !dx) return NGC_BAD_ARG;
+        if (!aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws) || !aligned16(mask) || !aligned16(db)) return NGC_BAD_ARG;
+        StagedPlan sp;
+        if (!staged_plan(desc, NGC_OP_BWD_DATA, &sp)) return NGC_UNSUPPORTED;
+        if (!ws || ws_bytes < workspace_bytes(desc, db ? NGC_OP_BWD_DATA_DB : NGC_OP_BWD_DATA, V_STAGED, P, Q)) return NGC_WORKSPACE_TOO_SMALL;
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        unsigned char *base = static_cast<unsigned char *>(ws);
+        const void *dyin = dy, *min = mask;
+        void *dxout = dx;
+        if (sp.cy) {
+            const hipError_t e = launch_layout_convert(2, desc->n, desc->k, P, Q, dy, NGC_NCHW, base + sp.y_off, NGC_NCHW16C, st);
+            if (e != hipSuccess) return launch_status(e);
+            dyin = base + sp.y_off;
+        }
+        if (sp.cx && mask) {
+            const hipError_t e = launch_layout_convert(2, desc->n, desc->c, desc->h, desc->w, mask, NGC_NCHW, base + sp.m_off, NGC_NCHW16C, st);
+            if (e != hipSuccess) return launch_status(e);
+            min = base + sp.m_off;
+        }
+        if (sp.cx) dxout = base + sp.x_off;
+        const int rc = bwd_data_impl(&sp.inner, dyin, w, min, dxout, db, base + sp.inner_off, ws_bytes - sp.inner_off, hip_stream);
+        if (rc != NGC_OK || !sp.cx) return rc;
+        return launch_status(launch_layout_convert(2, desc->n, desc->c, desc->h, desc->w, dxout, NGC_NCHW16C, dx, NGC_NCHW, st));
+    }
     if (!db) return bwd_data_core(desc, dy, w, mask, dx, ws, ws_bytes, hip_stream, nullptr);
     if (!aligned16(db) || !aligned16(ws)) return NGC_BAD_ARG;
     if ((size_t)desc->n * desc->h * desc->w >= 0xFFFF0000ull) return NGC_BAD_SHAPE;
@@ -1837,6 +1949,24 @@ int ngc_conv_bwd_filters(const ngc_conv_desc *desc, const void *x, const void *d
     }
     const Variant v = pick(desc, NGC_OP_BWD_FILTERS);
     if (v == V_DIRECT) return launch_status(launch_direct_bwd_filters(*desc, P, Q, x, dy, dw, st));
+    if (v == V_STAGED) {
+        StagedPlan sp;
+        if (!staged_plan(desc, NGC_OP_BWD_FILTERS, &sp)) return NGC_UNSUPPORTED;
+        if (!ws || ws_bytes < workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q)) return NGC_WORKSPACE_TOO_SMALL;
+        unsigned char *base = static_cast<unsigned char *>(ws);
+        const void *xin = x, *dyin = dy;
+        if (sp.cx) {
+            const hipError_t e = launch_layout_convert(2, desc->n, desc->c, desc->h, desc->w, x, NGC_NCHW, base + sp.x_off, NGC_NCHW16C, st);
+            if (e != hipSuccess) return launch_status(e);
+            xin = base + sp.x_off;
+        }
+        if (sp.cy) {
+            const hipError_t e = launch_layout_convert(2, desc->n, desc->k, P, Q, dy, NGC_NCHW, base + sp.y_off, NGC_NCHW16C, st);
+            if (e != hipSuccess) return launch_status(e);
+            dyin = base + sp.y_off;
+        }
+        return ngc_conv_bwd_filters(&sp.inner, xin, dyin, dw, base + sp.inner_off, ws_bytes - sp.inner_off, hip_stream);
+    }
 
     const size_t need = workspace_bytes(desc, NGC_OP_BWD_FILTERS, v, P, Q);
     if (!ws || ws_bytes < need) return NGC_WORKSPACE_TOO_SMALL;

@@ -172,11 +172,15 @@ def test_kernel_selection_and_sizes():
         assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_BWD, **kw), ng.NGC_OP_BWD_DATA) == "gemm1x1_bf16"
         assert ng.ngc_conv_variant(_good(**kw), ng.NGC_OP_BWD_FILTERS) == "wgrad_gemm_bf16"
         kw7 = dict(kw, h=7, w=7)                                              # 49 positions per image
-        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_FWD) == "direct"
-        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_BWD_FILTERS) == "direct"
-        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **kw7), ng.NGC_OP_FWD) == "unsupported"
+        # anything else with NCHW tensors runs on blocked copies in the workspace, with the kernel of the blocked node
+        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_FWD) == "staged:gemm1x1_bf16"
+        assert ng.ngc_conv_variant(_good(**kw7), ng.NGC_OP_BWD_FILTERS) == "staged:wgrad_gemm_bf16"
+        assert ng.ngc_conv_variant(_good(w_layout=ng.NGC_BLOCKED_FWD, **kw7), ng.NGC_OP_FWD) == "staged:gemm1x1_bf16"
         kws = dict(kw, stride=(2, 2))
-        assert ng.ngc_conv_variant(_good(**kws), ng.NGC_OP_BWD_DATA) == "direct"
+        assert ng.ngc_conv_variant(_good(**kws), ng.NGC_OP_BWD_DATA) == "staged:gemm1x1_bf16"
+        blocked = ng.ngc_conv_workspace_bytes(_good(**dict(kw7, x_layout=ng.NGC_NCHW16C, y_layout=ng.NGC_NCHW16C)), ng.NGC_OP_FWD)
+        copies = (64 * 256 * 49 * 2 if xl == ng.NGC_NCHW else 0) + (64 * 64 * 49 * 2 if yl == ng.NGC_NCHW else 0)
+        assert ng.ngc_conv_workspace_bytes(_good(**kw7), ng.NGC_OP_FWD) == blocked + copies
     # channel counts: multiples of 16 run on the MFMA kernels (partial last tiles), anything else on the direct kernels
     for c, k in ((48, 96), (80, 16), (16, 208)):
         t3 = dict(n=8, c=c, k=k, h=28, w=28)
@@ -190,8 +194,16 @@ def test_kernel_selection_and_sizes():
         assert ws >= ((k + 63) // 64) * ((c + 63) // 64) * 64 * 64 * 4      # partials cover whole tiles
     odd = dict(n=8, c=40, k=72, h=28, w=28)
     assert [ng.ngc_conv_variant(_good(**odd), o) for o in range(3)] == ["direct"] * 3
-    three = _good(n=8, h=56, w=56, x_layout=ng.NGC_NCHW)                      # 3x3 with NCHW x: not propagated
-    assert [ng.ngc_conv_variant(three, o) for o in range(3)] == ["direct"] * 3
+    three = _good(n=8, h=56, w=56, x_layout=ng.NGC_NCHW)                      # 3x3 with NCHW x: a blocked copy of x
+    assert [ng.ngc_conv_variant(three, o) for o in range(3)] == ["staged:strip_bf16", "staged:strip_bf16", "staged:wgrad_strip_bf16"]
+    xcopy = 8 * 64 * 56 * 56 * 2
+    three_b = _good(n=8, h=56, w=56)
+    assert ng.ngc_conv_workspace_bytes(three, ng.NGC_OP_BWD_DATA) == 2 * xcopy + ng.ngc_conv_workspace_bytes(three_b, ng.NGC_OP_BWD_DATA)
+    assert ng.ngc_conv_workspace_bytes(three, ng.NGC_OP_BWD_FILTERS) == xcopy + ng.ngc_conv_workspace_bytes(three_b, ng.NGC_OP_BWD_FILTERS)
+    # the low-channel first layer with an NCHW result: only y gets a copy, the kernel still reads the NCHW x itself
+    stem_n = ng.make_desc(8, 3, 224, 224, 64, 7, 7, (2, 2), (1, 1), (3, 3), (3, 3), x_layout=ng.NGC_NCHW, y_layout=ng.NGC_NCHW)
+    assert ng.ngc_conv_variant(stem_n, ng.NGC_OP_FWD) == "staged:stem_fwd_bf16"
+    assert ng.ngc_conv_workspace_bytes(stem_n, ng.NGC_OP_FWD) == 8 * 64 * 112 * 112 * 2
     assert ng.ngc_data_elems(d, 0) == 64 * 64 * 56 * 56 and ng.ngc_data_elems(d, 1) == 64 * 64 * 56 * 56
     assert ng.ngc_filter_elems(d, ng.NGC_BLOCKED_FWD) == 9 * 4 * 64 * 16
     f32 = _good(dtype=ng.NGC_F32, x_layout=ng.NGC_NCHW, y_layout=ng.NGC_NCHW)

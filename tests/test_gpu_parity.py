@@ -413,11 +413,11 @@ def test_gemm1x1_reads_and_writes_nchw(case, xl, yl, pre, variant, monkeypatch):
     _check_all(a, "bf16", xl, yl, pre, 7300 + case, ("gemm1x1", "gemm1x1", "wgrad_gemm"))
 
 
-def test_nchw_1x1_outside_the_fast_path_takes_the_direct_kernel():
+def test_nchw_1x1_outside_the_in_place_path_runs_on_blocked_copies():
     a = Attrs(2, 64, 7, 7, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0)       # 49 positions per image: not a multiple of 8
-    _check_all(a, "bf16", NCHW, BLK, False, 7400, ("direct", "direct", "direct"))
+    _check_all(a, "bf16", NCHW, BLK, False, 7400, ("staged:gemm1x1", "staged:gemm1x1", "staged:wgrad_gemm"))
     b = Attrs(2, 64, 8, 8, 64, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0)       # stride 2
-    _check_all(b, "bf16", BLK, NCHW, False, 7401, ("direct", "direct", "direct"))
+    _check_all(b, "bf16", BLK, NCHW, False, 7401, ("staged:gemm1x1", "staged:gemm1x1", "staged:"))
 
 
 @pytest.mark.parametrize("case", [0, 3, 4, 5])
