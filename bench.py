@@ -79,7 +79,8 @@ def parse():
                          "[64,256,56,56] bf16 tensor: 102.8 MB read + 102.8 MB written) so that HBM counters can be scaled")
     ap.add_argument("--settle", type=float, default=0.5,
                     help="seconds of untimed load (the workload's own steps) before the warm-up steps; 0 = none")
-    ap.add_argument("--layer", default=None, help="cfg7 only: time this one layer of the set (e.g. v_3x3x3_c64k128)")
+    ap.add_argument("--layer", default=None, help="cfg5 / cfg6 / cfg7: time this one layer of the set only "
+                    "(e.g. c256k1024hw14r1s1, v_3x3x3_c64k128); for profiles of one kernel")
     return ap.parse_args()
 
 
@@ -520,6 +521,11 @@ def main():
         return
     cfg = int(args.workload[3:])
     layers = synth_inputs.config_layers(cfg)
+    if args.layer is not None:
+        layers = [L for L in layers if L.name == args.layer]
+        if not layers:
+            print(f"bench.py: no layer {args.layer} in {args.workload}", file=sys.stderr)
+            sys.exit(2)
     sets = 1
     if args.cold:
         per_set = sum(2 * 2 * (L.n * L.c * L.h * L.w + L.n * L.k * L.p * L.q) for L in layers[:1])
@@ -629,6 +635,7 @@ def main():
                                    "per-axis strides) N=32 bf16, 8 layers x (fwd+bias+ReLU, bwd_data, bwd_filters)"}[cfg],
                    "layout": "nChw16c activations, blocked filters, fp32 dw", "cache": "cold" if args.cold else "warm",
                    "streams": 1,
+                   **({"layer": args.layer} if args.layer else {}),
                    **({"x_layout": "NCHW read / written by the ops themselves, no conversion pass"} if args.propagate_layout else {}),
                    **({"fused_backward": "bwd_data + bwd_filters of the 1x1 stride-1 layers as one call"} if args.fused_backward else {})},
         "value_basis": "nominal flop of the step / sum of the single-stream kernel medians (kernel_sum.us)",
