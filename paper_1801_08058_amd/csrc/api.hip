@@ -915,6 +915,12 @@ bool gemm1x1_plan_uncached(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1
         OP = a < d->h ? (d->h - a + sh - 1) / sh : 0;
         OQ = b < d->w ? (d->w - b + sw_ - 1) / sw_ : 0;
         z = sh > 1 || sw_ > 1;
+        // the lattice starts at pixel (0, 0) and its blocks of sh x sw pixels tile the image: the kernel writes the
+        // zeros of a block next to its one computed pixel, no fill pass
+        if (z && a == 0 && b == 0 && sh * sw_ <= 4 && !q.out_nchw && OP * sh >= d->h && OQ * sw_ >= d->w) {
+            q.zero_sib = 1;
+            z = false;
+        }
     }
     const size_t in_bytes = (size_t)d->n * Cin * q.Hin * q.Win * 2, wt_bytes = (size_t)Cin * Cout * 2;
     const size_t m = (size_t)d->n * OP * OQ;

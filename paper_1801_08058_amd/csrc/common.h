@@ -447,6 +447,7 @@ struct Gemm1x1Params {
     int32_t is_h, is_w, dh, dw;        // input pixel of lattice position (i,j): (i*is_h + dh, j*is_w + dw)
     int32_t os_h, os_w, oa_h, oa_w;    // output pixel: (i*os_h + oa_h, j*os_w + oa_w)
     int32_t relu;
+    int32_t zero_sib;          // also store zeros to the other pixels of the position's os_h x os_w block (oa = 0)
     uint32_t M;                // N * OP * OQ lattice positions
     uint32_t in_bytes, wt_bytes;
     FastDiv div_pq, div_q;

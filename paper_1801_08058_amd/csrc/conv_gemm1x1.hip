@@ -311,6 +311,15 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
                     *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    if (p.zero_sib) {
+                        // strided backprop-data whose one class of pixels starts at (0, 0): the pixels of the block
+                        // that no tap reaches are zero, written here instead of by a fill pass over the whole dx
+                        for (int zh = 0; zh < p.os_h; ++zh)
+                            for (int zw = 0; zw < p.os_w; ++zw)
+                                if ((zh | zw) != 0 && oh + zh < p.Hout && ow + zw < p.Wout)
+                                    *reinterpret_cast<uint4 *>(p.out + (blk + (size_t)(zh * p.Wout + zw)) * 16 + lg * 8) =
+                                        make_uint4(0, 0, 0, 0);
+                    }
                     if (DB) {                                            // the rounded, masked values as stored
                         const uint32_t w4[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll

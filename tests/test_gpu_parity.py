@@ -337,6 +337,27 @@ def test_channel_counts_not_multiples_of_64(case, pre):
     _check_all(a, "bf16", BLK, BLK, pre, 7500 + case, (fb, fb, "wgrad_gemm"))
 
 
+STRIDED_1X1_CASES = [
+    # 1x1 windows with strides: backprop-data computes one pixel per stride block and writes zeros to the rest
+    Attrs(2, 64, 7, 7, 64, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),        # odd image: the last block row / column is cut
+    Attrs(2, 32, 9, 12, 64, 1, 1, 2, 1, 1, 1, 0, 0, 0, 0),       # stride (2, 1)
+    Attrs(3, 64, 8, 9, 32, 1, 1, 1, 2, 1, 1, 0, 0, 0, 0),        # stride (1, 2), odd width
+    Attrs(2, 64, 10, 10, 64, 1, 1, 3, 3, 1, 1, 0, 0, 0, 0),      # 9 pixels per block: fill pass
+    Attrs(2, 64, 9, 9, 64, 1, 1, 2, 2, 1, 1, 1, 1, 1, 1),        # padding: the lattice starts at pixel (1, 1): fill pass
+    Attrs(1, 64, 3, 3, 64, 1, 1, 4, 4, 1, 1, 0, 0, 0, 0),        # stride beyond the image: one position
+    Attrs(4, 128, 28, 28, 256, 1, 1, 2, 2, 1, 1, 0, 0, 0, 0),    # several position tiles
+]
+
+
+@pytest.mark.parametrize("case", range(len(STRIDED_1X1_CASES)))
+@pytest.mark.parametrize("pre", [True, False])
+def test_strided_1x1_backprop_data_writes_every_pixel(case, pre):
+    """The output tensor starts as NaN bit patterns (out_tensor), so a pixel that neither the computed class nor the
+    zeros next to it (or the fill pass) reach fails the comparison; the ReLU-mask and channel-sum compounds run on the
+    same launches."""
+    _check_all(STRIDED_1X1_CASES[case], "bf16", BLK, BLK, pre, 7700 + case, ("gemm1x1", "gemm1x1", "wgrad"))
+
+
 @pytest.mark.parametrize("case", range(len(CHANNEL_TAIL_CASES)))
 def test_channel_tail_loads_never_look_behind_the_filter_tensor(case):
     """Filter rows past Cout and channel blocks past Cin of a partial tile / stage must read as zeros, not whatever
