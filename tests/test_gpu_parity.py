@@ -602,6 +602,21 @@ def test_stem_kernels_small(case, bh, monkeypatch):
     _check_all(a, "bf16", NCHW, BLK, False, 5000 + case, ("stem_fwd", "", ""))
 
 
+@pytest.mark.parametrize("tp", [1, 5, 11, 14, 16])
+def test_stem_forward_tile_heights(tp, monkeypatch):
+    """Output rows per workgroup of the low-channel forward kernel (the dispatcher picks 4..16 by the number of
+    workgroup rounds; forced here): ragged last tiles, tiles taller than the image part left, one row."""
+    monkeypatch.setenv("NGC_STEM_TP", str(tp))
+    for case in (0, 4):
+        a = STEM_CASES[case]
+        x, w, b, dy = _tensors(a, "bf16", 5200 + case)
+        run = Run(a, "bf16", NCHW, BLK, False)
+        y = run.fwd(x, w, bias=b, relu=True)
+        assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_FWD) == "stem_fwd_bf16"
+        e = oracle.max_normalised_error(y, oracle.conv_fwd(a, x, w, bias=b, relu=True))
+        assert e <= bound("bf16", "act"), f"tp {tp} case {case} err {e}"
+
+
 def test_stem_backprop_data_unstaged_store():
     """Width not a multiple of 8: the sub-pixel store cannot go through whole 16-byte row pieces."""
     a = Attrs(2, 3, 30, 44, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3)
