@@ -758,26 +758,49 @@ bool wgrad_stem_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStemPar
     if (dy_bytes >= ((size_t)1 << 31)) return false;
     WgradStemParams q;
     memset(&q, 0, sizeof(q));
-    int sr = 1;
-    while ((sr * Q) % 32 != 0) ++sr;                                    // <= 4 since Q % 8 == 0
+    const size_t x_bytes = (size_t)d->n * d->c * d->h * d->w * 2;
+    if (x_bytes >= ((size_t)1 << 31)) return false;
+    int sr0 = 1;
+    while ((sr0 * Q) % 32 != 0) ++sr0;                                  // <= 4 since Q % 8 == 0
     // positions per stage (NGC_WSTEM_POS, experiments): a stage costs a load latency whatever its size
     int stage_pos = 512;
     const char *fp = env_switch(SW_WSTEM_POS);
     if (fp && atoi(fp) >= 32 && atoi(fp) <= 1024) stage_pos = atoi(fp);
-    while (2 * sr * Q <= stage_pos && 2 * sr <= P) sr *= 2;
-    // the two stage buffers have to fit the LDS and the input rows 3 chunks per thread
-    while (sr > 1 && sr % 2 == 0 && ((sr / 2) * Q) % 32 == 0 &&
-           (2 * ((size_t)4 * ((sr * Q / 32) * 1024 + 128) + (size_t)d->c * (2 * sr + 5) * 2 * (d->w + 16) + 16) > LDS_LIMIT ||
-            d->c * (2 * sr + 5) * (d->w / 8) > 1536))
-        sr /= 2;
+    // LDS of a workgroup with `nbuf` stage buffers of sr dy rows (+ two staging areas for the raw input rows when
+    // there are three); 0 if the input rows of a stage need more than 3 pieces per thread
+    // LDS pitches of the input rows: a parity plane holds W + 16 bytes; with the plane pitch = 8 and the row pitch = 64
+    // (mod 256 bytes) the lanes of one operand read - two (c, r) rows, both planes, four position groups 16 bytes apart,
+    // two neighbouring dwords - hit 64 different banks (with W + 16 and twice that, plane and group offsets collide)
+    q.PL = (d->w + 16 - 8 + 255) / 256 * 256 + 8;
+    q.RPX = (2 * q.PL - 64 + 255) / 256 * 256 + 64;
+    const int rpx = q.RPX;
+    auto lds_need = [&](int sr, int nbuf) -> size_t {
+        const int rows_in = 2 * sr + 5;
+        const int xchunks = d->c * rows_in * (d->w / 8);
+        if (xchunks > 1536) return 0;
+        const size_t dyplane = (size_t)(sr * Q / 32) * 1024 + 128;
+        const size_t xbytes = (size_t)d->c * rows_in * rpx;
+        size_t lds = nbuf * (4 * dyplane + ((xbytes + 15) & ~(size_t)15));
+        if (nbuf == 3) lds += 2 * (size_t)((xchunks + 63) & ~63) * 16;
+        return lds < 98304 ? 98304 : lds;                               // final cross-wave tree
+    };
+    auto largest_sr = [&](int nbuf) {
+        if (lds_need(sr0, nbuf) == 0 || lds_need(sr0, nbuf) > LDS_LIMIT) return 0;
+        int sr = sr0;
+        while (2 * sr * Q <= stage_pos && 2 * sr <= P && lds_need(2 * sr, nbuf) != 0 && lds_need(2 * sr, nbuf) <= LDS_LIMIT) sr *= 2;
+        return sr;
+    };
+    // Three buffers (the loads of two stages in flight behind the one being multiplied) when they fit, else two.
+    // NGC_WSTEM_RING (tests / benchmarks only): 2 = two buffers.
+    const char *fr = env_switch(SW_WSTEM_RING);
+    int sr = (fr && atoi(fr) == 2) ? 0 : largest_sr(3);
+    q.ring = sr > 0;
+    if (!q.ring) sr = largest_sr(2);
+    if (sr == 0) return false;
     q.SR = sr;
-    const int rows_in = 2 * sr + 5;
-    if (d->c * rows_in * (d->w / 8) > 1536) return false;               // 3 x-chunks per thread
     q.dyplane = (sr * Q / 32) * 1024 + 128;
-    const size_t xbytes = (size_t)d->c * rows_in * 2 * (d->w + 16);
-    size_t lds = 2 * ((size_t)4 * q.dyplane + ((xbytes + 15) & ~(size_t)15));
-    if (lds < 98304) lds = 98304;                                       // final cross-wave tree
-    if (lds > LDS_LIMIT) return false;
+    const size_t lds = lds_need(sr, q.ring ? 3 : 2);
+    q.x_bytes = (uint32_t)x_bytes;
     const int ktiles = d->k / 64;
     int strips = (NUM_CUS + d->n * ktiles - 1) / (d->n * ktiles);
     const int max_strips = (P + sr - 1) / sr;

@@ -20,7 +20,7 @@ namespace ngc {
 // The NGC_* variables are read once per process, at the first use, into a table; env_switch(SW_X) returns the value of
 // NGC_X or nullptr.  ngc_reload_switches() (exported for the test suite) reads them again and bumps the epoch, which
 // also drops every cached plan.
-enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_ROWS, SW_ROWS_LATE, SW_STAGED, SW_DRY_RUN, SW_COUNT };
+enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_WSTEM_RING, SW_ROWS, SW_ROWS_LATE, SW_STAGED, SW_DRY_RUN, SW_COUNT };
 const char *env_switch(Switch s);
 uint32_t sw_epoch();
 // NGC_DRY_RUN=1: every launch is skipped after the host-side planning (host-path timing without a GPU)
@@ -388,7 +388,9 @@ struct WgradStemParams {
     int32_t TP, strips;        // dy rows per workgroup (multiple of SR), strips per image
     int32_t SR;                // dy rows per LDS stage (SR*Q multiple of 32)
     int32_t dyplane;           // bytes per 16-channel dy plane of a stage
-    uint32_t dy_bytes;
+    uint32_t dy_bytes, x_bytes;
+    int32_t ring;              // three stage buffers + staging area for the raw input rows (else two buffers)
+    int32_t PL, RPX;           // LDS bytes per parity plane of an input row (>= W + 16) and per row (>= 2 PL)
     FastDiv div_q;
 };
 

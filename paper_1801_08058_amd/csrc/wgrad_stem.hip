@@ -39,6 +39,10 @@ __device__ __forceinline__ bf16x8 tr_frag_s(const unsigned char *lo, const unsig
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// RING: three stage buffers and every global read as a direct global->LDS load with counted waits (the input rows
+// land as they are in a small staging area and the thread that requested a 16-byte piece splits it into the parity
+// planes once it is there); else two stage buffers, the input rows through registers.
+template <bool RING>
 __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -59,8 +63,10 @@ __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
     const int PQ = p.P * p.Q;
     const int KB = p.K >> 4;
     const int rows_in = 2 * p.SR + 5;                        // input rows per stage
-    const int PL = p.W + 16;                                 // bytes per parity plane of a row (4 + W/2 + 4 bf16)
-    const int RPX = 2 * PL;
+    // bytes per parity plane of a row (4 + W/2 + 4 bf16 = W + 16 used) and per row; the host pads both so that the
+    // 64 lanes of an operand read (2 (c,r) pairs x 2 planes x 4 position groups x 2 dwords) fall into 64 different banks
+    const int PL = p.PL;
+    const int RPX = p.RPX;
     const int xbytes = p.C * rows_in * RPX;
     const int stage_bytes = 4 * p.dyplane + ((xbytes + 15) & ~15);
     const int steps_full = (p.SR * p.Q) >> 5;                // SR*Q is a multiple of 32
@@ -136,8 +142,8 @@ __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
                     *reinterpret_cast<uint2 *>(row + PL) = make_uint2(0, 0);
                 }
                 if (ch == cpr - 1) {
-                    *reinterpret_cast<uint2 *>(row + PL - 8) = make_uint2(0, 0);
-                    *reinterpret_cast<uint2 *>(row + 2 * PL - 8) = make_uint2(0, 0);
+                    *reinterpret_cast<uint2 *>(row + 8 + p.W) = make_uint2(0, 0);
+                    *reinterpret_cast<uint2 *>(row + PL + 8 + p.W) = make_uint2(0, 0);
                 }
             }
         }
@@ -154,23 +160,103 @@ __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
     const int lane_col = (L & 3) * 8;
     const int nfr = cg ? WST_NF - 1 : WST_NF;               // the 12th fragment does not exist
 
-    issue_dy(0, 0);
-    load_x(0);
-    store_x(0);
+    // ---- RING: stage s lives in buffer s % 3; raw input rows of stage s in staging area s & 1 behind the ring
+    const ngc_u32x4 rw_dy = make_rsrc_words(p.dy, p.dy_bytes);
+    const ngc_u32x4 rw_x = make_rsrc_words(p.x, p.x_bytes);
+    unsigned char *raw0 = smem + 3 * stage_bytes;
+    const int raw_bytes = ((xchunks + 63) & ~63) * 16;
+    const int ndy = (4 * steps_full - wave + 7) / 8;        // this wave's dy loads per stage
+    int nxw = (xchunks - wave * 64 + 511) / 512;            // and its loads of input-row pieces
+    nxw = nxw < 0 ? 0 : nxw > WST_XCH ? WST_XCH : nxw;
+    const int lpw = nxw + ndy;
+    auto issue_stage = [&](int s) {                         // lpw loads, always
+        const int h0 = 2 * (p0 + s * p.SR) - p.pbh;
+        unsigned char *raw = raw0 + (s & 1) * raw_bytes;
+#pragma unroll
+        for (int u = 0; u < WST_XCH; ++u) {
+            const int i = tid + 512 * u;
+            const int ch = i % cpr;
+            const int rr = i / cpr;
+            const int c = rr / rows_in;
+            const int h = h0 + (rr - c * rows_in);
+            const bool ok = i < xchunks && (unsigned)h < (unsigned)p.H;
+            const unsigned off = ok ? (unsigned)(((((img * p.C + c) * p.H + h) * p.W) + ch * 8) * 2) : WST_OOB;
+            if (wave * 64 + 512 * u < xchunks)              // wave-uniform; the staging area ends at a multiple of 64 pieces
+                dma_load_lds16(rw_x, raw + (wave * 64 + 512 * u) * 16, off, 0);
+        }
+        unsigned char *base = smem + (s % 3) * stage_bytes;
+        const int r0 = s * p.SR;
+        int rows = rows_strip - r0;
+        if (rows > p.SR) rows = p.SR;
+        const int nvalid = rows * p.Q;
+        for (int it = wave; it < 4 * steps_full; it += 8) {
+            const int pln = it / steps_full, blk = it - pln * steps_full;
+            const unsigned dy_base = (unsigned)((((img * KB + kt * 4 + pln) * PQ) + (p0 + r0) * p.Q) * 32);
+            const int pos = blk * 32 + (lane >> 1);
+            const unsigned off = (pos < nvalid) ? dy_base + (unsigned)(pos * 32 + (lane & 1) * 16) : WST_OOB;
+            // the quotient comes out of the vector unit: hand the (wave-uniform) destination over as a scalar
+            dma_load_lds16(rw_dy, base + __builtin_amdgcn_readfirstlane(pln * p.dyplane + blk * 1024), off, 0);
+        }
+    };
+    auto split_x = [&](int s) {                             // own pieces of stage s: staging area -> parity planes
+        const unsigned char *raw = raw0 + (s & 1) * raw_bytes;
+        unsigned char *xs = smem + (s % 3) * stage_bytes + 4 * p.dyplane;
+#pragma unroll
+        for (int u = 0; u < WST_XCH; ++u) {
+            const int i = tid + 512 * u;
+            if (i < xchunks) {
+                const int ch = i % cpr;
+                const int rr = i / cpr;
+                const uint4 v = *reinterpret_cast<const uint4 *>(raw + i * 16);
+                unsigned char *row = xs + rr * RPX;
+                const uint2 ev = make_uint2((v.x & 0xFFFFu) | (v.y << 16), (v.z & 0xFFFFu) | (v.w << 16));
+                const uint2 od = make_uint2((v.x >> 16) | (v.y & 0xFFFF0000u), (v.z >> 16) | (v.w & 0xFFFF0000u));
+                *reinterpret_cast<uint2 *>(row + 8 + ch * 8) = ev;
+                *reinterpret_cast<uint2 *>(row + PL + 8 + ch * 8) = od;
+                if (ch == 0) {
+                    *reinterpret_cast<uint2 *>(row) = make_uint2(0, 0);
+                    *reinterpret_cast<uint2 *>(row + PL) = make_uint2(0, 0);
+                }
+                if (ch == cpr - 1) {
+                    *reinterpret_cast<uint2 *>(row + 8 + p.W) = make_uint2(0, 0);
+                    *reinterpret_cast<uint2 *>(row + PL + 8 + p.W) = make_uint2(0, 0);
+                }
+            }
+        }
+    };
+
+    if constexpr (RING) {
+        issue_stage(0);
+        if (nstages > 1) issue_stage(1);
+        wait_vmcnt(nstages > 1 ? lpw : 0);                  // stage 0 has landed (this wave's part)
+        split_x(0);
+    } else {
+        issue_dy(0, 0);
+        load_x(0);
+        store_x(0);
+    }
     for (int s = 0; s < nstages; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): dy of stage s has landed (this wave's part)
-        __syncthreads();
         const bool more = s + 1 < nstages;
-        if (more) {
-            issue_dy(s + 1, (s + 1) & 1);
-            load_x(s + 1);
+        if constexpr (RING) {
+            // every wave has split its input pieces of stage s and seen its dy loads of stage s land; the barrier
+            // makes that true for the workgroup and frees the buffer of stage s - 1 for the loads of stage s + 2
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            wg_barrier_nofence();
+            if (s + 2 < nstages) issue_stage(s + 2);
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): dy of stage s has landed (this wave's part)
+            __syncthreads();
+            if (more) {
+                issue_dy(s + 1, (s + 1) & 1);
+                load_x(s + 1);
+            }
         }
         int rows = rows_strip - s * p.SR;
         if (rows > p.SR) rows = p.SR;
         const int nsteps = (rows * p.Q) >> 5;               // rows*Q is a multiple of 8; partial steps handled by zero dy
         const int nsteps_up = (rows * p.Q + 31) >> 5;
         (void)nsteps;
-        const unsigned char *dys = smem + (s & 1) * stage_bytes;
+        const unsigned char *dys = smem + (RING ? s % 3 : s & 1) * stage_bytes;
         const unsigned char *xs = dys + 4 * p.dyplane;
         for (int j = (wh - (s * steps_full) % 4 + 4) % 4; j < nsteps_up; j += 4) {
             // this lane group's 8 positions: m8 .. m8+7, all in dy row pr
@@ -199,7 +285,14 @@ __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
                 }
             }
         }
-        if (more) store_x((s + 1) & 1);
+        if constexpr (RING) {
+            if (more) {
+                wait_vmcnt(s + 2 < nstages ? lpw : 0);              // stage s + 1 has landed (this wave's part)
+                split_x(s + 1);
+            }
+        } else {
+            if (more) store_x((s + 1) & 1);
+        }
     }
     __syncthreads();
 
@@ -276,13 +369,18 @@ __global__ __launch_bounds__(256) void wgrad_stem_reduce(const f32x4 *__restrict
 
 hipError_t launch_wgrad_stem(const WgradStemParams &p, size_t lds_bytes, hipStream_t st)
 {
-    static LdsLimitOnce lds_limit;                  // per template instantiation
-    {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_stem_bf16));
-        if (e != hipSuccess) return e;
-    }
     dim3 grid(p.N * p.strips, p.K / 64);
-    NGC_LAUNCH(wgrad_stem_bf16, grid, dim3(512), lds_bytes, st, p);
+    if (p.ring) {
+        static LdsLimitOnce lds_limit;              // per template instantiation
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_stem_bf16<true>));
+        if (e != hipSuccess) return e;
+        NGC_LAUNCH(wgrad_stem_bf16<true>, grid, dim3(512), lds_bytes, st, p);
+    } else {
+        static LdsLimitOnce lds_limit;
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_stem_bf16<false>));
+        if (e != hipSuccess) return e;
+        NGC_LAUNCH(wgrad_stem_bf16<false>, grid, dim3(512), lds_bytes, st, p);
+    }
     hipError_t e = ngc::launch_result();
     if (e != hipSuccess) return e;
     const size_t per4 = (size_t)(p.K / 64) * 2 * 4 * WST_NF * 64;

@@ -617,6 +617,20 @@ def test_stem_forward_tile_heights(tp, monkeypatch):
         assert e <= bound("bf16", "act"), f"tp {tp} case {case} err {e}"
 
 
+@pytest.mark.parametrize("case", [1, 2, 3, 4])                       # the cases whose Q is a multiple of 8
+def test_stem_backprop_filters_two_buffer_form(case, monkeypatch):
+    """The low-channel backprop-filters kernel with two stage buffers and the input rows through registers (the form
+    taken when three buffers plus the staging area do not fit the LDS; forced here)."""
+    monkeypatch.setenv("NGC_WSTEM_RING", "2")
+    a = STEM_CASES[case]
+    x, w, b, dy = _tensors(a, "bf16", 5300 + case)
+    run = Run(a, "bf16", NCHW, BLK, False)
+    dw = run.bwd_filters(x, dy)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_FILTERS) == "wgrad_stem_bf16"
+    e = oracle.max_normalised_error(dw, oracle.conv_bwd_filters(a, x, dy))
+    assert e <= bound("bf16", "dw"), f"err {e}"
+
+
 def test_stem_backprop_data_unstaged_store():
     """Width not a multiple of 8: the sub-pixel store cannot go through whole 16-byte row pieces."""
     a = Attrs(2, 3, 30, 44, 64, 7, 7, 2, 2, 1, 1, 3, 3, 3, 3)
