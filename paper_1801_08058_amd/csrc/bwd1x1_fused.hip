@@ -202,8 +202,8 @@ __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams
                 const uint32_t pq1 = (in1 ? m1 : 0) - n1 * p.div_hw.d;
                 o1 = in1 ? (unsigned)(((n1 * CBt + ct * 4 + cblk0) * HW + pq1) * 32 + grp * 8) : BF_OOB;
             }
-            __builtin_amdgcn_raw_buffer_store_b64(v0, rs_dx, (int)o0, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(v1, rs_dx, (int)o1, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(v0, rs_dx, (int)o0, 0, NGC_ST_AUX);
+            __builtin_amdgcn_raw_buffer_store_b64(v1, rs_dx, (int)o1, 0, NGC_ST_AUX);
         }
     }
 

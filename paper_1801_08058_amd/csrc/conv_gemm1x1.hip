@@ -260,13 +260,14 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 uint4 o = *reinterpret_cast<const uint4 *>(st + ch * YROW + piece * 16);
                 const size_t off = ((size_t)n * p.Cout + (n0 + wn * 32 * FA + ch)) * HWout + pp;
                 if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + off));
-                *reinterpret_cast<uint4 *>(p.out + off) = o;
+                store16_result(p.out + off, o, true);
             }
         }
         return;
     }
     // ---- epilogue: bias, ReLU, one RNE rounding, lane-pair exchange, 16-byte stores
     const int CBout = p.Cout >> 4;
+    const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines
     float csum[DB ? FA : 1][2][8];                        // DB: channel sums of this lane's stored values
 #pragma unroll
     for (int a = 0; a < (DB ? FA : 1); ++a)
@@ -310,15 +311,14 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
                 if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
-                    *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    store16_result(p.out + blk * 16 + lg * 8, o, dense_out);
                     if (p.zero_sib) {
                         // strided backprop-data whose one class of pixels starts at (0, 0): the pixels of the block
                         // that no tap reaches are zero, written here instead of by a fill pass over the whole dx
                         for (int zh = 0; zh < p.os_h; ++zh)
                             for (int zw = 0; zw < p.os_w; ++zw)
                                 if ((zh | zw) != 0 && oh + zh < p.Hout && ow + zw < p.Wout)
-                                    *reinterpret_cast<uint4 *>(p.out + (blk + (size_t)(zh * p.Wout + zw)) * 16 + lg * 8) =
-                                        make_uint4(0, 0, 0, 0);
+                                    store16_result(p.out + (blk + (size_t)(zh * p.Wout + zw)) * 16 + lg * 8, make_uint4(0, 0, 0, 0), false);
                     }
                     if (DB) {                                            // the rounded, masked values as stored
                         const uint32_t w4[4] = {o.x, o.y, o.z, o.w};

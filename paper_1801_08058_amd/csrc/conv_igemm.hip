@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
                 if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * HWout;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
-                    *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    store16_result(p.out + blk * 16 + lg * 8, o, p.os_h == 1 && p.os_w == 1);
                 }
             }
         }

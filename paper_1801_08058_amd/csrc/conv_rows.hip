@@ -261,7 +261,7 @@ __global__ __launch_bounds__(ROWS_NW * 64) void conv_rows_bf16(const RowsParams 
                 const uint4 o = relu_keep8(make_uint4(ov[0], ov[1], ov[2], ov[3]), mk);
                 ov = u32x4{o.x, o.y, o.z, o.w};
             }
-            __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
         }
     };
 

@@ -161,10 +161,10 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
                     const unsigned off = ok ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * PQ)) * 32u + (unsigned)(lg * 16)
                                             : 0x80000000u;
                     ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
-                    __builtin_amdgcn_raw_buffer_store_b128(ov, rs_y, (int)off, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(ov, rs_y, (int)off, 0, NGC_ST_AUX);
                 } else if (ok) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * PQ;
-                    *reinterpret_cast<uint4 *>(p.y + blk * 16 + lg * 8) = o;
+                    store16_result(p.y + blk * 16 + lg * 8, o, true);
                 }
             }
         }

@@ -366,7 +366,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 uint4 val = *reinterpret_cast<const uint4 *>(ob + (size_t)row * WP + ch * 8);
                 const size_t off = (((size_t)n * p.sub_C + c) * p.sub_H + y) * p.sub_W + ch * 8;
                 if (p.mask) val = relu_keep8(val, *reinterpret_cast<const uint4 *>(p.mask + off));
-                *reinterpret_cast<uint4 *>(p.out + off) = val;
+                store16_result(p.out + off, val, true);
             }
         }
         return;
@@ -374,6 +374,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // blocked rank-2 output below 2 GiB: 16-byte stores with 32-bit offsets into a buffer descriptor, lanes that
     // must not store get an out-of-range offset (no 64-bit address arithmetic, no divergent branch per store)
     const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
+    const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines, streaming stores
     __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
     const int relu_on = p.relu;
 #pragma unroll
@@ -450,13 +451,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                     const unsigned off = st ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * plane_out)) * 32u + (unsigned)(lg * 16)
                                             : STRIP_OOB;
                     ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
-                    __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
+                    if (dense_out) __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
+                    else __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
                     continue;
                 }
                 if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * plane_out;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
-                    *reinterpret_cast<uint4 *>(p.out + blk * 16 + lg * 8) = o;
+                    store16_result(p.out + blk * 16 + lg * 8, o, dense_out);
                     if (DB) {                                            // the rounded, masked values as stored
                         const uint32_t w4[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll

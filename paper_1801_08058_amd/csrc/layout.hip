@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void nchw_to_blocked16_b16(const uint16_t *__r
                 w[e] = lo | (hi << 16);
             }
             uint16_t *g = dst + (((size_t)n * CB + cb) * HW + px0 + px) * 16 + half * 8;
-            *reinterpret_cast<uint4 *>(g) = make_uint4(w[0], w[1], w[2], w[3]);
+            store16_result(g, make_uint4(w[0], w[1], w[2], w[3]), true);
         }
     }
 }

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(NT == 64 ? 256 : NT) void softmax_rows_reg(const T 
 #pragma unroll
     for (int j = 0; j < V; ++j) {
         const int vi = j * NT + lane;
-        if (vi < nvec) *reinterpret_cast<uint4 *>(out + base + (size_t)vi * E) = SmElem<T>::pack(va[j]);
+        if (vi < nvec) store16_result(out + base + (size_t)vi * E, SmElem<T>::pack(va[j]), true);
     }
 }
 
