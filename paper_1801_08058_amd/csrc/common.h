@@ -19,9 +19,10 @@
 // tensor, i.e. output pixel stride 1) they are marked as streaming, so they leave the L2 as they are written instead of
 // when the kernel ends (headline 3x3 layer: forward 18.9 -> 17.4 us).  Strided backprop-data writes every other pixel
 // per launch or per store instruction and keeps ordinary stores (streaming partial lines doubles its time).
-// NGC_ST_AUX = 0: ordinary stores everywhere.
+// The buffer stores also carry the system-scope bit (aux 16: written through; another 2-4 % on the strip and stem
+// kernels).  NGC_ST_AUX = 0: ordinary stores everywhere.
 #ifndef NGC_ST_AUX
-#define NGC_ST_AUX 2
+#define NGC_ST_AUX 18
 #endif
 namespace ngc {
 
