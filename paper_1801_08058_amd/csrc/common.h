@@ -44,7 +44,7 @@ __device__ __forceinline__ void store16_result(void *dst, uint4 v, bool stream)
 // The NGC_* variables are read once per process, at the first use, into a table; env_switch(SW_X) returns the value of
 // NGC_X or nullptr.  ngc_reload_switches() (exported for the test suite) reads them again and bumps the epoch, which
 // also drops every cached plan.
-enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_WSTEM_RING, SW_ROWS, SW_ROWS_LATE, SW_STAGED, SW_DRY_RUN, SW_COUNT };
+enum Switch { SW_CONV3D_RANK2, SW_CONV3D_STRIP, SW_DB_FUSE, SW_G1_NCHW, SW_G1_VARIANT, SW_GEMM1X1, SW_STEM_BH, SW_STEM_TP, SW_STRIP_1WAVE, SW_STRIP_BW, SW_STRIP_MERGE, SW_STRIP_NF, SW_STRIP_ROWS, SW_STRIP_STRIDED, SW_STRIP_XCD, SW_WGG3_PARTS, SW_WGG_SLOTS, SW_WGG_SP, SW_WGG_TILE, SW_WGG_XCD, SW_WGRAD_G1, SW_WGRAD_GEMM, SW_WGRAD_LATE, SW_WGRAD_NCQ, SW_WGRAD_RING, SW_WGRAD_STRIP, SW_WSTEM_POS, SW_WSTEM_RING, SW_ROWS, SW_ROWS_LATE, SW_STAGED, SW_STRIP_TAIL, SW_DRY_RUN, SW_COUNT };
 const char *env_switch(Switch s);
 uint32_t sw_epoch();
 // NGC_DRY_RUN=1: every launch is skipped after the host-side planning (host-path timing without a GPU)
@@ -116,9 +116,31 @@ __device__ __forceinline__ float relu_f32(float v)
 
 __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
 {
+    // as one vector conversion: two scalar casts become two conversions and a byte permute
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    bf16x2_t r = {(__bf16)lo, (__bf16)hi};
-    return __builtin_bit_cast(uint32_t, r);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// A kernel's by-value argument struct lives in the kernel-argument segment and is read with scalar loads where a
+// field is first used; every 64-byte line of it that is touched for the first time costs a round trip to memory, and
+// left to the compiler these come one after the other all through the set-up code.  Reading one word of every line
+// at the top of the kernel brings the whole segment into the scalar cache in one batch of loads under one wait.
+template <class P>
+__device__ __forceinline__ void preload_kernargs(const P &p)
+{
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(&p);
+    constexpr unsigned n = sizeof(P) / 4;
+#pragma unroll
+    for (unsigned b = 0; b < n; b += 256) {               // 16 lines per statement: one clause of loads, one wait
+#define NGC_KARG_LINE(k) w[b + 16 * (k) < n ? b + 16 * (k) : 0]
+        asm volatile("" ::"s"(NGC_KARG_LINE(0)), "s"(NGC_KARG_LINE(1)), "s"(NGC_KARG_LINE(2)), "s"(NGC_KARG_LINE(3)),
+                     "s"(NGC_KARG_LINE(4)), "s"(NGC_KARG_LINE(5)), "s"(NGC_KARG_LINE(6)), "s"(NGC_KARG_LINE(7)),
+                     "s"(NGC_KARG_LINE(8)), "s"(NGC_KARG_LINE(9)), "s"(NGC_KARG_LINE(10)), "s"(NGC_KARG_LINE(11)),
+                     "s"(NGC_KARG_LINE(12)), "s"(NGC_KARG_LINE(13)), "s"(NGC_KARG_LINE(14)), "s"(NGC_KARG_LINE(15)));
+#undef NGC_KARG_LINE
+    }
 }
 
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n; waiting for fewer outstanding loads than
@@ -317,6 +339,8 @@ struct StripParams {
     int32_t dt_off[STRIP_MAX_DT], dt_slab[STRIP_MAX_DT];
     FastDiv div_od;
     int32_t xcd_order;         // single launches: one-dimensional grid, the output-channel tiles of a strip on one XCD
+    int32_t tail_fuse;         // blocked rank-2 output through the buffer descriptor: the last chunk runs fragment after
+                               // fragment with each fragment's epilogue behind its taps
     // Column tiles (rows wider than a strip holds): a strip covers BW of the Wout lattice columns; `strips` counts
     // (row strip, column tile) pairs, column tile fastest; the geometry fields and divisors above are those of a
     // BW-wide lattice.  ncolt = 1: BW = Wout.

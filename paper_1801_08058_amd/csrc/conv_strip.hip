@@ -3,6 +3,13 @@
 
 namespace ngc {
 
+#ifdef NGC_TIMELINE
+extern "C" int ngc_debug_strip_timeline(unsigned *host_dst, size_t count)
+{
+    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_strip_timeline), count * sizeof(unsigned));
+}
+#endif
+
 template <int NF, int NW, int SUB = 0>
 static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStream_t st)
 {
@@ -28,6 +35,10 @@ hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipSt
     const char *xo = env_switch(SW_STRIP_XCD);
     const int gx = p.groups * p.strips;                  // strips per XCD must come out even: a multiple of 8, or many
     if (p.Cout > 64 && (gx % 8 == 0 || gx >= 64) && !(xo && atoi(xo) == 0)) p.xcd_order = 1;
+    {
+        const char *tf = env_switch(SW_STRIP_TAIL);      // NGC_STRIP_TAIL=0: epilogues behind the last chunk, not in it
+        p.tail_fuse = (tf && atoi(tf) == 0) ? 0 : 1;
+    }
     if (p.r3) {                                          // blocked output, two waves per SIMD; a code object of its own
         if (p.out_mode != 0 || !two_waves) return hipErrorInvalidValue;
         return launch_strip_r3(p, nf, lds_bytes, st);

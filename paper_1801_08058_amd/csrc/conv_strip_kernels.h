@@ -36,6 +36,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void;
 
+#ifdef NGC_TIMELINE
+// development builds only: time stamps (100 MHz counter, low 32 bits) of every wave, 16 slots, kept in registers
+static __device__ unsigned g_strip_timeline[1024 * 8 * 16];   // one copy per translation unit
+#define STRIP_TL(k) tl[k] = (unsigned)wall_clock64()
+#else
+#define STRIP_TL(k) do { } while (0)
+#endif
+
 constexpr int STRIP_WPITCH = 64 * 16 + 128;     // bytes per (tap, g) filter plane
 constexpr int STRIP_MAXBLOCKS = 24;             // 64-pixel patch blocks per plane (whole workgroup)
 constexpr unsigned STRIP_OOB = 0x80000000u;     // byte offset beyond any buffer -> load returns 0
@@ -67,17 +75,23 @@ __device__ __forceinline__ void strip_chunk_mfma(f32x16 (&acc)[NF][2], const uns
 #pragma unroll
         for (int i = 0; i < NFR; ++i) b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
     }
+#ifndef NGC_EXP
+#define NGC_EXP 0
+#endif
     for (int t = 1; t < ntaps; ++t) {
         const int toff = __builtin_amdgcn_readlane(tapv, t);
-        const bf16x8 a0n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T);
-        bf16x8 a1n = a0n;
-        if (UPPER) a1n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T + 32 * 16);
+        bf16x8 a0n = a0, a1n = a1;
+        if (!(NGC_EXP & 2)) {
+            a0n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T);
+            a1n = a0n;
+            if (UPPER) a1n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T + 32 * 16);
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NFR; ++i) {
             acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b[i], acc[i][0], 0, 0, 0);
             if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b[i], acc[i][1], 0, 0, 0);
-            b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+            if (!(NGC_EXP & 1)) b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
             __builtin_amdgcn_sched_barrier(0);
         }
         a0 = a0n;
@@ -87,6 +101,42 @@ __device__ __forceinline__ void strip_chunk_mfma(f32x16 (&acc)[NF][2], const uns
     for (int i = 0; i < NFR; ++i) {
         acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b[i], acc[i][0], 0, 0, 0);
         if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b[i], acc[i][1], 0, 0, 0);
+    }
+}
+
+// The last chunk of a workgroup, fragment after fragment instead of tap after tap: a fragment's accumulators are
+// final after its own taps, so its epilogue (epi(i): bias, ReLU, rounding, stores) runs while the wave's other
+// fragments - and the other wave of the SIMD - still have MFMAs to issue, and the results leave the chip during the
+// chunk instead of all at once behind it.  Costs the two filter operands once per fragment and tap instead of once
+// per tap (LDS is far from busy).  Same MFMAs per accumulator in the same order as strip_chunk_mfma: same bits.
+template <int NF, int NFR, bool UPPER, int WSTRIDE_T, class Epi>
+__device__ __forceinline__ void strip_chunk_mfma_last(f32x16 (&acc)[NF][2], const unsigned char *xs, const unsigned char *ws,
+                                                      const int (&pbase)[NF], const int tapv, const int ntaps, Epi &&epi)
+{
+    static_assert(NFR >= 1 && NFR <= NF, "fragments held by the wave");
+#pragma unroll
+    for (int i = 0; i < NFR; ++i) {
+        bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws);
+        bf16x8 a1 = a0;
+        if (UPPER) a1 = *reinterpret_cast<const bf16x8 *>(ws + 32 * 16);
+        bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + __builtin_amdgcn_readlane(tapv, 0));
+        for (int t = 1; t < ntaps; ++t) {
+            const int toff = __builtin_amdgcn_readlane(tapv, t);
+            const bf16x8 a0n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T);
+            bf16x8 a1n = a0n;
+            if (UPPER) a1n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T + 32 * 16);
+            const bf16x8 bn = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
+            if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = a0n;
+            a1 = a1n;
+            b = bn;
+        }
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
+        if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+        epi(i);
     }
 }
 
@@ -117,6 +167,20 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int lg = lane >> 5;
+#ifdef NGC_TIMELINE
+    unsigned tl[16] = {};
+    STRIP_TL(0);
+    auto tl_flush = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        STRIP_TL(15);
+        if (lane < 16 && bx < 1024 && by == 0) {
+            unsigned v = 0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v = lane == k ? tl[k] : v;
+            g_strip_timeline[(bx * 8 + wave) * 16 + lane] = v;
+        }
+    };
+#endif
 
     const int grp = bx / p.strips;
     int strip = bx - grp * p.strips;
@@ -242,8 +306,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         pbase[i] = pb * 16;
     }
 
-    // bias values of this lane's channels, requested before the chunk loop so that the epilogue does not start with
-    // a round trip to memory
+    // bias values of this lane's channels
     float4 bv[2][2][2];                                   // [a][h][which quad]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -256,13 +319,79 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             }
         }
 
+    // Blocked output: the accumulators start from the bias (register 8 h + e of channel half a holds the channel of
+    // bv[a][h][e / 4], component e % 4), so the epilogue has no additions and the bias registers are free during the
+    // chunk loop.  The sub-pixel store modes take no bias.
     f32x16 acc[NF][2];
 #pragma unroll
     for (int i = 0; i < NF; ++i)
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][a][v] = 0.f;
+            for (int h = 0; h < 2; ++h) {
+                const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
+                const float bias8[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[i][a][8 * h + e] = SUB == 0 ? bias8[e] : 0.f;
+            }
+
+    // Blocked rank-2 output below 2 GiB: 16-byte stores with 32-bit offsets into a buffer descriptor, lanes that
+    // must not store get an out-of-range offset (no 64-bit address arithmetic, no divergent branch per store).
+    const int CBout = p.Cout >> 4;
+    const int HWout = p.Hfull * p.Wfull;
+    const int plane_out = R3 ? p.Dfull * HWout : HWout;  // pixel blocks per 16-channel plane of a batch element
+    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
+    const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines, streaming stores
+    __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
+    const int relu_on = p.relu;
+    // ReLU on the rounded values, two at a time: as 16-bit integers the negative bf16 values (and -0) are the
+    // negative numbers, so a signed maximum with 0 is max(v, 0) of both halves in one instruction (rounding keeps the
+    // sign, so it commutes with ReLU); a maximum with the most negative integer changes nothing (ReLU off).
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    const short relu_floor = relu_on ? (short)0 : (short)-32768;
+    auto relu_bf16x2 = [&](uint32_t w) {
+        const s16x2 v = __builtin_bit_cast(s16x2, w), f = {relu_floor, relu_floor};
+        return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, f));
+    };
+    // Epilogue of fragment i on that path (the bias is in the accumulators): one rounding, ReLU, lane-pair exchange,
+    // stores.  STREAM: every pixel of the tensor is written by this launch, the stores are streaming stores.
+    auto store_frag32 = [&](const int i, auto stream_tag) {
+        constexpr bool STREAM = decltype(stream_tag)::value;
+        const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
+        bool ok = m < (uint32_t)p.npix;
+        const uint32_t mm = ok ? m : 0;
+        const uint32_t ti = fd_div(mm, p.div_tpq);
+        const uint32_t rem = mm - ti * p.div_tpq.d;
+        const uint32_t tp = fd_div(rem, p.div_q);
+        const uint32_t q = rem - tp * p.div_q.d;
+        const int n = n0 + (int)ti;
+        const int oh = p0 + (int)tp;
+        ok = ok && n < p.N && oh < p.Hout;
+        if constexpr (CT) ok = ok && q0 + (int)q < p.Wout;
+        const unsigned pix = (unsigned)((oh * p.os_h + p.oa_h) * p.Wfull + ((CT ? q0 : 0) + (int)q) * p.os_w + p.oa_w) +
+                             (unsigned)(n * CBout * HWout);
+        const unsigned off0 = ok ? (pix + (unsigned)((k0 >> 4) * plane_out)) * 32u + (unsigned)(lg * 16) : STRIP_OOB;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const f32x16 &t = acc[i][a];
+                const uint32_t w0 = relu_bf16x2(pack_bf16x2_hw(t[8 * h], t[8 * h + 1]));
+                const uint32_t w1 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 2], t[8 * h + 3]));
+                const uint32_t w2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]));
+                const uint32_t w3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]));
+                const uint4 o = lane_pair_exchange(w0, w1, w2, w3);
+                const int cb = 2 * a + h;                                // 16-channel block inside the tile
+                const bool st = off0 != STRIP_OOB && (k0 >> 4) + cb < CBout;
+                const unsigned off = st ? off0 + (unsigned)(cb * plane_out) * 32u : STRIP_OOB;
+                ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
+                if constexpr (STREAM) __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
+                else __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
+            }
+        }
+    };
+    // the last chunk runs fragment-outer with the epilogues inside it (strip_chunk_mfma_last)
+    const bool tail_fuse = SUB == 0 && !DB && !R3 && store32 && dense_out && p.tail_fuse != 0;
 
     // the sub-pixel store mode may use no more than 32 of the 64 output columns: skip the upper MFMA
     constexpr bool upper = !HALF;
@@ -271,12 +400,19 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // sequence; the others (ragged strips) the loop that tests every fragment.  NFR = 0 selects the latter.
     static_assert(STRIP_MAX_TAPS <= 64, "one lane per tap");
     const int tapv = p.tap_off[lane < p.ntaps ? lane : 0] * 16;
-    auto chunk_loop = [&](auto nfr_tag) {
+    auto chunk_loop = [&](auto nfr_tag) -> bool {
         constexpr int NFR = decltype(nfr_tag)::value;
+        const bool tail = NFR > 0 && tail_fuse;
+        const int nmain = tail ? nchunks - 1 : nchunks;
+        STRIP_TL(1);
         issue_loads(0, 0);
-        for (int c = 0; c < nchunks; ++c) {
+        STRIP_TL(2);
+        for (int c = 0; c < nmain; ++c) {
             __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wave's loads of chunk c have landed
             __syncthreads();                                // ... and everybody else's; stage (c+1)&1 is free
+#ifdef NGC_TIMELINE
+            if (c < 5) { if (c == 0) STRIP_TL(3); else if (c == 1) STRIP_TL(4); else if (c == 2) STRIP_TL(5); else if (c == 3) STRIP_TL(6); else STRIP_TL(7); }
+#endif
             if (c + 1 < nchunks) issue_loads(c + 1, (c + 1) & 1);
             const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
             const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
@@ -299,15 +435,34 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 }
             }
         }
+        if constexpr (NFR > 0 && SUB == 0 && !DB && !R3) {
+            if (tail) {                                     // last chunk, with the epilogues inside it
+                const int c = nchunks - 1;
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __syncthreads();
+                STRIP_TL(8);
+                const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
+                const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
+                strip_chunk_mfma_last<NF, NFR, upper, wstride_t>(acc, xs, ws, pbase, tapv, p.ntaps,
+                                                                [&](const int i) { store_frag32(i, std::true_type{}); });
+                STRIP_TL(10);
+#ifdef NGC_TIMELINE
+                tl_flush();
+#endif
+                return true;
+            }
+        }
+        return false;
     };
-    if (nfrag == NF) chunk_loop(std::integral_constant<int, NF>{});
-    else if (NF > 1 && nfrag == NF - 1) chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{});
-    else chunk_loop(std::integral_constant<int, 0>{});
+    if (nfrag == NF) {
+        if (chunk_loop(std::integral_constant<int, NF>{})) return;
+    } else if (NF > 1 && nfrag == NF - 1) {
+        if (chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{})) return;
+    } else {
+        chunk_loop(std::integral_constant<int, 0>{});
+    }
 
     // ---- epilogue
-    const int CBout = p.Cout >> 4;
-    const int HWout = p.Hfull * p.Wfull;
-    const int plane_out = R3 ? p.Dfull * HWout : HWout;  // pixel blocks per 16-channel plane of a batch element
     float csum[DB ? 2 : 1][2][8];                         // DB: channel sums of this lane's stored values
 #pragma unroll
     for (int a = 0; a < (DB ? 2 : 1); ++a)
@@ -371,12 +526,23 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         return;
     }
-    // blocked rank-2 output below 2 GiB: 16-byte stores with 32-bit offsets into a buffer descriptor, lanes that
-    // must not store get an out-of-range offset (no 64-bit address arithmetic, no divergent branch per store)
-    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
-    const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines, streaming stores
-    __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
-    const int relu_on = p.relu;
+    if (store32 && !DB) {
+        STRIP_TL(9);
+        if (dense_out) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if (i < nfrag) store_frag32(i, std::true_type{});
+        } else {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if (i < nfrag) store_frag32(i, std::false_type{});
+        }
+        STRIP_TL(10);
+#ifdef NGC_TIMELINE
+        tl_flush();
+#endif
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         if (i >= nfrag) break;
@@ -433,12 +599,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             for (int h = 0; h < 2; ++h) {
                 float v[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = acc[i][a][8 * h + e];
-                {
-                    const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
-                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                }
+                for (int e = 0; e < 8; ++e) v[e] = acc[i][a][8 * h + e];      // bias included
                 if (relu_on) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = relu_f32(v[e]);
@@ -446,15 +607,6 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
                 const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
                 uint4 o = lane_pair_exchange(q0, q1, q2, q3);
-                if (store32 && !DB) {
-                    const bool st = ok && (co_base >> 4) + h < CBout;
-                    const unsigned off = st ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * plane_out)) * 32u + (unsigned)(lg * 16)
-                                            : STRIP_OOB;
-                    ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
-                    if (dense_out) __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
-                    else __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
-                    continue;
-                }
                 if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * plane_out;
                     if (p.mask) o = relu_keep8(o, *reinterpret_cast<const uint4 *>(p.mask + blk * 16 + lg * 8));
@@ -489,6 +641,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 template <int NF, int NW, int SUB = 0, bool DB = false, bool R3 = false, bool CT = false>
 __global__ __launch_bounds__(NW * 64) void conv_strip_bf16(const StripParams p)
 {
+    preload_kernargs(p);
     if (p.xcd_order) {
         // one-dimensional grid: workgroup ids go round-robin to the 8 XCDs (one L2 each); strip bx lives on XCD
         // bx % 8 and its output-channel tiles are consecutive there, so they share the strip's input through that L2

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     constexpr int NW = 8;
     constexpr int NH = NW / NCQ;             // waves per channel group = step interleave
     extern __shared__ __align__(16) unsigned char smem[];
+    preload_kernargs(p);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
