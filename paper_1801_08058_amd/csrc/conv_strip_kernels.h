@@ -205,6 +205,19 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
 
+    // bias values of this lane's channels
+    float4 bv[2][2][2];                                   // [a][h][which quad]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.bias && k0 + a * 32 + 16 * h < p.Cout) {       // the last 64-channel tile may be partial (Cout % 16 == 0)
+                bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
+                bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
+            }
+        }
+
     // ---- loader bookkeeping: wave w loads patch blocks b = w, w+4, ... of both planes
     const int nblocks = (p.npatch + 63) >> 6;
     unsigned xoff[MAXXB];
@@ -290,6 +303,12 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
     };
 
+    // The first chunk is requested before anything else is set up: position tables and initial accumulators cost a
+    // few hundred vector instructions per wave, which run while the loads are in flight.
+    STRIP_TL(1);
+    issue_loads(0, 0);
+    STRIP_TL(2);
+
     // ---- positions owned by this lane: fragment f = wave + 4 i, position m = 32 f + l32
     int pbase[NF];          // patch pixel index of the position at tap offset 0 (clamped to 0 if invalid)
 #pragma unroll
@@ -305,19 +324,6 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         pbase[i] = pb * 16;
     }
-
-    // bias values of this lane's channels
-    float4 bv[2][2][2];                                   // [a][h][which quad]
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bv[a][h][0] = bv[a][h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (p.bias && k0 + a * 32 + 16 * h < p.Cout) {       // the last 64-channel tile may be partial (Cout % 16 == 0)
-                bv[a][h][0] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 4 * lg);
-                bv[a][h][1] = *reinterpret_cast<const float4 *>(p.bias + k0 + a * 32 + 16 * h + 8 + 4 * lg);
-            }
-        }
 
     // Blocked output: the accumulators start from the bias (register 8 h + e of channel half a holds the channel of
     // bv[a][h][e / 4], component e % 4), so the epilogue has no additions and the bias registers are free during the
@@ -404,9 +410,6 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         constexpr int NFR = decltype(nfr_tag)::value;
         const bool tail = NFR > 0 && tail_fuse;
         const int nmain = tail ? nchunks - 1 : nchunks;
-        STRIP_TL(1);
-        issue_loads(0, 0);
-        STRIP_TL(2);
         for (int c = 0; c < nmain; ++c) {
             __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wave's loads of chunk c have landed
             __syncthreads();                                // ... and everybody else's; stage (c+1)&1 is free
