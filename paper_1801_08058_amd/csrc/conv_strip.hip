@@ -38,6 +38,8 @@ hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipSt
     {
         const char *tf = env_switch(SW_STRIP_TAIL);      // NGC_STRIP_TAIL=0: epilogues behind the last chunk, not in it
         p.tail_fuse = (tf && atoi(tf) == 0) ? 0 : 1;
+        const char *fs = env_switch(SW_STRIP_SPLIT);     // NGC_STRIP_SPLIT=0: the odd last fragment stays with wave 0
+        p.frag_split = (fs && atoi(fs) == 0) ? 0 : 1;
     }
     if (p.r3) {                                          // blocked output, two waves per SIMD; a code object of its own
         if (p.out_mode != 0 || !two_waves) return hipErrorInvalidValue;

@@ -61,59 +61,71 @@ __device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, unsigned
 // wave never waits for a read it has just issued, at the price of 8 more registers.  No branch inside the loop: the
 // counted waits the compiler derives stay exact.  tapv holds the patch byte offset of tap l in lane l
 // (STRIP_MAX_TAPS <= 64): a lane read brings it into a scalar register without a memory operation in the loop.
-template <int NF, int NFR, bool UPPER, int WSTRIDE_T>
+// HS: the wave also holds one channel half of a fragment it shares with another wave (slot NFR of acc / pbase, tile 0;
+// wsh = ws moved to that channel half's filter rows): one MFMA per tap.
+template <int NF, int NFR, bool HS, bool UPPER, int WSTRIDE_T>
 __device__ __forceinline__ void strip_chunk_mfma(f32x16 (&acc)[NF][2], const unsigned char *xs, const unsigned char *ws,
-                                                 const int (&pbase)[NF], const int tapv, const int ntaps)
+                                                 const unsigned char *wsh, const int (&pbase)[NF], const int tapv,
+                                                 const int ntaps)
 {
-    static_assert(NFR >= 1 && NFR <= NF, "fragments held by the wave");
+    static_assert(NFR >= 1 && NFR + (HS ? 1 : 0) <= NF, "fragments held by the wave");
+    constexpr int SH = HS ? NFR : 0;                     // slot of the shared fragment
     bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws);
     bf16x8 a1 = a0;
     if (UPPER) a1 = *reinterpret_cast<const bf16x8 *>(ws + 32 * 16);
+    bf16x8 ah = a0, bh = a0;
+    if (HS) ah = *reinterpret_cast<const bf16x8 *>(wsh);
     bf16x8 b[NFR];
     {
         const int toff = __builtin_amdgcn_readlane(tapv, 0);
 #pragma unroll
         for (int i = 0; i < NFR; ++i) b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+        if (HS) bh = *reinterpret_cast<const bf16x8 *>(xs + pbase[SH] + toff);
     }
-#ifndef NGC_EXP
-#define NGC_EXP 0
-#endif
     for (int t = 1; t < ntaps; ++t) {
         const int toff = __builtin_amdgcn_readlane(tapv, t);
-        bf16x8 a0n = a0, a1n = a1;
-        if (!(NGC_EXP & 2)) {
-            a0n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T);
-            a1n = a0n;
-            if (UPPER) a1n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T + 32 * 16);
-        }
+        const bf16x8 a0n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T);
+        bf16x8 a1n = a0n;
+        if (UPPER) a1n = *reinterpret_cast<const bf16x8 *>(ws + t * WSTRIDE_T + 32 * 16);
+        bf16x8 ahn = a0n;
+        if (HS) ahn = *reinterpret_cast<const bf16x8 *>(wsh + t * WSTRIDE_T);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NFR; ++i) {
             acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b[i], acc[i][0], 0, 0, 0);
             if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b[i], acc[i][1], 0, 0, 0);
-            if (!(NGC_EXP & 1)) b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+            b[i] = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (HS) {
+            acc[SH][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[SH][0], 0, 0, 0);
+            bh = *reinterpret_cast<const bf16x8 *>(xs + pbase[SH] + toff);
             __builtin_amdgcn_sched_barrier(0);
         }
         a0 = a0n;
         a1 = a1n;
+        ah = ahn;
     }
 #pragma unroll
     for (int i = 0; i < NFR; ++i) {
         acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b[i], acc[i][0], 0, 0, 0);
         if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b[i], acc[i][1], 0, 0, 0);
     }
+    if (HS) acc[SH][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[SH][0], 0, 0, 0);
 }
 
 // The last chunk of a workgroup, fragment after fragment instead of tap after tap: a fragment's accumulators are
-// final after its own taps, so its epilogue (epi(i): bias, ReLU, rounding, stores) runs while the wave's other
-// fragments - and the other wave of the SIMD - still have MFMAs to issue, and the results leave the chip during the
-// chunk instead of all at once behind it.  Costs the two filter operands once per fragment and tap instead of once
-// per tap (LDS is far from busy).  Same MFMAs per accumulator in the same order as strip_chunk_mfma: same bits.
-template <int NF, int NFR, bool UPPER, int WSTRIDE_T, class Epi>
+// final after its own taps, so its epilogue (epi(i): ReLU, rounding, stores; epih() for the shared fragment) runs
+// while the wave's other fragments - and the other wave of the SIMD - still have MFMAs to issue, and the results leave
+// the chip during the chunk instead of all at once behind it.  Costs the two filter operands once per fragment and tap
+// instead of once per tap (LDS is far from busy).  Same MFMAs per accumulator in the same order as strip_chunk_mfma:
+// same bits.
+template <int NF, int NFR, bool HS, bool UPPER, int WSTRIDE_T, class Epi, class EpiH>
 __device__ __forceinline__ void strip_chunk_mfma_last(f32x16 (&acc)[NF][2], const unsigned char *xs, const unsigned char *ws,
-                                                      const int (&pbase)[NF], const int tapv, const int ntaps, Epi &&epi)
+                                                      const unsigned char *wsh, const int (&pbase)[NF], const int tapv,
+                                                      const int ntaps, Epi &&epi, EpiH &&epih)
 {
-    static_assert(NFR >= 1 && NFR <= NF, "fragments held by the wave");
+    static_assert(NFR >= 1 && NFR + (HS ? 1 : 0) <= NF, "fragments held by the wave");
 #pragma unroll
     for (int i = 0; i < NFR; ++i) {
         bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws);
@@ -137,6 +149,23 @@ __device__ __forceinline__ void strip_chunk_mfma_last(f32x16 (&acc)[NF][2], cons
         acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
         if (UPPER) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
         epi(i);
+    }
+    if constexpr (HS) {
+        constexpr int SH = NFR;
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(wsh);
+        bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[SH] + __builtin_amdgcn_readlane(tapv, 0));
+        for (int t = 1; t < ntaps; ++t) {
+            const int toff = __builtin_amdgcn_readlane(tapv, t);
+            const bf16x8 an = *reinterpret_cast<const bf16x8 *>(wsh + t * WSTRIDE_T);
+            const bf16x8 bn = *reinterpret_cast<const bf16x8 *>(xs + pbase[SH] + toff);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[SH][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[SH][0], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a = an;
+            b = bn;
+        }
+        acc[SH][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[SH][0], 0, 0, 0);
+        epih();
     }
 }
 
@@ -256,6 +285,16 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     int nfrag = 0;
 #pragma unroll
     for (int i = 0; i < NF; ++i) nfrag += ((wave + NW * i) * 32 < p.npix) ? 1 : 0;
+    // blocked rank-2 output below 2 GiB without a mask: the epilogue that stores through a buffer descriptor
+    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
+    // Shared last fragment.  When the strip has NW (NF - 1) + 1 fragments, wave 0 would hold one more than every other
+    // wave and its SIMD 7 fragments against 6 on the others (the 784 positions of 14 rows of 56: 24.5 fragments).  The
+    // two 32-channel halves of that fragment then go to waves 0 and 1 (two SIMDs with 6.5 each): slot NF - 1 of both
+    // waves is fragment nfrag_all - 1, tile 0 of the slot holds channel half hsel = wave.
+    const int nfrag_all = (p.npix + 31) >> 5;
+    const bool split = SUB == 0 && !DB && !R3 && NF > 1 && store32 && p.frag_split != 0 && nfrag_all == NW * (NF - 1) + 1;
+    const bool half_slot = split && wave < 2;
+    const int hsel = half_slot ? wave : 0;
 
     // R3: the loads are issued chunk after chunk; (ld_td, ld_cb) is the (depth tap, channel chunk) pair of the next call
     int ld_td = 0, ld_cb = 0;
@@ -313,7 +352,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     int pbase[NF];          // patch pixel index of the position at tap offset 0 (clamped to 0 if invalid)
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
+        const int frag = (half_slot && i == NF - 1) ? nfrag_all - 1 : wave + NW * i;
+        const uint32_t m = (uint32_t)(frag * 32 + l32);
         int pb = 0;
         if (m < (uint32_t)p.npix) {
             const uint32_t ti = fd_div(m, p.div_tpq);
@@ -335,7 +375,11 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
+                float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
+                if (NF > 1 && i == NF - 1 && a == 0 && hsel) {           // wave-uniform
+                    b0 = bv[1][h][0];
+                    b1 = bv[1][h][1];
+                }
                 const float bias8[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[i][a][8 * h + e] = SUB == 0 ? bias8[e] : 0.f;
@@ -346,7 +390,6 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const int CBout = p.Cout >> 4;
     const int HWout = p.Hfull * p.Wfull;
     const int plane_out = R3 ? p.Dfull * HWout : HWout;  // pixel blocks per 16-channel plane of a batch element
-    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
     const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines, streaming stores
     __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
     const int relu_on = p.relu;
@@ -361,9 +404,11 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     };
     // Epilogue of fragment i on that path (the bias is in the accumulators): one rounding, ReLU, lane-pair exchange,
     // stores.  STREAM: every pixel of the tensor is written by this launch, the stores are streaming stores.
-    auto store_frag32 = [&](const int i, auto stream_tag) {
+    // SHARED: slot i is the shared fragment; its tile 0 goes to channel half hsel, there is no tile 1.
+    auto store_frag32 = [&](const int i, auto stream_tag, auto shared_tag) {
         constexpr bool STREAM = decltype(stream_tag)::value;
-        const uint32_t m = (uint32_t)((wave + NW * i) * 32 + l32);
+        constexpr bool SHARED = decltype(shared_tag)::value;
+        const uint32_t m = (uint32_t)((SHARED ? nfrag_all - 1 : wave + NW * i) * 32 + l32);
         bool ok = m < (uint32_t)p.npix;
         const uint32_t mm = ok ? m : 0;
         const uint32_t ti = fd_div(mm, p.div_tpq);
@@ -378,7 +423,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                              (unsigned)(n * CBout * HWout);
         const unsigned off0 = ok ? (pix + (unsigned)((k0 >> 4) * plane_out)) * 32u + (unsigned)(lg * 16) : STRIP_OOB;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+        for (int a = 0; a < (SHARED ? 1 : 2); ++a) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const f32x16 &t = acc[i][a];
@@ -387,7 +432,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 const uint32_t w2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]));
                 const uint32_t w3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]));
                 const uint4 o = lane_pair_exchange(w0, w1, w2, w3);
-                const int cb = 2 * a + h;                                // 16-channel block inside the tile
+                const int cb = 2 * (SHARED ? hsel : a) + h;              // 16-channel block inside the tile
                 const bool st = off0 != STRIP_OOB && (k0 >> 4) + cb < CBout;
                 const unsigned off = st ? off0 + (unsigned)(cb * plane_out) * 32u : STRIP_OOB;
                 ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
@@ -406,8 +451,9 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // sequence; the others (ragged strips) the loop that tests every fragment.  NFR = 0 selects the latter.
     static_assert(STRIP_MAX_TAPS <= 64, "one lane per tap");
     const int tapv = p.tap_off[lane < p.ntaps ? lane : 0] * 16;
-    auto chunk_loop = [&](auto nfr_tag) -> bool {
+    auto chunk_loop = [&](auto nfr_tag, auto hs_tag) -> bool {
         constexpr int NFR = decltype(nfr_tag)::value;
+        constexpr bool HS = decltype(hs_tag)::value;
         const bool tail = NFR > 0 && tail_fuse;
         const int nmain = tail ? nchunks - 1 : nchunks;
         for (int c = 0; c < nmain; ++c) {
@@ -420,7 +466,7 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
             const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
             const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
             if constexpr (NFR > 0) {
-                strip_chunk_mfma<NF, NFR, upper, wstride_t>(acc, xs, ws, pbase, tapv, p.ntaps);
+                strip_chunk_mfma<NF, NFR, HS, upper, wstride_t>(acc, xs, ws, ws + hsel * (32 * 16), pbase, tapv, p.ntaps);
             } else {
                 for (int t = 0; t < p.ntaps; ++t) {
                     const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t);
@@ -446,8 +492,10 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 STRIP_TL(8);
                 const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
                 const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
-                strip_chunk_mfma_last<NF, NFR, upper, wstride_t>(acc, xs, ws, pbase, tapv, p.ntaps,
-                                                                [&](const int i) { store_frag32(i, std::true_type{}); });
+                strip_chunk_mfma_last<NF, NFR, HS, upper, wstride_t>(
+                    acc, xs, ws, ws + hsel * (32 * 16), pbase, tapv, p.ntaps,
+                    [&](const int i) { store_frag32(i, std::true_type{}, std::false_type{}); },
+                    [&]() { store_frag32(NF - 1, std::true_type{}, std::true_type{}); });
                 STRIP_TL(10);
 #ifdef NGC_TIMELINE
                 tl_flush();
@@ -457,12 +505,15 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         return false;
     };
-    if (nfrag == NF) {
-        if (chunk_loop(std::integral_constant<int, NF>{})) return;
+    constexpr bool CAN_SPLIT = SUB == 0 && !DB && !R3 && NF > 1;
+    if (CAN_SPLIT && half_slot) {
+        if (chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 1)>{}, std::integral_constant<bool, CAN_SPLIT>{})) return;
+    } else if (nfrag == NF) {
+        if (chunk_loop(std::integral_constant<int, NF>{}, std::false_type{})) return;
     } else if (NF > 1 && nfrag == NF - 1) {
-        if (chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{})) return;
+        if (chunk_loop(std::integral_constant<int, (NF > 1 ? NF - 1 : 0)>{}, std::false_type{})) return;
     } else {
-        chunk_loop(std::integral_constant<int, 0>{});
+        chunk_loop(std::integral_constant<int, 0>{}, std::false_type{});
     }
 
     // ---- epilogue
@@ -531,14 +582,17 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     }
     if (store32 && !DB) {
         STRIP_TL(9);
+        const int nfull = half_slot ? NF - 1 : nfrag;
         if (dense_out) {
 #pragma unroll
             for (int i = 0; i < NF; ++i)
-                if (i < nfrag) store_frag32(i, std::true_type{});
+                if (i < nfull) store_frag32(i, std::true_type{}, std::false_type{});
+            if (NF > 1 && half_slot) store_frag32(NF - 1, std::true_type{}, std::true_type{});
         } else {
 #pragma unroll
             for (int i = 0; i < NF; ++i)
-                if (i < nfrag) store_frag32(i, std::false_type{});
+                if (i < nfull) store_frag32(i, std::false_type{}, std::false_type{});
+            if (NF > 1 && half_slot) store_frag32(NF - 1, std::false_type{}, std::true_type{});
         }
         STRIP_TL(10);
 #ifdef NGC_TIMELINE

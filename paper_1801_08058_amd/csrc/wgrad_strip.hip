@@ -28,7 +28,7 @@
 // shifted copies).
 //
 // Per 32-position step a wave issues 8 (dy) + 18 (x, 9 taps) transpose loads for 36 MFMAs; x
-// fragments run three taps ahead of the MFMAs in a rolling 3-slot buffer (across step
+// fragments run a whole step ahead of the MFMAs in a rolling 9-slot buffer (across step
 // boundaries), the dy fragments of the wave's next step are fetched during the current one.
 // The per-workgroup partial (in register order) goes to the workspace; wgrad_strip_reduce adds the
 // workgroups in index order (deterministic) and writes dw as [K][C][R][S].
@@ -59,6 +59,9 @@ __device__ unsigned long long g_ws_timeline[1024 * 8 * 64];
 
 constexpr unsigned WS_OOB = 0x80000000u;
 constexpr int WS_NT = 9;
+constexpr int WS_NB = 9;                           // x operand slots of a wave: a divisor of WS_NT, so that the slot of a tap is the
+                                                   // same in every step; 9 = every tap's operand is requested a whole step ahead
+                                                   // (3: cfg2 27.5 -> 27.3 us, 256 -> 256 at 14x14 43.4 -> 42.4 us, others unchanged)
 constexpr int WS_MAXDY = 4;                        // dy load slots per wave and stage: 4 planes x at most 7 blocks over 8 waves
 constexpr int WS_MAXX = 7;                         // x load slots per wave and stage (the host plan keeps NCQ * blocks <= 56)
 
@@ -278,11 +281,11 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
         int j = (wh - (s * steps_full) % NH + NH) % NH;
         if (j < nsteps) {
             int dyo[2], xo[2];
-            bf16x8 acur[4], b[3];
+            bf16x8 acur[4], b[WS_NB];
             step_offsets(j, dyo, xo);
             load_a(dyo, acur);
 #pragma unroll
-            for (int t = 0; t < 3; ++t) b[t] = load_b(xo, t);
+            for (int t = 0; t < WS_NB; ++t) b[t] = load_b(xo, t);
             // One step = 9 taps x 4 MFMAs.  The body exists in two straight-line versions (with and
             // without the fetches of the wave's next step) so that every LDS wait is an exact count.
             auto step_body = [&](auto has_next_tag) {
@@ -294,10 +297,10 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
                 for (int t = 0; t < WS_NT; ++t) {
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb)
-                        acc[kb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[kb], b[t % 3], acc[kb][t], 0, 0, 0);
-                    // refill the slot just consumed: tap t+3 of this step, or tap t+3-9 of the next
-                    if (t + 3 < WS_NT) b[t % 3] = load_b(xo, t + 3);
-                    else if (HAS_NEXT) b[t % 3] = load_b(xn, t + 3 - WS_NT);
+                        acc[kb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(acur[kb], b[t % WS_NB], acc[kb][t], 0, 0, 0);
+                    // refill the slot just consumed: tap t + WS_NB of this step, or tap t + WS_NB - 9 of the next
+                    if (t + WS_NB < WS_NT) b[t % WS_NB] = load_b(xo, t + WS_NB);
+                    else if (HAS_NEXT) b[t % WS_NB] = load_b(xn, t + WS_NB - WS_NT);
                     if (t == 2 && HAS_NEXT) load_a(dyn, anext);
                 }
                 if (HAS_NEXT) {
