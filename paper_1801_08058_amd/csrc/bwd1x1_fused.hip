@@ -46,6 +46,7 @@ __device__ __forceinline__ bf16x8 tr_frag_f(const unsigned char *lo)
 template <int KT, int NBUF>
 __global__ __launch_bounds__(512) void bwd1x1_fused_bf16(const Bwd1x1FusedParams p)
 {
+    preload_kernargs(p);
     constexpr int NW = 8;
     constexpr int BF_NBUF = NBUF;
     constexpr int KB = 4 * KT;                    // 16-channel planes of dy

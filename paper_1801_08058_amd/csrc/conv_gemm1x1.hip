@@ -56,6 +56,7 @@ constexpr unsigned G1_OOB = 0x80000000u;
 template <int WM, int WN, int NS, int KB, int NL, int FA, bool XN, bool YN, bool DB = false>
 __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const Gemm1x1Params p)
 {
+    preload_kernargs(p);
     constexpr int BM = 64 * WM, BN = 32 * FA * WN;
     constexpr int WB = BN / 64;                       // 64-row blocks of a filter plane
     constexpr int XPLANE = BM * 16 + 128, WPLANE = BN * 16 + 128;

@@ -60,6 +60,7 @@ struct IgemmCfg {
 template <int BM, int BN, bool R3>
 __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
 {
+    preload_kernargs(p);
     using Cfg = IgemmCfg<BM, BN>;
     __shared__ __align__(16) unsigned char smem[2 * Cfg::STAGE];
 

@@ -25,6 +25,7 @@ constexpr int STEM_KSTEPS = 11;      // ceil(21 pairs / 2)
 
 __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
 {
+    preload_kernargs(p);
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;

@@ -722,6 +722,7 @@ __global__ __launch_bounds__(NW * 64) void conv_strip_multi_bf16(const StripMult
     int cls = 0;
     while (cls + 1 < mp.n && (int)blockIdx.x >= mp.wg_end[cls]) ++cls;   // uniform per workgroup
     const int bx = (int)blockIdx.x - (cls ? mp.wg_end[cls - 1] : 0);
+    preload_kernargs(mp.c[cls]);
     conv_strip_body<NF, NW, 0, DB, R3>(mp.c[cls], bx, blockIdx.y);
 }
 

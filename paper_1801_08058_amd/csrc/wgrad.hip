@@ -45,6 +45,7 @@ __device__ __forceinline__ void interleave_store(unsigned char *tile, int half, 
 
 __global__ __launch_bounds__(256) void wgrad_bf16(const WgradParams p)
 {
+    preload_kernargs(p);
     __shared__ __align__(16) unsigned char smem[2 * WG_STAGE];       // 36864 B; reused for the final reduction
 
     const int tid = threadIdx.x;

@@ -58,6 +58,7 @@ __device__ __forceinline__ bf16x8 nchw_frag_g(const unsigned char *lo)
 template <int WK, int WC, int SP, bool XN, bool DN, bool R3 = false, bool XO = R3>
 __global__ __launch_bounds__(512) void wgrad_gemm_bf16(const WgradGemmParams p)
 {
+    preload_kernargs(p);
     static_assert(!(R3 && (XN || DN)), "rank-3 tensors are read blocked");
     static_assert(XO || !R3, "rank-3 launches use the XCD-ordered grid");
     constexpr int NW = 8;

@@ -45,6 +45,7 @@ __device__ __forceinline__ bf16x8 tr_frag_s(const unsigned char *lo, const unsig
 template <bool RING>
 __global__ __launch_bounds__(512) void wgrad_stem_bf16(const WgradStemParams p)
 {
+    preload_kernargs(p);
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
