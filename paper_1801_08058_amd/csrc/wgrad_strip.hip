@@ -79,7 +79,10 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lo, const unsigne
 // chunks for the same number of workgroups, i.e. fewer partial copies of dw to write and re-read.
 // MULTI: stages of several whole images (p.G of them); a separate instantiation so that the
 // one-image path carries none of the extra index arithmetic.
-template <int NCQ, bool MULTI>
+// U3: the nine taps are three rows of three with a column step of one pixel (a 3x3 window with dilation 1 along w):
+// the taps of a row then differ by a constant 32 bytes, which rides in the offset field of the LDS read - two address
+// additions per row and step instead of two per tap.
+template <int NCQ, bool MULTI, bool U3>
 __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p)
 {
     constexpr int NW = 8;
@@ -274,6 +277,10 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
                 a[kb] = tr_frag(dys + (kb ^ kbm) * p.dyplane + dyoff[0], dys + (kb ^ kbm) * p.dyplane + dyoff[1]);
         };
         auto load_b = [&](const int (&xoff)[2], int t) {
+            if constexpr (U3) {
+                const int row = p.tap_off[(t / 3) * 3] * 32;
+                return tr_frag(xs + xoff[0] + row + (t % 3) * 32, xs + xoff[1] + row + (t % 3) * 32);
+            }
             return tr_frag(xs + xoff[0] + p.tap_off[t] * 32, xs + xoff[1] + p.tap_off[t] * 32);
         };
 
@@ -444,20 +451,28 @@ __global__ __launch_bounds__(256) void wgrad_strip_reduce(const f32x4 *__restric
     }
 }
 
-template <int NCQ, bool MULTI>
-static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
+template <int NCQ, bool MULTI, bool U3>
+static hipError_t launch_wgrad_strip_t(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
 {
     static LdsLimitOnce lds_limit;                  // per template instantiation
     {
-        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ, MULTI>));
+        const hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(&wgrad_strip_bf16<NCQ, MULTI, U3>));
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.nparts, (p.K / 64) * p.ctiles);
 #ifdef NGC_TIMELINE
     lds_bytes += 4096;
 #endif
-    NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI>), grid, dim3(512), lds_bytes, st, p);
+    NGC_LAUNCH((wgrad_strip_bf16<NCQ, MULTI, U3>), grid, dim3(512), lds_bytes, st, p);
     return ngc::launch_result();
+}
+
+template <int NCQ, bool MULTI>
+static hipError_t launch_wgrad_strip_ncq(const WgradStripParams &p, size_t lds_bytes, hipStream_t st)
+{
+    bool u3 = true;
+    for (int t = 0; t < WS_NT; ++t) u3 = u3 && p.tap_off[t] == p.tap_off[(t / 3) * 3] + t % 3;
+    return u3 ? launch_wgrad_strip_t<NCQ, MULTI, true>(p, lds_bytes, st) : launch_wgrad_strip_t<NCQ, MULTI, false>(p, lds_bytes, st);
 }
 
 #ifdef NGC_TIMELINE
