@@ -285,8 +285,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     int nfrag = 0;
 #pragma unroll
     for (int i = 0; i < NF; ++i) nfrag += ((wave + NW * i) * 32 < p.npix) ? 1 : 0;
-    // blocked rank-2 output below 2 GiB without a mask: the epilogue that stores through a buffer descriptor
-    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0 && p.mask == nullptr;
+    // blocked rank-2 output below 2 GiB: the epilogue that stores through a buffer descriptor
+    const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0;
     // Shared last fragment.  When the strip has NW (NF - 1) + 1 fragments, wave 0 would hold one more than every other
     // wave and its SIMD 7 fragments against 6 on the others (the 784 positions of 14 rows of 56: 24.5 fragments).  The
     // two 32-channel halves of that fragment then go to waves 0 and 1 (two SIMDs with 6.5 each): slot NF - 1 of both
@@ -393,6 +393,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines, streaming stores
     __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
     const int relu_on = p.relu;
+    const bool has_mask = p.mask != nullptr;
+    __amdgpu_buffer_rsrc_t rs_mask = __builtin_amdgcn_make_buffer_rsrc((void *)p.mask, 0, has_mask ? (int)p.out_bytes : 0, 0x00020000);
     // ReLU on the rounded values, two at a time: as 16-bit integers the negative bf16 values (and -0) are the
     // negative numbers, so a signed maximum with 0 is max(v, 0) of both halves in one instruction (rounding keeps the
     // sign, so it commutes with ReLU); a maximum with the most negative integer changes nothing (ReLU off).
@@ -431,10 +433,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 const uint32_t w1 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 2], t[8 * h + 3]));
                 const uint32_t w2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]));
                 const uint32_t w3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]));
-                const uint4 o = lane_pair_exchange(w0, w1, w2, w3);
+                uint4 o = lane_pair_exchange(w0, w1, w2, w3);
                 const int cb = 2 * (SHARED ? hsel : a) + h;              // 16-channel block inside the tile
                 const bool st = off0 != STRIP_OOB && (k0 >> 4) + cb < CBout;
                 const unsigned off = st ? off0 + (unsigned)(cb * plane_out) * 32u : STRIP_OOB;
+                if (has_mask) {                                          // same shape and layout as the stored tensor
+                    const ngc_u32x4 mk = __builtin_amdgcn_raw_buffer_load_b128(rs_mask, (int)off, 0, 0);
+                    o = relu_keep8(o, make_uint4(mk[0], mk[1], mk[2], mk[3]));
+                }
                 ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
                 if constexpr (STREAM) __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
                 else __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
