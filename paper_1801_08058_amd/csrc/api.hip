@@ -685,6 +685,12 @@ bool wgrad_strip_plan_uncached(const ngc_conv_desc *d, int P, int Q, WgradStripP
     for (int r = 0; r < d->r; ++r)
         for (int s2 = 0; s2 < d->s; ++s2) q.tap_off[t++] = r * d->dil_h * q.PC + s2 * d->dil_w;
     q.ctiles = d->c / (16 * q.ncq);
+    {
+        // NGC_WGRAD_NT (tests / experiments): 0 / 1 = never / always
+        const size_t part_bytes = (size_t)q.nparts * 9 * d->k * d->c * sizeof(float);
+        const char *fn = env_switch(SW_WGRAD_NT);
+        q.stream_partials = fn ? (atoi(fn) != 0) : (part_bytes <= ((size_t)24 << 20));
+    }
     q.x_bytes = (uint32_t)x_bytes;
     q.dy_bytes = (uint32_t)dy_bytes;
     q.div_q = make_fastdiv((uint32_t)Q);

@@ -337,6 +337,13 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
     f32x4 *red = reinterpret_cast<f32x4 *>(smem);
     f32x4 *out = reinterpret_cast<f32x4 *>(p.partial) +
                  (((size_t)blockIdx.x * gridDim.y + blockIdx.y) * NCQ + cq) * (4 * WS_NT * 64);
+    // Partials are streamed out (non-temporal stores) when there are few enough of them for the reduce kernel to find
+    // them in the memory-side cache anyway; with more, ordinary stores are faster (the host decides, p.stream_partials).
+    const bool stream_part = p.stream_partials != 0;
+    auto put = [&](int idx, const f32x4 &v) {
+        const ngc_u32x4 w = __builtin_bit_cast(ngc_u32x4, v);
+        store16_result(out + idx, make_uint4(w[0], w[1], w[2], w[3]), stream_part);
+    };
     if constexpr (NH == 2 || NH == 4) {
         // Butterfly over the streams: in every round each wave hands half of the k blocks it still owns to the
         // partner stream and adds the partner's copy of the half it keeps, so all eight waves move data in every
@@ -363,12 +370,12 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
 #pragma unroll
             for (int t = 0; t < WS_NT; ++t) acc[0][t] += inbox2[t * 64 + lane];
 #pragma unroll
-            for (int t = 0; t < WS_NT; ++t) out[(kbm * WS_NT + t) * 64 + lane] = acc[0][t];
+            for (int t = 0; t < WS_NT; ++t) put((kbm * WS_NT + t) * 64 + lane, acc[0][t]);
         } else {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int t = 0; t < WS_NT; ++t) out[((kbm + i) * WS_NT + t) * 64 + lane] = acc[i][t];
+                for (int t = 0; t < WS_NT; ++t) put(((kbm + i) * WS_NT + t) * 64 + lane, acc[i][t]);
         }
         WS_TL();
     } else {
@@ -397,7 +404,7 @@ __global__ __launch_bounds__(512) void wgrad_strip_bf16(const WgradStripParams p
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                for (int t = 0; t < WS_NT; ++t) out[(kb * WS_NT + t) * 64 + lane] = acc[kb][t];
+                for (int t = 0; t < WS_NT; ++t) put((kb * WS_NT + t) * 64 + lane, acc[kb][t]);
         }
     }
 #ifdef NGC_TIMELINE
