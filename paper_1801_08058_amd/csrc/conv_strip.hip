@@ -41,6 +41,18 @@ hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipSt
         const char *fs = env_switch(SW_STRIP_SPLIT);     // NGC_STRIP_SPLIT=0: the odd last fragment stays with wave 0
         p.frag_split = (fs && atoi(fs) == 0) ? 0 : 1;
     }
+    // Small strips (two or four fragments per SIMD) of a launch that leaves no room for a second workgroup per compute
+    // unit anyway take two chunks per LDS stage when that fits: half as many barriers (NGC_STRIP_CPS=1: never).
+    {
+        const char *fc = env_switch(SW_STRIP_CPS);
+        const long wgs = (long)p.groups * p.strips * ((p.Cout + 63) / 64);
+        p.cps = 1;
+        if (!p.r3 && p.out_mode == 0 && nf <= 4 && two_waves && (p.Cin >> 4) >= 4 && 2 * lds_bytes <= 160 * 1024 &&
+            wgs <= 256 && !(fc && atoi(fc) == 1)) {
+            p.cps = 2;
+            lds_bytes *= 2;
+        }
+    }
     if (p.r3) {                                          // blocked output, two waves per SIMD; a code object of its own
         if (p.out_mode != 0 || !two_waves) return hipErrorInvalidValue;
         return launch_strip_r3(p, nf, lds_bytes, st);

@@ -229,7 +229,11 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     // filter planes of a stage: (tap, g) planes of 64 output channels, or one plane per tap (HALF)
     constexpr int wstride_t = HALF ? STRIP_WPITCH : 2 * STRIP_WPITCH;
     constexpr int wstride_g = HALF ? 512 : STRIP_WPITCH;
-    const int stage_bytes = 2 * xplane + p.ntaps * wstride_t;
+    // A stage of the LDS ring holds cps chunks (1, or 2 for small strips: half as many barriers where a chunk is only a
+    // few hundred MFMA cycles per wave); sub_bytes = one chunk's patch planes and filter planes.
+    const int cps = (!R3 && p.cps == 2) ? 2 : 1;
+    const int sub_bytes = 2 * xplane + p.ntaps * wstride_t;
+    const int stage_bytes = cps * sub_bytes;
 
     __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)p.in_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rs_wt = __builtin_amdgcn_make_buffer_rsrc((void *)p.wt, 0, (int)p.wt_bytes, 0x00020000);
@@ -298,8 +302,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 
     // R3: the loads are issued chunk after chunk; (ld_td, ld_cb) is the (depth tap, channel chunk) pair of the next call
     int ld_td = 0, ld_cb = 0;
-    auto issue_loads = [&](int chunk, int stage) {
-        unsigned char *xs = smem + stage * stage_bytes;
+    auto issue_loads = [&](int chunk, int stage, int sub) {
+        unsigned char *xs = smem + stage * stage_bytes + sub * sub_bytes;
         unsigned char *ws = xs + 2 * xplane;
         if constexpr (R3) chunk = ld_cb;
         const unsigned soff_x = (unsigned)(chunk * (R3 ? p.Din * HWin : HWin) * 32);
@@ -344,8 +348,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 
     // The first chunk is requested before anything else is set up: position tables and initial accumulators cost a
     // few hundred vector instructions per wave, which run while the loads are in flight.
+    const int nchunks = R3 ? p.ndt * CB : CB;
+    const int nstages = (nchunks + cps - 1) / cps;
+    auto issue_stage = [&](int s) {
+        issue_loads(s * cps, s & 1, 0);
+        if (cps == 2 && s * 2 + 1 < nchunks) issue_loads(s * 2 + 1, s & 1, 1);
+    };
     STRIP_TL(1);
-    issue_loads(0, 0);
+    issue_stage(0);
     STRIP_TL(2);
 
     // ---- positions owned by this lane: fragment f = wave + 4 i, position m = 32 f + l32
@@ -452,7 +462,6 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 
     // the sub-pixel store mode may use no more than 32 of the 64 output columns: skip the upper MFMA
     constexpr bool upper = !HALF;
-    const int nchunks = R3 ? p.ndt * CB : CB;
     // Waves that hold every fragment, or all but the last, run chunk loops with the software-pipelined MFMA
     // sequence; the others (ragged strips) the loop that tests every fragment.  NFR = 0 selects the latter.
     static_assert(STRIP_MAX_TAPS <= 64, "one lane per tap");
@@ -461,30 +470,36 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         constexpr int NFR = decltype(nfr_tag)::value;
         constexpr bool HS = decltype(hs_tag)::value;
         const bool tail = NFR > 0 && tail_fuse;
-        const int nmain = tail ? nchunks - 1 : nchunks;
-        for (int c = 0; c < nmain; ++c) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wave's loads of chunk c have landed
-            __syncthreads();                                // ... and everybody else's; stage (c+1)&1 is free
+        const int last = nchunks - 1;
+        for (int sg = 0; sg < nstages; ++sg) {
+            const int c0 = sg * cps;
+            if (tail && c0 == last) break;                  // this stage holds nothing but the tail chunk: below
+            __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wave's loads of stage sg have landed
+            __syncthreads();                                // ... and everybody else's; stage (sg+1)&1 is free
 #ifdef NGC_TIMELINE
-            if (c < 5) { if (c == 0) STRIP_TL(3); else if (c == 1) STRIP_TL(4); else if (c == 2) STRIP_TL(5); else if (c == 3) STRIP_TL(6); else STRIP_TL(7); }
+            if (sg < 5) { if (sg == 0) STRIP_TL(3); else if (sg == 1) STRIP_TL(4); else if (sg == 2) STRIP_TL(5); else if (sg == 3) STRIP_TL(6); else STRIP_TL(7); }
 #endif
-            if (c + 1 < nchunks) issue_loads(c + 1, (c + 1) & 1);
-            const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
-            const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
-            if constexpr (NFR > 0) {
-                strip_chunk_mfma<NF, NFR, HS, upper, wstride_t>(acc, xs, ws, ws + hsel * (32 * 16), pbase, tapv, p.ntaps);
-            } else {
-                for (int t = 0; t < p.ntaps; ++t) {
-                    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t);
-                    bf16x8 a1 = a0;
-                    if (upper) a1 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t + 32 * 16);
-                    const int toff = p.tap_off[t] * 16;
+            if (sg + 1 < nstages) issue_stage(sg + 1);
+            for (int u = 0; u < cps; ++u) {
+                const int c = c0 + u;
+                if (c > last || (tail && c == last)) break;
+                const unsigned char *xs = smem + (sg & 1) * stage_bytes + u * sub_bytes + lg * xplane;
+                const unsigned char *ws = smem + (sg & 1) * stage_bytes + u * sub_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
+                if constexpr (NFR > 0) {
+                    strip_chunk_mfma<NF, NFR, HS, upper, wstride_t>(acc, xs, ws, ws + hsel * (32 * 16), pbase, tapv, p.ntaps);
+                } else {
+                    for (int t = 0; t < p.ntaps; ++t) {
+                        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t);
+                        bf16x8 a1 = a0;
+                        if (upper) a1 = *reinterpret_cast<const bf16x8 *>(ws + t * wstride_t + 32 * 16);
+                        const int toff = p.tap_off[t] * 16;
 #pragma unroll
-                    for (int i = 0; i < NF; ++i) {
-                        if (i < nfrag) {
-                            const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
-                            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
-                            if (upper) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+                        for (int i = 0; i < NF; ++i) {
+                            if (i < nfrag) {
+                                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + pbase[i] + toff);
+                                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[i][0], 0, 0, 0);
+                                if (upper) acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[i][1], 0, 0, 0);
+                            }
                         }
                     }
                 }
@@ -492,12 +507,14 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
         }
         if constexpr (NFR > 0 && SUB == 0 && !DB && !R3) {
             if (tail) {                                     // last chunk, with the epilogues inside it
-                const int c = nchunks - 1;
-                __builtin_amdgcn_s_waitcnt(0x0F70);
-                __syncthreads();
+                const int sg = last / cps, u = last - sg * cps;
+                if (u == 0) {                               // its stage has not been opened yet
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    __syncthreads();
+                }
                 STRIP_TL(8);
-                const unsigned char *xs = smem + (c & 1) * stage_bytes + lg * xplane;
-                const unsigned char *ws = smem + (c & 1) * stage_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
+                const unsigned char *xs = smem + (sg & 1) * stage_bytes + u * sub_bytes + lg * xplane;
+                const unsigned char *ws = smem + (sg & 1) * stage_bytes + u * sub_bytes + 2 * xplane + lg * wstride_g + l32 * 16;
                 strip_chunk_mfma_last<NF, NFR, HS, upper, wstride_t>(
                     acc, xs, ws, ws + hsel * (32 * 16), pbase, tapv, p.ntaps,
                     [&](const int i) { store_frag32(i, std::true_type{}, std::false_type{}); },
