@@ -291,14 +291,18 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     for (int i = 0; i < NF; ++i) nfrag += ((wave + NW * i) * 32 < p.npix) ? 1 : 0;
     // blocked rank-2 output below 2 GiB: the epilogue that stores through a buffer descriptor
     const bool store32 = !R3 && SUB == 0 && p.out_bytes != 0;
-    // Shared last fragment.  When the strip has NW (NF - 1) + 1 fragments, wave 0 would hold one more than every other
-    // wave and its SIMD 7 fragments against 6 on the others (the 784 positions of 14 rows of 56: 24.5 fragments).  The
-    // two 32-channel halves of that fragment then go to waves 0 and 1 (two SIMDs with 6.5 each): slot NF - 1 of both
-    // waves is fragment nfrag_all - 1, tile 0 of the slot holds channel half hsel = wave.
+    // Shared last fragment.  The fragments are dealt round-robin, so with NW (NF - 1) + r of them waves 0 .. r - 1 hold
+    // NF and the others NF - 1.  When r is 1 or 5 exactly one SIMD carries one fragment more than every other (the 784
+    // positions of 14 rows of 56 are 24.5 fragments: 7 against 6, 6, 6).  The two 32-channel halves of the last fragment
+    // then go to its owner, wave r - 1, and to wave r on the next SIMD (6.5 / 6.5 / 6 / 6): slot NF - 1 of both waves is
+    // fragment nfrag_all - 1, tile 0 of the slot holds channel half hsel = wave - owner.
     const int nfrag_all = (p.npix + 31) >> 5;
-    const bool split = SUB == 0 && !DB && !R3 && NF > 1 && store32 && p.frag_split != 0 && nfrag_all == NW * (NF - 1) + 1;
-    const bool half_slot = split && wave < 2;
-    const int hsel = half_slot ? wave : 0;
+    const int r_extra = nfrag_all - NW * (NF - 1);
+    const bool split = SUB == 0 && !DB && !R3 && NF > 1 && store32 && p.frag_split != 0 && r_extra >= 1 && r_extra < NW &&
+                       (r_extra & 3) == 1;
+    const int owner = r_extra - 1;
+    const bool half_slot = split && (wave == owner || wave == owner + 1);
+    const int hsel = half_slot ? wave - owner : 0;
 
     // R3: the loads are issued chunk after chunk; (ld_td, ld_cb) is the (depth tap, channel chunk) pair of the next call
     int ld_td = 0, ld_cb = 0;
