@@ -748,6 +748,30 @@ def test_strip_two_dimensional_grid_switch(monkeypatch):
     _check_all(a, "bf16", BLK, BLK, True, 9200, ("strip", "strip", "wgrad"))
 
 
+STRIP_PATH_CASES = [
+    # n  c   h   w   k   r  s  sh sw dh dw pbh pbw pah paw
+    Attrs(2, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # 14-row strips: 25 fragments, the last one shared (r = 1)
+    Attrs(2, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # two images per strip: 13 fragments, shared (r = 5)
+    Attrs(4, 80, 14, 14, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),       # 5 chunks: two per stage leaves the last stage half full
+    Attrs(6, 128, 14, 14, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),     # 8 chunks, two output-channel tiles
+    Attrs(10, 64, 7, 7, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),        # one fragment per wave
+    Attrs(3, 96, 20, 24, 80, 3, 3, 1, 1, 2, 2, 2, 2, 2, 2),       # dilated window: backprop-filters without the shared row addresses
+]
+
+
+@pytest.mark.parametrize("switch", [None, ("NGC_STRIP_TAIL", "0"), ("NGC_STRIP_SPLIT", "0"), ("NGC_STRIP_CPS", "1"),
+                                    ("NGC_WGRAD_NT", "0"), ("NGC_WGRAD_NT", "1")])
+@pytest.mark.parametrize("a", STRIP_PATH_CASES)
+def test_strip_epilogue_split_and_stage_paths(a, switch, monkeypatch):
+    """The strip kernel's store path with the epilogues inside the last chunk, the shared last fragment and two
+    chunks per LDS stage, and each of them switched off (the paths the other launches take); the backprop-filters
+    partial stores in both forms.  Forward with and without bias + ReLU, backprop-data bare and with the ReLU-backprop
+    mask, backprop-filters: all against the oracle."""
+    if switch:
+        monkeypatch.setenv(*switch)
+    _check_all(a, "bf16", BLK, BLK, True, 9250 + a.c + a.h, ("strip", "strip", "wgrad"))
+
+
 WIDE_ROW_CASES = [
     # n  c   h   w     k   r  s  sh sw dh dw pbh pbw pah paw      rows wider than a strip holds: column tiles
     Attrs(1, 32, 5, 1000, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),
