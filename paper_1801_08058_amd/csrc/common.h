@@ -105,15 +105,6 @@ __host__ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 }
 
 // two fp32 -> packed bf16x2 with the hardware conversion (v_cvt_pk_bf16_f32, round-to-nearest-even)
-// max(v, 0) in one instruction.  fmaxf() costs two here (the compiler first canonicalises its operand with a
-// v_max_f32 v, v); the result is the same for every input, NaN included (v_max_f32 returns the other operand).
-__device__ __forceinline__ float relu_f32(float v)
-{
-    float r;
-    asm("v_max_f32 %0, 0, %1" : "=v"(r) : "v"(v));
-    return r;
-}
-
 __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
 {
     // as one vector conversion: two scalar casts become two conversions and a byte permute
@@ -121,6 +112,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2_hw(float lo, float hi)
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     const f32x2_t v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// ReLU of two rounded bf16 values at once (or of neither: on = false).  As 16-bit integers the negative bf16 values
+// (and -0) are the negative numbers, so a signed maximum with 0 is max(v, 0) of both halves in one instruction, and
+// rounding to nearest even keeps the sign, so it commutes with ReLU for every finite value and the infinities; a
+// maximum with the most negative integer changes nothing.  (A NaN, which finite inputs cannot produce, stays a NaN here
+// where an fp32 maximum would give 0.)
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t w, bool on)
+{
+    typedef short ngc_s16x2 __attribute__((ext_vector_type(2)));
+    const short fl = on ? (short)0 : (short)-32768;
+    const ngc_s16x2 v = __builtin_bit_cast(ngc_s16x2, w), f = {fl, fl};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, f));
 }
 
 // A kernel's by-value argument struct lives in the kernel-argument segment and is read with scalar loads where a

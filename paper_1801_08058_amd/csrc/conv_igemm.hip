@@ -248,12 +248,9 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
                     v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                     v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
                 }
-                if (p.relu) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-                }
-                const uint32_t p0 = pack_bf16x2_hw(v[0], v[1]), p1 = pack_bf16x2_hw(v[2], v[3]);
-                const uint32_t p2 = pack_bf16x2_hw(v[4], v[5]), p3 = pack_bf16x2_hw(v[6], v[7]);
+                const bool relu_on = p.relu != 0;                        // ReLU on the rounded pairs: see relu_bf16x2
+                const uint32_t p0 = relu_bf16x2(pack_bf16x2_hw(v[0], v[1]), relu_on), p1 = relu_bf16x2(pack_bf16x2_hw(v[2], v[3]), relu_on);
+                const uint32_t p2 = relu_bf16x2(pack_bf16x2_hw(v[4], v[5]), relu_on), p3 = relu_bf16x2(pack_bf16x2_hw(v[6], v[7]), relu_on);
                 // lg=0 owns channels {0-3, 8-11}, lg=1 owns {4-7, 12-15}; swap so that
                 // lg=0 ends with 0-7 and lg=1 with 8-15
                 uint4 o = lane_pair_exchange(p0, p1, p2, p3);

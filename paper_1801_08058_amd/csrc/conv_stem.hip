@@ -151,12 +151,8 @@ __global__ __launch_bounds__(256) void conv_stem_fwd_bf16(const StemFwdParams p)
                 const float4 b0 = bv[a][h][0], b1 = bv[a][h][1];
                 v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
                 v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                if (relu_on) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = relu_f32(v[e]);
-                }
-                const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
-                const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
+                const uint32_t q0 = relu_bf16x2(pack_bf16x2_hw(v[0], v[1]), relu_on), q1 = relu_bf16x2(pack_bf16x2_hw(v[2], v[3]), relu_on);
+                const uint32_t q2 = relu_bf16x2(pack_bf16x2_hw(v[4], v[5]), relu_on), q3 = relu_bf16x2(pack_bf16x2_hw(v[6], v[7]), relu_on);
                 const uint4 o = lane_pair_exchange(q0, q1, q2, q3);
                 if (store32) {
                     const unsigned off = ok ? ((unsigned)pix + (unsigned)(((co_base >> 4) + h) * PQ)) * 32u + (unsigned)(lg * 16)

@@ -409,15 +409,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
     const int relu_on = p.relu;
     const bool has_mask = p.mask != nullptr;
     __amdgpu_buffer_rsrc_t rs_mask = __builtin_amdgcn_make_buffer_rsrc((void *)p.mask, 0, has_mask ? (int)p.out_bytes : 0, 0x00020000);
-    // ReLU on the rounded values, two at a time: as 16-bit integers the negative bf16 values (and -0) are the
-    // negative numbers, so a signed maximum with 0 is max(v, 0) of both halves in one instruction (rounding keeps the
-    // sign, so it commutes with ReLU); a maximum with the most negative integer changes nothing (ReLU off).
-    typedef short s16x2 __attribute__((ext_vector_type(2)));
-    const short relu_floor = relu_on ? (short)0 : (short)-32768;
-    auto relu_bf16x2 = [&](uint32_t w) {
-        const s16x2 v = __builtin_bit_cast(s16x2, w), f = {relu_floor, relu_floor};
-        return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, f));
-    };
+    // ReLU on the rounded values, two at a time (relu_bf16x2)
+    const bool relu_b = relu_on != 0;
     // Epilogue of fragment i on that path (the bias is in the accumulators): one rounding, ReLU, lane-pair exchange,
     // stores.  STREAM: every pixel of the tensor is written by this launch, the stores are streaming stores.
     // SHARED: slot i is the shared fragment; its tile 0 goes to channel half hsel, there is no tile 1.
@@ -443,10 +436,10 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const f32x16 &t = acc[i][a];
-                const uint32_t w0 = relu_bf16x2(pack_bf16x2_hw(t[8 * h], t[8 * h + 1]));
-                const uint32_t w1 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 2], t[8 * h + 3]));
-                const uint32_t w2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]));
-                const uint32_t w3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]));
+                const uint32_t w0 = relu_bf16x2(pack_bf16x2_hw(t[8 * h], t[8 * h + 1]), relu_b);
+                const uint32_t w1 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 2], t[8 * h + 3]), relu_b);
+                const uint32_t w2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]), relu_b);
+                const uint32_t w3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]), relu_b);
                 uint4 o = lane_pair_exchange(w0, w1, w2, w3);
                 const int cb = 2 * (SHARED ? hsel : a) + h;              // 16-channel block inside the tile
                 const bool st = off0 != STRIP_OOB && (k0 >> 4) + cb < CBout;
@@ -684,12 +677,8 @@ __device__ __forceinline__ void conv_strip_body(const StripParams &p, const int 
                 float v[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = acc[i][a][8 * h + e];      // bias included
-                if (relu_on) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = relu_f32(v[e]);
-                }
-                const uint32_t q0 = pack_bf16x2_hw(v[0], v[1]), q1 = pack_bf16x2_hw(v[2], v[3]);
-                const uint32_t q2 = pack_bf16x2_hw(v[4], v[5]), q3 = pack_bf16x2_hw(v[6], v[7]);
+                const uint32_t q0 = relu_bf16x2(pack_bf16x2_hw(v[0], v[1]), relu_on != 0), q1 = relu_bf16x2(pack_bf16x2_hw(v[2], v[3]), relu_on != 0);
+                const uint32_t q2 = relu_bf16x2(pack_bf16x2_hw(v[4], v[5]), relu_on != 0), q3 = relu_bf16x2(pack_bf16x2_hw(v[6], v[7]), relu_on != 0);
                 uint4 o = lane_pair_exchange(q0, q1, q2, q3);
                 if (ok && (co_base >> 4) + h < CBout) {
                     const size_t blk = pix + (size_t)((co_base >> 4) + h) * plane_out;
