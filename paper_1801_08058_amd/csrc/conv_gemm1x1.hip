@@ -194,13 +194,21 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     const int l32 = lane & 31;
     const int lg = lane >> 5;
 
+    // The accumulators start from the bias (register v of fragment a holds channel n0 + 32 FA wn + 32 a + 8 (v / 4) +
+    // 4 lg + v % 4): the loads are under the ring's start-up and the epilogue has no additions.
     f32x16 acc[FA][2];
 #pragma unroll
     for (int a = 0; a < FA; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int j = 0; j < 4; ++j) {
+            const int ch = n0 + wn * 32 * FA + a * 32 + 8 * j + 4 * lg;
+            float4 b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.bias && ch < p.Cout) b4 = *reinterpret_cast<const float4 *>(p.bias + ch);      // Cout % 16 == 0
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int b = 0; b < 2; ++b) {
+                acc[a][b][4 * j] = b4.x; acc[a][b][4 * j + 1] = b4.y; acc[a][b][4 * j + 2] = b4.z; acc[a][b][4 * j + 3] = b4.w;
+            }
+        }
 
     for (int s = 0; s < nsteps; ++s) {
         wg_barrier_nofence();
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 
     const int HWout = p.Hout * p.Wout;
     if constexpr (YN) {
-        // ---- NCHW epilogue: bias, ReLU, one RNE rounding, wave tile -> LDS [channel][64 positions] -> 16-byte stores
+        // ---- NCHW epilogue: ReLU (bias is in the accumulators), one RNE rounding, wave tile -> LDS [channel][64 positions] -> 16-byte stores
         wg_barrier_nofence();                          // every wave is done with the ring
         unsigned char *st = smem + wave * (32 * FA * YROW);
 #pragma unroll
@@ -242,8 +250,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int ch = a * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    float val = acc[a][b][v];
-                    if (p.bias && n0 + wn * 32 * FA + ch < p.Cout) val += p.bias[n0 + wn * 32 * FA + ch];
+                    float val = acc[a][b][v];                          // bias included
                     if (p.relu) val = fmaxf(val, 0.f);
                     *reinterpret_cast<uint16_t *>(st + ch * YROW + (b * 32 + l32) * 2) =
                         (uint16_t)(pack_bf16x2_hw(val, 0.f) & 0xFFFFu);
@@ -266,7 +273,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         }
         return;
     }
-    // ---- epilogue: bias, ReLU, one RNE rounding, lane-pair exchange, 16-byte stores
+    // ---- epilogue: ReLU (bias is in the accumulators), one RNE rounding, lane-pair exchange, 16-byte stores
     const int CBout = p.Cout >> 4;
     const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines
     float csum[DB ? FA : 1][2][8];                        // DB: channel sums of this lane's stored values
@@ -295,13 +302,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
             for (int h = 0; h < 2; ++h) {
                 float v[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = acc[a][b][8 * h + e];
-                if (p.bias && co_base + 16 * h < p.Cout) {
-                    const float4 b0 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 4 * lg);
-                    const float4 b1 = *reinterpret_cast<const float4 *>(p.bias + co_base + 16 * h + 8 + 4 * lg);
-                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                }
+                for (int e = 0; e < 8; ++e) v[e] = acc[a][b][8 * h + e];      // bias included
                 const bool relu_on = p.relu != 0;                        // ReLU on the rounded pairs: see relu_bf16x2
                 const uint32_t q0 = relu_bf16x2(pack_bf16x2_hw(v[0], v[1]), relu_on), q1 = relu_bf16x2(pack_bf16x2_hw(v[2], v[3]), relu_on);
                 const uint32_t q2 = relu_bf16x2(pack_bf16x2_hw(v[4], v[5]), relu_on), q3 = relu_bf16x2(pack_bf16x2_hw(v[6], v[7]), relu_on);
