@@ -976,6 +976,10 @@ bool gemm1x1_plan_uncached(const ngc_conv_desc *d, int op, int P, int Q, Gemm1x1
     q.M = (uint32_t)m;
     q.in_bytes = (uint32_t)in_bytes;
     q.wt_bytes = (uint32_t)wt_bytes;
+    {
+        const size_t out_bytes = (size_t)d->n * ((Cout + 15) / 16) * q.Hout * q.Wout * 32;
+        q.out_bytes = (!q.out_nchw && out_bytes < 0x80000000ull) ? (uint32_t)out_bytes : 0;
+    }
     q.div_pq = make_fastdiv((uint32_t)(OP * OQ > 0 ? OP * OQ : 1));
     q.div_q = make_fastdiv((uint32_t)(OQ > 0 ? OQ : 1));
     if (gp) *gp = q;

@@ -507,6 +507,8 @@ struct Gemm1x1Params {
     int32_t zero_sib;          // also store zeros to the other pixels of the position's os_h x os_w block (oa = 0)
     uint32_t M;                // N * OP * OQ lattice positions
     uint32_t in_bytes, wt_bytes;
+    uint32_t out_bytes;        // blocked result: bytes of the stored tensor if below 2 GiB (stores then take 32-bit offsets
+                               // into a buffer descriptor), else 0
     FastDiv div_pq, div_q;
 };
 

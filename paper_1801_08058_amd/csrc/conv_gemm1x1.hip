@@ -276,6 +276,9 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
     // ---- epilogue: ReLU (bias is in the accumulators), one RNE rounding, lane-pair exchange, 16-byte stores
     const int CBout = p.Cout >> 4;
     const bool dense_out = p.os_h == 1 && p.os_w == 1;     // every pixel written: whole cache lines
+    const bool fast = !DB && p.out_bytes != 0 && p.mask == nullptr && !p.zero_sib;
+    const bool relu_b = p.relu != 0;
+    const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)p.out_bytes, 0x00020000);
     float csum[DB ? FA : 1][2][8];                        // DB: channel sums of this lane's stored values
 #pragma unroll
     for (int a = 0; a < (DB ? FA : 1); ++a)
@@ -295,6 +298,27 @@ __global__ __launch_bounds__(64 * (WM * WN + NL)) void conv_gemm1x1_bf16(const G
         const int oh = (int)i * p.os_h + p.oa_h;
         const int ow = (int)j * p.os_w + p.oa_w;
         const size_t pix = (size_t)n * CBout * HWout + (size_t)oh * p.Wout + ow;
+        if (fast) {
+            // plain blocked stores below 2 GiB: 32-bit offsets into a buffer descriptor, lanes that must not store get an
+            // out-of-range offset (no 64-bit address arithmetic, no divergent branch per store)
+#pragma unroll
+            for (int a = 0; a < FA; ++a)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const f32x16 &t = acc[a][b];
+                    const uint32_t q0 = relu_bf16x2(pack_bf16x2_hw(t[8 * h], t[8 * h + 1]), relu_b);
+                    const uint32_t q1 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 2], t[8 * h + 3]), relu_b);
+                    const uint32_t q2 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 4], t[8 * h + 5]), relu_b);
+                    const uint32_t q3 = relu_bf16x2(pack_bf16x2_hw(t[8 * h + 6], t[8 * h + 7]), relu_b);
+                    const uint4 o = lane_pair_exchange(q0, q1, q2, q3);
+                    const int cb = ((n0 + wn * 32 * FA + a * 32) >> 4) + h;
+                    const unsigned off = (ok && cb < CBout) ? ((unsigned)pix + (unsigned)(cb * HWout)) * 32u + (unsigned)(lg * 16) : 0x80000000u;
+                    const ngc_u32x4 ov = {o.x, o.y, o.z, o.w};
+                    if (dense_out) __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, NGC_ST_AUX);
+                    else __builtin_amdgcn_raw_buffer_store_b128(ov, rs_out, (int)off, 0, 0);
+                }
+            continue;
+        }
 #pragma unroll
         for (int a = 0; a < FA; ++a) {
             const int co_base = n0 + wn * 32 * FA + a * 32;
