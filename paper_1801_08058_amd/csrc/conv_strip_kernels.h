@@ -21,8 +21,11 @@
 // 2 * NF MFMAs per wave, about 4000 cycles for 3x3), so one barrier per chunk suffices.
 //
 // MFMA roles as in the gather kernel: A = filters (rows = output channels), B = activations
-// (columns = positions), v_mfma_f32_32x32x16_bf16; epilogue (bias, ReLU, one RNE rounding,
-// lane-pair exchange, 16-byte stores) identical.
+// (columns = positions), v_mfma_f32_32x32x16_bf16.  Epilogue: the accumulators start from the bias, one RNE
+// rounding, ReLU on the rounded pairs, lane-pair exchange, 16-byte stores; for blocked rank-2 results below 2 GiB it
+// runs inside the last chunk, fragment after fragment (strip_chunk_mfma_last).  The kernels here also come with two
+// waves per SIMD (NW = 8: wave w owns fragments w, w + 8, ...), a fragment shared between two waves where that evens
+// out the SIMDs, and two chunks per LDS stage for small strips (StripParams::cps).
 #pragma once
 #include "common.h"
 
