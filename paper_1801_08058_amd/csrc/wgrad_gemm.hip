@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
                                                         int nparts, int K, int C, int RS, int ktiles, int ctiles, int WK, int WC)
 {
     constexpr int NO = 256 / SL;
-    __shared__ f32x4 sm[SL][NO];
+    __shared__ f32x4 sm[SL == 1 ? 1 : SL][SL == 1 ? 1 : NO];
     const size_t per4 = (size_t)RS * ktiles * ctiles * WK * WC * (64 * 64 / 4);
     const int o = threadIdx.x % NO;
     const int sl = threadIdx.x / NO;
@@ -293,13 +293,18 @@ __global__ __launch_bounds__(256) void wgrad_gemm_reduce(const f32x4 *__restrict
         t1 += partial[(size_t)(sp + SL) * per4 + i];
     }
     if (sp < nparts) t0 += partial[(size_t)sp * per4 + i];
-    sm[sl][o] = t0 + t1;
-    __syncthreads();
+    if constexpr (SL > 1) {
+        sm[sl][o] = t0 + t1;
+        __syncthreads();
+    }
     if (sl == 0) {
-        f32x4 q[8];
+        f32x4 r = t0 + t1;                                  // SL == 1: one thread per output, no exchange
+        if constexpr (SL > 1) {
+            f32x4 q[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) q[j] = SL == 16 ? sm[2 * j][o] + sm[(2 * j + 1) % SL][o] : sm[j][o];
-        const f32x4 r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+            for (int j = 0; j < 8; ++j) q[j] = SL == 16 ? sm[2 * j][o] + sm[(2 * j + 1) % SL][o] : sm[j % SL][o];
+            r = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+        }
         const int lane = (int)(i & 63);
         size_t u = i >> 6;
         const int cq = (int)(u & 3); u >>= 2;
@@ -375,8 +380,11 @@ hipError_t launch_wgrad_gemm(const WgradGemmParams &p, hipStream_t st)
     if (p.nparts >= 16)
         NGC_LAUNCH(wgrad_gemm_reduce<16>, dim3((unsigned)(per4 / 16)), dim3(256), 0, st,
                    reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
-    else
+    else if (p.nparts > 8)
         NGC_LAUNCH(wgrad_gemm_reduce<8>, dim3((unsigned)(per4 / 32)), dim3(256), 0, st,
+                   reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
+    else                                                // a handful of parts: one thread per output adds them itself
+        NGC_LAUNCH(wgrad_gemm_reduce<1>, dim3((unsigned)(per4 / 256)), dim3(256), 0, st,
                    reinterpret_cast<const f32x4 *>(p.partial), p.dw, p.nparts, p.K, p.C, taps, p.ktiles, p.ctiles, p.wk, p.wc);
     return ngc::launch_result();
 }
