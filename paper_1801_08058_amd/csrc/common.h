@@ -212,8 +212,16 @@ __device__ __forceinline__ uint4 lane_pair_exchange(uint32_t q0, uint32_t q1, ui
 // comparison: +0, -0, negatives and NaN block), zero the others.
 __device__ __forceinline__ uint32_t relu_keep2(uint32_t v, uint32_t m)
 {
-    const float lo = __uint_as_float(m << 16), hi = __uint_as_float(m & 0xFFFF0000u);
-    return v & ((lo > 0.f ? 0x0000FFFFu : 0u) | (hi > 0.f ? 0xFFFF0000u : 0u));
+    // As 16-bit integers the bf16 values greater than zero are 1 .. 0x7F80 (+inf); the NaNs lie above, zero and the
+    // negative values (-0 is the most negative integer) below.  Two saturating differences have their sign bit set
+    // exactly for m > 0 and for m < 0x7F81; their conjunction, shifted down arithmetically, is the 16-bit keep mask:
+    // five packed instructions per pair.
+    typedef short ngc_s16x2 __attribute__((ext_vector_type(2)));
+    const ngc_s16x2 mm = __builtin_bit_cast(ngc_s16x2, m), zero = {0, 0}, lim = {0x7F81, 0x7F81};
+    const ngc_s16x2 a = __builtin_elementwise_sub_sat(zero, mm);
+    const ngc_s16x2 b = __builtin_elementwise_sub_sat(mm, lim);
+    const ngc_s16x2 k = (a & b) >> 15;
+    return v & __builtin_bit_cast(uint32_t, k);
 }
 __device__ __forceinline__ uint4 relu_keep8(uint4 v, uint4 m)
 {

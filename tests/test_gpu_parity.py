@@ -772,6 +772,37 @@ def test_strip_epilogue_split_and_stage_paths(a, switch, monkeypatch):
     _check_all(a, "bf16", BLK, BLK, True, 9250 + a.c + a.h, ("strip", "strip", "wgrad"))
 
 
+@pytest.mark.parametrize("a,variant", [
+    (Attrs(2, 64, 12, 12, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1), "strip"),
+    (Attrs(2, 64, 12, 12, 64, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0), "gemm1x1"),
+    (Attrs(2, 64, 12, 12, 64, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1), "strip"),
+])
+@pytest.mark.filterwarnings("ignore:invalid value encountered")          # the signalling NaN among the patterns
+def test_relu_backprop_mask_special_values(a, variant):
+    """The ReLU-backprop mask is `x_in > 0` as a comparison of floats: +0, -0, negative values (denormals and -inf
+    included) and NaNs of either sign block, positive denormals and +inf pass.  x_in carries each of those bit patterns
+    at seeded places; everything else about the call is the ordinary parity case."""
+    x, w, b, dy = _tensors(a, "bf16", 9700 + a.r + a.sh)
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x7F80, 0xFF80, 0x7FC0, 0xFFC0, 0x7F81, 0x3F80, 0xBF80],
+                        dtype=np.uint16)
+    vals = (specials.astype(np.uint32) << 16).view(np.float32)
+    rng = np.random.default_rng(9700)
+    x_in = np.array(x, dtype=np.float32, copy=True)
+    flat = x_in.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 3, replace=False)
+    flat[idx] = vals[rng.integers(0, len(vals), size=idx.size)]
+    run = Run(a, "bf16", BLK, BLK, True)
+    dxr = run.bwd_data_relu(dy, w, x_in)
+    assert ng.ngc_conv_variant(run.last_desc, ng.NGC_OP_BWD_DATA).startswith(variant)
+    ref = oracle.relu_bwd_mask(oracle.conv_bwd_data(a, dy, w), x_in)
+    assert oracle.max_normalised_error(dxr, ref) <= bound("bf16", "act")
+    with np.errstate(invalid="ignore"):
+        blocked = ~(x_in > 0)
+    assert np.all(dxr[blocked] == 0) and not np.signbit(dxr[blocked]).any()
+    passed = dxr[~blocked]
+    assert np.count_nonzero(passed) > 0.9 * passed.size            # positive denormals and +inf let the gradient through
+
+
 WIDE_ROW_CASES = [
     # n  c   h   w     k   r  s  sh sw dh dw pbh pbw pah paw      rows wider than a strip holds: column tiles
     Attrs(1, 32, 5, 1000, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1),
