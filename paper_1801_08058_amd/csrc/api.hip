@@ -440,7 +440,7 @@ bool rows_plan_uncached(const ngc_conv_desc *d, int op, int P, int Q, RowsParams
     // NGC_ROWS=1 selects it (tests / experiments).
     const char *sw = env_switch(SW_ROWS);
     if (!sw || atoi(sw) != 1) return false;
-    if (env_switch(SW_STRIP_NF) || env_switch(SW_STRIP_1WAVE)) return false;   // forced strip-kernel variants
+    if (env_switch(SW_STRIP_NF)) return false;   // forced strip-kernel variant
     if (d->stride_h != 1 || d->stride_w != 1) return false;
     const int ntaps = d->r * d->s;
     if (ntaps != 9) return false;                                        // the kernel's tap loop is unrolled for 9 taps
@@ -1223,7 +1223,7 @@ bool db_fusable(const ngc_conv_desc *d, Variant v)
     if (v == V_ROWS) v = V_STRIP;                         // channel sums come from the strip kernel's launches
     if (v == V_STRIP) {                                   // the kernels with column tiles write no channel sums
         int P, Q;
-        return env_switch(SW_STRIP_1WAVE) == nullptr && validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
+        return validate(d, &P, &Q) == NGC_OK && !strip_col_tiles(d, NGC_OP_BWD_DATA, P, Q);
     }
     if (v == V_GEMM1X1) return d->x_layout == NGC_NCHW16C && d->y_layout == NGC_NCHW16C;
     return false;
@@ -1688,8 +1688,7 @@ int bwd_data_core(const ngc_conv_desc *desc, const void *dy, const void *w, cons
         }
         const int ncls = strip_classes(desc, NGC_OP_BWD_DATA);
         // the residue classes of the stride: one launch each, or (up to 4 classes, 8-wave kernels) all in one grid
-        const bool merge = !(env_switch(SW_STRIP_MERGE) && atoi(env_switch(SW_STRIP_MERGE)) == 0) &&
-                                  env_switch(SW_STRIP_1WAVE) == nullptr;
+        const bool merge = !(env_switch(SW_STRIP_MERGE) && atoi(env_switch(SW_STRIP_MERGE)) == 0);
         StripMulti mp;
         mp.n = 0;
         int nf_max = 0;

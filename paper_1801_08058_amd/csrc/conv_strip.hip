@@ -24,11 +24,10 @@ static hipError_t launch_strip_nf(const StripParams &p, size_t lds_bytes, hipStr
     return launch_strip_d<NF, NW, SUB, false>(p, lds_bytes, st);
 }
 
-// nf = 32-position fragments per SIMD (7, 4 or 2); the fragments of a SIMD are spread over
-// `waves_per_simd` waves so that one wave's LDS latency hides behind the other's MFMAs
+// nf = 32-position fragments per SIMD (7, 4 or 2); the fragments of a SIMD are spread over two
+// waves so that one wave's LDS latency hides behind the other's MFMAs
 hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipStream_t st)
 {
-    const int two_waves = env_switch(SW_STRIP_1WAVE) ? 0 : 1;
     StripParams p = p_in;
     // several output-channel tiles: XCD-ordered grid, so that the tiles of a strip read its input through one L2
     // (strided forward layers of the ResNet-50 stack 58 -> 55 us, others 0-2 %; NGC_STRIP_XCD=0: two-dimensional grid)
@@ -47,14 +46,14 @@ hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipSt
         const char *fc = env_switch(SW_STRIP_CPS);
         const long wgs = (long)p.groups * p.strips * ((p.Cout + 63) / 64);
         p.cps = 1;
-        if (!p.r3 && p.out_mode == 0 && nf <= 4 && two_waves && (p.Cin >> 4) >= 4 && 2 * lds_bytes <= 160 * 1024 &&
+        if (!p.r3 && p.out_mode == 0 && nf <= 4 && (p.Cin >> 4) >= 4 && 2 * lds_bytes <= 160 * 1024 &&
             wgs <= 256 && !(fc && atoi(fc) == 1)) {
             p.cps = 2;
             lds_bytes *= 2;
         }
     }
     if (p.r3) {                                          // blocked output, two waves per SIMD; a code object of its own
-        if (p.out_mode != 0 || !two_waves) return hipErrorInvalidValue;
+        if (p.out_mode != 0) return hipErrorInvalidValue;
         return launch_strip_r3(p, nf, lds_bytes, st);
     }
     if (p.out_mode == 1 && p.half_cols) {
@@ -74,9 +73,9 @@ hipError_t launch_strip(const StripParams &p_in, int nf, size_t lds_bytes, hipSt
         }
     }
     switch (nf) {
-    case 7: return two_waves ? launch_strip_nf<4, 8>(p, lds_bytes, st) : launch_strip_nf<7, 4>(p, lds_bytes, st);
-    case 4: return two_waves ? launch_strip_nf<2, 8>(p, lds_bytes, st) : launch_strip_nf<4, 4>(p, lds_bytes, st);
-    case 2: return two_waves ? launch_strip_nf<1, 8>(p, lds_bytes, st) : launch_strip_nf<2, 4>(p, lds_bytes, st);
+    case 7: return launch_strip_nf<4, 8>(p, lds_bytes, st);
+    case 4: return launch_strip_nf<2, 8>(p, lds_bytes, st);
+    case 2: return launch_strip_nf<1, 8>(p, lds_bytes, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -9,7 +9,7 @@
 namespace ngc {
 
 namespace {
-const char *const kNames[SW_COUNT] = {"NGC_CONV3D_RANK2", "NGC_CONV3D_STRIP", "NGC_DB_FUSE", "NGC_G1_NCHW", "NGC_G1_VARIANT", "NGC_GEMM1X1", "NGC_STEM_BH", "NGC_STEM_TP", "NGC_STRIP_1WAVE", "NGC_STRIP_BW", "NGC_STRIP_MERGE", "NGC_STRIP_NF", "NGC_STRIP_ROWS", "NGC_STRIP_STRIDED", "NGC_STRIP_XCD", "NGC_WGG3_PARTS", "NGC_WGG_SLOTS", "NGC_WGG_SP", "NGC_WGG_TILE", "NGC_WGG_XCD", "NGC_WGRAD_G1", "NGC_WGRAD_GEMM", "NGC_WGRAD_LATE", "NGC_WGRAD_NCQ", "NGC_WGRAD_RING", "NGC_WGRAD_STRIP", "NGC_WSTEM_POS", "NGC_WSTEM_RING", "NGC_ROWS", "NGC_ROWS_LATE", "NGC_STAGED", "NGC_STRIP_TAIL", "NGC_STRIP_SPLIT", "NGC_WGRAD_NT", "NGC_STRIP_CPS", "NGC_DRY_RUN"};
+const char *const kNames[SW_COUNT] = {"NGC_CONV3D_RANK2", "NGC_CONV3D_STRIP", "NGC_DB_FUSE", "NGC_G1_NCHW", "NGC_G1_VARIANT", "NGC_GEMM1X1", "NGC_STEM_BH", "NGC_STEM_TP", "NGC_STRIP_BW", "NGC_STRIP_MERGE", "NGC_STRIP_NF", "NGC_STRIP_ROWS", "NGC_STRIP_STRIDED", "NGC_STRIP_XCD", "NGC_WGG3_PARTS", "NGC_WGG_SLOTS", "NGC_WGG_SP", "NGC_WGG_TILE", "NGC_WGG_XCD", "NGC_WGRAD_G1", "NGC_WGRAD_GEMM", "NGC_WGRAD_LATE", "NGC_WGRAD_NCQ", "NGC_WGRAD_RING", "NGC_WGRAD_STRIP", "NGC_WSTEM_POS", "NGC_WSTEM_RING", "NGC_ROWS", "NGC_ROWS_LATE", "NGC_STAGED", "NGC_STRIP_TAIL", "NGC_STRIP_SPLIT", "NGC_WGRAD_NT", "NGC_STRIP_CPS", "NGC_DRY_RUN"};
 char *g_val[SW_COUNT] = {};
 std::atomic<uint32_t> g_epoch{0};
 std::atomic<int> g_dry{0};
