@@ -144,7 +144,9 @@ __global__ __launch_bounds__(256) void igemm_bf16(const IgemmParams p)
         for (int u = 0; u < Cfg::WU; ++u) {
             const int cbi = (BN == 128) ? u : w_cbi0;
             const size_t row = ((size_t)tp.slab * CBin + (c32 * 2 + cbi)) * p.Cout + n0 + w_row;
-            wr[u] = *reinterpret_cast<const uint4 *>(p.wt + row * 16 + ldg * 8);
+            // through a named value: assigned straight from the dereference, wr[] was kept in scratch memory
+            const uint4 t = *reinterpret_cast<const uint4 *>(p.wt + row * 16 + ldg * 8);
+            wr[u] = t;
         }
     };
 
