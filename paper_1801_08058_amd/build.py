@@ -13,14 +13,37 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "layout.hip", "conv_direct.hip", "conv_igemm.hip", "conv_strip.hip", "conv_rows.hip", "conv_strip3.hip", "conv_stem.hip", "wgrad.hip", "wgrad_strip.hip", "wgrad_stem.hip", "wgrad_gemm.hip", "conv_gemm1x1.hip", "bias_grad.hip", "softmax.hip", "conv3d_direct.hip", "api3d.hip", "static_scratch.hip", "switches.hip", "bwd1x1_fused.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage"]
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    # the compiler's per-kernel resource report: kept out of the output, except that a kernel which uses scratch
+    # memory (a register array that was not promoted, or spilled registers) is named - none of them should
+    err_lines, held, kernel, in_remark = [], [], "?", False
+    for l in r.stderr.splitlines():
+        if "packed-fp32-ops" in l:
+            continue
+        if l.startswith("In file included from"):
+            held.append(l)                        # belongs to the diagnostic that follows
+            continue
+        if in_remark and (l.split("|")[0].strip().isdigit() or l.lstrip().startswith("|")):
+            continue                              # the source line and caret printed under a remark
+        in_remark = "-Rpass-analysis=kernel-resource-usage" in l
+        if in_remark:
+            held = []
+            if "Function Name:" in l:
+                kernel = l.split("Function Name:")[1].split("[-Rpass")[0].strip()
+            elif "ScratchSize [bytes/lane]:" in l:
+                n = int(l.split("ScratchSize [bytes/lane]:")[1].split()[0])
+                if n:
+                    err_lines.append(f"warning: {src}: kernel {kernel} uses {n} bytes of scratch memory per lane")
+            continue
+        err_lines += held + [l]
+        held = []
+    err = "\n".join(err_lines)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
